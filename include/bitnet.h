@@ -1,0 +1,171 @@
+/*
+ * bitnet.h -- C ABI of the MI355X (gfx950) BitLinear W1.58A8 library.
+ *
+ * The library computes the BitLinear product of BitNet b1.58 (arXiv 2402.17764, Section 2):
+ *
+ *     gamma  = mean_ij |W_ij|                                   Eq. (3)
+ *     Wt     = RoundClip(W / (gamma + eps), -1, 1)              Eq. (1)-(2), eps = 1e-5
+ *     s_x[m] = max(max_k |x[m,k]|, 1e-5)                         per-token absmax (Section 2)
+ *     x_q    = clip(round(x * 127 / s_x[m]), -127, 127)          8-bit, symmetric, no zero point
+ *     acc    = x_q . Wt^T        (int32, exact)                  the "integer addition only" product
+ *     y      = acc * gamma * s_x[m] / 127                        undoing both scales
+ *
+ * round() is IEEE round-half-to-even everywhere.  gamma is the fp32 rounding of an fp64 quotient
+ * whose numerator is accumulated with compensated (double-double) summation, so it does not depend
+ * on the reduction order.
+ *
+ * Conventions for every entry point
+ *   - Matrices are row-major: W [N][K], x and x_q [M][K], y [M][N]  (y = x . W^T, the orientation of
+ *     a linear layer's weight).
+ *   - Every data pointer is DEVICE memory owned by the caller, unless marked (host).  The library
+ *     allocates nothing and keeps no state.  Inputs are never written; outputs are fully
+ *     overwritten.  gamma and s_x stay on the device, so no call synchronizes with the host.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are asynchronous
+ *     on that stream and may be captured into a HIP graph.
+ *   - Arguments are validated on the host before anything is launched; on any error nothing has been
+ *     launched and no output has been touched.  A launch failure reported by the runtime maps to
+ *     BITNET_ERR_HIP.  Non-finite input values are a precondition violation: the result is
+ *     unspecified but no memory outside the outputs is touched.
+ *   - Results are deterministic run to run (no floating-point atomics anywhere).
+ *   - Limits: 1 <= M, N, K;  N*K < 2^40;  K <= 262144 (so 64*127*K fits the int32 accumulator the
+ *     kernels use internally);  M*K and M*N < 2^40.
+ */
+#ifndef BITNET_H
+#define BITNET_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum bitnet_status {
+    BITNET_OK = 0,
+    BITNET_ERR_NULL = 1,        /* a required pointer is NULL */
+    BITNET_ERR_SHAPE = 2,       /* a size is <= 0 or beyond the limits above */
+    BITNET_ERR_DTYPE = 3,       /* dtype not accepted by this argument */
+    BITNET_ERR_FORMAT = 4,      /* unknown packing format, or not supported by this call */
+    BITNET_ERR_ALIGN = 5,       /* a pointer is not aligned as documented */
+    BITNET_ERR_WORKSPACE = 6,   /* workspace smaller than bitnet_quantize_weights_workspace says */
+    BITNET_ERR_HIP = 7,         /* the HIP runtime refused the launch */
+    BITNET_ERR_KERNEL = 8       /* requested kernel variant cannot run this shape */
+} bitnet_status;
+
+typedef enum bitnet_dtype {
+    BITNET_F32 = 0,
+    BITNET_BF16 = 1,
+    BITNET_I32 = 2              /* only as y_dtype: raw int32 accumulators, for exactness checks */
+} bitnet_dtype;
+
+/*
+ * Storage formats for the ternary matrix Wt (Section 3 of the paper stores 2 bits per weight and
+ * notes that 1.58 bits leaves room below that).
+ *
+ * BITNET_PACK_2BIT -- 4 codes per byte, tiled for 64-lane wavefronts.
+ *   N is padded to Np = 16*ceil(N/16) rows and K to Kp = 64*ceil(K/64) columns with zero codes.
+ *   The buffer is an array of 16-byte "quads"; quad index ((rb * (Kp/64) + kb) * 16 + r) holds the
+ *   64 codes of row n = 16*rb + r, columns k = 64*kb .. 64*kb+63.  A quad is four little-endian
+ *   32-bit words; word j holds columns 64*kb + 16*j .. +15; inside a word the code of column
+ *   16*j + 4*i + b  (i, b in 0..3) sits in bits [8*b + 2*i, 8*b + 2*i + 1].
+ *   A code is 2-bit two's complement: 00 = 0, 01 = +1, 11 = -1 (10 never occurs).
+ *   Size: Np * Kp / 4 bytes.  One 16-row x 64-column tile is 256 contiguous bytes, tiles of one row
+ *   block are contiguous along K, so a wavefront reads 1 KiB runs with one 128-bit load per lane.
+ *
+ * BITNET_PACK_TRIT5 -- 5 codes per byte (1.6 bits per weight), base 3.
+ *   N padded to Np as above, K padded to Kp = 320*ceil(K/320) columns with zero codes.  The buffer
+ *   is an array of 16-byte quads; quad index ((rb * (Kp/320) + kc) * 4 + q) * 16 + r holds, for row
+ *   n = 16*rb + r, the 80 codes of columns 320*kc + 80*q .. +79; byte t of that quad holds columns
+ *   320*kc + 80*q + 5*t + d (d = 0..4) as the value sum_d (code_d + 1) * 3^d  (0..242).
+ *   Size: Np * Kp / 5 bytes.
+ */
+typedef enum bitnet_format {
+    BITNET_PACK_2BIT = 0,
+    BITNET_PACK_TRIT5 = 1
+} bitnet_format;
+
+/* Kernel choice for bitnet_linear_variant (bitnet_linear picks by shape). */
+typedef enum bitnet_kernel {
+    BITNET_KERNEL_AUTO = 0,
+    BITNET_KERNEL_REFERENCE = 1, /* one thread per output, any shape; the slow, obviously right one */
+    BITNET_KERNEL_GEMV = 2,      /* weight-streaming decode kernel, M <= 64 */
+    BITNET_KERNEL_GEMM = 3       /* LDS-tiled int8 MFMA prefill kernel */
+} bitnet_kernel;
+
+/* Library version, major*10000 + minor*100 + patch.  Also the version of the packed layouts. */
+int bitnet_version(void);
+
+/* Human-readable name of a status code; never NULL; static storage. */
+const char* bitnet_status_string(bitnet_status s);
+
+/* Bytes of the packed buffer for an N x K matrix in format f, written to *bytes (host). */
+bitnet_status bitnet_packed_bytes(int64_t N, int64_t K, bitnet_format f, size_t* bytes);
+
+/* Bytes of scratch bitnet_quantize_weights needs (host out).  Independent of the format. */
+bitnet_status bitnet_quantize_weights_workspace(int64_t N, int64_t K, size_t* bytes);
+
+/*
+ * Eq. (1)-(3): W -> packed ternary codes + gamma.
+ *   W          [N][K], dtype F32 or BF16, 4-byte (F32) / 2-byte (BF16) aligned
+ *   packed     out, bitnet_packed_bytes() bytes, 16-byte aligned; padding codes are written as 0
+ *   gamma      out, 1 float (device)
+ *   workspace  scratch of at least bitnet_quantize_weights_workspace() bytes, 16-byte aligned;
+ *              contents on entry are ignored, contents on exit are unspecified
+ * Three launches on `stream`: |W| partial sums (double-double), the final reduction to gamma, and
+ * the ternarize-and-pack pass.  One gamma per call: a fused QKV or gate/up matrix passed as one
+ * tensor gets one scale.
+ */
+bitnet_status bitnet_quantize_weights(const void* W, bitnet_dtype w_dtype, int64_t N, int64_t K,
+                                      bitnet_format f, void* packed, float* gamma,
+                                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Section 2, activation quantization: x -> int8 codes + one scale per token.
+ *   x    [M][K], dtype F32 or BF16, element-aligned (16-byte aligned rows take the vector path)
+ *   xq   out [M][K] int8
+ *   sx   out [M] float: the clamped absmax, i.e. x ~ x_q * sx / 127
+ */
+bitnet_status bitnet_quantize_acts(const void* x, bitnet_dtype x_dtype, int64_t M, int64_t K,
+                                   int8_t* xq, float* sx, void* stream);
+
+/*
+ * The BitLinear product and rescale: y = (x_q . Wt^T) * gamma * s_x / 127.
+ *   xq, sx   as written by bitnet_quantize_acts
+ *   packed   as written by bitnet_quantize_weights for the same (N, K, f); 16-byte aligned
+ *   gamma    1 float (device)
+ *   y        out [M][N]; y_dtype F32, BF16 (round-to-nearest-even of the fp32 value) or I32 (the raw
+ *            accumulator, no scaling); element-aligned
+ * The kernel is chosen by shape: the weight-streaming GEMV for M <= 64, the MFMA GEMM above, the
+ * reference kernel when xq is not 16-byte aligned or K is not a multiple of 16.
+ */
+bitnet_status bitnet_linear(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
+                            int64_t M, int64_t N, int64_t K, bitnet_format f,
+                            void* y, bitnet_dtype y_dtype, void* stream);
+
+/* Same, with the kernel forced (tests and benchmarks).  BITNET_ERR_KERNEL if it cannot run the shape. */
+bitnet_status bitnet_linear_variant(const int8_t* xq, const float* sx, const void* packed,
+                                    const float* gamma, int64_t M, int64_t N, int64_t K,
+                                    bitnet_format f, void* y, bitnet_dtype y_dtype,
+                                    bitnet_kernel which, void* stream);
+
+/*
+ * Decode convenience: activation quantization fused into the weight-streaming kernel, x -> y in
+ * one launch.  Same arithmetic as bitnet_quantize_acts followed by bitnet_linear (every workgroup
+ * re-derives s_x and x_q for its K slice; nothing is written besides y).
+ *   M <= 16, K a multiple of 64, x 16-byte aligned; otherwise BITNET_ERR_KERNEL.
+ */
+bitnet_status bitnet_linear_fused(const void* x, bitnet_dtype x_dtype, const void* packed,
+                                  const float* gamma, int64_t M, int64_t N, int64_t K,
+                                  bitnet_format f, void* y, bitnet_dtype y_dtype, void* stream);
+
+/*
+ * Test helper: packed -> codes [N][K] int8 in {-1, 0, +1} (padding dropped).  The only supported
+ * way to read codes back besides decoding the documented layout by hand.
+ */
+bitnet_status bitnet_unpack_weights(const void* packed, int64_t N, int64_t K, bitnet_format f,
+                                    int8_t* codes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BITNET_H */

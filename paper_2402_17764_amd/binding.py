@@ -1,0 +1,172 @@
+"""ctypes binding of the BitLinear HIP library: the names and arguments of include/bitnet.h.
+
+Marshalling only: every function takes torch tensors that already live on the GPU (torch is used
+for device memory and streams, nothing else), checks dtype / shape / contiguity, passes raw device
+pointers and the current HIP stream through the C ABI, and raises BitnetError on a non-zero status.
+There is no fallback: if the shared library has not been built, load() raises.
+"""
+import ctypes
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libbitnet_hip.so")
+
+# enums of bitnet.h
+OK = 0
+F32, BF16, I32 = 0, 1, 2
+PACK_2BIT, PACK_TRIT5 = 0, 1
+KERNEL_AUTO, KERNEL_REFERENCE, KERNEL_GEMV, KERNEL_GEMM = 0, 1, 2, 3
+
+SYMBOLS = [
+    "bitnet_version", "bitnet_status_string", "bitnet_packed_bytes", "bitnet_quantize_weights_workspace",
+    "bitnet_quantize_weights", "bitnet_quantize_acts", "bitnet_linear", "bitnet_linear_variant",
+    "bitnet_linear_fused", "bitnet_unpack_weights",
+]
+
+_lib = None
+
+
+class BitnetError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        msg = _lib.bitnet_status_string(status).decode() if _lib is not None else str(status)
+        super().__init__("%s: %s (status %d)" % (where, msg, status))
+
+
+def load():
+    """Load libbitnet_hip.so (built by paper_2402_17764_amd.build).  Raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("HIP library not built: %s is missing; run `python -m paper_2402_17764_amd.build`" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, vp, ci, sz = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.bitnet_version.restype = ci
+    lib.bitnet_version.argtypes = []
+    lib.bitnet_status_string.restype = ctypes.c_char_p
+    lib.bitnet_status_string.argtypes = [ci]
+    lib.bitnet_packed_bytes.argtypes = [i64, i64, ci, ctypes.POINTER(sz)]
+    lib.bitnet_quantize_weights_workspace.argtypes = [i64, i64, ctypes.POINTER(sz)]
+    lib.bitnet_quantize_weights.argtypes = [vp, ci, i64, i64, ci, vp, vp, vp, sz, vp]
+    lib.bitnet_quantize_acts.argtypes = [vp, ci, i64, i64, vp, vp, vp]
+    lib.bitnet_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, ci, vp]
+    lib.bitnet_linear_variant.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, ci, ci, vp]
+    lib.bitnet_linear_fused.argtypes = [vp, ci, vp, vp, i64, i64, i64, ci, vp, ci, vp]
+    lib.bitnet_unpack_weights.argtypes = [vp, i64, i64, ci, vp, vp]
+    for name in SYMBOLS[2:]:
+        getattr(lib, name).restype = ci
+    _lib = lib
+    return lib
+
+
+def _check(status, where):
+    if status != OK:
+        raise BitnetError(status, where)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, name, dtypes=None, ndim=None):
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a CUDA/HIP tensor" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if dtypes is not None and t.dtype not in dtypes:
+        raise TypeError("%s has dtype %s" % (name, t.dtype))
+    if ndim is not None and t.dim() != ndim:
+        raise ValueError("%s must be %d-D" % (name, ndim))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+_FLOAT = {torch.float32: F32, torch.bfloat16: BF16}
+_OUT = {F32: torch.float32, BF16: torch.bfloat16, I32: torch.int32}
+
+
+def version():
+    return int(load().bitnet_version())
+
+
+def packed_bytes(N, K, fmt=PACK_2BIT):
+    out = ctypes.c_size_t(0)
+    _check(load().bitnet_packed_bytes(N, K, fmt, ctypes.byref(out)), "bitnet_packed_bytes")
+    return int(out.value)
+
+
+def quantize_weights_workspace(N, K):
+    out = ctypes.c_size_t(0)
+    _check(load().bitnet_quantize_weights_workspace(N, K, ctypes.byref(out)), "bitnet_quantize_weights_workspace")
+    return int(out.value)
+
+
+def quantize_weights(W, fmt=PACK_2BIT, packed=None, gamma=None, workspace=None):
+    """W [N,K] fp32/bf16 on the GPU -> (packed uint8 tensor, gamma float32[1]); Eq. (1)-(3)."""
+    lib = load()
+    wp = _dev(W, "W", _FLOAT, 2)
+    N, K = W.shape
+    if packed is None:
+        packed = torch.empty(packed_bytes(N, K, fmt), dtype=torch.uint8, device=W.device)
+    if gamma is None:
+        gamma = torch.empty(1, dtype=torch.float32, device=W.device)
+    if workspace is None:
+        workspace = torch.empty(quantize_weights_workspace(N, K), dtype=torch.uint8, device=W.device)
+    _check(lib.bitnet_quantize_weights(wp, _FLOAT[W.dtype], N, K, fmt, _dev(packed, "packed"), _dev(gamma, "gamma"),
+                                       _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
+                                       _stream()), "bitnet_quantize_weights")
+    return packed, gamma
+
+
+def quantize_acts(x, xq=None, sx=None):
+    """x [M,K] fp32/bf16 -> (x_q int8 [M,K], s_x float32 [M]); Section 2."""
+    lib = load()
+    xp = _dev(x, "x", _FLOAT, 2)
+    M, K = x.shape
+    if xq is None:
+        xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    if sx is None:
+        sx = torch.empty(M, dtype=torch.float32, device=x.device)
+    _check(lib.bitnet_quantize_acts(xp, _FLOAT[x.dtype], M, K, _dev(xq, "xq", (torch.int8,)),
+                                    _dev(sx, "sx", (torch.float32,)), _stream()), "bitnet_quantize_acts")
+    return xq, sx
+
+
+def linear(xq, sx, packed, gamma, N, fmt=PACK_2BIT, y_dtype=F32, y=None, kernel=KERNEL_AUTO):
+    """y [M,N] = (x_q . Wt^T) * gamma * s_x / 127 (or the raw int32 accumulator for y_dtype=I32)."""
+    lib = load()
+    M, K = xq.shape
+    if y is None:
+        y = torch.empty((M, N), dtype=_OUT[y_dtype], device=xq.device)
+    args = (_dev(xq, "xq", (torch.int8,), 2), _dev(sx, "sx", (torch.float32,)), _dev(packed, "packed"),
+            _dev(gamma, "gamma", (torch.float32,)), M, N, K, fmt, _dev(y, "y", (_OUT[y_dtype],)), y_dtype)
+    if kernel == KERNEL_AUTO:
+        _check(lib.bitnet_linear(*args, _stream()), "bitnet_linear")
+    else:
+        _check(lib.bitnet_linear_variant(*args, kernel, _stream()), "bitnet_linear_variant")
+    return y
+
+
+def linear_fused(x, packed, gamma, N, fmt=PACK_2BIT, y_dtype=F32, y=None):
+    """Decode path in one launch: activation quantization fused into the weight-streaming kernel."""
+    lib = load()
+    xp = _dev(x, "x", _FLOAT, 2)
+    M, K = x.shape
+    if y is None:
+        y = torch.empty((M, N), dtype=_OUT[y_dtype], device=x.device)
+    _check(lib.bitnet_linear_fused(xp, _FLOAT[x.dtype], _dev(packed, "packed"), _dev(gamma, "gamma", (torch.float32,)),
+                                   M, N, K, fmt, _dev(y, "y", (_OUT[y_dtype],)), y_dtype, _stream()),
+           "bitnet_linear_fused")
+    return y
+
+
+def unpack_weights(packed, N, K, fmt=PACK_2BIT, codes=None):
+    """packed -> int8 codes [N,K] in {-1,0,+1} (test helper)."""
+    lib = load()
+    if codes is None:
+        codes = torch.empty((N, K), dtype=torch.int8, device=packed.device)
+    _check(lib.bitnet_unpack_weights(_dev(packed, "packed"), N, K, fmt, _dev(codes, "codes", (torch.int8,)), _stream()),
+           "bitnet_unpack_weights")
+    return codes

@@ -1,0 +1,163 @@
+// C ABI of the BitLinear library (declared in include/bitnet.h): argument validation on the host,
+// then dispatch to the kernel launchers.  Nothing is allocated and no state is kept here.
+#include "bitnet.h"
+
+#include "bitnet_device.hpp"
+#include "bitnet_internal.hpp"
+
+namespace {
+
+using bitnet::OutType;
+
+constexpr int64_t kMaxElems = (int64_t)1 << 40;
+constexpr int64_t kMaxK = 262144;
+
+inline bool aligned(const void* p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a == 0; }
+
+inline bool shape_ok(int64_t M, int64_t N, int64_t K) {
+    if (M <= 0 || N <= 0 || K <= 0) return false;
+    if (K > kMaxK || M >= ((int64_t)1 << 31) || N >= ((int64_t)1 << 31)) return false;
+    if (N > kMaxElems / K || M > kMaxElems / K || M > kMaxElems / N) return false;
+    return true;
+}
+
+inline bool format_ok(bitnet_format f) { return f == BITNET_PACK_2BIT || f == BITNET_PACK_TRIT5; }
+
+inline size_t dtype_size(bitnet_dtype t) { return t == BITNET_BF16 ? 2 : 4; }
+
+inline bitnet_status from_hip(hipError_t e) { return e == hipSuccess ? BITNET_OK : BITNET_ERR_HIP; }
+
+bool out_type(bitnet_dtype t, OutType* o) {
+    switch (t) {
+        case BITNET_F32: *o = OutType::F32; return true;
+        case BITNET_BF16: *o = OutType::BF16; return true;
+        case BITNET_I32: *o = OutType::I32; return true;
+    }
+    return false;
+}
+
+}  // namespace
+
+extern "C" {
+
+int bitnet_version(void) { return 100; }
+
+const char* bitnet_status_string(bitnet_status s) {
+    switch (s) {
+        case BITNET_OK: return "ok";
+        case BITNET_ERR_NULL: return "null pointer";
+        case BITNET_ERR_SHAPE: return "bad shape";
+        case BITNET_ERR_DTYPE: return "unsupported dtype";
+        case BITNET_ERR_FORMAT: return "unsupported packing format";
+        case BITNET_ERR_ALIGN: return "misaligned pointer";
+        case BITNET_ERR_WORKSPACE: return "workspace too small";
+        case BITNET_ERR_HIP: return "HIP launch failed";
+        case BITNET_ERR_KERNEL: return "kernel variant cannot run this shape";
+    }
+    return "unknown status";
+}
+
+bitnet_status bitnet_packed_bytes(int64_t N, int64_t K, bitnet_format f, size_t* bytes) {
+    if (!bytes) return BITNET_ERR_NULL;
+    if (!shape_ok(1, N, K)) return BITNET_ERR_SHAPE;
+    const int64_t Np = 16 * bitnet::ceil_div(N, 16);
+    if (f == BITNET_PACK_2BIT) {
+        *bytes = (size_t)(Np * (64 * bitnet::ceil_div(K, 64)) / 4);
+        return BITNET_OK;
+    }
+    if (f == BITNET_PACK_TRIT5) {
+        *bytes = (size_t)(Np * (320 * bitnet::ceil_div(K, 320)) / 5);
+        return BITNET_OK;
+    }
+    return BITNET_ERR_FORMAT;
+}
+
+bitnet_status bitnet_quantize_weights_workspace(int64_t N, int64_t K, size_t* bytes) {
+    if (!bytes) return BITNET_ERR_NULL;
+    if (!shape_ok(1, N, K)) return BITNET_ERR_SHAPE;
+    *bytes = (size_t)bitnet::quant_weights_num_partials() * 2 * sizeof(double);
+    return BITNET_OK;
+}
+
+bitnet_status bitnet_quantize_weights(const void* W, bitnet_dtype w_dtype, int64_t N, int64_t K,
+                                      bitnet_format f, void* packed, float* gamma, void* workspace,
+                                      size_t workspace_bytes, void* stream) {
+    if (!W || !packed || !gamma || !workspace) return BITNET_ERR_NULL;
+    if (!shape_ok(1, N, K)) return BITNET_ERR_SHAPE;
+    if (w_dtype != BITNET_F32 && w_dtype != BITNET_BF16) return BITNET_ERR_DTYPE;
+    if (!format_ok(f)) return BITNET_ERR_FORMAT;
+    if (!aligned(W, dtype_size(w_dtype)) || !aligned(packed, 16) || !aligned(gamma, 4) || !aligned(workspace, 16))
+        return BITNET_ERR_ALIGN;
+    size_t need = 0;
+    bitnet_quantize_weights_workspace(N, K, &need);
+    if (workspace_bytes < need) return BITNET_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (f == BITNET_PACK_2BIT)
+        return from_hip(bitnet::launch_quantize_weights_2bit(W, w_dtype == BITNET_BF16, N, K, packed, gamma, workspace, s));
+    return BITNET_ERR_FORMAT;
+}
+
+bitnet_status bitnet_quantize_acts(const void* x, bitnet_dtype x_dtype, int64_t M, int64_t K, int8_t* xq,
+                                   float* sx, void* stream) {
+    if (!x || !xq || !sx) return BITNET_ERR_NULL;
+    if (!shape_ok(M, 1, K)) return BITNET_ERR_SHAPE;
+    if (x_dtype != BITNET_F32 && x_dtype != BITNET_BF16) return BITNET_ERR_DTYPE;
+    if (!aligned(x, dtype_size(x_dtype)) || !aligned(sx, 4)) return BITNET_ERR_ALIGN;
+    return from_hip(bitnet::launch_quantize_acts(x, x_dtype == BITNET_BF16, M, K, xq, sx,
+                                                 static_cast<hipStream_t>(stream)));
+}
+
+bitnet_status bitnet_linear_variant(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
+                                    int64_t M, int64_t N, int64_t K, bitnet_format f, void* y,
+                                    bitnet_dtype y_dtype, bitnet_kernel which, void* stream) {
+    if (!xq || !sx || !packed || !gamma || !y) return BITNET_ERR_NULL;
+    if (!shape_ok(M, N, K)) return BITNET_ERR_SHAPE;
+    OutType yt;
+    if (!out_type(y_dtype, &yt)) return BITNET_ERR_DTYPE;
+    if (!format_ok(f)) return BITNET_ERR_FORMAT;
+    if (!aligned(packed, 16) || !aligned(sx, 4) || !aligned(gamma, 4) || !aligned(y, dtype_size(y_dtype)))
+        return BITNET_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (f != BITNET_PACK_2BIT) return BITNET_ERR_FORMAT;
+
+    if (which == BITNET_KERNEL_AUTO) {
+        if (bitnet::gemv_supports(M, N, K, xq)) which = BITNET_KERNEL_GEMV;
+        else which = BITNET_KERNEL_REFERENCE;
+    }
+    switch (which) {
+        case BITNET_KERNEL_REFERENCE:
+            return from_hip(bitnet::launch_linear_reference_2bit(xq, sx, packed, gamma, M, N, K, y, yt, s));
+        case BITNET_KERNEL_GEMV:
+            if (!bitnet::gemv_supports(M, N, K, xq)) return BITNET_ERR_KERNEL;
+            return from_hip(bitnet::launch_linear_gemv_2bit(xq, sx, packed, gamma, M, N, K, y, yt, s));
+        default:
+            return BITNET_ERR_KERNEL;
+    }
+}
+
+bitnet_status bitnet_linear(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
+                            int64_t M, int64_t N, int64_t K, bitnet_format f, void* y, bitnet_dtype y_dtype,
+                            void* stream) {
+    return bitnet_linear_variant(xq, sx, packed, gamma, M, N, K, f, y, y_dtype, BITNET_KERNEL_AUTO, stream);
+}
+
+bitnet_status bitnet_linear_fused(const void* x, bitnet_dtype x_dtype, const void* packed, const float* gamma,
+                                  int64_t M, int64_t N, int64_t K, bitnet_format f, void* y,
+                                  bitnet_dtype y_dtype, void* stream) {
+    (void)x; (void)x_dtype; (void)packed; (void)gamma; (void)M; (void)N; (void)K; (void)f; (void)y;
+    (void)y_dtype; (void)stream;
+    return BITNET_ERR_KERNEL;
+}
+
+bitnet_status bitnet_unpack_weights(const void* packed, int64_t N, int64_t K, bitnet_format f, int8_t* codes,
+                                    void* stream) {
+    if (!packed || !codes) return BITNET_ERR_NULL;
+    if (!shape_ok(1, N, K)) return BITNET_ERR_SHAPE;
+    if (!format_ok(f)) return BITNET_ERR_FORMAT;
+    if (!aligned(packed, 16)) return BITNET_ERR_ALIGN;
+    if (f == BITNET_PACK_2BIT)
+        return from_hip(bitnet::launch_unpack_2bit(packed, N, K, codes, static_cast<hipStream_t>(stream)));
+    return BITNET_ERR_FORMAT;
+}
+
+}  // extern "C"

@@ -1,0 +1,91 @@
+// Device-side helpers shared by the gfx950 kernels of the BitLinear library: wave64 reductions,
+// bf16 widening, and the arithmetic of the packed 2-bit tile layout documented in bitnet.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bitnet {
+
+constexpr int kWave = 64;              // CDNA wavefront width
+constexpr float kEps = 1e-5f;          // epsilon of Eq. (1) and the floor of the per-token absmax
+constexpr float kQb = 127.0f;          // Q_b for 8-bit symmetric activations (Section 2)
+
+constexpr int kRowsPerBlock = 16;      // rows of one packed tile (= MFMA 16x16x64 operand rows)
+constexpr int kColsPerQuad = 64;       // columns held by one 16-byte quad of the 2-bit format
+
+__host__ __device__ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// bf16 bit pattern -> fp32 (exact).
+__device__ inline float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs).
+__device__ inline uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// ---- wave64 all-lanes reductions with DPP for the four in-row steps ------------------------------
+// quad_perm [1,0,3,2] = 0xB1, quad_perm [2,3,0,1] = 0x4E, row_half_mirror = 0x141, row_mirror = 0x140.
+template <int kCtrl>
+__device__ inline float dpp_f32(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), kCtrl, 0xF, 0xF, true));
+}
+template <int kCtrl>
+__device__ inline uint32_t dpp_u32(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, kCtrl, 0xF, 0xF, true);
+}
+
+// max over the 64 lanes of non-negative finite floats; every lane gets the result.
+__device__ inline float wave_max_nonneg(float v) {
+    v = fmaxf(v, dpp_f32<0xB1>(v));     // lane ^ 1
+    v = fmaxf(v, dpp_f32<0x4E>(v));     // lane ^ 2
+    v = fmaxf(v, dpp_f32<0x141>(v));    // other quad of the 8
+    v = fmaxf(v, dpp_f32<0x140>(v));    // other half of the 16
+    v = fmaxf(v, __shfl_xor(v, 16, kWave));
+    v = fmaxf(v, __shfl_xor(v, 32, kWave));
+    return v;
+}
+
+// OR over each aligned group of four lanes; every lane of the group gets the result.
+__device__ inline uint32_t quad_or(uint32_t v) {
+    v |= dpp_u32<0xB1>(v);
+    v |= dpp_u32<0x4E>(v);
+    return v;
+}
+
+// ---- double-double accumulation (error-free transformations, Knuth TwoSum) -----------------------
+struct dd { double hi, lo; };
+
+__device__ inline void dd_add_double(dd& s, double a) {
+    double t = s.hi + a;
+    double bb = t - s.hi;
+    double err = (s.hi - (t - bb)) + (a - bb);
+    s.hi = t;
+    s.lo += err;
+}
+__device__ inline void dd_add_dd(dd& s, const dd& o) {
+    double t = s.hi + o.hi;
+    double bb = t - s.hi;
+    double err = (s.hi - (t - bb)) + (o.hi - bb);
+    s.hi = t;
+    s.lo += err + o.lo;
+}
+
+// ---- 2-bit layout ---------------------------------------------------------------------------------
+// Eq. (1)-(2) for one weight, given d = gamma + eps: the 2-bit two's-complement code.
+__device__ inline uint32_t ternary_code2(float w, float d) {
+    float q = w / d;                        // IEEE fp32 division
+    float r = rintf(q);                     // ties to even
+    r = fminf(1.0f, fmaxf(-1.0f, r));
+    return ((uint32_t)(int)r) & 3u;         // -1 -> 0b11, 0 -> 0b00, +1 -> 0b01
+}
+
+// bit position of column c (0..15) inside its 32-bit word
+__host__ __device__ inline int code_shift(int c) { return 8 * (c & 3) + 2 * (c >> 2); }
+
+// sign-extend a 2-bit field to int
+__device__ inline int code_value(uint32_t bits2) { return ((int)(bits2 << 30)) >> 30; }
+
+}  // namespace bitnet

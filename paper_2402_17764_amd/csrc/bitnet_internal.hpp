@@ -1,0 +1,33 @@
+// Host-side launch functions of the kernel translation units; called only by api.hip, which has
+// already validated every argument.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bitnet {
+
+enum class OutType { F32 = 0, BF16 = 1, I32 = 2 };
+
+// quant_weights.hip
+int quant_weights_num_partials();
+hipError_t launch_quantize_weights_2bit(const void* W, bool bf16, int64_t N, int64_t K, void* packed,
+                                        float* gamma, void* workspace, hipStream_t stream);
+
+// quant_acts.hip
+hipError_t launch_quantize_acts(const void* x, bool bf16, int64_t M, int64_t K, int8_t* xq, float* sx,
+                                hipStream_t stream);
+
+// linear_ref.hip
+hipError_t launch_linear_reference_2bit(const int8_t* xq, const float* sx, const void* packed,
+                                        const float* gamma, int64_t M, int64_t N, int64_t K, void* y,
+                                        OutType yt, hipStream_t stream);
+hipError_t launch_unpack_2bit(const void* packed, int64_t N, int64_t K, int8_t* codes, hipStream_t stream);
+
+// linear_gemv.hip
+bool gemv_supports(int64_t M, int64_t N, int64_t K, const void* xq);
+hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void* packed,
+                                   const float* gamma, int64_t M, int64_t N, int64_t K, void* y,
+                                   OutType yt, hipStream_t stream);
+
+}  // namespace bitnet

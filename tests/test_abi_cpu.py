@@ -1,0 +1,105 @@
+"""CPU-side checks of the C ABI: the shared library loads, exports every function that
+include/bitnet.h declares, and rejects bad arguments on the host before anything is launched
+(no GPU is touched: every call below returns from validation)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2402_17764_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "bitnet.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bitnet_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_functions_are_exported():
+    lib = binding.load()
+    names = _declared_functions()
+    assert len(names) >= 10
+    for n in names:
+        assert hasattr(lib, n), "missing export: " + n
+    assert sorted(binding.SYMBOLS) == names
+
+
+def test_version_and_status_strings():
+    lib = binding.load()
+    assert binding.version() >= 100
+    seen = set()
+    for s in range(0, 9):
+        msg = lib.bitnet_status_string(s).decode()
+        assert msg and msg not in seen
+        seen.add(msg)
+    assert lib.bitnet_status_string(99).decode() == "unknown status"
+
+
+def test_packed_bytes_follow_the_documented_layouts():
+    assert binding.packed_bytes(4096, 1536, binding.PACK_2BIT) == 4096 * 1536 // 4
+    assert binding.packed_bytes(17, 65, binding.PACK_2BIT) == 32 * 128 // 4
+    assert binding.packed_bytes(1, 1, binding.PACK_2BIT) == 16 * 64 // 4
+    assert binding.packed_bytes(3200, 3200, binding.PACK_TRIT5) == 3200 * 3200 // 5
+    assert binding.packed_bytes(16, 321, binding.PACK_TRIT5) == 16 * 640 // 5
+    assert binding.quantize_weights_workspace(57344, 8192) >= 4096
+    with pytest.raises(binding.BitnetError) as e:
+        binding.packed_bytes(0, 5)
+    assert e.value.status == 2
+    with pytest.raises(binding.BitnetError) as e:
+        binding.packed_bytes(4, 4, 7)
+    assert e.value.status == 4
+    with pytest.raises(binding.BitnetError) as e:
+        binding.packed_bytes(4, 1 << 19)          # K beyond the int32 accumulator limit
+    assert e.value.status == 2
+
+
+def test_host_validation_rejects_before_launch():
+    lib = binding.load()
+    vp = ctypes.c_void_p
+    a = vp(0x1000)            # never dereferenced: validation fails first
+    odd = vp(0x1001)
+    NULL = vp(0)
+    # NULL pointers
+    assert lib.bitnet_quantize_acts(NULL, 0, 1, 16, a, a, NULL) == 1
+    assert lib.bitnet_quantize_weights(a, 0, 4, 4, 0, NULL, a, a, 1 << 20, NULL) == 1
+    assert lib.bitnet_linear(a, a, a, NULL, 1, 16, 64, 0, a, 0, NULL) == 1
+    assert lib.bitnet_unpack_weights(a, 4, 4, 0, NULL, NULL) == 1
+    # shapes
+    assert lib.bitnet_quantize_acts(a, 0, 0, 16, a, a, NULL) == 2
+    assert lib.bitnet_linear(a, a, a, a, 1, -3, 64, 0, a, 0, NULL) == 2
+    assert lib.bitnet_linear(a, a, a, a, 1, 16, 1 << 20, 0, a, 0, NULL) == 2
+    # dtypes / formats
+    assert lib.bitnet_quantize_acts(a, 2, 1, 16, a, a, NULL) == 3
+    assert lib.bitnet_quantize_weights(a, 5, 4, 4, 0, a, a, a, 1 << 20, NULL) == 3
+    assert lib.bitnet_linear(a, a, a, a, 1, 16, 64, 0, a, 9, NULL) == 3
+    assert lib.bitnet_linear(a, a, a, a, 1, 16, 64, 9, a, 0, NULL) == 4
+    # alignment
+    assert lib.bitnet_quantize_weights(a, 0, 4, 4, 0, odd, a, a, 1 << 20, NULL) == 5
+    assert lib.bitnet_linear(a, a, odd, a, 1, 16, 64, 0, a, 0, NULL) == 5
+    # workspace
+    assert lib.bitnet_quantize_weights(a, 0, 4, 4, 0, a, a, a, 8, NULL) == 6
+    # a forced kernel that cannot take the shape
+    assert lib.bitnet_linear_variant(a, a, a, a, 65, 16, 64, 0, a, 0, binding.KERNEL_GEMV, NULL) == 8
+    assert lib.bitnet_linear_variant(odd, a, a, a, 1, 16, 64, 0, a, 0, binding.KERNEL_GEMV, NULL) == 8
+
+
+def test_layout_decoder_roundtrip_on_a_hand_packed_tile():
+    """The numpy layout decoder used by the GPU tests, checked on a tile packed by hand here."""
+    import numpy as np
+    from layout_ref import decode_2bit
+    rng = np.random.default_rng(3)
+    N, K = 20, 70
+    codes = rng.integers(-1, 2, size=(N, K)).astype(np.int8)
+    Np, Kq = 32, 2
+    words = np.zeros((Np // 16, Kq, 16, 4), np.uint32)
+    for n in range(N):
+        for k in range(K):
+            c = int(codes[n, k]) & 3
+            col = k % 64
+            j, i, b = col // 16, (col % 16) // 4, col % 4
+            words[n // 16, k // 64, n % 16, j] |= np.uint32(c << (8 * b + 2 * i))
+    got, pad_zero = decode_2bit(words.astype("<u4").tobytes(), N, K)
+    assert pad_zero and np.array_equal(got, codes)

@@ -1,0 +1,270 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, through the C ABI.
+
+Bars (BitLinear of arXiv 2402.17764, Section 2): ternary codes, gamma, int8 activations, per-token
+scales and int32 accumulators are bit-exact; the rescaled output is within 1e-5 relative (fp32 out)
+or 1e-2 relative (bf16 out) of the oracle's fp64 value.
+"""
+import json
+import os
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+from layout_ref import decode_2bit
+from paper_2402_17764_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+RTOL_F32 = 1e-5
+RTOL_BF16 = 1e-2
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def bf16_tensor(bits_u16):
+    return torch.from_numpy(bits_u16.view(np.int16).copy()).cuda().view(torch.bfloat16)
+
+
+def check_y(y_gpu, y_ref, rtol):
+    y_gpu = np.asarray(y_gpu, np.float64)
+    zero = y_ref == 0
+    assert np.all(y_gpu[zero] == 0), "acc == 0 must give exactly 0"
+    err = np.abs(y_gpu[~zero] - y_ref[~zero]) / np.abs(y_ref[~zero])
+    assert err.size == 0 or err.max() <= rtol, "max rel err %.3g > %.1g" % (err.max(), rtol)
+
+
+# ------------------------------------------------------------------------------------------------
+# weights
+# ------------------------------------------------------------------------------------------------
+WEIGHT_SHAPES = [(4096, 1536), (16, 64), (1, 1), (37, 129), (100, 70), (17, 1000), (33, 2050), (250, 4100)]
+
+
+@pytest.mark.parametrize("N,K", WEIGHT_SHAPES)
+def test_quantize_weights_matches_oracle(gpu_lib, N, K):
+    say("quantize_weights fp32 N=%d K=%d" % (N, K))
+    W = synth.weights(N, K, config=0, layer=N % 7, tensor=0)
+    codes_ref, gamma_ref = oracle.quantize_weights(W)
+    packed, gamma = gpu_lib.quantize_weights(dev(W))
+    torch.cuda.synchronize()
+    assert gamma.cpu().numpy()[0].tobytes() == np.float32(gamma_ref).tobytes(), "gamma bits differ"
+    codes = gpu_lib.unpack_weights(packed, N, K).cpu().numpy()
+    assert np.array_equal(codes, codes_ref)
+    # the bytes follow the documented layout, and padding is zero codes
+    assert packed.numel() == gpu_lib.packed_bytes(N, K)
+    dec, pad_zero = decode_2bit(packed.cpu().numpy(), N, K)
+    assert pad_zero and np.array_equal(dec, codes_ref)
+
+
+def test_quantize_weights_bf16_input_and_unaligned_rows(gpu_lib):
+    say("quantize_weights bf16 + odd K")
+    for (N, K) in [(64, 256), (19, 77)]:
+        Wf, bits = synth.to_bf16(synth.weights(N, K, config=0, layer=5))
+        codes_ref, gamma_ref = oracle.quantize_weights(Wf)
+        packed, gamma = gpu_lib.quantize_weights(bf16_tensor(bits).view(N, K))
+        assert gamma.cpu().numpy()[0] == gamma_ref
+        assert np.array_equal(gpu_lib.unpack_weights(packed, N, K).cpu().numpy(), codes_ref)
+    # fp32 matrix whose base pointer is only 4-byte aligned
+    N, K = 24, 132
+    W = synth.weights(N, K, config=0, layer=6)
+    buf = torch.empty(N * K + 1, dtype=torch.float32, device="cuda")
+    buf[1:] = dev(W).reshape(-1)
+    codes_ref, gamma_ref = oracle.quantize_weights(W)
+    packed, gamma = gpu_lib.quantize_weights(buf[1:].view(N, K))
+    assert gamma.cpu().numpy()[0] == gamma_ref
+    assert np.array_equal(gpu_lib.unpack_weights(packed, N, K).cpu().numpy(), codes_ref)
+
+
+def test_quantize_weights_edge_values(gpu_lib):
+    say("quantize_weights edge values")
+    # all-zero matrix
+    Z = np.zeros((20, 70), np.float32)
+    packed, gamma = gpu_lib.quantize_weights(dev(Z))
+    assert gamma.cpu().numpy()[0] == 0 and not packed.cpu().numpy().any()
+    # exact ties of Eq. (2): gamma + eps == 2^-3, so W = q/8 reproduces the golden q list exactly
+    g = json.load(open(os.path.join(GOLDEN, "rounding_ties.json")))["round_clip"]
+    q = np.array(g["q"], np.float32)
+    target_gamma = np.float32(0.125) - np.float32(1e-5)
+    # build a matrix whose mean |W| is exactly target_gamma is awkward; instead check through the
+    # oracle on a matrix that contains the tie values: both sides must agree bit for bit
+    W = synth.weights(8, 64, config=0, layer=8)
+    gam, _ = oracle.absmean_gamma(W)
+    d = np.float32(np.float32(gam) + np.float32(1e-5))
+    W[0, : q.size] = q * d
+    codes_ref, gamma_ref = oracle.quantize_weights(W)
+    packed, gamma = gpu_lib.quantize_weights(dev(W))
+    assert gamma.cpu().numpy()[0] == gamma_ref
+    assert np.array_equal(gpu_lib.unpack_weights(packed, 8, 64).cpu().numpy(), codes_ref)
+    # wide dynamic range: the compensated sum must not lose the small terms
+    W = np.full((4, 64), 1.0, np.float32)
+    W[0, 0] = 1e8
+    W[3, 63] = -1e8
+    codes_ref, gamma_ref = oracle.quantize_weights(W)
+    packed, gamma = gpu_lib.quantize_weights(dev(W))
+    assert gamma.cpu().numpy()[0] == gamma_ref
+    assert np.array_equal(gpu_lib.unpack_weights(packed, 4, 64).cpu().numpy(), codes_ref)
+    # determinism: same bytes twice
+    W = synth.weights(300, 700, config=0, layer=9)
+    p1, g1 = gpu_lib.quantize_weights(dev(W))
+    p2, g2 = gpu_lib.quantize_weights(dev(W))
+    assert torch.equal(p1, p2) and torch.equal(g1, g2)
+
+
+# ------------------------------------------------------------------------------------------------
+# activations
+# ------------------------------------------------------------------------------------------------
+ACT_SHAPES = [(1, 1536), (16, 1536), (1, 1), (3, 515), (5, 28672), (70, 4096), (2, 40000)]
+
+
+@pytest.mark.parametrize("M,K", ACT_SHAPES)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_quantize_acts_matches_oracle(gpu_lib, M, K, dtype):
+    say("quantize_acts %s M=%d K=%d" % (dtype, M, K))
+    if dtype == "bf16":
+        x, bits = synth.activations(M, K, config=0, layer=K % 11, bf16=True)
+        xd = bf16_tensor(bits).view(M, K)
+    else:
+        x = synth.activations(M, K, config=0, layer=K % 11)
+        xd = dev(x)
+    xq_ref, sx_ref = oracle.quantize_acts(x)
+    xq, sx = gpu_lib.quantize_acts(xd)
+    assert np.array_equal(sx.cpu().numpy().view(np.uint32), sx_ref.view(np.uint32))
+    assert np.array_equal(xq.cpu().numpy(), xq_ref)
+
+
+def test_quantize_acts_edge_values(gpu_lib):
+    say("quantize_acts edge values")
+    g = json.load(open(os.path.join(GOLDEN, "rounding_ties.json")))["acts"]
+    xq, sx = gpu_lib.quantize_acts(dev(np.array(g["x"], np.float32)))
+    assert xq.cpu().numpy().tolist() == g["xq"] and sx.cpu().numpy().tolist() == g["sx"]
+    # all-zero token, sub-floor token, one huge outlier, misaligned base pointer
+    x = np.zeros((4, 64), np.float32)
+    x[1, 3] = 5e-6
+    x[2] = 0.001
+    x[2, 5] = -1000.0
+    x[3] = synth.activations(1, 64, config=0, layer=2)[0]
+    xq_ref, sx_ref = oracle.quantize_acts(x)
+    xq, sx = gpu_lib.quantize_acts(dev(x))
+    assert np.array_equal(xq.cpu().numpy(), xq_ref) and np.array_equal(sx.cpu().numpy(), sx_ref)
+    buf = torch.empty(4 * 64 + 1, dtype=torch.float32, device="cuda")
+    buf[1:] = dev(x).reshape(-1)
+    xq, sx = gpu_lib.quantize_acts(buf[1:].view(4, 64))
+    assert np.array_equal(xq.cpu().numpy(), xq_ref) and np.array_equal(sx.cpu().numpy(), sx_ref)
+
+
+# ------------------------------------------------------------------------------------------------
+# the product
+# ------------------------------------------------------------------------------------------------
+def _run_linear_case(gpu_lib, M, N, K, kernels, layer=0, bf16_acts=False):
+    W = synth.weights(N, K, config=0, layer=layer, tensor=0)
+    if bf16_acts:
+        x, bits = synth.activations(M, K, config=0, layer=layer, bf16=True)
+        xd = bf16_tensor(bits).view(M, K)
+    else:
+        x = synth.activations(M, K, config=0, layer=layer)
+        xd = dev(x)
+    ref = oracle.bitlinear(x, W)
+    packed, gamma = gpu_lib.quantize_weights(dev(W))
+    xq, sx = gpu_lib.quantize_acts(xd)
+    assert np.array_equal(xq.cpu().numpy(), ref["xq"])
+    for kern in kernels:
+        acc = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.I32, kernel=kern)
+        assert np.array_equal(acc.cpu().numpy(), ref["acc"]), "int32 accumulators differ (kernel %d)" % kern
+        y32 = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.F32, kernel=kern)
+        check_y(y32.cpu().numpy(), ref["y"], RTOL_F32)
+        y16 = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.BF16, kernel=kern)
+        check_y(y16.float().cpu().numpy(), ref["y"], RTOL_BF16)
+    return ref
+
+
+def test_worked_example_on_gpu(gpu_lib):
+    say("worked example")
+    g = json.load(open(os.path.join(GOLDEN, "worked_example.json")))
+    W = np.array(g["W"], np.float32)
+    x = np.array(g["x"], np.float32)
+    packed, gamma = gpu_lib.quantize_weights(dev(W))
+    xq, sx = gpu_lib.quantize_acts(dev(x))
+    assert gamma.cpu().numpy()[0] == g["gamma"]
+    assert gpu_lib.unpack_weights(packed, 2, 4).cpu().numpy().tolist() == g["codes"]
+    assert xq.cpu().numpy().tolist() == g["xq"] and sx.cpu().numpy().tolist() == g["sx"]
+    acc = gpu_lib.linear(xq, sx, packed, gamma, 2, y_dtype=gpu_lib.I32)
+    assert acc.cpu().numpy().tolist() == g["acc"]
+    y = gpu_lib.linear(xq, sx, packed, gamma, 2)
+    np.testing.assert_allclose(y.cpu().numpy(), np.array(g["y"]), rtol=RTOL_F32)
+
+
+REF_SHAPES = [(1, 1, 1), (3, 5, 7), (2, 37, 129), (5, 100, 70), (16, 4096, 1536)]
+
+
+@pytest.mark.parametrize("M,N,K", REF_SHAPES)
+def test_linear_reference_kernel(gpu_lib, M, N, K):
+    say("linear reference M=%d N=%d K=%d" % (M, N, K))
+    _run_linear_case(gpu_lib, M, N, K, [gpu_lib.KERNEL_REFERENCE, gpu_lib.KERNEL_AUTO], layer=M)
+
+
+# several tiles plus ragged tails in every dimension the GEMV kernel tiles: N (16-row blocks, groups
+# of 1/2/4 blocks), K (quads of 64, steps of 256, split over 4 or 8 waves), M (tiles of 16)
+GEMV_SHAPES = [(1, 4096, 1536), (16, 4096, 1536), (1, 16, 64), (1, 17, 16), (3, 100, 80), (7, 250, 1040),
+               (16, 33, 4112), (17, 70, 528), (32, 1000, 3200), (33, 130, 272), (64, 96, 1024), (50, 49, 2064)]
+
+
+@pytest.mark.parametrize("M,N,K", GEMV_SHAPES)
+def test_linear_gemv_kernel(gpu_lib, M, N, K):
+    say("linear gemv M=%d N=%d K=%d" % (M, N, K))
+    _run_linear_case(gpu_lib, M, N, K, [gpu_lib.KERNEL_GEMV, gpu_lib.KERNEL_AUTO], layer=M, bf16_acts=(M % 2 == 0))
+
+
+def test_linear_extreme_accumulators(gpu_lib):
+    """Every product at +-127 with all-(+1) / all-(-1) rows: the largest accumulators a shape can give."""
+    say("linear extreme accumulators")
+    M, N, K = 2, 32, 28672
+    W = np.ones((N, K), np.float32)
+    W[1::2] = -1.0
+    x = np.full((M, K), 3.0, np.float32)
+    x[1] = -3.0
+    ref = oracle.bitlinear(x, W)
+    assert abs(int(ref["acc"][0, 0])) == 127 * K
+    packed, gamma = gpu_lib.quantize_weights(dev(W))
+    xq, sx = gpu_lib.quantize_acts(dev(x))
+    for kern in (gpu_lib.KERNEL_REFERENCE, gpu_lib.KERNEL_GEMV):
+        acc = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.I32, kernel=kern)
+        assert np.array_equal(acc.cpu().numpy(), ref["acc"])
+
+
+def test_linear_is_deterministic(gpu_lib):
+    say("linear determinism")
+    M, N, K = 8, 1000, 3200
+    packed, gamma = gpu_lib.quantize_weights(dev(synth.weights(N, K, config=0, layer=3)))
+    xq, sx = gpu_lib.quantize_acts(dev(synth.activations(M, K, config=0, layer=3)))
+    a = gpu_lib.linear(xq, sx, packed, gamma, N)
+    b = gpu_lib.linear(xq, sx, packed, gamma, N)
+    assert torch.equal(a, b)
+
+
+def test_outputs_do_not_spill_past_their_buffers(gpu_lib):
+    say("canaries")
+    M, N, K = 3, 50, 144
+    W = dev(synth.weights(N, K, config=0, layer=4))
+    x = dev(synth.activations(M, K, config=0, layer=4))
+    nbytes = gpu_lib.packed_bytes(N, K)
+    big = torch.full((nbytes + 64,), 0xAB, dtype=torch.uint8, device="cuda")
+    packed, gamma = gpu_lib.quantize_weights(W, packed=big[:nbytes])
+    assert bool((big[nbytes:] == 0xAB).all())
+    xq_big = torch.full((M * K + 64,), 0x55, dtype=torch.int8, device="cuda")
+    xq, sx = gpu_lib.quantize_acts(x, xq=xq_big[: M * K].view(M, K))
+    assert bool((xq_big[M * K:] == 0x55).all())
+    y_big = torch.full((M * N + 16,), 7.0, dtype=torch.float32, device="cuda")
+    for kern in (gpu_lib.KERNEL_REFERENCE, gpu_lib.KERNEL_GEMV):
+        gpu_lib.linear(xq, sx, packed, gamma, N, y=y_big[: M * N].view(M, N), kernel=kern)
+        assert bool((y_big[M * N:] == 7.0).all())
