@@ -62,15 +62,19 @@ typedef enum bitnet_dtype {
  * Storage formats for the ternary matrix Wt (Section 3 of the paper stores 2 bits per weight and
  * notes that 1.58 bits leaves room below that).
  *
- * BITNET_PACK_2BIT -- 4 codes per byte, tiled for 64-lane wavefronts.
- *   N is padded to Np = 16*ceil(N/16) rows and K to Kp = 64*ceil(K/64) columns with zero codes.
- *   The buffer is an array of 16-byte "quads"; quad index ((rb * (Kp/64) + kb) * 16 + r) holds the
- *   64 codes of row n = 16*rb + r, columns k = 64*kb .. 64*kb+63.  A quad is four little-endian
- *   32-bit words; word j holds columns 64*kb + 16*j .. +15; inside a word the code of column
- *   16*j + 4*i + b  (i, b in 0..3) sits in bits [8*b + 2*i, 8*b + 2*i + 1].
- *   A code is 2-bit two's complement: 00 = 0, 01 = +1, 11 = -1 (10 never occurs).
- *   Size: Np * Kp / 4 bytes.  One 16-row x 64-column tile is 256 contiguous bytes, tiles of one row
- *   block are contiguous along K, so a wavefront reads 1 KiB runs with one 128-bit load per lane.
+ * BITNET_PACK_2BIT -- 4 codes per byte, tiled for 64-lane wavefronts, K-step major.
+ *   N is padded to Np = 16*ceil(N/16) rows (RB = Np/16 row blocks) and K to Kp = 64*ceil(K/64)
+ *   columns (Kq = Kp/64) with zero codes.  The buffer is an array of 16-byte "quads"; one quad holds
+ *   the 64 codes of one row for 64 consecutive columns.  Columns are grouped into steps of 256
+ *   (4 quads); the last step may hold fewer: nq(s) = min(4, Kq - 4*s).  The quad of row
+ *   n = 16*rb + r, columns 64*(4*s + g) .. +63  (g < nq(s)) has index
+ *       64*RB*s + 16*nq(s)*rb + 16*g + r,
+ *   i.e. for each step all row blocks follow one another, and one (step, row block) chunk is the
+ *   1 KiB that the 64 lanes of a wavefront fetch with one 128-bit load each (lane = 16*g + r).
+ *   A quad is four little-endian 32-bit words; word j holds columns 16*j .. 16*j+15 of the quad;
+ *   inside a word the code of column 16*j + 4*i + b  (i, b in 0..3) sits in bits
+ *   [8*b + 2*i, 8*b + 2*i + 1].  A code is 2-bit two's complement: 00 = 0, 01 = +1, 11 = -1
+ *   (10 never occurs).  Size: Np * Kp / 4 bytes.
  *
  * BITNET_PACK_TRIT5 -- 5 codes per byte (1.6 bits per weight), base 3.
  *   N padded to Np as above, K padded to Kp = 320*ceil(K/320) columns with zero codes.  The buffer

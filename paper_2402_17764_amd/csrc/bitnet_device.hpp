@@ -82,6 +82,14 @@ __device__ inline uint32_t ternary_code2(float w, float d) {
     return ((uint32_t)(int)r) & 3u;         // -1 -> 0b11, 0 -> 0b00, +1 -> 0b01
 }
 
+// index of the quad holding row 16*rb + r, columns 64*kq .. 64*kq+63 (Kq quads per row, RB row blocks):
+// steps of four quad columns are outermost, row blocks next, then the quad column and the row.
+__host__ __device__ inline int64_t quad_index_2bit(int64_t kq, int64_t rb, int r, int64_t Kq, int64_t RB) {
+    const int64_t s = kq >> 2, g = kq & 3;
+    const int64_t nq = (Kq - 4 * s) < 4 ? (Kq - 4 * s) : 4;
+    return 64 * RB * s + 16 * nq * rb + 16 * g + r;
+}
+
 // bit position of column c (0..15) inside its 32-bit word
 __host__ __device__ inline int code_shift(int c) { return 8 * (c & 3) + 2 * (c >> 2); }
 

@@ -113,14 +113,15 @@ __global__ __launch_bounds__(kSumThreads) void finish_gamma(const double* __rest
 // reads 1024 consecutive columns (lane l, sub-step t: columns 256 t + 4 l .. +3, a 16-byte load for
 // fp32), so reads are 1 KiB runs.  The four codes of a lane land in one word at bits 8 b + 2 i with
 // i = l & 3; OR-ing the four lanes of a quad completes the word.  Words are staged in LDS in output
-// order ([16 quads of K][16 rows][4 words] = 4 KiB) and written out as one contiguous run.
+// order ([16 quads of K][16 rows][4 words] = 4 KiB) and written out as 256-byte runs, one per quad
+// column, which land inside the 1 KiB (step, row block) chunks of the packed layout.
 constexpr int kPackWaves = 16;
 constexpr int kPackThreads = kPackWaves * kWave;          // 1024
 constexpr int kPackColsPerStep = 1024;                    // 16 quads along K per workgroup step
 
 template <typename T, bool kVec>
 __global__ __launch_bounds__(kPackThreads) void ternarize_pack_2bit(const T* __restrict__ W, int64_t N, int64_t K,
-                                                                    int64_t Kq /* quads per row */,
+                                                                    int64_t Kq /* quads per row */, int64_t RB,
                                                                     const float* __restrict__ gamma,
                                                                     uint32_t* __restrict__ packed) {
     using V = typename Vec4<T>::type;
@@ -163,7 +164,7 @@ __global__ __launch_bounds__(kPackThreads) void ternarize_pack_2bit(const T* __r
         {
             const int quad = threadIdx.x >> 6;
             const int64_t kq = k0 / kColsPerQuad + quad;
-            if (kq < Kq) packed[((rb * Kq + kq) * 16) * 4 + (threadIdx.x & 63)] = stage[threadIdx.x];
+            if (kq < Kq) packed[quad_index_2bit(kq, rb, 0, Kq, RB) * 4 + (threadIdx.x & 63)] = stage[threadIdx.x];
         }
         __syncthreads();
     }
@@ -201,12 +202,12 @@ hipError_t launch_quantize_weights_2bit(const void* W, bool bf16, int64_t N, int
     uint32_t* out = static_cast<uint32_t*>(packed);
     if (bf16) {
         const uint16_t* w = static_cast<const uint16_t*>(W);
-        if (vec) hipLaunchKernelGGL((ternarize_pack_2bit<uint16_t, true>), grid, dim3(kPackThreads), 0, stream, w, N, K, Kq, gamma, out);
-        else     hipLaunchKernelGGL((ternarize_pack_2bit<uint16_t, false>), grid, dim3(kPackThreads), 0, stream, w, N, K, Kq, gamma, out);
+        if (vec) hipLaunchKernelGGL((ternarize_pack_2bit<uint16_t, true>), grid, dim3(kPackThreads), 0, stream, w, N, K, Kq, RB, gamma, out);
+        else     hipLaunchKernelGGL((ternarize_pack_2bit<uint16_t, false>), grid, dim3(kPackThreads), 0, stream, w, N, K, Kq, RB, gamma, out);
     } else {
         const float* w = static_cast<const float*>(W);
-        if (vec) hipLaunchKernelGGL((ternarize_pack_2bit<float, true>), grid, dim3(kPackThreads), 0, stream, w, N, K, Kq, gamma, out);
-        else     hipLaunchKernelGGL((ternarize_pack_2bit<float, false>), grid, dim3(kPackThreads), 0, stream, w, N, K, Kq, gamma, out);
+        if (vec) hipLaunchKernelGGL((ternarize_pack_2bit<float, true>), grid, dim3(kPackThreads), 0, stream, w, N, K, Kq, RB, gamma, out);
+        else     hipLaunchKernelGGL((ternarize_pack_2bit<float, false>), grid, dim3(kPackThreads), 0, stream, w, N, K, Kq, RB, gamma, out);
     }
     return hipGetLastError();
 }

@@ -3,6 +3,16 @@
 import numpy as np
 
 
+def quad_index_2bit(n, kq, N, K):
+    """Index of the 16-byte quad that holds row n, columns 64*kq .. 64*kq+63."""
+    RB = (N + 15) // 16
+    Kq = (K + 63) // 64
+    rb, r = divmod(n, 16)
+    s, g = divmod(kq, 4)
+    nq = min(4, Kq - 4 * s)
+    return 64 * RB * s + 16 * nq * rb + 16 * g + r
+
+
 def decode_2bit(packed_bytes, N, K):
     """bytes of a BITNET_PACK_2BIT buffer -> (codes [N,K] int8, padding_is_zero bool)."""
     Np = 16 * ((N + 15) // 16)
@@ -13,18 +23,24 @@ def decode_2bit(packed_bytes, N, K):
         raw = np.ascontiguousarray(packed_bytes, dtype=np.uint8).tobytes()
     words = np.frombuffer(raw, dtype="<u4")
     assert words.size == Np * Kq * 4, "buffer size does not match the documented layout"
-    # quad index ((rb*Kq + kb)*16 + r), 4 words per quad
-    words = words.reshape(Np // 16, Kq, 16, 4)                 # [rb][kb][r][j]
-    full = np.zeros((Np, Kq * 64), np.int8)
+    quads = words.reshape(-1, 4)
+    # gather quads into [n][kq][word]
+    n_idx = np.arange(Np)[:, None]
+    kq_idx = np.arange(Kq)[None, :]
+    rb, r = n_idx // 16, n_idx % 16
+    s, g = kq_idx // 4, kq_idx % 4
+    nq = np.minimum(4, Kq - 4 * s)
+    qi = 64 * (Np // 16) * s + 16 * nq * rb + 16 * g + r
+    assert np.array_equal(np.sort(qi.ravel()), np.arange(Np * Kq)), "layout is not a bijection"
+    by_row = quads[qi]                                        # [Np][Kq][4]
+    full = np.zeros((Np, Kq, 64), np.int8)
     for j in range(4):
         for i in range(4):
             for b in range(4):
-                col = 16 * j + 4 * i + b
-                field = (words[:, :, :, j] >> np.uint32(8 * b + 2 * i)) & np.uint32(3)   # [rb][kb][r]
-                val = np.where(field == 3, -1, field.astype(np.int8)).astype(np.int8)
+                field = (by_row[:, :, j] >> np.uint32(8 * b + 2 * i)) & np.uint32(3)
                 assert not np.any(field == 2), "code 10 must never occur"
-                # rows rb*16 + r, columns kb*64 + col
-                full.reshape(Np // 16, 16, Kq, 64)[:, :, :, col] = val.transpose(0, 2, 1)
+                full[:, :, 16 * j + 4 * i + b] = np.where(field == 3, -1, field.astype(np.int8))
+    full = full.reshape(Np, Kq * 64)
     codes = full[:N, :K].copy()
     pad_zero = (not full[N:, :].any()) and (not full[:, K:].any())
     return codes, pad_zero

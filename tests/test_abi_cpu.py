@@ -89,17 +89,22 @@ def test_host_validation_rejects_before_launch():
 def test_layout_decoder_roundtrip_on_a_hand_packed_tile():
     """The numpy layout decoder used by the GPU tests, checked on a tile packed by hand here."""
     import numpy as np
-    from layout_ref import decode_2bit
+    from layout_ref import decode_2bit, quad_index_2bit
     rng = np.random.default_rng(3)
-    N, K = 20, 70
-    codes = rng.integers(-1, 2, size=(N, K)).astype(np.int8)
-    Np, Kq = 32, 2
-    words = np.zeros((Np // 16, Kq, 16, 4), np.uint32)
-    for n in range(N):
-        for k in range(K):
-            c = int(codes[n, k]) & 3
-            col = k % 64
-            j, i, b = col // 16, (col % 16) // 4, col % 4
-            words[n // 16, k // 64, n % 16, j] |= np.uint32(c << (8 * b + 2 * i))
-    got, pad_zero = decode_2bit(words.astype("<u4").tobytes(), N, K)
-    assert pad_zero and np.array_equal(got, codes)
+    for (N, K) in [(20, 70), (33, 600), (16, 256)]:
+        codes = rng.integers(-1, 2, size=(N, K)).astype(np.int8)
+        Np, Kq = 16 * ((N + 15) // 16), (K + 63) // 64
+        words = np.zeros((Np * Kq, 4), np.uint32)
+        for n in range(N):
+            for k in range(K):
+                c = int(codes[n, k]) & 3
+                col = k % 64
+                j, i, b = col // 16, (col % 16) // 4, col % 4
+                words[quad_index_2bit(n, k // 64, N, K), j] |= np.uint32(c << (8 * b + 2 * i))
+        got, pad_zero = decode_2bit(words.astype("<u4").tobytes(), N, K)
+        assert pad_zero and np.array_equal(got, codes)
+    # spot values of the index formula: 600 columns = 10 quads = two full steps and one of two quads
+    assert quad_index_2bit(0, 0, 33, 600) == 0
+    assert quad_index_2bit(17, 1, 33, 600) == 64 * 1 + 16 * 1 + 1          # rb 1, g 1, r 1
+    assert quad_index_2bit(0, 4, 33, 600) == 64 * 3                          # step 1 starts after 3 row blocks
+    assert quad_index_2bit(32, 9, 33, 600) == 64 * 3 * 2 + 16 * 2 * 2 + 16 * 1 + 0   # partial step: 2 quads per chunk

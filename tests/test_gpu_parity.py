@@ -95,9 +95,7 @@ def test_quantize_weights_edge_values(gpu_lib):
     # exact ties of Eq. (2): gamma + eps == 2^-3, so W = q/8 reproduces the golden q list exactly
     g = json.load(open(os.path.join(GOLDEN, "rounding_ties.json")))["round_clip"]
     q = np.array(g["q"], np.float32)
-    target_gamma = np.float32(0.125) - np.float32(1e-5)
-    # build a matrix whose mean |W| is exactly target_gamma is awkward; instead check through the
-    # oracle on a matrix that contains the tie values: both sides must agree bit for bit
+    # a matrix that contains the tie values scaled by its own gamma + eps: both sides must agree bit for bit
     W = synth.weights(8, 64, config=0, layer=8)
     gam, _ = oracle.absmean_gamma(W)
     d = np.float32(np.float32(gam) + np.float32(1e-5))
@@ -216,7 +214,10 @@ def test_linear_reference_kernel(gpu_lib, M, N, K):
 # several tiles plus ragged tails in every dimension the GEMV kernel tiles: N (16-row blocks, groups
 # of 1/2/4 blocks), K (quads of 64, steps of 256, split over 4 or 8 waves), M (tiles of 16)
 GEMV_SHAPES = [(1, 4096, 1536), (16, 4096, 1536), (1, 16, 64), (1, 17, 16), (3, 100, 80), (7, 250, 1040),
-               (16, 33, 4112), (17, 70, 528), (32, 1000, 3200), (33, 130, 272), (64, 96, 1024), (50, 49, 2064)]
+               (16, 33, 4112), (17, 70, 528), (32, 1000, 3200), (33, 130, 272), (64, 96, 1024), (50, 49, 2064),
+               # one shape per branch of the kernel-selection heuristic (row blocks x K steps)
+               (2, 32800, 528), (3, 16400, 4112), (1, 16400, 272), (5, 6416, 16400), (4, 6416, 1040),
+               (2, 100, 6160), (16, 1000, 8192)]
 
 
 @pytest.mark.parametrize("M,N,K", GEMV_SHAPES)
