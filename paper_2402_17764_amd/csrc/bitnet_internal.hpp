@@ -29,5 +29,8 @@ bool gemv_supports(int64_t M, int64_t N, int64_t K, const void* xq);
 hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void* packed,
                                    const float* gamma, int64_t M, int64_t N, int64_t K, void* y,
                                    OutType yt, hipStream_t stream);
+bool gemv_fused_supports(int64_t M, int64_t N, int64_t K, const void* x);
+hipError_t launch_linear_fused_2bit(const void* x, bool bf16, const void* packed, const float* gamma, int64_t M,
+                                    int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);
 
 }  // namespace bitnet

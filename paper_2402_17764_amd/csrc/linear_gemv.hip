@@ -69,66 +69,146 @@ __device__ inline void store_row4(void* y, OutType yt, int64_t base, int64_t n0,
 // ---------------------------------------------------------------------------------------------------
 // M <= 16
 // ---------------------------------------------------------------------------------------------------
+// Where the activation operand comes from.
+enum XMode : int {
+    kXGlobal = 0,      // int8 x_q read from global memory with every step
+    kXLds = 1,         // int8 x_q copied once per workgroup into LDS
+    kXFusedBf16 = 2,   // bf16 x: per-token absmax quantization done in the kernel, x_q lives only in LDS
+    kXFusedF32 = 3     // fp32 x, same
+};
+
+constexpr int kGemvLdsHeader = 8;       // uint4 slots in front of the x region: reduction scratch + s_x
+
+// Quantize the M tokens of x into LDS (Section 2 of the paper: per-token absmax, Q_b = 127), the same
+// arithmetic as the stand-alone activation kernel: s = max(absmax, 1e-5), inv = 127 / s,
+// x_q = clip(rint(x * inv)).  Rows are zero padded to Kpad columns.  s_x[m] is left in sxl[m].
+template <bool kBf16, int kThreads>
+__device__ inline void fused_quantize_to_lds(const void* __restrict__ xv, int M, int64_t K, int Kpad,
+                                             float* red /* kThreads/64 floats */, float* sxl, uint4* xlds) {
+    constexpr int kE = kBf16 ? 8 : 4;                 // elements per 16-byte load
+    const int nvec = (int)(K / kE);
+    const int nvec_pad = Kpad / kE;
+    for (int m = 0; m < M; ++m) {
+        const uint4* row = reinterpret_cast<const uint4*>(static_cast<const char*>(xv) + (int64_t)m * K * (kBf16 ? 2 : 4));
+        float amax = 0.0f;
+        for (int v = threadIdx.x; v < nvec; v += kThreads) {
+            const uint4 q = row[v];
+            const uint32_t u[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (kBf16) {
+                    amax = fmaxf(amax, fabsf(__uint_as_float(u[e] << 16)));
+                    amax = fmaxf(amax, fabsf(__uint_as_float(u[e] & 0xFFFF0000u)));
+                } else {
+                    amax = fmaxf(amax, fabsf(__uint_as_float(u[e])));
+                }
+            }
+        }
+        amax = wave_max_nonneg(amax);
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = amax;
+        __syncthreads();
+        float mx = red[0];
+#pragma unroll
+        for (int w = 1; w < kThreads / kWave; ++w) mx = fmaxf(mx, red[w]);
+        const float sc = fmaxf(mx, kEps);
+        const float inv = kQb / sc;                   // one IEEE division per token
+        if (threadIdx.x == 0) sxl[m] = sc;
+        uint32_t* out = reinterpret_cast<uint32_t*>(xlds) + (size_t)m * (Kpad >> 2);
+        for (int v = threadIdx.x; v < nvec_pad; v += kThreads) {
+            uint4 q = make_uint4(0, 0, 0, 0);
+            if (v < nvec) q = row[v];
+            const uint32_t u[4] = {q.x, q.y, q.z, q.w};
+            if (kBf16) {
+                uint32_t o[2] = {0, 0};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float lo = rintf(__uint_as_float(u[e] << 16) * inv);
+                    const float hi = rintf(__uint_as_float(u[e] & 0xFFFF0000u) * inv);
+                    const int ql = (int)fminf(kQb, fmaxf(-kQb, lo));
+                    const int qh = (int)fminf(kQb, fmaxf(-kQb, hi));
+                    o[e >> 1] |= (((uint32_t)ql & 0xFFu) | (((uint32_t)qh & 0xFFu) << 8)) << (16 * (e & 1));
+                }
+                out[2 * v] = o[0];
+                out[2 * v + 1] = o[1];
+            } else {
+                uint32_t o = 0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float f = rintf(__uint_as_float(u[e]) * inv);
+                    o |= ((uint32_t)(int)fminf(kQb, fmaxf(-kQb, f)) & 0xFFu) << (8 * e);
+                }
+                out[v] = o;
+            }
+        }
+        __syncthreads();                              // red[] is reused by the next token
+    }
+}
+
 // kR    row blocks (16 rows each) per wave
 // kS    waves that split K: wave ws takes steps ws, ws + kS, ...
 // kW    row slots per workgroup (waves with different row blocks), workgroup = kS * kW waves
 // kD    register prefetch depth in steps
-// kXLds activations staged once per workgroup in LDS (needs M * Kpad bytes) instead of global loads
-template <int kR, int kS, int kW, int kD, bool kXLds>
+// kX    XMode
+template <int kR, int kS, int kW, int kD, int kX>
 __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
-        const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
-        const float* __restrict__ gamma, int M, int64_t N, int64_t K, int Kq, int RB,
+        const void* __restrict__ xin /* x_q, or x for the fused modes */, const float* __restrict__ sx,
+        const uint4* __restrict__ packed, const float* __restrict__ gamma, int M, int64_t N, int64_t K, int Kq, int RB,
         int items /* K steps per wave, rounded up to a multiple of kD */, void* __restrict__ y, OutType yt) {
     extern __shared__ uint4 smem[];
+    constexpr int kThreads = kS * kW * kWave;
+    constexpr bool kFromLds = kX != kXGlobal;
+    constexpr bool kFused = kX == kXFusedBf16 || kX == kXFusedF32;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const int r = lane & 15;
     const int g = lane >> 4;
     const int ws = wave % kS;
     const int ww = wave / kS;
-    const int steps = (Kq + 3) >> 2;
+    const int steps = (Kq + 3) >> 2;                   // K steps of 256 columns, the last may be partial
+    const int tail_quads = 16 * (Kq - 4 * (steps - 1));   // quads in the last step's chunk (64 if whole)
     const int rbw = (blockIdx.x * kW + ww) * kR;
     const int Kpad = steps * 256;
-    const int last_full = (int)(K >> 8) - 1;         // last step whose 256 columns all exist (-1: none)
+    const int8_t* xq = static_cast<const int8_t*>(xin);
 
-    if (kXLds) {
-        // rows < M of x_q, zero padded to Kpad columns
-        const int nvec = M * (Kpad >> 4);
-        for (int v = threadIdx.x; v < nvec; v += kS * kW * kWave) {
-            const int m = v / (Kpad >> 4), kv = v % (Kpad >> 4);
-            uint4 val = make_uint4(0, 0, 0, 0);
-            if ((int64_t)kv * 16 + 16 <= K) val = reinterpret_cast<const uint4*>(xq + (int64_t)m * K)[kv];
-            smem[v] = val;
-        }
-    }
+    float* red = reinterpret_cast<float*>(smem);       // [16] reduction scratch (fused modes)
+    float* sxl = red + 16;                             // [16] s_x of the fused modes
+    uint4* xlds = smem + kGemvLdsHeader;               // x_q rows, Kpad bytes each; later the fold buffer
 
-    const uint4* wp[kR];
+    const int64_t wstride = (int64_t)RB * 64;          // quads per whole step
+    int rbc[kR];
 #pragma unroll
-    for (int a = 0; a < kR; ++a) wp[a] = packed + (int64_t)min(rbw + a, RB - 1) * 64 + lane;
-    const int64_t wstride = (int64_t)RB * 64;                      // quads per full step
+    for (int a = 0; a < kR; ++a) rbc[a] = min(rbw + a, RB - 1);   // row blocks past the matrix: clamped, never stored
     const int mrow = min(r, M - 1);
-    const uint4* xg = reinterpret_cast<const uint4*>(xq + (int64_t)mrow * K + 64 * g);
-    const uint4* xl = smem + mrow * (Kpad >> 4) + 4 * g;
+    const int8_t* xg = xq + (int64_t)mrow * K;
+    const uint4* xl = xlds + mrow * (Kpad >> 4) + 4 * g;
 
     v4i acc[kR];
 #pragma unroll
     for (int a = 0; a < kR; ++a) acc[a] = (v4i){0, 0, 0, 0};
 
+    // One K step of operands.  Steps past the end are redirected to the last step and masked in mac();
+    // in the last step only the first tail_quads lanes hold a quad, the others are clamped and masked.
     struct Stage { uint4 w[kR]; uint4 x[4]; };
     auto load = [&](Stage& s, int item) {
-        const int sl = max(min(ws + item * kS, last_full), 0);     // redirected if past the last full step
+        const int sl = min(ws + item * kS, steps - 1);
+        const int cq = sl == steps - 1 ? tail_quads : 64;
+        const int ln = min(lane, cq - 1);
 #pragma unroll
-        for (int a = 0; a < kR; ++a) s.w[a] = wp[a][(int64_t)sl * wstride];
-        if (!kXLds) {
+        for (int a = 0; a < kR; ++a) s.w[a] = packed[(int64_t)sl * wstride + (int64_t)rbc[a] * cq + ln];
+        if (!kFromLds) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) s.x[j] = xg[(int64_t)sl * 16 + j];
+            for (int j = 0; j < 4; ++j) {
+                const int64_t col = min((int64_t)sl * 256 + 64 * g + 16 * j, K - 16);   // past-the-end columns meet zero codes
+                s.x[j] = *reinterpret_cast<const uint4*>(xg + col);
+            }
         }
     };
     auto mac = [&](Stage& s, int item) {
         const int step = ws + item * kS;
-        const uint32_t keep = step <= last_full ? 0xFFFFFFFFu : 0u;
-        if (kXLds) {
-            const int sl = max(min(step, last_full), 0);
+        const int sl = min(step, steps - 1);
+        const int cq = sl == steps - 1 ? tail_quads : 64;
+        const uint32_t keep = (step < steps && lane < cq) ? 0xFFFFFFFFu : 0u;
+        if (kFromLds) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) s.x[j] = xl[sl * 16 + j];
         }
@@ -140,49 +220,44 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
                                                                acc[a], 0, 0, 0);
     };
 
-    if (kXLds) __syncthreads();
-    if (last_full >= 0) {
-        Stage st[kD];
+    // weights first: their loads are in flight while the activations are staged
+    Stage st[kD];
 #pragma unroll
-        for (int d = 0; d < kD; ++d) load(st[d], d);
-        int i = 0;
-        for (; i + kD < items; i += kD) {
-#pragma unroll
-            for (int d = 0; d < kD; ++d) {
-                // the fences keep the refill of a stage right behind its use, kD steps ahead of need
-                mac(st[d], i + d);
-                __builtin_amdgcn_sched_barrier(0);
-                load(st[d], i + d + kD);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+    for (int d = 0; d < kD; ++d) load(st[d], d);
+
+    if (kX == kXLds) {
+        const int nvec = M * (Kpad >> 4);
+        for (int v = threadIdx.x; v < nvec; v += kThreads) {
+            const int m = v / (Kpad >> 4), kv = v % (Kpad >> 4);
+            uint4 val = make_uint4(0, 0, 0, 0);
+            if ((int64_t)kv * 16 + 16 <= K) val = reinterpret_cast<const uint4*>(xq + (int64_t)m * K)[kv];
+            xlds[v] = val;
         }
-#pragma unroll
-        for (int d = 0; d < kD; ++d) mac(st[d], i + d);
+        __syncthreads();
+    } else if (kFused) {
+        fused_quantize_to_lds<kX == kXFusedBf16, kThreads>(xin, M, K, Kpad, red, sxl, xlds);
     }
 
-    // columns past the last whole step (K % 256 != 0): one guarded step, taken by one K-split wave
-    if ((K & 255) != 0 && ws == (last_full + 1) % kS) {
-        const int step = last_full + 1;
-        const int kq = 4 * step + g;
-        const int nq = Kq - 4 * step;
-        const int64_t kbase = (int64_t)kq * 64;
+    int i = 0;
+    for (; i + kD < items; i += kD) {
 #pragma unroll
-        for (int a = 0; a < kR; ++a) {
-            uint4 wq = make_uint4(0, 0, 0, 0);
-            const int rb = min(rbw + a, RB - 1);
-            if (kq < Kq) wq = packed[(int64_t)step * wstride + (int64_t)rb * 16 * nq + lane];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                uint4 xv = make_uint4(0, 0, 0, 0);
-                if (kbase + 16 * j + 16 <= K) xv = xg[(int64_t)step * 16 + j];
-                acc[a] = __builtin_amdgcn_mfma_i32_16x16x64_i8(decode_word(quad_word(wq, j)), as_v4i(xv), acc[a], 0, 0, 0);
-            }
+        for (int d = 0; d < kD; ++d) {
+            // the fences keep the refill of a stage right behind its use, kD steps ahead of need
+            mac(st[d], i + d);
+            __builtin_amdgcn_sched_barrier(0);
+            load(st[d], i + d + kD);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
+#pragma unroll
+    for (int d = 0; d < kD; ++d) mac(st[d], i + d);
+
+    float sc_row = 0.0f;
+    if (yt != OutType::I32) sc_row = kFused ? sxl[mrow] : sx[mrow];
 
     if (kS > 1) {
-        // fold the K slices; the LDS region is shared with x, so wait until every wave is done with it
-        v4i* fold = reinterpret_cast<v4i*>(smem);
+        // fold the K slices; the buffer aliases the x region, so wait until every wave is done with it
+        v4i* fold = reinterpret_cast<v4i*>(xlds);
         __syncthreads();
 #pragma unroll
         for (int a = 0; a < kR; ++a) fold[((ww * kS + ws) * kR + a) * kWave + lane] = acc[a];
@@ -201,7 +276,7 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
     }
 
     if (r < M) {                                                    // MFMA output column = lane & 15 = token
-        const float scale = yt == OutType::I32 ? 0.0f : (gamma[0] * sx[r]) / kQb;
+        const float scale = (gamma[0] * sc_row) / kQb;
 #pragma unroll
         for (int a = 0; a < kR; ++a) {
             const int64_t n0 = (int64_t)(rbw + a) * 16 + 4 * g;     // rows 4 g .. 4 g + 3 of the row block
@@ -356,26 +431,31 @@ bool gemv_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
 
 constexpr size_t kGemvLdsBudget = 65536;
 
+static size_t gemv16_x_lds_bytes(int64_t M, int64_t K) { return (size_t)M * ceil_div(K, 256) * 256; }
+
 template <int kR, int kS, int kW, int kD>
-static void launch16(bool xlds, const int8_t* xq, const float* sx, const void* packed, const float* gamma, int64_t M,
+static void launch16(int xmode, const void* x, const float* sx, const void* packed, const float* gamma, int64_t M,
                      int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
     const int Kq = (int)ceil_div(K, kColsPerQuad);
     const int RB = (int)ceil_div(N, kRowsPerBlock);
-    const int steps = (Kq + 3) / 4;
-    int items = (int)ceil_div(K >> 8, kS);
+    int items = (int)ceil_div(ceil_div(K, 256), kS);
     items = (int)ceil_div(items, kD) * kD;
+    const size_t header = kGemvLdsHeader * sizeof(uint4);
     const size_t lds_fold = kS > 1 ? (size_t)kW * kS * kR * kWave * 16 : 0;
-    const size_t lds_x = (size_t)M * steps * 256;
-    if (lds_x > kGemvLdsBudget) xlds = false;
-    const size_t lds = xlds && lds_x > lds_fold ? lds_x : lds_fold;
+    const size_t lds_x = gemv16_x_lds_bytes(M, K);
+    if (xmode == kXLds && header + lds_x > kGemvLdsBudget) xmode = kXGlobal;
+    const size_t lds = header + (xmode != kXGlobal && lds_x > lds_fold ? lds_x : lds_fold);
     dim3 grid((unsigned)ceil_div(RB, kW * kR)), block(kS * kW * kWave);
     const uint4* p = static_cast<const uint4*>(packed);
-    if (xlds)
-        hipLaunchKernelGGL((linear_gemv16_2bit<kR, kS, kW, kD, true>), grid, block, lds, stream, xq, sx, p, gamma, (int)M, N, K,
-                           Kq, RB, items, y, yt);
-    else
-        hipLaunchKernelGGL((linear_gemv16_2bit<kR, kS, kW, kD, false>), grid, block, lds, stream, xq, sx, p, gamma, (int)M, N, K,
-                           Kq, RB, items, y, yt);
+#define GO(X_) hipLaunchKernelGGL((linear_gemv16_2bit<kR, kS, kW, kD, X_>), grid, block, lds, stream, x, sx, p, gamma, (int)M, N, \
+                                  K, Kq, RB, items, y, yt)
+    switch (xmode) {
+        case kXGlobal: GO(kXGlobal); break;
+        case kXLds: GO(kXLds); break;
+        case kXFusedBf16: GO(kXFusedBf16); break;
+        default: GO(kXFusedF32); break;
+    }
+#undef GO
 }
 
 template <int kR, int kMT, int kS>
@@ -390,27 +470,46 @@ static void launch64(const int8_t* xq, const float* sx, const void* packed, cons
 
 // Shape heuristics, from sweeps on MI355X: many row blocks -> few deep-prefetching waves, each owning
 // four row blocks for all of K; few row blocks -> split K over more waves so that the whole matrix is
-// requested within the first memory round trip.
+// requested within the first memory round trip.  xmode < 0 lets the shape decide between global and
+// LDS-staged x_q; the fused modes pass their own.
+static void dispatch16(int xmode, const void* x, const float* sx, const void* packed, const float* gamma, int64_t M,
+                       int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
+    const int64_t RB = ceil_div(N, kRowsPerBlock);
+    const int64_t steps = ceil_div(K, 256);
+    const bool pick = xmode < 0;
+#define GEMV16(R_, S_, W_, D_, X_) launch16<R_, S_, W_, D_>(pick ? (X_) : xmode, x, sx, packed, gamma, M, N, K, y, yt, stream)
+    if (RB >= 2048)                       GEMV16(4, 1, 4, 2, kXGlobal);
+    else if (RB >= 1024 && steps >= 16)   GEMV16(1, 2, 2, 4, kXLds);
+    else if (RB >= 1024)                  GEMV16(1, 4, 2, 1, kXLds);
+    else if (RB >= 400 && steps >= 64)    GEMV16(2, 4, 1, 4, kXGlobal);
+    else if (RB >= 400)                   GEMV16(1, 4, 1, 4, kXLds);
+    else if (steps >= 24)                 GEMV16(1, 16, 1, 1, kXLds);
+    else                                  GEMV16(1, 4, 1, 4, kXGlobal);
+#undef GEMV16
+}
+
 hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void* packed,
                                    const float* gamma, int64_t M, int64_t N, int64_t K, void* y,
                                    OutType yt, hipStream_t stream) {
-    const int64_t RB = ceil_div(N, kRowsPerBlock);
-    const int64_t steps = ceil_div(K, 256);
-#define GEMV16(R_, S_, W_, D_, X_) launch16<R_, S_, W_, D_>(X_, xq, sx, packed, gamma, M, N, K, y, yt, stream)
     if (M <= 16) {
-        if (RB >= 2048)                       GEMV16(4, 1, 4, 2, false);
-        else if (RB >= 1024 && steps >= 16)   GEMV16(1, 2, 2, 4, true);
-        else if (RB >= 1024)                  GEMV16(1, 4, 2, 1, true);
-        else if (RB >= 400 && steps >= 64)    GEMV16(2, 4, 1, 4, false);
-        else if (RB >= 400)                   GEMV16(1, 4, 1, 4, true);
-        else if (steps >= 24)                 GEMV16(1, 16, 1, 1, true);
-        else                                  GEMV16(1, 4, 1, 4, false);
+        dispatch16(-1, xq, sx, packed, gamma, M, N, K, y, yt, stream);
     } else if (M <= 32) {
         launch64<4, 2, 4>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
     } else {
         launch64<2, 4, 4>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
     }
-#undef GEMV16
+    return hipGetLastError();
+}
+
+bool gemv_fused_supports(int64_t M, int64_t N, int64_t K, const void* x) {
+    (void)N;
+    return M >= 1 && M <= 16 && K % 16 == 0 && reinterpret_cast<uintptr_t>(x) % 16 == 0 &&
+           kGemvLdsHeader * sizeof(uint4) + gemv16_x_lds_bytes(M, K) <= kGemvLdsBudget;
+}
+
+hipError_t launch_linear_fused_2bit(const void* x, bool bf16, const void* packed, const float* gamma, int64_t M,
+                                    int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
+    dispatch16(bf16 ? kXFusedBf16 : kXFusedF32, x, nullptr, packed, gamma, M, N, K, y, yt, stream);
     return hipGetLastError();
 }
 

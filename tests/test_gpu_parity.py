@@ -226,6 +226,46 @@ def test_linear_gemv_kernel(gpu_lib, M, N, K):
     _run_linear_case(gpu_lib, M, N, K, [gpu_lib.KERNEL_GEMV, gpu_lib.KERNEL_AUTO], layer=M, bf16_acts=(M % 2 == 0))
 
 
+FUSED_SHAPES = [(1, 4096, 1536), (16, 4096, 1536), (1, 17, 16), (3, 100, 80), (7, 250, 1040), (2, 32800, 528),
+                (3, 16400, 4112), (1, 16400, 272), (4, 6416, 1040), (2, 100, 6160), (1, 3200, 8640), (1, 17280, 3200)]
+
+
+@pytest.mark.parametrize("M,N,K", FUSED_SHAPES)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_linear_fused_matches_oracle(gpu_lib, M, N, K, dtype):
+    """x -> y in one launch: the in-kernel activation quantization must reproduce x_q and s_x exactly,
+    which shows in the int32 accumulators."""
+    say("linear fused %s M=%d N=%d K=%d" % (dtype, M, N, K))
+    W = synth.weights(N, K, config=0, layer=M + 20, tensor=0)
+    if dtype == "bf16":
+        x, bits = synth.activations(M, K, config=0, layer=M + 20, bf16=True)
+        xd = bf16_tensor(bits).view(M, K)
+    else:
+        x = synth.activations(M, K, config=0, layer=M + 20)
+        xd = dev(x)
+    ref = oracle.bitlinear(x, W)
+    packed, gamma = gpu_lib.quantize_weights(dev(W))
+    acc = gpu_lib.linear_fused(xd, packed, gamma, N, y_dtype=gpu_lib.I32)
+    assert np.array_equal(acc.cpu().numpy(), ref["acc"])
+    check_y(gpu_lib.linear_fused(xd, packed, gamma, N, y_dtype=gpu_lib.F32).cpu().numpy(), ref["y"], RTOL_F32)
+    check_y(gpu_lib.linear_fused(xd, packed, gamma, N, y_dtype=gpu_lib.BF16).float().cpu().numpy(), ref["y"], RTOL_BF16)
+
+
+def test_linear_fused_rejects_what_it_cannot_run(gpu_lib):
+    say("linear fused limits")
+    W = dev(synth.weights(32, 8192, config=0, layer=1))
+    packed, gamma = gpu_lib.quantize_weights(W)
+    x = dev(synth.activations(16, 8192, config=0, layer=1))          # 16 x 8192 int8 does not fit the LDS budget
+    with pytest.raises(gpu_lib.BitnetError) as e:
+        gpu_lib.linear_fused(x, packed, gamma, 32)
+    assert e.value.status == 8
+    x17 = dev(synth.activations(17, 64, config=0, layer=1))
+    p2, g2 = gpu_lib.quantize_weights(dev(synth.weights(32, 64, config=0, layer=1)))
+    with pytest.raises(gpu_lib.BitnetError) as e:
+        gpu_lib.linear_fused(x17, p2, g2, 32)
+    assert e.value.status == 8
+
+
 def test_linear_extreme_accumulators(gpu_lib):
     """Every product at +-127 with all-(+1) / all-(-1) rows: the largest accumulators a shape can give."""
     say("linear extreme accumulators")
