@@ -79,68 +79,98 @@ enum XMode : int {
 
 constexpr int kGemvLdsHeader = 8;       // uint4 slots in front of the x region: reduction scratch + s_x
 
-// Quantize the M tokens of x into LDS (Section 2 of the paper: per-token absmax, Q_b = 127), the same
-// arithmetic as the stand-alone activation kernel: s = max(absmax, 1e-5), inv = 127 / s,
-// x_q = clip(rint(x * inv)).  Rows are zero padded to Kpad columns.  s_x[m] is left in sxl[m].
+// In-kernel activation quantization for the fused modes (Section 2 of the paper: per-token absmax,
+// Q_b = 127), the same arithmetic as the stand-alone activation kernel: s = max(absmax, 1e-5),
+// inv = 127 / s, x_q = clip(rint(x * inv)).  Rows land in LDS zero padded to Kpad columns, s_x[m] in
+// sxl[m].  Token 0 is fetched into registers before the weight prefetch is issued (so that waiting for
+// it does not wait for the weights) and quantized from there; further tokens take two sweeps.
+constexpr int kFusedRegVecs = 4;          // 16-byte vectors of token 0 a thread can hold
+
+template <bool kBf16>
+__device__ inline float vec_absmax(const uint4& q, float amax) {
+    const uint32_t u[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (kBf16) {
+            amax = fmaxf(amax, fabsf(__uint_as_float(u[e] << 16)));
+            amax = fmaxf(amax, fabsf(__uint_as_float(u[e] & 0xFFFF0000u)));
+        } else {
+            amax = fmaxf(amax, fabsf(__uint_as_float(u[e])));
+        }
+    }
+    return amax;
+}
+
+__device__ inline uint32_t quant_byte(float v, float inv) {
+    const float f = rintf(v * inv);                   // one fp32 multiply, ties to even
+    return (uint32_t)(int)fminf(kQb, fmaxf(-kQb, f)) & 0xFFu;
+}
+
+// one 16-byte vector of x -> its int8 codes, written to the token's LDS row (32-bit words)
+template <bool kBf16>
+__device__ inline void vec_quantize_store(const uint4& q, float inv, uint32_t* out, int v) {
+    const uint32_t u[4] = {q.x, q.y, q.z, q.w};
+    if (kBf16) {
+        uint32_t o[2] = {0, 0};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t lo = quant_byte(__uint_as_float(u[e] << 16), inv);
+            const uint32_t hi = quant_byte(__uint_as_float(u[e] & 0xFFFF0000u), inv);
+            o[e >> 1] |= (lo | (hi << 8)) << (16 * (e & 1));
+        }
+        out[2 * v] = o[0];
+        out[2 * v + 1] = o[1];
+    } else {
+        uint32_t o = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o |= quant_byte(__uint_as_float(u[e]), inv) << (8 * e);
+        out[v] = o;
+    }
+}
+
+template <int kThreads>
+__device__ inline float block_absmax_to_scale(float amax, float* red) {
+    amax = wave_max_nonneg(amax);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = amax;
+    __syncthreads();
+    float mx = red[0];
+#pragma unroll
+    for (int w = 1; w < kThreads / kWave; ++w) mx = fmaxf(mx, red[w]);
+    return fmaxf(mx, kEps);
+}
+
 template <bool kBf16, int kThreads>
-__device__ inline void fused_quantize_to_lds(const void* __restrict__ xv, int M, int64_t K, int Kpad,
-                                             float* red /* kThreads/64 floats */, float* sxl, uint4* xlds) {
-    constexpr int kE = kBf16 ? 8 : 4;                 // elements per 16-byte load
+__device__ inline void fused_quantize_to_lds(const void* __restrict__ xv, const uint4 (&row0)[kFusedRegVecs], bool row0_in_regs,
+                                             int M, int64_t K, int Kpad, float* red, float* sxl, uint4* xlds) {
+    constexpr int kE = kBf16 ? 8 : 4;                 // elements per 16-byte vector
     const int nvec = (int)(K / kE);
     const int nvec_pad = Kpad / kE;
     for (int m = 0; m < M; ++m) {
         const uint4* row = reinterpret_cast<const uint4*>(static_cast<const char*>(xv) + (int64_t)m * K * (kBf16 ? 2 : 4));
+        uint32_t* out = reinterpret_cast<uint32_t*>(xlds) + (size_t)m * (Kpad >> 2);
+        const bool regs = m == 0 && row0_in_regs;
         float amax = 0.0f;
-        for (int v = threadIdx.x; v < nvec; v += kThreads) {
-            const uint4 q = row[v];
-            const uint32_t u[4] = {q.x, q.y, q.z, q.w};
+        if (regs) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (kBf16) {
-                    amax = fmaxf(amax, fabsf(__uint_as_float(u[e] << 16)));
-                    amax = fmaxf(amax, fabsf(__uint_as_float(u[e] & 0xFFFF0000u)));
-                } else {
-                    amax = fmaxf(amax, fabsf(__uint_as_float(u[e])));
-                }
-            }
+            for (int v = 0; v < kFusedRegVecs; ++v) amax = vec_absmax<kBf16>(row0[v], amax);   // clamped duplicates are harmless
+        } else {
+            for (int v = threadIdx.x; v < nvec; v += kThreads) amax = vec_absmax<kBf16>(row[v], amax);
         }
-        amax = wave_max_nonneg(amax);
-        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = amax;
-        __syncthreads();
-        float mx = red[0];
-#pragma unroll
-        for (int w = 1; w < kThreads / kWave; ++w) mx = fmaxf(mx, red[w]);
-        const float sc = fmaxf(mx, kEps);
+        const float sc = block_absmax_to_scale<kThreads>(amax, red);
         const float inv = kQb / sc;                   // one IEEE division per token
         if (threadIdx.x == 0) sxl[m] = sc;
-        uint32_t* out = reinterpret_cast<uint32_t*>(xlds) + (size_t)m * (Kpad >> 2);
-        for (int v = threadIdx.x; v < nvec_pad; v += kThreads) {
-            uint4 q = make_uint4(0, 0, 0, 0);
-            if (v < nvec) q = row[v];
-            const uint32_t u[4] = {q.x, q.y, q.z, q.w};
-            if (kBf16) {
-                uint32_t o[2] = {0, 0};
+        if (regs) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float lo = rintf(__uint_as_float(u[e] << 16) * inv);
-                    const float hi = rintf(__uint_as_float(u[e] & 0xFFFF0000u) * inv);
-                    const int ql = (int)fminf(kQb, fmaxf(-kQb, lo));
-                    const int qh = (int)fminf(kQb, fmaxf(-kQb, hi));
-                    o[e >> 1] |= (((uint32_t)ql & 0xFFu) | (((uint32_t)qh & 0xFFu) << 8)) << (16 * (e & 1));
-                }
-                out[2 * v] = o[0];
-                out[2 * v + 1] = o[1];
-            } else {
-                uint32_t o = 0;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float f = rintf(__uint_as_float(u[e]) * inv);
-                    o |= ((uint32_t)(int)fminf(kQb, fmaxf(-kQb, f)) & 0xFFu) << (8 * e);
-                }
-                out[v] = o;
+            for (int v = 0; v < kFusedRegVecs; ++v) {
+                const int idx = v * kThreads + (int)threadIdx.x;
+                if (idx < nvec) vec_quantize_store<kBf16>(row0[v], inv, out, idx);
             }
+        } else {
+            for (int v = threadIdx.x; v < nvec; v += kThreads) vec_quantize_store<kBf16>(row[v], inv, out, v);
         }
-        __syncthreads();                              // red[] is reused by the next token
+        for (int v = nvec + threadIdx.x; v < nvec_pad; v += kThreads)                          // zero padding
+            vec_quantize_store<kBf16>(make_uint4(0, 0, 0, 0), inv, out, v);
+        __syncthreads();                              // red[] is reused by the next token; LDS rows complete
     }
 }
 
@@ -220,10 +250,25 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
                                                                acc[a], 0, 0, 0);
     };
 
-    // weights first: their loads are in flight while the activations are staged
+    // fused modes: token 0 goes to registers first (cache hits, back long before the weights)
+    uint4 row0[kFusedRegVecs];
+    bool row0_in_regs = false;
+    if (kFused) {
+        const int nvec = (int)(K / (kX == kXFusedBf16 ? 8 : 4));
+        row0_in_regs = nvec <= kFusedRegVecs * kThreads;
+        if (row0_in_regs) {
+#pragma unroll
+            for (int v = 0; v < kFusedRegVecs; ++v)
+                row0[v] = static_cast<const uint4*>(xin)[min(v * kThreads + (int)threadIdx.x, nvec - 1)];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // then the weights: their loads stay in flight while the activations are staged
     Stage st[kD];
 #pragma unroll
     for (int d = 0; d < kD; ++d) load(st[d], d);
+    __builtin_amdgcn_sched_barrier(0);
 
     if (kX == kXLds) {
         const int nvec = M * (Kpad >> 4);
@@ -235,7 +280,7 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
         }
         __syncthreads();
     } else if (kFused) {
-        fused_quantize_to_lds<kX == kXFusedBf16, kThreads>(xin, M, K, Kpad, red, sxl, xlds);
+        fused_quantize_to_lds<kX == kXFusedBf16, kThreads>(xin, row0, row0_in_regs, M, K, Kpad, red, sxl, xlds);
     }
 
     int i = 0;
@@ -468,23 +513,37 @@ static void launch64(const int8_t* xq, const float* sx, const void* packed, cons
                        static_cast<const uint4*>(packed), gamma, (int)M, N, K, Kq, RB, y, yt);
 }
 
-// Shape heuristics, from sweeps on MI355X: many row blocks -> few deep-prefetching waves, each owning
-// four row blocks for all of K; few row blocks -> split K over more waves so that the whole matrix is
-// requested within the first memory round trip.  xmode < 0 lets the shape decide between global and
-// LDS-staged x_q; the fused modes pass their own.
+// Shape heuristics from sweeps on MI355X (M = 1, HIP-graph replay over many distinct weight buffers):
+//   * many row blocks: few waves, each owning four row blocks for all of K with 2-3 steps of loads
+//     in flight -- the dense step-major front does the rest;
+//   * fewer row blocks: one row block per wave and K split over 4-8 waves, with depth chosen so that
+//     S * D covers all steps, i.e. the whole matrix is requested within the first memory round trip;
+//   * long K with few row blocks: two row blocks per wave, K split four ways, four steps in flight.
+// xmode < 0 (x_q given) lets the shape decide between global and LDS-staged x_q; the fused modes
+// pass their own and need the wide workgroups that can hold token 0 in registers.
 static void dispatch16(int xmode, const void* x, const float* sx, const void* packed, const float* gamma, int64_t M,
                        int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
     const int64_t RB = ceil_div(N, kRowsPerBlock);
     const int64_t steps = ceil_div(K, 256);
-    const bool pick = xmode < 0;
-#define GEMV16(R_, S_, W_, D_, X_) launch16<R_, S_, W_, D_>(pick ? (X_) : xmode, x, sx, packed, gamma, M, N, K, y, yt, stream)
-    if (RB >= 2048)                       GEMV16(4, 1, 4, 2, kXGlobal);
-    else if (RB >= 1024 && steps >= 16)   GEMV16(1, 2, 2, 4, kXLds);
-    else if (RB >= 1024)                  GEMV16(1, 4, 2, 1, kXLds);
-    else if (RB >= 400 && steps >= 64)    GEMV16(2, 4, 1, 4, kXGlobal);
-    else if (RB >= 400)                   GEMV16(1, 4, 1, 4, kXLds);
-    else if (steps >= 24)                 GEMV16(1, 16, 1, 1, kXLds);
-    else                                  GEMV16(1, 4, 1, 4, kXGlobal);
+    const bool fused = xmode >= 0;
+    const bool fits_lds = kGemvLdsHeader * sizeof(uint4) + gemv16_x_lds_bytes(M, K) <= kGemvLdsBudget;
+#define GEMV16(R_, S_, W_, D_, X_) launch16<R_, S_, W_, D_>(fused ? xmode : (X_), x, sx, packed, gamma, M, N, K, y, yt, stream)
+    if (M > 4 && !fused) {
+        // x traffic grows with M: stage x_q in LDS when it fits, else amortize it over four row blocks
+        if (fits_lds && RB < 2048)  GEMV16(1, 4, 1, 4, kXLds);
+        else if (RB >= 1024)        GEMV16(4, 1, 4, 2, kXGlobal);
+        else                        GEMV16(4, 2, 2, 2, kXGlobal);
+    } else if (RB >= 2048) {
+        if (fused) GEMV16(4, 1, 4, 2, kXGlobal); else GEMV16(4, 1, 4, 3, kXGlobal);
+    } else if (steps >= 64) {
+        if (fused) GEMV16(1, 8, 2, 2, kXGlobal); else GEMV16(2, 4, 1, 4, kXGlobal);
+    } else if (steps >= 24) {
+        if (steps <= 40) GEMV16(1, 8, 1, 5, kXLds); else GEMV16(1, 8, 1, 3, kXLds);
+    } else if (RB >= 1024 && steps >= 16 && !fused) {
+        GEMV16(2, 4, 1, 4, kXGlobal);
+    } else {
+        GEMV16(1, 4, 1, 4, (RB >= 400 && steps < 16) ? kXLds : kXGlobal);
+    }
 #undef GEMV16
 }
 

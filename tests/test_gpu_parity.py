@@ -217,7 +217,8 @@ GEMV_SHAPES = [(1, 4096, 1536), (16, 4096, 1536), (1, 16, 64), (1, 17, 16), (3, 
                (16, 33, 4112), (17, 70, 528), (32, 1000, 3200), (33, 130, 272), (64, 96, 1024), (50, 49, 2064),
                # one shape per branch of the kernel-selection heuristic (row blocks x K steps)
                (2, 32800, 528), (3, 16400, 4112), (1, 16400, 272), (5, 6416, 16400), (4, 6416, 1040),
-               (2, 100, 6160), (16, 1000, 8192)]
+               (2, 100, 6160), (16, 1000, 8192), (1, 600, 16400), (1, 100, 11008), (8, 300, 2048), (6, 16400, 512),
+               (12, 16400, 8192)]
 
 
 @pytest.mark.parametrize("M,N,K", GEMV_SHAPES)
@@ -227,7 +228,8 @@ def test_linear_gemv_kernel(gpu_lib, M, N, K):
 
 
 FUSED_SHAPES = [(1, 4096, 1536), (16, 4096, 1536), (1, 17, 16), (3, 100, 80), (7, 250, 1040), (2, 32800, 528),
-                (3, 16400, 4112), (1, 16400, 272), (4, 6416, 1040), (2, 100, 6160), (1, 3200, 8640), (1, 17280, 3200)]
+                (3, 16400, 4112), (1, 16400, 272), (4, 6416, 1040), (2, 100, 6160), (1, 3200, 8640), (1, 17280, 3200),
+                (1, 600, 16400), (1, 100, 11008), (2, 64, 28672)]
 
 
 @pytest.mark.parametrize("M,N,K", FUSED_SHAPES)
