@@ -122,6 +122,7 @@ bitnet_status bitnet_linear_variant(const int8_t* xq, const float* sx, const voi
 
     if (which == BITNET_KERNEL_AUTO) {
         if (bitnet::gemv_supports(M, N, K, xq)) which = BITNET_KERNEL_GEMV;
+        else if (bitnet::gemm_supports(M, N, K, xq)) which = BITNET_KERNEL_GEMM;
         else which = BITNET_KERNEL_REFERENCE;
     }
     switch (which) {
@@ -130,6 +131,9 @@ bitnet_status bitnet_linear_variant(const int8_t* xq, const float* sx, const voi
         case BITNET_KERNEL_GEMV:
             if (!bitnet::gemv_supports(M, N, K, xq)) return BITNET_ERR_KERNEL;
             return from_hip(bitnet::launch_linear_gemv_2bit(xq, sx, packed, gamma, M, N, K, y, yt, s));
+        case BITNET_KERNEL_GEMM:
+            if (!bitnet::gemm_supports(M, N, K, xq)) return BITNET_ERR_KERNEL;
+            return from_hip(bitnet::launch_linear_gemm_2bit(xq, sx, packed, gamma, M, N, K, y, yt, s));
         default:
             return BITNET_ERR_KERNEL;
     }

@@ -33,4 +33,9 @@ bool gemv_fused_supports(int64_t M, int64_t N, int64_t K, const void* x);
 hipError_t launch_linear_fused_2bit(const void* x, bool bf16, const void* packed, const float* gamma, int64_t M,
                                     int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);
 
+// linear_gemm.hip
+bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq);
+hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
+                                   int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);
+
 }  // namespace bitnet

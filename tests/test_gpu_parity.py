@@ -268,6 +268,64 @@ def test_linear_fused_rejects_what_it_cannot_run(gpu_lib):
     assert e.value.status == 8
 
 
+# tiles of 256 x 256 with ragged edges in M, N and K (K steps of 256 with a partial last step), token
+# counts below one tile, and several tiles in each direction
+GEMM_SHAPES = [(65, 300, 528), (128, 256, 256), (100, 40, 16), (300, 520, 1040), (257, 1000, 3200), (513, 270, 4112),
+               (1024, 512, 1536)]
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_linear_gemm_kernel(gpu_lib, M, N, K):
+    say("linear gemm M=%d N=%d K=%d" % (M, N, K))
+    _run_linear_case(gpu_lib, M, N, K, [gpu_lib.KERNEL_GEMM, gpu_lib.KERNEL_AUTO], layer=M % 13, bf16_acts=(M % 2 == 0))
+
+
+def test_linear_gemm_small_m_and_forced_on_decode_shapes(gpu_lib):
+    say("linear gemm forced at small M")
+    _run_linear_case(gpu_lib, 1, 100, 80, [gpu_lib.KERNEL_GEMM], layer=2)
+    _run_linear_case(gpu_lib, 16, 4096, 1536, [gpu_lib.KERNEL_GEMM], layer=3)
+
+
+@pytest.mark.parametrize("M,N,K,layer", [(2048, 27648, 5120, 2), (512, 5120, 13824, 3)])
+def test_linear_gemm_full_size_sampled(gpu_lib, M, N, K, layer):
+    """13B-class prefill shapes at full size, in the launch configuration the benchmark times; the oracle
+    recomputes a seeded sample of 48 tokens x 384 weight rows (codes, x_q, accumulators bit-exact)."""
+    say("linear gemm full size M=%d N=%d K=%d" % (M, N, K))
+    W = synth.weights(N, K, config=3, layer=0, tensor=layer)
+    x, bits = synth.activations(M, K, config=3, layer=0, tensor=100 + layer, bf16=True)
+    gamma_ref, _ = oracle.absmean_gamma(W)
+    rng = np.random.default_rng(layer)
+    rows = np.sort(rng.choice(M, 48, replace=False))
+    rows[0], rows[-1] = 0, M - 1
+    cols = np.sort(rng.choice(N, 384, replace=False))
+    cols[0], cols[-1] = 0, N - 1
+    codes_ref = oracle.ternarize(W[cols], gamma_ref)
+    xq_ref, sx_ref = oracle.quantize_acts(x[rows])
+    acc_ref = oracle.ternary_matmul(xq_ref, codes_ref)
+    y_ref = oracle.rescale(acc_ref, gamma_ref, sx_ref)
+    packed, gamma = gpu_lib.quantize_weights(dev(W))
+    del W
+    xq, sx = gpu_lib.quantize_acts(bf16_tensor(bits).view(M, K))
+    assert gamma.cpu().numpy()[0] == gamma_ref
+    assert np.array_equal(xq.cpu().numpy()[rows], xq_ref)
+    ri = torch.from_numpy(rows).cuda()
+    ci = torch.from_numpy(cols).cuda()
+    acc = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.I32)
+    assert np.array_equal(acc[ri][:, ci].cpu().numpy(), acc_ref)
+    del acc
+    y16 = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.BF16)
+    check_y(y16[ri][:, ci].float().cpu().numpy(), y_ref, RTOL_BF16)
+    del y16
+    y32 = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.F32)
+    check_y(y32[ri][:, ci].cpu().numpy(), y_ref, RTOL_F32)
+    # any-size property: the integer result does not depend on which kernel produced it
+    sub = slice(0, 64)
+    a_ref = gpu_lib.linear(xq[sub].contiguous(), sx[sub].contiguous(), packed, gamma, N, y_dtype=gpu_lib.I32,
+                           kernel=gpu_lib.KERNEL_GEMV)
+    a_gemm = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.I32)[sub]
+    assert torch.equal(a_ref, a_gemm)
+
+
 def test_linear_extreme_accumulators(gpu_lib):
     """Every product at +-127 with all-(+1) / all-(-1) rows: the largest accumulators a shape can give."""
     say("linear extreme accumulators")
@@ -280,7 +338,7 @@ def test_linear_extreme_accumulators(gpu_lib):
     assert abs(int(ref["acc"][0, 0])) == 127 * K
     packed, gamma = gpu_lib.quantize_weights(dev(W))
     xq, sx = gpu_lib.quantize_acts(dev(x))
-    for kern in (gpu_lib.KERNEL_REFERENCE, gpu_lib.KERNEL_GEMV):
+    for kern in (gpu_lib.KERNEL_REFERENCE, gpu_lib.KERNEL_GEMV, gpu_lib.KERNEL_GEMM):
         acc = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.I32, kernel=kern)
         assert np.array_equal(acc.cpu().numpy(), ref["acc"])
 
@@ -308,6 +366,6 @@ def test_outputs_do_not_spill_past_their_buffers(gpu_lib):
     xq, sx = gpu_lib.quantize_acts(x, xq=xq_big[: M * K].view(M, K))
     assert bool((xq_big[M * K:] == 0x55).all())
     y_big = torch.full((M * N + 16,), 7.0, dtype=torch.float32, device="cuda")
-    for kern in (gpu_lib.KERNEL_REFERENCE, gpu_lib.KERNEL_GEMV):
+    for kern in (gpu_lib.KERNEL_REFERENCE, gpu_lib.KERNEL_GEMV, gpu_lib.KERNEL_GEMM):
         gpu_lib.linear(xq, sx, packed, gamma, N, y=y_big[: M * N].view(M, N), kernel=kern)
         assert bool((y_big[M * N:] == 7.0).all())
