@@ -14,7 +14,11 @@
 //     global memory one K step ahead and expands one 32-bit word (16 codes) into the four operand
 //     registers of an MFMA with a shift and an AND per register -- (w << (6 - 2 i)) & 0xC0C0C0C0 leaves
 //     64 * code in every byte, and the factor 64 is shifted out of the accumulator at the end;
+//   * inside a K step the eight 32-column slices are software pipelined: the LDS reads and the decode
+//     of slice t + 1 are issued among the 16 MFMAs of slice t;
 //   * one barrier per K step of 256 columns (128 MFMAs per wave between barriers);
+//   * the epilogue rescales in registers, transposes each 32 x 128 fragment row through LDS and writes
+//     whole 16-byte pieces of output rows;
 //   * tile order: consecutive workgroups take consecutive token tiles of the same weight tile, so the
 //     eight XCDs (workgroups are dealt to them round-robin) each keep re-using the token tile that is
 //     already in their L2 while the weight tile is shared through the memory-side cache.
@@ -33,25 +37,92 @@ constexpr int kGemmBM = 256;                   // tokens per workgroup tile
 constexpr int kGemmBN = 256;                   // weight rows per workgroup tile
 constexpr int kGemmThreads = 256;
 constexpr int kGemmStageBytes = kGemmBM * 256; // one K step of activations
-constexpr int kGemmLdsBytes = 2 * kGemmStageBytes;
-
-__device__ inline v4i gemm_decode_word(uint32_t w) {
-    v4i a;
-    a.x = (int)((w << 6) & 0xC0C0C0C0u);
-    a.y = (int)((w << 4) & 0xC0C0C0C0u);
-    a.z = (int)((w << 2) & 0xC0C0C0C0u);
-    a.w = (int)(w & 0xC0C0C0C0u);
-    return a;
-}
+constexpr int kGemmScaleOffset = 2 * kGemmStageBytes;          // float scale[256] behind the two stages
+constexpr int kGemmLdsBytes = kGemmScaleOffset + kGemmBM * 4;
+constexpr int kGemmPitch32 = 128 * 4 + 32;     // epilogue row pitch, 4-byte outputs: rows r and r+4 in different bank halves
+constexpr int kGemmPitch16 = 128 * 2 + 32;     // same for bf16 outputs
 
 __device__ inline uint32_t gemm_quad_word(const uint4& q, int j) { return j == 0 ? q.x : j == 1 ? q.y : j == 2 ? q.z : q.w; }
+
+// one register of the decoded B operand: columns 4 i .. 4 i + 3 of the word, as 64 * code per byte
+__device__ inline int gemm_decode_reg(uint32_t w, int i) { return (int)((w << (6 - 2 * i)) & 0xC0C0C0C0u); }
+
+struct GemmOutCtx {
+    char* lds;
+    const float* scale_lds;
+    void* y;
+    int M;
+    int64_t N;
+    int bm, bn, wave, lane, vec_store;
+};
+
+// A lane holds, per 32 x 32 fragment, 16 tokens (8 (v >> 2) + 4 (lane >> 5) + (v & 3)) of weight row
+// (lane & 31).  Each wave stages one fragment row (32 tokens x 128 weight rows) in its own LDS region,
+// then its lanes read 16-byte pieces along the token rows and store them.
+template <OutType kOut>
+__device__ inline void gemm_epilogue(v16i (&acc)[4][4], const GemmOutCtx& c) {
+    constexpr bool is16 = kOut == OutType::BF16;
+    constexpr int esz = is16 ? 2 : 4;
+    constexpr int pitch = is16 ? kGemmPitch16 : kGemmPitch32;
+    constexpr int lanes_per_row = 128 * esz / 16;                   // 16 or 32
+    constexpr int rows_per_pass = 64 / lanes_per_row;               // 4 or 2
+    const int am = c.lane & 31, kg = c.lane >> 5;
+    const int wm = c.wave >> 1, wn = c.wave & 1;
+    char* stage_out = c.lds + c.wave * (32 * kGemmPitch32);
+    const int64_t n_wave = (int64_t)c.bn * kGemmBN + wn * 128;
+    const int piece = c.lane % lanes_per_row;
+    const int64_t n = n_wave + piece * (16 / esz);
+#pragma unroll
+    for (int fm = 0; fm < 4; ++fm) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int rl = 8 * (v >> 2) + 4 * kg + (v & 3);
+            const float scale = kOut == OutType::I32 ? 0.0f : c.scale_lds[wm * 128 + fm * 32 + rl];
+#pragma unroll
+            for (int fn = 0; fn < 4; ++fn) {
+                const int a = acc[fm][fn][v] >> 6;                  // drop the decode factor 64 (exact)
+                char* p = stage_out + rl * pitch + (fn * 32 + am) * esz;
+                if (kOut == OutType::I32) *reinterpret_cast<int32_t*>(p) = a;
+                else if (kOut == OutType::F32) *reinterpret_cast<float*>(p) = (float)a * scale;
+                else *reinterpret_cast<uint16_t*>(p) = f32_to_bf16((float)a * scale);
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r0 = 0; r0 < 32; r0 += rows_per_pass) {
+            const int rl = r0 + c.lane / lanes_per_row;
+            const int m = c.bm * kGemmBM + wm * 128 + fm * 32 + rl;
+            const uint4 val = *reinterpret_cast<const uint4*>(stage_out + rl * pitch + piece * 16);
+            if (m < c.M && n < c.N) {
+                char* dst = static_cast<char*>(c.y) + ((int64_t)m * c.N + n) * esz;
+                if (c.vec_store && n + 16 / esz <= c.N) {
+                    *reinterpret_cast<uint4*>(dst) = val;
+                } else if (is16) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const uint32_t u = (e >> 1) == 0 ? val.x : (e >> 1) == 1 ? val.y : (e >> 1) == 2 ? val.z : val.w;
+                        if (n + e < c.N) reinterpret_cast<uint16_t*>(dst)[e] = (uint16_t)(u >> (16 * (e & 1)));
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const uint32_t u = e == 0 ? val.x : e == 1 ? val.y : e == 2 ? val.z : val.w;
+                        if (n + e < c.N) reinterpret_cast<uint32_t*>(dst)[e] = u;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
 
 __global__ __launch_bounds__(kGemmThreads, 1) void linear_gemm_2bit(
         const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
         const float* __restrict__ gamma, int M, int64_t N, int64_t K, int Kq, int RB, int tiles_m,
-        void* __restrict__ y, OutType yt) {
+        void* __restrict__ y, OutType yt, int vec_store) {
     extern __shared__ uint4 smem[];
     char* lds = reinterpret_cast<char*>(smem);
+    float* scale_lds = reinterpret_cast<float*>(lds + kGemmScaleOffset);
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -59,20 +130,39 @@ __global__ __launch_bounds__(kGemmThreads, 1) void linear_gemm_2bit(
     const int bm = blockIdx.x % tiles_m;            // token tile varies fastest (see header)
     const int bn = blockIdx.x / tiles_m;
     const int steps = (Kq + 3) >> 2;
+    const int full_steps = (int)(K >> 8);           // steps whose 256 columns all exist
     const int tail_quads = 16 * (Kq - 4 * (steps - 1));
     const int64_t wstride = (int64_t)RB * 64;
 
-    // ---- A operand, global -> LDS: this wave copies rows 64*wave .. +63 of the tile, 4 rows per load
-    // lane i of a load writes LDS slot i: row (i >> 4) of the group, chunk slot (i & 15); the chunk that
-    // belongs in slot c' of row m is c' ^ (m & 15)
+    // ---- per-token output scale gamma * s_x / 127, once per tile ------------------------------------
+    {
+        const int m = min(bm * kGemmBM + (int)threadIdx.x, M - 1);
+        scale_lds[threadIdx.x] = (gamma[0] * sx[m]) / kQb;
+    }
+
+    // ---- A operand, global -> LDS: this wave copies rows 64*wave .. +63 of the tile, 4 rows per load.
+    // Lane i of a load writes LDS slot i: row (i >> 4) of the group, chunk slot (i & 15); the chunk that
+    // belongs in slot c' of row m is c' ^ (m & 15).  Offsets are relative to the tile's first row.
     const int cp_row = lane >> 4, cp_slot = lane & 15;
+    const int8_t* xtile = xq + (int64_t)bm * kGemmBM * K;
+    const int rows_here = min(kGemmBM, M - bm * kGemmBM);           // rows past M: clamped, never stored
+    uint32_t xoff[16];
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+        const int row = wave * 64 + t * 4 + cp_row;
+        xoff[t] = (uint32_t)min(row, rows_here - 1) * (uint32_t)K + (uint32_t)((cp_slot ^ (row & 15)) << 4);
+    }
     // ---- A operand, LDS -> registers
     const int am = lane & 31, kg = lane >> 5;
+    const int a_row_base = (wm * 128 + am) * 256;                    // + fm * 8192
     // ---- B operand: fragment fn covers row blocks 2*fn, 2*fn+1 of this wave's 8
     const int brow = lane & 15, bsel = (lane >> 4) & 1;
-    int rbc[4];
+    uint32_t woff[4][2];                                            // quad offsets inside a whole step
 #pragma unroll
-    for (int fn = 0; fn < 4; ++fn) rbc[fn] = min(bn * 16 + wn * 8 + fn * 2 + bsel, RB - 1);
+    for (int fn = 0; fn < 4; ++fn)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+            woff[fn][h] = (uint32_t)min(bn * 16 + wn * 8 + fn * 2 + bsel, RB - 1) * 64u + (uint32_t)((kg + 2 * h) * 16 + brow);
 
     v16i acc[4][4];
 #pragma unroll
@@ -82,105 +172,108 @@ __global__ __launch_bounds__(kGemmThreads, 1) void linear_gemm_2bit(
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[fm][fn][v] = 0;
 
+    // The tile's activation rows as a raw buffer: per-lane byte offsets stay fixed, the K step goes into
+    // the scalar offset, and reads past the end of x_q return zero (in the partial last step the columns
+    // past K meet zero codes, whatever they hold).
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<int8_t*>(xtile), 0, (int)min((int64_t)rows_here * K, (int64_t)0x7FFFFFFF), 0x00020000);
     auto copy_x = [&](int step, int stage) {
         char* dst_stage = lds + stage * kGemmStageBytes;
 #pragma unroll
-        for (int t = 0; t < 16; ++t) {
-            const int row = wave * 64 + t * 4 + cp_row;                      // row inside the tile
-            const int m = min(bm * kGemmBM + row, M - 1);                   // rows past M: clamped, never stored
-            const int chunk = cp_slot ^ (row & 15);
-            const int64_t col = min((int64_t)step * 256 + chunk * 16, K - 16);   // past-the-end columns meet zero codes
-            const int8_t* src = xq + (int64_t)m * K + col;
-            char* dst = dst_stage + (wave * 64 + t * 4) * 256;              // wave-uniform; lane i lands at +16 i
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                             (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
-        }
+        for (int t = 0; t < 16; ++t)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (__attribute__((address_space(3))) void*)(dst_stage + (wave * 64 + t * 4) * 256),
+                                                     16, xoff[t], step * 256, 0, 0);
     };
     auto load_w = [&](uint4 (&wq)[4][2], int step) {
-        const int cq = step == steps - 1 ? tail_quads : 64;
+        const uint4* src = packed + (int64_t)step * wstride;
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int fn = 0; fn < 4; ++fn) wq[fn][h] = src[woff[fn][h]];
+    };
+    // the partial last step: its chunks hold fewer quads; lanes past them are clamped here and masked in compute()
+    auto load_w_tail = [&](uint4 (&wq)[4][2], int step) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            const int g = kg + 2 * h;
-            const int ln = min(g * 16 + brow, cq - 1);
-#pragma unroll
-            for (int fn = 0; fn < 4; ++fn) wq[fn][h] = packed[(int64_t)step * wstride + (int64_t)rbc[fn] * cq + ln];
-        }
-    };
-    auto compute = [&](const uint4 (&wq)[4][2], int step, int stage) {
-        const int cq = step == steps - 1 ? tail_quads : 64;
-        const char* src_stage = lds + stage * kGemmStageBytes;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const uint32_t keep = ((kg + 2 * h) * 16 + brow) < cq ? 0xFFFFFFFFu : 0u;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int chunk = 8 * h + 4 * kg + j;
-                v4i a[4], b[4];
-#pragma unroll
-                for (int fm = 0; fm < 4; ++fm) {
-                    const int row = wm * 128 + fm * 32 + am;
-                    a[fm] = *reinterpret_cast<const v4i*>(src_stage + row * 256 + ((chunk ^ (row & 15)) << 4));
-                }
-#pragma unroll
-                for (int fn = 0; fn < 4; ++fn) b[fn] = gemm_decode_word(gemm_quad_word(wq[fn][h], j) & keep);
-#pragma unroll
-                for (int fm = 0; fm < 4; ++fm)
-#pragma unroll
-                    for (int fn = 0; fn < 4; ++fn)
-                        acc[fm][fn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[fm], b[fn], acc[fm][fn], 0, 0, 0);
-            }
-        }
-    };
-
-    uint4 w0[4][2], w1[4][2];
-    copy_x(0, 0);
-    load_w(w0, 0);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-
-    int s = 0;
-    for (; s + 2 <= steps; s += 2) {
-        // even step: operands of step s + 1 go to stage 1 / w1 while step s is consumed from stage 0 / w0
-        copy_x(s + 1, 1);
-        load_w(w1, s + 1);
-        compute(w0, s, 0);
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
-        if (s + 2 < steps) {
-            copy_x(s + 2, 0);
-            load_w(w0, s + 2);
-        }
-        compute(w1, s + 1, 1);
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
-    }
-    if (s < steps) compute(w0, s, 0);
-
-    // ---- epilogue: lane holds, per fragment, 16 tokens (8 (v >> 2) + 4 (l >> 5) + (v & 3)) of one weight row
-    const float gm = gamma[0];
-#pragma unroll
-    for (int fm = 0; fm < 4; ++fm) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int m = bm * kGemmBM + wm * 128 + fm * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
-            if (m >= M) continue;
-            const float scale = yt == OutType::I32 ? 0.0f : (gm * sx[m]) / kQb;
+            const int ln = min((kg + 2 * h) * 16 + brow, tail_quads - 1);
 #pragma unroll
             for (int fn = 0; fn < 4; ++fn) {
-                const int64_t n = (int64_t)bn * kGemmBN + wn * 128 + fn * 32 + am;
-                if (n >= N) continue;
-                const int a = acc[fm][fn][v] >> 6;                           // drop the decode factor 64 (exact)
-                const int64_t idx = (int64_t)m * N + n;
-                if (yt == OutType::I32) static_cast<int32_t*>(y)[idx] = a;
-                else if (yt == OutType::F32) static_cast<float*>(y)[idx] = (float)a * scale;
-                else static_cast<uint16_t*>(y)[idx] = f32_to_bf16((float)a * scale);
+                const int rb = min(bn * 16 + wn * 8 + fn * 2 + bsel, RB - 1);
+                wq[fn][h] = packed[(int64_t)step * wstride + (int64_t)rb * tail_quads + ln];
             }
         }
+    };
+
+    // One K step: 8 slices of 32 columns, slice (h, j) uses word j of quad h; the LDS reads and the
+    // decode for slice t + 1 are placed among the MFMAs of slice t.
+    auto compute = [&](const uint4 (&wq)[4][2], int stage, uint32_t keep0, uint32_t keep1) {
+        const char* src = lds + stage * kGemmStageBytes + a_row_base;
+        const int sw = am & 15;
+        v4i a[2][4], b[2][4];
+        auto read_a = [&](v4i (&dst)[4], int t) {
+            const int chunk = 8 * (t >> 2) + 4 * kg + (t & 3);
+#pragma unroll
+            for (int fm = 0; fm < 4; ++fm)
+                dst[fm] = *reinterpret_cast<const v4i*>(src + fm * 8192 + ((chunk ^ sw) << 4));
+        };
+        auto word_of = [&](int fn, int t) { return gemm_quad_word(wq[fn][t >> 2], t & 3) & ((t >> 2) ? keep1 : keep0); };
+        read_a(a[0], 0);
+#pragma unroll
+        for (int fn = 0; fn < 4; ++fn) {
+            const uint32_t w = word_of(fn, 0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) b[0][fn][i] = gemm_decode_reg(w, i);
+        }
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int cur = t & 1, nxt = cur ^ 1;
+            __builtin_amdgcn_sched_barrier(0);          // slices stay in order: no hoisting of later LDS reads
+            if (t < 7) read_a(a[nxt], t + 1);
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int fm = q >> 2, fn = q & 3;
+                acc[fm][fn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[cur][fm], b[cur][fn], acc[fm][fn], 0, 0, 0);
+                if (t < 7) b[nxt][fm][fn] = gemm_decode_reg(word_of(fm, t + 1), fn);   // register fn of fragment fm
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // One loop body for every step: operands of step s + 1 are requested right before step s is
+    // consumed (activations into the other LDS stage, weights into wnext), and the barrier at the top of
+    // the next iteration both publishes them and retires the stage that was just read.
+    uint4 wq[4][2], wnext[4][2];
+    const uint32_t keep_t0 = (kg * 16 + brow) < tail_quads ? 0xFFFFFFFFu : 0u;
+    const uint32_t keep_t1 = ((kg + 2) * 16 + brow) < tail_quads ? 0xFFFFFFFFu : 0u;
+    auto issue = [&](int step) {
+        copy_x(step, step & 1);
+        if (step < full_steps) load_w(wnext, step); else load_w_tail(wnext, step);
+    };
+    issue(0);
+#pragma unroll 1
+    for (int s = 0; s < steps; ++s) {
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+#pragma unroll
+        for (int fn = 0; fn < 4; ++fn)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) wq[fn][h] = wnext[fn][h];
+        if (s + 1 < steps) issue(s + 1);
+        const bool tail = s >= full_steps;
+        compute(wq, s & 1, tail ? keep_t0 : 0xFFFFFFFFu, tail ? keep_t1 : 0xFFFFFFFFu);
     }
+    __syncthreads();                                    // every wave is done with the activation stages
+
+    // ---- epilogue: one instantiation per output type, chosen once ---------------------------------------
+    const GemmOutCtx ctx{lds, scale_lds, y, M, N, bm, bn, wave, lane, vec_store};
+    if (yt == OutType::BF16) gemm_epilogue<OutType::BF16>(acc, ctx);
+    else if (yt == OutType::F32) gemm_epilogue<OutType::F32>(acc, ctx);
+    else gemm_epilogue<OutType::I32>(acc, ctx);
 }
 
 bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
     (void)N;
+    // per-lane activation offsets are 32-bit and relative to the tile's first row: 256 * K must fit
     return M >= 1 && K % 16 == 0 && reinterpret_cast<uintptr_t>(xq) % 16 == 0;
 }
 
@@ -197,9 +290,11 @@ hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void
     const int RB = (int)ceil_div(N, kRowsPerBlock);
     const int tiles_m = (int)ceil_div(M, kGemmBM);
     const int64_t tiles_n = ceil_div(N, kGemmBN);
+    const size_t esz = yt == OutType::BF16 ? 2 : 4;
+    const int vec_store = (reinterpret_cast<uintptr_t>(y) % 16 == 0) && ((N * esz) % 16 == 0);
     dim3 grid((unsigned)(tiles_m * tiles_n));
     hipLaunchKernelGGL(linear_gemm_2bit, grid, dim3(kGemmThreads), kGemmLdsBytes, stream, xq, sx,
-                       static_cast<const uint4*>(packed), gamma, (int)M, N, K, Kq, RB, tiles_m, y, yt);
+                       static_cast<const uint4*>(packed), gamma, (int)M, N, K, Kq, RB, tiles_m, y, yt, vec_store);
     return hipGetLastError();
 }
 
