@@ -4,10 +4,12 @@
 // (Sections 1-2 of arXiv 2402.17764).  At these M the cost is the contraction itself, so the kernel is
 // organised around keeping v_mfma_i32_32x32x32_i8 issuing:
 //
-//   * a workgroup of four waves owns a 256 x 256 output tile, each wave a 128 x 128 quarter held as
-//     4 x 4 accumulator fragments of 32 x 32 (256 accumulator registers per lane);
+//   * a workgroup of four waves owns a 128 x 256 output tile, each wave a 128 x 64 piece held as 4 x 2
+//     accumulator fragments of 32 x 32; two workgroups share a CU, so every SIMD has two waves that are
+//     not tied to the same barrier: one workgroup's loads, decode and barrier waits run under the other's
+//     MFMAs (a single wave does not overlap its own VALU work with its MFMAs);
 //   * activations (the A operand) are copied global -> LDS with 128-bit LDS-direct loads, two stages of
-//     256 rows x 256 bytes; the 16-byte chunks of a row are XOR-swizzled with the row index so that the
+//     128 rows x 256 bytes; the 16-byte chunks of a row are XOR-swizzled with the row index so that the
 //     ds_read_b128 of 16 consecutive rows hit all 64 banks;
 //   * weights (the B operand) never touch LDS: the packed layout already stores, for every 16-row block,
 //     the 64 codes a lane needs as one 16-byte quad, so each lane loads its own quads straight from
@@ -16,8 +18,8 @@
 //     64 * code in every byte, and the factor 64 is shifted out of the accumulator at the end;
 //   * inside a K step the eight 32-column slices are software pipelined: the LDS reads and the decode
 //     of slice t + 1 are issued among the 16 MFMAs of slice t;
-//   * one barrier per K step of 256 columns (128 MFMAs per wave between barriers);
-//   * the epilogue rescales in registers, transposes each 32 x 128 fragment row through LDS and writes
+//   * one barrier per K step of 256 columns (64 MFMAs per wave between barriers);
+//   * the epilogue rescales in registers, transposes each 32 x 64 fragment row through LDS and writes
 //     whole 16-byte pieces of output rows;
 //   * tile order: consecutive workgroups take consecutive token tiles of the same weight tile, so the
 //     eight XCDs (workgroups are dealt to them round-robin) each keep re-using the token tile that is
@@ -33,14 +35,15 @@ namespace bitnet {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int kGemmBM = 256;                   // tokens per workgroup tile
+constexpr int kGemmBM = 128;                   // tokens per workgroup tile
 constexpr int kGemmBN = 256;                   // weight rows per workgroup tile
 constexpr int kGemmThreads = 256;
+constexpr int kGemmFN = 2;                     // 32-row weight fragments per wave (four waves side by side along the weight rows)
 constexpr int kGemmStageBytes = kGemmBM * 256; // one K step of activations
 constexpr int kGemmScaleOffset = 2 * kGemmStageBytes;          // float scale[256] behind the two stages
 constexpr int kGemmLdsBytes = kGemmScaleOffset + kGemmBM * 4;
-constexpr int kGemmPitch32 = 128 * 4 + 32;     // epilogue row pitch, 4-byte outputs: rows r and r+4 in different bank halves
-constexpr int kGemmPitch16 = 128 * 2 + 32;     // same for bf16 outputs
+constexpr int kGemmPitch32 = 64 * 4 + 32;      // epilogue row pitch, 4-byte outputs: rows r and r+4 in different bank halves
+constexpr int kGemmPitch16 = 64 * 2 + 32;      // same for bf16 outputs
 
 __device__ inline uint32_t gemm_quad_word(const uint4& q, int j) { return j == 0 ? q.x : j == 1 ? q.y : j == 2 ? q.z : q.w; }
 
@@ -57,19 +60,19 @@ struct GemmOutCtx {
 };
 
 // A lane holds, per 32 x 32 fragment, 16 tokens (8 (v >> 2) + 4 (lane >> 5) + (v & 3)) of weight row
-// (lane & 31).  Each wave stages one fragment row (32 tokens x 128 weight rows) in its own LDS region,
+// (lane & 31).  Each wave stages one fragment row (32 tokens x 64 weight rows) in its own LDS region,
 // then its lanes read 16-byte pieces along the token rows and store them.
 template <OutType kOut>
-__device__ inline void gemm_epilogue(v16i (&acc)[4][4], const GemmOutCtx& c) {
+__device__ inline void gemm_epilogue(v16i (&acc)[4][kGemmFN], const GemmOutCtx& c) {
     constexpr bool is16 = kOut == OutType::BF16;
     constexpr int esz = is16 ? 2 : 4;
     constexpr int pitch = is16 ? kGemmPitch16 : kGemmPitch32;
-    constexpr int lanes_per_row = 128 * esz / 16;                   // 16 or 32
-    constexpr int rows_per_pass = 64 / lanes_per_row;               // 4 or 2
+    constexpr int lanes_per_row = 64 * esz / 16;                    // 8 or 16
+    constexpr int rows_per_pass = 64 / lanes_per_row;               // 8 or 4
     const int am = c.lane & 31, kg = c.lane >> 5;
-    const int wm = c.wave >> 1, wn = c.wave & 1;
+    const int wm = 0, wn = c.wave;
     char* stage_out = c.lds + c.wave * (32 * kGemmPitch32);
-    const int64_t n_wave = (int64_t)c.bn * kGemmBN + wn * 128;
+    const int64_t n_wave = (int64_t)c.bn * kGemmBN + wn * 64;
     const int piece = c.lane % lanes_per_row;
     const int64_t n = n_wave + piece * (16 / esz);
 #pragma unroll
@@ -79,7 +82,7 @@ __device__ inline void gemm_epilogue(v16i (&acc)[4][4], const GemmOutCtx& c) {
             const int rl = 8 * (v >> 2) + 4 * kg + (v & 3);
             const float scale = kOut == OutType::I32 ? 0.0f : c.scale_lds[wm * 128 + fm * 32 + rl];
 #pragma unroll
-            for (int fn = 0; fn < 4; ++fn) {
+            for (int fn = 0; fn < kGemmFN; ++fn) {
                 const int a = acc[fm][fn][v] >> 6;                  // drop the decode factor 64 (exact)
                 char* p = stage_out + rl * pitch + (fn * 32 + am) * esz;
                 if (kOut == OutType::I32) *reinterpret_cast<int32_t*>(p) = a;
@@ -116,7 +119,7 @@ __device__ inline void gemm_epilogue(v16i (&acc)[4][4], const GemmOutCtx& c) {
     }
 }
 
-__global__ __launch_bounds__(kGemmThreads, 1) void linear_gemm_2bit(
+__global__ __launch_bounds__(kGemmThreads, 2) void linear_gemm_2bit(
         const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
         const float* __restrict__ gamma, int M, int64_t N, int64_t K, int Kq, int RB, int tiles_m,
         void* __restrict__ y, OutType yt, int vec_store) {
@@ -126,7 +129,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void linear_gemm_2bit(
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = 0, wn = wave;
     const int bm = blockIdx.x % tiles_m;            // token tile varies fastest (see header)
     const int bn = blockIdx.x / tiles_m;
     const int steps = (Kq + 3) >> 2;
@@ -135,40 +138,40 @@ __global__ __launch_bounds__(kGemmThreads, 1) void linear_gemm_2bit(
     const int64_t wstride = (int64_t)RB * 64;
 
     // ---- per-token output scale gamma * s_x / 127, once per tile ------------------------------------
-    {
+    if (threadIdx.x < kGemmBM) {
         const int m = min(bm * kGemmBM + (int)threadIdx.x, M - 1);
         scale_lds[threadIdx.x] = (gamma[0] * sx[m]) / kQb;
     }
 
-    // ---- A operand, global -> LDS: this wave copies rows 64*wave .. +63 of the tile, 4 rows per load.
+    // ---- A operand, global -> LDS: this wave copies rows 32*wave .. +31 of the tile, 4 rows per load.
     // Lane i of a load writes LDS slot i: row (i >> 4) of the group, chunk slot (i & 15); the chunk that
     // belongs in slot c' of row m is c' ^ (m & 15).  Offsets are relative to the tile's first row.
     const int cp_row = lane >> 4, cp_slot = lane & 15;
     const int8_t* xtile = xq + (int64_t)bm * kGemmBM * K;
     const int rows_here = min(kGemmBM, M - bm * kGemmBM);           // rows past M: clamped, never stored
-    uint32_t xoff[16];
+    uint32_t xoff[8];
 #pragma unroll
-    for (int t = 0; t < 16; ++t) {
-        const int row = wave * 64 + t * 4 + cp_row;
+    for (int t = 0; t < 8; ++t) {
+        const int row = wave * 32 + t * 4 + cp_row;
         xoff[t] = (uint32_t)min(row, rows_here - 1) * (uint32_t)K + (uint32_t)((cp_slot ^ (row & 15)) << 4);
     }
     // ---- A operand, LDS -> registers
     const int am = lane & 31, kg = lane >> 5;
     const int a_row_base = (wm * 128 + am) * 256;                    // + fm * 8192
-    // ---- B operand: fragment fn covers row blocks 2*fn, 2*fn+1 of this wave's 8
+    // ---- B operand: fragment fn covers row blocks 2*fn, 2*fn+1 of this wave's 4
     const int brow = lane & 15, bsel = (lane >> 4) & 1;
-    uint32_t woff[4][2];                                            // quad offsets inside a whole step
+    uint32_t woff[kGemmFN][2];                                      // quad offsets inside a whole step
 #pragma unroll
-    for (int fn = 0; fn < 4; ++fn)
+    for (int fn = 0; fn < kGemmFN; ++fn)
 #pragma unroll
         for (int h = 0; h < 2; ++h)
-            woff[fn][h] = (uint32_t)min(bn * 16 + wn * 8 + fn * 2 + bsel, RB - 1) * 64u + (uint32_t)((kg + 2 * h) * 16 + brow);
+            woff[fn][h] = (uint32_t)min(bn * 16 + wn * 4 + fn * 2 + bsel, RB - 1) * 64u + (uint32_t)((kg + 2 * h) * 16 + brow);
 
-    v16i acc[4][4];
+    v16i acc[4][kGemmFN];
 #pragma unroll
     for (int fm = 0; fm < 4; ++fm)
 #pragma unroll
-        for (int fn = 0; fn < 4; ++fn)
+        for (int fn = 0; fn < kGemmFN; ++fn)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[fm][fn][v] = 0;
 
@@ -180,25 +183,25 @@ __global__ __launch_bounds__(kGemmThreads, 1) void linear_gemm_2bit(
     auto copy_x = [&](int step, int stage) {
         char* dst_stage = lds + stage * kGemmStageBytes;
 #pragma unroll
-        for (int t = 0; t < 16; ++t)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (__attribute__((address_space(3))) void*)(dst_stage + (wave * 64 + t * 4) * 256),
+        for (int t = 0; t < 8; ++t)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (__attribute__((address_space(3))) void*)(dst_stage + (wave * 32 + t * 4) * 256),
                                                      16, xoff[t], step * 256, 0, 0);
     };
-    auto load_w = [&](uint4 (&wq)[4][2], int step) {
+    auto load_w = [&](uint4 (&wq)[kGemmFN][2], int step) {
         const uint4* src = packed + (int64_t)step * wstride;
 #pragma unroll
         for (int h = 0; h < 2; ++h)
 #pragma unroll
-            for (int fn = 0; fn < 4; ++fn) wq[fn][h] = src[woff[fn][h]];
+            for (int fn = 0; fn < kGemmFN; ++fn) wq[fn][h] = src[woff[fn][h]];
     };
     // the partial last step: its chunks hold fewer quads; lanes past them are clamped here and masked in compute()
-    auto load_w_tail = [&](uint4 (&wq)[4][2], int step) {
+    auto load_w_tail = [&](uint4 (&wq)[kGemmFN][2], int step) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int ln = min((kg + 2 * h) * 16 + brow, tail_quads - 1);
 #pragma unroll
-            for (int fn = 0; fn < 4; ++fn) {
-                const int rb = min(bn * 16 + wn * 8 + fn * 2 + bsel, RB - 1);
+            for (int fn = 0; fn < kGemmFN; ++fn) {
+                const int rb = min(bn * 16 + wn * 4 + fn * 2 + bsel, RB - 1);
                 wq[fn][h] = packed[(int64_t)step * wstride + (int64_t)rb * tail_quads + ln];
             }
         }
@@ -206,20 +209,20 @@ __global__ __launch_bounds__(kGemmThreads, 1) void linear_gemm_2bit(
 
     // One K step: 8 slices of 32 columns, slice (h, j) uses word j of quad h; the LDS reads and the
     // decode for slice t + 1 are placed among the MFMAs of slice t.
-    auto compute = [&](const uint4 (&wq)[4][2], int stage, uint32_t keep0, uint32_t keep1) {
+    auto compute = [&](const uint4 (&wq)[kGemmFN][2], int stage) {
         const char* src = lds + stage * kGemmStageBytes + a_row_base;
         const int sw = am & 15;
-        v4i a[2][4], b[2][4];
+        v4i a[2][4], b[2][kGemmFN];
         auto read_a = [&](v4i (&dst)[4], int t) {
             const int chunk = 8 * (t >> 2) + 4 * kg + (t & 3);
 #pragma unroll
             for (int fm = 0; fm < 4; ++fm)
                 dst[fm] = *reinterpret_cast<const v4i*>(src + fm * 8192 + ((chunk ^ sw) << 4));
         };
-        auto word_of = [&](int fn, int t) { return gemm_quad_word(wq[fn][t >> 2], t & 3) & ((t >> 2) ? keep1 : keep0); };
+        auto word_of = [&](int fn, int t) { return gemm_quad_word(wq[fn][t >> 2], t & 3); };
         read_a(a[0], 0);
 #pragma unroll
-        for (int fn = 0; fn < 4; ++fn) {
+        for (int fn = 0; fn < kGemmFN; ++fn) {
             const uint32_t w = word_of(fn, 0);
 #pragma unroll
             for (int i = 0; i < 4; ++i) b[0][fn][i] = gemm_decode_reg(w, i);
@@ -230,10 +233,10 @@ __global__ __launch_bounds__(kGemmThreads, 1) void linear_gemm_2bit(
             __builtin_amdgcn_sched_barrier(0);          // slices stay in order: no hoisting of later LDS reads
             if (t < 7) read_a(a[nxt], t + 1);
 #pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                const int fm = q >> 2, fn = q & 3;
+            for (int q = 0; q < 4 * kGemmFN; ++q) {
+                const int fm = q / kGemmFN, fn = q % kGemmFN;
                 acc[fm][fn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[cur][fm], b[cur][fn], acc[fm][fn], 0, 0, 0);
-                if (t < 7) b[nxt][fm][fn] = gemm_decode_reg(word_of(fm, t + 1), fn);   // register fn of fragment fm
+                if (t < 7) b[nxt][q >> 2][q & 3] = gemm_decode_reg(word_of(q >> 2, t + 1), q & 3);   // one register per MFMA
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -242,7 +245,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void linear_gemm_2bit(
     // One loop body for every step: operands of step s + 1 are requested right before step s is
     // consumed (activations into the other LDS stage, weights into wnext), and the barrier at the top of
     // the next iteration both publishes them and retires the stage that was just read.
-    uint4 wq[4][2], wnext[4][2];
+    uint4 wq[kGemmFN][2], wnext[kGemmFN][2];
     const uint32_t keep_t0 = (kg * 16 + brow) < tail_quads ? 0xFFFFFFFFu : 0u;
     const uint32_t keep_t1 = ((kg + 2) * 16 + brow) < tail_quads ? 0xFFFFFFFFu : 0u;
     auto issue = [&](int step) {
@@ -254,13 +257,17 @@ __global__ __launch_bounds__(kGemmThreads, 1) void linear_gemm_2bit(
     for (int s = 0; s < steps; ++s) {
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-#pragma unroll
-        for (int fn = 0; fn < 4; ++fn)
-#pragma unroll
-            for (int h = 0; h < 2; ++h) wq[fn][h] = wnext[fn][h];
-        if (s + 1 < steps) issue(s + 1);
+        // move the step's quads out of the landing registers; lanes past a partial last step are zeroed here
         const bool tail = s >= full_steps;
-        compute(wq, s & 1, tail ? keep_t0 : 0xFFFFFFFFu, tail ? keep_t1 : 0xFFFFFFFFu);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t keep = !tail ? 0xFFFFFFFFu : (h ? keep_t1 : keep_t0);
+#pragma unroll
+            for (int fn = 0; fn < kGemmFN; ++fn)
+                wq[fn][h] = make_uint4(wnext[fn][h].x & keep, wnext[fn][h].y & keep, wnext[fn][h].z & keep, wnext[fn][h].w & keep);
+        }
+        if (s + 1 < steps) issue(s + 1);
+        compute(wq, s & 1);
     }
     __syncthreads();                                    // every wave is done with the activation stages
 
