@@ -42,6 +42,21 @@ def gemv_bytes(M, N, K, out_bytes=2):
     return N * K // 4 + M * K + 4 * M + M * N * out_bytes
 
 
+def measured_traffic(N, K):
+    """HBM bytes per launch of the M = 1 product on an N x K layer, from the committed rocprofv3 --pmc summary
+    (profiles/hbm_traffic.json: FETCH_SIZE + WRITE_SIZE, each scaled by what the counter reads for a plain
+    256 MiB copy).  None if the summary has no entry for this launch shape."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        table = json.load(f)
+    for key, v in table.get("kernels", {}).items():
+        if key.startswith("linear_gemv16_2bit") and v.get("N") == N and v.get("K") == K:
+            return int(v["fetch_bytes"] + v["write_bytes"])
+    return None
+
+
 def make_acts(torch, M, K, gen, seed_channels):
     import numpy as np
     from paper_2402_17764_amd import synth
@@ -115,6 +130,77 @@ def cpu_baseline(cfg_idx, M, seconds_target=12.0):
     }
 
 
+def large_gemv_leg(torch, B, synth, gen, stream, args):
+    """M = 1 on the 70B-class FFN shapes (the sizes at which a weight stream can approach the HBM roofline):
+    each shape is replayed over enough distinct layers to exceed the 256 MB memory-side cache."""
+    res = {}
+    for (name, K, N) in synth.CONFIGS[4]["shapes"]:
+        per = N * K // 4
+        layers = max(3, int(math.ceil(600e6 / per)))
+        packs = []
+        for l in range(layers):
+            W = torch.randn((N, K), device="cuda", generator=gen, dtype=torch.float32) * synth.SIGMA_W
+            packs.append(B.quantize_weights(W))
+            del W
+        x = make_acts(torch, 1, K, gen, 4)
+        y = torch.empty((1, N), dtype=torch.bfloat16, device="cuda")
+
+        def run():
+            for (p, g) in packs:
+                B.linear_fused(x, p, g, N, y_dtype=B.BF16, y=y)
+
+        ms, _, _ = time_graph(torch, run, args.warmup, args.steps, stream)
+        us = ms * 1e3 / layers
+        gbs = gemv_bytes(1, N, K) / (us * 1e-6) / 1e9
+        res[name] = {"K": K, "N": N, "layers": layers, "us_per_launch": round(us, 2), "GB/s": round(gbs, 1),
+                     "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+        del packs
+        torch.cuda.empty_cache()
+    return res
+
+
+def gemm_leg(torch, B, synth, gen, args, M=2048):
+    """Prefill: M = 2048 tokens on the 13B-class shapes, bitnet_quantize_acts + bitnet_linear (MFMA kernel)."""
+    res = {"M": M, "shapes": {}}
+    tot_ops, tot_us = 0.0, 0.0
+    for (name, K, N) in synth.CONFIGS[3]["shapes"]:
+        W = torch.randn((N, K), device="cuda", generator=gen, dtype=torch.float32) * synth.SIGMA_W
+        p, g = B.quantize_weights(W)
+        del W
+        x = make_acts(torch, M, K, gen, 3)
+        xq, sx = B.quantize_acts(x)
+        y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        iters = max(5, args.steps // 2)
+        for _ in range(3):
+            B.linear(xq, sx, p, g, N, y_dtype=B.BF16, y=y)
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            B.linear(xq, sx, p, g, N, y_dtype=B.BF16, y=y)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / iters
+        e0.record()
+        for _ in range(iters):
+            B.quantize_acts(x, xq=xq, sx=sx)
+        e1.record()
+        torch.cuda.synchronize()
+        us_q = e0.elapsed_time(e1) * 1e3 / iters
+        ops = 2.0 * M * N * K
+        res["shapes"][name] = {"K": K, "N": N, "us_linear": round(us, 1), "us_quantize_acts": round(us_q, 1),
+                               "TOPS": round(ops / us * 1e-6, 1), "frac_int8_mfma_peak": round(ops / us * 1e-6 / INT8_MFMA_PEAK_TOPS, 4)}
+        tot_ops += ops
+        tot_us += us
+        del p, x, xq, y
+        torch.cuda.empty_cache()
+    res["TOPS"] = round(tot_ops / tot_us * 1e-6, 1)
+    res["roofline"] = {"bound": "mfma", "kernel": "linear_gemm_2bit", "achieved": round(tot_ops / tot_us * 1e-6, 1),
+                       "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(tot_ops / tot_us * 1e-6 / INT8_MFMA_PEAK_TOPS, 4)}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -124,6 +210,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--unfused", action="store_true",
                     help="two launches per product (bitnet_quantize_acts + bitnet_linear) instead of bitnet_linear_fused")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy (torch copy_) three times, so that a rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE run of this command contains a kernel of known traffic to scale by")
     ap.add_argument("--no-extras", action="store_true", help="skip the weight_quant and large-shape legs")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -137,6 +226,14 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     B.load()
+
+    if args.pmc_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     cfg_idx, M, L = WORKLOADS[args.workload]
     cfg = synth.CONFIGS[cfg_idx]
@@ -204,7 +301,7 @@ def main():
     roofline = {
         "bound": "hbm", "kernel": "linear_gemv16_2bit", "shape": "%s K=%d N=%d M=%d" % (dname, dK, dN, M),
         "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "bytes_per_launch": dom_bytes, "us_per_launch": round(dom_us, 3), "traffic": None,
+        "bytes_per_launch": dom_bytes, "us_per_launch": round(dom_us, 3), "traffic": measured_traffic(dN, dK),
     }
 
     out = {
@@ -225,6 +322,10 @@ def main():
         out["weight_quant"] = {"ms_per_pass": round(wq_ms, 3), "tensors": L * len(shapes),
                                "GB/s": round(wq_bytes / (wq_ms * 1e-3) / 1e9, 1),
                                "note": "quantize + pack of every layer, 8.25 algorithmic bytes per weight"}
+        del packed, acts
+        torch.cuda.empty_cache()
+        out["gemv_70b_m1"] = large_gemv_leg(torch, B, synth, gen, stream, args)
+        out["gemm_m2048"] = gemm_leg(torch, B, synth, gen, args)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg_idx, M)
     print(json.dumps(out))
