@@ -76,12 +76,18 @@ typedef enum bitnet_dtype {
  *   [8*b + 2*i, 8*b + 2*i + 1].  A code is 2-bit two's complement: 00 = 0, 01 = +1, 11 = -1
  *   (10 never occurs).  Size: Np * Kp / 4 bytes.
  *
- * BITNET_PACK_TRIT5 -- 5 codes per byte (1.6 bits per weight), base 3.
- *   N padded to Np as above, K padded to Kp = 320*ceil(K/320) columns with zero codes.  The buffer
- *   is an array of 16-byte quads; quad index ((rb * (Kp/320) + kc) * 4 + q) * 16 + r holds, for row
- *   n = 16*rb + r, the 80 codes of columns 320*kc + 80*q .. +79; byte t of that quad holds columns
- *   320*kc + 80*q + 5*t + d (d = 0..4) as the value sum_d (code_d + 1) * 3^d  (0..242).
- *   Size: Np * Kp / 5 bytes.
+ * BITNET_PACK_TRIT5 -- 5 codes per byte (1.6 bits per weight), base 3, K-step major like the 2-bit format.
+ *   N is padded to Np = 16*ceil(N/16) rows (RB row blocks), K to Kp = 320*ceil(K/320) columns with zero
+ *   codes.  A quad (16 bytes) holds the 80 codes of one row for 80 consecutive columns; a step is 320
+ *   columns (4 quads).  The quad of row n = 16*rb + r, columns 320*s + 80*g .. +79 has index
+ *       64*(RB*s + rb) + 16*g + r.
+ *   Byte p (0..15) of a quad holds five base-3 digits, value = sum_d (code_d + 1) * 3^d  (0..242):
+ *   digits 0..3 are the codes of columns 4*p + 0..3 of the quad, digit 4 the code of column 64 + p.
+ *   (So one table look-up per byte yields four consecutive codes, i.e. one 32-bit MFMA operand
+ *   register, and the sixteen fifth digits of a quad form the operand of a fifth MFMA.)
+ *   Size: Np * Kp / 5 bytes.  Supported by bitnet_quantize_weights, bitnet_unpack_weights and
+ *   bitnet_linear (weight-streaming kernel for M <= 16, reference kernel above); bitnet_linear_fused
+ *   and the MFMA prefill kernel take the 2-bit format only.
  */
 typedef enum bitnet_format {
     BITNET_PACK_2BIT = 0,

@@ -94,7 +94,9 @@ bitnet_status bitnet_quantize_weights(const void* W, bitnet_dtype w_dtype, int64
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (f == BITNET_PACK_2BIT)
         return from_hip(bitnet::launch_quantize_weights_2bit(W, w_dtype == BITNET_BF16, N, K, packed, gamma, workspace, s));
-    return BITNET_ERR_FORMAT;
+    hipError_t e = bitnet::launch_absmean_gamma(W, w_dtype == BITNET_BF16, N, K, gamma, workspace, s);
+    if (e != hipSuccess) return BITNET_ERR_HIP;
+    return from_hip(bitnet::launch_pack_trit5(W, w_dtype == BITNET_BF16, N, K, gamma, packed, s));
 }
 
 bitnet_status bitnet_quantize_acts(const void* x, bitnet_dtype x_dtype, int64_t M, int64_t K, int8_t* xq,
@@ -118,7 +120,17 @@ bitnet_status bitnet_linear_variant(const int8_t* xq, const float* sx, const voi
     if (!aligned(packed, 16) || !aligned(sx, 4) || !aligned(gamma, 4) || !aligned(y, dtype_size(y_dtype)))
         return BITNET_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (f != BITNET_PACK_2BIT) return BITNET_ERR_FORMAT;
+
+    if (f == BITNET_PACK_TRIT5) {
+        // the 5-trit format has the reference kernel and the weight-streaming kernel for M <= 16
+        if (which == BITNET_KERNEL_AUTO)
+            which = bitnet::gemv_trit5_supports(M, N, K, xq) ? BITNET_KERNEL_GEMV : BITNET_KERNEL_REFERENCE;
+        if (which == BITNET_KERNEL_REFERENCE)
+            return from_hip(bitnet::launch_linear_reference_trit5(xq, sx, packed, gamma, M, N, K, y, yt, s));
+        if (which == BITNET_KERNEL_GEMV && bitnet::gemv_trit5_supports(M, N, K, xq))
+            return from_hip(bitnet::launch_linear_gemv_trit5(xq, sx, packed, gamma, M, N, K, y, yt, s));
+        return BITNET_ERR_KERNEL;
+    }
 
     if (which == BITNET_KERNEL_AUTO) {
         if (bitnet::gemv_supports(M, N, K, xq)) which = BITNET_KERNEL_GEMV;
@@ -169,7 +181,7 @@ bitnet_status bitnet_unpack_weights(const void* packed, int64_t N, int64_t K, bi
     if (!aligned(packed, 16)) return BITNET_ERR_ALIGN;
     if (f == BITNET_PACK_2BIT)
         return from_hip(bitnet::launch_unpack_2bit(packed, N, K, codes, static_cast<hipStream_t>(stream)));
-    return BITNET_ERR_FORMAT;
+    return from_hip(bitnet::launch_unpack_trit5(packed, N, K, codes, static_cast<hipStream_t>(stream)));
 }
 
 }  // extern "C"

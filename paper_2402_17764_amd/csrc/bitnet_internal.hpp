@@ -11,6 +11,8 @@ enum class OutType { F32 = 0, BF16 = 1, I32 = 2 };
 
 // quant_weights.hip
 int quant_weights_num_partials();
+hipError_t launch_absmean_gamma(const void* W, bool bf16, int64_t N, int64_t K, float* gamma, void* workspace,
+                                hipStream_t stream);
 hipError_t launch_quantize_weights_2bit(const void* W, bool bf16, int64_t N, int64_t K, void* packed,
                                         float* gamma, void* workspace, hipStream_t stream);
 
@@ -37,5 +39,15 @@ hipError_t launch_linear_fused_2bit(const void* x, bool bf16, const void* packed
 bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq);
 hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                    int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);
+
+// trit5.hip
+hipError_t launch_pack_trit5(const void* W, bool bf16, int64_t N, int64_t K, const float* gamma, void* packed,
+                             hipStream_t stream);
+hipError_t launch_unpack_trit5(const void* packed, int64_t N, int64_t K, int8_t* codes, hipStream_t stream);
+hipError_t launch_linear_reference_trit5(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
+                                         int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);
+bool gemv_trit5_supports(int64_t M, int64_t N, int64_t K, const void* xq);
+hipError_t launch_linear_gemv_trit5(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
+                                    int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);
 
 }  // namespace bitnet

@@ -175,8 +175,9 @@ __global__ __launch_bounds__(kPackThreads) void ternarize_pack_2bit(const T* __r
 // ---------------------------------------------------------------------------------------------------
 int quant_weights_num_partials() { return 2048; }
 
-hipError_t launch_quantize_weights_2bit(const void* W, bool bf16, int64_t N, int64_t K, void* packed,
-                                        float* gamma, void* workspace, hipStream_t stream) {
+// Eq. (3): passes 1 and 2, shared by every packing format
+hipError_t launch_absmean_gamma(const void* W, bool bf16, int64_t N, int64_t K, float* gamma, void* workspace,
+                                hipStream_t stream) {
     const int64_t count = N * K;
     double* partials = static_cast<double*>(workspace);
     int64_t want = ceil_div(count, (int64_t)kSumThreads * 16);
@@ -190,6 +191,15 @@ hipError_t launch_quantize_weights_2bit(const void* W, bool bf16, int64_t N, int
         hipLaunchKernelGGL(abs_sum_partials<float>, dim3(blocks), dim3(kSumThreads), 0, stream,
                            static_cast<const float*>(W), count, vec_ok, partials);
     hipLaunchKernelGGL(finish_gamma, dim3(1), dim3(kSumThreads), 0, stream, partials, blocks, count, gamma);
+    return hipGetLastError();
+}
+
+hipError_t launch_quantize_weights_2bit(const void* W, bool bf16, int64_t N, int64_t K, void* packed,
+                                        float* gamma, void* workspace, hipStream_t stream) {
+    hipError_t err = launch_absmean_gamma(W, bf16, N, K, gamma, workspace, stream);
+    if (err != hipSuccess) return err;
+    const size_t esz = bf16 ? 2 : 4;
+    const int vec_ok = (reinterpret_cast<uintptr_t>(W) % (4 * esz)) == 0;
 
     const int64_t Kq = ceil_div(K, kColsPerQuad);
     const int64_t RB = ceil_div(N, kRowsPerBlock);

@@ -1,0 +1,294 @@
+// The 5-trits-per-byte format (1.6 bits per weight; the paper notes that 2 bits leave room above the
+// 1.58-bit information content of a ternary weight, Section 3 of arXiv 2402.17764): packer, unpack
+// helper, reference product and a weight-streaming kernel for M <= 16, measured against the 2-bit one.
+//
+// Layout (bitnet.h): byte p of a 16-byte quad carries digits 0..3 = four consecutive columns 4p..4p+3
+// and digit 4 = column 64 + p of the quad's 80 columns.  The streaming kernel keeps a 243-entry table
+// in LDS that maps a byte to its five decoded operand bytes (64 * code), so a byte's first four digits
+// arrive as one ready MFMA operand register; the sixteen fifth digits of a quad are gathered into the
+// four registers of a fifth MFMA.  One step = 320 columns = five v_mfma_i32_16x16x64_i8 per row block.
+#include "bitnet_device.hpp"
+#include "bitnet_internal.hpp"
+
+namespace bitnet {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+constexpr int kTritCols = 80;            // columns per quad
+constexpr int kTritStep = 320;           // columns per step (4 quads)
+
+// byte offset and digit of column k of row n
+__host__ __device__ inline void trit5_locate(int64_t n, int64_t k, int64_t RB, int64_t* byte_index, int* digit) {
+    const int64_t s = k / kTritStep;
+    const int c = (int)(k % kTritStep);
+    const int g = c / kTritCols, q = c % kTritCols;
+    const int64_t quad = 64 * (RB * s + (n >> 4)) + 16 * g + (n & 15);
+    if (q < 64) { *byte_index = quad * 16 + (q >> 2); *digit = q & 3; }
+    else        { *byte_index = quad * 16 + (q - 64); *digit = 4; }
+}
+
+__device__ inline int trit5_digit(uint32_t byte, int d) {
+    const uint32_t p3 = d == 0 ? 1u : d == 1 ? 3u : d == 2 ? 9u : d == 3 ? 27u : 81u;
+    return (int)((byte / p3) % 3u) - 1;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// packer: one thread per (row, quad): 80 consecutive weights in, 16 bytes out
+// ---------------------------------------------------------------------------------------------------
+__device__ inline float trit_w(const float* p) { return *p; }
+__device__ inline float trit_w(const uint16_t* p) { return bf16_to_f32(*p); }
+
+template <typename T>
+__global__ __launch_bounds__(256) void ternarize_pack_trit5(const T* __restrict__ W, int64_t N, int64_t K, int64_t RB,
+                                                            int64_t steps, const float* __restrict__ gamma,
+                                                            uint4* __restrict__ packed) {
+    const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;      // = (n_padded * steps * 4 + quad-in-row)
+    const int64_t quads_per_row = steps * 4;
+    const int64_t n = tid / quads_per_row;
+    const int64_t qr = tid % quads_per_row;
+    if (n >= RB * 16) return;
+    const int64_t s = qr >> 2;
+    const int g = (int)(qr & 3);
+    const int64_t k0 = s * kTritStep + g * kTritCols;
+    const float d = gamma[0] + kEps;                                   // Eq. (1): gamma + eps
+    uint32_t t[80];                                                    // code + 1 per column
+#pragma unroll
+    for (int c = 0; c < 80; ++c) {
+        float w = 0.0f;                                                // padding quantizes to code 0
+        if (n < N && k0 + c < K) w = trit_w(W + n * K + k0 + c);
+        const float r = fminf(1.0f, fmaxf(-1.0f, rintf(w / d)));       // Eq. (1)-(2)
+        t[c] = (uint32_t)((int)r + 1);
+    }
+    uint32_t words[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int p = 0; p < 16; ++p) {
+        const uint32_t b = t[4 * p] + 3 * t[4 * p + 1] + 9 * t[4 * p + 2] + 27 * t[4 * p + 3] + 81 * t[64 + p];
+        words[p >> 2] |= b << (8 * (p & 3));
+    }
+    packed[64 * (RB * s + (n >> 4)) + 16 * g + (n & 15)] = make_uint4(words[0], words[1], words[2], words[3]);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// unpack helper and reference product
+// ---------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void unpack_trit5(const uint8_t* __restrict__ packed, int64_t N, int64_t K, int64_t RB,
+                                                    int8_t* __restrict__ codes) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= N * K) return;
+    int64_t bi; int dg;
+    trit5_locate(idx / K, idx % K, RB, &bi, &dg);
+    codes[idx] = (int8_t)trit5_digit(packed[bi], dg);
+}
+
+__global__ __launch_bounds__(256) void linear_reference_trit5(const int8_t* __restrict__ xq, const float* __restrict__ sx,
+                                                              const uint8_t* __restrict__ packed,
+                                                              const float* __restrict__ gamma, int64_t N, int64_t K,
+                                                              int64_t RB, void* __restrict__ y, OutType yt) {
+    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t m = blockIdx.y;
+    if (n >= N) return;
+    const int8_t* xr = xq + m * K;
+    int32_t acc = 0;
+    for (int64_t k = 0; k < K; ++k) {
+        int64_t bi; int dg;
+        trit5_locate(n, k, RB, &bi, &dg);
+        const int code = trit5_digit(packed[bi], dg);
+        if (code > 0) acc += xr[k];
+        else if (code < 0) acc -= xr[k];
+    }
+    const int64_t idx = m * N + n;
+    if (yt == OutType::I32) static_cast<int32_t*>(y)[idx] = acc;
+    else {
+        const float v = (float)acc * ((gamma[0] * sx[m]) / kQb);
+        if (yt == OutType::F32) static_cast<float*>(y)[idx] = v;
+        else static_cast<uint16_t*>(y)[idx] = f32_to_bf16(v);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// weight-streaming kernel, M <= 16
+// ---------------------------------------------------------------------------------------------------
+__device__ inline v4i trit_as_v4i(const uint4& u) {
+    v4i a;
+    a.x = (int)u.x; a.y = (int)u.y; a.z = (int)u.z; a.w = (int)u.w;
+    return a;
+}
+
+// kR row blocks per wave, kS waves splitting K, kD steps of loads in flight (same scheme as the 2-bit kernel:
+// branch-free masked loop, out-of-range steps / rows / tokens redirected and zeroed)
+template <int kR, int kS, int kD>
+__global__ __launch_bounds__(kS * kWave) void linear_gemv16_trit5(
+        const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
+        const float* __restrict__ gamma, int M, int64_t N, int64_t K, int RB, int steps, int items,
+        void* __restrict__ y, OutType yt) {
+    __shared__ uint2 lut[256];                       // byte -> {digits 0..3 as 4 operand bytes, digit 4 as 1 byte}
+    __shared__ v4i fold[kS][kR][kWave];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    const int r = lane & 15, g = lane >> 4;
+    const int rb0 = blockIdx.x * kR;
+
+    for (int b = threadIdx.x; b < 256; b += kS * kWave) {
+        uint32_t lo = 0, hi = 0;
+        if (b < 243) {
+#pragma unroll
+            for (int dgt = 0; dgt < 4; ++dgt) lo |= ((uint32_t)(trit5_digit(b, dgt) * 64) & 0xFFu) << (8 * dgt);
+            hi = (uint32_t)(trit5_digit(b, 4) * 64) & 0xFFu;
+        }
+        lut[b] = make_uint2(lo, hi);
+    }
+
+    const int64_t wstride = (int64_t)RB * 64;
+    const uint4* wp[kR];
+#pragma unroll
+    for (int a = 0; a < kR; ++a) wp[a] = packed + (int64_t)min(rb0 + a, RB - 1) * 64 + lane;
+    const int8_t* xg = xq + (int64_t)min(r, M - 1) * K;
+
+    v4i acc[kR];
+#pragma unroll
+    for (int a = 0; a < kR; ++a) acc[a] = (v4i){0, 0, 0, 0};
+
+    struct Stage { uint4 w[kR]; uint4 x[5]; };
+    auto load = [&](Stage& s, int item) {
+        const int sl = min(wave + item * kS, steps - 1);
+#pragma unroll
+        for (int a = 0; a < kR; ++a) s.w[a] = wp[a][(int64_t)sl * wstride];
+#pragma unroll
+        for (int j = 0; j < 5; ++j) {
+            const int64_t col = min((int64_t)sl * kTritStep + kTritCols * g + 16 * j, K - 16);   // past K: zero codes
+            s.x[j] = *reinterpret_cast<const uint4*>(xg + col);
+        }
+    };
+    auto mac = [&](Stage& s, int item) {
+        const bool live = wave + item * kS < steps;
+#pragma unroll
+        for (int a = 0; a < kR; ++a) {
+            const uint32_t wd[4] = {s.w[a].x, s.w[a].y, s.w[a].z, s.w[a].w};
+            v4i op[5];
+#pragma unroll
+            for (int p = 0; p < 16; ++p) {
+                // byte 121 = digits (1,1,1,1,1) = five zero codes: what a step past the end contributes
+                const uint32_t byte = live ? ((wd[p >> 2] >> (8 * (p & 3))) & 0xFFu) : 121u;
+                const uint2 e = lut[byte];
+                op[p >> 2][p & 3] = (int)e.x;
+                if ((p & 3) == 0) op[4][p >> 2] = (int)e.y;
+                else op[4][p >> 2] |= (int)(e.y << (8 * (p & 3)));
+            }
+#pragma unroll
+            for (int j = 0; j < 5; ++j)
+                acc[a] = __builtin_amdgcn_mfma_i32_16x16x64_i8(op[j], trit_as_v4i(s.x[j]), acc[a], 0, 0, 0);
+        }
+    };
+
+    Stage st[kD];
+#pragma unroll
+    for (int d = 0; d < kD; ++d) load(st[d], d);
+    __syncthreads();                                  // table ready
+    int i = 0;
+    for (; i + kD < items; i += kD) {
+#pragma unroll
+        for (int d = 0; d < kD; ++d) {
+            mac(st[d], i + d);
+            __builtin_amdgcn_sched_barrier(0);
+            load(st[d], i + d + kD);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+#pragma unroll
+    for (int d = 0; d < kD; ++d) mac(st[d], i + d);
+
+    if (kS > 1) {
+#pragma unroll
+        for (int a = 0; a < kR; ++a) fold[wave][a][lane] = acc[a];
+        __syncthreads();
+        if (wave != 0) return;
+#pragma unroll
+        for (int a = 0; a < kR; ++a)
+#pragma unroll
+            for (int w = 1; w < kS; ++w) {
+                const v4i o = fold[w][a][lane];
+                acc[a].x += o.x; acc[a].y += o.y; acc[a].z += o.z; acc[a].w += o.w;
+            }
+    }
+    if (r < M) {
+        const float scale = yt == OutType::I32 ? 0.0f : (gamma[0] * sx[r]) / kQb;
+#pragma unroll
+        for (int a = 0; a < kR; ++a) {
+            const int64_t n0 = (int64_t)(rb0 + a) * 16 + 4 * g;
+            const int v[4] = {acc[a].x >> 6, acc[a].y >> 6, acc[a].z >> 6, acc[a].w >> 6};   // drop the factor 64
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (n0 + e >= N) continue;
+                const int64_t idx = (int64_t)r * N + n0 + e;
+                if (yt == OutType::I32) static_cast<int32_t*>(y)[idx] = v[e];
+                else if (yt == OutType::F32) static_cast<float*>(y)[idx] = (float)v[e] * scale;
+                else static_cast<uint16_t*>(y)[idx] = f32_to_bf16((float)v[e] * scale);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------------
+hipError_t launch_pack_trit5(const void* W, bool bf16, int64_t N, int64_t K, const float* gamma, void* packed,
+                             hipStream_t stream) {
+    const int64_t RB = ceil_div(N, kRowsPerBlock);
+    const int64_t steps = ceil_div(K, kTritStep);
+    const int64_t threads = RB * 16 * steps * 4;
+    dim3 grid((unsigned)ceil_div(threads, 256));
+    if (bf16)
+        hipLaunchKernelGGL(ternarize_pack_trit5<uint16_t>, grid, dim3(256), 0, stream, static_cast<const uint16_t*>(W), N, K, RB,
+                           steps, gamma, static_cast<uint4*>(packed));
+    else
+        hipLaunchKernelGGL(ternarize_pack_trit5<float>, grid, dim3(256), 0, stream, static_cast<const float*>(W), N, K, RB,
+                           steps, gamma, static_cast<uint4*>(packed));
+    return hipGetLastError();
+}
+
+hipError_t launch_unpack_trit5(const void* packed, int64_t N, int64_t K, int8_t* codes, hipStream_t stream) {
+    hipLaunchKernelGGL(unpack_trit5, dim3((unsigned)ceil_div(N * K, 256)), dim3(256), 0, stream,
+                       static_cast<const uint8_t*>(packed), N, K, ceil_div(N, kRowsPerBlock), codes);
+    return hipGetLastError();
+}
+
+hipError_t launch_linear_reference_trit5(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
+                                         int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
+    const size_t ysz = yt == OutType::BF16 ? 2 : 4;
+    for (int64_t m0 = 0; m0 < M; m0 += 32768) {
+        const int64_t mc = (M - m0) < 32768 ? (M - m0) : 32768;
+        dim3 grid((unsigned)ceil_div(N, 256), (unsigned)mc);
+        hipLaunchKernelGGL(linear_reference_trit5, grid, dim3(256), 0, stream, xq + m0 * K, sx + m0,
+                           static_cast<const uint8_t*>(packed), gamma, N, K, ceil_div(N, kRowsPerBlock),
+                           static_cast<char*>(y) + m0 * N * ysz, yt);
+    }
+    return hipGetLastError();
+}
+
+bool gemv_trit5_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
+    (void)N;
+    return M >= 1 && M <= 16 && K % 16 == 0 && reinterpret_cast<uintptr_t>(xq) % 16 == 0;
+}
+
+template <int kR, int kS, int kD>
+static void launch_trit5(const int8_t* xq, const float* sx, const void* packed, const float* gamma, int64_t M, int64_t N,
+                         int64_t K, void* y, OutType yt, hipStream_t stream) {
+    const int RB = (int)ceil_div(N, kRowsPerBlock);
+    const int steps = (int)ceil_div(K, kTritStep);
+    int items = (int)ceil_div(steps, kS);
+    items = (int)ceil_div(items, kD) * kD;
+    hipLaunchKernelGGL((linear_gemv16_trit5<kR, kS, kD>), dim3((unsigned)ceil_div(RB, kR)), dim3(kS * kWave), 0, stream, xq, sx,
+                       static_cast<const uint4*>(packed), gamma, (int)M, N, K, RB, steps, items, y, yt);
+}
+
+hipError_t launch_linear_gemv_trit5(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
+                                    int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
+    const int64_t RB = ceil_div(N, kRowsPerBlock);
+    const int64_t steps = ceil_div(K, kTritStep);
+    if (RB >= 2048)        launch_trit5<2, 2, 2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
+    else if (steps >= 24)  launch_trit5<1, 8, 2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
+    else                   launch_trit5<1, 4, 2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
+    return hipGetLastError();
+}
+
+}  // namespace bitnet

@@ -44,3 +44,29 @@ def decode_2bit(packed_bytes, N, K):
     codes = full[:N, :K].copy()
     pad_zero = (not full[N:, :].any()) and (not full[:, K:].any())
     return codes, pad_zero
+
+
+def decode_trit5(packed_bytes, N, K):
+    """bytes of a BITNET_PACK_TRIT5 buffer -> (codes [N,K] int8, padding_is_zero bool)."""
+    RB = (N + 15) // 16
+    steps = (K + 319) // 320
+    if isinstance(packed_bytes, (bytes, bytearray)):
+        raw = np.frombuffer(bytes(packed_bytes), dtype=np.uint8)
+    else:
+        raw = np.ascontiguousarray(packed_bytes, dtype=np.uint8).ravel()
+    assert raw.size == RB * 16 * steps * 320 // 5, "buffer size does not match the documented layout"
+    assert raw.max() <= 242, "a byte holds five base-3 digits"
+    quads = raw.reshape(steps, RB, 4, 16, 16)              # [s][rb][g][r][p]
+    full = np.zeros((RB * 16, steps * 320), np.int8)
+    view = full.reshape(RB, 16, steps, 4, 80)              # [rb][r][s][g][column in quad]
+    v = quads.astype(np.int32)
+    for d in range(5):
+        digit = (v // (3 ** d)) % 3 - 1                    # [s][rb][g][r][p]
+        digit = digit.transpose(1, 3, 0, 2, 4)             # [rb][r][s][g][p]
+        if d < 4:
+            view[:, :, :, :, d:64:4] = digit               # columns 4p + d
+        else:
+            view[:, :, :, :, 64:80] = digit                # columns 64 + p
+    codes = full[:N, :K].copy()
+    pad_zero = (not full[N:, :].any()) and (not full[:, K:].any())
+    return codes, pad_zero

@@ -108,3 +108,25 @@ def test_layout_decoder_roundtrip_on_a_hand_packed_tile():
     assert quad_index_2bit(17, 1, 33, 600) == 64 * 1 + 16 * 1 + 1          # rb 1, g 1, r 1
     assert quad_index_2bit(0, 4, 33, 600) == 64 * 3                          # step 1 starts after 3 row blocks
     assert quad_index_2bit(32, 9, 33, 600) == 64 * 3 * 2 + 16 * 2 * 2 + 16 * 1 + 0   # partial step: 2 quads per chunk
+
+
+def test_trit5_layout_decoder_on_a_hand_packed_matrix():
+    import numpy as np
+    from layout_ref import decode_trit5
+    rng = np.random.default_rng(4)
+    for (N, K) in [(20, 70), (33, 700), (16, 320)]:
+        codes = rng.integers(-1, 2, size=(N, K)).astype(np.int8)
+        RB, steps = (N + 15) // 16, (K + 319) // 320
+        buf = np.full((steps, RB, 4, 16, 16), 121, np.int32)           # 121 = five zero codes
+        buf[:] = 0
+        digits = np.ones((steps, RB, 4, 16, 16, 5), np.int32)          # code + 1, padding = 1
+        for n in range(N):
+            for k in range(K):
+                s_, c = divmod(k, 320)
+                g, q = divmod(c, 80)
+                p_, d = (q // 4, q % 4) if q < 64 else (q - 64, 4)
+                digits[s_, n // 16, g, n % 16, p_, d] = int(codes[n, k]) + 1
+        buf = (digits * np.array([1, 3, 9, 27, 81])).sum(-1)
+        got, pad_zero = decode_trit5(buf.astype(np.uint8).tobytes(), N, K)
+        assert pad_zero and np.array_equal(got, codes)
+        assert buf.size == binding.packed_bytes(N, K, binding.PACK_TRIT5)

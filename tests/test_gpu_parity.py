@@ -12,7 +12,7 @@ import numpy as np
 import pytest
 
 import oracle
-from layout_ref import decode_2bit
+from layout_ref import decode_2bit, decode_trit5
 from paper_2402_17764_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -324,6 +324,70 @@ def test_linear_gemm_full_size_sampled(gpu_lib, M, N, K, layer):
                            kernel=gpu_lib.KERNEL_GEMV)
     a_gemm = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.I32)[sub]
     assert torch.equal(a_ref, a_gemm)
+
+
+# ------------------------------------------------------------------------------------------------
+# the 5-trits-per-byte format
+# ------------------------------------------------------------------------------------------------
+TRIT_WEIGHT_SHAPES = [(4096, 1536), (16, 320), (1, 1), (37, 129), (100, 70), (17, 1000), (250, 4100)]
+
+
+@pytest.mark.parametrize("N,K", TRIT_WEIGHT_SHAPES)
+def test_trit5_quantize_weights_matches_oracle(gpu_lib, N, K):
+    say("trit5 quantize_weights N=%d K=%d" % (N, K))
+    W = synth.weights(N, K, config=0, layer=N % 5, tensor=2)
+    codes_ref, gamma_ref = oracle.quantize_weights(W)
+    packed, gamma = gpu_lib.quantize_weights(dev(W), fmt=gpu_lib.PACK_TRIT5)
+    assert gamma.cpu().numpy()[0].tobytes() == np.float32(gamma_ref).tobytes()
+    assert packed.numel() == gpu_lib.packed_bytes(N, K, gpu_lib.PACK_TRIT5)
+    assert np.array_equal(gpu_lib.unpack_weights(packed, N, K, fmt=gpu_lib.PACK_TRIT5).cpu().numpy(), codes_ref)
+    dec, pad_zero = decode_trit5(packed.cpu().numpy(), N, K)
+    assert pad_zero and np.array_equal(dec, codes_ref)
+    # same codes as the 2-bit format, from bf16 weights too
+    Wf, bits = synth.to_bf16(W)
+    p5, _ = gpu_lib.quantize_weights(bf16_tensor(bits).view(N, K), fmt=gpu_lib.PACK_TRIT5)
+    p2, _ = gpu_lib.quantize_weights(bf16_tensor(bits).view(N, K))
+    assert torch.equal(gpu_lib.unpack_weights(p5, N, K, fmt=gpu_lib.PACK_TRIT5), gpu_lib.unpack_weights(p2, N, K))
+
+
+TRIT_LINEAR_SHAPES = [(1, 4096, 1536), (16, 4096, 1536), (1, 17, 16), (3, 100, 80), (7, 250, 1040), (1, 3200, 3200),
+                      (2, 32800, 528), (2, 64, 8640), (16, 300, 4112), (20, 70, 336), (70, 40, 640)]
+
+
+@pytest.mark.parametrize("M,N,K", TRIT_LINEAR_SHAPES)
+def test_trit5_linear_matches_oracle(gpu_lib, M, N, K):
+    say("trit5 linear M=%d N=%d K=%d" % (M, N, K))
+    W = synth.weights(N, K, config=0, layer=M + 40, tensor=0)
+    x = synth.activations(M, K, config=0, layer=M + 40)
+    ref = oracle.bitlinear(x, W)
+    packed, gamma = gpu_lib.quantize_weights(dev(W), fmt=gpu_lib.PACK_TRIT5)
+    xq, sx = gpu_lib.quantize_acts(dev(x))
+    kernels = [gpu_lib.KERNEL_AUTO, gpu_lib.KERNEL_REFERENCE] + ([gpu_lib.KERNEL_GEMV] if M <= 16 else [])
+    for kern in kernels:
+        acc = gpu_lib.linear(xq, sx, packed, gamma, N, fmt=gpu_lib.PACK_TRIT5, y_dtype=gpu_lib.I32, kernel=kern)
+        assert np.array_equal(acc.cpu().numpy(), ref["acc"]), "kernel %d" % kern
+        y32 = gpu_lib.linear(xq, sx, packed, gamma, N, fmt=gpu_lib.PACK_TRIT5, y_dtype=gpu_lib.F32, kernel=kern)
+        check_y(y32.cpu().numpy(), ref["y"], RTOL_F32)
+        y16 = gpu_lib.linear(xq, sx, packed, gamma, N, fmt=gpu_lib.PACK_TRIT5, y_dtype=gpu_lib.BF16, kernel=kern)
+        check_y(y16.float().cpu().numpy(), ref["y"], RTOL_BF16)
+    if M > 16:
+        with pytest.raises(gpu_lib.BitnetError) as e:
+            gpu_lib.linear(xq, sx, packed, gamma, N, fmt=gpu_lib.PACK_TRIT5, kernel=gpu_lib.KERNEL_GEMV)
+        assert e.value.status == 8
+
+
+def test_trit5_is_rejected_where_unsupported(gpu_lib):
+    say("trit5 limits")
+    W = dev(synth.weights(32, 320, config=0, layer=1))
+    packed, gamma = gpu_lib.quantize_weights(W, fmt=gpu_lib.PACK_TRIT5)
+    x = dev(synth.activations(1, 320, config=0, layer=1))
+    with pytest.raises(gpu_lib.BitnetError) as e:
+        gpu_lib.linear_fused(x, packed, gamma, 32, fmt=gpu_lib.PACK_TRIT5)
+    assert e.value.status == 4
+    xq, sx = gpu_lib.quantize_acts(x)
+    with pytest.raises(gpu_lib.BitnetError) as e:
+        gpu_lib.linear(xq, sx, packed, gamma, 32, fmt=gpu_lib.PACK_TRIT5, kernel=gpu_lib.KERNEL_GEMM)
+    assert e.value.status == 8
 
 
 def test_linear_extreme_accumulators(gpu_lib):
