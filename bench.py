@@ -159,6 +159,40 @@ def large_gemv_leg(torch, B, synth, gen, stream, args):
     return res
 
 
+def format_leg(torch, B, synth, gen, stream, args):
+    """The 5-trits-per-byte format measured against the 2-bit one on the M = 1 product (bitnet_linear on
+    pre-quantized activations), same weights, on the dominant 3B shape and the 70B gate/up shape."""
+    res = {}
+    for (tag, K, N) in (("3b_gate_up", 3200, 17280), ("70b_gate_up", 8192, 57344)):
+        entry = {"K": K, "N": N}
+        x = make_acts(torch, 1, K, gen, 1)
+        xq, sx = B.quantize_acts(x)
+        y = torch.empty((1, N), dtype=torch.bfloat16, device="cuda")
+        for (fname, fmt) in (("2bit", B.PACK_2BIT), ("trit5", B.PACK_TRIT5)):
+            per = B.packed_bytes(N, K, fmt)
+            layers = max(3, int(math.ceil(600e6 / per)))
+            g2 = torch.Generator(device="cuda")
+            g2.manual_seed(1234)
+            packs = []
+            for l in range(layers):
+                W = torch.randn((N, K), device="cuda", generator=g2, dtype=torch.float32) * synth.SIGMA_W
+                packs.append(B.quantize_weights(W, fmt=fmt))
+                del W
+
+            def run():
+                for (p, g) in packs:
+                    B.linear(xq, sx, p, g, N, fmt=fmt, y_dtype=B.BF16, y=y)
+
+            ms, _, _ = time_graph(torch, run, args.warmup, args.steps, stream)
+            us = ms * 1e3 / layers
+            entry[fname] = {"packed_bytes": per, "us_per_launch": round(us, 2), "GB/s": round(per / (us * 1e-6) / 1e9, 1)}
+            del packs
+            torch.cuda.empty_cache()
+        entry["time_ratio_trit5_over_2bit"] = round(entry["trit5"]["us_per_launch"] / entry["2bit"]["us_per_launch"], 3)
+        res[tag] = entry
+    return res
+
+
 def gemm_leg(torch, B, synth, gen, args, M=2048):
     """Prefill: M = 2048 tokens on the 13B-class shapes, bitnet_quantize_acts + bitnet_linear (MFMA kernel)."""
     res = {"M": M, "shapes": {}}
@@ -326,6 +360,7 @@ def main():
         torch.cuda.empty_cache()
         out["gemv_70b_m1"] = large_gemv_leg(torch, B, synth, gen, stream, args)
         out["gemm_m2048"] = gemm_leg(torch, B, synth, gen, args)
+        out["trit5_vs_2bit_m1"] = format_leg(torch, B, synth, gen, stream, args)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg_idx, M)
     print(json.dumps(out))
