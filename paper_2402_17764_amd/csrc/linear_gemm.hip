@@ -175,9 +175,9 @@ __global__ __launch_bounds__(kGemmThreads, 2) void linear_gemm_2bit(
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[fm][fn][v] = 0;
 
-    // The tile's activation rows as a raw buffer: per-lane byte offsets stay fixed, the K step goes into
-    // the scalar offset, and reads past the end of x_q return zero (in the partial last step the columns
-    // past K meet zero codes, whatever they hold).
+    // The tile's activation rows as a raw buffer.  The whole byte offset travels in the vector offset,
+    // the operand the hardware range check is certain to cover, so reads past the end of x_q return
+    // zero (in the partial last step the columns past K meet zero codes, whatever they hold).
     const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<int8_t*>(xtile), 0, (int)min((int64_t)rows_here * K, (int64_t)0x7FFFFFFF), 0x00020000);
     auto copy_x = [&](int step, int stage) {
@@ -185,7 +185,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void linear_gemm_2bit(
 #pragma unroll
         for (int t = 0; t < 8; ++t)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (__attribute__((address_space(3))) void*)(dst_stage + (wave * 32 + t * 4) * 256),
-                                                     16, xoff[t], step * 256, 0, 0);
+                                                     16, xoff[t] + (uint32_t)step * 256u, 0, 0, 0);
     };
     auto load_w = [&](uint4 (&wq)[kGemmFN][2], int step) {
         const uint4* src = packed + (int64_t)step * wstride;

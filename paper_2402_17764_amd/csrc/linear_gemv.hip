@@ -46,6 +46,13 @@ __device__ inline v4i as_v4i(const uint4& u) {
 
 __device__ inline uint32_t quad_word(const uint4& q, int j) { return j == 0 ? q.x : j == 1 ? q.y : j == 2 ? q.z : q.w; }
 
+// Pins the order of memory instructions for kernels that count loads in flight: nothing moves across
+// it, neither in the optimizer nor in the instruction scheduler.
+__device__ inline void issue_fence() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 __device__ inline void store_row4(void* y, OutType yt, int64_t base, int64_t n0, int64_t N, const v4i& s, float scale) {
     const int v[4] = {s.x >> 6, s.y >> 6, s.z >> 6, s.w >> 6};   // drop the decode factor 64 (exact)
     if (yt == OutType::I32) {
@@ -331,42 +338,88 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
 }
 
 // ---------------------------------------------------------------------------------------------------
-// 16 < M <= 64: same stream, kMT token tiles per wave, activations read from global memory
+// 16 < M <= 64: the skinny kernel
 // ---------------------------------------------------------------------------------------------------
-template <int kR, int kMT>
-struct GemvStage {
-    uint4 w[kR];          // one quad per row block
-    uint4 x[kMT][4];      // 64 activation bytes per token tile
-};
-
-template <int kR, int kMT>
-__device__ inline void gemv_mac(const GemvStage<kR, kMT>& st, v4i (&acc)[kR][kMT]) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-#pragma unroll
-        for (int a = 0; a < kR; ++a) {
-            const v4i A = decode_word(quad_word(st.w[a], j));
-#pragma unroll
-            for (int t = 0; t < kMT; ++t)
-                acc[a][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A, as_v4i(st.x[t][j]), acc[a][t], 0, 0, 0);
-        }
-    }
-}
-
-// kR row blocks per workgroup (every wave handles all of them), kMT token tiles of 16, kS waves split K
-template <int kR, int kMT, int kS>
-__global__ __launch_bounds__(kS * kWave) void linear_gemv64_2bit(const int8_t* __restrict__ xq, const float* __restrict__ sx,
-                                                                  const uint4* __restrict__ packed,
-                                                                  const float* __restrict__ gamma, int M, int64_t N, int64_t K,
-                                                                  int Kq, int RB, void* __restrict__ y, OutType yt) {
-    __shared__ v4i fold[kS][kR * kMT][kWave];
+// Between decode and prefill the weights are still streamed once from HBM, but every wave now needs
+// 16 * kMT tokens x 256 bytes of activations for each K step, far more than the 1 KiB of weights a row
+// block contributes.  A workgroup is kS groups of kW waves:
+//   * a group owns a contiguous range of K steps and walks it in lock-step; the x_q rows of a step are
+//     copied global -> LDS once per group with buffer loads (XOR-swizzled 16-byte chunks, read back with
+//     conflict-free ds_read_b128), kLx steps ahead, through a ring of kLx + 1 stages;
+//   * each wave owns kR row blocks, prefetches their quads kD steps ahead in registers and uses one
+//     activation operand read from LDS for all kR of them (LDS bandwidth, not HBM, is the next limit:
+//     16 * kMT / kR KiB of LDS reads per KiB of weights);
+//   * the groups' partial accumulators are folded through LDS in a fixed order at the end.
+// The workgroup covers kW * kR row blocks for all of K, so the host picks kR and kW to make the number
+// of workgroups fit the CUs, and kS * kW * kR * kD KiB of weights are in flight per workgroup.
+//
+// Waiting: LDS-DMA completion is counted by vmcnt together with the weight loads, in issue order.  The
+// prologue issues copies and weight loads in exactly the order of the loop body, so from the first
+// step on the loads younger than this wave's copy for the current step number kSkinnyYounger, and an
+// explicit s_waitcnt with that count retires the copy without draining the prefetch behind it.  The
+// scheduling fences keep the compiler from moving loads across the counted wait; the barrier is the
+// bare instruction because a fence-carrying barrier makes the compiler wait for every LDS-DMA load.
+template <int kMT, int kR, int kW, int kS, int kD, int kLx>
+__global__ __launch_bounds__(kS * kW * kWave) void linear_skinny_2bit(
+        const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
+        const float* __restrict__ gamma, int M, int64_t N, int64_t K, int Kq, int RB, int spg,
+        void* __restrict__ y, OutType yt) {
+#if defined(__HIP_DEVICE_COMPILE__)      // the buffer-resource builtins exist in the device pass only
+    extern __shared__ uint4 smem[];
+    constexpr int kRing = kLx + 1;                     // LDS stages per group
+    constexpr int kStageBytes = kMT * 16 * 256;        // tokens staged per step x 256 columns
+    constexpr int kGroupBytes = kRing * kStageBytes;
+    constexpr int kCopies = kMT * 4;                   // 1 KiB wave-loads per stage (4 token rows each)
+    constexpr int kC = kCopies / kW;                   // ... issued by each wave of the group
+    constexpr int kYounger = kR + (kLx - 1) * (kC + kR);
+    static_assert(kCopies % kW == 0, "every wave issues the same number of copies: no guard, no branch");
+    static_assert(kLx >= 1 && kLx <= kD, "activations are never requested before the weights of their step");
+    static_assert(kYounger < 64, "vmcnt is six bits");
+    static_assert((kS - 1) * kW * kR * kMT * 1024 <= kS * kGroupBytes, "the fold reuses the activation ring");
+    char* lds = reinterpret_cast<char*>(smem);
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
-    const int r = lane & 15;
-    const int g = lane >> 4;
-    const int rb0 = blockIdx.x * kR;
-    const int full_steps = (int)(K >> 8);            // steps whose 256 columns all exist
+    const int ks = wave / kW, wv = wave - ks * kW;     // K group, wave within the group
+    const int r = lane & 15, g = lane >> 4;
+    const int steps = (Kq + 3) >> 2;
+    const int tail_quads = 16 * (Kq - 4 * (steps - 1));
+    const int s_begin = ks * spg;                                      // this group's steps: s_begin + [0, n_here)
+    const int n_here = max(0, min(spg, steps - s_begin));
+    const int rbw = (blockIdx.x * kW + wv) * kR;
+    const int64_t wstride = (int64_t)RB * 64;
+    char* glds = lds + ks * kGroupBytes;
+
+    // activation copy: lane i of a load fills slot i = (row i >> 4 of a group of four, chunk slot i & 15);
+    // the chunk stored in slot c' of token m is c' ^ (m & 15).  The whole byte offset travels in the vector
+    // offset, which the hardware range check covers: reads past the end of x_q return zero.
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<int8_t*>(xq), 0, (int)min((int64_t)M * K, (int64_t)0x7FFFFFFF), 0x00020000);
+    uint32_t xoff[kC];
+#pragma unroll
+    for (int t = 0; t < kC; ++t) {
+        const int row = (wv + t * kW) * 4 + (lane >> 4);
+        xoff[t] = (uint32_t)min(row, M - 1) * (uint32_t)K + (uint32_t)(((lane & 15) ^ (row & 15)) << 4) +
+                  (uint32_t)s_begin * 256u;
+    }
+    auto copy_x = [&](int i, int stage) {                              // local step i of this group
+#pragma unroll
+        for (int t = 0; t < kC; ++t)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                xrsrc, (__attribute__((address_space(3))) void*)(glds + stage * kStageBytes + (wv + t * kW) * 1024),
+                16, xoff[t] + (uint32_t)i * 256u, 0, 0, 0);
+    };
+
+    int rbc[kR];
+#pragma unroll
+    for (int a = 0; a < kR; ++a) rbc[a] = min(rbw + a, RB - 1);
+    auto load_w = [&](uint4 (&w)[kR], int i) {
+        const int sl = min(s_begin + i, steps - 1);                    // past the end: redirected, masked below
+        const int cq = sl == steps - 1 ? tail_quads : 64;
+        const int ln = min(lane, cq - 1);
+#pragma unroll
+        for (int a = 0; a < kR; ++a) w[a] = packed[(int64_t)sl * wstride + (int64_t)rbc[a] * cq + ln];
+    };
 
     v4i acc[kR][kMT];
 #pragma unroll
@@ -374,96 +427,96 @@ __global__ __launch_bounds__(kS * kWave) void linear_gemv64_2bit(const int8_t* _
 #pragma unroll
         for (int t = 0; t < kMT; ++t) acc[a][t] = (v4i){0, 0, 0, 0};
 
-    // per-lane base pointers; row blocks and tokens beyond the matrix are clamped to the last valid one
-    const int64_t wstride = (int64_t)RB * 64;
-    const uint4* wp[kR];
+    auto compute = [&](const uint4 (&w)[kR], int i, int stage) {
+        const int cq = s_begin + i == steps - 1 ? tail_quads : 64;
+        const uint32_t keep = (i < n_here && lane < cq) ? 0xFFFFFFFFu : 0u;   // padded steps contribute nothing
+        const char* src = glds + stage * kStageBytes + r * 256;
 #pragma unroll
-    for (int a = 0; a < kR; ++a) wp[a] = packed + (int64_t)min(rb0 + a, RB - 1) * 64 + lane;
-    const uint4* xp[kMT];
+        for (int j = 0; j < 4; ++j) {
+            v4i A[kR];
 #pragma unroll
-    for (int t = 0; t < kMT; ++t) {
-        const int m = min(16 * t + r, M - 1);
-        xp[t] = reinterpret_cast<const uint4*>(xq + (int64_t)m * K + 64 * g);   // + 16 uint4 per step
-    }
-
-    auto load = [&](GemvStage<kR, kMT>& st, int step) {
+            for (int a = 0; a < kR; ++a) A[a] = decode_word(quad_word(w[a], j) & keep);
+            const int slot = ((4 * g + j) ^ r) << 4;
 #pragma unroll
-        for (int a = 0; a < kR; ++a) st.w[a] = wp[a][(int64_t)step * wstride];
+            for (int t = 0; t < kMT; ++t) {
+                const v4i X = *reinterpret_cast<const v4i*>(src + t * 4096 + slot);
 #pragma unroll
-        for (int t = 0; t < kMT; ++t)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) st.x[t][j] = xp[t][(int64_t)step * 16 + j];
+                for (int a = 0; a < kR; ++a)
+                    acc[a][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A[a], X, acc[a][t], 0, 0, 0);
+            }
+        }
     };
 
-    // software pipeline over this wave's whole steps: wave, wave + kS, ...
-    const int mine = full_steps > wave ? (full_steps - wave + kS - 1) / kS : 0;
-    if (mine > 0) {
-        GemvStage<kR, kMT> s0, s1;
-        load(s0, wave);
-        int i = 0;
-        for (; i + 2 <= mine - 1; i += 2) {
-            load(s1, wave + (i + 1) * kS);
-            __builtin_amdgcn_sched_barrier(0);
-            gemv_mac<kR, kMT>(s0, acc);
-            __builtin_amdgcn_sched_barrier(0);
-            load(s0, wave + (i + 2) * kS);
-            __builtin_amdgcn_sched_barrier(0);
-            gemv_mac<kR, kMT>(s1, acc);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if (i + 1 <= mine - 1) {
-            load(s1, wave + (i + 1) * kS);
-            gemv_mac<kR, kMT>(s0, acc);
-            gemv_mac<kR, kMT>(s1, acc);
-        } else {
-            gemv_mac<kR, kMT>(s0, acc);
-        }
+    // Prologue: the issue pattern of steps -kD ... -1 of the loop below.  Where the loop would copy a
+    // step before the first, step 0 is copied (again) so that the count of loads in flight is the same.
+    uint4 wst[kD][kR];
+#pragma unroll
+    for (int p = 0; p < kD; ++p) {
+        constexpr int kLead = kD - kLx;
+        const int xs = p >= kLead ? p - kLead : 0;
+        copy_x(xs, xs % kRing);
+        load_w(wst[p], p);
+        issue_fence();
     }
 
-    // columns past the last whole step (K % 256 != 0): one guarded step, taken by one wave
-    if ((K & 255) != 0 && wave == full_steps % kS) {
-        const int kq = 4 * full_steps + g;
-        const int nq = Kq - 4 * full_steps;
-        const int64_t kbase = (int64_t)kq * 64;
-        const uint4 zero4 = make_uint4(0, 0, 0, 0);
-        GemvStage<kR, kMT> st;
+    // Steps are walked in groups of kD so that the register stages are indexed statically; the count is
+    // padded to a whole group with steps whose weights are masked to zero, so the body has no guards.
+    const int padded = (spg + kD - 1) / kD * kD;                      // >= kD: the loop runs at least once
+    int i0 = 0;
+    do {
 #pragma unroll
-        for (int a = 0; a < kR; ++a) {
-            st.w[a] = zero4;
-            if (kq < Kq) st.w[a] = packed[(int64_t)full_steps * wstride + (int64_t)min(rb0 + a, RB - 1) * 16 * nq + lane];
+        for (int d = 0; d < kD; ++d) {
+            const int i = i0 + d;
+            // loads issued after this wave's copy for step i: kR weight loads, then for each of the next
+            // kLx - 1 steps kC copies and kR weight loads
+            // (imm: vmcnt[3:0] | expcnt 7 << 4 | lgkmcnt 15 << 8 | vmcnt[5:4] << 14)
+            issue_fence();
+            __builtin_amdgcn_s_waitcnt((kYounger & 15) | 0x0F70 | ((kYounger >> 4) << 14));
+            __builtin_amdgcn_s_barrier();                              // stage i is complete, stage i - 1 is free
+            issue_fence();
+            copy_x(i + kLx, (i + kLx) % kRing);
+            compute(wst[d], i, i % kRing);
+            load_w(wst[d], i + kD);                                    // after the last use: reloaded in place
         }
-#pragma unroll
-        for (int t = 0; t < kMT; ++t)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                st.x[t][j] = zero4;
-                if (kbase + 16 * j + 16 <= K) st.x[t][j] = xp[t][(int64_t)full_steps * 16 + j];
-            }
-        gemv_mac<kR, kMT>(st, acc);
-    }
+        i0 += kD;
+    } while (i0 < padded);
+    issue_fence();
 
-    // fold the K slices of the kS waves
+    if constexpr (kS > 1) {
+        // fold the K groups: groups 1 ... kS - 1 park their accumulators in LDS, group 0 adds them in order
+        __builtin_amdgcn_s_waitcnt(0);                                 // copies past the end have landed
+        __syncthreads();
+        v4i* fold = reinterpret_cast<v4i*>(lds);
+        if (ks > 0) {
 #pragma unroll
-    for (int a = 0; a < kR; ++a)
+            for (int a = 0; a < kR; ++a)
 #pragma unroll
-        for (int t = 0; t < kMT; ++t) fold[wave][a * kMT + t][lane] = acc[a][t];
-    __syncthreads();
+                for (int t = 0; t < kMT; ++t)
+                    fold[((((ks - 1) * kW + wv) * kR + a) * kMT + t) * kWave + lane] = acc[a][t];
+        }
+        __syncthreads();
+        if (ks > 0) return;
+        for (int q = 0; q < kS - 1; ++q)
+#pragma unroll
+            for (int a = 0; a < kR; ++a)
+#pragma unroll
+                for (int t = 0; t < kMT; ++t)
+                    acc[a][t] += fold[(((q * kW + wv) * kR + a) * kMT + t) * kWave + lane];
+    }
 
     const float gm = gamma[0];
-    for (int tile = wave; tile < kR * kMT; tile += kS) {
-        v4i s = fold[0][tile][lane];
 #pragma unroll
-        for (int w = 1; w < kS; ++w) {
-            const v4i o = fold[w][tile][lane];
-            s.x += o.x; s.y += o.y; s.z += o.z; s.w += o.w;
-        }
-        const int a = tile / kMT, t = tile % kMT;
-        const int m = 16 * t + r;
-        const int64_t n0 = (int64_t)(rb0 + a) * 16 + 4 * g;
-        if (m >= M || n0 >= N) continue;
+    for (int t = 0; t < kMT; ++t) {
+        const int m = 16 * t + r;                                      // MFMA output column = token
+        if (m >= M) continue;
         const float scale = yt == OutType::I32 ? 0.0f : (gm * sx[m]) / kQb;
-        store_row4(y, yt, (int64_t)m * N + n0, n0, N, s, scale);
+#pragma unroll
+        for (int a = 0; a < kR; ++a) {
+            const int64_t n0 = (int64_t)(rbw + a) * 16 + 4 * g;
+            if (n0 < N) store_row4(y, yt, (int64_t)m * N + n0, n0, N, acc[a][t], scale);
+        }
     }
+#endif
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -471,7 +524,7 @@ __global__ __launch_bounds__(kS * kWave) void linear_gemv64_2bit(const int8_t* _
 // ---------------------------------------------------------------------------------------------------
 bool gemv_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
     (void)N;
-    return M >= 1 && M <= 64 && K % 16 == 0 && reinterpret_cast<uintptr_t>(xq) % 16 == 0;
+    return M >= 1 && M <= 64 && K % 16 == 0 && reinterpret_cast<uintptr_t>(xq) % 16 == 0 && M * K < ((int64_t)1 << 31);
 }
 
 constexpr size_t kGemvLdsBudget = 65536;
@@ -503,14 +556,29 @@ static void launch16(int xmode, const void* x, const float* sx, const void* pack
 #undef GO
 }
 
-template <int kR, int kMT, int kS>
-static void launch64(const int8_t* xq, const float* sx, const void* packed, const float* gamma, int64_t M,
-                     int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
+template <int kMT, int kR, int kW, int kS, int kD, int kLx>
+static hipError_t launch_skinny(const int8_t* xq, const float* sx, const void* packed, const float* gamma, int64_t M,
+                                int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
+    constexpr size_t lds = (size_t)kS * (kLx + 1) * kMT * 16 * 256;
+    static_assert(lds <= 160 * 1024, "activation rings must fit the LDS of a CU");
+    static_assert(kS * kW <= 16, "at most 1024 threads per workgroup");
+    auto* kern = linear_skinny_2bit<kMT, kR, kW, kS, kD, kLx>;
+    if (lds > 65536) {
+        static bool raised = false;                    // the default dynamic-LDS limit is 64 KiB per kernel
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+    }
     const int Kq = (int)ceil_div(K, kColsPerQuad);
     const int RB = (int)ceil_div(N, kRowsPerBlock);
-    dim3 grid((unsigned)ceil_div(RB, kR));
-    hipLaunchKernelGGL((linear_gemv64_2bit<kR, kMT, kS>), grid, dim3(kS * kWave), 0, stream, xq, sx,
-                       static_cast<const uint4*>(packed), gamma, (int)M, N, K, Kq, RB, y, yt);
+    const int spg = (int)ceil_div(ceil_div(K, 256), kS);
+    dim3 grid((unsigned)ceil_div(RB, kW * kR));
+    hipLaunchKernelGGL(kern, grid, dim3(kS * kW * kWave), lds, stream, xq, sx, static_cast<const uint4*>(packed), gamma,
+                       (int)M, N, K, Kq, RB, spg, y, yt);
+    return hipGetLastError();
 }
 
 // Shape heuristics from sweeps on MI355X (M = 1, HIP-graph replay over many distinct weight buffers):
@@ -552,10 +620,19 @@ hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void
                                    OutType yt, hipStream_t stream) {
     if (M <= 16) {
         dispatch16(-1, xq, sx, packed, gamma, M, N, K, y, yt, stream);
-    } else if (M <= 32) {
-        launch64<4, 2, 4>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
     } else {
-        launch64<2, 4, 4>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
+        // Sweeps on MI355X over the 7B layer shapes at M = 32 and 64: the workgroups should about cover
+        // the 256 CUs, so the row blocks per workgroup (kW * kR) follow N; with few row blocks each wave
+        // takes its own quarter of K instead.  Two steps of prefetch were best throughout.
+        const int64_t RB = ceil_div(N, kRowsPerBlock);
+        if (M <= 32) {
+            if (RB >= 1280)     return launch_skinny<2, 3, 2, 2, 2, 2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
+            else if (RB >= 512) return launch_skinny<2, 2, 2, 4, 2, 2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
+            else                return launch_skinny<2, 1, 1, 4, 2, 2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
+        }
+        if (RB >= 1280)     return launch_skinny<4, 3, 2, 2, 2, 2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
+        else if (RB >= 512) return launch_skinny<4, 1, 4, 2, 2, 2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
+        else                return launch_skinny<4, 1, 1, 4, 2, 1>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
     }
     return hipGetLastError();
 }

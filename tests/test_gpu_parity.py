@@ -218,7 +218,12 @@ GEMV_SHAPES = [(1, 4096, 1536), (16, 4096, 1536), (1, 16, 64), (1, 17, 16), (3, 
                # one shape per branch of the kernel-selection heuristic (row blocks x K steps)
                (2, 32800, 528), (3, 16400, 4112), (1, 16400, 272), (5, 6416, 16400), (4, 6416, 1040),
                (2, 100, 6160), (16, 1000, 8192), (1, 600, 16400), (1, 100, 11008), (8, 300, 2048), (6, 16400, 512),
-               (12, 16400, 8192)]
+               (12, 16400, 8192),
+               # the skinny kernel: 16 < M <= 64, ragged token tiles, every branch of its selection (row blocks
+               # below 512, below 1280, above; up to 32 tokens and above), K tails, K steps from 1 to 17 and
+               # fewer steps than K groups
+               (20, 16400, 272), (48, 300, 4112), (64, 100, 1040), (40, 1000, 528), (33, 260, 2048), (56, 16400, 512),
+               (24, 20488, 272), (50, 20500, 528), (35, 48, 64), (18, 20, 16), (64, 8200, 4096)]
 
 
 @pytest.mark.parametrize("M,N,K", GEMV_SHAPES)
