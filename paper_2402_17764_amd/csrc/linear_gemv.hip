@@ -594,14 +594,8 @@ static void dispatch16(int xmode, const void* x, const float* sx, const void* pa
     const int64_t RB = ceil_div(N, kRowsPerBlock);
     const int64_t steps = ceil_div(K, 256);
     const bool fused = xmode >= 0;
-    const bool fits_lds = kGemvLdsHeader * sizeof(uint4) + gemv16_x_lds_bytes(M, K) <= kGemvLdsBudget;
 #define GEMV16(R_, S_, W_, D_, X_) launch16<R_, S_, W_, D_>(fused ? xmode : (X_), x, sx, packed, gamma, M, N, K, y, yt, stream)
-    if (M > 4 && !fused) {
-        // x traffic grows with M: stage x_q in LDS when it fits, else amortize it over four row blocks
-        if (fits_lds && RB < 2048)  GEMV16(1, 4, 1, 4, kXLds);
-        else if (RB >= 1024)        GEMV16(4, 1, 4, 2, kXGlobal);
-        else                        GEMV16(4, 2, 2, 2, kXGlobal);
-    } else if (RB >= 2048) {
+    if (RB >= 2048) {
         if (fused) GEMV16(4, 1, 4, 2, kXGlobal); else GEMV16(4, 1, 4, 3, kXGlobal);
     } else if (steps >= 64) {
         if (fused) GEMV16(1, 8, 2, 2, kXGlobal); else GEMV16(2, 4, 1, 4, kXGlobal);
@@ -618,23 +612,32 @@ static void dispatch16(int xmode, const void* x, const float* sx, const void* pa
 hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void* packed,
                                    const float* gamma, int64_t M, int64_t N, int64_t K, void* y,
                                    OutType yt, hipStream_t stream) {
-    if (M <= 16) {
+    if (M <= 4) {
         dispatch16(-1, xq, sx, packed, gamma, M, N, K, y, yt, stream);
-    } else {
-        // Sweeps on MI355X over the 7B layer shapes at M = 32 and 64: the workgroups should about cover
-        // the 256 CUs, so the row blocks per workgroup (kW * kR) follow N; with few row blocks each wave
-        // takes its own quarter of K instead.  Two steps of prefetch were best throughout.
-        const int64_t RB = ceil_div(N, kRowsPerBlock);
-        if (M <= 32) {
-            if (RB >= 1280)     return launch_skinny<2, 3, 2, 2, 2, 2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
-            else if (RB >= 512) return launch_skinny<2, 2, 2, 4, 2, 2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
-            else                return launch_skinny<2, 1, 1, 4, 2, 2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
-        }
-        if (RB >= 1280)     return launch_skinny<4, 3, 2, 2, 2, 2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
-        else if (RB >= 512) return launch_skinny<4, 1, 4, 2, 2, 2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
-        else                return launch_skinny<4, 1, 1, 4, 2, 1>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
+        return hipGetLastError();
     }
-    return hipGetLastError();
+    // More than four tokens: the activations of a step outweigh the weights a wave reads with them, so they
+    // are staged once per group of waves (skinny kernel), 16 * kMT >= M tokens per step.  From sweeps on
+    // MI355X over 3B/7B/70B layer shapes: the workgroups should about cover the 256 CUs, so the row blocks
+    // per workgroup (kW * kR) follow N; with few row blocks the waves split K further instead.  Two steps
+    // of prefetch were best throughout.
+    const int64_t RB = ceil_div(N, kRowsPerBlock);
+#define SKINNY(...) return launch_skinny<__VA_ARGS__>(xq, sx, packed, gamma, M, N, K, y, yt, stream)
+    if (M <= 16) {
+        if (RB >= 2048)      SKINNY(1, 4, 4, 2, 2, 2);
+        else if (RB >= 1024) SKINNY(1, 3, 2, 4, 2, 2);
+        else if (RB >= 512)  SKINNY(1, 3, 1, 4, 2, 2);
+        else                 SKINNY(1, 1, 1, 8, 2, 2);
+    } else if (M <= 32) {
+        if (RB >= 1280)      SKINNY(2, 3, 2, 2, 2, 2);
+        else if (RB >= 512)  SKINNY(2, 2, 2, 4, 2, 2);
+        else                 SKINNY(2, 1, 1, 4, 2, 2);
+    } else {
+        if (RB >= 1280)      SKINNY(4, 3, 2, 2, 2, 2);
+        else if (RB >= 512)  SKINNY(4, 1, 4, 2, 2, 2);
+        else                 SKINNY(4, 1, 1, 4, 2, 1);
+    }
+#undef SKINNY
 }
 
 bool gemv_fused_supports(int64_t M, int64_t N, int64_t K, const void* x) {

@@ -223,7 +223,9 @@ GEMV_SHAPES = [(1, 4096, 1536), (16, 4096, 1536), (1, 16, 64), (1, 17, 16), (3, 
                # below 512, below 1280, above; up to 32 tokens and above), K tails, K steps from 1 to 17 and
                # fewer steps than K groups
                (20, 16400, 272), (48, 300, 4112), (64, 100, 1040), (40, 1000, 528), (33, 260, 2048), (56, 16400, 512),
-               (24, 20488, 272), (50, 20500, 528), (35, 48, 64), (18, 20, 16), (64, 8200, 4096)]
+               (24, 20488, 272), (50, 20500, 528), (35, 48, 64), (18, 20, 16), (64, 8200, 4096),
+               # ... and its single-token-tile form for 4 < M <= 16, one shape per row-block class
+               (9, 9000, 528), (10, 32800, 272), (5, 40, 16), (13, 16400, 1040)]
 
 
 @pytest.mark.parametrize("M,N,K", GEMV_SHAPES)
