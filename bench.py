@@ -193,6 +193,41 @@ def format_leg(torch, B, synth, gen, stream, args):
     return res
 
 
+def batched_decode_leg(torch, B, synth, gen, stream, args):
+    """The transition between decode and prefill: M = 1 ... 64 tokens on the 7B-class shapes, bitnet_linear on
+    pre-quantized activations, each shape replayed over enough distinct layers to exceed the memory-side
+    cache.  Both rooflines are reported because M = 64 sits near the ridge between them."""
+    res = {}
+    for (name, K, N) in synth.CONFIGS[2]["shapes"]:
+        per = N * K // 4
+        layers = max(3, int(math.ceil(550e6 / per)))
+        packs = []
+        for l in range(layers):
+            W = torch.randn((N, K), device="cuda", generator=gen, dtype=torch.float32) * synth.SIGMA_W
+            packs.append(B.quantize_weights(W))
+            del W
+        entry = {"K": K, "N": N, "layers": layers}
+        for M in (1, 8, 16, 32, 64):
+            x = make_acts(torch, M, K, gen, 2)
+            xq, sx = B.quantize_acts(x)
+            y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+
+            def run():
+                for (p, g) in packs:
+                    B.linear(xq, sx, p, g, N, y_dtype=B.BF16, y=y)
+
+            ms, _, graph = time_graph(torch, run, max(2, args.warmup // 5), max(5, args.steps // 5), stream)
+            us = ms * 1e3 / layers
+            entry["M=%d" % M] = {"us_per_launch": round(us, 2),
+                                 "GB/s": round(gemv_bytes(M, N, K) / (us * 1e-6) / 1e9, 1),
+                                 "TOPS": round(2.0 * M * N * K / us * 1e-6, 1)}
+            del graph
+        res[name] = entry
+        del packs
+        torch.cuda.empty_cache()
+    return res
+
+
 def gemm_leg(torch, B, synth, gen, args, M=2048):
     """Prefill: M = 2048 tokens on the 13B-class shapes, bitnet_quantize_acts + bitnet_linear (MFMA kernel)."""
     res = {"M": M, "shapes": {}}
@@ -359,6 +394,7 @@ def main():
         del packed, acts
         torch.cuda.empty_cache()
         out["gemv_70b_m1"] = large_gemv_leg(torch, B, synth, gen, stream, args)
+        out["batched_decode_7b"] = batched_decode_leg(torch, B, synth, gen, stream, args)
         out["gemm_m2048"] = gemm_leg(torch, B, synth, gen, args)
         out["trit5_vs_2bit_m1"] = format_leg(torch, B, synth, gen, stream, args)
     if not args.no_cpu_baseline:

@@ -74,7 +74,7 @@ __device__ inline void store_row4(void* y, OutType yt, int64_t base, int64_t n0,
 }
 
 // ---------------------------------------------------------------------------------------------------
-// M <= 16
+// M <= 16 (the product on pre-quantized activations uses it up to M = 4, the fused entry point up to 16)
 // ---------------------------------------------------------------------------------------------------
 // Where the activation operand comes from.
 enum XMode : int {
@@ -338,11 +338,11 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
 }
 
 // ---------------------------------------------------------------------------------------------------
-// 16 < M <= 64: the skinny kernel
+// 4 < M <= 64: the skinny kernel
 // ---------------------------------------------------------------------------------------------------
 // Between decode and prefill the weights are still streamed once from HBM, but every wave now needs
-// 16 * kMT tokens x 256 bytes of activations for each K step, far more than the 1 KiB of weights a row
-// block contributes.  A workgroup is kS groups of kW waves:
+// 16 * kMT tokens x 256 bytes of activations for each K step (kMT = 1, 2 or 4 tiles of 16 tokens), more
+// than the 1 KiB of weights a row block contributes.  A workgroup is kS groups of kW waves:
 //   * a group owns a contiguous range of K steps and walks it in lock-step; the x_q rows of a step are
 //     copied global -> LDS once per group with buffer loads (XOR-swizzled 16-byte chunks, read back with
 //     conflict-free ds_read_b128), kLx steps ahead, through a ring of kLx + 1 stages;
