@@ -10,7 +10,7 @@ launch per product, or bitnet_quantize_acts + bitnet_linear with --unfused.  The
 once into a HIP graph and replayed, the way a decode loop would run it.  Weight quantization +
 packing (Eq. 1-3) happens once per layer before the timed region, as it does for inference, and is
 timed separately (`weight_quant`).  The prefill GEMM (M = 2048, 13B-class shapes) is timed as its
-own leg (`gemm_m2048`).  Every input is seeded and synthetic (see paper_2402_17764_amd/synth.py for the
+own leg (`gemm_m2048`), batched decode (M = 1 ... 64, 7B-class shapes) as `batched_decode_7b`.  Every input is seeded and synthetic (see paper_2402_17764_amd/synth.py for the
 recipe); big tensors are drawn on the device with the same distributions.
 
 Prints ONE JSON line.
@@ -394,8 +394,8 @@ def main():
         del packed, acts
         torch.cuda.empty_cache()
         out["gemv_70b_m1"] = large_gemv_leg(torch, B, synth, gen, stream, args)
-        out["batched_decode_7b"] = batched_decode_leg(torch, B, synth, gen, stream, args)
         out["gemm_m2048"] = gemm_leg(torch, B, synth, gen, args)
+        out["batched_decode_7b"] = batched_decode_leg(torch, B, synth, gen, stream, args)
         out["trit5_vs_2bit_m1"] = format_leg(torch, B, synth, gen, stream, args)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg_idx, M)

@@ -35,13 +35,14 @@ namespace bitnet {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int kGemmBM = 128;                   // tokens per workgroup tile
+// tokens per workgroup tile: kFM fragments of 32; 4 (128 tokens) is the default, 3 (96 tokens) exists for shapes
+// whose 128-token tiles would leave many of the 512 workgroup slots (256 CUs x 2) empty
 constexpr int kGemmBN = 256;                   // weight rows per workgroup tile
 constexpr int kGemmThreads = 256;
 constexpr int kGemmFN = 2;                     // 32-row weight fragments per wave (four waves side by side along the weight rows)
-constexpr int kGemmStageBytes = kGemmBM * 256; // one K step of activations
-constexpr int kGemmScaleOffset = 2 * kGemmStageBytes;          // float scale[256] behind the two stages
-constexpr int kGemmLdsBytes = kGemmScaleOffset + kGemmBM * 4;
+constexpr int gemm_stage_bytes(int fm) { return fm * 32 * 256; }            // one K step of activations
+constexpr int gemm_scale_offset(int fm) { return 2 * gemm_stage_bytes(fm); } // float scale[32 * fm] behind the two stages
+constexpr int gemm_lds_bytes(int fm) { return gemm_scale_offset(fm) + fm * 32 * 4; }
 constexpr int kGemmPitch32 = 64 * 4 + 32;      // epilogue row pitch, 4-byte outputs: rows r and r+4 in different bank halves
 constexpr int kGemmPitch16 = 64 * 2 + 32;      // same for bf16 outputs
 
@@ -62,25 +63,25 @@ struct GemmOutCtx {
 // A lane holds, per 32 x 32 fragment, 16 tokens (8 (v >> 2) + 4 (lane >> 5) + (v & 3)) of weight row
 // (lane & 31).  Each wave stages one fragment row (32 tokens x 64 weight rows) in its own LDS region,
 // then its lanes read 16-byte pieces along the token rows and store them.
-template <OutType kOut>
-__device__ inline void gemm_epilogue(v16i (&acc)[4][kGemmFN], const GemmOutCtx& c) {
+template <OutType kOut, int kFM>
+__device__ inline void gemm_epilogue(v16i (&acc)[kFM][kGemmFN], const GemmOutCtx& c) {
     constexpr bool is16 = kOut == OutType::BF16;
     constexpr int esz = is16 ? 2 : 4;
     constexpr int pitch = is16 ? kGemmPitch16 : kGemmPitch32;
     constexpr int lanes_per_row = 64 * esz / 16;                    // 8 or 16
     constexpr int rows_per_pass = 64 / lanes_per_row;               // 8 or 4
     const int am = c.lane & 31, kg = c.lane >> 5;
-    const int wm = 0, wn = c.wave;
+    const int wn = c.wave;
     char* stage_out = c.lds + c.wave * (32 * kGemmPitch32);
     const int64_t n_wave = (int64_t)c.bn * kGemmBN + wn * 64;
     const int piece = c.lane % lanes_per_row;
     const int64_t n = n_wave + piece * (16 / esz);
 #pragma unroll
-    for (int fm = 0; fm < 4; ++fm) {
+    for (int fm = 0; fm < kFM; ++fm) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int rl = 8 * (v >> 2) + 4 * kg + (v & 3);
-            const float scale = kOut == OutType::I32 ? 0.0f : c.scale_lds[wm * 128 + fm * 32 + rl];
+            const float scale = kOut == OutType::I32 ? 0.0f : c.scale_lds[fm * 32 + rl];
 #pragma unroll
             for (int fn = 0; fn < kGemmFN; ++fn) {
                 const int a = acc[fm][fn][v] >> 6;                  // drop the decode factor 64 (exact)
@@ -94,7 +95,7 @@ __device__ inline void gemm_epilogue(v16i (&acc)[4][kGemmFN], const GemmOutCtx& 
 #pragma unroll
         for (int r0 = 0; r0 < 32; r0 += rows_per_pass) {
             const int rl = r0 + c.lane / lanes_per_row;
-            const int m = c.bm * kGemmBM + wm * 128 + fm * 32 + rl;
+            const int m = c.bm * (32 * kFM) + fm * 32 + rl;
             const uint4 val = *reinterpret_cast<const uint4*>(stage_out + rl * pitch + piece * 16);
             if (m < c.M && n < c.N) {
                 char* dst = static_cast<char*>(c.y) + ((int64_t)m * c.N + n) * esz;
@@ -119,17 +120,22 @@ __device__ inline void gemm_epilogue(v16i (&acc)[4][kGemmFN], const GemmOutCtx& 
     }
 }
 
+template <int kFM>
 __global__ __launch_bounds__(kGemmThreads, 2) void linear_gemm_2bit(
         const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
         const float* __restrict__ gamma, int M, int64_t N, int64_t K, int Kq, int RB, int tiles_m,
         void* __restrict__ y, OutType yt, int vec_store) {
+#if defined(__HIP_DEVICE_COMPILE__)      // the buffer-resource builtins exist in the device pass only
     extern __shared__ uint4 smem[];
+    constexpr int kGemmBM = 32 * kFM;
+    constexpr int kGemmStageBytes = gemm_stage_bytes(kFM);
+    constexpr int kCopies = 2 * kFM;                // 1 KiB wave-loads (4 token rows) per wave and stage
     char* lds = reinterpret_cast<char*>(smem);
-    float* scale_lds = reinterpret_cast<float*>(lds + kGemmScaleOffset);
+    float* scale_lds = reinterpret_cast<float*>(lds + gemm_scale_offset(kFM));
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int wm = 0, wn = wave;
+    const int wn = wave;
     const int bm = blockIdx.x % tiles_m;            // token tile varies fastest (see header)
     const int bn = blockIdx.x / tiles_m;
     const int steps = (Kq + 3) >> 2;
@@ -143,21 +149,21 @@ __global__ __launch_bounds__(kGemmThreads, 2) void linear_gemm_2bit(
         scale_lds[threadIdx.x] = (gamma[0] * sx[m]) / kQb;
     }
 
-    // ---- A operand, global -> LDS: this wave copies rows 32*wave .. +31 of the tile, 4 rows per load.
+    // ---- A operand, global -> LDS: this wave copies rows 8*kFM*wave .. +8*kFM-1 of the tile, 4 rows per load.
     // Lane i of a load writes LDS slot i: row (i >> 4) of the group, chunk slot (i & 15); the chunk that
     // belongs in slot c' of row m is c' ^ (m & 15).  Offsets are relative to the tile's first row.
     const int cp_row = lane >> 4, cp_slot = lane & 15;
     const int8_t* xtile = xq + (int64_t)bm * kGemmBM * K;
     const int rows_here = min(kGemmBM, M - bm * kGemmBM);           // rows past M: clamped, never stored
-    uint32_t xoff[8];
+    uint32_t xoff[kCopies];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-        const int row = wave * 32 + t * 4 + cp_row;
+    for (int t = 0; t < kCopies; ++t) {
+        const int row = wave * (4 * kCopies) + t * 4 + cp_row;
         xoff[t] = (uint32_t)min(row, rows_here - 1) * (uint32_t)K + (uint32_t)((cp_slot ^ (row & 15)) << 4);
     }
     // ---- A operand, LDS -> registers
     const int am = lane & 31, kg = lane >> 5;
-    const int a_row_base = (wm * 128 + am) * 256;                    // + fm * 8192
+    const int a_row_base = am * 256;                                 // + fm * 8192
     // ---- B operand: fragment fn covers row blocks 2*fn, 2*fn+1 of this wave's 4
     const int brow = lane & 15, bsel = (lane >> 4) & 1;
     uint32_t woff[kGemmFN][2];                                      // quad offsets inside a whole step
@@ -167,9 +173,9 @@ __global__ __launch_bounds__(kGemmThreads, 2) void linear_gemm_2bit(
         for (int h = 0; h < 2; ++h)
             woff[fn][h] = (uint32_t)min(bn * 16 + wn * 4 + fn * 2 + bsel, RB - 1) * 64u + (uint32_t)((kg + 2 * h) * 16 + brow);
 
-    v16i acc[4][kGemmFN];
+    v16i acc[kFM][kGemmFN];
 #pragma unroll
-    for (int fm = 0; fm < 4; ++fm)
+    for (int fm = 0; fm < kFM; ++fm)
 #pragma unroll
         for (int fn = 0; fn < kGemmFN; ++fn)
 #pragma unroll
@@ -183,8 +189,8 @@ __global__ __launch_bounds__(kGemmThreads, 2) void linear_gemm_2bit(
     auto copy_x = [&](int step, int stage) {
         char* dst_stage = lds + stage * kGemmStageBytes;
 #pragma unroll
-        for (int t = 0; t < 8; ++t)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (__attribute__((address_space(3))) void*)(dst_stage + (wave * 32 + t * 4) * 256),
+        for (int t = 0; t < kCopies; ++t)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (__attribute__((address_space(3))) void*)(dst_stage + (wave * (4 * kCopies) + t * 4) * 256),
                                                      16, xoff[t] + (uint32_t)step * 256u, 0, 0, 0);
     };
     auto load_w = [&](uint4 (&wq)[kGemmFN][2], int step) {
@@ -212,11 +218,11 @@ __global__ __launch_bounds__(kGemmThreads, 2) void linear_gemm_2bit(
     auto compute = [&](const uint4 (&wq)[kGemmFN][2], int stage) {
         const char* src = lds + stage * kGemmStageBytes + a_row_base;
         const int sw = am & 15;
-        v4i a[2][4], b[2][kGemmFN];
-        auto read_a = [&](v4i (&dst)[4], int t) {
+        v4i a[2][kFM], b[2][kGemmFN];
+        auto read_a = [&](v4i (&dst)[kFM], int t) {
             const int chunk = 8 * (t >> 2) + 4 * kg + (t & 3);
 #pragma unroll
-            for (int fm = 0; fm < 4; ++fm)
+            for (int fm = 0; fm < kFM; ++fm)
                 dst[fm] = *reinterpret_cast<const v4i*>(src + fm * 8192 + ((chunk ^ sw) << 4));
         };
         auto word_of = [&](int fn, int t) { return gemm_quad_word(wq[fn][t >> 2], t & 3); };
@@ -232,11 +238,16 @@ __global__ __launch_bounds__(kGemmThreads, 2) void linear_gemm_2bit(
             const int cur = t & 1, nxt = cur ^ 1;
             __builtin_amdgcn_sched_barrier(0);          // slices stay in order: no hoisting of later LDS reads
             if (t < 7) read_a(a[nxt], t + 1);
+            constexpr int kMfmas = kFM * kGemmFN, kRegs = 4 * kGemmFN;
 #pragma unroll
-            for (int q = 0; q < 4 * kGemmFN; ++q) {
+            for (int q = 0; q < kMfmas; ++q) {
                 const int fm = q / kGemmFN, fn = q % kGemmFN;
                 acc[fm][fn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[cur][fm], b[cur][fn], acc[fm][fn], 0, 0, 0);
-                if (t < 7) b[nxt][q >> 2][q & 3] = gemm_decode_reg(word_of(q >> 2, t + 1), q & 3);   // one register per MFMA
+                if (t < 7) {                                        // the next slice's decode, spread over the MFMAs
+#pragma unroll
+                    for (int d = q * kRegs / kMfmas; d < (q + 1) * kRegs / kMfmas; ++d)
+                        b[nxt][d >> 2][d & 3] = gemm_decode_reg(word_of(d >> 2, t + 1), d & 3);
+                }
             }
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -273,9 +284,10 @@ __global__ __launch_bounds__(kGemmThreads, 2) void linear_gemm_2bit(
 
     // ---- epilogue: one instantiation per output type, chosen once ---------------------------------------
     const GemmOutCtx ctx{lds, scale_lds, y, M, N, bm, bn, wave, lane, vec_store};
-    if (yt == OutType::BF16) gemm_epilogue<OutType::BF16>(acc, ctx);
-    else if (yt == OutType::F32) gemm_epilogue<OutType::F32>(acc, ctx);
-    else gemm_epilogue<OutType::I32>(acc, ctx);
+    if (yt == OutType::BF16) gemm_epilogue<OutType::BF16, kFM>(acc, ctx);
+    else if (yt == OutType::F32) gemm_epilogue<OutType::F32, kFM>(acc, ctx);
+    else gemm_epilogue<OutType::I32, kFM>(acc, ctx);
+#endif
 }
 
 bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
@@ -284,25 +296,37 @@ bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
     return M >= 1 && K % 16 == 0 && reinterpret_cast<uintptr_t>(xq) % 16 == 0;
 }
 
-hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
-                                   int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
+template <int kFM>
+static hipError_t launch_gemm_tiles(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
+                                    int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_gemm_2bit),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_gemm_2bit<kFM>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, gemm_lds_bytes(kFM));
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int Kq = (int)ceil_div(K, kColsPerQuad);
     const int RB = (int)ceil_div(N, kRowsPerBlock);
-    const int tiles_m = (int)ceil_div(M, kGemmBM);
+    const int tiles_m = (int)ceil_div(M, 32 * kFM);
     const int64_t tiles_n = ceil_div(N, kGemmBN);
     const size_t esz = yt == OutType::BF16 ? 2 : 4;
     const int vec_store = (reinterpret_cast<uintptr_t>(y) % 16 == 0) && ((N * esz) % 16 == 0);
     dim3 grid((unsigned)(tiles_m * tiles_n));
-    hipLaunchKernelGGL(linear_gemm_2bit, grid, dim3(kGemmThreads), kGemmLdsBytes, stream, xq, sx,
+    hipLaunchKernelGGL(linear_gemm_2bit<kFM>, grid, dim3(kGemmThreads), gemm_lds_bytes(kFM), stream, xq, sx,
                        static_cast<const uint4*>(packed), gamma, (int)M, N, K, Kq, RB, tiles_m, y, yt, vec_store);
     return hipGetLastError();
+}
+
+hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
+                                   int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
+    // 512 workgroups are resident at a time (256 CUs x 2).  When the 128-token tiles do not fill them but
+    // 96-token tiles still fit in one round, the smaller tile shortens the round by a quarter.
+    const int64_t tiles_n = ceil_div(N, kGemmBN);
+    const int64_t t128 = ceil_div(M, 128) * tiles_n, t96 = ceil_div(M, 96) * tiles_n;
+    if (t128 <= 400 && t96 <= 512 && M > 96)
+        return launch_gemm_tiles<3>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
+    return launch_gemm_tiles<4>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
 }
 
 }  // namespace bitnet

@@ -277,8 +277,10 @@ def test_linear_fused_rejects_what_it_cannot_run(gpu_lib):
 
 # tiles of 256 x 256 with ragged edges in M, N and K (K steps of 256 with a partial last step), token
 # counts below one tile, and several tiles in each direction
+# Few tiles select the 96-token tile, more than 400 tiles of 128 tokens the 128-token tile: both are covered
+# with ragged tails in M, N and K (the last two shapes have 420 and 402 tiles of 128 x 256).
 GEMM_SHAPES = [(65, 300, 528), (128, 256, 256), (100, 40, 16), (300, 520, 1040), (257, 1000, 3200), (513, 270, 4112),
-               (1024, 512, 1536)]
+               (1024, 512, 1536), (96, 256, 64), (97, 257, 272), (300, 35850, 80), (700, 17000, 528)]
 
 
 @pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
