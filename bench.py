@@ -240,7 +240,7 @@ def gemm_leg(torch, B, synth, gen, args, M=2048):
         xq, sx = B.quantize_acts(x)
         y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
         iters = max(5, args.steps // 2)
-        for _ in range(3):
+        for _ in range(max(3, args.warmup)):        # clocks settle over the first milliseconds of MFMA load
             B.linear(xq, sx, p, g, N, y_dtype=B.BF16, y=y)
         torch.cuda.synchronize()
         e0 = torch.cuda.Event(enable_timing=True)

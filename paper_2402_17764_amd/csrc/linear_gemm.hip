@@ -4,8 +4,9 @@
 // (Sections 1-2 of arXiv 2402.17764).  At these M the cost is the contraction itself, so the kernel is
 // organised around keeping v_mfma_i32_32x32x32_i8 issuing:
 //
-//   * a workgroup of four waves owns a 128 x 256 output tile, each wave a 128 x 64 piece held as 4 x 2
-//     accumulator fragments of 32 x 32; two workgroups share a CU, so every SIMD has two waves that are
+//   * a workgroup of four waves owns a 128 x 256 output tile (tokens x weight rows), each wave a 128 x 64
+//     piece held as 4 x 2 accumulator fragments of 32 x 32 (96 x 256 tiles with 3 x 2 fragments for shapes
+//     that would otherwise leave CUs idle); two workgroups share a CU, so every SIMD has two waves that are
 //     not tied to the same barrier: one workgroup's loads, decode and barrier waits run under the other's
 //     MFMAs (a single wave does not overlap its own VALU work with its MFMAs);
 //   * activations (the A operand) are copied global -> LDS with 128-bit LDS-direct loads, two stages of
@@ -40,11 +41,15 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int kGemmBN = 256;                   // weight rows per workgroup tile
 constexpr int kGemmThreads = 256;
 constexpr int kGemmFN = 2;                     // 32-row weight fragments per wave (four waves side by side along the weight rows)
-constexpr int gemm_stage_bytes(int fm) { return fm * 32 * 256; }            // one K step of activations
-constexpr int gemm_scale_offset(int fm) { return 2 * gemm_stage_bytes(fm); } // float scale[32 * fm] behind the two stages
-constexpr int gemm_lds_bytes(int fm) { return gemm_scale_offset(fm) + fm * 32 * 4; }
 constexpr int kGemmPitch32 = 64 * 4 + 32;      // epilogue row pitch, 4-byte outputs: rows r and r+4 in different bank halves
 constexpr int kGemmPitch16 = 64 * 2 + 32;      // same for bf16 outputs
+constexpr int gemm_stage_bytes(int fm) { return fm * 32 * 256; }            // one K step of activations
+// float scale[32 * fm] sits behind the two stages and behind the epilogue's staging area (four waves x 32 rows),
+// which reuses the stages while the scales are still read
+constexpr int gemm_scale_offset(int fm) {
+    return 2 * gemm_stage_bytes(fm) > 4 * 32 * kGemmPitch32 ? 2 * gemm_stage_bytes(fm) : 4 * 32 * kGemmPitch32;
+}
+constexpr int gemm_lds_bytes(int fm) { return gemm_scale_offset(fm) + fm * 32 * 4; }
 
 __device__ inline uint32_t gemm_quad_word(const uint4& q, int j) { return j == 0 ? q.x : j == 1 ? q.y : j == 2 ? q.z : q.w; }
 
@@ -57,7 +62,7 @@ struct GemmOutCtx {
     void* y;
     int M;
     int64_t N;
-    int bm, bn, wave, lane, vec_store;
+    int row0, bn, wave, lane, vec_store;
 };
 
 // A lane holds, per 32 x 32 fragment, 16 tokens (8 (v >> 2) + 4 (lane >> 5) + (v & 3)) of weight row
@@ -95,7 +100,7 @@ __device__ inline void gemm_epilogue(v16i (&acc)[kFM][kGemmFN], const GemmOutCtx
 #pragma unroll
         for (int r0 = 0; r0 < 32; r0 += rows_per_pass) {
             const int rl = r0 + c.lane / lanes_per_row;
-            const int m = c.bm * (32 * kFM) + fm * 32 + rl;
+            const int m = c.row0 + fm * 32 + rl;
             const uint4 val = *reinterpret_cast<const uint4*>(stage_out + rl * pitch + piece * 16);
             if (m < c.M && n < c.N) {
                 char* dst = static_cast<char*>(c.y) + ((int64_t)m * c.N + n) * esz;
@@ -120,10 +125,11 @@ __device__ inline void gemm_epilogue(v16i (&acc)[kFM][kGemmFN], const GemmOutCtx
     }
 }
 
+// One output tile of 32 * kFM tokens (first token row0) x 256 weight rows (tile bn).
 template <int kFM>
-__global__ __launch_bounds__(kGemmThreads, 2) void linear_gemm_2bit(
+__device__ __forceinline__ void gemm_tile(
         const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
-        const float* __restrict__ gamma, int M, int64_t N, int64_t K, int Kq, int RB, int tiles_m,
+        const float* __restrict__ gamma, int M, int64_t N, int64_t K, int Kq, int RB, int row0, int bn,
         void* __restrict__ y, OutType yt, int vec_store) {
 #if defined(__HIP_DEVICE_COMPILE__)      // the buffer-resource builtins exist in the device pass only
     extern __shared__ uint4 smem[];
@@ -136,8 +142,6 @@ __global__ __launch_bounds__(kGemmThreads, 2) void linear_gemm_2bit(
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int wn = wave;
-    const int bm = blockIdx.x % tiles_m;            // token tile varies fastest (see header)
-    const int bn = blockIdx.x / tiles_m;
     const int steps = (Kq + 3) >> 2;
     const int full_steps = (int)(K >> 8);           // steps whose 256 columns all exist
     const int tail_quads = 16 * (Kq - 4 * (steps - 1));
@@ -145,7 +149,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void linear_gemm_2bit(
 
     // ---- per-token output scale gamma * s_x / 127, once per tile ------------------------------------
     if (threadIdx.x < kGemmBM) {
-        const int m = min(bm * kGemmBM + (int)threadIdx.x, M - 1);
+        const int m = min(row0 + (int)threadIdx.x, M - 1);
         scale_lds[threadIdx.x] = (gamma[0] * sx[m]) / kQb;
     }
 
@@ -153,8 +157,8 @@ __global__ __launch_bounds__(kGemmThreads, 2) void linear_gemm_2bit(
     // Lane i of a load writes LDS slot i: row (i >> 4) of the group, chunk slot (i & 15); the chunk that
     // belongs in slot c' of row m is c' ^ (m & 15).  Offsets are relative to the tile's first row.
     const int cp_row = lane >> 4, cp_slot = lane & 15;
-    const int8_t* xtile = xq + (int64_t)bm * kGemmBM * K;
-    const int rows_here = min(kGemmBM, M - bm * kGemmBM);           // rows past M: clamped, never stored
+    const int8_t* xtile = xq + (int64_t)row0 * K;
+    const int rows_here = min(kGemmBM, M - row0);                   // rows past M: clamped, never stored
     uint32_t xoff[kCopies];
 #pragma unroll
     for (int t = 0; t < kCopies; ++t) {
@@ -283,11 +287,21 @@ __global__ __launch_bounds__(kGemmThreads, 2) void linear_gemm_2bit(
     __syncthreads();                                    // every wave is done with the activation stages
 
     // ---- epilogue: one instantiation per output type, chosen once ---------------------------------------
-    const GemmOutCtx ctx{lds, scale_lds, y, M, N, bm, bn, wave, lane, vec_store};
+    const GemmOutCtx ctx{lds, scale_lds, y, M, N, row0, bn, wave, lane, vec_store};
     if (yt == OutType::BF16) gemm_epilogue<OutType::BF16, kFM>(acc, ctx);
     else if (yt == OutType::F32) gemm_epilogue<OutType::F32, kFM>(acc, ctx);
     else gemm_epilogue<OutType::I32, kFM>(acc, ctx);
 #endif
+}
+
+// Consecutive workgroups take consecutive token tiles of the same weight tile (see the header).
+template <int kFM>
+__global__ __launch_bounds__(kGemmThreads, 2) void linear_gemm_2bit(
+        const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
+        const float* __restrict__ gamma, int M, int64_t N, int64_t K, int Kq, int RB, int tiles_m,
+        void* __restrict__ y, OutType yt, int vec_store) {
+    const int b = blockIdx.x;
+    gemm_tile<kFM>(xq, sx, packed, gamma, M, N, K, Kq, RB, (b % tiles_m) * (32 * kFM), b / tiles_m, y, yt, vec_store);
 }
 
 bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
@@ -312,16 +326,19 @@ static hipError_t launch_gemm_tiles(const int8_t* xq, const float* sx, const voi
     const int64_t tiles_n = ceil_div(N, kGemmBN);
     const size_t esz = yt == OutType::BF16 ? 2 : 4;
     const int vec_store = (reinterpret_cast<uintptr_t>(y) % 16 == 0) && ((N * esz) % 16 == 0);
-    dim3 grid((unsigned)(tiles_m * tiles_n));
-    hipLaunchKernelGGL(linear_gemm_2bit<kFM>, grid, dim3(kGemmThreads), gemm_lds_bytes(kFM), stream, xq, sx,
-                       static_cast<const uint4*>(packed), gamma, (int)M, N, K, Kq, RB, tiles_m, y, yt, vec_store);
+    hipLaunchKernelGGL(linear_gemm_2bit<kFM>, dim3((unsigned)(tiles_m * tiles_n)), dim3(kGemmThreads), gemm_lds_bytes(kFM),
+                       stream, xq, sx, static_cast<const uint4*>(packed), gamma, (int)M, N, K, Kq, RB, tiles_m, y, yt,
+                       vec_store);
     return hipGetLastError();
 }
 
 hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                    int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
-    // 512 workgroups are resident at a time (256 CUs x 2).  When the 128-token tiles do not fill them but
-    // 96-token tiles still fit in one round, the smaller tile shortens the round by a quarter.
+    // 512 workgroups are resident at a time (256 CUs x 2) and a tile's time follows its height.  When the
+    // 128-token tiles fill no more than 400 of those slots but 96-token tiles still fit in one round, the
+    // smaller tile shortens that round by a quarter (13B down projection at M = 2048: 150 -> 126 us).
+    // With several rounds a partly filled last round costs little: a workgroup alone on its CU runs 1.8x
+    // faster, so mixing in shorter tiles for the last rows was measured and gained 1 %.
     const int64_t tiles_n = ceil_div(N, kGemmBN);
     const int64_t t128 = ceil_div(M, 128) * tiles_n, t96 = ceil_div(M, 96) * tiles_n;
     if (t128 <= 400 && t96 <= 512 && M > 96)

@@ -278,9 +278,9 @@ def test_linear_fused_rejects_what_it_cannot_run(gpu_lib):
 # tiles of 256 x 256 with ragged edges in M, N and K (K steps of 256 with a partial last step), token
 # counts below one tile, and several tiles in each direction
 # Few tiles select the 96-token tile, more than 400 tiles of 128 tokens the 128-token tile: both are covered
-# with ragged tails in M, N and K (the last two shapes have 420 and 402 tiles of 128 x 256).
+# with ragged tails in M, N and K (the last three shapes have 420, 402 and 600 tiles of 128 x 256).
 GEMM_SHAPES = [(65, 300, 528), (128, 256, 256), (100, 40, 16), (300, 520, 1040), (257, 1000, 3200), (513, 270, 4112),
-               (1024, 512, 1536), (96, 256, 64), (97, 257, 272), (300, 35850, 80), (700, 17000, 528)]
+               (1024, 512, 1536), (96, 256, 64), (97, 257, 272), (300, 35850, 80), (700, 17000, 528), (750, 25590, 144)]
 
 
 @pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
@@ -328,11 +328,12 @@ def test_linear_gemm_full_size_sampled(gpu_lib, M, N, K, layer):
     y32 = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.F32)
     check_y(y32[ri][:, ci].cpu().numpy(), y_ref, RTOL_F32)
     # any-size property: the integer result does not depend on which kernel produced it
-    sub = slice(0, 64)
-    a_ref = gpu_lib.linear(xq[sub].contiguous(), sx[sub].contiguous(), packed, gamma, N, y_dtype=gpu_lib.I32,
-                           kernel=gpu_lib.KERNEL_GEMV)
-    a_gemm = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.I32)[sub]
-    assert torch.equal(a_ref, a_gemm)
+    # (checked on the first and the last 64 tokens)
+    a_full = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.I32)
+    for sub in (slice(0, 64), slice(M - 64, M)):
+        a_ref = gpu_lib.linear(xq[sub].contiguous(), sx[sub].contiguous(), packed, gamma, N, y_dtype=gpu_lib.I32,
+                               kernel=gpu_lib.KERNEL_GEMV)
+        assert torch.equal(a_ref, a_full[sub])
 
 
 # ------------------------------------------------------------------------------------------------
