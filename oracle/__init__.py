@@ -31,8 +31,13 @@ def _load():
         lib.oracle_quantize_acts.argtypes = [vp, i64, i64, vp, vp]
         lib.oracle_ternary_matmul.argtypes = [vp, vp, i64, i64, i64, vp]
         lib.oracle_rescale.argtypes = [vp, ctypes.c_float, vp, i64, i64, vp]
+        lib.oracle_rmsnorm_quantize.argtypes = [vp, vp, ctypes.c_float, i64, i64, vp, vp, vp]
+        lib.oracle_swiglu_quantize.argtypes = [vp, i64, i64, vp, vp, vp]
+        lib.oracle_exp32.argtypes = [ctypes.c_float]
+        lib.oracle_exp32.restype = ctypes.c_float
         for f in (lib.oracle_absmean_gamma, lib.oracle_ternarize, lib.oracle_quantize_acts,
-                  lib.oracle_ternary_matmul, lib.oracle_rescale, lib.oracle_num_threads):
+                  lib.oracle_ternary_matmul, lib.oracle_rescale, lib.oracle_num_threads,
+                  lib.oracle_rmsnorm_quantize, lib.oracle_swiglu_quantize):
             f.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -91,6 +96,45 @@ def quantize_acts(x):
     sx = np.empty(x.shape[0], np.float32)
     _check(_load().oracle_quantize_acts(_ptr(x), x.shape[0], x.shape[1], _ptr(xq), _ptr(sx)), "quantize_acts")
     return xq, sx
+
+
+def rmsnorm_quantize(x, g=None, eps=1e-6):
+    """RMSNorm (optional gain g [K]) followed by per-token absmax quantization.
+    Returns (x_q int8 [M,K], s_x float32 [M], z float32 [M,K] = the normalised rows)."""
+    x = _f32_2d(x, "x")
+    M, K = x.shape
+    gp = None
+    if g is not None:
+        g = np.ascontiguousarray(g, dtype=np.float32)
+        if g.shape != (K,):
+            raise ValueError("g must have one entry per column")
+        gp = _ptr(g)
+    xq = np.empty((M, K), np.int8)
+    sx = np.empty(M, np.float32)
+    z = np.empty((M, K), np.float32)
+    _check(_load().oracle_rmsnorm_quantize(_ptr(x), gp, np.float32(eps), M, K, _ptr(xq), _ptr(sx), _ptr(z)),
+           "rmsnorm_quantize")
+    return xq, sx, z
+
+
+def exp32(t):
+    """The fixed-step fp32 exponential used by swiglu_quantize."""
+    return np.float32(_load().oracle_exp32(np.float32(t)))
+
+
+def swiglu_quantize(gu):
+    """h = silu(gu[:, :F]) * gu[:, F:] followed by per-token absmax quantization.
+    Returns (h_q int8 [M,F], s_h float32 [M], h float32 [M,F])."""
+    gu = _f32_2d(gu, "gu")
+    M, F2 = gu.shape
+    if F2 % 2:
+        raise ValueError("gu must have an even number of columns")
+    F = F2 // 2
+    hq = np.empty((M, F), np.int8)
+    sh = np.empty(M, np.float32)
+    h = np.empty((M, F), np.float32)
+    _check(_load().oracle_swiglu_quantize(_ptr(gu), M, F, _ptr(hq), _ptr(sh), _ptr(h)), "swiglu_quantize")
+    return hq, sh, h
 
 
 def ternary_matmul(xq, codes):

@@ -77,6 +77,43 @@ int oracle_ternary_matmul(const int8_t* xq, const int8_t* codes, int64_t M, int6
 int oracle_rescale(const int32_t* acc, float gamma, const float* sx, int64_t M, int64_t N,
                    double* y);
 
+/*
+ * The block around BitLinear (Section 2, "LLaMA-alike components": RMSNorm and SwiGLU are named,
+ * not printed; these are the textbook definitions, with the precision of every step fixed so that
+ * the int8 codes they lead to are decided in one stated way).
+ *
+ * RMSNorm followed by the activation quantization above: per token m,
+ *   ms   = (1/K) * sum_k x[m][k]^2          (fp64, compensated: the exact mean of squares)
+ *   r    = (float)(1 / sqrt(ms + eps))      (fp64 arithmetic, one rounding to fp32)
+ *   z[k] = (x[m][k] * r) * g[k]             (two fp32 multiplies; g == NULL means no gain: one multiply)
+ * then s_x, inv and x_q from z exactly as in oracle_quantize_acts.  z (optional, may be NULL)
+ * receives the normalised row.
+ * Pins: hand-worked dyadic example; the fp64 definition evaluated by numpy (z to 1e-6 relative, codes
+ * to one step); unit mean square of z when g is absent; scaling a token by a power of two with eps = 0
+ * changes nothing; reduces to oracle_quantize_acts when the token already has unit mean square.
+ */
+int oracle_rmsnorm_quantize(const float* x, const float* g, float eps, int64_t M, int64_t K,
+                            int8_t* xq, float* sx, float* z);
+
+/*
+ * The exponential used by the gate below, in fp32 with every step fixed:
+ *   t clamped to [-87, 88];  n = round(t * log2(e));  r = (t - n * 0.693359375) - n * (-2.12194440e-4);
+ *   p = 1 + r (1 + r (1/2 + r (1/6 + r (1/24 + r (1/120 + r / 720)))))   (Horner, multiply then add);
+ *   result = p * 2^n.
+ * Pin: libm's exp in fp64 to 4e-7 relative on a dense grid; exp32(0) == 1.
+ */
+float oracle_exp32(float t);
+
+/*
+ * SwiGLU gating followed by the activation quantization: gu is [M][2F], gate = gu[:, :F],
+ * up = gu[:, F:];  per element  e = exp32(-gate), s = gate / (1 + e), h = s * up  (fp32 add, IEEE
+ * division, fp32 multiply), then s_x, inv and x_q from h as in oracle_quantize_acts.  h (optional)
+ * receives the gated row.
+ * Pins: silu(gate) * up in fp64 by numpy (1e-6 relative); gate = 0 gives 0; large gate gives
+ * gate * up; swapping gate and up halves changes the result (orientation).
+ */
+int oracle_swiglu_quantize(const float* gu, int64_t M, int64_t F, int8_t* hq, float* sh, float* h);
+
 /* Number of OpenMP threads the row loops will use (the gamma sum is always one thread). */
 int oracle_num_threads(void);
 
