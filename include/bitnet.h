@@ -139,6 +139,35 @@ bitnet_status bitnet_quantize_acts(const void* x, bitnet_dtype x_dtype, int64_t 
                                    int8_t* xq, float* sx, void* stream);
 
 /*
+ * Producers of int8 activations.  Section 2 ("LLaMA-alike components") names RMSNorm and SwiGLU as the
+ * operations around BitLinear; these two entry points fuse the activation quantization above into them,
+ * so a block hands int8 codes and scales from layer to layer and bitnet_linear never waits for a separate
+ * quantization launch.  Every rounding step is fixed (stated below), so x_q and the scale are exactly
+ * reproducible.
+ *
+ * bitnet_rmsnorm_quantize: per token, ms = mean_k x^2 (exact in fp64), r = (float)(1 / sqrt(ms + eps))
+ * computed in fp64, z = (x * r) * g in fp32 (g == NULL: no gain, z = x * r), then sx / xq from z as in
+ * bitnet_quantize_acts.
+ *   x    [M][K], dtype F32 or BF16, element-aligned (16- / 8-byte aligned rows with K % 4 == 0 and
+ *        K <= 16384 stay in registers between the passes; other shapes re-read x)
+ *   g    [K] float (device) or NULL
+ *   eps  added to the mean square; >= 0
+ *   xq   out [M][K] int8;  sx  out [M] float
+ *
+ * bitnet_swiglu_quantize: gu is [M][2 F] (the output of a merged gate/up projection), per element
+ * h = (gate / (1 + exp(-gate))) * up with gate = gu[m][f], up = gu[m][F + f]; exp is evaluated in fp32 as
+ * 2^n * p(r), n = round(-gate * log2 e), r = -gate - n ln 2 (two-constant reduction), p the degree-6
+ * Taylor polynomial in Horner form, arguments clamped to [-87, 88]; add, divide and multiply are single
+ * fp32 operations.  Then sh / hq from h as in bitnet_quantize_acts.
+ *   gu   [M][2 F], dtype F32 or BF16, element-aligned
+ *   hq   out [M][F] int8;  sh  out [M] float
+ */
+bitnet_status bitnet_rmsnorm_quantize(const void* x, bitnet_dtype x_dtype, const float* g, float eps,
+                                      int64_t M, int64_t K, int8_t* xq, float* sx, void* stream);
+bitnet_status bitnet_swiglu_quantize(const void* gu, bitnet_dtype gu_dtype, int64_t M, int64_t F,
+                                     int8_t* hq, float* sh, void* stream);
+
+/*
  * The BitLinear product and rescale: y = (x_q . Wt^T) * gamma * s_x / 127.
  *   xq, sx   as written by bitnet_quantize_acts
  *   packed   as written by bitnet_quantize_weights for the same (N, K, f); 16-byte aligned

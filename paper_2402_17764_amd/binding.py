@@ -22,7 +22,7 @@ KERNEL_AUTO, KERNEL_REFERENCE, KERNEL_GEMV, KERNEL_GEMM = 0, 1, 2, 3
 SYMBOLS = [
     "bitnet_version", "bitnet_status_string", "bitnet_packed_bytes", "bitnet_quantize_weights_workspace",
     "bitnet_quantize_weights", "bitnet_quantize_acts", "bitnet_linear", "bitnet_linear_variant",
-    "bitnet_linear_fused", "bitnet_unpack_weights",
+    "bitnet_linear_fused", "bitnet_unpack_weights", "bitnet_rmsnorm_quantize", "bitnet_swiglu_quantize",
 ]
 
 _lib = None
@@ -56,6 +56,8 @@ def load():
     lib.bitnet_linear_variant.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, ci, ci, vp]
     lib.bitnet_linear_fused.argtypes = [vp, ci, vp, vp, i64, i64, i64, ci, vp, ci, vp]
     lib.bitnet_unpack_weights.argtypes = [vp, i64, i64, ci, vp, vp]
+    lib.bitnet_rmsnorm_quantize.argtypes = [vp, ci, vp, ctypes.c_float, i64, i64, vp, vp, vp]
+    lib.bitnet_swiglu_quantize.argtypes = [vp, ci, i64, i64, vp, vp, vp]
     for name in SYMBOLS[2:]:
         getattr(lib, name).restype = ci
     _lib = lib
@@ -132,6 +134,42 @@ def quantize_acts(x, xq=None, sx=None):
     _check(lib.bitnet_quantize_acts(xp, _FLOAT[x.dtype], M, K, _dev(xq, "xq", (torch.int8,)),
                                     _dev(sx, "sx", (torch.float32,)), _stream()), "bitnet_quantize_acts")
     return xq, sx
+
+
+def rmsnorm_quantize(x, g=None, eps=1e-6, xq=None, sx=None):
+    """RMSNorm (optional gain g [K], float32) fused with the activation quantization:
+    x [M,K] fp32/bf16 -> (x_q int8 [M,K], s_x float32 [M])."""
+    lib = load()
+    xp = _dev(x, "x", _FLOAT, 2)
+    M, K = x.shape
+    if xq is None:
+        xq = torch.empty((M, K), dtype=torch.int8, device=x.device)
+    if sx is None:
+        sx = torch.empty(M, dtype=torch.float32, device=x.device)
+    gp = None if g is None else _dev(g, "g", (torch.float32,))
+    if g is not None and tuple(g.shape) != (K,):
+        raise ValueError("g must have one entry per column")
+    _check(lib.bitnet_rmsnorm_quantize(xp, _FLOAT[x.dtype], gp, float(eps), M, K, _dev(xq, "xq", (torch.int8,)),
+                                       _dev(sx, "sx", (torch.float32,)), _stream()), "bitnet_rmsnorm_quantize")
+    return xq, sx
+
+
+def swiglu_quantize(gu, hq=None, sh=None):
+    """SwiGLU gating fused with the activation quantization: gu [M,2F] fp32/bf16 (gate | up) ->
+    (h_q int8 [M,F], s_h float32 [M]) with h = silu(gate) * up."""
+    lib = load()
+    gp = _dev(gu, "gu", _FLOAT, 2)
+    M, F2 = gu.shape
+    if F2 % 2:
+        raise ValueError("gu must have an even number of columns")
+    F = F2 // 2
+    if hq is None:
+        hq = torch.empty((M, F), dtype=torch.int8, device=gu.device)
+    if sh is None:
+        sh = torch.empty(M, dtype=torch.float32, device=gu.device)
+    _check(lib.bitnet_swiglu_quantize(gp, _FLOAT[gu.dtype], M, F, _dev(hq, "hq", (torch.int8,)),
+                                      _dev(sh, "sh", (torch.float32,)), _stream()), "bitnet_swiglu_quantize")
+    return hq, sh
 
 
 def linear(xq, sx, packed, gamma, N, fmt=PACK_2BIT, y_dtype=F32, y=None, kernel=KERNEL_AUTO):

@@ -109,6 +109,26 @@ bitnet_status bitnet_quantize_acts(const void* x, bitnet_dtype x_dtype, int64_t 
                                                  static_cast<hipStream_t>(stream)));
 }
 
+bitnet_status bitnet_rmsnorm_quantize(const void* x, bitnet_dtype x_dtype, const float* g, float eps, int64_t M,
+                                      int64_t K, int8_t* xq, float* sx, void* stream) {
+    if (!x || !xq || !sx) return BITNET_ERR_NULL;
+    if (!shape_ok(M, 1, K) || !(eps >= 0.0f)) return BITNET_ERR_SHAPE;
+    if (x_dtype != BITNET_F32 && x_dtype != BITNET_BF16) return BITNET_ERR_DTYPE;
+    if (!aligned(x, dtype_size(x_dtype)) || !aligned(sx, 4) || (g && !aligned(g, 4))) return BITNET_ERR_ALIGN;
+    return from_hip(bitnet::launch_rmsnorm_quantize(x, x_dtype == BITNET_BF16, g, eps, M, K, xq, sx,
+                                                    static_cast<hipStream_t>(stream)));
+}
+
+bitnet_status bitnet_swiglu_quantize(const void* gu, bitnet_dtype gu_dtype, int64_t M, int64_t F, int8_t* hq,
+                                     float* sh, void* stream) {
+    if (!gu || !hq || !sh) return BITNET_ERR_NULL;
+    if (F <= 0 || F > kMaxK / 2 || !shape_ok(M, 1, 2 * F)) return BITNET_ERR_SHAPE;
+    if (gu_dtype != BITNET_F32 && gu_dtype != BITNET_BF16) return BITNET_ERR_DTYPE;
+    if (!aligned(gu, dtype_size(gu_dtype)) || !aligned(sh, 4)) return BITNET_ERR_ALIGN;
+    return from_hip(bitnet::launch_swiglu_quantize(gu, gu_dtype == BITNET_BF16, M, F, hq, sh,
+                                                   static_cast<hipStream_t>(stream)));
+}
+
 bitnet_status bitnet_linear_variant(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                     int64_t M, int64_t N, int64_t K, bitnet_format f, void* y,
                                     bitnet_dtype y_dtype, bitnet_kernel which, void* stream) {

@@ -20,6 +20,11 @@ hipError_t launch_quantize_weights_2bit(const void* W, bool bf16, int64_t N, int
 hipError_t launch_quantize_acts(const void* x, bool bf16, int64_t M, int64_t K, int8_t* xq, float* sx,
                                 hipStream_t stream);
 
+hipError_t launch_rmsnorm_quantize(const void* x, bool bf16, const float* g, float eps, int64_t M, int64_t K,
+                                   int8_t* xq, float* sx, hipStream_t stream);
+hipError_t launch_swiglu_quantize(const void* gu, bool bf16, int64_t M, int64_t F, int8_t* hq, float* sh,
+                                  hipStream_t stream);
+
 // linear_ref.hip
 hipError_t launch_linear_reference_2bit(const int8_t* xq, const float* sx, const void* packed,
                                         const float* gamma, int64_t M, int64_t N, int64_t K, void* y,

@@ -110,6 +110,236 @@ __global__ __launch_bounds__(kActThreads) void quantize_acts_any(const void* __r
         out[k] = (int8_t)quantize_one(kBf16 ? bf16_to_f32(rh[k]) : rf[k], inv);
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Producers of int8 activations: the operations that precede a BitLinear layer in a LLaMA-style block
+// (Section 2, "LLaMA-alike components": RMSNorm, SwiGLU) with the activation quantization fused in,
+// so that the normalised / gated activations never travel through HBM as bf16.
+// ---------------------------------------------------------------------------------------------------
+constexpr int kProdMaxChunks = 16;     // register-resident path: up to 16 chunks of 4 elements per thread
+
+// four consecutive elements of a row, widened to fp32 (k is a multiple of 4; the row is 16- / 8-byte aligned)
+template <bool kBf16>
+__device__ inline void load_chunk(const void* row, int64_t k, float (&f)[4]) {
+    if (kBf16) {
+        const uint2 u = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(row) + k);
+        f[0] = __uint_as_float(u.x << 16);
+        f[1] = __uint_as_float(u.x & 0xFFFF0000u);
+        f[2] = __uint_as_float(u.y << 16);
+        f[3] = __uint_as_float(u.y & 0xFFFF0000u);
+    } else {
+        const float4 v = *reinterpret_cast<const float4*>(static_cast<const float*>(row) + k);
+        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+    }
+}
+template <bool kBf16>
+__device__ inline float load_elem(const void* row, int64_t k) {
+    return kBf16 ? bf16_to_f32(static_cast<const uint16_t*>(row)[k]) : static_cast<const float*>(row)[k];
+}
+
+// exact sum over the block of per-thread double-double partial sums (fixed-shape tree, every thread gets it)
+__device__ inline double block_sum_dd(dd v, double* sh_hi, double* sh_lo) {
+    sh_hi[threadIdx.x] = v.hi;
+    sh_lo[threadIdx.x] = v.lo;
+    __syncthreads();
+    for (int s = kActThreads / 2; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) {
+            dd a{sh_hi[threadIdx.x], sh_lo[threadIdx.x]};
+            const dd b{sh_hi[threadIdx.x + s], sh_lo[threadIdx.x + s]};
+            dd_add_dd(a, b);
+            sh_hi[threadIdx.x] = a.hi;
+            sh_lo[threadIdx.x] = a.lo;
+        }
+        __syncthreads();
+    }
+    return sh_hi[0] + sh_lo[0];
+}
+
+__device__ inline uint32_t pack4(const float (&v)[4], float inv) {
+    uint32_t p = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) p |= ((uint32_t)quantize_one(v[e], inv) & 0xFFu) << (8 * e);
+    return p;
+}
+
+// RMSNorm -> absmax int8.  Per token: ms = mean of squares (exact: squares of fp32 values are exact in
+// fp64 and the sum is carried in double-double), r = (float)(1 / sqrt(ms + eps)) in fp64, z = (x * r) * g
+// in fp32, then the per-token quantization of z.  kVec: the token stays in registers between the passes.
+template <bool kBf16, bool kVec>
+__global__ __launch_bounds__(kActThreads) void rmsnorm_quantize_kernel(
+        const void* __restrict__ xv, const float* __restrict__ g, float eps, int64_t K, int8_t* __restrict__ xq,
+        float* __restrict__ sx) {
+    __shared__ double sh_hi[kActThreads], sh_lo[kActThreads];
+    __shared__ float sh[kActWaves];
+    const int64_t m = blockIdx.x;
+    const void* row = static_cast<const char*>(xv) + m * K * (kBf16 ? 2 : 4);
+    int8_t* out = xq + m * K;
+    const int nchunks = (int)(K / 4);
+    float v[kVec ? kProdMaxChunks : 1][4];
+
+    dd acc{0.0, 0.0};
+    if (kVec) {
+#pragma unroll
+        for (int i = 0; i < kProdMaxChunks; ++i) {
+            const int c = i * kActThreads + threadIdx.x;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[i][e] = 0.0f;
+            if (c < nchunks) load_chunk<kBf16>(row, 4 * (int64_t)c, v[i]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) dd_add_double(acc, (double)v[i][e] * (double)v[i][e]);
+        }
+    } else {
+        for (int64_t k = threadIdx.x; k < K; k += kActThreads) {
+            const double a = (double)load_elem<kBf16>(row, k);
+            dd_add_double(acc, a * a);
+        }
+    }
+    const double ms = block_sum_dd(acc, sh_hi, sh_lo) / (double)K;
+    const float r = (float)(1.0 / sqrt(ms + (double)eps));
+
+    float amax = 0.0f;
+    if (kVec) {
+#pragma unroll
+        for (int i = 0; i < kProdMaxChunks; ++i) {
+            const int c = i * kActThreads + threadIdx.x;
+            if (c < nchunks) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float z = v[i][e] * r;
+                    if (g) z = z * g[4 * c + e];
+                    v[i][e] = z;
+                    amax = fmaxf(amax, fabsf(z));
+                }
+            }
+        }
+    } else {
+        for (int64_t k = threadIdx.x; k < K; k += kActThreads) {
+            float z = load_elem<kBf16>(row, k) * r;
+            if (g) z = z * g[k];
+            amax = fmaxf(amax, fabsf(z));
+        }
+    }
+    amax = block_max_nonneg(amax, sh);
+    const float s = fmaxf(amax, kEps);
+    const float inv = kQb / s;
+    if (threadIdx.x == 0) sx[m] = s;
+
+    if (kVec) {
+#pragma unroll
+        for (int i = 0; i < kProdMaxChunks; ++i) {
+            const int c = i * kActThreads + threadIdx.x;
+            if (c < nchunks) reinterpret_cast<uint32_t*>(out)[c] = pack4(v[i], inv);
+        }
+    } else {
+        for (int64_t k = threadIdx.x; k < K; k += kActThreads) {
+            float z = load_elem<kBf16>(row, k) * r;                // the same two multiplies: the same z
+            if (g) z = z * g[k];
+            out[k] = (int8_t)quantize_one(z, inv);
+        }
+    }
+}
+
+// exp(t) in fp32 with every step fixed (no fused multiply-add: this file is compiled with contraction
+// off): clamp to [-87, 88], n = round(t log2 e), two-constant reduction by ln 2, degree-6 Horner, scale
+// by 2^n.  Relative error below 4e-7; what matters is that the steps, not a library, define the value.
+__device__ inline float exp32(float t) {
+    t = fminf(fmaxf(t, -87.0f), 88.0f);
+    const float n = rintf(t * 1.44269504f);
+    float r = t - n * 0.693359375f;
+    r = r - n * -2.12194440e-4f;
+    float p = 1.0f / 720.0f;
+    p = p * r + 1.0f / 120.0f;
+    p = p * r + 1.0f / 24.0f;
+    p = p * r + 1.0f / 6.0f;
+    p = p * r + 0.5f;
+    p = p * r + 1.0f;
+    p = p * r + 1.0f;
+    return ldexpf(p, (int)n);
+}
+
+__device__ inline float swiglu_one(float gate, float up) {
+    const float e = exp32(-gate);
+    const float s = gate / (1.0f + e);                     // IEEE fp32 division
+    return s * up;
+}
+
+// SwiGLU gating -> absmax int8.  gu is [M][2F]: h = silu(gu[:, :F]) * gu[:, F:], then the per-token
+// quantization of h.
+template <bool kBf16, bool kVec>
+__global__ __launch_bounds__(kActThreads) void swiglu_quantize_kernel(
+        const void* __restrict__ guv, int64_t F, int8_t* __restrict__ hq, float* __restrict__ sh_out) {
+    __shared__ float sh[kActWaves];
+    const int64_t m = blockIdx.x;
+    const void* gate = static_cast<const char*>(guv) + m * 2 * F * (kBf16 ? 2 : 4);
+    const void* up = static_cast<const char*>(gate) + F * (kBf16 ? 2 : 4);
+    int8_t* out = hq + m * F;
+    const int nchunks = (int)(F / 4);
+    float v[kVec ? kProdMaxChunks : 1][4];
+
+    float amax = 0.0f;
+    if (kVec) {
+#pragma unroll
+        for (int i = 0; i < kProdMaxChunks; ++i) {
+            const int c = i * kActThreads + threadIdx.x;
+            if (c < nchunks) {
+                float a[4], b[4];
+                load_chunk<kBf16>(gate, 4 * (int64_t)c, a);
+                load_chunk<kBf16>(up, 4 * (int64_t)c, b);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    v[i][e] = swiglu_one(a[e], b[e]);
+                    amax = fmaxf(amax, fabsf(v[i][e]));
+                }
+            }
+        }
+    } else {
+        for (int64_t f = threadIdx.x; f < F; f += kActThreads)
+            amax = fmaxf(amax, fabsf(swiglu_one(load_elem<kBf16>(gate, f), load_elem<kBf16>(up, f))));
+    }
+    amax = block_max_nonneg(amax, sh);
+    const float s = fmaxf(amax, kEps);
+    const float inv = kQb / s;
+    if (threadIdx.x == 0) sh_out[m] = s;
+
+    if (kVec) {
+#pragma unroll
+        for (int i = 0; i < kProdMaxChunks; ++i) {
+            const int c = i * kActThreads + threadIdx.x;
+            if (c < nchunks) reinterpret_cast<uint32_t*>(out)[c] = pack4(v[i], inv);
+        }
+    } else {
+        for (int64_t f = threadIdx.x; f < F; f += kActThreads)
+            out[f] = (int8_t)quantize_one(swiglu_one(load_elem<kBf16>(gate, f), load_elem<kBf16>(up, f)), inv);
+    }
+}
+
+static bool producer_vec_ok(const void* in, size_t esz, int64_t cols, const void* out) {
+    // chunks of four: rows must start on a chunk boundary of the input loads and of the 32-bit stores
+    return cols % 4 == 0 && cols / 4 <= (int64_t)kProdMaxChunks * kActThreads &&
+           reinterpret_cast<uintptr_t>(in) % (4 * esz) == 0 && reinterpret_cast<uintptr_t>(out) % 4 == 0;
+}
+
+hipError_t launch_rmsnorm_quantize(const void* x, bool bf16, const float* g, float eps, int64_t M, int64_t K,
+                                   int8_t* xq, float* sx, hipStream_t stream) {
+    const bool vec = producer_vec_ok(x, bf16 ? 2 : 4, K, xq);
+    dim3 grid((unsigned)M), block(kActThreads);
+#define GO(B_, V_) hipLaunchKernelGGL((rmsnorm_quantize_kernel<B_, V_>), grid, block, 0, stream, x, g, eps, K, xq, sx)
+    if (bf16) { if (vec) GO(true, true); else GO(true, false); }
+    else      { if (vec) GO(false, true); else GO(false, false); }
+#undef GO
+    return hipGetLastError();
+}
+
+hipError_t launch_swiglu_quantize(const void* gu, bool bf16, int64_t M, int64_t F, int8_t* hq, float* sh,
+                                  hipStream_t stream) {
+    const bool vec = producer_vec_ok(gu, bf16 ? 2 : 4, F, hq);
+    dim3 grid((unsigned)M), block(kActThreads);
+#define GO(B_, V_) hipLaunchKernelGGL((swiglu_quantize_kernel<B_, V_>), grid, block, 0, stream, gu, F, hq, sh)
+    if (bf16) { if (vec) GO(true, true); else GO(true, false); }
+    else      { if (vec) GO(false, true); else GO(false, false); }
+#undef GO
+    return hipGetLastError();
+}
+
 hipError_t launch_quantize_acts(const void* x, bool bf16, int64_t M, int64_t K, int8_t* xq, float* sx,
                                 hipStream_t stream) {
     const int elems = bf16 ? 8 : 4;

@@ -67,8 +67,15 @@ def test_host_validation_rejects_before_launch():
     assert lib.bitnet_quantize_weights(a, 0, 4, 4, 0, NULL, a, a, 1 << 20, NULL) == 1
     assert lib.bitnet_linear(a, a, a, NULL, 1, 16, 64, 0, a, 0, NULL) == 1
     assert lib.bitnet_unpack_weights(a, 4, 4, 0, NULL, NULL) == 1
+    assert lib.bitnet_rmsnorm_quantize(NULL, 0, NULL, 0.0, 1, 16, a, a, NULL) == 1
+    assert lib.bitnet_swiglu_quantize(a, 0, 1, 16, NULL, a, NULL) == 1
     # shapes
     assert lib.bitnet_quantize_acts(a, 0, 0, 16, a, a, NULL) == 2
+    assert lib.bitnet_rmsnorm_quantize(a, 0, NULL, 0.0, 1, 0, a, a, NULL) == 2
+    assert lib.bitnet_rmsnorm_quantize(a, 0, NULL, -1.0, 1, 16, a, a, NULL) == 2     # negative eps
+    assert lib.bitnet_swiglu_quantize(a, 0, 1, 0, a, a, NULL) == 2
+    assert lib.bitnet_rmsnorm_quantize(a, 2, NULL, 0.0, 1, 16, a, a, NULL) == 3      # I32 is not an input type
+    assert lib.bitnet_swiglu_quantize(odd, 1, 1, 16, a, a, NULL) == 5
     assert lib.bitnet_linear(a, a, a, a, 1, -3, 64, 0, a, 0, NULL) == 2
     assert lib.bitnet_linear(a, a, a, a, 1, 16, 1 << 20, 0, a, 0, NULL) == 2
     # dtypes / formats

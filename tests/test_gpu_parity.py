@@ -337,6 +337,112 @@ def test_linear_gemm_full_size_sampled(gpu_lib, M, N, K, layer):
 
 
 # ------------------------------------------------------------------------------------------------
+# producers of int8 activations: RMSNorm -> int8, SwiGLU -> int8 (bit-exact codes and scales)
+# ------------------------------------------------------------------------------------------------
+# register-resident and re-reading paths (K % 4, K > 16384), one token and many, with and without gain
+PRODUCER_SHAPES = [(1, 3200), (16, 1536), (5, 4), (3, 1), (7, 1003), (2, 16384), (2, 16388), (1, 28672), (33, 8640),
+                   (300, 520)]
+
+
+@pytest.mark.parametrize("M,K", PRODUCER_SHAPES)
+@pytest.mark.parametrize("bf16", [False, True])
+def test_rmsnorm_quantize_matches_oracle(gpu_lib, M, K, bf16):
+    say("rmsnorm_quantize M=%d K=%d bf16=%s" % (M, K, bf16))
+    x, bits = synth.activations(M, K, config=2, layer=K % 7, tensor=3, bf16=True)
+    if not bf16:
+        x = synth.activations(M, K, config=0, layer=K % 7, tensor=3)
+    rng = np.random.default_rng([7, K])
+    g = (1.0 + 0.25 * rng.standard_normal(K)).astype(np.float32)
+    xt = bf16_tensor(bits).view(M, K) if bf16 else dev(x)
+    for gain, eps in ((None, 1e-6), (g, 1e-5), (g, 0.0)):
+        xq_ref, sx_ref, _ = oracle.rmsnorm_quantize(x, gain, eps)
+        xq, sx = gpu_lib.rmsnorm_quantize(xt, None if gain is None else dev(gain), eps)
+        assert sx.cpu().numpy().tobytes() == sx_ref.tobytes()
+        assert np.array_equal(xq.cpu().numpy(), xq_ref)
+
+
+def test_rmsnorm_quantize_edge_cases(gpu_lib):
+    say("rmsnorm_quantize edge cases")
+    x = np.zeros((3, 64), np.float32)
+    x[1, 5] = 1e-20          # vanishes under eps
+    x[2, :] = -3.0
+    for eps in (1e-6, 0.25):
+        xq_ref, sx_ref, _ = oracle.rmsnorm_quantize(x, None, eps)
+        xq, sx = gpu_lib.rmsnorm_quantize(dev(x), None, eps)
+        assert sx.cpu().numpy().tobytes() == sx_ref.tobytes()
+        assert np.array_equal(xq.cpu().numpy(), xq_ref)
+    # an unaligned view (odd element offset) takes the re-reading path and gives the same codes
+    M, K = 4, 1000
+    xa = synth.activations(M, K + 1, config=0, layer=1, tensor=4)
+    flat = dev(xa.reshape(-1))
+    view = flat[1:1 + M * K].view(M, K)
+    xq_ref, sx_ref, _ = oracle.rmsnorm_quantize(view.cpu().numpy(), None, 1e-6)
+    xq, sx = gpu_lib.rmsnorm_quantize(view, None, 1e-6)
+    assert np.array_equal(xq.cpu().numpy(), xq_ref) and sx.cpu().numpy().tobytes() == sx_ref.tobytes()
+
+
+@pytest.mark.parametrize("M,F", [(1, 8640), (16, 1536), (5, 4), (3, 1), (7, 1003), (2, 16384), (2, 16390), (1, 28672),
+                                 (40, 11008), (300, 260)])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_swiglu_quantize_matches_oracle(gpu_lib, M, F, bf16):
+    say("swiglu_quantize M=%d F=%d bf16=%s" % (M, F, bf16))
+    gu, bits = synth.activations(M, 2 * F, config=2, layer=F % 5, tensor=5, bf16=True)
+    if not bf16:
+        gu = synth.activations(M, 2 * F, config=0, layer=F % 5, tensor=5)
+    gt = bf16_tensor(bits).view(M, 2 * F) if bf16 else dev(gu)
+    hq_ref, sh_ref, _ = oracle.swiglu_quantize(gu)
+    hq, sh = gpu_lib.swiglu_quantize(gt)
+    assert sh.cpu().numpy().tobytes() == sh_ref.tobytes()
+    assert np.array_equal(hq.cpu().numpy(), hq_ref)
+
+
+def test_swiglu_quantize_edge_cases(gpu_lib):
+    say("swiglu_quantize edge cases")
+    F = 96
+    gu = np.zeros((4, 2 * F), np.float32)
+    gu[1, :F] = np.linspace(-120.0, 120.0, F)      # both clamps of the exponential
+    gu[1, F:] = 1.0
+    gu[2, :F] = 30.0
+    gu[2, F:] = np.linspace(-2.0, 2.0, F)
+    gu[3, :F] = -1e-30
+    gu[3, F:] = 1e30
+    hq_ref, sh_ref, _ = oracle.swiglu_quantize(gu)
+    hq, sh = gpu_lib.swiglu_quantize(dev(gu))
+    assert sh.cpu().numpy().tobytes() == sh_ref.tobytes()
+    assert np.array_equal(hq.cpu().numpy(), hq_ref)
+
+
+def test_producers_feed_the_product(gpu_lib):
+    """norm -> gate/up product -> gate -> down product on the library path equals the same chain on the oracle
+    (int8 codes, scales and accumulators bit-exact; bf16 hand-over between the two products as a block does)."""
+    say("producer chain")
+    M, H, F = 6, 512, 1280
+    x = synth.activations(M, H, config=0, layer=5, tensor=6)
+    Wgu = synth.weights(2 * F, H, config=0, layer=5, tensor=7)
+    Wd = synth.weights(H, F, config=0, layer=5, tensor=8)
+    # oracle
+    xq_r, sx_r, _ = oracle.rmsnorm_quantize(x, None, 1e-6)
+    cgu, ggu = oracle.quantize_weights(Wgu)
+    acc1_r = oracle.ternary_matmul(xq_r, cgu)
+    # library
+    xq, sx = gpu_lib.rmsnorm_quantize(dev(x), None, 1e-6)
+    pgu, gam_gu = gpu_lib.quantize_weights(dev(Wgu))
+    acc1 = gpu_lib.linear(xq, sx, pgu, gam_gu, 2 * F, y_dtype=gpu_lib.I32)
+    assert np.array_equal(acc1.cpu().numpy(), acc1_r)
+    gu16 = gpu_lib.linear(xq, sx, pgu, gam_gu, 2 * F, y_dtype=gpu_lib.BF16)
+    # the oracle continues from the bf16 values the library handed over (its own y is fp64; the hand-over
+    # rounding is the library's and was checked against the oracle by the product tests)
+    hq_r, sh_r, _ = oracle.swiglu_quantize(gu16.float().cpu().numpy())
+    hq, sh = gpu_lib.swiglu_quantize(gu16)
+    assert np.array_equal(hq.cpu().numpy(), hq_r) and sh.cpu().numpy().tobytes() == sh_r.tobytes()
+    cd, gd = oracle.quantize_weights(Wd)
+    pd, gam_d = gpu_lib.quantize_weights(dev(Wd))
+    y = gpu_lib.linear(hq, sh, pd, gam_d, H, y_dtype=gpu_lib.F32)
+    y_ref = oracle.rescale(oracle.ternary_matmul(hq_r, cd), gd, sh_r)
+    check_y(y.cpu().numpy(), y_ref, RTOL_F32)
+
+
+# ------------------------------------------------------------------------------------------------
 # the 5-trits-per-byte format
 # ------------------------------------------------------------------------------------------------
 TRIT_WEIGHT_SHAPES = [(4096, 1536), (16, 320), (1, 1), (37, 129), (100, 70), (17, 1000), (250, 4100)]
