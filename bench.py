@@ -228,6 +228,56 @@ def batched_decode_leg(torch, B, synth, gen, stream, args):
     return res
 
 
+def decoder_block_leg(torch, B, synth, gen, stream, args, cfg_idx=1, layers=26):
+    """Per-token latency of the BitLinear chain of a decoder stack at M = 1 with int8 activations handed from
+    producer to product: RMSNorm->int8, QKV, [attention excluded: its output buffer is quantized as it would
+    arrive], O, RMSNorm->int8, gate/up, SwiGLU->int8, down -- eight launches per layer in one HIP graph.
+    Residual additions and attention are not part of the path and are left out."""
+    cfg = synth.CONFIGS[cfg_idx]
+    shapes = {name: (K, N) for (name, K, N) in cfg["shapes"]}
+    H = shapes["qkv"][0]
+    F = shapes["down"][0]
+    packs = []
+    for l in range(layers):
+        d = {}
+        for name, (K, N) in shapes.items():
+            W = torch.randn((N, K), device="cuda", generator=gen, dtype=torch.float32) * synth.SIGMA_W
+            d[name] = B.quantize_weights(W)
+            del W
+        packs.append(d)
+    M = 1
+    h = make_acts(torch, M, H, gen, cfg_idx)
+    att = make_acts(torch, M, H, gen, cfg_idx)
+    gain = torch.ones(H, dtype=torch.float32, device="cuda")
+    xq_h = torch.empty((M, H), dtype=torch.int8, device="cuda")
+    xq_f = torch.empty((M, F), dtype=torch.int8, device="cuda")
+    s1 = torch.empty(M, dtype=torch.float32, device="cuda")
+    y_qkv = torch.empty((M, shapes["qkv"][1]), dtype=torch.bfloat16, device="cuda")
+    y_o = torch.empty((M, H), dtype=torch.bfloat16, device="cuda")
+    y_gu = torch.empty((M, 2 * F), dtype=torch.bfloat16, device="cuda")
+    y_d = torch.empty((M, H), dtype=torch.bfloat16, device="cuda")
+
+    def run():
+        x = h
+        for d in packs:
+            B.rmsnorm_quantize(x, gain, 1e-6, xq=xq_h, sx=s1)
+            B.linear(xq_h, s1, d["qkv"][0], d["qkv"][1], shapes["qkv"][1], y_dtype=B.BF16, y=y_qkv)
+            B.quantize_acts(att, xq=xq_h, sx=s1)
+            B.linear(xq_h, s1, d["o"][0], d["o"][1], H, y_dtype=B.BF16, y=y_o)
+            B.rmsnorm_quantize(y_o, gain, 1e-6, xq=xq_h, sx=s1)
+            B.linear(xq_h, s1, d["gate_up"][0], d["gate_up"][1], 2 * F, y_dtype=B.BF16, y=y_gu)
+            B.swiglu_quantize(y_gu, hq=xq_f, sh=s1)
+            B.linear(xq_f, s1, d["down"][0], d["down"][1], H, y_dtype=B.BF16, y=y_d)
+            x = y_d
+
+    ms, _, _ = time_graph(torch, run, args.warmup, args.steps, stream)
+    nbytes = layers * sum(gemv_bytes(M, N, K) for (K, N) in shapes.values())
+    return {"model": cfg["name"], "layers": layers, "launches": 8 * layers, "ms_per_token": round(ms, 4),
+            "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+            "note": "rmsnorm_quantize, linear(qkv), quantize_acts, linear(o), rmsnorm_quantize, linear(gate_up), "
+                    "swiglu_quantize, linear(down) per layer; attention and residual adds excluded"}
+
+
 def gemm_leg(torch, B, synth, gen, args, M=2048):
     """Prefill: M = 2048 tokens on the 13B-class shapes, bitnet_quantize_acts + bitnet_linear (MFMA kernel)."""
     res = {"M": M, "shapes": {}}
@@ -397,6 +447,7 @@ def main():
         out["gemm_m2048"] = gemm_leg(torch, B, synth, gen, args)
         out["batched_decode_7b"] = batched_decode_leg(torch, B, synth, gen, stream, args)
         out["trit5_vs_2bit_m1"] = format_leg(torch, B, synth, gen, stream, args)
+        out["decoder_chain_3b_m1"] = decoder_block_leg(torch, B, synth, gen, stream, args)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg_idx, M)
     print(json.dumps(out))

@@ -20,6 +20,7 @@ __device__ inline int quantize_one(float v, float inv) {
     return (int)r;
 }
 
+template <int kWaves = kActWaves>
 __device__ inline float block_max_nonneg(float v, float* sh) {
     v = wave_max_nonneg(v);
     const int wave = threadIdx.x >> 6;
@@ -27,7 +28,7 @@ __device__ inline float block_max_nonneg(float v, float* sh) {
     __syncthreads();
     float m = sh[0];
 #pragma unroll
-    for (int w = 1; w < kActWaves; ++w) m = fmaxf(m, sh[w]);
+    for (int w = 1; w < kWaves; ++w) m = fmaxf(m, sh[w]);
     return m;
 }
 
@@ -115,7 +116,7 @@ __global__ __launch_bounds__(kActThreads) void quantize_acts_any(const void* __r
 // (Section 2, "LLaMA-alike components": RMSNorm, SwiGLU) with the activation quantization fused in,
 // so that the normalised / gated activations never travel through HBM as bf16.
 // ---------------------------------------------------------------------------------------------------
-constexpr int kProdMaxChunks = 16;     // register-resident path: up to 16 chunks of 4 elements per thread
+constexpr int kProdMaxElems = 16384;   // register-resident path: rows of up to this many elements, in chunks of 4 per thread
 
 // four consecutive elements of a row, widened to fp32 (k is a multiple of 4; the row is 16- / 8-byte aligned)
 template <bool kBf16>
@@ -136,22 +137,22 @@ __device__ inline float load_elem(const void* row, int64_t k) {
     return kBf16 ? bf16_to_f32(static_cast<const uint16_t*>(row)[k]) : static_cast<const float*>(row)[k];
 }
 
-// exact sum over the block of per-thread double-double partial sums (fixed-shape tree, every thread gets it)
+// exact sum over the block of per-thread double-double partial sums (fixed-shape tree: butterfly inside each
+// wave, then the waves in order; every thread gets the result)
+template <int kWaves>
 __device__ inline double block_sum_dd(dd v, double* sh_hi, double* sh_lo) {
-    sh_hi[threadIdx.x] = v.hi;
-    sh_lo[threadIdx.x] = v.lo;
-    __syncthreads();
-    for (int s = kActThreads / 2; s > 0; s >>= 1) {
-        if ((int)threadIdx.x < s) {
-            dd a{sh_hi[threadIdx.x], sh_lo[threadIdx.x]};
-            const dd b{sh_hi[threadIdx.x + s], sh_lo[threadIdx.x + s]};
-            dd_add_dd(a, b);
-            sh_hi[threadIdx.x] = a.hi;
-            sh_lo[threadIdx.x] = a.lo;
-        }
-        __syncthreads();
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const dd o{__shfl_xor(v.hi, off, kWave), __shfl_xor(v.lo, off, kWave)};
+        dd_add_dd(v, o);
     }
-    return sh_hi[0] + sh_lo[0];
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { sh_hi[wave] = v.hi; sh_lo[wave] = v.lo; }
+    __syncthreads();
+    dd t{sh_hi[0], sh_lo[0]};
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) dd_add_dd(t, dd{sh_hi[w], sh_lo[w]});
+    return t.hi + t.lo;
 }
 
 __device__ inline uint32_t pack4(const float (&v)[4], float inv) {
@@ -164,61 +165,75 @@ __device__ inline uint32_t pack4(const float (&v)[4], float inv) {
 // RMSNorm -> absmax int8.  Per token: ms = mean of squares (exact: squares of fp32 values are exact in
 // fp64 and the sum is carried in double-double), r = (float)(1 / sqrt(ms + eps)) in fp64, z = (x * r) * g
 // in fp32, then the per-token quantization of z.  kVec: the token stays in registers between the passes.
-template <bool kBf16, bool kVec>
-__global__ __launch_bounds__(kActThreads) void rmsnorm_quantize_kernel(
+template <bool kBf16, bool kVec, int kThreads>
+__global__ __launch_bounds__(kThreads) void rmsnorm_quantize_kernel(
         const void* __restrict__ xv, const float* __restrict__ g, float eps, int64_t K, int8_t* __restrict__ xq,
         float* __restrict__ sx) {
-    __shared__ double sh_hi[kActThreads], sh_lo[kActThreads];
-    __shared__ float sh[kActWaves];
+    constexpr int kWaves = kThreads / kWave, kProdMaxChunks = kProdMaxElems / (4 * kThreads);
+    __shared__ double sh_hi[kWaves], sh_lo[kWaves];
+    __shared__ float sh[kWaves];
     const int64_t m = blockIdx.x;
     const void* row = static_cast<const char*>(xv) + m * K * (kBf16 ? 2 : 4);
     int8_t* out = xq + m * K;
     const int nchunks = (int)(K / 4);
-    float v[kVec ? kProdMaxChunks : 1][4];
+    float v[kVec ? kProdMaxChunks : 1][4], gv[kVec ? kProdMaxChunks : 1][4];
 
-    dd acc{0.0, 0.0};
+    // two interleaved double-double accumulators: the sums are exact, so splitting them changes nothing
+    // but the length of the dependent chain
+    dd acc{0.0, 0.0}, acc2{0.0, 0.0};
     if (kVec) {
 #pragma unroll
         for (int i = 0; i < kProdMaxChunks; ++i) {
-            const int c = i * kActThreads + threadIdx.x;
+            if (i * kThreads >= nchunks) break;                 // uniform: whole iterations past the row
+            const int c = i * kThreads + threadIdx.x;
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[i][e] = 0.0f;
-            if (c < nchunks) load_chunk<kBf16>(row, 4 * (int64_t)c, v[i]);
+            if (c < nchunks) {
+                load_chunk<kBf16>(row, 4 * (int64_t)c, v[i]);
+                if (g) {                                           // requested now, needed after the reduction
 #pragma unroll
-            for (int e = 0; e < 4; ++e) dd_add_double(acc, (double)v[i][e] * (double)v[i][e]);
+                    for (int e = 0; e < 4; ++e) gv[i][e] = g[4 * c + e];
+                }
+            }
+            dd_add_double(acc, (double)v[i][0] * (double)v[i][0]);
+            dd_add_double(acc2, (double)v[i][1] * (double)v[i][1]);
+            dd_add_double(acc, (double)v[i][2] * (double)v[i][2]);
+            dd_add_double(acc2, (double)v[i][3] * (double)v[i][3]);
         }
+        dd_add_dd(acc, acc2);
     } else {
-        for (int64_t k = threadIdx.x; k < K; k += kActThreads) {
+        for (int64_t k = threadIdx.x; k < K; k += kThreads) {
             const double a = (double)load_elem<kBf16>(row, k);
             dd_add_double(acc, a * a);
         }
     }
-    const double ms = block_sum_dd(acc, sh_hi, sh_lo) / (double)K;
+    const double ms = block_sum_dd<kWaves>(acc, sh_hi, sh_lo) / (double)K;
     const float r = (float)(1.0 / sqrt(ms + (double)eps));
 
     float amax = 0.0f;
     if (kVec) {
 #pragma unroll
         for (int i = 0; i < kProdMaxChunks; ++i) {
-            const int c = i * kActThreads + threadIdx.x;
+            if (i * kThreads >= nchunks) break;
+            const int c = i * kThreads + threadIdx.x;
             if (c < nchunks) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     float z = v[i][e] * r;
-                    if (g) z = z * g[4 * c + e];
+                    if (g) z = z * gv[i][e];
                     v[i][e] = z;
                     amax = fmaxf(amax, fabsf(z));
                 }
             }
         }
     } else {
-        for (int64_t k = threadIdx.x; k < K; k += kActThreads) {
+        for (int64_t k = threadIdx.x; k < K; k += kThreads) {
             float z = load_elem<kBf16>(row, k) * r;
             if (g) z = z * g[k];
             amax = fmaxf(amax, fabsf(z));
         }
     }
-    amax = block_max_nonneg(amax, sh);
+    amax = block_max_nonneg<kWaves>(amax, sh);
     const float s = fmaxf(amax, kEps);
     const float inv = kQb / s;
     if (threadIdx.x == 0) sx[m] = s;
@@ -226,11 +241,12 @@ __global__ __launch_bounds__(kActThreads) void rmsnorm_quantize_kernel(
     if (kVec) {
 #pragma unroll
         for (int i = 0; i < kProdMaxChunks; ++i) {
-            const int c = i * kActThreads + threadIdx.x;
+            if (i * kThreads >= nchunks) break;
+            const int c = i * kThreads + threadIdx.x;
             if (c < nchunks) reinterpret_cast<uint32_t*>(out)[c] = pack4(v[i], inv);
         }
     } else {
-        for (int64_t k = threadIdx.x; k < K; k += kActThreads) {
+        for (int64_t k = threadIdx.x; k < K; k += kThreads) {
             float z = load_elem<kBf16>(row, k) * r;                // the same two multiplies: the same z
             if (g) z = z * g[k];
             out[k] = (int8_t)quantize_one(z, inv);
@@ -264,10 +280,11 @@ __device__ inline float swiglu_one(float gate, float up) {
 
 // SwiGLU gating -> absmax int8.  gu is [M][2F]: h = silu(gu[:, :F]) * gu[:, F:], then the per-token
 // quantization of h.
-template <bool kBf16, bool kVec>
-__global__ __launch_bounds__(kActThreads) void swiglu_quantize_kernel(
+template <bool kBf16, bool kVec, int kThreads>
+__global__ __launch_bounds__(kThreads) void swiglu_quantize_kernel(
         const void* __restrict__ guv, int64_t F, int8_t* __restrict__ hq, float* __restrict__ sh_out) {
-    __shared__ float sh[kActWaves];
+    constexpr int kWaves = kThreads / kWave, kProdMaxChunks = kProdMaxElems / (4 * kThreads);
+    __shared__ float sh[kWaves];
     const int64_t m = blockIdx.x;
     const void* gate = static_cast<const char*>(guv) + m * 2 * F * (kBf16 ? 2 : 4);
     const void* up = static_cast<const char*>(gate) + F * (kBf16 ? 2 : 4);
@@ -279,7 +296,8 @@ __global__ __launch_bounds__(kActThreads) void swiglu_quantize_kernel(
     if (kVec) {
 #pragma unroll
         for (int i = 0; i < kProdMaxChunks; ++i) {
-            const int c = i * kActThreads + threadIdx.x;
+            if (i * kThreads >= nchunks) break;
+            const int c = i * kThreads + threadIdx.x;
             if (c < nchunks) {
                 float a[4], b[4];
                 load_chunk<kBf16>(gate, 4 * (int64_t)c, a);
@@ -292,10 +310,10 @@ __global__ __launch_bounds__(kActThreads) void swiglu_quantize_kernel(
             }
         }
     } else {
-        for (int64_t f = threadIdx.x; f < F; f += kActThreads)
+        for (int64_t f = threadIdx.x; f < F; f += kThreads)
             amax = fmaxf(amax, fabsf(swiglu_one(load_elem<kBf16>(gate, f), load_elem<kBf16>(up, f))));
     }
-    amax = block_max_nonneg(amax, sh);
+    amax = block_max_nonneg<kWaves>(amax, sh);
     const float s = fmaxf(amax, kEps);
     const float inv = kQb / s;
     if (threadIdx.x == 0) sh_out[m] = s;
@@ -303,40 +321,49 @@ __global__ __launch_bounds__(kActThreads) void swiglu_quantize_kernel(
     if (kVec) {
 #pragma unroll
         for (int i = 0; i < kProdMaxChunks; ++i) {
-            const int c = i * kActThreads + threadIdx.x;
+            if (i * kThreads >= nchunks) break;
+            const int c = i * kThreads + threadIdx.x;
             if (c < nchunks) reinterpret_cast<uint32_t*>(out)[c] = pack4(v[i], inv);
         }
     } else {
-        for (int64_t f = threadIdx.x; f < F; f += kActThreads)
+        for (int64_t f = threadIdx.x; f < F; f += kThreads)
             out[f] = (int8_t)quantize_one(swiglu_one(load_elem<kBf16>(gate, f), load_elem<kBf16>(up, f)), inv);
     }
 }
 
+// Few tokens: 1024 threads per token, so that the dependent chains of the gate (exponential, division) and
+// of the exact sum interleave over four waves per SIMD; many tokens: 256, and the tokens fill the CUs.
+constexpr int kProdFewTokens = 64;
+
 static bool producer_vec_ok(const void* in, size_t esz, int64_t cols, const void* out) {
     // chunks of four: rows must start on a chunk boundary of the input loads and of the 32-bit stores
-    return cols % 4 == 0 && cols / 4 <= (int64_t)kProdMaxChunks * kActThreads &&
+    return cols % 4 == 0 && cols <= kProdMaxElems &&
            reinterpret_cast<uintptr_t>(in) % (4 * esz) == 0 && reinterpret_cast<uintptr_t>(out) % 4 == 0;
 }
 
 hipError_t launch_rmsnorm_quantize(const void* x, bool bf16, const float* g, float eps, int64_t M, int64_t K,
                                    int8_t* xq, float* sx, hipStream_t stream) {
+    const int threads = M < kProdFewTokens ? 1024 : 256;
     const bool vec = producer_vec_ok(x, bf16 ? 2 : 4, K, xq);
-    dim3 grid((unsigned)M), block(kActThreads);
-#define GO(B_, V_) hipLaunchKernelGGL((rmsnorm_quantize_kernel<B_, V_>), grid, block, 0, stream, x, g, eps, K, xq, sx)
-    if (bf16) { if (vec) GO(true, true); else GO(true, false); }
-    else      { if (vec) GO(false, true); else GO(false, false); }
+    dim3 grid((unsigned)M), block(threads);
+#define GO(B_, V_, T_) hipLaunchKernelGGL((rmsnorm_quantize_kernel<B_, V_, T_>), grid, block, 0, stream, x, g, eps, K, xq, sx)
+#define PICK(B_, V_) do { if (threads == 1024) GO(B_, V_, 1024); else GO(B_, V_, 256); } while (0)
+    if (bf16) { if (vec) PICK(true, true); else PICK(true, false); }
+    else      { if (vec) PICK(false, true); else PICK(false, false); }
 #undef GO
     return hipGetLastError();
 }
 
 hipError_t launch_swiglu_quantize(const void* gu, bool bf16, int64_t M, int64_t F, int8_t* hq, float* sh,
                                   hipStream_t stream) {
+    const int threads = M < kProdFewTokens ? 1024 : 256;
     const bool vec = producer_vec_ok(gu, bf16 ? 2 : 4, F, hq);
-    dim3 grid((unsigned)M), block(kActThreads);
-#define GO(B_, V_) hipLaunchKernelGGL((swiglu_quantize_kernel<B_, V_>), grid, block, 0, stream, gu, F, hq, sh)
-    if (bf16) { if (vec) GO(true, true); else GO(true, false); }
-    else      { if (vec) GO(false, true); else GO(false, false); }
+    dim3 grid((unsigned)M), block(threads);
+#define GO(B_, V_, T_) hipLaunchKernelGGL((swiglu_quantize_kernel<B_, V_, T_>), grid, block, 0, stream, gu, F, hq, sh)
+    if (bf16) { if (vec) PICK(true, true); else PICK(true, false); }
+    else      { if (vec) PICK(false, true); else PICK(false, false); }
 #undef GO
+#undef PICK
     return hipGetLastError();
 }
 
