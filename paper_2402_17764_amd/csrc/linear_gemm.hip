@@ -334,15 +334,25 @@ static hipError_t launch_gemm_tiles(const int8_t* xq, const float* sx, const voi
 
 hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                    int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
-    // 512 workgroups are resident at a time (256 CUs x 2) and a tile's time follows its height.  When the
-    // 128-token tiles fill no more than 400 of those slots but 96-token tiles still fit in one round, the
-    // smaller tile shortens that round by a quarter (13B down projection at M = 2048: 150 -> 126 us).
-    // With several rounds a partly filled last round costs little: a workgroup alone on its CU runs 1.8x
-    // faster, so mixing in shorter tiles for the last rows was measured and gained 1 %.
+    // Tile height (32 * kFM tokens) from a cost model fitted to measurements on MI355X:
+    //   * a K step of one tile costs about 1000 + 512 kFM cycles (weight decode, loads and barrier are per
+    //     tile, the MFMAs grow with its height);
+    //   * up to 256 tiles every workgroup has a CU to itself; two workgroups sharing a CU each run about 1.9x
+    //     slower, so up to 512 tiles the launch takes 1.9 tile times, and beyond that 1.9 per 512 tiles (a
+    //     partly filled last round costs little, because its workgroups run alone).
+    // 13B down projection at M = 2048 (N = 5120): 320 tiles of 128 tokens 150 us, 440 tiles of 96 tokens 126 us;
+    // M = 512, N = 5120: 80 tiles of 128 tokens 38 us, fewer tokens per tile spread the work over more CUs.
     const int64_t tiles_n = ceil_div(N, kGemmBN);
-    const int64_t t128 = ceil_div(M, 128) * tiles_n, t96 = ceil_div(M, 96) * tiles_n;
-    if (t128 <= 400 && t96 <= 512 && M > 96)
-        return launch_gemm_tiles<3>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
+    int best = 4;
+    double best_cost = 0.0;
+    for (int fm = 4; fm >= 2; --fm) {
+        const double tiles = (double)(ceil_div(M, 32 * fm) * tiles_n);
+        const double share = tiles <= 256.0 ? 1.0 : tiles <= 512.0 ? 1.9 : 1.9 * tiles / 512.0;
+        const double cost = (1000.0 + 512.0 * fm) * share;
+        if (fm == 4 || cost < 0.97 * best_cost) { best = fm; best_cost = cost; }
+    }
+    if (best == 2) return launch_gemm_tiles<2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
+    if (best == 3) return launch_gemm_tiles<3>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
     return launch_gemm_tiles<4>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
 }
 
