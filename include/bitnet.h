@@ -201,6 +201,35 @@ bitnet_status bitnet_linear_fused(const void* x, bitnet_dtype x_dtype, const voi
                                   bitnet_format f, void* y, bitnet_dtype y_dtype, void* stream);
 
 /*
+ * One scale per segment of rows.  Eq. (3) gives every weight matrix its own gamma; when several
+ * matrices are stored as one (merged Q|K|V or gate|up projections) these entry points keep one gamma per
+ * original matrix instead of one for the merged tensor.
+ *
+ * bitnet_quantize_weights_segmented: rows are split into nseg consecutive segments of seg_rows[i] rows
+ * (host array; every segment but the last a multiple of 16 rows; the sum is N).  Each segment gets its own
+ * gamma (Eq. (3) over its rows) and its codes (Eq. (1)-(2) with that gamma), packed into one buffer with
+ * the layout of the whole [N][K] matrix.
+ *   gamma_rb   out, ceil(N / 16) floats (device): the gamma of the segment that each 16-row block belongs to
+ *   workspace  as for bitnet_quantize_weights; used by one segment after the other in stream order
+ * 2-bit format only (BITNET_ERR_FORMAT otherwise).
+ *
+ * bitnet_linear_segmented / bitnet_linear_fused_segmented: as bitnet_linear_variant / bitnet_linear_fused
+ * with y[m][n] = acc * gamma_rb[n / 16] * s_x[m] / 127.  `which` as in bitnet_linear_variant
+ * (BITNET_KERNEL_AUTO picks by shape).
+ */
+bitnet_status bitnet_quantize_weights_segmented(const void* W, bitnet_dtype w_dtype, int64_t N, int64_t K,
+                                                int nseg, const int64_t* seg_rows, bitnet_format f,
+                                                void* packed, float* gamma_rb, void* workspace,
+                                                size_t workspace_bytes, void* stream);
+bitnet_status bitnet_linear_segmented(const int8_t* xq, const float* sx, const void* packed,
+                                      const float* gamma_rb, int64_t M, int64_t N, int64_t K,
+                                      bitnet_format f, void* y, bitnet_dtype y_dtype, bitnet_kernel which,
+                                      void* stream);
+bitnet_status bitnet_linear_fused_segmented(const void* x, bitnet_dtype x_dtype, const void* packed,
+                                            const float* gamma_rb, int64_t M, int64_t N, int64_t K,
+                                            bitnet_format f, void* y, bitnet_dtype y_dtype, void* stream);
+
+/*
  * Test helper: packed -> codes [N][K] int8 in {-1, 0, +1} (padding dropped).  The only supported
  * way to read codes back besides decoding the documented layout by hand.
  */

@@ -23,6 +23,7 @@ SYMBOLS = [
     "bitnet_version", "bitnet_status_string", "bitnet_packed_bytes", "bitnet_quantize_weights_workspace",
     "bitnet_quantize_weights", "bitnet_quantize_acts", "bitnet_linear", "bitnet_linear_variant",
     "bitnet_linear_fused", "bitnet_unpack_weights", "bitnet_rmsnorm_quantize", "bitnet_swiglu_quantize",
+    "bitnet_quantize_weights_segmented", "bitnet_linear_segmented", "bitnet_linear_fused_segmented",
 ]
 
 _lib = None
@@ -58,6 +59,9 @@ def load():
     lib.bitnet_unpack_weights.argtypes = [vp, i64, i64, ci, vp, vp]
     lib.bitnet_rmsnorm_quantize.argtypes = [vp, ci, vp, ctypes.c_float, i64, i64, vp, vp, vp]
     lib.bitnet_swiglu_quantize.argtypes = [vp, ci, i64, i64, vp, vp, vp]
+    lib.bitnet_quantize_weights_segmented.argtypes = [vp, ci, i64, i64, ci, ctypes.POINTER(i64), ci, vp, vp, vp, sz, vp]
+    lib.bitnet_linear_segmented.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, ci, ci, vp]
+    lib.bitnet_linear_fused_segmented.argtypes = [vp, ci, vp, vp, i64, i64, i64, ci, vp, ci, vp]
     for name in SYMBOLS[2:]:
         getattr(lib, name).restype = ci
     _lib = lib
@@ -197,6 +201,58 @@ def linear_fused(x, packed, gamma, N, fmt=PACK_2BIT, y_dtype=F32, y=None):
     _check(lib.bitnet_linear_fused(xp, _FLOAT[x.dtype], _dev(packed, "packed"), _dev(gamma, "gamma", (torch.float32,)),
                                    M, N, K, fmt, _dev(y, "y", (_OUT[y_dtype],)), y_dtype, _stream()),
            "bitnet_linear_fused")
+    return y
+
+
+def quantize_weights_segmented(W, seg_rows, fmt=PACK_2BIT, packed=None, gamma_rb=None, workspace=None):
+    """W [N,K] split into consecutive row segments (seg_rows, e.g. the Q, K, V parts of a merged projection),
+    each quantized with its own gamma -> (packed uint8 tensor, gamma_rb float32[ceil(N/16)])."""
+    lib = load()
+    wp = _dev(W, "W", _FLOAT, 2)
+    N, K = W.shape
+    seg = (ctypes.c_int64 * len(seg_rows))(*[int(r) for r in seg_rows])
+    if packed is None:
+        packed = torch.empty(packed_bytes(N, K, fmt), dtype=torch.uint8, device=W.device)
+    if gamma_rb is None:
+        gamma_rb = torch.empty((N + 15) // 16, dtype=torch.float32, device=W.device)
+    if workspace is None:
+        workspace = torch.empty(quantize_weights_workspace(N, K), dtype=torch.uint8, device=W.device)
+    _check(lib.bitnet_quantize_weights_segmented(wp, _FLOAT[W.dtype], N, K, len(seg_rows), seg, fmt,
+                                                 _dev(packed, "packed"), _dev(gamma_rb, "gamma_rb", (torch.float32,)),
+                                                 _dev(workspace, "workspace"),
+                                                 workspace.numel() * workspace.element_size(), _stream()),
+           "bitnet_quantize_weights_segmented")
+    return packed, gamma_rb
+
+
+def linear_segmented(xq, sx, packed, gamma_rb, N, fmt=PACK_2BIT, y_dtype=F32, y=None, kernel=KERNEL_AUTO):
+    """bitnet_linear with one gamma per 16-row block (gamma_rb from quantize_weights_segmented)."""
+    lib = load()
+    M, K = xq.shape
+    if y is None:
+        y = torch.empty((M, N), dtype=_OUT[y_dtype], device=xq.device)
+    if gamma_rb.numel() < (N + 15) // 16:
+        raise ValueError("gamma_rb needs one entry per 16-row block")
+    _check(lib.bitnet_linear_segmented(_dev(xq, "xq", (torch.int8,), 2), _dev(sx, "sx", (torch.float32,)),
+                                       _dev(packed, "packed"), _dev(gamma_rb, "gamma_rb", (torch.float32,)), M, N, K, fmt,
+                                       _dev(y, "y", (_OUT[y_dtype],)), y_dtype, kernel, _stream()),
+           "bitnet_linear_segmented")
+    return y
+
+
+def linear_fused_segmented(x, packed, gamma_rb, N, fmt=PACK_2BIT, y_dtype=F32, y=None):
+    """bitnet_linear_fused with one gamma per 16-row block."""
+    lib = load()
+    xp = _dev(x, "x", _FLOAT, 2)
+    M, K = x.shape
+    if y is None:
+        y = torch.empty((M, N), dtype=_OUT[y_dtype], device=x.device)
+    if gamma_rb.numel() < (N + 15) // 16:
+        raise ValueError("gamma_rb needs one entry per 16-row block")
+    _check(lib.bitnet_linear_fused_segmented(xp, _FLOAT[x.dtype], _dev(packed, "packed"),
+                                             _dev(gamma_rb, "gamma_rb", (torch.float32,)), M, N, K, fmt,
+                                             _dev(y, "y", (_OUT[y_dtype],)), y_dtype, _stream()),
+           "bitnet_linear_fused_segmented")
     return y
 
 

@@ -129,9 +129,9 @@ bitnet_status bitnet_swiglu_quantize(const void* gu, bitnet_dtype gu_dtype, int6
                                                    static_cast<hipStream_t>(stream)));
 }
 
-bitnet_status bitnet_linear_variant(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
-                                    int64_t M, int64_t N, int64_t K, bitnet_format f, void* y,
-                                    bitnet_dtype y_dtype, bitnet_kernel which, void* stream) {
+static bitnet_status linear_any(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
+                                int gstride, int64_t M, int64_t N, int64_t K, bitnet_format f, void* y,
+                                bitnet_dtype y_dtype, bitnet_kernel which, void* stream) {
     if (!xq || !sx || !packed || !gamma || !y) return BITNET_ERR_NULL;
     if (!shape_ok(M, N, K)) return BITNET_ERR_SHAPE;
     OutType yt;
@@ -142,6 +142,7 @@ bitnet_status bitnet_linear_variant(const int8_t* xq, const float* sx, const voi
     hipStream_t s = static_cast<hipStream_t>(stream);
 
     if (f == BITNET_PACK_TRIT5) {
+        if (gstride) return BITNET_ERR_FORMAT;         // per-segment scales exist for the 2-bit format only
         // the 5-trit format has the reference kernel and the weight-streaming kernel for M <= 16
         if (which == BITNET_KERNEL_AUTO)
             which = bitnet::gemv_trit5_supports(M, N, K, xq) ? BITNET_KERNEL_GEMV : BITNET_KERNEL_REFERENCE;
@@ -159,27 +160,75 @@ bitnet_status bitnet_linear_variant(const int8_t* xq, const float* sx, const voi
     }
     switch (which) {
         case BITNET_KERNEL_REFERENCE:
-            return from_hip(bitnet::launch_linear_reference_2bit(xq, sx, packed, gamma, M, N, K, y, yt, s));
+            return from_hip(bitnet::launch_linear_reference_2bit(xq, sx, packed, gamma, gstride, M, N, K, y, yt, s));
         case BITNET_KERNEL_GEMV:
             if (!bitnet::gemv_supports(M, N, K, xq)) return BITNET_ERR_KERNEL;
-            return from_hip(bitnet::launch_linear_gemv_2bit(xq, sx, packed, gamma, M, N, K, y, yt, s));
+            return from_hip(bitnet::launch_linear_gemv_2bit(xq, sx, packed, gamma, gstride, M, N, K, y, yt, s));
         case BITNET_KERNEL_GEMM:
             if (!bitnet::gemm_supports(M, N, K, xq)) return BITNET_ERR_KERNEL;
-            return from_hip(bitnet::launch_linear_gemm_2bit(xq, sx, packed, gamma, M, N, K, y, yt, s));
+            return from_hip(bitnet::launch_linear_gemm_2bit(xq, sx, packed, gamma, gstride, M, N, K, y, yt, s));
         default:
             return BITNET_ERR_KERNEL;
     }
 }
 
+bitnet_status bitnet_linear_variant(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
+                                    int64_t M, int64_t N, int64_t K, bitnet_format f, void* y,
+                                    bitnet_dtype y_dtype, bitnet_kernel which, void* stream) {
+    return linear_any(xq, sx, packed, gamma, 0, M, N, K, f, y, y_dtype, which, stream);
+}
+
 bitnet_status bitnet_linear(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                             int64_t M, int64_t N, int64_t K, bitnet_format f, void* y, bitnet_dtype y_dtype,
                             void* stream) {
-    return bitnet_linear_variant(xq, sx, packed, gamma, M, N, K, f, y, y_dtype, BITNET_KERNEL_AUTO, stream);
+    return linear_any(xq, sx, packed, gamma, 0, M, N, K, f, y, y_dtype, BITNET_KERNEL_AUTO, stream);
 }
 
-bitnet_status bitnet_linear_fused(const void* x, bitnet_dtype x_dtype, const void* packed, const float* gamma,
-                                  int64_t M, int64_t N, int64_t K, bitnet_format f, void* y,
-                                  bitnet_dtype y_dtype, void* stream) {
+bitnet_status bitnet_linear_segmented(const int8_t* xq, const float* sx, const void* packed, const float* gamma_rb,
+                                      int64_t M, int64_t N, int64_t K, bitnet_format f, void* y,
+                                      bitnet_dtype y_dtype, bitnet_kernel which, void* stream) {
+    return linear_any(xq, sx, packed, gamma_rb, 1, M, N, K, f, y, y_dtype, which, stream);
+}
+
+bitnet_status bitnet_quantize_weights_segmented(const void* W, bitnet_dtype w_dtype, int64_t N, int64_t K,
+                                                int nseg, const int64_t* seg_rows, bitnet_format f, void* packed,
+                                                float* gamma_rb, void* workspace, size_t workspace_bytes,
+                                                void* stream) {
+    if (!W || !packed || !gamma_rb || !workspace || !seg_rows) return BITNET_ERR_NULL;
+    if (!shape_ok(1, N, K) || nseg <= 0) return BITNET_ERR_SHAPE;
+    if (w_dtype != BITNET_F32 && w_dtype != BITNET_BF16) return BITNET_ERR_DTYPE;
+    if (f != BITNET_PACK_2BIT) return BITNET_ERR_FORMAT;
+    if (!aligned(W, dtype_size(w_dtype)) || !aligned(packed, 16) || !aligned(gamma_rb, 4) || !aligned(workspace, 16))
+        return BITNET_ERR_ALIGN;
+    int64_t total = 0;
+    for (int sgm = 0; sgm < nseg; ++sgm) {
+        // a segment owns whole 16-row blocks: only the last may end inside one
+        if (seg_rows[sgm] <= 0 || (sgm + 1 < nseg && seg_rows[sgm] % 16 != 0)) return BITNET_ERR_SHAPE;
+        total += seg_rows[sgm];
+    }
+    if (total != N) return BITNET_ERR_SHAPE;
+    size_t need = 0;
+    bitnet_quantize_weights_workspace(N, K, &need);
+    if (workspace_bytes < need) return BITNET_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t rb_total = bitnet::ceil_div(N, 16);
+    int64_t row0 = 0;
+    for (int sgm = 0; sgm < nseg; ++sgm) {
+        const int64_t rows = seg_rows[sgm];
+        const char* Ws = static_cast<const char*>(W) + row0 * K * (int64_t)dtype_size(w_dtype);
+        // the launches of one segment finish with the workspace before the next segment's start (stream order)
+        hipError_t e = bitnet::launch_quantize_weights_2bit(Ws, w_dtype == BITNET_BF16, rows, K, packed,
+                                                            gamma_rb + row0 / 16, workspace, s, row0 / 16, rb_total,
+                                                            bitnet::ceil_div(rows, 16));
+        if (e != hipSuccess) return BITNET_ERR_HIP;
+        row0 += rows;
+    }
+    return BITNET_OK;
+}
+
+static bitnet_status linear_fused_any(const void* x, bitnet_dtype x_dtype, const void* packed, const float* gamma,
+                                      int gstride, int64_t M, int64_t N, int64_t K, bitnet_format f, void* y,
+                                      bitnet_dtype y_dtype, void* stream) {
     if (!x || !packed || !gamma || !y) return BITNET_ERR_NULL;
     if (!shape_ok(M, N, K)) return BITNET_ERR_SHAPE;
     if (x_dtype != BITNET_F32 && x_dtype != BITNET_BF16) return BITNET_ERR_DTYPE;
@@ -189,8 +238,20 @@ bitnet_status bitnet_linear_fused(const void* x, bitnet_dtype x_dtype, const voi
     if (!aligned(packed, 16) || !aligned(gamma, 4) || !aligned(y, dtype_size(y_dtype))) return BITNET_ERR_ALIGN;
     if (f != BITNET_PACK_2BIT) return BITNET_ERR_FORMAT;
     if (!bitnet::gemv_fused_supports(M, N, K, x)) return BITNET_ERR_KERNEL;
-    return from_hip(bitnet::launch_linear_fused_2bit(x, x_dtype == BITNET_BF16, packed, gamma, M, N, K, y, yt,
+    return from_hip(bitnet::launch_linear_fused_2bit(x, x_dtype == BITNET_BF16, packed, gamma, gstride, M, N, K, y, yt,
                                                      static_cast<hipStream_t>(stream)));
+}
+
+bitnet_status bitnet_linear_fused(const void* x, bitnet_dtype x_dtype, const void* packed, const float* gamma,
+                                  int64_t M, int64_t N, int64_t K, bitnet_format f, void* y,
+                                  bitnet_dtype y_dtype, void* stream) {
+    return linear_fused_any(x, x_dtype, packed, gamma, 0, M, N, K, f, y, y_dtype, stream);
+}
+
+bitnet_status bitnet_linear_fused_segmented(const void* x, bitnet_dtype x_dtype, const void* packed,
+                                            const float* gamma_rb, int64_t M, int64_t N, int64_t K, bitnet_format f,
+                                            void* y, bitnet_dtype y_dtype, void* stream) {
+    return linear_fused_any(x, x_dtype, packed, gamma_rb, 1, M, N, K, f, y, y_dtype, stream);
 }
 
 bitnet_status bitnet_unpack_weights(const void* packed, int64_t N, int64_t K, bitnet_format f, int8_t* codes,

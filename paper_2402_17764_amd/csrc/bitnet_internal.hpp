@@ -9,12 +9,29 @@ namespace bitnet {
 
 enum class OutType { F32 = 0, BF16 = 1, I32 = 2 };
 
+// Raises a kernel's dynamic-LDS limit above the 64 KiB default, once per device and kernel (the attribute
+// belongs to the function on the current device).  `done` is the caller's per-kernel flag array.
+constexpr int kMaxDevices = 64;
+inline hipError_t raise_dynamic_lds(const void* kernel, int bytes, bool (&done)[kMaxDevices]) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (done[dev]) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done[dev] = true;
+    return e;
+}
+
 // quant_weights.hip
 int quant_weights_num_partials();
+// nout: how many consecutive floats receive gamma (one per 16-row block of a segment; 1 for a whole tensor)
 hipError_t launch_absmean_gamma(const void* W, bool bf16, int64_t N, int64_t K, float* gamma, void* workspace,
-                                hipStream_t stream);
+                                hipStream_t stream, int64_t nout = 1);
+// rb_off / rb_total: the rows are row blocks rb_off ... of a packed matrix of rb_total row blocks (0: all of it)
 hipError_t launch_quantize_weights_2bit(const void* W, bool bf16, int64_t N, int64_t K, void* packed,
-                                        float* gamma, void* workspace, hipStream_t stream);
+                                        float* gamma, void* workspace, hipStream_t stream, int64_t rb_off = 0,
+                                        int64_t rb_total = 0, int64_t nout = 1);
 
 // quant_acts.hip
 hipError_t launch_quantize_acts(const void* x, bool bf16, int64_t M, int64_t K, int8_t* xq, float* sx,
@@ -26,24 +43,26 @@ hipError_t launch_swiglu_quantize(const void* gu, bool bf16, int64_t M, int64_t 
                                   hipStream_t stream);
 
 // linear_ref.hip
+// gstride (all product launchers): 0 = gamma is one float, 1 = gamma[rb] is the scale of 16-row block rb
 hipError_t launch_linear_reference_2bit(const int8_t* xq, const float* sx, const void* packed,
-                                        const float* gamma, int64_t M, int64_t N, int64_t K, void* y,
+                                        const float* gamma, int gstride, int64_t M, int64_t N, int64_t K, void* y,
                                         OutType yt, hipStream_t stream);
 hipError_t launch_unpack_2bit(const void* packed, int64_t N, int64_t K, int8_t* codes, hipStream_t stream);
 
 // linear_gemv.hip
 bool gemv_supports(int64_t M, int64_t N, int64_t K, const void* xq);
 hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void* packed,
-                                   const float* gamma, int64_t M, int64_t N, int64_t K, void* y,
+                                   const float* gamma, int gstride, int64_t M, int64_t N, int64_t K, void* y,
                                    OutType yt, hipStream_t stream);
 bool gemv_fused_supports(int64_t M, int64_t N, int64_t K, const void* x);
-hipError_t launch_linear_fused_2bit(const void* x, bool bf16, const void* packed, const float* gamma, int64_t M,
-                                    int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);
+hipError_t launch_linear_fused_2bit(const void* x, bool bf16, const void* packed, const float* gamma, int gstride,
+                                    int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);
 
 // linear_gemm.hip
 bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq);
 hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
-                                   int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);
+                                   int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt,
+                                   hipStream_t stream);
 
 // trit5.hip
 hipError_t launch_pack_trit5(const void* W, bool bf16, int64_t N, int64_t K, const float* gamma, void* packed,

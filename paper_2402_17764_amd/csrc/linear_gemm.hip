@@ -60,6 +60,8 @@ struct GemmOutCtx {
     char* lds;
     const float* scale_lds;
     void* y;
+    const float* gamma;
+    int gstride, RB;
     int M;
     int64_t N;
     int row0, bn, wave, lane, vec_store;
@@ -79,6 +81,14 @@ __device__ inline void gemm_epilogue(v16i (&acc)[kFM][kGemmFN], const GemmOutCtx
     const int wn = c.wave;
     char* stage_out = c.lds + c.wave * (32 * kGemmPitch32);
     const int64_t n_wave = (int64_t)c.bn * kGemmBN + wn * 64;
+    // with one gamma per row block the lane's weight row (am of fragment fn) picks its own; otherwise the
+    // factor is 1 and the staged scale already carries gamma
+    float gfn[kGemmFN];
+#pragma unroll
+    for (int fn = 0; fn < kGemmFN; ++fn) {
+        const int rb = min((int)((n_wave + fn * 32 + am) / kRowsPerBlock), c.RB - 1);
+        gfn[fn] = c.gstride ? c.gamma[rb] : 1.0f;
+    }
     const int piece = c.lane % lanes_per_row;
     const int64_t n = n_wave + piece * (16 / esz);
 #pragma unroll
@@ -92,8 +102,8 @@ __device__ inline void gemm_epilogue(v16i (&acc)[kFM][kGemmFN], const GemmOutCtx
                 const int a = acc[fm][fn][v] >> 6;                  // drop the decode factor 64 (exact)
                 char* p = stage_out + rl * pitch + (fn * 32 + am) * esz;
                 if (kOut == OutType::I32) *reinterpret_cast<int32_t*>(p) = a;
-                else if (kOut == OutType::F32) *reinterpret_cast<float*>(p) = (float)a * scale;
-                else *reinterpret_cast<uint16_t*>(p) = f32_to_bf16((float)a * scale);
+                else if (kOut == OutType::F32) *reinterpret_cast<float*>(p) = (float)a * (gfn[fn] * scale);
+                else *reinterpret_cast<uint16_t*>(p) = f32_to_bf16((float)a * (gfn[fn] * scale));
             }
         }
         __syncthreads();
@@ -129,7 +139,7 @@ __device__ inline void gemm_epilogue(v16i (&acc)[kFM][kGemmFN], const GemmOutCtx
 template <int kFM>
 __device__ __forceinline__ void gemm_tile(
         const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
-        const float* __restrict__ gamma, int M, int64_t N, int64_t K, int Kq, int RB, int row0, int bn,
+        const float* __restrict__ gamma, int gstride, int M, int64_t N, int64_t K, int Kq, int RB, int row0, int bn,
         void* __restrict__ y, OutType yt, int vec_store) {
 #if defined(__HIP_DEVICE_COMPILE__)      // the buffer-resource builtins exist in the device pass only
     extern __shared__ uint4 smem[];
@@ -150,7 +160,7 @@ __device__ __forceinline__ void gemm_tile(
     // ---- per-token output scale gamma * s_x / 127, once per tile ------------------------------------
     if (threadIdx.x < kGemmBM) {
         const int m = min(row0 + (int)threadIdx.x, M - 1);
-        scale_lds[threadIdx.x] = (gamma[0] * sx[m]) / kQb;
+        scale_lds[threadIdx.x] = gstride ? sx[m] / kQb : (gamma[0] * sx[m]) / kQb;
     }
 
     // ---- A operand, global -> LDS: this wave copies rows 8*kFM*wave .. +8*kFM-1 of the tile, 4 rows per load.
@@ -287,7 +297,7 @@ __device__ __forceinline__ void gemm_tile(
     __syncthreads();                                    // every wave is done with the activation stages
 
     // ---- epilogue: one instantiation per output type, chosen once ---------------------------------------
-    const GemmOutCtx ctx{lds, scale_lds, y, M, N, row0, bn, wave, lane, vec_store};
+    const GemmOutCtx ctx{lds, scale_lds, y, gamma, gstride, RB, M, N, row0, bn, wave, lane, vec_store};
     if (yt == OutType::BF16) gemm_epilogue<OutType::BF16, kFM>(acc, ctx);
     else if (yt == OutType::F32) gemm_epilogue<OutType::F32, kFM>(acc, ctx);
     else gemm_epilogue<OutType::I32, kFM>(acc, ctx);
@@ -298,10 +308,10 @@ __device__ __forceinline__ void gemm_tile(
 template <int kFM>
 __global__ __launch_bounds__(kGemmThreads, 2) void linear_gemm_2bit(
         const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
-        const float* __restrict__ gamma, int M, int64_t N, int64_t K, int Kq, int RB, int tiles_m,
+        const float* __restrict__ gamma, int gstride, int M, int64_t N, int64_t K, int Kq, int RB, int tiles_m,
         void* __restrict__ y, OutType yt, int vec_store) {
     const int b = blockIdx.x;
-    gemm_tile<kFM>(xq, sx, packed, gamma, M, N, K, Kq, RB, (b % tiles_m) * (32 * kFM), b / tiles_m, y, yt, vec_store);
+    gemm_tile<kFM>(xq, sx, packed, gamma, gstride, M, N, K, Kq, RB, (b % tiles_m) * (32 * kFM), b / tiles_m, y, yt, vec_store);
 }
 
 bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
@@ -312,14 +322,11 @@ bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
 
 template <int kFM>
 static hipError_t launch_gemm_tiles(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
-                                    int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(linear_gemm_2bit<kFM>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, gemm_lds_bytes(kFM));
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+                                    int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt,
+                                    hipStream_t stream) {
+    static bool raised[kMaxDevices] = {};
+    const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(linear_gemm_2bit<kFM>), gemm_lds_bytes(kFM), raised);
+    if (e != hipSuccess) return e;
     const int Kq = (int)ceil_div(K, kColsPerQuad);
     const int RB = (int)ceil_div(N, kRowsPerBlock);
     const int tiles_m = (int)ceil_div(M, 32 * kFM);
@@ -327,13 +334,14 @@ static hipError_t launch_gemm_tiles(const int8_t* xq, const float* sx, const voi
     const size_t esz = yt == OutType::BF16 ? 2 : 4;
     const int vec_store = (reinterpret_cast<uintptr_t>(y) % 16 == 0) && ((N * esz) % 16 == 0);
     hipLaunchKernelGGL(linear_gemm_2bit<kFM>, dim3((unsigned)(tiles_m * tiles_n)), dim3(kGemmThreads), gemm_lds_bytes(kFM),
-                       stream, xq, sx, static_cast<const uint4*>(packed), gamma, (int)M, N, K, Kq, RB, tiles_m, y, yt,
+                       stream, xq, sx, static_cast<const uint4*>(packed), gamma, gstride, (int)M, N, K, Kq, RB, tiles_m, y, yt,
                        vec_store);
     return hipGetLastError();
 }
 
 hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
-                                   int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
+                                   int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt,
+                                   hipStream_t stream) {
     // Tile height (32 * kFM tokens) from a cost model fitted to measurements on MI355X:
     //   * a K step of one tile costs about 1000 + 512 kFM cycles (weight decode, loads and barrier are per
     //     tile, the MFMAs grow with its height);
@@ -351,9 +359,9 @@ hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void
         const double cost = (1000.0 + 512.0 * fm) * share;
         if (fm == 4 || cost < 0.97 * best_cost) { best = fm; best_cost = cost; }
     }
-    if (best == 2) return launch_gemm_tiles<2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
-    if (best == 3) return launch_gemm_tiles<3>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
-    return launch_gemm_tiles<4>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
+    if (best == 2) return launch_gemm_tiles<2>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream);
+    if (best == 3) return launch_gemm_tiles<3>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream);
+    return launch_gemm_tiles<4>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream);
 }
 
 }  // namespace bitnet

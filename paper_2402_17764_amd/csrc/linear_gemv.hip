@@ -189,7 +189,8 @@ __device__ inline void fused_quantize_to_lds(const void* __restrict__ xv, const 
 template <int kR, int kS, int kW, int kD, int kX>
 __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
         const void* __restrict__ xin /* x_q, or x for the fused modes */, const float* __restrict__ sx,
-        const uint4* __restrict__ packed, const float* __restrict__ gamma, int M, int64_t N, int64_t K, int Kq, int RB,
+        const uint4* __restrict__ packed, const float* __restrict__ gamma, int gstride /* 0: one gamma, 1: one per row block */,
+        int M, int64_t N, int64_t K, int Kq, int RB,
         int items /* K steps per wave, rounded up to a multiple of kD */, void* __restrict__ y, OutType yt) {
     extern __shared__ uint4 smem[];
     constexpr int kThreads = kS * kW * kWave;
@@ -328,9 +329,9 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
     }
 
     if (r < M) {                                                    // MFMA output column = lane & 15 = token
-        const float scale = (gamma[0] * sc_row) / kQb;
 #pragma unroll
         for (int a = 0; a < kR; ++a) {
+            const float scale = (gamma[gstride * rbc[a]] * sc_row) / kQb;
             const int64_t n0 = (int64_t)(rbw + a) * 16 + 4 * g;     // rows 4 g .. 4 g + 3 of the row block
             if (n0 < N) store_row4(y, yt, (int64_t)r * N + n0, n0, N, acc[a], scale);
         }
@@ -362,7 +363,7 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
 template <int kMT, int kR, int kW, int kS, int kD, int kLx>
 __global__ __launch_bounds__(kS * kW * kWave) void linear_skinny_2bit(
         const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
-        const float* __restrict__ gamma, int M, int64_t N, int64_t K, int Kq, int RB, int spg,
+        const float* __restrict__ gamma, int gstride, int M, int64_t N, int64_t K, int Kq, int RB, int spg,
         void* __restrict__ y, OutType yt) {
 #if defined(__HIP_DEVICE_COMPILE__)      // the buffer-resource builtins exist in the device pass only
     extern __shared__ uint4 smem[];
@@ -504,14 +505,17 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_skinny_2bit(
                     acc[a][t] += fold[(((q * kW + wv) * kR + a) * kMT + t) * kWave + lane];
     }
 
-    const float gm = gamma[0];
+    float gm[kR];
+#pragma unroll
+    for (int a = 0; a < kR; ++a) gm[a] = gamma[gstride * rbc[a]];
 #pragma unroll
     for (int t = 0; t < kMT; ++t) {
         const int m = 16 * t + r;                                      // MFMA output column = token
         if (m >= M) continue;
-        const float scale = yt == OutType::I32 ? 0.0f : (gm * sx[m]) / kQb;
+        const float sxm = yt == OutType::I32 ? 0.0f : sx[m];
 #pragma unroll
         for (int a = 0; a < kR; ++a) {
+            const float scale = (gm[a] * sxm) / kQb;
             const int64_t n0 = (int64_t)(rbw + a) * 16 + 4 * g;
             if (n0 < N) store_row4(y, yt, (int64_t)m * N + n0, n0, N, acc[a][t], scale);
         }
@@ -532,8 +536,8 @@ constexpr size_t kGemvLdsBudget = 65536;
 static size_t gemv16_x_lds_bytes(int64_t M, int64_t K) { return (size_t)M * ceil_div(K, 256) * 256; }
 
 template <int kR, int kS, int kW, int kD>
-static void launch16(int xmode, const void* x, const float* sx, const void* packed, const float* gamma, int64_t M,
-                     int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
+static void launch16(int xmode, const void* x, const float* sx, const void* packed, const float* gamma, int gstride,
+                     int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
     const int Kq = (int)ceil_div(K, kColsPerQuad);
     const int RB = (int)ceil_div(N, kRowsPerBlock);
     int items = (int)ceil_div(ceil_div(K, 256), kS);
@@ -545,7 +549,7 @@ static void launch16(int xmode, const void* x, const float* sx, const void* pack
     const size_t lds = header + (xmode != kXGlobal && lds_x > lds_fold ? lds_x : lds_fold);
     dim3 grid((unsigned)ceil_div(RB, kW * kR)), block(kS * kW * kWave);
     const uint4* p = static_cast<const uint4*>(packed);
-#define GO(X_) hipLaunchKernelGGL((linear_gemv16_2bit<kR, kS, kW, kD, X_>), grid, block, lds, stream, x, sx, p, gamma, (int)M, N, \
+#define GO(X_) hipLaunchKernelGGL((linear_gemv16_2bit<kR, kS, kW, kD, X_>), grid, block, lds, stream, x, sx, p, gamma, gstride, (int)M, N, \
                                   K, Kq, RB, items, y, yt)
     switch (xmode) {
         case kXGlobal: GO(kXGlobal); break;
@@ -557,27 +561,23 @@ static void launch16(int xmode, const void* x, const float* sx, const void* pack
 }
 
 template <int kMT, int kR, int kW, int kS, int kD, int kLx>
-static hipError_t launch_skinny(const int8_t* xq, const float* sx, const void* packed, const float* gamma, int64_t M,
-                                int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
+static hipError_t launch_skinny(const int8_t* xq, const float* sx, const void* packed, const float* gamma, int gstride,
+                                int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
     constexpr size_t lds = (size_t)kS * (kLx + 1) * kMT * 16 * 256;
     static_assert(lds <= 160 * 1024, "activation rings must fit the LDS of a CU");
     static_assert(kS * kW <= 16, "at most 1024 threads per workgroup");
     auto* kern = linear_skinny_2bit<kMT, kR, kW, kS, kD, kLx>;
     if (lds > 65536) {
-        static bool raised = false;                    // the default dynamic-LDS limit is 64 KiB per kernel
-        if (!raised) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            raised = true;
-        }
+        static bool raised[kMaxDevices] = {};
+        const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(kern), (int)lds, raised);
+        if (e != hipSuccess) return e;
     }
     const int Kq = (int)ceil_div(K, kColsPerQuad);
     const int RB = (int)ceil_div(N, kRowsPerBlock);
     const int spg = (int)ceil_div(ceil_div(K, 256), kS);
     dim3 grid((unsigned)ceil_div(RB, kW * kR));
     hipLaunchKernelGGL(kern, grid, dim3(kS * kW * kWave), lds, stream, xq, sx, static_cast<const uint4*>(packed), gamma,
-                       (int)M, N, K, Kq, RB, spg, y, yt);
+                       gstride, (int)M, N, K, Kq, RB, spg, y, yt);
     return hipGetLastError();
 }
 
@@ -589,12 +589,12 @@ static hipError_t launch_skinny(const int8_t* xq, const float* sx, const void* p
 //   * long K with few row blocks: two row blocks per wave, K split four ways, four steps in flight.
 // xmode < 0 (x_q given) lets the shape decide between global and LDS-staged x_q; the fused modes
 // pass their own and need the wide workgroups that can hold token 0 in registers.
-static void dispatch16(int xmode, const void* x, const float* sx, const void* packed, const float* gamma, int64_t M,
-                       int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
+static void dispatch16(int xmode, const void* x, const float* sx, const void* packed, const float* gamma, int gstride,
+                       int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
     const int64_t RB = ceil_div(N, kRowsPerBlock);
     const int64_t steps = ceil_div(K, 256);
     const bool fused = xmode >= 0;
-#define GEMV16(R_, S_, W_, D_, X_) launch16<R_, S_, W_, D_>(fused ? xmode : (X_), x, sx, packed, gamma, M, N, K, y, yt, stream)
+#define GEMV16(R_, S_, W_, D_, X_) launch16<R_, S_, W_, D_>(fused ? xmode : (X_), x, sx, packed, gamma, gstride, M, N, K, y, yt, stream)
     if (RB >= 2048) {
         if (fused) GEMV16(4, 1, 4, 2, kXGlobal); else GEMV16(4, 1, 4, 3, kXGlobal);
     } else if (steps >= 64) {
@@ -610,10 +610,10 @@ static void dispatch16(int xmode, const void* x, const float* sx, const void* pa
 }
 
 hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void* packed,
-                                   const float* gamma, int64_t M, int64_t N, int64_t K, void* y,
+                                   const float* gamma, int gstride, int64_t M, int64_t N, int64_t K, void* y,
                                    OutType yt, hipStream_t stream) {
     if (M <= 4) {
-        dispatch16(-1, xq, sx, packed, gamma, M, N, K, y, yt, stream);
+        dispatch16(-1, xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream);
         return hipGetLastError();
     }
     // More than four tokens: the activations of a step outweigh the weights a wave reads with them, so they
@@ -622,7 +622,7 @@ hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void
     // per workgroup (kW * kR) follow N; with few row blocks the waves split K further instead.  Two steps
     // of prefetch were best throughout.
     const int64_t RB = ceil_div(N, kRowsPerBlock);
-#define SKINNY(...) return launch_skinny<__VA_ARGS__>(xq, sx, packed, gamma, M, N, K, y, yt, stream)
+#define SKINNY(...) return launch_skinny<__VA_ARGS__>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream)
     if (M <= 16) {
         if (RB >= 2048)      SKINNY(1, 4, 4, 2, 2, 2);
         else if (RB >= 1024) SKINNY(1, 3, 2, 4, 2, 2);
@@ -646,9 +646,9 @@ bool gemv_fused_supports(int64_t M, int64_t N, int64_t K, const void* x) {
            kGemvLdsHeader * sizeof(uint4) + gemv16_x_lds_bytes(M, K) <= kGemvLdsBudget;
 }
 
-hipError_t launch_linear_fused_2bit(const void* x, bool bf16, const void* packed, const float* gamma, int64_t M,
-                                    int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
-    dispatch16(bf16 ? kXFusedBf16 : kXFusedF32, x, nullptr, packed, gamma, M, N, K, y, yt, stream);
+hipError_t launch_linear_fused_2bit(const void* x, bool bf16, const void* packed, const float* gamma, int gstride,
+                                    int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
+    dispatch16(bf16 ? kXFusedBf16 : kXFusedF32, x, nullptr, packed, gamma, gstride, M, N, K, y, yt, stream);
     return hipGetLastError();
 }
 

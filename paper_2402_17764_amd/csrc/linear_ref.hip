@@ -25,8 +25,9 @@ __device__ inline void store_out(void* y, OutType yt, int64_t idx, int32_t acc, 
 
 __global__ __launch_bounds__(256) void linear_reference_2bit(const int8_t* __restrict__ xq, const float* __restrict__ sx,
                                                              const uint32_t* __restrict__ packed,
-                                                             const float* __restrict__ gamma, int64_t M, int64_t N,
-                                                             int64_t K, int64_t Kq, int64_t RB, void* __restrict__ y, OutType yt) {
+                                                             const float* __restrict__ gamma, int gstride, int64_t M,
+                                                             int64_t N, int64_t K, int64_t Kq, int64_t RB, void* __restrict__ y,
+                                                             OutType yt) {
     const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t m = blockIdx.y;
     if (n >= N) return;
@@ -41,7 +42,7 @@ __global__ __launch_bounds__(256) void linear_reference_2bit(const int8_t* __res
             else if (code < 0) acc -= xr[k0 + c];
         }
     }
-    const float scale = (gamma[0] * sx[m]) / kQb;
+    const float scale = (gamma[gstride * (n / kRowsPerBlock)] * sx[m]) / kQb;
     store_out(y, yt, m * N + n, acc, scale);
 }
 
@@ -55,7 +56,7 @@ __global__ __launch_bounds__(256) void unpack_2bit(const uint32_t* __restrict__ 
 }
 
 hipError_t launch_linear_reference_2bit(const int8_t* xq, const float* sx, const void* packed,
-                                        const float* gamma, int64_t M, int64_t N, int64_t K, void* y,
+                                        const float* gamma, int gstride, int64_t M, int64_t N, int64_t K, void* y,
                                         OutType yt, hipStream_t stream) {
     const int64_t Kq = ceil_div(K, kColsPerQuad);
     // gridDim.y is limited to 65535: walk M in slabs
@@ -64,7 +65,7 @@ hipError_t launch_linear_reference_2bit(const int8_t* xq, const float* sx, const
         dim3 grid((unsigned)ceil_div(N, 256), (unsigned)mc);
         const size_t ysz = yt == OutType::BF16 ? 2 : 4;
         hipLaunchKernelGGL(linear_reference_2bit, grid, dim3(256), 0, stream, xq + m0 * K, sx + m0,
-                           static_cast<const uint32_t*>(packed), gamma, mc, N, K, Kq, ceil_div(N, kRowsPerBlock),
+                           static_cast<const uint32_t*>(packed), gamma, gstride, mc, N, K, Kq, ceil_div(N, kRowsPerBlock),
                            static_cast<char*>(y) + m0 * N * ysz, yt);
     }
     return hipGetLastError();

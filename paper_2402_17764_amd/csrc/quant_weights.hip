@@ -78,8 +78,9 @@ __global__ __launch_bounds__(kSumThreads) void abs_sum_partials(const T* __restr
 // ---------------------------------------------------------------------------------------------------
 // pass 2
 // ---------------------------------------------------------------------------------------------------
+// gamma[0 .. nout-1] all receive the value (nout > 1: one copy per 16-row block of a segment)
 __global__ __launch_bounds__(kSumThreads) void finish_gamma(const double* __restrict__ partials, int nparts,
-                                                            int64_t count, float* __restrict__ gamma) {
+                                                            int64_t count, float* __restrict__ gamma, int64_t nout) {
     dd acc{0.0, 0.0};
     for (int i = threadIdx.x; i < nparts; i += kSumThreads) {
         dd p{partials[2 * i], partials[2 * i + 1]};
@@ -100,10 +101,9 @@ __global__ __launch_bounds__(kSumThreads) void finish_gamma(const double* __rest
         }
         __syncthreads();
     }
-    if (threadIdx.x == 0) {
-        double S = sh_hi[0] + sh_lo[0];
-        gamma[0] = (float)(S / (double)count);      // Eq. (3); fp64 IEEE division, one rounding to fp32
-    }
+    const double S = sh_hi[0] + sh_lo[0];
+    const float g = (float)(S / (double)count);     // Eq. (3); fp64 IEEE division, one rounding to fp32
+    for (int64_t i = threadIdx.x; i < nout; i += kSumThreads) gamma[i] = g;
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -119,10 +119,12 @@ constexpr int kPackWaves = 16;
 constexpr int kPackThreads = kPackWaves * kWave;          // 1024
 constexpr int kPackColsPerStep = 1024;                    // 16 quads along K per workgroup step
 
+// W, N: the rows being packed (a whole matrix, or one segment of it); they become row blocks rb_off ... of a
+// packed matrix of RB row blocks in all.
 template <typename T, bool kVec>
 __global__ __launch_bounds__(kPackThreads) void ternarize_pack_2bit(const T* __restrict__ W, int64_t N, int64_t K,
                                                                     int64_t Kq /* quads per row */, int64_t RB,
-                                                                    const float* __restrict__ gamma,
+                                                                    int64_t rb_off, const float* __restrict__ gamma,
                                                                     uint32_t* __restrict__ packed) {
     using V = typename Vec4<T>::type;
     __shared__ uint32_t stage[16 * 16 * 4];
@@ -164,7 +166,7 @@ __global__ __launch_bounds__(kPackThreads) void ternarize_pack_2bit(const T* __r
         {
             const int quad = threadIdx.x >> 6;
             const int64_t kq = k0 / kColsPerQuad + quad;
-            if (kq < Kq) packed[quad_index_2bit(kq, rb, 0, Kq, RB) * 4 + (threadIdx.x & 63)] = stage[threadIdx.x];
+            if (kq < Kq) packed[quad_index_2bit(kq, rb + rb_off, 0, Kq, RB) * 4 + (threadIdx.x & 63)] = stage[threadIdx.x];
         }
         __syncthreads();
     }
@@ -177,7 +179,7 @@ int quant_weights_num_partials() { return 2048; }
 
 // Eq. (3): passes 1 and 2, shared by every packing format
 hipError_t launch_absmean_gamma(const void* W, bool bf16, int64_t N, int64_t K, float* gamma, void* workspace,
-                                hipStream_t stream) {
+                                hipStream_t stream, int64_t nout) {
     const int64_t count = N * K;
     double* partials = static_cast<double*>(workspace);
     int64_t want = ceil_div(count, (int64_t)kSumThreads * 16);
@@ -190,19 +192,21 @@ hipError_t launch_absmean_gamma(const void* W, bool bf16, int64_t N, int64_t K, 
     else
         hipLaunchKernelGGL(abs_sum_partials<float>, dim3(blocks), dim3(kSumThreads), 0, stream,
                            static_cast<const float*>(W), count, vec_ok, partials);
-    hipLaunchKernelGGL(finish_gamma, dim3(1), dim3(kSumThreads), 0, stream, partials, blocks, count, gamma);
+    hipLaunchKernelGGL(finish_gamma, dim3(1), dim3(kSumThreads), 0, stream, partials, blocks, count, gamma, nout);
     return hipGetLastError();
 }
 
 hipError_t launch_quantize_weights_2bit(const void* W, bool bf16, int64_t N, int64_t K, void* packed,
-                                        float* gamma, void* workspace, hipStream_t stream) {
-    hipError_t err = launch_absmean_gamma(W, bf16, N, K, gamma, workspace, stream);
+                                        float* gamma, void* workspace, hipStream_t stream, int64_t rb_off,
+                                        int64_t rb_total, int64_t nout) {
+    hipError_t err = launch_absmean_gamma(W, bf16, N, K, gamma, workspace, stream, nout);
     if (err != hipSuccess) return err;
     const size_t esz = bf16 ? 2 : 4;
     const int vec_ok = (reinterpret_cast<uintptr_t>(W) % (4 * esz)) == 0;
 
     const int64_t Kq = ceil_div(K, kColsPerQuad);
-    const int64_t RB = ceil_div(N, kRowsPerBlock);
+    const int64_t RB = ceil_div(N, kRowsPerBlock);                       // row blocks packed by this call
+    const int64_t RBT = rb_total > 0 ? rb_total : RB;                      // ... of the whole packed matrix
     const int64_t steps = ceil_div(Kq * kColsPerQuad, kPackColsPerStep);
     // enough workgroups to fill the chip even for few row blocks: split K across blockIdx.y
     int64_t ysplit = 1;
@@ -212,12 +216,12 @@ hipError_t launch_quantize_weights_2bit(const void* W, bool bf16, int64_t N, int
     uint32_t* out = static_cast<uint32_t*>(packed);
     if (bf16) {
         const uint16_t* w = static_cast<const uint16_t*>(W);
-        if (vec) hipLaunchKernelGGL((ternarize_pack_2bit<uint16_t, true>), grid, dim3(kPackThreads), 0, stream, w, N, K, Kq, RB, gamma, out);
-        else     hipLaunchKernelGGL((ternarize_pack_2bit<uint16_t, false>), grid, dim3(kPackThreads), 0, stream, w, N, K, Kq, RB, gamma, out);
+        if (vec) hipLaunchKernelGGL((ternarize_pack_2bit<uint16_t, true>), grid, dim3(kPackThreads), 0, stream, w, N, K, Kq, RBT, rb_off, gamma, out);
+        else     hipLaunchKernelGGL((ternarize_pack_2bit<uint16_t, false>), grid, dim3(kPackThreads), 0, stream, w, N, K, Kq, RBT, rb_off, gamma, out);
     } else {
         const float* w = static_cast<const float*>(W);
-        if (vec) hipLaunchKernelGGL((ternarize_pack_2bit<float, true>), grid, dim3(kPackThreads), 0, stream, w, N, K, Kq, RB, gamma, out);
-        else     hipLaunchKernelGGL((ternarize_pack_2bit<float, false>), grid, dim3(kPackThreads), 0, stream, w, N, K, Kq, RB, gamma, out);
+        if (vec) hipLaunchKernelGGL((ternarize_pack_2bit<float, true>), grid, dim3(kPackThreads), 0, stream, w, N, K, Kq, RBT, rb_off, gamma, out);
+        else     hipLaunchKernelGGL((ternarize_pack_2bit<float, false>), grid, dim3(kPackThreads), 0, stream, w, N, K, Kq, RBT, rb_off, gamma, out);
     }
     return hipGetLastError();
 }

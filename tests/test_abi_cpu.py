@@ -68,6 +68,18 @@ def test_host_validation_rejects_before_launch():
     assert lib.bitnet_linear(a, a, a, NULL, 1, 16, 64, 0, a, 0, NULL) == 1
     assert lib.bitnet_unpack_weights(a, 4, 4, 0, NULL, NULL) == 1
     assert lib.bitnet_rmsnorm_quantize(NULL, 0, NULL, 0.0, 1, 16, a, a, NULL) == 1
+    i64 = ctypes.c_int64
+    seg_ok = (i64 * 2)(32, 16)
+    seg_ragged = (i64 * 2)(24, 24)       # a segment that is not the last must own whole 16-row blocks
+    seg_short = (i64 * 2)(32, 8)
+    assert lib.bitnet_quantize_weights_segmented(a, 0, 48, 64, 2, seg_ok, 0, a, a, NULL, 1 << 20, NULL) == 1
+    assert lib.bitnet_quantize_weights_segmented(a, 0, 48, 64, 2, seg_ragged, 0, a, a, a, 1 << 20, NULL) == 2
+    assert lib.bitnet_quantize_weights_segmented(a, 0, 48, 64, 2, seg_short, 0, a, a, a, 1 << 20, NULL) == 2
+    assert lib.bitnet_quantize_weights_segmented(a, 0, 48, 64, 0, seg_ok, 0, a, a, a, 1 << 20, NULL) == 2
+    assert lib.bitnet_quantize_weights_segmented(a, 0, 48, 64, 2, seg_ok, 1, a, a, a, 1 << 20, NULL) == 4
+    assert lib.bitnet_quantize_weights_segmented(a, 0, 48, 64, 2, seg_ok, 0, a, a, a, 8, NULL) == 6
+    assert lib.bitnet_linear_segmented(a, a, a, a, 1, 48, 64, 1, a, 0, 0, NULL) == 4          # 5-trit: no segment scales
+    assert lib.bitnet_linear_segmented(a, a, a, NULL, 1, 48, 64, 0, a, 0, 0, NULL) == 1
     assert lib.bitnet_swiglu_quantize(a, 0, 1, 16, NULL, a, NULL) == 1
     # shapes
     assert lib.bitnet_quantize_acts(a, 0, 0, 16, a, a, NULL) == 2

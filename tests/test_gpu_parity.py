@@ -443,6 +443,79 @@ def test_producers_feed_the_product(gpu_lib):
 
 
 # ------------------------------------------------------------------------------------------------
+# one gamma per row segment (merged projections keep the scale of each original matrix, Eq. (3))
+# ------------------------------------------------------------------------------------------------
+def _segmented_reference(W, x, seg_rows):
+    xq, sx = oracle.quantize_acts(x)
+    codes, gammas, y_parts = [], [], []
+    r0 = 0
+    for rows in seg_rows:
+        c, g = oracle.quantize_weights(W[r0:r0 + rows])
+        codes.append(c)
+        gammas.append(g)
+        r0 += rows
+    codes = np.vstack(codes)
+    acc = oracle.ternary_matmul(xq, codes)
+    y = np.empty(acc.shape, np.float64)
+    gamma_rb = np.empty((W.shape[0] + 15) // 16, np.float32)
+    r0 = 0
+    for rows, g in zip(seg_rows, gammas):
+        y[:, r0:r0 + rows] = oracle.rescale(np.ascontiguousarray(acc[:, r0:r0 + rows]), g, sx)
+        gamma_rb[r0 // 16:(r0 + rows + 15) // 16] = g
+        r0 += rows
+    return dict(xq=xq, sx=sx, codes=codes, acc=acc, y=y, gamma_rb=gamma_rb)
+
+
+SEGMENT_CASES = [  # (M, K, segment rows): every product kernel, ragged last segment, unequal segments
+    (1, 528, [160, 48, 45]), (3, 272, [16, 16, 16, 16, 7]), (9, 1040, [4096, 1024, 1024]), (40, 528, [320, 64, 64]),
+    (64, 2048, [8192, 8200]), (100, 272, [256, 256, 250]), (300, 528, [1280, 2560]), (1, 80, [33]),
+]
+
+
+@pytest.mark.parametrize("M,K,seg_rows", SEGMENT_CASES)
+def test_segmented_gamma_matches_oracle(gpu_lib, M, K, seg_rows):
+    say("segmented M=%d K=%d segs=%s" % (M, K, seg_rows))
+    N = sum(seg_rows)
+    W = synth.weights(N, K, config=0, layer=len(seg_rows), tensor=9)
+    r0 = 0
+    for i, rows in enumerate(seg_rows):          # segments of different magnitude, so that one gamma would be wrong
+        W[r0:r0 + rows] *= np.float32(1.0 + 0.75 * i)
+        r0 += rows
+    x = synth.activations(M, K, config=0, layer=len(seg_rows), tensor=10)
+    ref = _segmented_reference(W, x, seg_rows)
+    packed, gamma_rb = gpu_lib.quantize_weights_segmented(dev(W), seg_rows)
+    assert gamma_rb.cpu().numpy().tobytes() == ref["gamma_rb"].tobytes()
+    assert np.array_equal(gpu_lib.unpack_weights(packed, N, K).cpu().numpy(), ref["codes"])
+    xq, sx = gpu_lib.quantize_acts(dev(x))
+    kernels = [gpu_lib.KERNEL_AUTO, gpu_lib.KERNEL_REFERENCE, gpu_lib.KERNEL_GEMM]
+    if M <= 64:
+        kernels.append(gpu_lib.KERNEL_GEMV)
+    for kern in kernels:
+        acc = gpu_lib.linear_segmented(xq, sx, packed, gamma_rb, N, y_dtype=gpu_lib.I32, kernel=kern)
+        assert np.array_equal(acc.cpu().numpy(), ref["acc"])
+        y32 = gpu_lib.linear_segmented(xq, sx, packed, gamma_rb, N, y_dtype=gpu_lib.F32, kernel=kern)
+        check_y(y32.cpu().numpy(), ref["y"], RTOL_F32)
+        y16 = gpu_lib.linear_segmented(xq, sx, packed, gamma_rb, N, y_dtype=gpu_lib.BF16, kernel=kern)
+        check_y(y16.float().cpu().numpy(), ref["y"], RTOL_BF16)
+    if M <= 16:
+        yf = gpu_lib.linear_fused_segmented(dev(x), packed, gamma_rb, N, y_dtype=gpu_lib.F32)
+        check_y(yf.cpu().numpy(), ref["y"], RTOL_F32)
+
+
+def test_segmented_with_one_segment_equals_plain(gpu_lib):
+    say("segmented, one segment")
+    N, K, M = 1000, 528, 5
+    W = synth.weights(N, K, config=0, layer=3, tensor=11)
+    x = synth.activations(M, K, config=0, layer=3, tensor=12)
+    p1, g1 = gpu_lib.quantize_weights(dev(W))
+    p2, grb = gpu_lib.quantize_weights_segmented(dev(W), [N])
+    assert torch.equal(p1, p2)
+    assert torch.equal(grb, g1.expand(grb.numel()))
+    xq, sx = gpu_lib.quantize_acts(dev(x))
+    assert torch.equal(gpu_lib.linear(xq, sx, p1, g1, N), gpu_lib.linear_segmented(xq, sx, p2, grb, N))
+
+
+# ------------------------------------------------------------------------------------------------
 # the 5-trits-per-byte format
 # ------------------------------------------------------------------------------------------------
 TRIT_WEIGHT_SHAPES = [(4096, 1536), (16, 320), (1, 1), (37, 129), (100, 70), (17, 1000), (250, 4100)]
