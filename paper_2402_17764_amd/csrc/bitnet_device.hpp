@@ -82,6 +82,24 @@ __device__ inline uint32_t ternary_code2(float w, float d) {
     return ((uint32_t)(int)r) & 3u;         // -1 -> 0b11, 0 -> 0b00, +1 -> 0b01
 }
 
+// Eq. (1)-(2) without a division per weight.  For w > 0, RoundClip(w / d, -1, 1) = 1 exactly when the fp32
+// quotient fl(w / d) exceeds 0.5 (a quotient of exactly 0.5 rounds to the even integer 0, anything from 1.5 up is
+// clipped to 1), and fl(w / d) is monotone in w; so the code is +1 from a threshold T(d) upward, and by the
+// odd symmetry of division and rounding -1 from -T downward.  T is found with the same fp32 division, starting
+// at d / 2 (exactly 0.5 after the division) and stepping through neighbouring floats.
+__device__ inline float ternary_threshold(float d) {
+    float t = 0.5f * d;
+#pragma unroll 1
+    for (int i = 0; i < 8 && !(t / d > 0.5f); ++i) t = __uint_as_float(__float_as_uint(t) + 1u);
+#pragma unroll 1
+    for (int i = 0; i < 8 && (__uint_as_float(__float_as_uint(t) - 1u) / d > 0.5f); ++i)
+        t = __uint_as_float(__float_as_uint(t) - 1u);
+    return t;
+}
+__device__ inline uint32_t ternary_code2_threshold(float w, float t) {
+    return w >= t ? 1u : (w <= -t ? 3u : 0u);           // +1 -> 0b01, -1 -> 0b11, 0 -> 0b00
+}
+
 // index of the quad holding row 16*rb + r, columns 64*kq .. 64*kq+63 (Kq quads per row, RB row blocks):
 // steps of four quad columns are outermost, row blocks next, then the quad column and the row.
 __host__ __device__ inline int64_t quad_index_2bit(int64_t kq, int64_t rb, int r, int64_t Kq, int64_t RB) {

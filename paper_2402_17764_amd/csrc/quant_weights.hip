@@ -43,12 +43,30 @@ __global__ __launch_bounds__(kSumThreads) void abs_sum_partials(const T* __restr
     if (vec_ok) {
         const int64_t nvec = count / 4;
         const V* Wv = reinterpret_cast<const V*>(W);
-        for (int64_t i = tid; i < nvec; i += nthreads) {
+        // four loads in flight per thread and four independent accumulators: the sums are exact, so the
+        // split changes nothing but the bytes in flight and the length of the dependent chains
+        dd part[4] = {{0.0, 0.0}, {0.0, 0.0}, {0.0, 0.0}, {0.0, 0.0}};
+        int64_t i = tid;
+        for (; i + 3 * nthreads < nvec; i += 4 * nthreads) {
+            V v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = Wv[i + u * nthreads];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float f[4];
+                Vec4<T>::widen(v[u], f);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) dd_add_double(part[e], (double)fabsf(f[e]));
+            }
+        }
+        for (; i < nvec; i += nthreads) {
             float f[4];
             Vec4<T>::widen(Wv[i], f);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) dd_add_double(acc, (double)fabsf(f[e]));
+            for (int e = 0; e < 4; ++e) dd_add_double(part[e], (double)fabsf(f[e]));
         }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) dd_add_dd(acc, part[e]);
         done = nvec * 4;
     }
     for (int64_t i = done + tid; i < count; i += nthreads) dd_add_double(acc, (double)fabsf(widen1(W[i])));
@@ -133,6 +151,7 @@ __global__ __launch_bounds__(kPackThreads) void ternarize_pack_2bit(const T* __r
     const int64_t rb = blockIdx.x;
     const int64_t n = rb * kRowsPerBlock + r;
     const float d = gamma[0] + kEps;                       // gamma + eps, one fp32 add (Eq. (1))
+    const float thr = ternary_threshold(d);                // |w| >= thr  <=>  RoundClip(w / d) = +-1
     const T* row = W + n * K;
     const int i = lane & 3;
 
@@ -153,7 +172,7 @@ __global__ __launch_bounds__(kPackThreads) void ternarize_pack_2bit(const T* __r
             }
             uint32_t w = 0;
 #pragma unroll
-            for (int b = 0; b < 4; ++b) w |= ternary_code2(f[b], d) << (8 * b + 2 * i);
+            for (int b = 0; b < 4; ++b) w |= ternary_code2_threshold(f[b], thr) << (8 * b + 2 * i);
             w = quad_or(w);
             if (i == 0) {
                 const int quad = 4 * t + (lane >> 4);      // which of the 16 quads of this step
