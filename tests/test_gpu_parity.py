@@ -336,6 +336,35 @@ def test_linear_gemm_full_size_sampled(gpu_lib, M, N, K, layer):
         assert torch.equal(a_ref, a_full[sub])
 
 
+def test_random_shapes_every_kernel_agrees(gpu_lib):
+    """48 seeded shapes drawn across the kernel-selection boundaries (tokens 1..300, rows 1..6000, K a multiple
+    of 16 up to 4096): every product kernel that accepts the shape returns the reference kernel's int32
+    accumulators bit for bit, and every eighth shape is also recomputed by the oracle."""
+    rng = np.random.default_rng(2402)
+    for case in range(48):
+        M = int(rng.choice([1, 2, 4, 5, 8, 16, 17, 31, 32, 33, 63, 64, 65, 96, 97, 128, 200, 300]))
+        N = int(rng.integers(1, 6001))
+        K = 16 * int(rng.integers(1, 257))
+        say("random shape %d: M=%d N=%d K=%d" % (case, M, N, K))
+        W = synth.weights(N, K, config=0, layer=case, tensor=13)
+        x = synth.activations(M, K, config=0, layer=case, tensor=14)
+        packed, gamma = gpu_lib.quantize_weights(dev(W))
+        xq, sx = gpu_lib.quantize_acts(dev(x))
+        ref_acc = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.I32, kernel=gpu_lib.KERNEL_REFERENCE)
+        kernels = [gpu_lib.KERNEL_AUTO, gpu_lib.KERNEL_GEMM] + ([gpu_lib.KERNEL_GEMV] if M <= 64 else [])
+        for kern in kernels:
+            acc = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.I32, kernel=kern)
+            assert torch.equal(acc, ref_acc), (M, N, K, kern)
+        if M <= 16:
+            yf = gpu_lib.linear_fused(dev(x), packed, gamma, N, y_dtype=gpu_lib.I32)
+            assert torch.equal(yf, ref_acc), (M, N, K, "fused")
+        if case % 8 == 0:
+            o = oracle.bitlinear(x, W)
+            assert np.array_equal(ref_acc.cpu().numpy(), o["acc"])
+            y32 = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.F32)
+            check_y(y32.cpu().numpy(), o["y"], RTOL_F32)
+
+
 # ------------------------------------------------------------------------------------------------
 # producers of int8 activations: RMSNorm -> int8, SwiGLU -> int8 (bit-exact codes and scales)
 # ------------------------------------------------------------------------------------------------
