@@ -4,6 +4,7 @@ hipcc cross-compiles without a GPU.  Objects go to paper_2402_17764_amd/_build/ 
 the shared library sits next to this file so that it travels with the tree.
 """
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -26,14 +27,39 @@ FLAGS = [
 ]
 
 
+# Kernels that count the vector-memory loads in flight (explicit s_waitcnt vmcnt(n)): a register spill would
+# add scratch loads to that count, so the build fails if the compiler gives any of them scratch memory.
+NO_SCRATCH = {"linear_gemv.hip": "linear_skinny_2bit"}
+
+
+def _check_no_scratch(src, stderr):
+    """stderr holds -Rpass-analysis=kernel-resource-usage remarks: 'Function Name: <mangled>' ... 'ScratchSize ...: n'."""
+    name, bad = None, []
+    for line in stderr.splitlines():
+        if "Function Name:" in line:
+            name = line.split("Function Name:")[1].split()[0]
+        elif "ScratchSize" in line and name and NO_SCRATCH[src] in name:
+            if int(line.split("]:")[1].split()[0]) != 0:
+                bad.append(name)
+    if bad:
+        raise RuntimeError("%s: kernels that count loads in flight must not spill: %s" % (src, ", ".join(bad)))
+
+
 def _compile(src):
     obj = os.path.join(BUILD, os.path.splitext(src)[0] + ".o")
     cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    if src in NO_SCRATCH:
+        cmd.append("-Rpass-analysis=kernel-resource-usage")
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
-    err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
+    lines = [l for l in r.stderr.splitlines() if noise not in l]
+    if src in NO_SCRATCH:                      # drop the resource remarks and the source excerpts printed under them
+        lines = [l for l in lines if "remark:" not in l and not re.match(r"^\s*\d*\s*\|", l)]
+    err = "\n".join(lines)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed on %s:\n%s" % (src, err))
+    if src in NO_SCRATCH:
+        _check_no_scratch(src, r.stderr)
     if err.strip():
         sys.stderr.write(err + "\n")
     return obj

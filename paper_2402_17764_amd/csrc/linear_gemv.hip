@@ -360,6 +360,8 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
 // explicit s_waitcnt with that count retires the copy without draining the prefetch behind it.  The
 // scheduling fences keep the compiler from moving loads across the counted wait; the barrier is the
 // bare instruction because a fence-carrying barrier makes the compiler wait for every LDS-DMA load.
+// The count holds only while the loop issues no other vector-memory instruction, i.e. while nothing spills:
+// the build checks that every instantiation compiles without scratch memory.
 template <int kMT, int kR, int kW, int kS, int kD, int kLx>
 __global__ __launch_bounds__(kS * kW * kWave) void linear_skinny_2bit(
         const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
