@@ -304,9 +304,10 @@ __device__ __forceinline__ void gemm_tile(
 #endif
 }
 
-// Consecutive workgroups take consecutive token tiles of the same weight tile (see the header).
+// Consecutive workgroups take consecutive token tiles of the same weight tile (see the header).  Two workgroups
+// per CU (three with 64-token tiles, whose waves need fewer registers).
 template <int kFM>
-__global__ __launch_bounds__(kGemmThreads, 2) void linear_gemm_2bit(
+__global__ __launch_bounds__(kGemmThreads, kFM == 2 ? 3 : 2) void linear_gemm_2bit(
         const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
         const float* __restrict__ gamma, int gstride, int M, int64_t N, int64_t K, int Kq, int RB, int tiles_m,
         void* __restrict__ y, OutType yt, int vec_store) {
@@ -342,21 +343,22 @@ static hipError_t launch_gemm_tiles(const int8_t* xq, const float* sx, const voi
 hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                    int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt,
                                    hipStream_t stream) {
-    // Tile height (32 * kFM tokens) from a cost model fitted to measurements on MI355X:
-    //   * a K step of one tile costs about 1000 + 512 kFM cycles (weight decode, loads and barrier are per
-    //     tile, the MFMAs grow with its height);
-    //   * up to 256 tiles every workgroup has a CU to itself; two workgroups sharing a CU each run about 1.9x
-    //     slower, so up to 512 tiles the launch takes 1.9 tile times, and beyond that 1.9 per 512 tiles (a
-    //     partly filled last round costs little, because its workgroups run alone).
-    // 13B down projection at M = 2048 (N = 5120): 320 tiles of 128 tokens 150 us, 440 tiles of 96 tokens 126 us;
-    // M = 512, N = 5120: 80 tiles of 128 tokens 38 us, fewer tokens per tile spread the work over more CUs.
+    // Tile height (32 * kFM tokens) from a cost model fitted to measurements on MI355X (M = 512 and 2048 on the
+    // four 13B shapes, every height):
+    //   * with at most one tile per CU the launch takes one tile's latency, which shrinks with its height
+    //     (1.05 : 0.87 : 0.73 for 128 : 96 : 64 tokens);
+    //   * with more, the CUs are saturated and a tile costs its share of the MFMA work (1 : 0.77 : 0.50), times
+    //     the largest number of tiles that any CU gets (tiles are dealt round-robin).
+    // Ties within 3 % go to the taller tile (less decode work per token).  Examples: 13B down projection at
+    // M = 2048 (N = 5120): 320 tiles of 128 tokens 150 us, 440 tiles of 96 tokens 126 us; M = 512, N = 5120: 36 us
+    // with 128-token tiles, 25 us with 64-token tiles.
     const int64_t tiles_n = ceil_div(N, kGemmBN);
+    static const double kSaturated[5] = {0, 0, 0.504, 0.773, 1.0}, kAlone[5] = {0, 0, 0.729, 0.872, 1.052};
     int best = 4;
     double best_cost = 0.0;
     for (int fm = 4; fm >= 2; --fm) {
-        const double tiles = (double)(ceil_div(M, 32 * fm) * tiles_n);
-        const double share = tiles <= 256.0 ? 1.0 : tiles <= 512.0 ? 1.9 : 1.9 * tiles / 512.0;
-        const double cost = (1000.0 + 512.0 * fm) * share;
+        const int64_t tiles = ceil_div(M, 32 * fm) * tiles_n;
+        const double cost = tiles <= 256 ? kAlone[fm] : kSaturated[fm] * (double)ceil_div(tiles, (int64_t)256);
         if (fm == 4 || cost < 0.97 * best_cost) { best = fm; best_cost = cost; }
     }
     if (best == 2) return launch_gemm_tiles<2>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream);
