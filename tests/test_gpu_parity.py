@@ -609,21 +609,27 @@ def test_trit5_is_rejected_where_unsupported(gpu_lib):
     assert e.value.status == 8
 
 
-def test_linear_extreme_accumulators(gpu_lib):
-    """Every product at +-127 with all-(+1) / all-(-1) rows: the largest accumulators a shape can give."""
-    say("linear extreme accumulators")
-    M, N, K = 2, 32, 28672
+@pytest.mark.parametrize("M,K", [(2, 28672), (2, 262144), (20, 262144), (70, 262144)])
+def test_linear_extreme_accumulators(gpu_lib, M, K):
+    """Every product at +-127 with all-(+1) / all-(-1) rows: the largest accumulators a shape can give, up to the
+    largest K the library accepts (262144: 64 * 127 * K is the last value below 2^31 that the kernels' scaled
+    accumulators must hold), on the M <= 4, skinny and MFMA paths."""
+    say("linear extreme accumulators M=%d K=%d" % (M, K))
+    N = 32
     W = np.ones((N, K), np.float32)
     W[1::2] = -1.0
     x = np.full((M, K), 3.0, np.float32)
-    x[1] = -3.0
+    x[1::2] = -3.0
     ref = oracle.bitlinear(x, W)
     assert abs(int(ref["acc"][0, 0])) == 127 * K
     packed, gamma = gpu_lib.quantize_weights(dev(W))
     xq, sx = gpu_lib.quantize_acts(dev(x))
-    for kern in (gpu_lib.KERNEL_REFERENCE, gpu_lib.KERNEL_GEMV, gpu_lib.KERNEL_GEMM):
+    for kern in (gpu_lib.KERNEL_REFERENCE, gpu_lib.KERNEL_GEMM) + ((gpu_lib.KERNEL_GEMV,) if M <= 64 else ()):
         acc = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.I32, kernel=kern)
         assert np.array_equal(acc.cpu().numpy(), ref["acc"])
+    with pytest.raises(gpu_lib.BitnetError) as e:            # one column more than the accumulators can take
+        gpu_lib.packed_bytes(N, K + 16) if K == 262144 else gpu_lib.packed_bytes(0, K)
+    assert e.value.status == 2
 
 
 def test_linear_is_deterministic(gpu_lib):
