@@ -86,8 +86,10 @@ typedef enum bitnet_dtype {
  *   (So one table look-up per byte yields four consecutive codes, i.e. one 32-bit MFMA operand
  *   register, and the sixteen fifth digits of a quad form the operand of a fifth MFMA.)
  *   Size: Np * Kp / 5 bytes.  Supported by bitnet_quantize_weights, bitnet_unpack_weights and
- *   bitnet_linear (weight-streaming kernel for M <= 16, reference kernel above); bitnet_linear_fused
- *   and the MFMA prefill kernel take the 2-bit format only.
+ *   bitnet_linear (weight-streaming kernel for 16 tokens at a time: more tokens re-stream the weights per
+ *   group of 16, so this is a storage format rather than a prefill one; the reference kernel serves shapes
+ *   the streaming kernel cannot); bitnet_linear_fused, the per-segment scales and the MFMA prefill kernel
+ *   take the 2-bit format only.
  */
 typedef enum bitnet_format {
     BITNET_PACK_2BIT = 0,

@@ -143,7 +143,18 @@ static bitnet_status linear_any(const int8_t* xq, const float* sx, const void* p
 
     if (f == BITNET_PACK_TRIT5) {
         if (gstride) return BITNET_ERR_FORMAT;         // per-segment scales exist for the 2-bit format only
-        // the 5-trit format has the reference kernel and the weight-streaming kernel for M <= 16
+        // the 5-trit format has the reference kernel and the weight-streaming kernel for M <= 16; more tokens
+        // are walked 16 at a time (the weights are streamed once per group: a storage format, not a prefill one)
+        if (which == BITNET_KERNEL_AUTO && M > 16 && bitnet::gemv_trit5_supports(16, N, K, xq)) {
+            const size_t ysz = dtype_size(y_dtype);
+            for (int64_t m0 = 0; m0 < M; m0 += 16) {
+                const int64_t mc = M - m0 < 16 ? M - m0 : 16;
+                const hipError_t e = bitnet::launch_linear_gemv_trit5(xq + m0 * K, sx + m0, packed, gamma, mc, N, K,
+                                                                      static_cast<char*>(y) + m0 * N * ysz, yt, s);
+                if (e != hipSuccess) return BITNET_ERR_HIP;
+            }
+            return BITNET_OK;
+        }
         if (which == BITNET_KERNEL_AUTO)
             which = bitnet::gemv_trit5_supports(M, N, K, xq) ? BITNET_KERNEL_GEMV : BITNET_KERNEL_REFERENCE;
         if (which == BITNET_KERNEL_REFERENCE)
