@@ -335,8 +335,8 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the weight_quant and large-shape legs")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (the hot path is a single-GPU kernel; "
-              "see DESIGN.md for how it would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the hot path is a single-GPU kernel; it would shard along "
+              "the output features with no collective on the path); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
