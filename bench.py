@@ -333,6 +333,9 @@ def main():
                     help="also run a plain 256 MiB device copy (torch copy_) three times, so that a rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE run of this command contains a kernel of known traffic to scale by")
     ap.add_argument("--no-extras", action="store_true", help="skip the weight_quant and large-shape legs")
+    ap.add_argument("--only", default=None,
+                    choices=["gemm_m2048", "gemv_70b_m1", "batched_decode_7b", "decoder_chain_3b_m1"],
+                    help="run one of the extra legs alone and print only its result (profiling a single kernel family)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (the hot path is a single-GPU kernel; it would shard along "
@@ -359,6 +362,16 @@ def main():
     shapes = cfg["shapes"]
     gen = torch.Generator(device="cuda")
     gen.manual_seed(240217764)
+
+    if args.only:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        legs = {"gemm_m2048": lambda: gemm_leg(torch, B, synth, gen, args),
+                "gemv_70b_m1": lambda: large_gemv_leg(torch, B, synth, gen, side, args),
+                "batched_decode_7b": lambda: batched_decode_leg(torch, B, synth, gen, side, args),
+                "decoder_chain_3b_m1": lambda: decoder_block_leg(torch, B, synth, gen, side, args)}
+        print(json.dumps({"only": args.only, "steps": args.steps, "warmup": args.warmup, args.only: legs[args.only]()}))
+        return
 
     # ---- weights: draw, quantize + pack through the library (timed per call with events) ----------
     packed, wq_ms, wq_bytes = {}, 0.0, 0

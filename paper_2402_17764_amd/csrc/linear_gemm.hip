@@ -252,6 +252,7 @@ __device__ __forceinline__ void gemm_tile(
             const int cur = t & 1, nxt = cur ^ 1;
             __builtin_amdgcn_sched_barrier(0);          // slices stay in order: no hoisting of later LDS reads
             if (t < 7) read_a(a[nxt], t + 1);
+            __builtin_amdgcn_sched_barrier(0);          // ... and no sinking: the reads lead their use by a whole slice
             constexpr int kMfmas = kFM * kGemmFN, kRegs = 4 * kGemmFN;
 #pragma unroll
             for (int q = 0; q < kMfmas; ++q) {
