@@ -150,7 +150,7 @@ __device__ __forceinline__ void gemm_tile(
     float* scale_lds = reinterpret_cast<float*>(lds + gemm_scale_offset(kFM));
 
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);    // scalar: LDS-DMA targets need no per-step broadcast
     const int wn = wave;
     const int steps = (Kq + 3) >> 2;
     const int full_steps = (int)(K >> 8);           // steps whose 256 columns all exist
@@ -180,12 +180,12 @@ __device__ __forceinline__ void gemm_tile(
     const int a_row_base = am * 256;                                 // + fm * 8192
     // ---- B operand: fragment fn covers row blocks 2*fn, 2*fn+1 of this wave's 4
     const int brow = lane & 15, bsel = (lane >> 4) & 1;
-    uint32_t woff[kGemmFN][2];                                      // quad offsets inside a whole step
+    uint32_t woff[kGemmFN][2];                                      // byte offsets of the lane's quads inside a whole step
 #pragma unroll
     for (int fn = 0; fn < kGemmFN; ++fn)
 #pragma unroll
         for (int h = 0; h < 2; ++h)
-            woff[fn][h] = (uint32_t)min(bn * 16 + wn * 4 + fn * 2 + bsel, RB - 1) * 64u + (uint32_t)((kg + 2 * h) * 16 + brow);
+            woff[fn][h] = ((uint32_t)min(bn * 16 + wn * 4 + fn * 2 + bsel, RB - 1) * 64u + (uint32_t)((kg + 2 * h) * 16 + brow)) * 16u;
 
     v16i acc[kFM][kGemmFN];
 #pragma unroll
@@ -195,24 +195,34 @@ __device__ __forceinline__ void gemm_tile(
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[fm][fn][v] = 0;
 
-    // The tile's activation rows as a raw buffer.  The whole byte offset travels in the vector offset,
-    // the operand the hardware range check is certain to cover, so reads past the end of x_q return
-    // zero (in the partial last step the columns past K meet zero codes, whatever they hold).
-    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<int8_t*>(xtile), 0, (int)min((int64_t)rows_here * K, (int64_t)0x7FFFFFFF), 0x00020000);
+    // Per K step both operands are addressed as "scalar base of the step + fixed per-lane byte offset".  For
+    // the activations that is a raw buffer whose base advances with the step (scalar arithmetic only) and whose
+    // size shrinks with it, so the hardware range check still ends at the last byte of the tile's x_q rows
+    // (reads past it return zero; in the partial last step the columns past K meet zero codes, whatever they
+    // hold).
+    const int64_t xbytes = (int64_t)rows_here * K;
     auto copy_x = [&](int step, int stage) {
+        const int64_t left = xbytes - (int64_t)step * 256;
+        const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<int8_t*>(xtile + (int64_t)step * 256), 0, (int)min(left, (int64_t)0x7FFFFFFF), 0x00020000);
         char* dst_stage = lds + stage * kGemmStageBytes;
 #pragma unroll
         for (int t = 0; t < kCopies; ++t)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (__attribute__((address_space(3))) void*)(dst_stage + (wave * (4 * kCopies) + t * 4) * 256),
-                                                     16, xoff[t] + (uint32_t)step * 256u, 0, 0, 0);
+                                                     16, xoff[t], 0, 0, 0);
     };
+    // For the weights a raw buffer per step as well: one whole step of the packed layout (RB KiB), the lane's
+    // byte offset in it as the vector offset -- no 64-bit address arithmetic per load.
     auto load_w = [&](uint4 (&wq)[kGemmFN][2], int step) {
-        const uint4* src = packed + (int64_t)step * wstride;
+        const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint4*>(packed + (int64_t)step * wstride), 0, (int)(wstride * 16), 0x00020000);
 #pragma unroll
         for (int h = 0; h < 2; ++h)
 #pragma unroll
-            for (int fn = 0; fn < kGemmFN; ++fn) wq[fn][h] = src[woff[fn][h]];
+            for (int fn = 0; fn < kGemmFN; ++fn) {
+                const v4i q = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, (int)woff[fn][h], 0, 0));
+                wq[fn][h] = make_uint4((uint32_t)q.x, (uint32_t)q.y, (uint32_t)q.z, (uint32_t)q.w);
+            }
     };
     // the partial last step: its chunks hold fewer quads; lanes past them are clamped here and masked in compute()
     auto load_w_tail = [&](uint4 (&wq)[kGemmFN][2], int step) {
@@ -284,10 +294,11 @@ __device__ __forceinline__ void gemm_tile(
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
         // move the step's quads out of the landing registers; lanes past a partial last step are zeroed here
-        const bool tail = s >= full_steps;
+        const uint32_t all = s >= full_steps ? 0u : 0xFFFFFFFFu;   // uniform
+        const uint32_t keep_h[2] = {keep_t0 | all, keep_t1 | all};
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            const uint32_t keep = !tail ? 0xFFFFFFFFu : (h ? keep_t1 : keep_t0);
+            const uint32_t keep = keep_h[h];
 #pragma unroll
             for (int fn = 0; fn < kGemmFN; ++fn)
                 wq[fn][h] = make_uint4(wnext[fn][h].x & keep, wnext[fn][h].y & keep, wnext[fn][h].z & keep, wnext[fn][h].w & keep);
@@ -317,9 +328,9 @@ __global__ __launch_bounds__(kGemmThreads, kFM == 2 ? 3 : 2) void linear_gemm_2b
 }
 
 bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
-    (void)N;
-    // per-lane activation offsets are 32-bit and relative to the tile's first row: 256 * K must fit
-    return M >= 1 && K % 16 == 0 && reinterpret_cast<uintptr_t>(xq) % 16 == 0;
+    // per-lane activation offsets are 32-bit and relative to the tile's first row (128 * K fits for every K the
+    // library accepts); one K step of the packed weights (1 KiB per 16-row block) is addressed as one raw buffer
+    return M >= 1 && K % 16 == 0 && reinterpret_cast<uintptr_t>(xq) % 16 == 0 && ceil_div(N, kRowsPerBlock) < ((int64_t)1 << 21);
 }
 
 template <int kFM>
