@@ -38,6 +38,16 @@ __device__ inline v4i decode_word(uint32_t w) {
     return a;
 }
 
+// the same with the lane's validity folded into the constant: km is 0xC0C0C0C0 or 0
+__device__ inline v4i decode_word_masked(uint32_t w, uint32_t km) {
+    v4i a;
+    a.x = (int)((w << 6) & km);
+    a.y = (int)((w << 4) & km);
+    a.z = (int)((w << 2) & km);
+    a.w = (int)(w & km);
+    return a;
+}
+
 __device__ inline v4i as_v4i(const uint4& u) {
     v4i a;
     a.x = (int)u.x; a.y = (int)u.y; a.z = (int)u.z; a.w = (int)u.w;
@@ -382,7 +392,7 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_skinny_2bit(
     char* lds = reinterpret_cast<char*>(smem);
 
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: LDS-DMA targets need no broadcast
     const int ks = wave / kW, wv = wave - ks * kW;     // K group, wave within the group
     const int r = lane & 15, g = lane >> 4;
     const int steps = (Kq + 3) >> 2;
@@ -413,15 +423,27 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_skinny_2bit(
                 16, xoff[t] + (uint32_t)i * 256u, 0, 0, 0);
     };
 
+    // weight quads: one K step of the packed layout as a raw buffer (scalar base per step) plus a 32-bit byte
+    // offset per lane; a row block's chunk is 64 quads in a whole step, tail_quads in a partial last one, and
+    // lanes past it are clamped here and masked in compute()
     int rbc[kR];
+    uint32_t woff_full[kR], woff_tail[kR];
 #pragma unroll
-    for (int a = 0; a < kR; ++a) rbc[a] = min(rbw + a, RB - 1);
+    for (int a = 0; a < kR; ++a) {
+        rbc[a] = min(rbw + a, RB - 1);
+        woff_full[a] = ((uint32_t)rbc[a] * 64u + (uint32_t)lane) * 16u;
+        woff_tail[a] = ((uint32_t)rbc[a] * (uint32_t)tail_quads + (uint32_t)min(lane, tail_quads - 1)) * 16u;
+    }
     auto load_w = [&](uint4 (&w)[kR], int i) {
         const int sl = min(s_begin + i, steps - 1);                    // past the end: redirected, masked below
-        const int cq = sl == steps - 1 ? tail_quads : 64;
-        const int ln = min(lane, cq - 1);
+        const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint4*>(packed + (int64_t)sl * wstride), 0, (int)(wstride * 16), 0x00020000);
+        const bool tail = sl == steps - 1;
 #pragma unroll
-        for (int a = 0; a < kR; ++a) w[a] = packed[(int64_t)sl * wstride + (int64_t)rbc[a] * cq + ln];
+        for (int a = 0; a < kR; ++a) {
+            const v4i q = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, (int)(tail ? woff_tail[a] : woff_full[a]), 0, 0));
+            w[a] = make_uint4((uint32_t)q.x, (uint32_t)q.y, (uint32_t)q.z, (uint32_t)q.w);
+        }
     };
 
     v4i acc[kR][kMT];
@@ -432,13 +454,13 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_skinny_2bit(
 
     auto compute = [&](const uint4 (&w)[kR], int i, int stage) {
         const int cq = s_begin + i == steps - 1 ? tail_quads : 64;
-        const uint32_t keep = (i < n_here && lane < cq) ? 0xFFFFFFFFu : 0u;   // padded steps contribute nothing
+        const uint32_t km = (i < n_here && lane < cq) ? 0xC0C0C0C0u : 0u;     // padded steps contribute nothing
         const char* src = glds + stage * kStageBytes + r * 256;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             v4i A[kR];
 #pragma unroll
-            for (int a = 0; a < kR; ++a) A[a] = decode_word(quad_word(w[a], j) & keep);
+            for (int a = 0; a < kR; ++a) A[a] = decode_word_masked(quad_word(w[a], j), km);
             const int slot = ((4 * g + j) ^ r) << 4;
 #pragma unroll
             for (int t = 0; t < kMT; ++t) {
@@ -529,8 +551,9 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_skinny_2bit(
 // host side
 // ---------------------------------------------------------------------------------------------------
 bool gemv_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
-    (void)N;
-    return M >= 1 && M <= 64 && K % 16 == 0 && reinterpret_cast<uintptr_t>(xq) % 16 == 0 && M * K < ((int64_t)1 << 31);
+    // x_q offsets are 32-bit; one K step of the packed weights (1 KiB per 16-row block) is addressed as one raw buffer
+    return M >= 1 && M <= 64 && K % 16 == 0 && reinterpret_cast<uintptr_t>(xq) % 16 == 0 && M * K < ((int64_t)1 << 31) &&
+           ceil_div(N, kRowsPerBlock) < ((int64_t)1 << 21);
 }
 
 constexpr size_t kGemvLdsBudget = 65536;
