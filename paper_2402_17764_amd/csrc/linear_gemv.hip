@@ -548,6 +548,185 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_skinny_2bit(
 }
 
 // ---------------------------------------------------------------------------------------------------
+// The skinny kernel with a loader wave (larger token tiles)
+// ---------------------------------------------------------------------------------------------------
+// With 32 or 64 tokens the LDS ring of the kernel above holds two or three steps of activations at most, and
+// because LDS-DMA copies and weight loads retire through one in-order counter, waiting for a step's copy also
+// drains every weight load issued before it: no more than kLx steps of weights are ever in flight, and the
+// waves spend 40-60 % of their cycles in s_waitcnt (measured).  Here the two streams get separate waves:
+//   * one loader wave per workgroup issues all LDS-DMA copies (every K group's stage of a step), waits for
+//     them with an exact count -- its counter sees nothing but copies -- and publishes each step at the barrier;
+//   * the kS * kW compute waves never wait for a copy: their counter tracks weight quads only, so the
+//     compiler's own waits leave kD - 1 steps of weights in flight per wave.
+// Everything else (K groups, kR row blocks per wave, swizzled LDS tiles, fold) is as above.
+template <int kMT, int kR, int kW, int kS, int kD, int kLx>
+__global__ __launch_bounds__((kS * kW + 1) * kWave) void linear_skinny_ws_2bit(
+        const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
+        const float* __restrict__ gamma, int gstride, int M, int64_t N, int64_t K, int Kq, int RB, int spg,
+        void* __restrict__ y, OutType yt) {
+#if defined(__HIP_DEVICE_COMPILE__)      // the buffer-resource builtins exist in the device pass only
+    extern __shared__ uint4 smem[];
+    constexpr int kRing = kLx + 1;                     // LDS stages per group
+    constexpr int kStageBytes = kMT * 16 * 256;        // tokens staged per step x 256 columns
+    constexpr int kGroupBytes = kRing * kStageBytes;
+    constexpr int kCopies = kMT * 4;                   // 1 KiB wave-loads per stage (4 token rows each)
+    constexpr int kYounger = (kLx - 1) * kS * kCopies; // copies issued after those of the step being awaited
+    static_assert(kLx >= 1 && kYounger < 64, "vmcnt is six bits");
+    static_assert((kS - 1) * kW * kR * kMT * 1024 <= kS * kGroupBytes, "the fold reuses the activation ring");
+    char* lds = reinterpret_cast<char*>(smem);
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = lane & 15, g = lane >> 4;
+    const int steps = (Kq + 3) >> 2;
+    const int tail_quads = 16 * (Kq - 4 * (steps - 1));
+    const int padded = (spg + kD - 1) / kD * kD;       // barriers per wave: the same for both roles
+
+    v4i acc[kR][kMT];
+#pragma unroll
+    for (int a = 0; a < kR; ++a)
+#pragma unroll
+        for (int t = 0; t < kMT; ++t) acc[a][t] = (v4i){0, 0, 0, 0};
+    int ks = 0, wv = 0, rbw = 0;
+
+    if (wave == kS * kW) {
+        // ---- loader: lane i of a copy fills slot i = (row i >> 4 of a group of four token rows, chunk slot
+        // i & 15); the chunk stored in slot c' of token m is c' ^ (m & 15).  Reads past x_q return zero.
+        const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<int8_t*>(xq), 0, (int)min((int64_t)M * K, (int64_t)0x7FFFFFFF), 0x00020000);
+        uint32_t xoff[kCopies];
+#pragma unroll
+        for (int t = 0; t < kCopies; ++t) {
+            const int row = t * 4 + (lane >> 4);
+            xoff[t] = (uint32_t)min(row, M - 1) * (uint32_t)K + (uint32_t)(((lane & 15) ^ (row & 15)) << 4);
+        }
+        auto copy_x = [&](int i, int stage) {                          // local step i of every group
+#pragma unroll
+            for (int q = 0; q < kS; ++q) {
+                const uint32_t col = (uint32_t)(q * spg + i) * 256u;
+#pragma unroll
+                for (int t = 0; t < kCopies; ++t)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                        xrsrc, (__attribute__((address_space(3))) void*)(lds + q * kGroupBytes + stage * kStageBytes + t * 1024),
+                        16, xoff[t] + col, 0, 0, 0);
+            }
+        };
+#pragma unroll
+        for (int p = 0; p < kLx; ++p) copy_x(p, p % kRing);
+        for (int i = 0; i < padded; ++i) {
+            issue_fence();
+            __builtin_amdgcn_s_waitcnt((kYounger & 15) | 0x0F70 | ((kYounger >> 4) << 14));   // step i has landed
+            __builtin_amdgcn_s_barrier();                              // publish it; stage i - 1 is free
+            issue_fence();
+            copy_x(i + kLx, (i + kLx) % kRing);
+        }
+        issue_fence();
+    } else {
+        // ---- compute waves
+        ks = wave / kW;
+        wv = wave - ks * kW;
+        rbw = (blockIdx.x * kW + wv) * kR;
+        const int s_begin = ks * spg;                                  // this group's steps: s_begin + [0, n_here)
+        const int n_here = max(0, min(spg, steps - s_begin));
+        const int64_t wstride = (int64_t)RB * 64;
+        const char* glds = lds + ks * kGroupBytes;
+        int rbc[kR];
+        uint32_t woff_full[kR], woff_tail[kR];
+#pragma unroll
+        for (int a = 0; a < kR; ++a) {
+            rbc[a] = min(rbw + a, RB - 1);
+            woff_full[a] = ((uint32_t)rbc[a] * 64u + (uint32_t)lane) * 16u;
+            woff_tail[a] = ((uint32_t)rbc[a] * (uint32_t)tail_quads + (uint32_t)min(lane, tail_quads - 1)) * 16u;
+        }
+        auto load_w = [&](uint4 (&w)[kR], int i) {
+            const int sl = min(s_begin + i, steps - 1);                // past the end: redirected, masked below
+            const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<uint4*>(packed + (int64_t)sl * wstride), 0, (int)(wstride * 16), 0x00020000);
+            const bool tail = sl == steps - 1;
+#pragma unroll
+            for (int a = 0; a < kR; ++a) {
+                const v4i q = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, (int)(tail ? woff_tail[a] : woff_full[a]), 0, 0));
+                w[a] = make_uint4((uint32_t)q.x, (uint32_t)q.y, (uint32_t)q.z, (uint32_t)q.w);
+            }
+        };
+        auto compute = [&](const uint4 (&w)[kR], int i, int stage) {
+            const int cq = s_begin + i == steps - 1 ? tail_quads : 64;
+            const uint32_t km = (i < n_here && lane < cq) ? 0xC0C0C0C0u : 0u; // padded steps contribute nothing
+            const char* src = glds + stage * kStageBytes + r * 256;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                v4i A[kR];
+#pragma unroll
+                for (int a = 0; a < kR; ++a) A[a] = decode_word_masked(quad_word(w[a], j), km);
+                const int slot = ((4 * g + j) ^ r) << 4;
+#pragma unroll
+                for (int t = 0; t < kMT; ++t) {
+                    const v4i X = *reinterpret_cast<const v4i*>(src + t * 4096 + slot);
+#pragma unroll
+                    for (int a = 0; a < kR; ++a)
+                        acc[a][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A[a], X, acc[a][t], 0, 0, 0);
+                }
+            }
+        };
+        uint4 wst[kD][kR];
+#pragma unroll
+        for (int d = 0; d < kD; ++d) load_w(wst[d], d);
+        int i0 = 0;
+        do {
+#pragma unroll
+            for (int d = 0; d < kD; ++d) {
+                const int i = i0 + d;
+                __builtin_amdgcn_s_barrier();                          // stage i is complete
+                compute(wst[d], i, i % kRing);
+                load_w(wst[d], i + kD);                                // after the last use: reloaded in place
+            }
+            i0 += kD;
+        } while (i0 < padded);
+    }
+
+    // fold the K groups (every wave meets the barriers; the loader has nothing to add)
+    __builtin_amdgcn_s_waitcnt(0);                                     // copies past the end have landed
+    __syncthreads();
+    if constexpr (kS > 1) {
+        v4i* fold = reinterpret_cast<v4i*>(lds);
+        if (wave < kS * kW && ks > 0) {
+#pragma unroll
+            for (int a = 0; a < kR; ++a)
+#pragma unroll
+                for (int t = 0; t < kMT; ++t)
+                    fold[((((ks - 1) * kW + wv) * kR + a) * kMT + t) * kWave + lane] = acc[a][t];
+        }
+        __syncthreads();
+        if (wave >= kS * kW || ks > 0) return;
+        for (int q = 0; q < kS - 1; ++q)
+#pragma unroll
+            for (int a = 0; a < kR; ++a)
+#pragma unroll
+                for (int t = 0; t < kMT; ++t)
+                    acc[a][t] += fold[(((q * kW + wv) * kR + a) * kMT + t) * kWave + lane];
+    } else {
+        if (wave >= kS * kW) return;
+    }
+
+    float gm[kR];
+#pragma unroll
+    for (int a = 0; a < kR; ++a) gm[a] = gamma[gstride * min(rbw + a, RB - 1)];
+#pragma unroll
+    for (int t = 0; t < kMT; ++t) {
+        const int m = 16 * t + r;                                      // MFMA output column = token
+        if (m >= M) continue;
+        const float sxm = yt == OutType::I32 ? 0.0f : sx[m];
+#pragma unroll
+        for (int a = 0; a < kR; ++a) {
+            const float scale = (gm[a] * sxm) / kQb;
+            const int64_t n0 = (int64_t)(rbw + a) * 16 + 4 * g;
+            if (n0 < N) store_row4(y, yt, (int64_t)m * N + n0, n0, N, acc[a][t], scale);
+        }
+    }
+#endif
+}
+
+// ---------------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------------
 bool gemv_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
@@ -606,6 +785,27 @@ static hipError_t launch_skinny(const int8_t* xq, const float* sx, const void* p
     return hipGetLastError();
 }
 
+template <int kMT, int kR, int kW, int kS, int kD, int kLx>
+static hipError_t launch_skinny_ws(const int8_t* xq, const float* sx, const void* packed, const float* gamma, int gstride,
+                                   int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
+    constexpr size_t lds = (size_t)kS * (kLx + 1) * kMT * 16 * 256;
+    static_assert(lds <= 160 * 1024, "activation rings must fit the LDS of a CU");
+    static_assert(kS * kW + 1 <= 16, "at most 1024 threads per workgroup");
+    auto* kern = linear_skinny_ws_2bit<kMT, kR, kW, kS, kD, kLx>;
+    if (lds > 65536) {
+        static bool raised[kMaxDevices] = {};
+        const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(kern), (int)lds, raised);
+        if (e != hipSuccess) return e;
+    }
+    const int Kq = (int)ceil_div(K, kColsPerQuad);
+    const int RB = (int)ceil_div(N, kRowsPerBlock);
+    const int spg = (int)ceil_div(ceil_div(K, 256), kS);
+    dim3 grid((unsigned)ceil_div(RB, kW * kR));
+    hipLaunchKernelGGL(kern, grid, dim3((kS * kW + 1) * kWave), lds, stream, xq, sx, static_cast<const uint4*>(packed), gamma,
+                       gstride, (int)M, N, K, Kq, RB, spg, y, yt);
+    return hipGetLastError();
+}
+
 // Shape heuristics from sweeps on MI355X (M = 1, HIP-graph replay over many distinct weight buffers):
 //   * many row blocks: few waves, each owning four row blocks for all of K with 2-3 steps of loads
 //     in flight -- the dense step-major front does the rest;
@@ -648,21 +848,26 @@ hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void
     // of prefetch were best throughout.
     const int64_t RB = ceil_div(N, kRowsPerBlock);
 #define SKINNY(...) return launch_skinny<__VA_ARGS__>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream)
+#define SKINNY_WS(...) return launch_skinny_ws<__VA_ARGS__>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream)
     if (M <= 16) {
         if (RB >= 2048)      SKINNY(1, 4, 4, 2, 2, 2);
         else if (RB >= 1024) SKINNY(1, 3, 2, 4, 2, 2);
         else if (RB >= 512)  SKINNY(1, 3, 1, 4, 2, 2);
         else                 SKINNY(1, 1, 1, 8, 2, 2);
     } else if (M <= 32) {
-        if (RB >= 1280)      SKINNY(2, 3, 2, 2, 2, 2);
+        // from 1280 row blocks on, the form with a loader wave (weights 3 steps deep in flight per wave)
+        if (RB >= 2048)      SKINNY_WS(2, 4, 4, 1, 4, 3);
+        else if (RB >= 1280) SKINNY_WS(2, 2, 3, 2, 4, 3);
         else if (RB >= 512)  SKINNY(2, 2, 2, 4, 2, 2);
         else                 SKINNY(2, 1, 1, 4, 2, 2);
     } else {
-        if (RB >= 1280)      SKINNY(4, 3, 2, 2, 2, 2);
-        else if (RB >= 512)  SKINNY(4, 1, 4, 2, 2, 2);
+        if (RB >= 2048)      SKINNY_WS(4, 4, 4, 1, 4, 2);
+        else if (RB >= 1280) SKINNY_WS(4, 2, 3, 1, 4, 2);
+        else if (RB >= 512)  SKINNY_WS(4, 2, 2, 2, 4, 2);
         else                 SKINNY(4, 1, 1, 4, 2, 1);
     }
 #undef SKINNY
+#undef SKINNY_WS
 }
 
 bool gemv_fused_supports(int64_t M, int64_t N, int64_t K, const void* x) {

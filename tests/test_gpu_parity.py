@@ -225,7 +225,10 @@ GEMV_SHAPES = [(1, 4096, 1536), (16, 4096, 1536), (1, 16, 64), (1, 17, 16), (3, 
                (20, 16400, 272), (48, 300, 4112), (64, 100, 1040), (40, 1000, 528), (33, 260, 2048), (56, 16400, 512),
                (24, 20488, 272), (50, 20500, 528), (35, 48, 64), (18, 20, 16), (64, 8200, 4096),
                # ... and its single-token-tile form for 4 < M <= 16, one shape per row-block class
-               (9, 9000, 528), (10, 32800, 272), (5, 40, 16), (13, 16400, 1040)]
+               (9, 9000, 528), (10, 32800, 272), (5, 40, 16), (13, 16400, 1040),
+               # ... and the form with a loader wave (many row blocks, more than 16 tokens): each of its five selections,
+               # K from one partial step to 33 steps
+               (30, 32784, 272), (60, 32800, 144), (17, 20490, 80), (64, 20480, 8208), (40, 8200, 1040)]
 
 
 @pytest.mark.parametrize("M,N,K", GEMV_SHAPES)
