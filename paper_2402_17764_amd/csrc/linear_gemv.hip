@@ -282,6 +282,16 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
         __builtin_amdgcn_sched_barrier(0);
     }
 
+    // the output scales are requested first: loaded where they are used, after the fold, each would add a
+    // cache round trip to the tail of a kernel that lives for only a few of them
+    float gm[kR] = {};
+    float sc_row = 0.0f;
+    if (ws == 0) {                                     // the waves that write the output
+#pragma unroll
+        for (int a = 0; a < kR; ++a) gm[a] = gamma[gstride * rbc[a]];
+        if (!kFused && yt != OutType::I32) sc_row = sx[mrow];
+    }
+
     // then the weights: their loads stay in flight while the activations are staged
     Stage st[kD];
 #pragma unroll
@@ -315,8 +325,7 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
 #pragma unroll
     for (int d = 0; d < kD; ++d) mac(st[d], i + d);
 
-    float sc_row = 0.0f;
-    if (yt != OutType::I32) sc_row = kFused ? sxl[mrow] : sx[mrow];
+    if (kFused && yt != OutType::I32) sc_row = sxl[mrow];
 
     if (kS > 1) {
         // fold the K slices; the buffer aliases the x region, so wait until every wave is done with it
@@ -341,7 +350,7 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
     if (r < M) {                                                    // MFMA output column = lane & 15 = token
 #pragma unroll
         for (int a = 0; a < kR; ++a) {
-            const float scale = (gamma[gstride * rbc[a]] * sc_row) / kQb;
+            const float scale = (gm[a] * sc_row) / kQb;
             const int64_t n0 = (int64_t)(rbw + a) * 16 + 4 * g;     // rows 4 g .. 4 g + 3 of the row block
             if (n0 < N) store_row4(y, yt, (int64_t)r * N + n0, n0, N, acc[a], scale);
         }
@@ -472,6 +481,17 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_skinny_2bit(
         }
     };
 
+    // The output scales are requested before anything else (loaded after the fold they would add a cache round
+    // trip to the tail of the kernel); being the oldest loads in flight they never disturb the counted waits.
+    float gm[kR] = {}, sxm[kMT] = {};
+    if (ks == 0) {                                                     // the group that writes the output
+#pragma unroll
+        for (int a = 0; a < kR; ++a) gm[a] = gamma[gstride * rbc[a]];
+#pragma unroll
+        for (int t = 0; t < kMT; ++t) sxm[t] = yt == OutType::I32 ? 0.0f : sx[min(16 * t + r, M - 1)];
+    }
+    issue_fence();
+
     // Prologue: the issue pattern of steps -kD ... -1 of the loop below.  Where the loop would copy a
     // step before the first, step 0 is copied (again) so that the count of loads in flight is the same.
     uint4 wst[kD][kR];
@@ -529,17 +549,13 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_skinny_2bit(
                     acc[a][t] += fold[(((q * kW + wv) * kR + a) * kMT + t) * kWave + lane];
     }
 
-    float gm[kR];
-#pragma unroll
-    for (int a = 0; a < kR; ++a) gm[a] = gamma[gstride * rbc[a]];
 #pragma unroll
     for (int t = 0; t < kMT; ++t) {
         const int m = 16 * t + r;                                      // MFMA output column = token
         if (m >= M) continue;
-        const float sxm = yt == OutType::I32 ? 0.0f : sx[m];
 #pragma unroll
         for (int a = 0; a < kR; ++a) {
-            const float scale = (gm[a] * sxm) / kQb;
+            const float scale = (gm[a] * sxm[t]) / kQb;
             const int64_t n0 = (int64_t)(rbw + a) * 16 + 4 * g;
             if (n0 < N) store_row4(y, yt, (int64_t)m * N + n0, n0, N, acc[a][t], scale);
         }
@@ -588,6 +604,7 @@ __global__ __launch_bounds__((kS * kW + 1) * kWave) void linear_skinny_ws_2bit(
 #pragma unroll
         for (int t = 0; t < kMT; ++t) acc[a][t] = (v4i){0, 0, 0, 0};
     int ks = 0, wv = 0, rbw = 0;
+    float gm[kR] = {}, sxm[kMT] = {};                                  // output scales, requested ahead of the weights
 
     if (wave == kS * kW) {
         // ---- loader: lane i of a copy fills slot i = (row i >> 4 of a group of four token rows, chunk slot
@@ -668,6 +685,12 @@ __global__ __launch_bounds__((kS * kW + 1) * kWave) void linear_skinny_ws_2bit(
                 }
             }
         };
+        if (ks == 0) {                                                 // the group that writes the output
+#pragma unroll
+            for (int a = 0; a < kR; ++a) gm[a] = gamma[gstride * rbc[a]];
+#pragma unroll
+            for (int t = 0; t < kMT; ++t) sxm[t] = yt == OutType::I32 ? 0.0f : sx[min(16 * t + r, M - 1)];
+        }
         uint4 wst[kD][kR];
 #pragma unroll
         for (int d = 0; d < kD; ++d) load_w(wst[d], d);
@@ -708,17 +731,13 @@ __global__ __launch_bounds__((kS * kW + 1) * kWave) void linear_skinny_ws_2bit(
         if (wave >= kS * kW) return;
     }
 
-    float gm[kR];
-#pragma unroll
-    for (int a = 0; a < kR; ++a) gm[a] = gamma[gstride * min(rbw + a, RB - 1)];
 #pragma unroll
     for (int t = 0; t < kMT; ++t) {
         const int m = 16 * t + r;                                      // MFMA output column = token
         if (m >= M) continue;
-        const float sxm = yt == OutType::I32 ? 0.0f : sx[m];
 #pragma unroll
         for (int a = 0; a < kR; ++a) {
-            const float scale = (gm[a] * sxm) / kQb;
+            const float scale = (gm[a] * sxm[t]) / kQb;
             const int64_t n0 = (int64_t)(rbw + a) * 16 + 4 * g;
             if (n0 < N) store_row4(y, yt, (int64_t)m * N + n0, n0, N, acc[a][t], scale);
         }
