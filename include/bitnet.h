@@ -101,7 +101,14 @@ typedef enum bitnet_kernel {
     BITNET_KERNEL_AUTO = 0,
     BITNET_KERNEL_REFERENCE = 1, /* one thread per output, any shape; the slow, obviously right one */
     BITNET_KERNEL_GEMV = 2,      /* weight-streaming decode kernel, M <= 64 */
-    BITNET_KERNEL_GEMM = 3       /* LDS-tiled int8 MFMA prefill kernel */
+    BITNET_KERNEL_GEMM = 3,      /* LDS-tiled int8 MFMA prefill kernel, tile shape picked by shape */
+    /* the prefill kernel with a fixed workgroup tile (tokens x weight rows): for tuning and tests */
+    BITNET_KERNEL_GEMM_128x256 = 0x142,
+    BITNET_KERNEL_GEMM_96x256 = 0x132,
+    BITNET_KERNEL_GEMM_64x256 = 0x122,
+    BITNET_KERNEL_GEMM_128x128 = 0x141,
+    BITNET_KERNEL_GEMM_96x128 = 0x131,
+    BITNET_KERNEL_GEMM_64x128 = 0x121
 } bitnet_kernel;
 
 /* Library version, major*10000 + minor*100 + patch.  Also the version of the packed layouts. */

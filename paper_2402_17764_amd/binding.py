@@ -18,6 +18,8 @@ OK = 0
 F32, BF16, I32 = 0, 1, 2
 PACK_2BIT, PACK_TRIT5 = 0, 1
 KERNEL_AUTO, KERNEL_REFERENCE, KERNEL_GEMV, KERNEL_GEMM = 0, 1, 2, 3
+# the prefill kernel with a fixed workgroup tile, tokens x weight rows (tuning and tests)
+KERNEL_GEMM_TILES = {(128, 256): 0x142, (96, 256): 0x132, (64, 256): 0x122, (128, 128): 0x141, (96, 128): 0x131, (64, 128): 0x121}
 
 SYMBOLS = [
     "bitnet_version", "bitnet_status_string", "bitnet_packed_bytes", "bitnet_quantize_weights_workspace",

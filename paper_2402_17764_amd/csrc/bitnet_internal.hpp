@@ -63,6 +63,9 @@ bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq);
 hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                    int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt,
                                    hipStream_t stream);
+// the same with the tile forced: 32 * fm tokens x 128 * fn weight rows, fm in 2 .. 4, fn in 1 .. 2 (hipErrorInvalidValue otherwise)
+hipError_t launch_linear_gemm_2bit_shape(int fm, int fn, const int8_t* xq, const float* sx, const void* packed, const float* gamma,
+                                         int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);
 
 // trit5.hip
 hipError_t launch_pack_trit5(const void* W, bool bf16, int64_t N, int64_t K, const float* gamma, void* packed,

@@ -40,9 +40,10 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 // tokens per workgroup tile: kFM fragments of 32; 4 (128 tokens) is the default, 3 (96 tokens) exists for shapes
 // whose 128-token tiles would leave many of the 512 workgroup slots (256 CUs x 2) empty
-constexpr int kGemmBN = 256;                   // weight rows per workgroup tile
 constexpr int kGemmThreads = 256;
-constexpr int kGemmFN = 2;                     // 32-row weight fragments per wave (four waves side by side along the weight rows)
+// kFN: 32-row weight fragments per wave; the four waves sit side by side along the weight rows, so a workgroup tile
+// has 128 * kFN of them.  2 is the default; 1 (narrow tiles) doubles the number of workgroups for shapes whose wide
+// tiles would leave most CUs idle, at the same decode work per MFMA (that depends on the tile height only).
 constexpr int kGemmPitch32 = 64 * 4 + 32;      // epilogue row pitch, 4-byte outputs: rows r and r+4 in different bank halves
 constexpr int kGemmPitch16 = 64 * 2 + 32;      // same for bf16 outputs
 constexpr int gemm_stage_bytes(int fm) { return fm * 32 * 256; }            // one K step of activations
@@ -80,22 +81,22 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi) {          // round t
     return __builtin_bit_cast(uint32_t, __builtin_convertvector((v2f){lo, hi}, v2bf));
 }
 
-template <OutType kOut, int kFM>
-__device__ inline void gemm_epilogue(v16i (&acc)[kFM][kGemmFN], const GemmOutCtx& c) {
+template <OutType kOut, int kFM, int kFN>
+__device__ inline void gemm_epilogue(v16i (&acc)[kFM][kFN], const GemmOutCtx& c) {
     constexpr bool is16 = kOut == OutType::BF16;
     constexpr int esz = is16 ? 2 : 4;
     constexpr int pitch = is16 ? kGemmPitch16 : kGemmPitch32;
-    constexpr int lanes_per_row = 64 * esz / 16;                    // 8 or 16
-    constexpr int rows_per_pass = 64 / lanes_per_row;               // 8 or 4
+    constexpr int lanes_per_row = 32 * kFN * esz / 16;              // 16-byte pieces of a staged row: 4, 8 or 16
+    constexpr int rows_per_pass = 64 / lanes_per_row;
     const int am = c.lane & 31, kg = c.lane >> 5;
     const int wn = c.wave;
     char* stage_out = c.lds + c.wave * (32 * kGemmPitch32);
-    const int64_t n_wave = (int64_t)c.bn * kGemmBN + wn * 64;
+    const int64_t n_wave = (int64_t)c.bn * (128 * kFN) + wn * (32 * kFN);
     // with one gamma per row block the lane's weight row (am of fragment fn) picks its own; otherwise the
     // factor is 1 and the staged scale already carries gamma
-    float gfn[kGemmFN];
+    float gfn[kFN];
 #pragma unroll
-    for (int fn = 0; fn < kGemmFN; ++fn) {
+    for (int fn = 0; fn < kFN; ++fn) {
         const int rb = min((int)((n_wave + fn * 32 + am) / kRowsPerBlock), c.RB - 1);
         gfn[fn] = c.gstride ? c.gamma[rb] : 1.0f;
     }
@@ -112,7 +113,7 @@ __device__ inline void gemm_epilogue(v16i (&acc)[kFM][kGemmFN], const GemmOutCtx
                 sc[1] = c.scale_lds[fm * 32 + rl + 1] * 0.015625f;
             }
 #pragma unroll
-            for (int fn = 0; fn < kGemmFN; ++fn) {
+            for (int fn = 0; fn < kFN; ++fn) {
                 char* p = stage_out + rl * pitch + (fn * 32 + am) * esz;
                 const int a0 = acc[fm][fn][v], a1 = acc[fm][fn][v + 1];
                 if (kOut == OutType::I32) {
@@ -160,8 +161,8 @@ __device__ inline void gemm_epilogue(v16i (&acc)[kFM][kGemmFN], const GemmOutCtx
     }
 }
 
-// One output tile of 32 * kFM tokens (first token row0) x 256 weight rows (tile bn).
-template <int kFM>
+// One output tile of 32 * kFM tokens (first token row0) x 128 * kFN weight rows (tile bn).
+template <int kFM, int kFN>
 __device__ __forceinline__ void gemm_tile(
         const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
         const float* __restrict__ gamma, int gstride, int M, int64_t N, int64_t K, int Kq, int RB, int row0, int bn,
@@ -203,20 +204,20 @@ __device__ __forceinline__ void gemm_tile(
     // ---- A operand, LDS -> registers
     const int am = lane & 31, kg = lane >> 5;
     const int a_row_base = am * 256;                                 // + fm * 8192
-    // ---- B operand: fragment fn covers row blocks 2*fn, 2*fn+1 of this wave's 4
+    // ---- B operand: fragment fn covers row blocks 2*fn, 2*fn+1 of this wave's 2 * kFN
     const int brow = lane & 15, bsel = (lane >> 4) & 1;
-    uint32_t woff[kGemmFN][2];                                      // byte offsets of the lane's quads inside a whole step
+    uint32_t woff[kFN][2];                                      // byte offsets of the lane's quads inside a whole step
 #pragma unroll
-    for (int fn = 0; fn < kGemmFN; ++fn)
+    for (int fn = 0; fn < kFN; ++fn)
 #pragma unroll
         for (int h = 0; h < 2; ++h)
-            woff[fn][h] = ((uint32_t)min(bn * 16 + wn * 4 + fn * 2 + bsel, RB - 1) * 64u + (uint32_t)((kg + 2 * h) * 16 + brow)) * 16u;
+            woff[fn][h] = ((uint32_t)min(bn * (8 * kFN) + wn * (2 * kFN) + fn * 2 + bsel, RB - 1) * 64u + (uint32_t)((kg + 2 * h) * 16 + brow)) * 16u;
 
-    v16i acc[kFM][kGemmFN];
+    v16i acc[kFM][kFN];
 #pragma unroll
     for (int fm = 0; fm < kFM; ++fm)
 #pragma unroll
-        for (int fn = 0; fn < kGemmFN; ++fn)
+        for (int fn = 0; fn < kFN; ++fn)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[fm][fn][v] = 0;
 
@@ -238,25 +239,25 @@ __device__ __forceinline__ void gemm_tile(
     };
     // For the weights a raw buffer per step as well: one whole step of the packed layout (RB KiB), the lane's
     // byte offset in it as the vector offset -- no 64-bit address arithmetic per load.
-    auto load_w = [&](uint4 (&wq)[kGemmFN][2], int step) {
+    auto load_w = [&](uint4 (&wq)[kFN][2], int step) {
         const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<uint4*>(packed + (int64_t)step * wstride), 0, (int)(wstride * 16), 0x00020000);
 #pragma unroll
         for (int h = 0; h < 2; ++h)
 #pragma unroll
-            for (int fn = 0; fn < kGemmFN; ++fn) {
+            for (int fn = 0; fn < kFN; ++fn) {
                 const v4i q = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, (int)woff[fn][h], 0, 0));
                 wq[fn][h] = make_uint4((uint32_t)q.x, (uint32_t)q.y, (uint32_t)q.z, (uint32_t)q.w);
             }
     };
     // the partial last step: its chunks hold fewer quads; lanes past them are clamped here and masked in compute()
-    auto load_w_tail = [&](uint4 (&wq)[kGemmFN][2], int step) {
+    auto load_w_tail = [&](uint4 (&wq)[kFN][2], int step) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int ln = min((kg + 2 * h) * 16 + brow, tail_quads - 1);
 #pragma unroll
-            for (int fn = 0; fn < kGemmFN; ++fn) {
-                const int rb = min(bn * 16 + wn * 4 + fn * 2 + bsel, RB - 1);
+            for (int fn = 0; fn < kFN; ++fn) {
+                const int rb = min(bn * (8 * kFN) + wn * (2 * kFN) + fn * 2 + bsel, RB - 1);
                 wq[fn][h] = packed[(int64_t)step * wstride + (int64_t)rb * tail_quads + ln];
             }
         }
@@ -264,10 +265,10 @@ __device__ __forceinline__ void gemm_tile(
 
     // One K step: 8 slices of 32 columns, slice (h, j) uses word j of quad h; the LDS reads and the
     // decode for slice t + 1 are placed among the MFMAs of slice t.
-    auto compute = [&](const uint4 (&wq)[kGemmFN][2], int stage) {
+    auto compute = [&](const uint4 (&wq)[kFN][2], int stage) {
         const char* src = lds + stage * kGemmStageBytes + a_row_base;
         const int sw = am & 15;
-        v4i a[2][kFM], b[2][kGemmFN];
+        v4i a[2][kFM], b[2][kFN];
         auto read_a = [&](v4i (&dst)[kFM], int t) {
             const int chunk = 8 * (t >> 2) + 4 * kg + (t & 3);
 #pragma unroll
@@ -277,7 +278,7 @@ __device__ __forceinline__ void gemm_tile(
         auto word_of = [&](int fn, int t) { return gemm_quad_word(wq[fn][t >> 2], t & 3); };
         read_a(a[0], 0);
 #pragma unroll
-        for (int fn = 0; fn < kGemmFN; ++fn) {
+        for (int fn = 0; fn < kFN; ++fn) {
             const uint32_t w = word_of(fn, 0);
 #pragma unroll
             for (int i = 0; i < 4; ++i) b[0][fn][i] = gemm_decode_reg(w, i);
@@ -288,10 +289,10 @@ __device__ __forceinline__ void gemm_tile(
             __builtin_amdgcn_sched_barrier(0);          // slices stay in order: no hoisting of later LDS reads
             if (t < 7) read_a(a[nxt], t + 1);
             __builtin_amdgcn_sched_barrier(0);          // ... and no sinking: the reads lead their use by a whole slice
-            constexpr int kMfmas = kFM * kGemmFN, kRegs = 4 * kGemmFN;
+            constexpr int kMfmas = kFM * kFN, kRegs = 4 * kFN;
 #pragma unroll
             for (int q = 0; q < kMfmas; ++q) {
-                const int fm = q / kGemmFN, fn = q % kGemmFN;
+                const int fm = q / kFN, fn = q % kFN;
                 acc[fm][fn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[cur][fm], b[cur][fn], acc[fm][fn], 0, 0, 0);
                 if (t < 7) {                                        // the next slice's decode, spread over the MFMAs
 #pragma unroll
@@ -306,7 +307,7 @@ __device__ __forceinline__ void gemm_tile(
     // One loop body for every step: operands of step s + 1 are requested right before step s is
     // consumed (activations into the other LDS stage, weights into wnext), and the barrier at the top of
     // the next iteration both publishes them and retires the stage that was just read.
-    uint4 wq[kGemmFN][2], wnext[kGemmFN][2];
+    uint4 wq[kFN][2], wnext[kFN][2];
     const uint32_t keep_t0 = (kg * 16 + brow) < tail_quads ? 0xFFFFFFFFu : 0u;
     const uint32_t keep_t1 = ((kg + 2) * 16 + brow) < tail_quads ? 0xFFFFFFFFu : 0u;
     auto issue = [&](int step) {
@@ -325,7 +326,7 @@ __device__ __forceinline__ void gemm_tile(
         for (int h = 0; h < 2; ++h) {
             const uint32_t keep = keep_h[h];
 #pragma unroll
-            for (int fn = 0; fn < kGemmFN; ++fn)
+            for (int fn = 0; fn < kFN; ++fn)
                 wq[fn][h] = make_uint4(wnext[fn][h].x & keep, wnext[fn][h].y & keep, wnext[fn][h].z & keep, wnext[fn][h].w & keep);
         }
         if (s + 1 < steps) issue(s + 1);
@@ -335,21 +336,23 @@ __device__ __forceinline__ void gemm_tile(
 
     // ---- epilogue: one instantiation per output type, chosen once ---------------------------------------
     const GemmOutCtx ctx{lds, scale_lds, y, gamma, gstride, RB, M, N, row0, bn, wave, lane, vec_store};
-    if (yt == OutType::BF16) gemm_epilogue<OutType::BF16, kFM>(acc, ctx);
-    else if (yt == OutType::F32) gemm_epilogue<OutType::F32, kFM>(acc, ctx);
-    else gemm_epilogue<OutType::I32, kFM>(acc, ctx);
+    if (yt == OutType::BF16) gemm_epilogue<OutType::BF16, kFM, kFN>(acc, ctx);
+    else if (yt == OutType::F32) gemm_epilogue<OutType::F32, kFM, kFN>(acc, ctx);
+    else gemm_epilogue<OutType::I32, kFM, kFN>(acc, ctx);
 #endif
 }
 
-// Consecutive workgroups take consecutive token tiles of the same weight tile (see the header).  Two workgroups
-// per CU (three with 64-token tiles, whose waves need fewer registers).
-template <int kFM>
-__global__ __launch_bounds__(kGemmThreads, kFM == 2 ? 3 : 2) void linear_gemm_2bit(
+// Consecutive workgroups take consecutive token tiles of the same weight tile (see the header).  Workgroups per
+// CU: what the registers and the LDS stages allow (two with the tall wide tiles, up to four with 64-token tiles).
+constexpr int gemm_blocks_per_cu(int fm, int fn) { return fn == 1 ? (fm == 2 ? 4 : fm == 3 ? 3 : 2) : (fm == 2 ? 3 : 2); }
+
+template <int kFM, int kFN>
+__global__ __launch_bounds__(kGemmThreads, gemm_blocks_per_cu(kFM, kFN)) void linear_gemm_2bit(
         const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
         const float* __restrict__ gamma, int gstride, int M, int64_t N, int64_t K, int Kq, int RB, int tiles_m,
         void* __restrict__ y, OutType yt, int vec_store) {
     const int b = blockIdx.x;
-    gemm_tile<kFM>(xq, sx, packed, gamma, gstride, M, N, K, Kq, RB, (b % tiles_m) * (32 * kFM), b / tiles_m, y, yt, vec_store);
+    gemm_tile<kFM, kFN>(xq, sx, packed, gamma, gstride, M, N, K, Kq, RB, (b % tiles_m) * (32 * kFM), b / tiles_m, y, yt, vec_store);
 }
 
 bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
@@ -358,49 +361,64 @@ bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
     return M >= 1 && K % 16 == 0 && reinterpret_cast<uintptr_t>(xq) % 16 == 0 && ceil_div(N, kRowsPerBlock) < ((int64_t)1 << 21);
 }
 
-template <int kFM>
+template <int kFM, int kFN>
 static hipError_t launch_gemm_tiles(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                     int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt,
                                     hipStream_t stream) {
     static bool raised[kMaxDevices] = {};
-    const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(linear_gemm_2bit<kFM>), gemm_lds_bytes(kFM), raised);
+    const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(linear_gemm_2bit<kFM, kFN>), gemm_lds_bytes(kFM), raised);
     if (e != hipSuccess) return e;
     const int Kq = (int)ceil_div(K, kColsPerQuad);
     const int RB = (int)ceil_div(N, kRowsPerBlock);
     const int tiles_m = (int)ceil_div(M, 32 * kFM);
-    const int64_t tiles_n = ceil_div(N, kGemmBN);
+    const int64_t tiles_n = ceil_div(N, 128 * kFN);
     const size_t esz = yt == OutType::BF16 ? 2 : 4;
     const int vec_store = (reinterpret_cast<uintptr_t>(y) % 16 == 0) && ((N * esz) % 16 == 0);
-    hipLaunchKernelGGL(linear_gemm_2bit<kFM>, dim3((unsigned)(tiles_m * tiles_n)), dim3(kGemmThreads), gemm_lds_bytes(kFM),
+    hipLaunchKernelGGL((linear_gemm_2bit<kFM, kFN>), dim3((unsigned)(tiles_m * tiles_n)), dim3(kGemmThreads), gemm_lds_bytes(kFM),
                        stream, xq, sx, static_cast<const uint4*>(packed), gamma, gstride, (int)M, N, K, Kq, RB, tiles_m, y, yt,
                        vec_store);
     return hipGetLastError();
 }
 
+// tile shape forced by the caller (tuning and tests); fm in 2 .. 4, fn in 1 .. 2
+hipError_t launch_linear_gemm_2bit_shape(int fm, int fn, const int8_t* xq, const float* sx, const void* packed, const float* gamma,
+                                         int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
+#define GEMM_SHAPE(FM_, FN_) if (fm == FM_ && fn == FN_) return launch_gemm_tiles<FM_, FN_>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream)
+    GEMM_SHAPE(2, 1); GEMM_SHAPE(3, 1); GEMM_SHAPE(4, 1); GEMM_SHAPE(2, 2); GEMM_SHAPE(3, 2); GEMM_SHAPE(4, 2);
+#undef GEMM_SHAPE
+    return hipErrorInvalidValue;
+}
+
 hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                    int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt,
                                    hipStream_t stream) {
-    // Tile height (32 * kFM tokens) from a cost model fitted to measurements on MI355X (M = 512 and 2048 on the
-    // four 13B shapes, every height):
-    //   * with at most one tile per CU the launch takes one tile's latency, which shrinks with its height
-    //     (1.05 : 0.87 : 0.73 for 128 : 96 : 64 tokens);
-    //   * with more, the CUs are saturated and a tile costs its share of the MFMA work (1 : 0.77 : 0.50), times
-    //     the largest number of tiles that any CU gets (tiles are dealt round-robin).
-    // Ties within 3 % go to the taller tile (less decode work per token).  Examples: 13B down projection at
-    // M = 2048 (N = 5120): 320 tiles of 128 tokens 150 us, 440 tiles of 96 tokens 126 us; M = 512, N = 5120: 36 us
-    // with 128-token tiles, 25 us with 64-token tiles.
-    const int64_t tiles_n = ceil_div(N, kGemmBN);
-    static const double kSaturated[5] = {0, 0, 0.504, 0.773, 1.0}, kAlone[5] = {0, 0, 0.729, 0.872, 1.052};
-    int best = 4;
+    // Tile shape (32 * fm tokens x 128 * fn weight rows) from a cost model fitted to measurements on MI355X
+    // (nine LLaMA-family shapes, M = 65 ... 2048, every tile shape).  In microseconds, per K step of 256 columns:
+    //   * a workgroup that has its CU to itself is latency bound and takes kAlone per step, a little more as the
+    //     chip fills up (tiles are not dealt perfectly evenly);
+    //   * a CU that holds n tiles is throughput bound at n * kSaturated per step; per unit of work the three wide
+    //     shapes cost the same there and the narrow ones 12-18 % more, so the narrow shapes win exactly where the
+    //     wide ones would leave most CUs idle (N <= 8192, or a few hundred tokens);
+    //   * kFixed covers launch, prologue and epilogue.
+    // Ties within 4 % go to the larger tile (less decode work and fewer activation re-reads per output).
+    // Examples (13B o projection, N = K = 5120): M = 512 runs 96 x 128 tiles in 19.6 us (64 x 256: 23.6 us,
+    // 128 x 256: 36 us); M = 128 runs 64 x 128 tiles in 15.2 us (22.9 us); M = 2048 stays on 96 x 256 tiles.
+    struct Shape { int fm, fn; double alone, saturated, fixed; };
+    static const Shape kShapes[6] = {{4, 2, 1.48, 1.45, 5.4}, {3, 2, 1.15, 1.10, 4.7}, {2, 2, 0.94, 0.74, 4.4},
+                                     {4, 1, 0.94, 0.86, 3.5}, {3, 1, 0.715, 0.613, 3.4}, {2, 1, 0.594, 0.43, 3.2}};
+    const double steps = (double)ceil_div(K, 256);
+    int best = 0;
     double best_cost = 0.0;
-    for (int fm = 4; fm >= 2; --fm) {
-        const int64_t tiles = ceil_div(M, 32 * fm) * tiles_n;
-        const double cost = tiles <= 256 ? kAlone[fm] : kSaturated[fm] * (double)ceil_div(tiles, (int64_t)256);
-        if (fm == 4 || cost < 0.97 * best_cost) { best = fm; best_cost = cost; }
+    for (int c = 0; c < 6; ++c) {                       // largest tile first
+        const Shape& sh = kShapes[c];
+        const int64_t tiles = ceil_div(M, 32 * sh.fm) * ceil_div(N, 128 * sh.fn);
+        const double fill = (double)tiles / 256.0;
+        const double alone = sh.alone * (1.0 + 0.2 * (fill < 1.0 ? fill * fill : 1.0));
+        const double shared = (double)ceil_div(tiles, (int64_t)256) * sh.saturated;
+        const double cost = sh.fixed + steps * (alone > shared ? alone : shared);
+        if (c == 0 || cost < 0.96 * best_cost) { best = c; best_cost = cost; }
     }
-    if (best == 2) return launch_gemm_tiles<2>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream);
-    if (best == 3) return launch_gemm_tiles<3>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream);
-    return launch_gemm_tiles<4>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream);
+    return launch_linear_gemm_2bit_shape(kShapes[best].fm, kShapes[best].fn, xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream);
 }
 
 }  // namespace bitnet

@@ -103,6 +103,12 @@ def test_host_validation_rejects_before_launch():
     # a forced kernel that cannot take the shape
     assert lib.bitnet_linear_variant(a, a, a, a, 65, 16, 64, 0, a, 0, binding.KERNEL_GEMV, NULL) == 8
     assert lib.bitnet_linear_variant(odd, a, a, a, 1, 16, 64, 0, a, 0, binding.KERNEL_GEMV, NULL) == 8
+    # fixed-tile selectors of the prefill kernel: tile codes outside the six built ones, or an operand it cannot take
+    assert lib.bitnet_linear_variant(a, a, a, a, 65, 16, 64, 0, a, 0, 0x152, NULL) == 8
+    assert lib.bitnet_linear_variant(a, a, a, a, 65, 16, 64, 0, a, 0, 0x143, NULL) == 8
+    assert lib.bitnet_linear_variant(a, a, a, a, 65, 16, 64, 0, a, 0, 0x110, NULL) == 8
+    assert lib.bitnet_linear_variant(odd, a, a, a, 65, 16, 64, 0, a, 0, binding.KERNEL_GEMM_TILES[(64, 128)], NULL) == 8
+    assert lib.bitnet_linear_variant(a, a, a, a, 65, 16, 64, 0, a, 0, 77, NULL) == 8
 
 
 def test_layout_decoder_roundtrip_on_a_hand_packed_tile():

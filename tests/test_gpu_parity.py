@@ -278,11 +278,10 @@ def test_linear_fused_rejects_what_it_cannot_run(gpu_lib):
     assert e.value.status == 8
 
 
-# tiles of 256 x 256 with ragged edges in M, N and K (K steps of 256 with a partial last step), token
-# counts below one tile, and several tiles in each direction
-# The tile height (64, 96 or 128 tokens) follows a cost model of tile count and height; the last three shapes
-# select 64-, 96- and 128-token tiles on large grids, the others 64-token tiles on small ones.  Ragged tails in
-# M, N and K throughout.
+# ragged edges in M, N and K (K steps of 256 with a partial last step), token counts below one tile, and several
+# tiles in each direction.  The workgroup tile (64, 96 or 128 tokens x 128 or 256 weight rows) follows a cost model
+# of tile count and shape; the last three shapes fill the chip, the others leave most of it idle and get the small
+# tiles (each tile shape is also forced on its own in test_linear_gemm_every_tile_shape).
 GEMM_SHAPES = [(65, 300, 528), (128, 256, 256), (100, 40, 16), (300, 520, 1040), (257, 1000, 3200), (513, 270, 4112),
                (1024, 512, 1536), (96, 256, 64), (97, 257, 272), (300, 35850, 80), (520, 15400, 144), (512, 27700, 80)]
 
@@ -291,6 +290,16 @@ GEMM_SHAPES = [(65, 300, 528), (128, 256, 256), (100, 40, 16), (300, 520, 1040),
 def test_linear_gemm_kernel(gpu_lib, M, N, K):
     say("linear gemm M=%d N=%d K=%d" % (M, N, K))
     _run_linear_case(gpu_lib, M, N, K, [gpu_lib.KERNEL_GEMM, gpu_lib.KERNEL_AUTO], layer=M % 13, bf16_acts=(M % 2 == 0))
+
+
+# every workgroup tile of the prefill kernel (tokens x weight rows), each on shapes with several tiles and ragged
+# tails in M, N and K, one of them smaller than a single tile
+@pytest.mark.parametrize("tile", [(128, 256), (96, 256), (64, 256), (128, 128), (96, 128), (64, 128)])
+def test_linear_gemm_every_tile_shape(gpu_lib, tile):
+    kern = gpu_lib.KERNEL_GEMM_TILES[tile]
+    for (M, N, K) in [(300, 520, 1040), (257, 1000, 528), (100, 40, 16), (129, 130, 272), (65, 2100, 80)]:
+        say("linear gemm tile %dx%d M=%d N=%d K=%d" % (tile[0], tile[1], M, N, K))
+        _run_linear_case(gpu_lib, M, N, K, [kern], layer=(M + tile[0] + tile[1]) % 11, bf16_acts=(M % 2 == 1))
 
 
 def test_linear_gemm_small_m_and_forced_on_decode_shapes(gpu_lib):
@@ -520,7 +529,8 @@ def test_segmented_gamma_matches_oracle(gpu_lib, M, K, seg_rows):
     assert gamma_rb.cpu().numpy().tobytes() == ref["gamma_rb"].tobytes()
     assert np.array_equal(gpu_lib.unpack_weights(packed, N, K).cpu().numpy(), ref["codes"])
     xq, sx = gpu_lib.quantize_acts(dev(x))
-    kernels = [gpu_lib.KERNEL_AUTO, gpu_lib.KERNEL_REFERENCE, gpu_lib.KERNEL_GEMM]
+    kernels = [gpu_lib.KERNEL_AUTO, gpu_lib.KERNEL_REFERENCE, gpu_lib.KERNEL_GEMM,
+               gpu_lib.KERNEL_GEMM_TILES[(96, 128)], gpu_lib.KERNEL_GEMM_TILES[(64, 128)], gpu_lib.KERNEL_GEMM_TILES[(128, 256)]]
     if M <= 64:
         kernels.append(gpu_lib.KERNEL_GEMV)
     for kern in kernels:
@@ -659,6 +669,6 @@ def test_outputs_do_not_spill_past_their_buffers(gpu_lib):
     xq, sx = gpu_lib.quantize_acts(x, xq=xq_big[: M * K].view(M, K))
     assert bool((xq_big[M * K:] == 0x55).all())
     y_big = torch.full((M * N + 16,), 7.0, dtype=torch.float32, device="cuda")
-    for kern in (gpu_lib.KERNEL_REFERENCE, gpu_lib.KERNEL_GEMV, gpu_lib.KERNEL_GEMM):
+    for kern in (gpu_lib.KERNEL_REFERENCE, gpu_lib.KERNEL_GEMV, gpu_lib.KERNEL_GEMM) + tuple(gpu_lib.KERNEL_GEMM_TILES.values()):
         gpu_lib.linear(xq, sx, packed, gamma, N, y=y_big[: M * N].view(M, N), kernel=kern)
         assert bool((y_big[M * N:] == 7.0).all())
