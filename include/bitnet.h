@@ -202,8 +202,8 @@ bitnet_status bitnet_linear_variant(const int8_t* xq, const float* sx, const voi
  * every workgroup re-derives them for all M tokens into LDS (x is small and cache-resident at decode
  * sizes); nothing is written besides y.
  *   x   [M][K], dtype F32 or BF16, 16-byte aligned
- *   Limits: M <= 16, K a multiple of 16 and M * 256 * ceil(K / 256) + 128 <= 65536 bytes of LDS
- *   (M = 1 up to K = 65280, M = 4 up to K = 16128); otherwise BITNET_ERR_KERNEL and nothing is launched.
+ *   Limits: M <= 16, K a multiple of 16 and M * 256 * ceil(K / 256) + 512 <= 65536 bytes of LDS
+ *   (M = 1 up to K = 65024, M = 4 up to K = 16128); otherwise BITNET_ERR_KERNEL and nothing is launched.
  * Meant for M = 1, where it saves a launch (3B-class layers on MI355X: 3.7-7.2 us against 5.6-8.9 us for the
  * two calls).  Because every workgroup repeats the quantization of all M tokens, bitnet_quantize_acts followed
  * by bitnet_linear is the faster route from about M = 4 on (measured: 10.7 us against 12.9 us on a 3200 ->
@@ -213,6 +213,26 @@ bitnet_status bitnet_linear_variant(const int8_t* xq, const float* sx, const voi
 bitnet_status bitnet_linear_fused(const void* x, bitnet_dtype x_dtype, const void* packed,
                                   const float* gamma, int64_t M, int64_t N, int64_t K,
                                   bitnet_format f, void* y, bitnet_dtype y_dtype, void* stream);
+
+/*
+ * The same with RMSNorm in front (Section 2, "LLaMA-alike components": RMSNorm precedes the attention and the
+ * feed-forward BitLinear layers): y = BitLinear(RMSNorm(x)) in one launch, x -> y.  Same arithmetic as
+ * bitnet_rmsnorm_quantize followed by bitnet_linear, with bit-identical x_q and s_x; every workgroup re-derives
+ * them into LDS, nothing is written besides y.  At decode (M = 1) it replaces two launches of a dependent chain.
+ *   x    [M][K], dtype F32 or BF16, 16-byte aligned
+ *   g    [K] float (device), 16-byte aligned, or NULL for no gain
+ *   eps  added to the mean square; >= 0 (BITNET_ERR_SHAPE otherwise)
+ *   Limits as for bitnet_linear_fused.  2-bit format only.
+ * bitnet_rmsnorm_linear_fused_segmented: with one gamma per 16-row block, as bitnet_linear_fused_segmented.
+ */
+bitnet_status bitnet_rmsnorm_linear_fused(const void* x, bitnet_dtype x_dtype, const float* g, float eps,
+                                          const void* packed, const float* gamma, int64_t M, int64_t N,
+                                          int64_t K, bitnet_format f, void* y, bitnet_dtype y_dtype,
+                                          void* stream);
+bitnet_status bitnet_rmsnorm_linear_fused_segmented(const void* x, bitnet_dtype x_dtype, const float* g,
+                                                    float eps, const void* packed, const float* gamma_rb,
+                                                    int64_t M, int64_t N, int64_t K, bitnet_format f,
+                                                    void* y, bitnet_dtype y_dtype, void* stream);
 
 /*
  * One scale per segment of rows.  Eq. (3) gives every weight matrix its own gamma; when several

@@ -26,6 +26,7 @@ SYMBOLS = [
     "bitnet_quantize_weights", "bitnet_quantize_acts", "bitnet_linear", "bitnet_linear_variant",
     "bitnet_linear_fused", "bitnet_unpack_weights", "bitnet_rmsnorm_quantize", "bitnet_swiglu_quantize",
     "bitnet_quantize_weights_segmented", "bitnet_linear_segmented", "bitnet_linear_fused_segmented",
+    "bitnet_rmsnorm_linear_fused", "bitnet_rmsnorm_linear_fused_segmented",
 ]
 
 _lib = None
@@ -64,6 +65,8 @@ def load():
     lib.bitnet_quantize_weights_segmented.argtypes = [vp, ci, i64, i64, ci, ctypes.POINTER(i64), ci, vp, vp, vp, sz, vp]
     lib.bitnet_linear_segmented.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, ci, ci, vp]
     lib.bitnet_linear_fused_segmented.argtypes = [vp, ci, vp, vp, i64, i64, i64, ci, vp, ci, vp]
+    lib.bitnet_rmsnorm_linear_fused.argtypes = [vp, ci, vp, ctypes.c_float, vp, vp, i64, i64, i64, ci, vp, ci, vp]
+    lib.bitnet_rmsnorm_linear_fused_segmented.argtypes = [vp, ci, vp, ctypes.c_float, vp, vp, i64, i64, i64, ci, vp, ci, vp]
     for name in SYMBOLS[2:]:
         getattr(lib, name).restype = ci
     _lib = lib
@@ -255,6 +258,26 @@ def linear_fused_segmented(x, packed, gamma_rb, N, fmt=PACK_2BIT, y_dtype=F32, y
                                              _dev(gamma_rb, "gamma_rb", (torch.float32,)), M, N, K, fmt,
                                              _dev(y, "y", (_OUT[y_dtype],)), y_dtype, _stream()),
            "bitnet_linear_fused_segmented")
+    return y
+
+
+def rmsnorm_linear_fused(x, g, eps, packed, gamma, N, fmt=PACK_2BIT, y_dtype=F32, y=None, segmented=False):
+    """y = BitLinear(RMSNorm(x) * g) in one launch (decode path; g [K] float32 or None).  With segmented=True
+    `gamma` holds one scale per 16-row block (from quantize_weights_segmented)."""
+    lib = load()
+    xp = _dev(x, "x", _FLOAT, 2)
+    M, K = x.shape
+    if y is None:
+        y = torch.empty((M, N), dtype=_OUT[y_dtype], device=x.device)
+    gp = None if g is None else _dev(g, "g", (torch.float32,))
+    if g is not None and tuple(g.shape) != (K,):
+        raise ValueError("g must have one entry per column")
+    if segmented and gamma.numel() < (N + 15) // 16:
+        raise ValueError("gamma needs one entry per 16-row block")
+    fn = lib.bitnet_rmsnorm_linear_fused_segmented if segmented else lib.bitnet_rmsnorm_linear_fused
+    _check(fn(xp, _FLOAT[x.dtype], gp, float(eps), _dev(packed, "packed"), _dev(gamma, "gamma", (torch.float32,)),
+              M, N, K, fmt, _dev(y, "y", (_OUT[y_dtype],)), y_dtype, _stream()),
+           "bitnet_rmsnorm_linear_fused_segmented" if segmented else "bitnet_rmsnorm_linear_fused")
     return y
 
 

@@ -270,6 +270,37 @@ bitnet_status bitnet_linear_fused_segmented(const void* x, bitnet_dtype x_dtype,
     return linear_fused_any(x, x_dtype, packed, gamma_rb, 1, M, N, K, f, y, y_dtype, stream);
 }
 
+static bitnet_status rmsnorm_linear_fused_any(const void* x, bitnet_dtype x_dtype, const float* g, float eps,
+                                              const void* packed, const float* gamma, int gstride, int64_t M,
+                                              int64_t N, int64_t K, bitnet_format f, void* y, bitnet_dtype y_dtype,
+                                              void* stream) {
+    if (!x || !packed || !gamma || !y) return BITNET_ERR_NULL;
+    if (!shape_ok(M, N, K) || !(eps >= 0.0f)) return BITNET_ERR_SHAPE;
+    if (x_dtype != BITNET_F32 && x_dtype != BITNET_BF16) return BITNET_ERR_DTYPE;
+    OutType yt;
+    if (!out_type(y_dtype, &yt)) return BITNET_ERR_DTYPE;
+    if (!format_ok(f)) return BITNET_ERR_FORMAT;
+    if (!aligned(packed, 16) || !aligned(gamma, 4) || !aligned(y, dtype_size(y_dtype)) || (g && !aligned(g, 16)))
+        return BITNET_ERR_ALIGN;
+    if (f != BITNET_PACK_2BIT) return BITNET_ERR_FORMAT;
+    if (!bitnet::gemv_fused_supports(M, N, K, x)) return BITNET_ERR_KERNEL;
+    return from_hip(bitnet::launch_rmsnorm_linear_fused_2bit(x, x_dtype == BITNET_BF16, g, eps, packed, gamma, gstride,
+                                                             M, N, K, y, yt, static_cast<hipStream_t>(stream)));
+}
+
+bitnet_status bitnet_rmsnorm_linear_fused(const void* x, bitnet_dtype x_dtype, const float* g, float eps,
+                                          const void* packed, const float* gamma, int64_t M, int64_t N, int64_t K,
+                                          bitnet_format f, void* y, bitnet_dtype y_dtype, void* stream) {
+    return rmsnorm_linear_fused_any(x, x_dtype, g, eps, packed, gamma, 0, M, N, K, f, y, y_dtype, stream);
+}
+
+bitnet_status bitnet_rmsnorm_linear_fused_segmented(const void* x, bitnet_dtype x_dtype, const float* g, float eps,
+                                                    const void* packed, const float* gamma_rb, int64_t M, int64_t N,
+                                                    int64_t K, bitnet_format f, void* y, bitnet_dtype y_dtype,
+                                                    void* stream) {
+    return rmsnorm_linear_fused_any(x, x_dtype, g, eps, packed, gamma_rb, 1, M, N, K, f, y, y_dtype, stream);
+}
+
 bitnet_status bitnet_unpack_weights(const void* packed, int64_t N, int64_t K, bitnet_format f, int8_t* codes,
                                     void* stream) {
     if (!packed || !codes) return BITNET_ERR_NULL;

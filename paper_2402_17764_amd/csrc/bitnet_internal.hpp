@@ -57,6 +57,10 @@ hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void
 bool gemv_fused_supports(int64_t M, int64_t N, int64_t K, const void* x);
 hipError_t launch_linear_fused_2bit(const void* x, bool bf16, const void* packed, const float* gamma, int gstride,
                                     int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);
+// the same with RMSNorm (optional per-column gain, 16-byte aligned) in front of the quantization
+hipError_t launch_rmsnorm_linear_fused_2bit(const void* x, bool bf16, const float* gain, float eps, const void* packed,
+                                            const float* gamma, int gstride, int64_t M, int64_t N, int64_t K, void* y,
+                                            OutType yt, hipStream_t stream);
 
 // linear_gemm.hip
 bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq);

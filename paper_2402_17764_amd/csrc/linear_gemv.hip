@@ -91,10 +91,14 @@ enum XMode : int {
     kXGlobal = 0,      // int8 x_q read from global memory with every step
     kXLds = 1,         // int8 x_q copied once per workgroup into LDS
     kXFusedBf16 = 2,   // bf16 x: per-token absmax quantization done in the kernel, x_q lives only in LDS
-    kXFusedF32 = 3     // fp32 x, same
+    kXFusedF32 = 3,    // fp32 x, same
+    kXNormBf16 = 4,    // bf16 x: RMSNorm (with an optional gain) and the quantization done in the kernel
+    kXNormF32 = 5      // fp32 x, same
 };
 
-constexpr int kGemvLdsHeader = 8;       // uint4 slots in front of the x region: reduction scratch + s_x
+// uint4 slots in front of the x region: 16 floats of reduction scratch, 16 floats of s_x, 2 x 16 doubles for the
+// double-double reduction of the RMSNorm modes
+constexpr int kGemvLdsHeader = 32;
 
 // In-kernel activation quantization for the fused modes (Section 2 of the paper: per-token absmax,
 // Q_b = 127), the same arithmetic as the stand-alone activation kernel: s = max(absmax, 1e-5),
@@ -156,22 +160,119 @@ __device__ inline float block_absmax_to_scale(float amax, float* red) {
     return fmaxf(mx, kEps);
 }
 
-template <bool kBf16, int kThreads>
+// a 16-byte vector of x widened to fp32
+template <bool kBf16>
+__device__ inline void vec_expand(const uint4& q, float (&f)[kBf16 ? 8 : 4]) {
+    const uint32_t u[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (kBf16) {
+            f[2 * e] = __uint_as_float(u[e] << 16);
+            f[2 * e + 1] = __uint_as_float(u[e] & 0xFFFF0000u);
+        } else {
+            f[e] = __uint_as_float(u[e]);
+        }
+    }
+}
+
+// exact sum over the block of per-thread double-double partial sums (butterfly inside each wave, then the
+// waves in order; every thread gets the result) -- the same fixed-shape tree as the stand-alone RMSNorm kernel
+template <int kWaves>
+__device__ inline double gemv_block_sum_dd(dd v, double* sh_hi, double* sh_lo) {
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const dd o{__shfl_xor(v.hi, off, kWave), __shfl_xor(v.lo, off, kWave)};
+        dd_add_dd(v, o);
+    }
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { sh_hi[wave] = v.hi; sh_lo[wave] = v.lo; }
+    __syncthreads();
+    dd t{sh_hi[0], sh_lo[0]};
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) dd_add_dd(t, dd{sh_hi[w], sh_lo[w]});
+    return t.hi + t.lo;
+}
+
+// kNorm: the token first goes through RMSNorm, z = (x * r) * gain with r = (float)(1 / sqrt(mean(x^2) + eps)),
+// the mean of squares exact (fp64 squares of fp32 values, double-double sums) -- the arithmetic of the
+// stand-alone RMSNorm -> int8 kernel, so both give the same codes and scales (Section 2 of the paper:
+// LLaMA-alike components, RMSNorm in front of the attention and feed-forward BitLinear layers).
+template <bool kBf16, bool kNorm, int kThreads>
 __device__ inline void fused_quantize_to_lds(const void* __restrict__ xv, const uint4 (&row0)[kFusedRegVecs], bool row0_in_regs,
-                                             int M, int64_t K, int Kpad, float* red, float* sxl, uint4* xlds) {
+                                             int M, int64_t K, int Kpad, const float* __restrict__ gain, float eps,
+                                             float* red, float* sxl, uint4* xlds) {
     constexpr int kE = kBf16 ? 8 : 4;                 // elements per 16-byte vector
+    constexpr int kWaves = kThreads / kWave;
     const int nvec = (int)(K / kE);
     const int nvec_pad = Kpad / kE;
+    double* sh_hi = reinterpret_cast<double*>(red + 32);
+    double* sh_lo = sh_hi + 16;
     for (int m = 0; m < M; ++m) {
         const uint4* row = reinterpret_cast<const uint4*>(static_cast<const char*>(xv) + (int64_t)m * K * (kBf16 ? 2 : 4));
         uint32_t* out = reinterpret_cast<uint32_t*>(xlds) + (size_t)m * (Kpad >> 2);
         const bool regs = m == 0 && row0_in_regs;
+        float r = 1.0f;
+        if (kNorm) {
+            // two interleaved accumulators: the sums are exact, so splitting them only shortens the dependent chain
+            dd acc{0.0, 0.0}, acc2{0.0, 0.0};
+            auto add_squares = [&](const uint4& q) {
+                float f[kE];
+                vec_expand<kBf16>(q, f);
+#pragma unroll
+                for (int e = 0; e < kE; e += 2) {
+                    dd_add_double(acc, (double)f[e] * (double)f[e]);
+                    dd_add_double(acc2, (double)f[e + 1] * (double)f[e + 1]);
+                }
+            };
+            if (regs) {
+#pragma unroll
+                for (int v = 0; v < kFusedRegVecs; ++v)
+                    if (v * kThreads + (int)threadIdx.x < nvec) add_squares(row0[v]);     // clamped duplicates do not count
+            } else {
+                for (int v = threadIdx.x; v < nvec; v += kThreads) add_squares(row[v]);
+            }
+            dd_add_dd(acc, acc2);
+            const double ms = gemv_block_sum_dd<kWaves>(acc, sh_hi, sh_lo) / (double)K;
+            r = (float)(1.0 / sqrt(ms + (double)eps));
+        }
+        // z of one vector (kNorm): the same two multiplies wherever it is evaluated, so the same value
+        auto normalized = [&](const uint4& q, int v, float (&f)[kE]) {
+            vec_expand<kBf16>(q, f);
+#pragma unroll
+            for (int e = 0; e < kE; ++e) f[e] = f[e] * r;
+            if (gain) {
+#pragma unroll
+                for (int h = 0; h < kE / 4; ++h) {
+                    const float4 gq = *reinterpret_cast<const float4*>(gain + (size_t)v * kE + 4 * h);
+                    f[4 * h] = f[4 * h] * gq.x; f[4 * h + 1] = f[4 * h + 1] * gq.y;
+                    f[4 * h + 2] = f[4 * h + 2] * gq.z; f[4 * h + 3] = f[4 * h + 3] * gq.w;
+                }
+            }
+        };
+        auto absmax_of = [&](const uint4& q, int v, float amax) {
+            if (!kNorm) return vec_absmax<kBf16>(q, amax);
+            float f[kE];
+            normalized(q, v, f);
+#pragma unroll
+            for (int e = 0; e < kE; ++e) amax = fmaxf(amax, fabsf(f[e]));
+            return amax;
+        };
+        auto quantize_store = [&](const uint4& q, int v, float inv) {
+            if (!kNorm) { vec_quantize_store<kBf16>(q, inv, out, v); return; }
+            float f[kE];
+            normalized(q, v, f);
+#pragma unroll
+            for (int h = 0; h < kE / 4; ++h)
+                out[(kE / 4) * v + h] = quant_byte(f[4 * h], inv) | (quant_byte(f[4 * h + 1], inv) << 8) |
+                                        (quant_byte(f[4 * h + 2], inv) << 16) | (quant_byte(f[4 * h + 3], inv) << 24);
+        };
         float amax = 0.0f;
         if (regs) {
 #pragma unroll
-            for (int v = 0; v < kFusedRegVecs; ++v) amax = vec_absmax<kBf16>(row0[v], amax);   // clamped duplicates are harmless
+            for (int v = 0; v < kFusedRegVecs; ++v)                                         // clamped duplicates are harmless
+                amax = absmax_of(row0[v], min(v * kThreads + (int)threadIdx.x, nvec - 1), amax);
         } else {
-            for (int v = threadIdx.x; v < nvec; v += kThreads) amax = vec_absmax<kBf16>(row[v], amax);
+            for (int v = threadIdx.x; v < nvec; v += kThreads) amax = absmax_of(row[v], v, amax);
         }
         const float sc = block_absmax_to_scale<kThreads>(amax, red);
         const float inv = kQb / sc;                   // one IEEE division per token
@@ -180,10 +281,10 @@ __device__ inline void fused_quantize_to_lds(const void* __restrict__ xv, const 
 #pragma unroll
             for (int v = 0; v < kFusedRegVecs; ++v) {
                 const int idx = v * kThreads + (int)threadIdx.x;
-                if (idx < nvec) vec_quantize_store<kBf16>(row0[v], inv, out, idx);
+                if (idx < nvec) quantize_store(row0[v], idx, inv);
             }
         } else {
-            for (int v = threadIdx.x; v < nvec; v += kThreads) vec_quantize_store<kBf16>(row[v], inv, out, v);
+            for (int v = threadIdx.x; v < nvec; v += kThreads) quantize_store(row[v], v, inv);
         }
         for (int v = nvec + threadIdx.x; v < nvec_pad; v += kThreads)                          // zero padding
             vec_quantize_store<kBf16>(make_uint4(0, 0, 0, 0), inv, out, v);
@@ -201,11 +302,14 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
         const void* __restrict__ xin /* x_q, or x for the fused modes */, const float* __restrict__ sx,
         const uint4* __restrict__ packed, const float* __restrict__ gamma, int gstride /* 0: one gamma, 1: one per row block */,
         int M, int64_t N, int64_t K, int Kq, int RB,
-        int items /* K steps per wave, rounded up to a multiple of kD */, void* __restrict__ y, OutType yt) {
+        int items /* K steps per wave, rounded up to a multiple of kD */, void* __restrict__ y, OutType yt,
+        const float* __restrict__ gain /* RMSNorm modes: per-column gain or null */, float eps) {
     extern __shared__ uint4 smem[];
     constexpr int kThreads = kS * kW * kWave;
     constexpr bool kFromLds = kX != kXGlobal;
-    constexpr bool kFused = kX == kXFusedBf16 || kX == kXFusedF32;
+    constexpr bool kFused = kX >= kXFusedBf16;
+    constexpr bool kNorm = kX >= kXNormBf16;
+    constexpr bool kInBf16 = kX == kXFusedBf16 || kX == kXNormBf16;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const int r = lane & 15;
@@ -219,7 +323,7 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
     const int8_t* xq = static_cast<const int8_t*>(xin);
 
     float* red = reinterpret_cast<float*>(smem);       // [16] reduction scratch (fused modes)
-    float* sxl = red + 16;                             // [16] s_x of the fused modes
+    float* sxl = red + 16;                             // [16] s_x of the fused modes; doubles for the RMSNorm sum follow
     uint4* xlds = smem + kGemvLdsHeader;               // x_q rows, Kpad bytes each; later the fold buffer
 
     const int64_t wstride = (int64_t)RB * 64;          // quads per whole step
@@ -272,7 +376,7 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
     uint4 row0[kFusedRegVecs];
     bool row0_in_regs = false;
     if (kFused) {
-        const int nvec = (int)(K / (kX == kXFusedBf16 ? 8 : 4));
+        const int nvec = (int)(K / (kInBf16 ? 8 : 4));
         row0_in_regs = nvec <= kFusedRegVecs * kThreads;
         if (row0_in_regs) {
 #pragma unroll
@@ -308,7 +412,7 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
         }
         __syncthreads();
     } else if (kFused) {
-        fused_quantize_to_lds<kX == kXFusedBf16, kThreads>(xin, row0, row0_in_regs, M, K, Kpad, red, sxl, xlds);
+        fused_quantize_to_lds<kInBf16, kNorm, kThreads>(xin, row0, row0_in_regs, M, K, Kpad, gain, eps, red, sxl, xlds);
     }
 
     int i = 0;
@@ -760,7 +864,7 @@ static size_t gemv16_x_lds_bytes(int64_t M, int64_t K) { return (size_t)M * ceil
 
 template <int kR, int kS, int kW, int kD>
 static void launch16(int xmode, const void* x, const float* sx, const void* packed, const float* gamma, int gstride,
-                     int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
+                     int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream, const float* gain, float eps) {
     const int Kq = (int)ceil_div(K, kColsPerQuad);
     const int RB = (int)ceil_div(N, kRowsPerBlock);
     int items = (int)ceil_div(ceil_div(K, 256), kS);
@@ -773,12 +877,14 @@ static void launch16(int xmode, const void* x, const float* sx, const void* pack
     dim3 grid((unsigned)ceil_div(RB, kW * kR)), block(kS * kW * kWave);
     const uint4* p = static_cast<const uint4*>(packed);
 #define GO(X_) hipLaunchKernelGGL((linear_gemv16_2bit<kR, kS, kW, kD, X_>), grid, block, lds, stream, x, sx, p, gamma, gstride, (int)M, N, \
-                                  K, Kq, RB, items, y, yt)
+                                  K, Kq, RB, items, y, yt, gain, eps)
     switch (xmode) {
         case kXGlobal: GO(kXGlobal); break;
         case kXLds: GO(kXLds); break;
         case kXFusedBf16: GO(kXFusedBf16); break;
-        default: GO(kXFusedF32); break;
+        case kXFusedF32: GO(kXFusedF32); break;
+        case kXNormBf16: GO(kXNormBf16); break;
+        default: GO(kXNormF32); break;
     }
 #undef GO
 }
@@ -834,11 +940,12 @@ static hipError_t launch_skinny_ws(const int8_t* xq, const float* sx, const void
 // xmode < 0 (x_q given) lets the shape decide between global and LDS-staged x_q; the fused modes
 // pass their own and need the wide workgroups that can hold token 0 in registers.
 static void dispatch16(int xmode, const void* x, const float* sx, const void* packed, const float* gamma, int gstride,
-                       int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
+                       int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream,
+                       const float* gain = nullptr, float eps = 0.0f) {
     const int64_t RB = ceil_div(N, kRowsPerBlock);
     const int64_t steps = ceil_div(K, 256);
     const bool fused = xmode >= 0;
-#define GEMV16(R_, S_, W_, D_, X_) launch16<R_, S_, W_, D_>(fused ? xmode : (X_), x, sx, packed, gamma, gstride, M, N, K, y, yt, stream)
+#define GEMV16(R_, S_, W_, D_, X_) launch16<R_, S_, W_, D_>(fused ? xmode : (X_), x, sx, packed, gamma, gstride, M, N, K, y, yt, stream, gain, eps)
     if (RB >= 2048) {
         if (fused) GEMV16(4, 1, 4, 2, kXGlobal); else GEMV16(4, 1, 4, 3, kXGlobal);
     } else if (steps >= 64) {
@@ -898,6 +1005,13 @@ bool gemv_fused_supports(int64_t M, int64_t N, int64_t K, const void* x) {
 hipError_t launch_linear_fused_2bit(const void* x, bool bf16, const void* packed, const float* gamma, int gstride,
                                     int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
     dispatch16(bf16 ? kXFusedBf16 : kXFusedF32, x, nullptr, packed, gamma, gstride, M, N, K, y, yt, stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_rmsnorm_linear_fused_2bit(const void* x, bool bf16, const float* gain, float eps, const void* packed,
+                                            const float* gamma, int gstride, int64_t M, int64_t N, int64_t K, void* y,
+                                            OutType yt, hipStream_t stream) {
+    dispatch16(bf16 ? kXNormBf16 : kXNormF32, x, nullptr, packed, gamma, gstride, M, N, K, y, yt, stream, gain, eps);
     return hipGetLastError();
 }
 

@@ -263,6 +263,71 @@ def test_linear_fused_matches_oracle(gpu_lib, M, N, K, dtype):
     check_y(gpu_lib.linear_fused(xd, packed, gamma, N, y_dtype=gpu_lib.BF16).float().cpu().numpy(), ref["y"], RTOL_BF16)
 
 
+# RMSNorm + quantization + product in one launch: each branch of the decode kernel's selection, token 0 in
+# registers and the re-reading path (M > 1, long K), K tails, with and without gain
+NORM_FUSED_SHAPES = [(1, 4096, 1536), (1, 100, 3200), (3, 250, 1040), (1, 33, 4112), (16, 70, 528), (1, 16400, 272),
+                     (2, 16400, 4112), (1, 600, 16400), (1, 6416, 8640), (4, 300, 8192), (1, 32800, 528), (5, 40, 16)]
+
+
+@pytest.mark.parametrize("M,N,K", NORM_FUSED_SHAPES)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_rmsnorm_linear_fused_matches_oracle(gpu_lib, M, N, K, dtype):
+    """x -> RMSNorm -> int8 -> product in one launch: x_q and s_x must be those of the oracle's RMSNorm
+    quantizer (the int32 accumulators show it), and the result that of the two separate GPU calls, bit for bit."""
+    say("rmsnorm linear fused %s M=%d N=%d K=%d" % (dtype, M, N, K))
+    W = synth.weights(N, K, config=0, layer=M + 30, tensor=0)
+    if dtype == "bf16":
+        x, bits = synth.activations(M, K, config=2, layer=M + 30, tensor=5, bf16=True)
+        xd = bf16_tensor(bits).view(M, K)
+    else:
+        x = synth.activations(M, K, config=0, layer=M + 30, tensor=5)
+        xd = dev(x)
+    rng = np.random.default_rng([11, K, M])
+    g = (1.0 + 0.25 * rng.standard_normal(K)).astype(np.float32)
+    gamma_ref, _ = oracle.absmean_gamma(W)
+    codes_ref = oracle.ternarize(W, gamma_ref)
+    packed, gamma = gpu_lib.quantize_weights(dev(W))
+    for gain, eps in ((g, 1e-5), (None, 1e-6)):
+        xq_ref, sx_ref, _ = oracle.rmsnorm_quantize(x, gain, eps)
+        acc_ref = oracle.ternary_matmul(xq_ref, codes_ref)
+        y_ref = oracle.rescale(acc_ref, gamma_ref, sx_ref)
+        gd = None if gain is None else dev(gain)
+        acc = gpu_lib.rmsnorm_linear_fused(xd, gd, eps, packed, gamma, N, y_dtype=gpu_lib.I32)
+        assert np.array_equal(acc.cpu().numpy(), acc_ref)
+        y32 = gpu_lib.rmsnorm_linear_fused(xd, gd, eps, packed, gamma, N, y_dtype=gpu_lib.F32)
+        check_y(y32.cpu().numpy(), y_ref, RTOL_F32)
+        y16 = gpu_lib.rmsnorm_linear_fused(xd, gd, eps, packed, gamma, N, y_dtype=gpu_lib.BF16)
+        check_y(y16.float().cpu().numpy(), y_ref, RTOL_BF16)
+        xq, sx = gpu_lib.rmsnorm_quantize(xd, gd, eps)
+        assert torch.equal(y32, gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.F32))
+
+
+def test_rmsnorm_linear_fused_segmented_and_limits(gpu_lib):
+    say("rmsnorm linear fused: segment scales, limits")
+    M, K, seg_rows = 2, 528, [48, 16, 100]
+    N = sum(seg_rows)
+    W = synth.weights(N, K, config=0, layer=3, tensor=9)
+    W[48:64] *= np.float32(2.5)
+    x = synth.activations(M, K, config=0, layer=3, tensor=10)
+    g = (1.0 + 0.1 * np.arange(K) / K).astype(np.float32)
+    packed, gamma_rb = gpu_lib.quantize_weights_segmented(dev(W), seg_rows)
+    xq, sx = gpu_lib.rmsnorm_quantize(dev(x), dev(g), 1e-6)
+    want = gpu_lib.linear_segmented(xq, sx, packed, gamma_rb, N, y_dtype=gpu_lib.F32, kernel=gpu_lib.KERNEL_REFERENCE)
+    got = gpu_lib.rmsnorm_linear_fused(dev(x), dev(g), 1e-6, packed, gamma_rb, N, y_dtype=gpu_lib.F32, segmented=True)
+    assert torch.equal(got, want)
+    # an all-zero token: r = 1 / sqrt(eps), z = 0, s_x = 1e-5, y = 0
+    z = torch.zeros((1, K), dtype=torch.float32, device="cuda")
+    p1, g1 = gpu_lib.quantize_weights(dev(W))
+    assert bool((gpu_lib.rmsnorm_linear_fused(z, None, 1e-6, p1, g1, N) == 0).all())
+    # limits: more than 16 tokens, a negative eps
+    with pytest.raises(gpu_lib.BitnetError) as e:
+        gpu_lib.rmsnorm_linear_fused(dev(synth.activations(17, K, config=0, layer=1)), None, 1e-6, p1, g1, N)
+    assert e.value.status == 8
+    with pytest.raises(gpu_lib.BitnetError) as e:
+        gpu_lib.rmsnorm_linear_fused(dev(x), None, -1.0, p1, g1, N)
+    assert e.value.status == 2
+
+
 def test_linear_fused_rejects_what_it_cannot_run(gpu_lib):
     say("linear fused limits")
     W = dev(synth.weights(32, 8192, config=0, layer=1))
