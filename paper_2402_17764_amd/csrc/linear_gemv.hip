@@ -106,6 +106,9 @@ constexpr int kGemvLdsHeader = 32;
 // sxl[m].  Token 0 is fetched into registers before the weight prefetch is issued (so that waiting for
 // it does not wait for the weights) and quantized from there; further tokens take two sweeps.
 constexpr int kFusedRegVecs = 4;          // 16-byte vectors of token 0 a thread can hold
+// ... and how many of them also get their RMSNorm gain prefetched (the rest read it after the reduction);
+// the 1024-thread workgroups have 128 registers per lane and none to spare
+constexpr int gain_reg_vecs(int threads) { return threads >= 1024 ? 0 : 2; }
 
 template <bool kBf16>
 __device__ inline float vec_absmax(const uint4& q, float amax) {
@@ -175,21 +178,40 @@ __device__ inline void vec_expand(const uint4& q, float (&f)[kBf16 ? 8 : 4]) {
     }
 }
 
-// exact sum over the block of per-thread double-double partial sums (butterfly inside each wave, then the
-// waves in order; every thread gets the result) -- the same fixed-shape tree as the stand-alone RMSNorm kernel
+// one double moved across lanes with a DPP control (both 32-bit halves)
+template <int kCtrl>
+__device__ inline double dpp_f64(double v) {
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = dpp_u32<kCtrl>((uint32_t)u), hi = dpp_u32<kCtrl>((uint32_t)(u >> 32));
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+__device__ inline double readlane_f64(double v, int lane) {
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)u, lane);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(u >> 32), lane);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+
+// Sum over the block of per-thread double-double partial sums; every thread gets the result.  The sums are
+// exact to ~2^-100, far below the rounding of the result to fp64, so the shape of the tree does not show:
+// four DPP steps inside each row of 16 lanes, the four rows of a wave through scalar reads, the waves in order.
 template <int kWaves>
 __device__ inline double gemv_block_sum_dd(dd v, double* sh_hi, double* sh_lo) {
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        const dd o{__shfl_xor(v.hi, off, kWave), __shfl_xor(v.lo, off, kWave)};
-        dd_add_dd(v, o);
-    }
+    dd_add_dd(v, dd{dpp_f64<0xB1>(v.hi), dpp_f64<0xB1>(v.lo)});       // lane ^ 1
+    dd_add_dd(v, dd{dpp_f64<0x4E>(v.hi), dpp_f64<0x4E>(v.lo)});       // lane ^ 2
+    dd_add_dd(v, dd{dpp_f64<0x141>(v.hi), dpp_f64<0x141>(v.lo)});     // other quad of the 8
+    dd_add_dd(v, dd{dpp_f64<0x140>(v.hi), dpp_f64<0x140>(v.lo)});     // other half of the 16
+    dd w{readlane_f64(v.hi, 0), readlane_f64(v.lo, 0)};
+    dd_add_dd(w, dd{readlane_f64(v.hi, 16), readlane_f64(v.lo, 16)});
+    dd_add_dd(w, dd{readlane_f64(v.hi, 32), readlane_f64(v.lo, 32)});
+    dd_add_dd(w, dd{readlane_f64(v.hi, 48), readlane_f64(v.lo, 48)});
+    if (kWaves == 1) return w.hi + w.lo;
     const int wave = threadIdx.x >> 6;
-    if ((threadIdx.x & 63) == 0) { sh_hi[wave] = v.hi; sh_lo[wave] = v.lo; }
+    if ((threadIdx.x & 63) == 0) { sh_hi[wave] = w.hi; sh_lo[wave] = w.lo; }
     __syncthreads();
     dd t{sh_hi[0], sh_lo[0]};
 #pragma unroll
-    for (int w = 1; w < kWaves; ++w) dd_add_dd(t, dd{sh_hi[w], sh_lo[w]});
+    for (int q = 1; q < kWaves; ++q) dd_add_dd(t, dd{sh_hi[q], sh_lo[q]});
     return t.hi + t.lo;
 }
 
@@ -199,6 +221,7 @@ __device__ inline double gemv_block_sum_dd(dd v, double* sh_hi, double* sh_lo) {
 // LLaMA-alike components, RMSNorm in front of the attention and feed-forward BitLinear layers).
 template <bool kBf16, bool kNorm, int kThreads>
 __device__ inline void fused_quantize_to_lds(const void* __restrict__ xv, const uint4 (&row0)[kFusedRegVecs], bool row0_in_regs,
+                                             const float4 (&gain0)[2][kBf16 ? 2 : 1] /* gain of row0's first columns */,
                                              int M, int64_t K, int Kpad, const float* __restrict__ gain, float eps,
                                              float* red, float* sxl, uint4* xlds) {
     constexpr int kE = kBf16 ? 8 : 4;                 // elements per 16-byte vector
@@ -236,31 +259,33 @@ __device__ inline void fused_quantize_to_lds(const void* __restrict__ xv, const 
             r = (float)(1.0 / sqrt(ms + (double)eps));
         }
         // z of one vector (kNorm): the same two multiplies wherever it is evaluated, so the same value
-        auto normalized = [&](const uint4& q, int v, float (&f)[kE]) {
+        // (slot >= 0: vector `slot` of the token held in registers, whose gain was requested with it)
+        auto normalized = [&](const uint4& q, int v, int slot, float (&f)[kE]) {
             vec_expand<kBf16>(q, f);
 #pragma unroll
             for (int e = 0; e < kE; ++e) f[e] = f[e] * r;
             if (gain) {
 #pragma unroll
                 for (int h = 0; h < kE / 4; ++h) {
-                    const float4 gq = *reinterpret_cast<const float4*>(gain + (size_t)v * kE + 4 * h);
+                    const float4 gq = (slot >= 0 && slot < gain_reg_vecs(kThreads)) ? gain0[slot][h]
+                                                                                    : *reinterpret_cast<const float4*>(gain + (size_t)v * kE + 4 * h);
                     f[4 * h] = f[4 * h] * gq.x; f[4 * h + 1] = f[4 * h + 1] * gq.y;
                     f[4 * h + 2] = f[4 * h + 2] * gq.z; f[4 * h + 3] = f[4 * h + 3] * gq.w;
                 }
             }
         };
-        auto absmax_of = [&](const uint4& q, int v, float amax) {
+        auto absmax_of = [&](const uint4& q, int v, int slot, float amax) {
             if (!kNorm) return vec_absmax<kBf16>(q, amax);
             float f[kE];
-            normalized(q, v, f);
+            normalized(q, v, slot, f);
 #pragma unroll
             for (int e = 0; e < kE; ++e) amax = fmaxf(amax, fabsf(f[e]));
             return amax;
         };
-        auto quantize_store = [&](const uint4& q, int v, float inv) {
+        auto quantize_store = [&](const uint4& q, int v, int slot, float inv) {
             if (!kNorm) { vec_quantize_store<kBf16>(q, inv, out, v); return; }
             float f[kE];
-            normalized(q, v, f);
+            normalized(q, v, slot, f);
 #pragma unroll
             for (int h = 0; h < kE / 4; ++h)
                 out[(kE / 4) * v + h] = quant_byte(f[4 * h], inv) | (quant_byte(f[4 * h + 1], inv) << 8) |
@@ -269,10 +294,14 @@ __device__ inline void fused_quantize_to_lds(const void* __restrict__ xv, const 
         float amax = 0.0f;
         if (regs) {
 #pragma unroll
-            for (int v = 0; v < kFusedRegVecs; ++v)                                         // clamped duplicates are harmless
-                amax = absmax_of(row0[v], min(v * kThreads + (int)threadIdx.x, nvec - 1), amax);
+            for (int v = 0; v < kFusedRegVecs; ++v) {
+                const int idx = v * kThreads + (int)threadIdx.x;
+                // plain absmax: clamped duplicates are harmless and cost less than a branch; with RMSNorm they
+                // would fetch their gain again
+                if (!kNorm || idx < nvec) amax = absmax_of(row0[v], min(idx, nvec - 1), v, amax);
+            }
         } else {
-            for (int v = threadIdx.x; v < nvec; v += kThreads) amax = absmax_of(row[v], v, amax);
+            for (int v = threadIdx.x; v < nvec; v += kThreads) amax = absmax_of(row[v], v, -1, amax);
         }
         const float sc = block_absmax_to_scale<kThreads>(amax, red);
         const float inv = kQb / sc;                   // one IEEE division per token
@@ -281,10 +310,10 @@ __device__ inline void fused_quantize_to_lds(const void* __restrict__ xv, const 
 #pragma unroll
             for (int v = 0; v < kFusedRegVecs; ++v) {
                 const int idx = v * kThreads + (int)threadIdx.x;
-                if (idx < nvec) quantize_store(row0[v], idx, inv);
+                if (idx < nvec) quantize_store(row0[v], idx, v, inv);
             }
         } else {
-            for (int v = threadIdx.x; v < nvec; v += kThreads) quantize_store(row[v], v, inv);
+            for (int v = threadIdx.x; v < nvec; v += kThreads) quantize_store(row[v], v, -1, inv);
         }
         for (int v = nvec + threadIdx.x; v < nvec_pad; v += kThreads)                          // zero padding
             vec_quantize_store<kBf16>(make_uint4(0, 0, 0, 0), inv, out, v);
@@ -374,6 +403,7 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
 
     // fused modes: token 0 goes to registers first (cache hits, back long before the weights)
     uint4 row0[kFusedRegVecs];
+    float4 gain0[2][kInBf16 ? 2 : 1];
     bool row0_in_regs = false;
     if (kFused) {
         const int nvec = (int)(K / (kInBf16 ? 8 : 4));
@@ -382,6 +412,13 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
 #pragma unroll
             for (int v = 0; v < kFusedRegVecs; ++v)
                 row0[v] = static_cast<const uint4*>(xin)[min(v * kThreads + (int)threadIdx.x, nvec - 1)];
+            if (kNorm && gain) {                       // the gain of the same columns, needed after the reduction
+#pragma unroll
+                for (int v = 0; v < gain_reg_vecs(kThreads); ++v)
+#pragma unroll
+                    for (int h = 0; h < (kInBf16 ? 2 : 1); ++h)
+                        gain0[v][h] = reinterpret_cast<const float4*>(gain)[(size_t)min(v * kThreads + (int)threadIdx.x, nvec - 1) * (kInBf16 ? 2 : 1) + h];
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -412,7 +449,7 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
         }
         __syncthreads();
     } else if (kFused) {
-        fused_quantize_to_lds<kInBf16, kNorm, kThreads>(xin, row0, row0_in_regs, M, K, Kpad, gain, eps, red, sxl, xlds);
+        fused_quantize_to_lds<kInBf16, kNorm, kThreads>(xin, row0, row0_in_regs, gain0, M, K, Kpad, gain, eps, red, sxl, xlds);
     }
 
     int i = 0;
@@ -949,11 +986,19 @@ static void dispatch16(int xmode, const void* x, const float* sx, const void* pa
     if (RB >= 2048) {
         if (fused) GEMV16(4, 1, 4, 2, kXGlobal); else GEMV16(4, 1, 4, 3, kXGlobal);
     } else if (steps >= 64) {
-        if (fused) GEMV16(1, 8, 2, 2, kXGlobal); else GEMV16(2, 4, 1, 4, kXGlobal);
+        if (xmode >= kXNormBf16) GEMV16(1, 8, 1, 3, kXGlobal);      // the RMSNorm modes need more registers than 1024 threads leave
+        else if (fused) GEMV16(1, 8, 2, 2, kXGlobal);
+        else GEMV16(2, 4, 1, 4, kXGlobal);
     } else if (steps >= 24) {
         if (steps <= 40) GEMV16(1, 8, 1, 5, kXLds); else GEMV16(1, 8, 1, 3, kXLds);
     } else if (RB >= 1024 && steps >= 16 && !fused) {
         GEMV16(2, 4, 1, 4, kXGlobal);
+    } else if (xmode >= kXNormBf16 && RB > 640) {
+        // RMSNorm modes: every workgroup repeats the normalisation (an fp64 reduction and a square root), which
+        // costs a microsecond of its CU's time -- so few, wide workgroups: four row blocks each, one wave per row block
+        GEMV16(1, 1, 4, 5, kXGlobal);
+    } else if (xmode >= kXNormBf16 && RB > 320) {
+        GEMV16(1, 2, 2, 4, kXGlobal);
     } else {
         GEMV16(1, 4, 1, 4, (RB >= 400 && steps < 16) ? kXLds : kXGlobal);
     }
