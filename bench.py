@@ -238,7 +238,7 @@ def batched_decode_leg(torch, B, synth, gen, stream, args):
 def decoder_block_leg(torch, B, synth, gen, stream, args, cfg_idx=1, layers=26):
     """Per-token latency of the BitLinear chain of a decoder stack at M = 1, two ways, each one HIP graph:
     "fused": RMSNorm+quantization fused into the QKV and gate/up launches, absmax quantization into the O launch,
-    SwiGLU->int8 as a producer in front of the down projection -- five launches per layer;
+    SwiGLU+quantization into the down launch -- four launches per layer;
     "handover": int8 activations handed from producer to product -- RMSNorm->int8, QKV, quantize, O, RMSNorm->int8,
     gate/up, SwiGLU->int8, down -- eight launches per layer.
     Attention itself and the residual additions are not part of the path and are left out (the attention output
@@ -286,17 +286,16 @@ def decoder_block_leg(torch, B, synth, gen, stream, args, cfg_idx=1, layers=26):
             B.rmsnorm_linear_fused(x, gain, 1e-6, d["qkv"][0], d["qkv"][1], shapes["qkv"][1], y_dtype=B.BF16, y=y_qkv)
             B.linear_fused(att, d["o"][0], d["o"][1], H, y_dtype=B.BF16, y=y_o)
             B.rmsnorm_linear_fused(y_o, gain, 1e-6, d["gate_up"][0], d["gate_up"][1], 2 * F, y_dtype=B.BF16, y=y_gu)
-            B.swiglu_quantize(y_gu, hq=xq_f, sh=s1)
-            B.linear(xq_f, s1, d["down"][0], d["down"][1], H, y_dtype=B.BF16, y=y_d)
+            B.swiglu_linear_fused(y_gu, d["down"][0], d["down"][1], H, y_dtype=B.BF16, y=y_d)
             x = y_d
 
     ms_f, _, _ = time_graph(torch, run_fused, args.warmup, args.steps, stream)
     ms_h, _, _ = time_graph(torch, run_handover, args.warmup, args.steps, stream)
     nbytes = layers * sum(gemv_bytes(M, N, K) for (K, N) in shapes.values())
-    return {"model": cfg["name"], "layers": layers, "launches": 5 * layers, "ms_per_token": round(ms_f, 4),
+    return {"model": cfg["name"], "layers": layers, "launches": 4 * layers, "ms_per_token": round(ms_f, 4),
             "GB/s": round(nbytes / (ms_f * 1e-3) / 1e9, 1),
-            "note": "rmsnorm_linear_fused(qkv), linear_fused(o), rmsnorm_linear_fused(gate_up), swiglu_quantize, "
-                    "linear(down) per layer; attention and residual adds excluded",
+            "note": "rmsnorm_linear_fused(qkv), linear_fused(o), rmsnorm_linear_fused(gate_up), swiglu_linear_fused(down) "
+                    "per layer; attention and residual adds excluded",
             "int8_handover": {"launches": 8 * layers, "ms_per_token": round(ms_h, 4),
                               "note": "rmsnorm_quantize, linear(qkv), quantize_acts, linear(o), rmsnorm_quantize, "
                                       "linear(gate_up), swiglu_quantize, linear(down) per layer"}}

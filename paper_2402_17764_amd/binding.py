@@ -26,7 +26,7 @@ SYMBOLS = [
     "bitnet_quantize_weights", "bitnet_quantize_acts", "bitnet_linear", "bitnet_linear_variant",
     "bitnet_linear_fused", "bitnet_unpack_weights", "bitnet_rmsnorm_quantize", "bitnet_swiglu_quantize",
     "bitnet_quantize_weights_segmented", "bitnet_linear_segmented", "bitnet_linear_fused_segmented",
-    "bitnet_rmsnorm_linear_fused", "bitnet_rmsnorm_linear_fused_segmented",
+    "bitnet_rmsnorm_linear_fused", "bitnet_rmsnorm_linear_fused_segmented", "bitnet_swiglu_linear_fused",
 ]
 
 _lib = None
@@ -67,6 +67,7 @@ def load():
     lib.bitnet_linear_fused_segmented.argtypes = [vp, ci, vp, vp, i64, i64, i64, ci, vp, ci, vp]
     lib.bitnet_rmsnorm_linear_fused.argtypes = [vp, ci, vp, ctypes.c_float, vp, vp, i64, i64, i64, ci, vp, ci, vp]
     lib.bitnet_rmsnorm_linear_fused_segmented.argtypes = [vp, ci, vp, ctypes.c_float, vp, vp, i64, i64, i64, ci, vp, ci, vp]
+    lib.bitnet_swiglu_linear_fused.argtypes = [vp, ci, vp, vp, i64, i64, i64, ci, vp, ci, vp]
     for name in SYMBOLS[2:]:
         getattr(lib, name).restype = ci
     _lib = lib
@@ -278,6 +279,21 @@ def rmsnorm_linear_fused(x, g, eps, packed, gamma, N, fmt=PACK_2BIT, y_dtype=F32
     _check(fn(xp, _FLOAT[x.dtype], gp, float(eps), _dev(packed, "packed"), _dev(gamma, "gamma", (torch.float32,)),
               M, N, K, fmt, _dev(y, "y", (_OUT[y_dtype],)), y_dtype, _stream()),
            "bitnet_rmsnorm_linear_fused_segmented" if segmented else "bitnet_rmsnorm_linear_fused")
+    return y
+
+
+def swiglu_linear_fused(gu, packed, gamma, N, fmt=PACK_2BIT, y_dtype=F32, y=None):
+    """y = BitLinear(silu(gate) * up) in one launch (decode path): gu [M,2F] fp32/bf16 (gate | up), packed an [N,F] matrix."""
+    lib = load()
+    gp = _dev(gu, "gu", _FLOAT, 2)
+    M, F2 = gu.shape
+    if F2 % 2:
+        raise ValueError("gu must hold a gate and an up half")
+    if y is None:
+        y = torch.empty((M, N), dtype=_OUT[y_dtype], device=gu.device)
+    _check(lib.bitnet_swiglu_linear_fused(gp, _FLOAT[gu.dtype], _dev(packed, "packed"), _dev(gamma, "gamma", (torch.float32,)),
+                                          M, N, F2 // 2, fmt, _dev(y, "y", (_OUT[y_dtype],)), y_dtype, _stream()),
+           "bitnet_swiglu_linear_fused")
     return y
 
 

@@ -301,6 +301,22 @@ bitnet_status bitnet_rmsnorm_linear_fused_segmented(const void* x, bitnet_dtype 
     return rmsnorm_linear_fused_any(x, x_dtype, g, eps, packed, gamma_rb, 1, M, N, K, f, y, y_dtype, stream);
 }
 
+bitnet_status bitnet_swiglu_linear_fused(const void* gu, bitnet_dtype gu_dtype, const void* packed, const float* gamma,
+                                         int64_t M, int64_t N, int64_t F, bitnet_format f, void* y, bitnet_dtype y_dtype,
+                                         void* stream) {
+    if (!gu || !packed || !gamma || !y) return BITNET_ERR_NULL;
+    if (!shape_ok(M, N, F)) return BITNET_ERR_SHAPE;
+    if (gu_dtype != BITNET_F32 && gu_dtype != BITNET_BF16) return BITNET_ERR_DTYPE;
+    OutType yt;
+    if (!out_type(y_dtype, &yt)) return BITNET_ERR_DTYPE;
+    if (!format_ok(f)) return BITNET_ERR_FORMAT;
+    if (!aligned(packed, 16) || !aligned(gamma, 4) || !aligned(y, dtype_size(y_dtype))) return BITNET_ERR_ALIGN;
+    if (f != BITNET_PACK_2BIT) return BITNET_ERR_FORMAT;
+    if (!bitnet::gemv_fused_supports(M, N, F, gu)) return BITNET_ERR_KERNEL;
+    return from_hip(bitnet::launch_swiglu_linear_fused_2bit(gu, gu_dtype == BITNET_BF16, packed, gamma, 0, M, N, F, y, yt,
+                                                            static_cast<hipStream_t>(stream)));
+}
+
 bitnet_status bitnet_unpack_weights(const void* packed, int64_t N, int64_t K, bitnet_format f, int8_t* codes,
                                     void* stream) {
     if (!packed || !codes) return BITNET_ERR_NULL;

@@ -73,6 +73,31 @@ __device__ inline void dd_add_dd(dd& s, const dd& o) {
     s.lo += err + o.lo;
 }
 
+// ---- SwiGLU gating with fixed arithmetic (shared by the stand-alone producer and the fused decode kernel) ----
+// exp(t) in fp32 with every step fixed (no fused multiply-add: the library is compiled with
+// contraction off): clamp to [-87, 88], n = round(t log2 e), two-constant reduction by ln 2, degree-6 Horner, scale
+// by 2^n.  Relative error below 4e-7; what matters is that the steps, not a library, define the value.
+__device__ inline float exp32(float t) {
+    t = fminf(fmaxf(t, -87.0f), 88.0f);
+    const float n = rintf(t * 1.44269504f);
+    float r = t - n * 0.693359375f;
+    r = r - n * -2.12194440e-4f;
+    float p = 1.0f / 720.0f;
+    p = p * r + 1.0f / 120.0f;
+    p = p * r + 1.0f / 24.0f;
+    p = p * r + 1.0f / 6.0f;
+    p = p * r + 0.5f;
+    p = p * r + 1.0f;
+    p = p * r + 1.0f;
+    return ldexpf(p, (int)n);
+}
+
+__device__ inline float swiglu_one(float gate, float up) {
+    const float e = exp32(-gate);
+    const float s = gate / (1.0f + e);                     // IEEE fp32 division
+    return s * up;
+}
+
 // ---- 2-bit layout ---------------------------------------------------------------------------------
 // Eq. (1)-(2) for one weight, given d = gamma + eps: the 2-bit two's-complement code.
 __device__ inline uint32_t ternary_code2(float w, float d) {

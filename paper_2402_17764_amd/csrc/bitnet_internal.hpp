@@ -61,6 +61,9 @@ hipError_t launch_linear_fused_2bit(const void* x, bool bf16, const void* packed
 hipError_t launch_rmsnorm_linear_fused_2bit(const void* x, bool bf16, const float* gain, float eps, const void* packed,
                                             const float* gamma, int gstride, int64_t M, int64_t N, int64_t K, void* y,
                                             OutType yt, hipStream_t stream);
+// ... and with SwiGLU gating in front: gu is [M][2 K] (gate | up), the product runs over K columns
+hipError_t launch_swiglu_linear_fused_2bit(const void* gu, bool bf16, const void* packed, const float* gamma, int gstride,
+                                           int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);
 
 // linear_gemm.hip
 bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq);

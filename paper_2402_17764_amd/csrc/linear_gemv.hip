@@ -93,8 +93,12 @@ enum XMode : int {
     kXFusedBf16 = 2,   // bf16 x: per-token absmax quantization done in the kernel, x_q lives only in LDS
     kXFusedF32 = 3,    // fp32 x, same
     kXNormBf16 = 4,    // bf16 x: RMSNorm (with an optional gain) and the quantization done in the kernel
-    kXNormF32 = 5      // fp32 x, same
+    kXNormF32 = 5,     // fp32 x, same
+    kXSwigluBf16 = 6,  // bf16 [gate | up] rows of 2 K elements: SwiGLU gating and the quantization done in the kernel
+    kXSwigluF32 = 7    // fp32, same
 };
+// what the fused modes do to a token before its absmax quantization
+enum PreOp : int { kPreNone = 0, kPreRmsNorm = 1, kPreSwiglu = 2 };
 
 // uint4 slots in front of the x region: 16 floats of reduction scratch, 16 floats of s_x, 2 x 16 doubles for the
 // double-double reduction of the RMSNorm modes
@@ -215,23 +219,29 @@ __device__ inline double gemv_block_sum_dd(dd v, double* sh_hi, double* sh_lo) {
     return t.hi + t.lo;
 }
 
-// kNorm: the token first goes through RMSNorm, z = (x * r) * gain with r = (float)(1 / sqrt(mean(x^2) + eps)),
-// the mean of squares exact (fp64 squares of fp32 values, double-double sums) -- the arithmetic of the
-// stand-alone RMSNorm -> int8 kernel, so both give the same codes and scales (Section 2 of the paper:
-// LLaMA-alike components, RMSNorm in front of the attention and feed-forward BitLinear layers).
-template <bool kBf16, bool kNorm, int kThreads>
-__device__ inline void fused_quantize_to_lds(const void* __restrict__ xv, const uint4 (&row0)[kFusedRegVecs], bool row0_in_regs,
+// kPre == kPreRmsNorm: the token first goes through RMSNorm, z = (x * r) * gain with
+// r = (float)(1 / sqrt(mean(x^2) + eps)), the mean of squares exact (fp64 squares of fp32 values, double-double
+// sums).  kPre == kPreSwiglu: the token is a [gate | up] row of 2 K elements and h = silu(gate) * up is what gets
+// quantized.  Both are the arithmetic of the stand-alone producer kernels, so they give the same codes and scales
+// (Section 2 of the paper, LLaMA-alike components: RMSNorm in front of the attention and feed-forward BitLinear
+// layers, SwiGLU in front of the down projection).
+template <bool kBf16, int kPre, int kThreads>
+__device__ inline void fused_quantize_to_lds(const void* __restrict__ xv, const uint4 (&row0)[kFusedRegVecs],
+                                             const uint4 (&up0)[kFusedRegVecs] /* SwiGLU: the up half of token 0 */,
+                                             bool row0_in_regs,
                                              const float4 (&gain0)[2][kBf16 ? 2 : 1] /* gain of row0's first columns */,
                                              int M, int64_t K, int Kpad, const float* __restrict__ gain, float eps,
                                              float* red, float* sxl, uint4* xlds) {
     constexpr int kE = kBf16 ? 8 : 4;                 // elements per 16-byte vector
     constexpr int kWaves = kThreads / kWave;
+    constexpr bool kNorm = kPre == kPreRmsNorm, kSwiglu = kPre == kPreSwiglu;
     const int nvec = (int)(K / kE);
     const int nvec_pad = Kpad / kE;
+    const int64_t row_bytes = (kSwiglu ? 2 : 1) * K * (kBf16 ? 2 : 4);
     double* sh_hi = reinterpret_cast<double*>(red + 32);
     double* sh_lo = sh_hi + 16;
     for (int m = 0; m < M; ++m) {
-        const uint4* row = reinterpret_cast<const uint4*>(static_cast<const char*>(xv) + (int64_t)m * K * (kBf16 ? 2 : 4));
+        const uint4* row = reinterpret_cast<const uint4*>(static_cast<const char*>(xv) + (int64_t)m * row_bytes);
         uint32_t* out = reinterpret_cast<uint32_t*>(xlds) + (size_t)m * (Kpad >> 2);
         const bool regs = m == 0 && row0_in_regs;
         float r = 1.0f;
@@ -258,50 +268,69 @@ __device__ inline void fused_quantize_to_lds(const void* __restrict__ xv, const 
             const double ms = gemv_block_sum_dd<kWaves>(acc, sh_hi, sh_lo) / (double)K;
             r = (float)(1.0 / sqrt(ms + (double)eps));
         }
-        // z of one vector (kNorm): the same two multiplies wherever it is evaluated, so the same value
-        // (slot >= 0: vector `slot` of the token held in registers, whose gain was requested with it)
-        auto normalized = [&](const uint4& q, int v, int slot, float (&f)[kE]) {
+        // The values that get quantized, for one vector of columns (kNorm, kSwiglu): the same operations wherever
+        // they are evaluated, so the same values.  slot >= 0: vector `slot` of the token held in registers.
+        auto values = [&](const uint4& q, const uint4& qu, int v, int slot, float (&f)[kE]) {
             vec_expand<kBf16>(q, f);
+            if (kNorm) {
 #pragma unroll
-            for (int e = 0; e < kE; ++e) f[e] = f[e] * r;
-            if (gain) {
+                for (int e = 0; e < kE; ++e) f[e] = f[e] * r;
+                if (gain) {
 #pragma unroll
-                for (int h = 0; h < kE / 4; ++h) {
-                    const float4 gq = (slot >= 0 && slot < gain_reg_vecs(kThreads)) ? gain0[slot][h]
-                                                                                    : *reinterpret_cast<const float4*>(gain + (size_t)v * kE + 4 * h);
-                    f[4 * h] = f[4 * h] * gq.x; f[4 * h + 1] = f[4 * h + 1] * gq.y;
-                    f[4 * h + 2] = f[4 * h + 2] * gq.z; f[4 * h + 3] = f[4 * h + 3] * gq.w;
+                    for (int h = 0; h < kE / 4; ++h) {
+                        const float4 gq = (slot >= 0 && slot < gain_reg_vecs(kThreads)) ? gain0[slot][h]
+                                                                                        : *reinterpret_cast<const float4*>(gain + (size_t)v * kE + 4 * h);
+                        f[4 * h] = f[4 * h] * gq.x; f[4 * h + 1] = f[4 * h + 1] * gq.y;
+                        f[4 * h + 2] = f[4 * h + 2] * gq.z; f[4 * h + 3] = f[4 * h + 3] * gq.w;
+                    }
                 }
             }
+            if (kSwiglu) {
+                float u[kE];
+                vec_expand<kBf16>(qu, u);
+#pragma unroll
+                for (int e = 0; e < kE; ++e) f[e] = swiglu_one(f[e], u[e]);
+            }
         };
-        auto absmax_of = [&](const uint4& q, int v, int slot, float amax) {
-            if (!kNorm) return vec_absmax<kBf16>(q, amax);
-            float f[kE];
-            normalized(q, v, slot, f);
+        auto absmax_floats = [&](const float (&f)[kE], float amax) {
 #pragma unroll
             for (int e = 0; e < kE; ++e) amax = fmaxf(amax, fabsf(f[e]));
             return amax;
         };
-        auto quantize_store = [&](const uint4& q, int v, int slot, float inv) {
-            if (!kNorm) { vec_quantize_store<kBf16>(q, inv, out, v); return; }
-            float f[kE];
-            normalized(q, v, slot, f);
+        auto store_floats = [&](const float (&f)[kE], int v, float inv) {
 #pragma unroll
             for (int h = 0; h < kE / 4; ++h)
                 out[(kE / 4) * v + h] = quant_byte(f[4 * h], inv) | (quant_byte(f[4 * h + 1], inv) << 8) |
                                         (quant_byte(f[4 * h + 2], inv) << 16) | (quant_byte(f[4 * h + 3], inv) << 24);
         };
+        float hk[kSwiglu ? kFusedRegVecs : 1][kE];     // SwiGLU: the gated values of token 0 stay in registers
         float amax = 0.0f;
         if (regs) {
 #pragma unroll
             for (int v = 0; v < kFusedRegVecs; ++v) {
                 const int idx = v * kThreads + (int)threadIdx.x;
-                // plain absmax: clamped duplicates are harmless and cost less than a branch; with RMSNorm they
-                // would fetch their gain again
-                if (!kNorm || idx < nvec) amax = absmax_of(row0[v], min(idx, nvec - 1), v, amax);
+                if (kPre == kPreNone) {
+                    amax = vec_absmax<kBf16>(row0[v], amax);        // clamped duplicates are harmless, cheaper than a branch
+                } else if (idx < nvec) {
+                    float f[kE];
+                    values(row0[v], up0[v], idx, v, f);
+                    amax = absmax_floats(f, amax);
+                    if (kSwiglu) {
+#pragma unroll
+                        for (int e = 0; e < kE; ++e) hk[kSwiglu ? v : 0][e] = f[e];
+                    }
+                }
             }
         } else {
-            for (int v = threadIdx.x; v < nvec; v += kThreads) amax = absmax_of(row[v], v, -1, amax);
+            for (int v = threadIdx.x; v < nvec; v += kThreads) {
+                if (kPre == kPreNone) {
+                    amax = vec_absmax<kBf16>(row[v], amax);
+                } else {
+                    float f[kE];
+                    values(row[v], row[kSwiglu ? nvec + v : v], v, -1, f);
+                    amax = absmax_floats(f, amax);
+                }
+            }
         }
         const float sc = block_absmax_to_scale<kThreads>(amax, red);
         const float inv = kQb / sc;                   // one IEEE division per token
@@ -310,10 +339,28 @@ __device__ inline void fused_quantize_to_lds(const void* __restrict__ xv, const 
 #pragma unroll
             for (int v = 0; v < kFusedRegVecs; ++v) {
                 const int idx = v * kThreads + (int)threadIdx.x;
-                if (idx < nvec) quantize_store(row0[v], idx, v, inv);
+                if (idx < nvec) {
+                    if (kPre == kPreNone) {
+                        vec_quantize_store<kBf16>(row0[v], inv, out, idx);
+                    } else if (kSwiglu) {
+                        store_floats(hk[kSwiglu ? v : 0], idx, inv);
+                    } else {
+                        float f[kE];
+                        values(row0[v], up0[v], idx, v, f);
+                        store_floats(f, idx, inv);
+                    }
+                }
             }
         } else {
-            for (int v = threadIdx.x; v < nvec; v += kThreads) quantize_store(row[v], v, -1, inv);
+            for (int v = threadIdx.x; v < nvec; v += kThreads) {
+                if (kPre == kPreNone) {
+                    vec_quantize_store<kBf16>(row[v], inv, out, v);
+                } else {
+                    float f[kE];
+                    values(row[v], row[kSwiglu ? nvec + v : v], v, -1, f);
+                    store_floats(f, v, inv);
+                }
+            }
         }
         for (int v = nvec + threadIdx.x; v < nvec_pad; v += kThreads)                          // zero padding
             vec_quantize_store<kBf16>(make_uint4(0, 0, 0, 0), inv, out, v);
@@ -337,8 +384,10 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
     constexpr int kThreads = kS * kW * kWave;
     constexpr bool kFromLds = kX != kXGlobal;
     constexpr bool kFused = kX >= kXFusedBf16;
-    constexpr bool kNorm = kX >= kXNormBf16;
-    constexpr bool kInBf16 = kX == kXFusedBf16 || kX == kXNormBf16;
+    constexpr bool kNorm = kX == kXNormBf16 || kX == kXNormF32;
+    constexpr bool kSwiglu = kX == kXSwigluBf16 || kX == kXSwigluF32;
+    constexpr int kPre = kNorm ? kPreRmsNorm : kSwiglu ? kPreSwiglu : kPreNone;
+    constexpr bool kInBf16 = kX == kXFusedBf16 || kX == kXNormBf16 || kX == kXSwigluBf16;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const int r = lane & 15;
@@ -402,7 +451,7 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
     };
 
     // fused modes: token 0 goes to registers first (cache hits, back long before the weights)
-    uint4 row0[kFusedRegVecs];
+    uint4 row0[kFusedRegVecs], up0[kFusedRegVecs];
     float4 gain0[2][kInBf16 ? 2 : 1];
     bool row0_in_regs = false;
     if (kFused) {
@@ -412,6 +461,11 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
 #pragma unroll
             for (int v = 0; v < kFusedRegVecs; ++v)
                 row0[v] = static_cast<const uint4*>(xin)[min(v * kThreads + (int)threadIdx.x, nvec - 1)];
+            if (kSwiglu) {                             // the up half of the row follows the K gate elements
+#pragma unroll
+                for (int v = 0; v < kFusedRegVecs; ++v)
+                    up0[v] = static_cast<const uint4*>(xin)[nvec + min(v * kThreads + (int)threadIdx.x, nvec - 1)];
+            }
             if (kNorm && gain) {                       // the gain of the same columns, needed after the reduction
 #pragma unroll
                 for (int v = 0; v < gain_reg_vecs(kThreads); ++v)
@@ -449,7 +503,7 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
         }
         __syncthreads();
     } else if (kFused) {
-        fused_quantize_to_lds<kInBf16, kNorm, kThreads>(xin, row0, row0_in_regs, gain0, M, K, Kpad, gain, eps, red, sxl, xlds);
+        fused_quantize_to_lds<kInBf16, kPre, kThreads>(xin, row0, up0, row0_in_regs, gain0, M, K, Kpad, gain, eps, red, sxl, xlds);
     }
 
     int i = 0;
@@ -921,7 +975,9 @@ static void launch16(int xmode, const void* x, const float* sx, const void* pack
         case kXFusedBf16: GO(kXFusedBf16); break;
         case kXFusedF32: GO(kXFusedF32); break;
         case kXNormBf16: GO(kXNormBf16); break;
-        default: GO(kXNormF32); break;
+        case kXNormF32: GO(kXNormF32); break;
+        case kXSwigluBf16: GO(kXSwigluBf16); break;
+        default: GO(kXSwigluF32); break;
     }
 #undef GO
 }
@@ -986,7 +1042,7 @@ static void dispatch16(int xmode, const void* x, const float* sx, const void* pa
     if (RB >= 2048) {
         if (fused) GEMV16(4, 1, 4, 2, kXGlobal); else GEMV16(4, 1, 4, 3, kXGlobal);
     } else if (steps >= 64) {
-        if (xmode >= kXNormBf16) GEMV16(1, 8, 1, 3, kXGlobal);      // the RMSNorm modes need more registers than 1024 threads leave
+        if (xmode >= kXNormBf16) GEMV16(1, 8, 1, 3, kXGlobal);      // RMSNorm / SwiGLU modes need more registers than 1024 threads leave
         else if (fused) GEMV16(1, 8, 2, 2, kXGlobal);
         else GEMV16(2, 4, 1, 4, kXGlobal);
     } else if (steps >= 24) {
@@ -994,8 +1050,9 @@ static void dispatch16(int xmode, const void* x, const float* sx, const void* pa
     } else if (RB >= 1024 && steps >= 16 && !fused) {
         GEMV16(2, 4, 1, 4, kXGlobal);
     } else if (xmode >= kXNormBf16 && RB > 640) {
-        // RMSNorm modes: every workgroup repeats the normalisation (an fp64 reduction and a square root), which
-        // costs a microsecond of its CU's time -- so few, wide workgroups: four row blocks each, one wave per row block
+        // RMSNorm and SwiGLU modes: every workgroup repeats the normalisation (an fp64 reduction and a square
+        // root) or the gating (an exponential and a division per element), which costs a microsecond or two of its
+        // CU's time -- so few, wide workgroups: four row blocks each, one wave per row block
         GEMV16(1, 1, 4, 5, kXGlobal);
     } else if (xmode >= kXNormBf16 && RB > 320) {
         GEMV16(1, 2, 2, 4, kXGlobal);
@@ -1057,6 +1114,12 @@ hipError_t launch_rmsnorm_linear_fused_2bit(const void* x, bool bf16, const floa
                                             const float* gamma, int gstride, int64_t M, int64_t N, int64_t K, void* y,
                                             OutType yt, hipStream_t stream) {
     dispatch16(bf16 ? kXNormBf16 : kXNormF32, x, nullptr, packed, gamma, gstride, M, N, K, y, yt, stream, gain, eps);
+    return hipGetLastError();
+}
+
+hipError_t launch_swiglu_linear_fused_2bit(const void* gu, bool bf16, const void* packed, const float* gamma, int gstride,
+                                           int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
+    dispatch16(bf16 ? kXSwigluBf16 : kXSwigluF32, gu, nullptr, packed, gamma, gstride, M, N, K, y, yt, stream);
     return hipGetLastError();
 }
 

@@ -88,6 +88,12 @@ def test_host_validation_rejects_before_launch():
     assert lib.bitnet_rmsnorm_linear_fused(a, 0, vp(0x1004), 1e-6, a, a, 1, 16, 64, 0, a, 0, NULL) == 5   # gain: 16-byte aligned
     assert lib.bitnet_rmsnorm_linear_fused(a, 0, NULL, 1e-6, a, a, 17, 16, 64, 0, a, 0, NULL) == 8
     assert lib.bitnet_rmsnorm_linear_fused_segmented(a, 0, NULL, 1e-6, a, a, 17, 16, 64, 0, a, 0, NULL) == 8
+    assert lib.bitnet_swiglu_linear_fused(NULL, 0, a, a, 1, 16, 64, 0, a, 0, NULL) == 1
+    assert lib.bitnet_swiglu_linear_fused(a, 0, a, a, 1, 16, 0, 0, a, 0, NULL) == 2
+    assert lib.bitnet_swiglu_linear_fused(a, 2, a, a, 1, 16, 64, 0, a, 0, NULL) == 3
+    assert lib.bitnet_swiglu_linear_fused(a, 0, a, a, 1, 16, 64, 1, a, 0, NULL) == 4
+    assert lib.bitnet_swiglu_linear_fused(a, 0, odd, a, 1, 16, 64, 0, a, 0, NULL) == 5
+    assert lib.bitnet_swiglu_linear_fused(a, 0, a, a, 17, 16, 64, 0, a, 0, NULL) == 8
     # shapes
     assert lib.bitnet_quantize_acts(a, 0, 0, 16, a, a, NULL) == 2
     assert lib.bitnet_rmsnorm_quantize(a, 0, NULL, 0.0, 1, 0, a, a, NULL) == 2

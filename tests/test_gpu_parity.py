@@ -328,6 +328,52 @@ def test_rmsnorm_linear_fused_segmented_and_limits(gpu_lib):
     assert e.value.status == 2
 
 
+# SwiGLU + quantization + product in one launch: F (the product's K) from one partial step to the 3B / 7B / 70B
+# feed-forward widths, token 0 in registers and the re-reading path, every branch of the kernel selection
+SWIGLU_FUSED_SHAPES = [(1, 3200, 8640), (1, 100, 1536), (3, 250, 1040), (1, 33, 4112), (16, 70, 528), (1, 16400, 272),
+                       (2, 6416, 4112), (1, 64, 28672), (1, 4096, 11008), (4, 300, 8192), (1, 32800, 528), (5, 40, 16)]
+
+
+@pytest.mark.parametrize("M,N,F", SWIGLU_FUSED_SHAPES)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_swiglu_linear_fused_matches_oracle(gpu_lib, M, N, F, dtype):
+    """[gate | up] -> SwiGLU -> int8 -> product in one launch: h_q and s_h must be those of the oracle's SwiGLU
+    quantizer (the int32 accumulators show it), and the result that of the two separate GPU calls, bit for bit."""
+    say("swiglu linear fused %s M=%d N=%d F=%d" % (dtype, M, N, F))
+    W = synth.weights(N, F, config=0, layer=M + 40, tensor=0)
+    if dtype == "bf16":
+        gu, bits = synth.activations(M, 2 * F, config=2, layer=M + 40, tensor=6, bf16=True)
+        gd = bf16_tensor(bits).view(M, 2 * F)
+    else:
+        gu = synth.activations(M, 2 * F, config=0, layer=M + 40, tensor=6)
+        gd = dev(gu)
+    gamma_ref, _ = oracle.absmean_gamma(W)
+    codes_ref = oracle.ternarize(W, gamma_ref)
+    packed, gamma = gpu_lib.quantize_weights(dev(W))
+    hq_ref, sh_ref, _ = oracle.swiglu_quantize(gu)
+    acc_ref = oracle.ternary_matmul(hq_ref, codes_ref)
+    y_ref = oracle.rescale(acc_ref, gamma_ref, sh_ref)
+    acc = gpu_lib.swiglu_linear_fused(gd, packed, gamma, N, y_dtype=gpu_lib.I32)
+    assert np.array_equal(acc.cpu().numpy(), acc_ref)
+    y32 = gpu_lib.swiglu_linear_fused(gd, packed, gamma, N, y_dtype=gpu_lib.F32)
+    check_y(y32.cpu().numpy(), y_ref, RTOL_F32)
+    y16 = gpu_lib.swiglu_linear_fused(gd, packed, gamma, N, y_dtype=gpu_lib.BF16)
+    check_y(y16.float().cpu().numpy(), y_ref, RTOL_BF16)
+    hq, sh = gpu_lib.swiglu_quantize(gd)
+    assert torch.equal(y32, gpu_lib.linear(hq, sh, packed, gamma, N, y_dtype=gpu_lib.F32))
+
+
+def test_swiglu_linear_fused_limits(gpu_lib):
+    say("swiglu linear fused: limits")
+    F, N = 64, 32
+    p, g = gpu_lib.quantize_weights(dev(synth.weights(N, F, config=0, layer=1)))
+    z = torch.zeros((2, 2 * F), dtype=torch.float32, device="cuda")       # silu(0) * 0 = 0: s_h = 1e-5, y = 0
+    assert bool((gpu_lib.swiglu_linear_fused(z, p, g, N) == 0).all())
+    with pytest.raises(gpu_lib.BitnetError) as e:
+        gpu_lib.swiglu_linear_fused(dev(synth.activations(17, 2 * F, config=0, layer=1)), p, g, N)
+    assert e.value.status == 8
+
+
 def test_linear_fused_rejects_what_it_cannot_run(gpu_lib):
     say("linear fused limits")
     W = dev(synth.weights(32, 8192, config=0, layer=1))
