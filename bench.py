@@ -237,8 +237,8 @@ def batched_decode_leg(torch, B, synth, gen, stream, args):
 
 def decoder_block_leg(torch, B, synth, gen, stream, args, cfg_idx=1, layers=26):
     """Per-token latency of the BitLinear chain of a decoder stack at M = 1, two ways, each one HIP graph:
-    "fused": RMSNorm+quantization fused into the QKV and gate/up launches, absmax quantization into the O launch,
-    SwiGLU+quantization into the down launch -- four launches per layer;
+    "fused": RMSNorm+quantization fused into the QKV and gate/up launches, the SwiGLU gate into the epilogue of the
+    gate/up launch, absmax quantization into the O and down launches -- four launches per layer;
     "handover": int8 activations handed from producer to product -- RMSNorm->int8, QKV, quantize, O, RMSNorm->int8,
     gate/up, SwiGLU->int8, down -- eight launches per layer.
     Attention itself and the residual additions are not part of the path and are left out (the attention output
@@ -266,6 +266,7 @@ def decoder_block_leg(torch, B, synth, gen, stream, args, cfg_idx=1, layers=26):
     y_o = torch.empty((M, H), dtype=torch.bfloat16, device="cuda")
     y_gu = torch.empty((M, 2 * F), dtype=torch.bfloat16, device="cuda")
     y_d = torch.empty((M, H), dtype=torch.bfloat16, device="cuda")
+    h_f = torch.empty((M, F), dtype=torch.bfloat16, device="cuda")
 
     def run_handover():
         x = h
@@ -285,8 +286,8 @@ def decoder_block_leg(torch, B, synth, gen, stream, args, cfg_idx=1, layers=26):
         for d in packs:
             B.rmsnorm_linear_fused(x, gain, 1e-6, d["qkv"][0], d["qkv"][1], shapes["qkv"][1], y_dtype=B.BF16, y=y_qkv)
             B.linear_fused(att, d["o"][0], d["o"][1], H, y_dtype=B.BF16, y=y_o)
-            B.rmsnorm_linear_fused(y_o, gain, 1e-6, d["gate_up"][0], d["gate_up"][1], 2 * F, y_dtype=B.BF16, y=y_gu)
-            B.swiglu_linear_fused(y_gu, d["down"][0], d["down"][1], H, y_dtype=B.BF16, y=y_d)
+            B.ffn_gate_up_fused(y_o, d["gate_up"][0], d["gate_up"][1], F, norm=True, g=gain, eps=1e-6, h_dtype=B.BF16, h=h_f)
+            B.linear_fused(h_f, d["down"][0], d["down"][1], H, y_dtype=B.BF16, y=y_d)
             x = y_d
 
     ms_f, _, _ = time_graph(torch, run_fused, args.warmup, args.steps, stream)
@@ -294,8 +295,8 @@ def decoder_block_leg(torch, B, synth, gen, stream, args, cfg_idx=1, layers=26):
     nbytes = layers * sum(gemv_bytes(M, N, K) for (K, N) in shapes.values())
     return {"model": cfg["name"], "layers": layers, "launches": 4 * layers, "ms_per_token": round(ms_f, 4),
             "GB/s": round(nbytes / (ms_f * 1e-3) / 1e9, 1),
-            "note": "rmsnorm_linear_fused(qkv), linear_fused(o), rmsnorm_linear_fused(gate_up), swiglu_linear_fused(down) "
-                    "per layer; attention and residual adds excluded",
+            "note": "rmsnorm_linear_fused(qkv), linear_fused(o), ffn_gate_up_fused (RMSNorm in, SwiGLU out), "
+                    "linear_fused(down) per layer; attention and residual adds excluded",
             "int8_handover": {"launches": 8 * layers, "ms_per_token": round(ms_h, 4),
                               "note": "rmsnorm_quantize, linear(qkv), quantize_acts, linear(o), rmsnorm_quantize, "
                                       "linear(gate_up), swiglu_quantize, linear(down) per layer"}}

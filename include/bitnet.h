@@ -253,6 +253,28 @@ bitnet_status bitnet_swiglu_linear_fused(const void* gu, bitnet_dtype gu_dtype, 
                                          bitnet_format f, void* y, bitnet_dtype y_dtype, void* stream);
 
 /*
+ * The front half of the feed-forward block in one decode launch (Section 2, "LLaMA-alike components": SwiGLU):
+ * [y_gate | y_up] = BitLinear(pre(x)) over a merged gate | up matrix, and h = silu(y_gate) * y_up is what gets
+ * stored -- the gate is applied where its two operands meet, once per element, and the 2 F projection outputs
+ * never travel through memory.  y_gate and y_up are the fp32 values bitnet_linear would store; silu as in
+ * bitnet_swiglu_quantize (same fixed-step exponential, one IEEE division).
+ *   x        [M][K], dtype F32 or BF16, 16-byte aligned
+ *   norm     0: pre = per-token absmax quantization (as bitnet_linear_fused);
+ *            1: pre = RMSNorm then quantization (as bitnet_rmsnorm_linear_fused), with g ([K] floats, 16-byte
+ *            aligned, or NULL) and eps >= 0; g and eps are ignored when norm == 0
+ *   packed   the [2 F][K] matrix, gate rows first; F a multiple of 16 (BITNET_ERR_SHAPE otherwise)
+ *   gamma    one float, or with gamma_per_block != 0 one per 16-row block (2 F / 16 floats, e.g. from
+ *            bitnet_quantize_weights_segmented with the segments {F, F})
+ *   h        out [M][F], dtype F32 or BF16 (BITNET_ERR_DTYPE for I32)
+ *   Limits as for bitnet_linear_fused.  2-bit format only.
+ * The down projection then takes h through bitnet_linear_fused.
+ */
+bitnet_status bitnet_ffn_gate_up_fused(const void* x, bitnet_dtype x_dtype, int norm, const float* g, float eps,
+                                       const void* packed, const float* gamma, int gamma_per_block,
+                                       int64_t M, int64_t F, int64_t K, bitnet_format f, void* h,
+                                       bitnet_dtype h_dtype, void* stream);
+
+/*
  * One scale per segment of rows.  Eq. (3) gives every weight matrix its own gamma; when several
  * matrices are stored as one (merged Q|K|V or gate|up projections) these entry points keep one gamma per
  * original matrix instead of one for the merged tensor.

@@ -27,6 +27,7 @@ SYMBOLS = [
     "bitnet_linear_fused", "bitnet_unpack_weights", "bitnet_rmsnorm_quantize", "bitnet_swiglu_quantize",
     "bitnet_quantize_weights_segmented", "bitnet_linear_segmented", "bitnet_linear_fused_segmented",
     "bitnet_rmsnorm_linear_fused", "bitnet_rmsnorm_linear_fused_segmented", "bitnet_swiglu_linear_fused",
+    "bitnet_ffn_gate_up_fused",
 ]
 
 _lib = None
@@ -68,6 +69,7 @@ def load():
     lib.bitnet_rmsnorm_linear_fused.argtypes = [vp, ci, vp, ctypes.c_float, vp, vp, i64, i64, i64, ci, vp, ci, vp]
     lib.bitnet_rmsnorm_linear_fused_segmented.argtypes = [vp, ci, vp, ctypes.c_float, vp, vp, i64, i64, i64, ci, vp, ci, vp]
     lib.bitnet_swiglu_linear_fused.argtypes = [vp, ci, vp, vp, i64, i64, i64, ci, vp, ci, vp]
+    lib.bitnet_ffn_gate_up_fused.argtypes = [vp, ci, ci, vp, ctypes.c_float, vp, vp, ci, i64, i64, i64, ci, vp, ci, vp]
     for name in SYMBOLS[2:]:
         getattr(lib, name).restype = ci
     _lib = lib
@@ -295,6 +297,22 @@ def swiglu_linear_fused(gu, packed, gamma, N, fmt=PACK_2BIT, y_dtype=F32, y=None
                                           M, N, F2 // 2, fmt, _dev(y, "y", (_OUT[y_dtype],)), y_dtype, _stream()),
            "bitnet_swiglu_linear_fused")
     return y
+
+
+def ffn_gate_up_fused(x, packed, gamma, F, norm=False, g=None, eps=1e-6, gamma_per_block=False, fmt=PACK_2BIT,
+                      h_dtype=F32, h=None):
+    """h [M,F] = silu(y_gate) * y_up with [y_gate | y_up] = BitLinear(pre(x)) over a merged gate|up matrix [2F,K] in one
+    decode launch; pre = RMSNorm (gain g or None, eps) when norm, else the plain absmax quantization."""
+    lib = load()
+    xp = _dev(x, "x", _FLOAT, 2)
+    M, K = x.shape
+    if h is None:
+        h = torch.empty((M, F), dtype=_OUT[h_dtype], device=x.device)
+    gp = None if g is None else _dev(g, "g", (torch.float32,))
+    _check(lib.bitnet_ffn_gate_up_fused(xp, _FLOAT[x.dtype], 1 if norm else 0, gp, float(eps), _dev(packed, "packed"),
+                                        _dev(gamma, "gamma", (torch.float32,)), 1 if gamma_per_block else 0, M, F, K, fmt,
+                                        _dev(h, "h", (_OUT[h_dtype],)), h_dtype, _stream()), "bitnet_ffn_gate_up_fused")
+    return h
 
 
 def unpack_weights(packed, N, K, fmt=PACK_2BIT, codes=None):

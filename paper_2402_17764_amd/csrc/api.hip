@@ -317,6 +317,24 @@ bitnet_status bitnet_swiglu_linear_fused(const void* gu, bitnet_dtype gu_dtype, 
                                                             static_cast<hipStream_t>(stream)));
 }
 
+bitnet_status bitnet_ffn_gate_up_fused(const void* x, bitnet_dtype x_dtype, int norm, const float* g, float eps,
+                                       const void* packed, const float* gamma, int gamma_per_block, int64_t M, int64_t F,
+                                       int64_t K, bitnet_format f, void* h, bitnet_dtype h_dtype, void* stream) {
+    if (!x || !packed || !gamma || !h) return BITNET_ERR_NULL;
+    if (F <= 0 || F % 16 != 0 || F >= ((int64_t)1 << 29) || !shape_ok(M, 2 * F, K) || (norm && !(eps >= 0.0f)))
+        return BITNET_ERR_SHAPE;
+    if (x_dtype != BITNET_F32 && x_dtype != BITNET_BF16) return BITNET_ERR_DTYPE;
+    if (h_dtype != BITNET_F32 && h_dtype != BITNET_BF16) return BITNET_ERR_DTYPE;
+    if (!format_ok(f)) return BITNET_ERR_FORMAT;
+    if (!aligned(packed, 16) || !aligned(gamma, 4) || !aligned(h, dtype_size(h_dtype)) || (norm && g && !aligned(g, 16)))
+        return BITNET_ERR_ALIGN;
+    if (f != BITNET_PACK_2BIT) return BITNET_ERR_FORMAT;
+    if (!bitnet::gemv_fused_supports(M, 2 * F, K, x)) return BITNET_ERR_KERNEL;
+    return from_hip(bitnet::launch_linear_fused_swiglu_out_2bit(
+        x, x_dtype == BITNET_BF16, norm != 0, norm ? g : nullptr, eps, packed, gamma, gamma_per_block ? 1 : 0, M, F, K, h,
+        h_dtype == BITNET_BF16 ? OutType::BF16 : OutType::F32, static_cast<hipStream_t>(stream)));
+}
+
 bitnet_status bitnet_unpack_weights(const void* packed, int64_t N, int64_t K, bitnet_format f, int8_t* codes,
                                     void* stream) {
     if (!packed || !codes) return BITNET_ERR_NULL;

@@ -64,6 +64,11 @@ hipError_t launch_rmsnorm_linear_fused_2bit(const void* x, bool bf16, const floa
 // ... and with SwiGLU gating in front: gu is [M][2 K] (gate | up), the product runs over K columns
 hipError_t launch_swiglu_linear_fused_2bit(const void* gu, bool bf16, const void* packed, const float* gamma, int gstride,
                                            int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);
+// merged gate | up projection ([2 F][K], F a multiple of 16) from x (absmax quantization, RMSNorm first if `norm`),
+// h = silu(y_gate) * y_up stored as [M][F] (F32 or BF16)
+hipError_t launch_linear_fused_swiglu_out_2bit(const void* x, bool bf16, bool norm, const float* gain, float eps,
+                                               const void* packed, const float* gamma, int gstride, int64_t M, int64_t F,
+                                               int64_t K, void* h, OutType yt, hipStream_t stream);
 
 // linear_gemm.hip
 bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq);

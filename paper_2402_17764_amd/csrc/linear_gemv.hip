@@ -371,13 +371,17 @@ __device__ inline void fused_quantize_to_lds(const void* __restrict__ xv, const 
 // kW    row slots per workgroup (waves with different row blocks), workgroup = kS * kW waves
 // kD    register prefetch depth in steps
 // kX    XMode
-template <int kR, int kS, int kW, int kD, int kX>
+// kPair the matrix is a merged gate | up projection of 2 * pair_off row blocks: a wave owns row block b of the gate half
+//       and row block b of the up half (kR = 2) and the epilogue stores h = silu(y_gate) * y_up, [M][N] with
+//       N = 16 * pair_off -- the SwiGLU of the feed-forward block applied where its two operands meet
+template <int kR, int kS, int kW, int kD, int kX, bool kPair = false>
 __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
         const void* __restrict__ xin /* x_q, or x for the fused modes */, const float* __restrict__ sx,
         const uint4* __restrict__ packed, const float* __restrict__ gamma, int gstride /* 0: one gamma, 1: one per row block */,
         int M, int64_t N, int64_t K, int Kq, int RB,
         int items /* K steps per wave, rounded up to a multiple of kD */, void* __restrict__ y, OutType yt,
-        const float* __restrict__ gain /* RMSNorm modes: per-column gain or null */, float eps) {
+        const float* __restrict__ gain /* RMSNorm modes: per-column gain or null */, float eps, int pair_off = 0) {
+    static_assert(!kPair || kR == 2, "a gate row block and an up row block per wave");
     extern __shared__ uint4 smem[];
     constexpr int kThreads = kS * kW * kWave;
     constexpr bool kFromLds = kX != kXGlobal;
@@ -394,7 +398,7 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
     const int ww = wave / kS;
     const int steps = (Kq + 3) >> 2;                   // K steps of 256 columns, the last may be partial
     const int tail_quads = 16 * (Kq - 4 * (steps - 1));   // quads in the last step's chunk (64 if whole)
-    const int rbw = (blockIdx.x * kW + ww) * kR;
+    const int rbw = kPair ? (int)(blockIdx.x * kW + ww) : (int)(blockIdx.x * kW + ww) * kR;
     const int Kpad = steps * 256;
     const int8_t* xq = static_cast<const int8_t*>(xin);
 
@@ -405,7 +409,8 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
     const int64_t wstride = (int64_t)RB * 64;          // quads per whole step
     int rbc[kR];
 #pragma unroll
-    for (int a = 0; a < kR; ++a) rbc[a] = min(rbw + a, RB - 1);   // row blocks past the matrix: clamped, never stored
+    for (int a = 0; a < kR; ++a)                                   // row blocks past the matrix: clamped, never stored
+        rbc[a] = kPair ? min(rbw, pair_off - 1) + a * pair_off : min(rbw + a, RB - 1);
     const int mrow = min(r, M - 1);
     const int8_t* xg = xq + (int64_t)mrow * K;
     const uint4* xl = xlds + mrow * (Kpad >> 4) + 4 * g;
@@ -540,6 +545,23 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
         }
     }
 
+    if (kPair) {
+        // y_gate and y_up exactly as the plain epilogue would store them in fp32, then the gate
+        if (r < M) {
+            const float s0 = (gm[0] * sc_row) / kQb, s1 = (gm[kR - 1] * sc_row) / kQb;
+            const int64_t n0 = (int64_t)rbw * 16 + 4 * g;
+            const int vg[4] = {acc[0].x >> 6, acc[0].y >> 6, acc[0].z >> 6, acc[0].w >> 6};
+            const int vu[4] = {acc[kR - 1].x >> 6, acc[kR - 1].y >> 6, acc[kR - 1].z >> 6, acc[kR - 1].w >> 6};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (n0 + e >= N) continue;
+                const float h = swiglu_one((float)vg[e] * s0, (float)vu[e] * s1);
+                if (yt == OutType::F32) static_cast<float*>(y)[(int64_t)r * N + n0 + e] = h;
+                else static_cast<uint16_t*>(y)[(int64_t)r * N + n0 + e] = f32_to_bf16(h);
+            }
+        }
+        return;
+    }
     if (r < M) {                                                    // MFMA output column = lane & 15 = token
 #pragma unroll
         for (int a = 0; a < kR; ++a) {
@@ -1112,6 +1134,45 @@ hipError_t launch_rmsnorm_linear_fused_2bit(const void* x, bool bf16, const floa
                                             const float* gamma, int gstride, int64_t M, int64_t N, int64_t K, void* y,
                                             OutType yt, hipStream_t stream) {
     dispatch16(bf16 ? kXNormBf16 : kXNormF32, x, nullptr, packed, gamma, gstride, M, N, K, y, yt, stream, gain, eps);
+    return hipGetLastError();
+}
+
+// merged gate | up projection with the SwiGLU gate in the epilogue; x goes through the fused quantization
+// (xmode: absmax only, or RMSNorm first).  F is a multiple of 16, so the up half starts on a row block.
+template <int kS, int kW, int kD>
+static void launch16_pair(int xmode, const void* x, const void* packed, const float* gamma, int gstride, int64_t M,
+                          int64_t F, int64_t K, void* h, OutType yt, hipStream_t stream, const float* gain, float eps) {
+    constexpr int kR = 2;
+    const int Kq = (int)ceil_div(K, kColsPerQuad);
+    const int pair_off = (int)(F / kRowsPerBlock);
+    const int RB = 2 * pair_off;
+    int items = (int)ceil_div(ceil_div(K, 256), kS);
+    items = (int)ceil_div(items, kD) * kD;
+    const size_t header = kGemvLdsHeader * sizeof(uint4);
+    const size_t lds_fold = kS > 1 ? (size_t)kW * kS * kR * kWave * 16 : 0;
+    const size_t lds_x = gemv16_x_lds_bytes(M, K);
+    const size_t lds = header + (lds_x > lds_fold ? lds_x : lds_fold);
+    dim3 grid((unsigned)ceil_div(pair_off, kW)), block(kS * kW * kWave);
+    const uint4* p = static_cast<const uint4*>(packed);
+#define GO(X_) hipLaunchKernelGGL((linear_gemv16_2bit<kR, kS, kW, kD, X_, true>), grid, block, lds, stream, x, (const float*)nullptr, p, gamma, \
+                                  gstride, (int)M, F, K, Kq, RB, items, h, yt, gain, eps, pair_off)
+    switch (xmode) {
+        case kXFusedBf16: GO(kXFusedBf16); break;
+        case kXFusedF32: GO(kXFusedF32); break;
+        case kXNormBf16: GO(kXNormBf16); break;
+        default: GO(kXNormF32); break;
+    }
+#undef GO
+}
+
+hipError_t launch_linear_fused_swiglu_out_2bit(const void* x, bool bf16, bool norm, const float* gain, float eps,
+                                               const void* packed, const float* gamma, int gstride, int64_t M, int64_t F,
+                                               int64_t K, void* h, OutType yt, hipStream_t stream) {
+    const int xmode = norm ? (bf16 ? kXNormBf16 : kXNormF32) : (bf16 ? kXFusedBf16 : kXFusedF32);
+    // few, wide workgroups as for the other pre-operations: two pairs per workgroup with K split in two, or four
+    // pairs with one wave each when there are many
+    if (F / kRowsPerBlock <= 700) launch16_pair<2, 2, 4>(xmode, x, packed, gamma, gstride, M, F, K, h, yt, stream, gain, eps);
+    else launch16_pair<1, 4, 5>(xmode, x, packed, gamma, gstride, M, F, K, h, yt, stream, gain, eps);
     return hipGetLastError();
 }
 

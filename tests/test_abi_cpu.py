@@ -94,6 +94,13 @@ def test_host_validation_rejects_before_launch():
     assert lib.bitnet_swiglu_linear_fused(a, 0, a, a, 1, 16, 64, 1, a, 0, NULL) == 4
     assert lib.bitnet_swiglu_linear_fused(a, 0, odd, a, 1, 16, 64, 0, a, 0, NULL) == 5
     assert lib.bitnet_swiglu_linear_fused(a, 0, a, a, 17, 16, 64, 0, a, 0, NULL) == 8
+    assert lib.bitnet_ffn_gate_up_fused(a, 0, 0, NULL, 0.0, a, NULL, 0, 1, 16, 64, 0, a, 0, NULL) == 1
+    assert lib.bitnet_ffn_gate_up_fused(a, 0, 0, NULL, 0.0, a, a, 0, 1, 24, 64, 0, a, 0, NULL) == 2          # F % 16
+    assert lib.bitnet_ffn_gate_up_fused(a, 0, 1, NULL, -1.0, a, a, 0, 1, 16, 64, 0, a, 0, NULL) == 2         # eps < 0 with norm
+    assert lib.bitnet_ffn_gate_up_fused(a, 0, 0, NULL, -1.0, a, a, 0, 17, 16, 64, 0, a, 0, NULL) == 8        # eps ignored without
+    assert lib.bitnet_ffn_gate_up_fused(a, 0, 0, NULL, 0.0, a, a, 0, 1, 16, 64, 0, a, 2, NULL) == 3          # I32 out
+    assert lib.bitnet_ffn_gate_up_fused(a, 0, 0, NULL, 0.0, a, a, 0, 1, 16, 64, 1, a, 0, NULL) == 4
+    assert lib.bitnet_ffn_gate_up_fused(a, 0, 1, vp(0x1004), 0.0, a, a, 0, 1, 16, 64, 0, a, 0, NULL) == 5
     # shapes
     assert lib.bitnet_quantize_acts(a, 0, 0, 16, a, a, NULL) == 2
     assert lib.bitnet_rmsnorm_quantize(a, 0, NULL, 0.0, 1, 0, a, a, NULL) == 2

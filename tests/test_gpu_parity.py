@@ -374,6 +374,65 @@ def test_swiglu_linear_fused_limits(gpu_lib):
     assert e.value.status == 8
 
 
+# merged gate | up projection with the gate applied in the epilogue: both workgroup shapes of its selection
+# (F / 16 up to 700 and above), K tails, several tokens, with and without RMSNorm, one scale and one per segment
+@pytest.mark.parametrize("M,F,K", [(1, 8640, 3200), (1, 11008, 4096), (3, 1008, 1040), (1, 16, 16), (2, 11216, 272),
+                                   (16, 48, 528), (1, 4000, 4112)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ffn_gate_up_fused(gpu_lib, M, F, K, dtype):
+    """h = silu(y_gate) * y_up must be the oracle's gate applied to the fp32 outputs of the plain fused launch
+    (bit for bit: same y, same fixed-step exponential), and the whole chain must match the oracle's chain."""
+    say("ffn gate/up fused %s M=%d F=%d K=%d" % (dtype, M, F, K))
+    W = synth.weights(2 * F, K, config=0, layer=M + 50, tensor=0)
+    W[F:] *= np.float32(1.5)                       # the halves differ in magnitude: one gamma per half matters
+    if dtype == "bf16":
+        x, bits = synth.activations(M, K, config=2, layer=M + 50, tensor=7, bf16=True)
+        xd = bf16_tensor(bits).view(M, K)
+    else:
+        x = synth.activations(M, K, config=0, layer=M + 50, tensor=7)
+        xd = dev(x)
+    rng = np.random.default_rng([13, K, M])
+    g = (1.0 + 0.25 * rng.standard_normal(K)).astype(np.float32)
+    packed, gamma = gpu_lib.quantize_weights(dev(W))
+    packed_s, gamma_rb = gpu_lib.quantize_weights_segmented(dev(W), [F, F])
+    # (a) against the plain fused launches + the oracle's gate on their fp32 output
+    for norm in (False, True):
+        y32 = (gpu_lib.rmsnorm_linear_fused(xd, dev(g), 1e-5, packed, gamma, 2 * F) if norm
+               else gpu_lib.linear_fused(xd, packed, gamma, 2 * F)).cpu().numpy()
+        h_ref = oracle.swiglu_quantize(y32)[2]
+        h32 = gpu_lib.ffn_gate_up_fused(xd, packed, gamma, F, norm=norm, g=dev(g) if norm else None, eps=1e-5)
+        assert h32.cpu().numpy().tobytes() == h_ref.tobytes()
+        h16 = gpu_lib.ffn_gate_up_fused(xd, packed, gamma, F, norm=norm, g=dev(g) if norm else None, eps=1e-5,
+                                        h_dtype=gpu_lib.BF16)
+        check_y(h16.float().cpu().numpy(), h_ref, RTOL_BF16)
+    y32 = gpu_lib.rmsnorm_linear_fused(xd, None, 1e-6, packed_s, gamma_rb, 2 * F, segmented=True).cpu().numpy()
+    h32 = gpu_lib.ffn_gate_up_fused(xd, packed_s, gamma_rb, F, norm=True, g=None, eps=1e-6, gamma_per_block=True)
+    assert h32.cpu().numpy().tobytes() == oracle.swiglu_quantize(y32)[2].tobytes()
+    # (b) against the oracle end to end: RMSNorm -> int8 -> product -> rescale -> gate
+    xq_ref, sx_ref, _ = oracle.rmsnorm_quantize(x, g, 1e-5)
+    gamma_ref, _ = oracle.absmean_gamma(W)
+    y_ref = oracle.rescale(oracle.ternary_matmul(xq_ref, oracle.ternarize(W, gamma_ref)), gamma_ref, sx_ref)
+    h_oracle = oracle.swiglu_quantize(y_ref)[2]
+    h32 = gpu_lib.ffn_gate_up_fused(xd, packed, gamma, F, norm=True, g=dev(g), eps=1e-5).cpu().numpy()
+    np.testing.assert_allclose(h32, h_oracle, rtol=5e-5, atol=1e-30)
+
+
+def test_ffn_gate_up_fused_limits(gpu_lib):
+    say("ffn gate/up fused: limits")
+    K = 64
+    p, g = gpu_lib.quantize_weights(dev(synth.weights(64, K, config=0, layer=1)))
+    x = dev(synth.activations(1, K, config=0, layer=1))
+    with pytest.raises(gpu_lib.BitnetError) as e:            # F must be a multiple of 16
+        gpu_lib.ffn_gate_up_fused(x, p, g, 24)
+    assert e.value.status == 2
+    with pytest.raises(gpu_lib.BitnetError) as e:            # int32 output makes no sense after the gate
+        gpu_lib.ffn_gate_up_fused(x, p, g, 32, h_dtype=gpu_lib.I32, h=torch.empty((1, 32), dtype=torch.int32, device="cuda"))
+    assert e.value.status == 3
+    with pytest.raises(gpu_lib.BitnetError) as e:
+        gpu_lib.ffn_gate_up_fused(dev(synth.activations(17, K, config=0, layer=1)), p, g, 32)
+    assert e.value.status == 8
+
+
 def test_linear_fused_rejects_what_it_cannot_run(gpu_lib):
     say("linear fused limits")
     W = dev(synth.weights(32, 8192, config=0, layer=1))
