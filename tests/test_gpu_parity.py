@@ -519,6 +519,81 @@ def test_linear_gemm_full_size_sampled(gpu_lib, M, N, K, layer):
         assert torch.equal(a_ref, a_full[sub])
 
 
+# the remaining benchmark configurations at full size, every token count the benchmark times
+FULL_SIZE_DECODE = [(2, "gate_up", 4096, 22016, (1, 8, 32, 64)), (2, "down", 11008, 4096, (1, 8, 32, 64)),
+                    (2, "qkv", 4096, 12288, (16, 64)), (4, "gate_up", 8192, 57344, (1, 64)), (4, "down", 28672, 8192, (1, 32))]
+
+
+@pytest.mark.parametrize("config,name,K,N,Ms", FULL_SIZE_DECODE)
+def test_linear_decode_full_size_sampled(gpu_lib, config, name, K, N, Ms):
+    """7B-class batched decode and 70B-class decode shapes at full size through bitnet_linear (and the fused entry
+    point at M = 1), as the benchmark launches them; the oracle recomputes a seeded sample of 512 weight rows for
+    every token (gamma over the whole matrix, codes, x_q, accumulators bit-exact)."""
+    say("linear decode full size config %d %s K=%d N=%d" % (config, name, K, N))
+    W = synth.weights(N, K, config=config, layer=0, tensor=len(name))
+    gamma_ref, _ = oracle.absmean_gamma(W)
+    rng = np.random.default_rng([config, K, N])
+    cols = np.sort(rng.choice(N, 512, replace=False))
+    cols[0], cols[-1] = 0, N - 1
+    codes_ref = oracle.ternarize(W[cols], gamma_ref)
+    packed, gamma = gpu_lib.quantize_weights(dev(W))
+    del W
+    assert gamma.cpu().numpy()[0] == gamma_ref
+    ci = torch.from_numpy(cols).cuda()
+    for M in Ms:
+        x, bits = synth.activations(M, K, config=config, layer=M, tensor=100, bf16=True)
+        xq_ref, sx_ref = oracle.quantize_acts(x)
+        acc_ref = oracle.ternary_matmul(xq_ref, codes_ref)
+        y_ref = oracle.rescale(acc_ref, gamma_ref, sx_ref)
+        xd = bf16_tensor(bits).view(M, K)
+        xq, sx = gpu_lib.quantize_acts(xd)
+        assert np.array_equal(xq.cpu().numpy(), xq_ref) and sx.cpu().numpy().tobytes() == sx_ref.tobytes()
+        acc = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.I32)
+        assert np.array_equal(acc[:, ci].cpu().numpy(), acc_ref)
+        y16 = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.BF16)
+        check_y(y16[:, ci].float().cpu().numpy(), y_ref, RTOL_BF16)
+        if M == 1:
+            accf = gpu_lib.linear_fused(xd, packed, gamma, N, y_dtype=gpu_lib.I32)
+            assert np.array_equal(accf[:, ci].cpu().numpy(), acc_ref)
+        # any-size property: the whole integer result equals the reference kernel's
+        a_ref = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.I32, kernel=gpu_lib.KERNEL_REFERENCE)
+        assert torch.equal(a_ref, acc)
+
+
+def test_linear_prefill_70b_full_size_sampled(gpu_lib):
+    """70B-class FFN shapes at M = 4096 (the prefill sweep of the last benchmark configuration), sampled."""
+    for (name, K, N) in (("gate_up", 8192, 57344), ("down", 28672, 8192)):
+        say("linear prefill full size 70B %s" % name)
+        M = 4096
+        W = synth.weights(N, K, config=4, layer=1, tensor=len(name))
+        gamma_ref, _ = oracle.absmean_gamma(W)
+        rng = np.random.default_rng([4, K, N])
+        rows = np.sort(rng.choice(M, 40, replace=False))
+        rows[0], rows[-1] = 0, M - 1
+        cols = np.sort(rng.choice(N, 320, replace=False))
+        cols[0], cols[-1] = 0, N - 1
+        codes_ref = oracle.ternarize(W[cols], gamma_ref)
+        packed, gamma = gpu_lib.quantize_weights(dev(W))
+        del W
+        assert gamma.cpu().numpy()[0] == gamma_ref
+        x, bits = synth.activations(M, K, config=4, layer=1, tensor=100, bf16=True)
+        xq_ref, sx_ref = oracle.quantize_acts(x[rows])
+        acc_ref = oracle.ternary_matmul(xq_ref, codes_ref)
+        y_ref = oracle.rescale(acc_ref, gamma_ref, sx_ref)
+        xq, sx = gpu_lib.quantize_acts(bf16_tensor(bits).view(M, K))
+        del x, bits
+        ri = torch.from_numpy(rows).cuda()
+        ci = torch.from_numpy(cols).cuda()
+        assert np.array_equal(xq[ri].cpu().numpy(), xq_ref)
+        acc = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.I32)
+        assert np.array_equal(acc[ri][:, ci].cpu().numpy(), acc_ref)
+        del acc
+        y16 = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.BF16)
+        check_y(y16[ri][:, ci].float().cpu().numpy(), y_ref, RTOL_BF16)
+        del y16, packed, xq
+        torch.cuda.empty_cache()
+
+
 def test_random_shapes_every_kernel_agrees(gpu_lib):
     """48 seeded shapes drawn across the kernel-selection boundaries (tokens 1..300, rows 1..6000, K a multiple
     of 16 up to 4096): every product kernel that accepts the shape returns the reference kernel's int32
