@@ -138,16 +138,28 @@ def cpu_baseline(cfg_idx, M, seconds_target=12.0):
 
 
 def large_gemv_leg(torch, B, synth, gen, stream, args):
-    """M = 1 on the 70B-class FFN shapes (the sizes at which a weight stream can approach the HBM roofline):
-    each shape is replayed over enough distinct layers to exceed the 256 MB memory-side cache."""
+    """The 70B-class FFN shapes (the sizes at which a weight stream can approach the HBM roofline): M = 1 with each
+    shape replayed over enough distinct layers to exceed the 256 MB memory-side cache, the M = 4096 prefill product,
+    and the one-off weight quantization + packing time per layer."""
     res = {}
     for (name, K, N) in synth.CONFIGS[4]["shapes"]:
         per = N * K // 4
         layers = max(3, int(math.ceil(600e6 / per)))
         packs = []
+        wq_ms = []
         for l in range(layers):
             W = torch.randn((N, K), device="cuda", generator=gen, dtype=torch.float32) * synth.SIGMA_W
-            packs.append(B.quantize_weights(W))
+            if l >= 1:
+                torch.cuda.synchronize()
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                packs.append(B.quantize_weights(W))
+                e1.record()
+                torch.cuda.synchronize()
+                wq_ms.append(e0.elapsed_time(e1))
+            else:
+                packs.append(B.quantize_weights(W))
             del W
         x = make_acts(torch, 1, K, gen, 4)
         y = torch.empty((1, N), dtype=torch.bfloat16, device="cuda")
@@ -160,8 +172,33 @@ def large_gemv_leg(torch, B, synth, gen, stream, args):
         us = ms * 1e3 / layers
         gbs = gemv_bytes(1, N, K) / (us * 1e-6) / 1e9
         res[name] = {"K": K, "N": N, "layers": layers, "us_per_launch": round(us, 2), "GB/s": round(gbs, 1),
-                     "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
-        del packs
+                     "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+                     "weight_quant_ms_per_layer": round(min(wq_ms), 3),
+                     "weight_quant_GB/s": round(8.25 * N * K / (min(wq_ms) * 1e-3) / 1e9, 1)}
+        # prefill on the same shape
+        M = 4096
+        xp = make_acts(torch, M, K, gen, 4)
+        xq, sx = B.quantize_acts(xp)
+        del xp
+        yp = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        p0, g0 = packs[0]
+        t_w = time.perf_counter()
+        while time.perf_counter() - t_w < 0.030:
+            B.linear(xq, sx, p0, g0, N, y_dtype=B.BF16, y=yp)
+            torch.cuda.synchronize()
+        iters = 5
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            B.linear(xq, sx, p0, g0, N, y_dtype=B.BF16, y=yp)
+        e1.record()
+        torch.cuda.synchronize()
+        us_p = e0.elapsed_time(e1) * 1e3 / iters
+        tops = 2.0 * M * N * K / (us_p * 1e-6) / 1e12
+        res[name]["prefill_m4096"] = {"us_linear": round(us_p, 1), "TOPS": round(tops, 1),
+                                      "frac_int8_mfma_peak": round(tops / INT8_MFMA_PEAK_TOPS, 4)}
+        del packs, xq, sx, yp
         torch.cuda.empty_cache()
     return res
 
