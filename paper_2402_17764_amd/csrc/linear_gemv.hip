@@ -29,16 +29,9 @@ namespace bitnet {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-__device__ inline v4i decode_word(uint32_t w) {
-    v4i a;
-    a.x = (int)((w << 6) & 0xC0C0C0C0u);
-    a.y = (int)((w << 4) & 0xC0C0C0C0u);
-    a.z = (int)((w << 2) & 0xC0C0C0C0u);
-    a.w = (int)(w & 0xC0C0C0C0u);
-    return a;
-}
-
-// the same with the lane's validity folded into the constant: km is 0xC0C0C0C0 or 0
+// One packed word (16 codes) -> the four int8 operand registers of an MFMA, 64 * code in every byte:
+// (w << (6 - 2 i)) & 0xC0C0C0C0 for register i.  The lane's validity is folded into the constant: km is
+// 0xC0C0C0C0, or 0 for lanes and steps whose weights must not count.
 __device__ inline v4i decode_word_masked(uint32_t w, uint32_t km) {
     v4i a;
     a.x = (int)((w << 6) & km);
@@ -440,7 +433,7 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
         const int step = ws + item * kS;
         const int sl = min(step, steps - 1);
         const int cq = sl == steps - 1 ? tail_quads : 64;
-        const uint32_t keep = (step < steps && lane < cq) ? 0xFFFFFFFFu : 0u;
+        const uint32_t km = (step < steps && lane < cq) ? 0xC0C0C0C0u : 0u;   // validity folded into the decode constant
         if (kFromLds) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) s.x[j] = xl[sl * 16 + j];
@@ -449,7 +442,7 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int a = 0; a < kR; ++a)
-                acc[a] = __builtin_amdgcn_mfma_i32_16x16x64_i8(decode_word(quad_word(s.w[a], j) & keep), as_v4i(s.x[j]),
+                acc[a] = __builtin_amdgcn_mfma_i32_16x16x64_i8(decode_word_masked(quad_word(s.w[a], j), km), as_v4i(s.x[j]),
                                                                acc[a], 0, 0, 0);
     };
 
