@@ -56,8 +56,9 @@ constexpr int gemm_lds_bytes(int fm) { return gemm_scale_offset(fm) + fm * 32 * 
 
 __device__ inline uint32_t gemm_quad_word(const uint4& q, int j) { return j == 0 ? q.x : j == 1 ? q.y : j == 2 ? q.z : q.w; }
 
-// one register of the decoded B operand: columns 4 i .. 4 i + 3 of the word, as 64 * code per byte
-__device__ inline int gemm_decode_reg(uint32_t w, int i) { return (int)((w << (6 - 2 * i)) & 0xC0C0C0C0u); }
+// one register of the decoded B operand: columns 4 i .. 4 i + 3 of the word, as 64 * code per byte; km is
+// 0xC0C0C0C0, or 0 for lanes whose quad lies past a partial last K step
+__device__ inline int gemm_decode_reg(uint32_t w, int i, uint32_t km) { return (int)((w << (6 - 2 * i)) & km); }
 
 struct GemmOutCtx {
     char* lds;
@@ -265,7 +266,7 @@ __device__ __forceinline__ void gemm_tile(
 
     // One K step: 8 slices of 32 columns, slice (h, j) uses word j of quad h; the LDS reads and the
     // decode for slice t + 1 are placed among the MFMAs of slice t.
-    auto compute = [&](const uint4 (&wq)[kFN][2], int stage) {
+    auto compute = [&](const uint4 (&wq)[kFN][2], const uint32_t (&km)[2], int stage) {
         const char* src = lds + stage * kGemmStageBytes + a_row_base;
         const int sw = am & 15;
         v4i a[2][kFM], b[2][kFN];
@@ -281,7 +282,7 @@ __device__ __forceinline__ void gemm_tile(
         for (int fn = 0; fn < kFN; ++fn) {
             const uint32_t w = word_of(fn, 0);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) b[0][fn][i] = gemm_decode_reg(w, i);
+            for (int i = 0; i < 4; ++i) b[0][fn][i] = gemm_decode_reg(w, i, km[0]);
         }
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
@@ -297,7 +298,7 @@ __device__ __forceinline__ void gemm_tile(
                 if (t < 7) {                                        // the next slice's decode, spread over the MFMAs
 #pragma unroll
                     for (int d = q * kRegs / kMfmas; d < (q + 1) * kRegs / kMfmas; ++d)
-                        b[nxt][d >> 2][d & 3] = gemm_decode_reg(word_of(d >> 2, t + 1), d & 3);
+                        b[nxt][d >> 2][d & 3] = gemm_decode_reg(word_of(d >> 2, t + 1), d & 3, km[(t + 1) >> 2]);
                 }
             }
         }
@@ -308,8 +309,8 @@ __device__ __forceinline__ void gemm_tile(
     // consumed (activations into the other LDS stage, weights into wnext), and the barrier at the top of
     // the next iteration both publishes them and retires the stage that was just read.
     uint4 wq[kFN][2], wnext[kFN][2];
-    const uint32_t keep_t0 = (kg * 16 + brow) < tail_quads ? 0xFFFFFFFFu : 0u;
-    const uint32_t keep_t1 = ((kg + 2) * 16 + brow) < tail_quads ? 0xFFFFFFFFu : 0u;
+    const uint32_t keep_t0 = (kg * 16 + brow) < tail_quads ? 0xC0C0C0C0u : 0u;
+    const uint32_t keep_t1 = ((kg + 2) * 16 + brow) < tail_quads ? 0xC0C0C0C0u : 0u;
     auto issue = [&](int step) {
         copy_x(step, step & 1);
         if (step < full_steps) load_w(wnext, step); else load_w_tail(wnext, step);
@@ -319,18 +320,15 @@ __device__ __forceinline__ void gemm_tile(
     for (int s = 0; s < steps; ++s) {
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        // move the step's quads out of the landing registers; lanes past a partial last step are zeroed here
-        const uint32_t all = s >= full_steps ? 0u : 0xFFFFFFFFu;   // uniform
-        const uint32_t keep_h[2] = {keep_t0 | all, keep_t1 | all};
+        // move the step's quads out of the landing registers; lanes past a partial last step get a zero decode constant
+        const uint32_t all = s >= full_steps ? 0u : 0xC0C0C0C0u;   // uniform
+        const uint32_t km[2] = {keep_t0 | all, keep_t1 | all};
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const uint32_t keep = keep_h[h];
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
-            for (int fn = 0; fn < kFN; ++fn)
-                wq[fn][h] = make_uint4(wnext[fn][h].x & keep, wnext[fn][h].y & keep, wnext[fn][h].z & keep, wnext[fn][h].w & keep);
-        }
+            for (int fn = 0; fn < kFN; ++fn) wq[fn][h] = wnext[fn][h];
         if (s + 1 < steps) issue(s + 1);
-        compute(wq, s & 1);
+        compute(wq, km, s & 1);
     }
     __syncthreads();                                    // every wave is done with the activation stages
 
