@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libbitnet_hip.so")
 
-SOURCES = ["api.hip", "quant_weights.hip", "quant_acts.hip", "linear_ref.hip", "linear_gemv.hip", "linear_gemm.hip", "trit5.hip"]
+SOURCES = ["api.hip", "quant_weights.hip", "quant_acts.hip", "linear_ref.hip", "linear_gemv.hip", "linear_skinny.hip", "linear_gemm.hip", "trit5.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -29,7 +29,7 @@ FLAGS = [
 
 # Kernels that count the vector-memory loads in flight (explicit s_waitcnt vmcnt(n)): a register spill would
 # add scratch loads to that count, so the build fails if the compiler gives any of them scratch memory.
-NO_SCRATCH = {"linear_gemv.hip": ("linear_skinny_2bit", "linear_skinny_ws_2bit")}
+NO_SCRATCH = {"linear_skinny.hip": ("linear_skinny_2bit", "linear_skinny_ws_2bit")}
 
 
 def _check_no_scratch(src, stderr):

@@ -54,6 +54,9 @@ bool gemv_supports(int64_t M, int64_t N, int64_t K, const void* xq);
 hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void* packed,
                                    const float* gamma, int gstride, int64_t M, int64_t N, int64_t K, void* y,
                                    OutType yt, hipStream_t stream);
+// the M <= 16 kernel alone (linear_gemv.hip); launch_linear_gemv_2bit (linear_skinny.hip) routes M <= 4 to it
+hipError_t launch_linear_gemv16_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma, int gstride,
+                                     int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);
 bool gemv_fused_supports(int64_t M, int64_t N, int64_t K, const void* x);
 hipError_t launch_linear_fused_2bit(const void* x, bool bf16, const void* packed, const float* gamma, int gstride,
                                     int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);
