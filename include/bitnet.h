@@ -47,7 +47,7 @@ typedef enum bitnet_status {
     BITNET_ERR_DTYPE = 3,       /* dtype not accepted by this argument */
     BITNET_ERR_FORMAT = 4,      /* unknown packing format, or not supported by this call */
     BITNET_ERR_ALIGN = 5,       /* a pointer is not aligned as documented */
-    BITNET_ERR_WORKSPACE = 6,   /* workspace smaller than bitnet_quantize_weights_workspace says */
+    BITNET_ERR_WORKSPACE = 6,   /* workspace smaller than the call needs (see the call's workspace query) */
     BITNET_ERR_HIP = 7,         /* the HIP runtime refused the launch */
     BITNET_ERR_KERNEL = 8       /* requested kernel variant cannot run this shape */
 } bitnet_status;
@@ -108,7 +108,11 @@ typedef enum bitnet_kernel {
     BITNET_KERNEL_GEMM_64x256 = 0x122,
     BITNET_KERNEL_GEMM_128x128 = 0x141,
     BITNET_KERNEL_GEMM_96x128 = 0x131,
-    BITNET_KERNEL_GEMM_64x128 = 0x121
+    BITNET_KERNEL_GEMM_64x128 = 0x121,
+    /* bitnet_linear_ws only: the prefill kernel with the K steps split over 2, 4 or 8 workgroups per tile */
+    BITNET_KERNEL_GEMM_SPLITK_2 = 0x202,
+    BITNET_KERNEL_GEMM_SPLITK_4 = 0x204,
+    BITNET_KERNEL_GEMM_SPLITK_8 = 0x208
 } bitnet_kernel;
 
 /* Library version, major*10000 + minor*100 + patch.  Also the version of the packed layouts. */
@@ -195,6 +199,29 @@ bitnet_status bitnet_linear_variant(const int8_t* xq, const float* sx, const voi
                                     const float* gamma, int64_t M, int64_t N, int64_t K,
                                     bitnet_format f, void* y, bitnet_dtype y_dtype,
                                     bitnet_kernel which, void* stream);
+
+/*
+ * bitnet_linear with a scratch buffer.  Between decode and large prefill -- a few hundred tokens on layers with few
+ * output features -- even the smallest tiles of the prefill kernel give the 256 CUs too few workgroups, each walking
+ * all of K.  With a workspace the K steps of a tile are split over 2, 4 or 8 workgroups that store int32 partial
+ * accumulators there; a second launch adds them (exact, independent of the split) and rescales.  Chosen by the same
+ * cost model as the tile shape, only where it pays: long K, few tiles (measured on MI355X, M = 128: 11008 -> 4096 in
+ * 18.1 instead of 25.4 us, 28672 -> 8192 in 40.7 instead of 70.9 us; nothing to gain at K = 4096 or from 512 tokens
+ * on).  Results are bit-identical to bitnet_linear / bitnet_linear_segmented.
+ *   gamma_per_block  0: one gamma; otherwise one per 16-row block (as bitnet_linear_segmented)
+ *   which            BITNET_KERNEL_AUTO, any selector of bitnet_linear_variant (the workspace is then unused), or
+ *                    BITNET_KERNEL_GEMM_SPLITK_n to force n splits (BITNET_ERR_WORKSPACE if the buffer is too small
+ *                    or K has fewer than n steps of 256 columns)
+ *   workspace        device memory, 16-byte aligned, or NULL (then this is bitnet_linear); contents are scratch:
+ *                    nothing is expected in it and nothing of value is left; calls that share it must not overlap
+ *   workspace_bytes  its size; bitnet_linear_workspace reports the size with which every split the model may want fits
+ *                    (0 where split-K is never considered: M <= 64, or 512 or more tiles of 64 x 128)
+ */
+bitnet_status bitnet_linear_workspace(int64_t M, int64_t N, int64_t K, size_t* bytes);
+bitnet_status bitnet_linear_ws(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
+                               int gamma_per_block, int64_t M, int64_t N, int64_t K, bitnet_format f,
+                               void* y, bitnet_dtype y_dtype, bitnet_kernel which, void* workspace,
+                               size_t workspace_bytes, void* stream);
 
 /*
  * Decode path in one launch: activation quantization fused into the weight-streaming kernel, x -> y.

@@ -19,6 +19,7 @@ F32, BF16, I32 = 0, 1, 2
 PACK_2BIT, PACK_TRIT5 = 0, 1
 KERNEL_AUTO, KERNEL_REFERENCE, KERNEL_GEMV, KERNEL_GEMM = 0, 1, 2, 3
 # the prefill kernel with a fixed workgroup tile, tokens x weight rows (tuning and tests)
+KERNEL_GEMM_SPLITK = {2: 0x202, 4: 0x204, 8: 0x208}       # bitnet_linear_ws only
 KERNEL_GEMM_TILES = {(128, 256): 0x142, (96, 256): 0x132, (64, 256): 0x122, (128, 128): 0x141, (96, 128): 0x131, (64, 128): 0x121}
 
 SYMBOLS = [
@@ -27,7 +28,7 @@ SYMBOLS = [
     "bitnet_linear_fused", "bitnet_unpack_weights", "bitnet_rmsnorm_quantize", "bitnet_swiglu_quantize",
     "bitnet_quantize_weights_segmented", "bitnet_linear_segmented", "bitnet_linear_fused_segmented",
     "bitnet_rmsnorm_linear_fused", "bitnet_rmsnorm_linear_fused_segmented", "bitnet_swiglu_linear_fused",
-    "bitnet_ffn_gate_up_fused",
+    "bitnet_ffn_gate_up_fused", "bitnet_linear_workspace", "bitnet_linear_ws",
 ]
 
 _lib = None
@@ -69,6 +70,8 @@ def load():
     lib.bitnet_rmsnorm_linear_fused.argtypes = [vp, ci, vp, ctypes.c_float, vp, vp, i64, i64, i64, ci, vp, ci, vp]
     lib.bitnet_rmsnorm_linear_fused_segmented.argtypes = [vp, ci, vp, ctypes.c_float, vp, vp, i64, i64, i64, ci, vp, ci, vp]
     lib.bitnet_swiglu_linear_fused.argtypes = [vp, ci, vp, vp, i64, i64, i64, ci, vp, ci, vp]
+    lib.bitnet_linear_workspace.argtypes = [i64, i64, i64, ctypes.POINTER(sz)]
+    lib.bitnet_linear_ws.argtypes = [vp, vp, vp, vp, ci, i64, i64, i64, ci, vp, ci, ci, vp, sz, vp]
     lib.bitnet_ffn_gate_up_fused.argtypes = [vp, ci, ci, vp, ctypes.c_float, vp, vp, ci, i64, i64, i64, ci, vp, ci, vp]
     for name in SYMBOLS[2:]:
         getattr(lib, name).restype = ci
@@ -196,6 +199,29 @@ def linear(xq, sx, packed, gamma, N, fmt=PACK_2BIT, y_dtype=F32, y=None, kernel=
         _check(lib.bitnet_linear(*args, _stream()), "bitnet_linear")
     else:
         _check(lib.bitnet_linear_variant(*args, kernel, _stream()), "bitnet_linear_variant")
+    return y
+
+
+def linear_workspace(M, N, K):
+    """Bytes of scratch with which linear_ws can use every split-K variant it may choose for this shape (0: none)."""
+    lib = load()
+    out = ctypes.c_size_t(0)
+    _check(lib.bitnet_linear_workspace(M, N, K, ctypes.byref(out)), "bitnet_linear_workspace")
+    return int(out.value)
+
+
+def linear_ws(xq, sx, packed, gamma, N, workspace, fmt=PACK_2BIT, y_dtype=F32, y=None, kernel=KERNEL_AUTO,
+              gamma_per_block=False):
+    """bitnet_linear with a scratch buffer (uint8 tensor or None) that lets the prefill kernel split K."""
+    lib = load()
+    M, K = xq.shape
+    if y is None:
+        y = torch.empty((M, N), dtype=_OUT[y_dtype], device=xq.device)
+    wp = None if workspace is None else _dev(workspace, "workspace")
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.bitnet_linear_ws(_dev(xq, "xq", (torch.int8,), 2), _dev(sx, "sx", (torch.float32,)), _dev(packed, "packed"),
+                                _dev(gamma, "gamma", (torch.float32,)), 1 if gamma_per_block else 0, M, N, K, fmt,
+                                _dev(y, "y", (_OUT[y_dtype],)), y_dtype, kernel, wp, wb, _stream()), "bitnet_linear_ws")
     return y
 
 

@@ -200,6 +200,44 @@ bitnet_status bitnet_linear(const int8_t* xq, const float* sx, const void* packe
     return linear_any(xq, sx, packed, gamma, 0, M, N, K, f, y, y_dtype, BITNET_KERNEL_AUTO, stream);
 }
 
+bitnet_status bitnet_linear_workspace(int64_t M, int64_t N, int64_t K, size_t* bytes) {
+    if (!bytes) return BITNET_ERR_NULL;
+    if (!shape_ok(M, N, K)) return BITNET_ERR_SHAPE;
+    // split-K is considered only where even 64 x 128 tiles leave workgroup slots empty (fewer than 512 of them)
+    const int64_t tiles = ((M + 63) / 64) * ((N + 127) / 128);
+    *bytes = (M > 64 && tiles < 512) ? bitnet::gemm_splitk_workspace_bytes(M, N, 8) : 0;
+    return BITNET_OK;
+}
+
+bitnet_status bitnet_linear_ws(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
+                               int gamma_per_block, int64_t M, int64_t N, int64_t K, bitnet_format f, void* y,
+                               bitnet_dtype y_dtype, bitnet_kernel which, void* workspace, size_t workspace_bytes,
+                               void* stream) {
+    const int gstride = gamma_per_block ? 1 : 0;
+    int force = 0;
+    if (((int)which & ~0xFF) == 0x200) {               // split-K forced: 0x200 | splits
+        force = (int)which & 0xFF;
+        if (force != 2 && force != 4 && force != 8) return BITNET_ERR_KERNEL;
+    } else if (which != BITNET_KERNEL_AUTO) {
+        return linear_any(xq, sx, packed, gamma, gstride, M, N, K, f, y, y_dtype, which, stream);
+    }
+    if (!xq || !sx || !packed || !gamma || !y) return BITNET_ERR_NULL;
+    if (!shape_ok(M, N, K)) return BITNET_ERR_SHAPE;
+    if (workspace && !aligned(workspace, 16)) return BITNET_ERR_ALIGN;
+    const bool gemm_path = f == BITNET_PACK_2BIT && (force || !bitnet::gemv_supports(M, N, K, xq)) && bitnet::gemm_supports(M, N, K, xq);
+    if (!gemm_path) {
+        if (force) return BITNET_ERR_KERNEL;
+        return linear_any(xq, sx, packed, gamma, gstride, M, N, K, f, y, y_dtype, BITNET_KERNEL_AUTO, stream);
+    }
+    OutType yt;
+    if (!out_type(y_dtype, &yt)) return BITNET_ERR_DTYPE;
+    if (!aligned(packed, 16) || !aligned(sx, 4) || !aligned(gamma, 4) || !aligned(y, dtype_size(y_dtype))) return BITNET_ERR_ALIGN;
+    if (force && (!workspace || workspace_bytes < bitnet::gemm_splitk_workspace_bytes(M, N, force) || force > (K + 255) / 256))
+        return BITNET_ERR_WORKSPACE;
+    return from_hip(bitnet::launch_linear_gemm_2bit(xq, sx, packed, gamma, gstride, M, N, K, y, yt, static_cast<hipStream_t>(stream),
+                                                    workspace, workspace ? workspace_bytes : 0, force));
+}
+
 bitnet_status bitnet_linear_segmented(const int8_t* xq, const float* sx, const void* packed, const float* gamma_rb,
                                       int64_t M, int64_t N, int64_t K, bitnet_format f, void* y,
                                       bitnet_dtype y_dtype, bitnet_kernel which, void* stream) {

@@ -75,12 +75,17 @@ hipError_t launch_linear_fused_swiglu_out_2bit(const void* x, bool bf16, bool no
 
 // linear_gemm.hip
 bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq);
+// workspace (may be null): room for split-K partials; force_splits > 0 picks the number of splits (1, 2, 4, 8) by hand
 hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                    int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt,
-                                   hipStream_t stream);
-// the same with the tile forced: 32 * fm tokens x 128 * fn weight rows, fm in 2 .. 4, fn in 1 .. 2 (hipErrorInvalidValue otherwise)
+                                   hipStream_t stream, void* workspace = nullptr, size_t workspace_bytes = 0,
+                                   int force_splits = 0);
+// the same with the tile forced: 32 * fm tokens x 128 * fn weight rows, fm in 2 .. 4, fn in 1 .. 2 (hipErrorInvalidValue
+// otherwise); splits > 1 needs a workspace of gemm_splitk_workspace_bytes(M, N, splits)
 hipError_t launch_linear_gemm_2bit_shape(int fm, int fn, const int8_t* xq, const float* sx, const void* packed, const float* gamma,
-                                         int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);
+                                         int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream,
+                                         int splits = 1, void* workspace = nullptr);
+size_t gemm_splitk_workspace_bytes(int64_t M, int64_t N, int splits);
 
 // trit5.hip
 hipError_t launch_pack_trit5(const void* W, bool bf16, int64_t N, int64_t K, const float* gamma, void* packed,

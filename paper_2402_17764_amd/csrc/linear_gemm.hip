@@ -167,6 +167,7 @@ template <int kFM, int kFN>
 __device__ __forceinline__ void gemm_tile(
         const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
         const float* __restrict__ gamma, int gstride, int M, int64_t N, int64_t K, int Kq, int RB, int row0, int bn,
+        int step0, int step1 /* the K steps of 256 columns this workgroup contracts: all of them, or one split */,
         void* __restrict__ y, OutType yt, int vec_store) {
 #if defined(__HIP_DEVICE_COMPILE__)      // the buffer-resource builtins exist in the device pass only
     extern __shared__ uint4 smem[];
@@ -315,9 +316,9 @@ __device__ __forceinline__ void gemm_tile(
         copy_x(step, step & 1);
         if (step < full_steps) load_w(wnext, step); else load_w_tail(wnext, step);
     };
-    issue(0);
+    issue(step0);
 #pragma unroll 1
-    for (int s = 0; s < steps; ++s) {
+    for (int s = step0; s < step1; ++s) {
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
         // move the step's quads out of the landing registers; lanes past a partial last step get a zero decode constant
@@ -327,7 +328,7 @@ __device__ __forceinline__ void gemm_tile(
         for (int h = 0; h < 2; ++h)
 #pragma unroll
             for (int fn = 0; fn < kFN; ++fn) wq[fn][h] = wnext[fn][h];
-        if (s + 1 < steps) issue(s + 1);
+        if (s + 1 < step1) issue(s + 1);
         compute(wq, km, s & 1);
     }
     __syncthreads();                                    // every wave is done with the activation stages
@@ -344,13 +345,50 @@ __device__ __forceinline__ void gemm_tile(
 // CU: what the registers and the LDS stages allow (two with the tall wide tiles, up to four with 64-token tiles).
 constexpr int gemm_blocks_per_cu(int fm, int fn) { return fn == 1 ? (fm == 2 ? 4 : fm == 3 ? 3 : 2) : (fm == 2 ? 3 : 2); }
 
+// blockIdx.y selects a split of the K steps (split-K: every split stores its int32 partial accumulators, [M][N] each,
+// one after the other at y; a second kernel adds them up and rescales).  One split: the whole product, stored as yt.
 template <int kFM, int kFN>
 __global__ __launch_bounds__(kGemmThreads, gemm_blocks_per_cu(kFM, kFN)) void linear_gemm_2bit(
         const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
         const float* __restrict__ gamma, int gstride, int M, int64_t N, int64_t K, int Kq, int RB, int tiles_m,
-        void* __restrict__ y, OutType yt, int vec_store) {
+        int steps_per_split, void* __restrict__ y, OutType yt, int vec_store) {
     const int b = blockIdx.x;
-    gemm_tile<kFM, kFN>(xq, sx, packed, gamma, gstride, M, N, K, Kq, RB, (b % tiles_m) * (32 * kFM), b / tiles_m, y, yt, vec_store);
+    const int steps = (Kq + 3) >> 2;
+    const int step0 = blockIdx.y * steps_per_split;
+    const int step1 = min(steps, step0 + steps_per_split);
+    void* yp = static_cast<char*>(y) + (int64_t)blockIdx.y * M * N * 4;        // blockIdx.y > 0 only with int32 partials
+    gemm_tile<kFM, kFN>(xq, sx, packed, gamma, gstride, M, N, K, Kq, RB, (b % tiles_m) * (32 * kFM), b / tiles_m, step0, step1,
+                        yp, yt, vec_store);
+}
+
+// split-K, second kernel: y[m][n] = (sum over the splits of the partial accumulators) * gamma * s_x[m] / 127, four
+// consecutive outputs per thread.  Integer sums: exact and independent of the number of splits.
+__global__ __launch_bounds__(256) void gemm_splitk_reduce(const int32_t* __restrict__ part, int splits, const float* __restrict__ sx,
+                                                          const float* __restrict__ gamma, int gstride, int64_t M, int64_t N,
+                                                          void* __restrict__ y, OutType yt) {
+    const int64_t quads_per_row = (N + 3) >> 2;
+    const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (q >= M * quads_per_row) return;
+    const int64_t m = q / quads_per_row, n0 = (q - m * quads_per_row) * 4;
+    int acc[4] = {0, 0, 0, 0};
+    for (int p = 0; p < splits; ++p) {
+        const int32_t* src = part + ((int64_t)p * M + m) * N + n0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (n0 + e < N) acc[e] += src[e];
+    }
+    const float sxm = yt == OutType::I32 ? 0.0f : sx[m];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (n0 + e >= N) continue;
+        const int64_t o = m * N + n0 + e;
+        if (yt == OutType::I32) { static_cast<int32_t*>(y)[o] = acc[e]; continue; }
+        // the same association as the one-launch epilogue, so that splitting never changes a bit of the output
+        const float scale = gstride ? gamma[(n0 + e) / kRowsPerBlock] * (sxm / kQb) : (gamma[0] * sxm) / kQb;
+        const float v = (float)acc[e] * scale;
+        if (yt == OutType::F32) static_cast<float*>(y)[o] = v;
+        else static_cast<uint16_t*>(y)[o] = f32_to_bf16(v);
+    }
 }
 
 bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
@@ -362,7 +400,7 @@ bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
 template <int kFM, int kFN>
 static hipError_t launch_gemm_tiles(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                     int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt,
-                                    hipStream_t stream) {
+                                    hipStream_t stream, int splits = 1, void* workspace = nullptr) {
     static bool raised[kMaxDevices] = {};
     const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(linear_gemm_2bit<kFM, kFN>), gemm_lds_bytes(kFM), raised);
     if (e != hipSuccess) return e;
@@ -370,26 +408,42 @@ static hipError_t launch_gemm_tiles(const int8_t* xq, const float* sx, const voi
     const int RB = (int)ceil_div(N, kRowsPerBlock);
     const int tiles_m = (int)ceil_div(M, 32 * kFM);
     const int64_t tiles_n = ceil_div(N, 128 * kFN);
-    const size_t esz = yt == OutType::BF16 ? 2 : 4;
-    const int vec_store = (reinterpret_cast<uintptr_t>(y) % 16 == 0) && ((N * esz) % 16 == 0);
-    hipLaunchKernelGGL((linear_gemm_2bit<kFM, kFN>), dim3((unsigned)(tiles_m * tiles_n)), dim3(kGemmThreads), gemm_lds_bytes(kFM),
-                       stream, xq, sx, static_cast<const uint4*>(packed), gamma, gstride, (int)M, N, K, Kq, RB, tiles_m, y, yt,
-                       vec_store);
+    const int steps = (int)ceil_div(K, 256);
+    if (splits > steps) splits = steps;
+    const int sps = (int)ceil_div(steps, splits);
+    splits = (int)ceil_div(steps, sps);                 // no empty split
+    const bool split = splits > 1;
+    void* out = split ? workspace : y;
+    const OutType ot = split ? OutType::I32 : yt;
+    const size_t esz = ot == OutType::BF16 ? 2 : 4;
+    const int vec_store = (reinterpret_cast<uintptr_t>(out) % 16 == 0) && ((N * esz) % 16 == 0);
+    hipLaunchKernelGGL((linear_gemm_2bit<kFM, kFN>), dim3((unsigned)(tiles_m * tiles_n), (unsigned)splits), dim3(kGemmThreads),
+                       gemm_lds_bytes(kFM), stream, xq, sx, static_cast<const uint4*>(packed), gamma, gstride, (int)M, N, K, Kq, RB,
+                       tiles_m, sps, out, ot, vec_store);
+    if (split) {
+        const int64_t quads = M * ceil_div(N, 4);
+        hipLaunchKernelGGL(gemm_splitk_reduce, dim3((unsigned)ceil_div(quads, 256)), dim3(256), 0, stream,
+                           static_cast<const int32_t*>(workspace), splits, sx, gamma, gstride, M, N, y, yt);
+    }
     return hipGetLastError();
 }
 
-// tile shape forced by the caller (tuning and tests); fm in 2 .. 4, fn in 1 .. 2
+// tile shape forced by the caller (tuning and tests); fm in 2 .. 4, fn in 1 .. 2; splits > 1: split-K through `workspace`
+// (splits * M * N int32)
 hipError_t launch_linear_gemm_2bit_shape(int fm, int fn, const int8_t* xq, const float* sx, const void* packed, const float* gamma,
-                                         int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
-#define GEMM_SHAPE(FM_, FN_) if (fm == FM_ && fn == FN_) return launch_gemm_tiles<FM_, FN_>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream)
+                                         int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream,
+                                         int splits, void* workspace) {
+#define GEMM_SHAPE(FM_, FN_) if (fm == FM_ && fn == FN_) return launch_gemm_tiles<FM_, FN_>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, splits, workspace)
     GEMM_SHAPE(2, 1); GEMM_SHAPE(3, 1); GEMM_SHAPE(4, 1); GEMM_SHAPE(2, 2); GEMM_SHAPE(3, 2); GEMM_SHAPE(4, 2);
 #undef GEMM_SHAPE
     return hipErrorInvalidValue;
 }
 
+size_t gemm_splitk_workspace_bytes(int64_t M, int64_t N, int splits) { return (size_t)splits * (size_t)M * (size_t)N * 4; }
+
 hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                    int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt,
-                                   hipStream_t stream) {
+                                   hipStream_t stream, void* workspace, size_t workspace_bytes, int force_splits) {
     // Tile shape (32 * fm tokens x 128 * fn weight rows) from a cost model fitted to measurements on MI355X
     // (nine LLaMA-family shapes, M = 65 ... 2048, every tile shape).  In microseconds, per K step of 256 columns:
     //   * a workgroup that has its CU to itself is latency bound and takes kAlone per step, a little more as the
@@ -401,22 +455,35 @@ hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void
     // Ties within 4 % go to the larger tile (less decode work and fewer activation re-reads per output).
     // Examples (13B o projection, N = K = 5120): M = 512 runs 96 x 128 tiles in 19.6 us (64 x 256: 23.6 us,
     // 128 x 256: 36 us); M = 128 runs 64 x 128 tiles in 15.2 us (22.9 us); M = 2048 stays on 96 x 256 tiles.
+    // With a workspace the K steps may also be split over 2, 4 or 8 workgroups per tile (each stores int32 partial
+    // accumulators, a second launch adds them and rescales): the same model with steps / splits per workgroup and
+    // tiles * splits workgroups, plus the second launch (a few microseconds and the partials' traffic).  It pays where
+    // even the smallest tiles leave CUs idle and K is long.
     struct Shape { int fm, fn; double alone, saturated, fixed; };
     static const Shape kShapes[6] = {{4, 2, 1.48, 1.45, 5.4}, {3, 2, 1.15, 1.10, 4.7}, {2, 2, 0.94, 0.74, 4.4},
                                      {4, 1, 0.94, 0.86, 3.5}, {3, 1, 0.715, 0.613, 3.4}, {2, 1, 0.594, 0.43, 3.2}};
-    const double steps = (double)ceil_div(K, 256);
-    int best = 0;
+    const int64_t steps_total = ceil_div(K, 256);
+    int best = 0, best_splits = 1;
     double best_cost = 0.0;
-    for (int c = 0; c < 6; ++c) {                       // largest tile first
-        const Shape& sh = kShapes[c];
-        const int64_t tiles = ceil_div(M, 32 * sh.fm) * ceil_div(N, 128 * sh.fn);
-        const double fill = (double)tiles / 256.0;
-        const double alone = sh.alone * (1.0 + 0.2 * (fill < 1.0 ? fill * fill : 1.0));
-        const double shared = (double)ceil_div(tiles, (int64_t)256) * sh.saturated;
-        const double cost = sh.fixed + steps * (alone > shared ? alone : shared);
-        if (c == 0 || cost < 0.96 * best_cost) { best = c; best_cost = cost; }
+    for (int sp = 1; sp <= 8; sp *= 2) {
+        if (force_splits > 0 && sp != force_splits) continue;
+        if (sp > 1 && (!workspace || workspace_bytes < gemm_splitk_workspace_bytes(M, N, sp) || sp > steps_total)) continue;
+        const double steps = (double)ceil_div(steps_total, (int64_t)sp);
+        const double second = sp > 1 ? 4.5 + (double)(sp + 1) * (double)M * (double)N * 4.0 / 3.0e6 : 0.0;   // launch + partials at 3 TB/s
+        for (int c = 0; c < 6; ++c) {                   // largest tile first
+            const Shape& sh = kShapes[c];
+            const int64_t tiles = ceil_div(M, 32 * sh.fm) * ceil_div(N, 128 * sh.fn) * sp;
+            const double fill = (double)tiles / 256.0;
+            const double alone = sh.alone * (1.0 + 0.2 * (fill < 1.0 ? fill * fill : 1.0));
+            const double shared = (double)ceil_div(tiles, (int64_t)256) * sh.saturated;
+            const double cost = sh.fixed + steps * (alone > shared ? alone : shared) + second;
+            if ((sp == 1 && c == 0) || (force_splits > 0 && sp == force_splits && c == 0) || cost < 0.96 * best_cost) {
+                best = c; best_splits = sp; best_cost = cost;
+            }
+        }
     }
-    return launch_linear_gemm_2bit_shape(kShapes[best].fm, kShapes[best].fn, xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream);
+    return launch_linear_gemm_2bit_shape(kShapes[best].fm, kShapes[best].fn, xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream,
+                                         best_splits, workspace);
 }
 
 }  // namespace bitnet

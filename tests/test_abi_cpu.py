@@ -94,6 +94,18 @@ def test_host_validation_rejects_before_launch():
     assert lib.bitnet_swiglu_linear_fused(a, 0, a, a, 1, 16, 64, 1, a, 0, NULL) == 4
     assert lib.bitnet_swiglu_linear_fused(a, 0, odd, a, 1, 16, 64, 0, a, 0, NULL) == 5
     assert lib.bitnet_swiglu_linear_fused(a, 0, a, a, 17, 16, 64, 0, a, 0, NULL) == 8
+    szp = ctypes.c_size_t(7)
+    assert lib.bitnet_linear_workspace(128, 4096, 11008, None) == 1
+    assert lib.bitnet_linear_workspace(128, 4096, 11008, ctypes.byref(szp)) == 0 and szp.value == 8 * 128 * 4096 * 4
+    assert lib.bitnet_linear_workspace(64, 4096, 11008, ctypes.byref(szp)) == 0 and szp.value == 0
+    assert lib.bitnet_linear_workspace(2048, 27648, 5120, ctypes.byref(szp)) == 0 and szp.value == 0
+    assert lib.bitnet_linear_workspace(0, 4096, 11008, ctypes.byref(szp)) == 2
+    assert lib.bitnet_linear_ws(a, a, a, NULL, 0, 128, 256, 512, 0, a, 0, 0, a, 1 << 20, NULL) == 1
+    assert lib.bitnet_linear_ws(a, a, a, a, 0, 128, 256, 512, 0, a, 0, 0, odd, 1 << 20, NULL) == 5
+    assert lib.bitnet_linear_ws(a, a, a, a, 0, 128, 256, 512, 0, a, 0, 0x203, a, 1 << 20, NULL) == 8        # 3 splits: no such variant
+    assert lib.bitnet_linear_ws(a, a, a, a, 0, 128, 256, 512, 0, a, 0, 0x204, a, 1 << 20, NULL) == 6        # 2 K steps, 4 splits
+    assert lib.bitnet_linear_ws(a, a, a, a, 0, 128, 256, 512, 0, a, 0, 0x202, a, 1024, NULL) == 6           # buffer too small
+    assert lib.bitnet_linear_ws(a, a, a, a, 0, 128, 256, 512, 1, a, 0, 0x202, a, 1 << 20, NULL) == 8        # 5-trit format
     assert lib.bitnet_ffn_gate_up_fused(a, 0, 0, NULL, 0.0, a, NULL, 0, 1, 16, 64, 0, a, 0, NULL) == 1
     assert lib.bitnet_ffn_gate_up_fused(a, 0, 0, NULL, 0.0, a, a, 0, 1, 24, 64, 0, a, 0, NULL) == 2          # F % 16
     assert lib.bitnet_ffn_gate_up_fused(a, 0, 1, NULL, -1.0, a, a, 0, 1, 16, 64, 0, a, 0, NULL) == 2         # eps < 0 with norm

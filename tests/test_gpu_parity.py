@@ -472,6 +472,60 @@ def test_linear_gemm_every_tile_shape(gpu_lib, tile):
         _run_linear_case(gpu_lib, M, N, K, [kern], layer=(M + tile[0] + tile[1]) % 11, bf16_acts=(M % 2 == 1))
 
 
+# split-K through a workspace: every split count on ragged shapes (K steps not divisible by the splits, a partial last
+# step, fewer steps than splits rejected), per-block scales, and the automatic choice on a shape where it pays
+@pytest.mark.parametrize("M,N,K", [(100, 300, 2064), (129, 520, 4112), (65, 40, 528), (300, 1000, 1040)])
+def test_linear_splitk_matches_reference(gpu_lib, M, N, K):
+    say("split-K M=%d N=%d K=%d" % (M, N, K))
+    W = synth.weights(N, K, config=0, layer=M % 7, tensor=15)
+    x = synth.activations(M, K, config=0, layer=M % 7, tensor=16)
+    packed, gamma = gpu_lib.quantize_weights(dev(W))
+    xq, sx = gpu_lib.quantize_acts(dev(x))
+    ws = torch.full((8 * M * N * 4 + 64,), 0xCD, dtype=torch.uint8, device="cuda")
+    for dt in (gpu_lib.I32, gpu_lib.F32, gpu_lib.BF16):
+        ref = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=dt, kernel=gpu_lib.KERNEL_REFERENCE)
+        for splits, code in gpu_lib.KERNEL_GEMM_SPLITK.items():
+            if splits > (K + 255) // 256:
+                with pytest.raises(gpu_lib.BitnetError) as e:
+                    gpu_lib.linear_ws(xq, sx, packed, gamma, N, ws[: 8 * M * N * 4], y_dtype=dt, kernel=code)
+                assert e.value.status == 6
+                continue
+            got = gpu_lib.linear_ws(xq, sx, packed, gamma, N, ws[: 8 * M * N * 4], y_dtype=dt, kernel=code)
+            assert torch.equal(got, ref)
+        assert torch.equal(gpu_lib.linear_ws(xq, sx, packed, gamma, N, ws[: 8 * M * N * 4], y_dtype=dt), ref)
+        assert torch.equal(gpu_lib.linear_ws(xq, sx, packed, gamma, N, None, y_dtype=dt), ref)
+    assert bool((ws[8 * M * N * 4:] == 0xCD).all())                     # nothing written past the stated size
+    with pytest.raises(gpu_lib.BitnetError) as e:                       # too small for the forced split
+        gpu_lib.linear_ws(xq, sx, packed, gamma, N, ws[: 2 * M * N * 4 - 16], kernel=gpu_lib.KERNEL_GEMM_SPLITK[2])
+    assert e.value.status == 6
+    # the oracle on the integer result once
+    ref = oracle.bitlinear(x, W)
+    acc = gpu_lib.linear_ws(xq, sx, packed, gamma, N, ws[: 8 * M * N * 4], y_dtype=gpu_lib.I32, kernel=gpu_lib.KERNEL_GEMM_SPLITK[2])
+    assert np.array_equal(acc.cpu().numpy(), ref["acc"])
+
+
+def test_linear_splitk_auto_and_segment_scales(gpu_lib):
+    say("split-K: automatic choice, per-block scales, workspace query")
+    M, N, K = 128, 4096, 11008                           # 64 tiles of 64 x 128 and 43 K steps: the model splits
+    assert gpu_lib.linear_workspace(M, N, K) == 8 * M * N * 4
+    assert gpu_lib.linear_workspace(64, N, K) == 0 and gpu_lib.linear_workspace(2048, 27648, 5120) == 0
+    W = synth.weights(N, K, config=2, layer=1, tensor=3)
+    W[2048:] *= np.float32(0.5)
+    x, bits = synth.activations(M, K, config=2, layer=1, tensor=103, bf16=True)
+    packed, gamma_rb = gpu_lib.quantize_weights_segmented(dev(W), [2048, 2048])
+    xq, sx = gpu_lib.quantize_acts(bf16_tensor(bits).view(M, K))
+    ws = torch.empty(gpu_lib.linear_workspace(M, N, K), dtype=torch.uint8, device="cuda")
+    ref = gpu_lib.linear_segmented(xq, sx, packed, gamma_rb, N, y_dtype=gpu_lib.BF16)
+    got = gpu_lib.linear_ws(xq, sx, packed, gamma_rb, N, ws, y_dtype=gpu_lib.BF16, gamma_per_block=True)
+    assert torch.equal(got, ref)
+    accr = gpu_lib.linear_segmented(xq, sx, packed, gamma_rb, N, y_dtype=gpu_lib.I32, kernel=gpu_lib.KERNEL_REFERENCE)
+    assert torch.equal(gpu_lib.linear_ws(xq, sx, packed, gamma_rb, N, ws, y_dtype=gpu_lib.I32, gamma_per_block=True), accr)
+    # decode shapes ignore the workspace
+    xq1, sx1 = xq[:8].contiguous(), sx[:8].contiguous()
+    assert torch.equal(gpu_lib.linear_ws(xq1, sx1, packed, gamma_rb, N, ws, gamma_per_block=True),
+                       gpu_lib.linear_segmented(xq1, sx1, packed, gamma_rb, N))
+
+
 def test_linear_gemm_small_m_and_forced_on_decode_shapes(gpu_lib):
     say("linear gemm forced at small M")
     _run_linear_case(gpu_lib, 1, 100, 80, [gpu_lib.KERNEL_GEMM], layer=2)
