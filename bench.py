@@ -238,8 +238,8 @@ def format_leg(torch, B, synth, gen, stream, args):
 
 
 def batched_decode_leg(torch, B, synth, gen, stream, args):
-    """The transition between decode and prefill: M = 1 ... 64 tokens on the 7B-class shapes, bitnet_linear on
-    pre-quantized activations, each shape replayed over enough distinct layers to exceed the memory-side
+    """The transition between decode and prefill: M = 1 ... 64 tokens (and 128, the first prefill-kernel size) on the
+    7B-class shapes, bitnet_linear on pre-quantized activations, each shape replayed over enough distinct layers to exceed the memory-side
     cache.  Both rooflines are reported because M = 64 sits near the ridge between them."""
     res = {}
     for (name, K, N) in synth.CONFIGS[2]["shapes"]:
@@ -266,6 +266,27 @@ def batched_decode_leg(torch, B, synth, gen, stream, args):
                                  "GB/s": round(gemv_bytes(M, N, K) / (us * 1e-6) / 1e9, 1),
                                  "TOPS": round(2.0 * M * N * K / us * 1e-6, 1)}
             del graph
+        # the serving regime just above the decode kernels: 128 tokens through the prefill kernel, without and with
+        # a split-K workspace (bitnet_linear_ws)
+        M = 128
+        x = make_acts(torch, M, K, gen, 2)
+        xq, sx = B.quantize_acts(x)
+        y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        ws = torch.empty(max(16, B.linear_workspace(M, N, K)), dtype=torch.uint8, device="cuda")
+
+        def run_plain():
+            for (p, g) in packs:
+                B.linear(xq, sx, p, g, N, y_dtype=B.BF16, y=y)
+
+        def run_ws():
+            for (p, g) in packs:
+                B.linear_ws(xq, sx, p, g, N, ws, y_dtype=B.BF16, y=y)
+
+        ms_p, _, g1 = time_graph(torch, run_plain, max(2, args.warmup // 5), max(5, args.steps // 5), stream)
+        ms_w, _, g2 = time_graph(torch, run_ws, max(2, args.warmup // 5), max(5, args.steps // 5), stream)
+        entry["M=128"] = {"us_per_launch": round(ms_p * 1e3 / layers, 2), "us_with_workspace": round(ms_w * 1e3 / layers, 2),
+                          "TOPS": round(2.0 * M * N * K / (min(ms_p, ms_w) * 1e3 / layers) * 1e-6, 1)}
+        del g1, g2
         res[name] = entry
         del packs
         torch.cuda.empty_cache()
