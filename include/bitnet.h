@@ -18,8 +18,9 @@
  *   - Matrices are row-major: W [N][K], x and x_q [M][K], y [M][N]  (y = x . W^T, the orientation of
  *     a linear layer's weight).
  *   - Every data pointer is DEVICE memory owned by the caller, unless marked (host).  The library
- *     allocates nothing and keeps no state.  Inputs are never written; outputs are fully
- *     overwritten.  gamma and s_x stay on the device, so no call synchronizes with the host.
+ *     allocates nothing and keeps no state between calls (beyond raising, once per device, the
+ *     dynamic-LDS limit of the kernels that need it).  Inputs are never written; outputs are fully
+ *     overwritten; workspaces are scratch.  gamma and s_x stay on the device, so no call synchronizes with the host.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are asynchronous
  *     on that stream and may be captured into a HIP graph.
  *   - Arguments are validated on the host before anything is launched; on any error nothing has been
