@@ -203,9 +203,12 @@ bitnet_status bitnet_linear(const int8_t* xq, const float* sx, const void* packe
 bitnet_status bitnet_linear_workspace(int64_t M, int64_t N, int64_t K, size_t* bytes) {
     if (!bytes) return BITNET_ERR_NULL;
     if (!shape_ok(M, N, K)) return BITNET_ERR_SHAPE;
-    // split-K is considered only where even 64 x 128 tiles leave workgroup slots empty (fewer than 512 of them)
+    // prefill kernel: split-K is considered only where even 64 x 128 tiles leave workgroup slots empty (fewer than
+    // 512 of them); batched-decode kernels: 2 or 4 splits at 33 ... 64 tokens on layers with few rows and a long K
     const int64_t tiles = ((M + 63) / 64) * ((N + 127) / 128);
-    *bytes = (M > 64 && tiles < 512) ? bitnet::gemm_splitk_workspace_bytes(M, N, 8) : 0;
+    const int skinny_splits = bitnet::skinny_splitk_splits(M, N, K);
+    if (M > 64) *bytes = tiles < 512 ? bitnet::splitk_workspace_bytes(M, N, 8) : 0;
+    else *bytes = skinny_splits > 1 ? bitnet::splitk_workspace_bytes(M, N, skinny_splits) : 0;
     return BITNET_OK;
 }
 
@@ -224,16 +227,24 @@ bitnet_status bitnet_linear_ws(const int8_t* xq, const float* sx, const void* pa
     if (!xq || !sx || !packed || !gamma || !y) return BITNET_ERR_NULL;
     if (!shape_ok(M, N, K)) return BITNET_ERR_SHAPE;
     if (workspace && !aligned(workspace, 16)) return BITNET_ERR_ALIGN;
-    const bool gemm_path = f == BITNET_PACK_2BIT && (force || !bitnet::gemv_supports(M, N, K, xq)) && bitnet::gemm_supports(M, N, K, xq);
-    if (!gemm_path) {
+    // a forced split runs on the kernel family the automatic choice would take for this M: the batched-decode
+    // kernels at 5 ... 64 tokens, the prefill kernel otherwise (the M <= 4 decode kernel has no split form)
+    const bool skinny_path = f == BITNET_PACK_2BIT && M > 4 && bitnet::gemv_supports(M, N, K, xq) &&
+                             (force || (workspace && bitnet::skinny_splitk_splits(M, N, K) > 1));
+    const bool gemm_path = f == BITNET_PACK_2BIT && !skinny_path && (force || !bitnet::gemv_supports(M, N, K, xq)) &&
+                           bitnet::gemm_supports(M, N, K, xq);
+    if (!gemm_path && !skinny_path) {
         if (force) return BITNET_ERR_KERNEL;
         return linear_any(xq, sx, packed, gamma, gstride, M, N, K, f, y, y_dtype, BITNET_KERNEL_AUTO, stream);
     }
     OutType yt;
     if (!out_type(y_dtype, &yt)) return BITNET_ERR_DTYPE;
     if (!aligned(packed, 16) || !aligned(sx, 4) || !aligned(gamma, 4) || !aligned(y, dtype_size(y_dtype))) return BITNET_ERR_ALIGN;
-    if (force && (!workspace || workspace_bytes < bitnet::gemm_splitk_workspace_bytes(M, N, force) || force > (K + 255) / 256))
+    if (force && (!workspace || workspace_bytes < bitnet::splitk_workspace_bytes(M, N, force) || force > (K + 255) / 256))
         return BITNET_ERR_WORKSPACE;
+    if (skinny_path)
+        return from_hip(bitnet::launch_linear_gemv_2bit(xq, sx, packed, gamma, gstride, M, N, K, y, yt, static_cast<hipStream_t>(stream),
+                                                        workspace, workspace ? workspace_bytes : 0, force));
     return from_hip(bitnet::launch_linear_gemm_2bit(xq, sx, packed, gamma, gstride, M, N, K, y, yt, static_cast<hipStream_t>(stream),
                                                     workspace, workspace ? workspace_bytes : 0, force));
 }

@@ -51,9 +51,12 @@ hipError_t launch_unpack_2bit(const void* packed, int64_t N, int64_t K, int8_t* 
 
 // linear_gemv.hip
 bool gemv_supports(int64_t M, int64_t N, int64_t K, const void* xq);
-hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void* packed,
-                                   const float* gamma, int gstride, int64_t M, int64_t N, int64_t K, void* y,
-                                   OutType yt, hipStream_t stream);
+// workspace (may be null) and force_splits as for launch_linear_gemm_2bit: split-K of the batched-decode kernels
+// (4 < M <= 64), taken by itself where skinny_splitk_splits() > 1 and the workspace holds that many partials
+int skinny_splitk_splits(int64_t M, int64_t N, int64_t K);
+hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
+                                   int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream,
+                                   void* workspace = nullptr, size_t workspace_bytes = 0, int force_splits = 0);
 // the M <= 16 kernel alone (linear_gemv.hip); launch_linear_gemv_2bit (linear_skinny.hip) routes M <= 4 to it
 hipError_t launch_linear_gemv16_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma, int gstride,
                                      int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);
@@ -81,11 +84,16 @@ hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void
                                    hipStream_t stream, void* workspace = nullptr, size_t workspace_bytes = 0,
                                    int force_splits = 0);
 // the same with the tile forced: 32 * fm tokens x 128 * fn weight rows, fm in 2 .. 4, fn in 1 .. 2 (hipErrorInvalidValue
-// otherwise); splits > 1 needs a workspace of gemm_splitk_workspace_bytes(M, N, splits)
+// otherwise); splits > 1 needs a workspace of splitk_workspace_bytes(M, N, splits)
 hipError_t launch_linear_gemm_2bit_shape(int fm, int fn, const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                          int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream,
                                          int splits = 1, void* workspace = nullptr);
-size_t gemm_splitk_workspace_bytes(int64_t M, int64_t N, int splits);
+size_t splitk_workspace_bytes(int64_t M, int64_t N, int splits);
+// split-K, second launch: y = (sum of `splits` int32 partial accumulators, [M][N] each) * gamma * s_x / 127;
+// prefill_assoc: the association of the prefill kernel's per-block-gamma epilogue (gamma * (s_x / 127)) instead of
+// the decode kernels' ((gamma * s_x) / 127)
+hipError_t launch_splitk_reduce(const int32_t* part, int splits, const float* sx, const float* gamma, int gstride,
+                                int prefill_assoc, int64_t M, int64_t N, void* y, OutType yt, hipStream_t stream);
 
 // trit5.hip
 hipError_t launch_pack_trit5(const void* W, bool bf16, int64_t N, int64_t K, const float* gamma, void* packed,

@@ -364,8 +364,8 @@ __global__ __launch_bounds__(kGemmThreads, gemm_blocks_per_cu(kFM, kFN)) void li
 // split-K, second kernel: y[m][n] = (sum over the splits of the partial accumulators) * gamma * s_x[m] / 127, four
 // consecutive outputs per thread.  Integer sums: exact and independent of the number of splits.
 __global__ __launch_bounds__(256) void gemm_splitk_reduce(const int32_t* __restrict__ part, int splits, const float* __restrict__ sx,
-                                                          const float* __restrict__ gamma, int gstride, int64_t M, int64_t N,
-                                                          void* __restrict__ y, OutType yt) {
+                                                          const float* __restrict__ gamma, int gstride, int prefill_assoc,
+                                                          int64_t M, int64_t N, void* __restrict__ y, OutType yt) {
     const int64_t quads_per_row = (N + 3) >> 2;
     const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (q >= M * quads_per_row) return;
@@ -383,12 +383,23 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce(const int32_t* __restr
         if (n0 + e >= N) continue;
         const int64_t o = m * N + n0 + e;
         if (yt == OutType::I32) { static_cast<int32_t*>(y)[o] = acc[e]; continue; }
-        // the same association as the one-launch epilogue, so that splitting never changes a bit of the output
-        const float scale = gstride ? gamma[(n0 + e) / kRowsPerBlock] * (sxm / kQb) : (gamma[0] * sxm) / kQb;
+        // the same association as the one-launch epilogue of the kernel that wrote the partials (the prefill kernel
+        // with per-block gamma: gamma * (s_x / 127); otherwise (gamma * s_x) / 127), so that splitting never changes
+        // a bit of the output
+        const float gm = gamma[gstride ? (n0 + e) / kRowsPerBlock : 0];
+        const float scale = (gstride && prefill_assoc) ? gm * (sxm / kQb) : (gm * sxm) / kQb;
         const float v = (float)acc[e] * scale;
         if (yt == OutType::F32) static_cast<float*>(y)[o] = v;
         else static_cast<uint16_t*>(y)[o] = f32_to_bf16(v);
     }
+}
+
+hipError_t launch_splitk_reduce(const int32_t* part, int splits, const float* sx, const float* gamma, int gstride,
+                                int prefill_assoc, int64_t M, int64_t N, void* y, OutType yt, hipStream_t stream) {
+    const int64_t quads = M * ceil_div(N, 4);
+    hipLaunchKernelGGL(gemm_splitk_reduce, dim3((unsigned)ceil_div(quads, 256)), dim3(256), 0, stream, part, splits, sx, gamma,
+                       gstride, prefill_assoc, M, N, y, yt);
+    return hipGetLastError();
 }
 
 bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
@@ -420,11 +431,8 @@ static hipError_t launch_gemm_tiles(const int8_t* xq, const float* sx, const voi
     hipLaunchKernelGGL((linear_gemm_2bit<kFM, kFN>), dim3((unsigned)(tiles_m * tiles_n), (unsigned)splits), dim3(kGemmThreads),
                        gemm_lds_bytes(kFM), stream, xq, sx, static_cast<const uint4*>(packed), gamma, gstride, (int)M, N, K, Kq, RB,
                        tiles_m, sps, out, ot, vec_store);
-    if (split) {
-        const int64_t quads = M * ceil_div(N, 4);
-        hipLaunchKernelGGL(gemm_splitk_reduce, dim3((unsigned)ceil_div(quads, 256)), dim3(256), 0, stream,
-                           static_cast<const int32_t*>(workspace), splits, sx, gamma, gstride, M, N, y, yt);
-    }
+    if (split)
+        return launch_splitk_reduce(static_cast<const int32_t*>(workspace), splits, sx, gamma, gstride, 1, M, N, y, yt, stream);
     return hipGetLastError();
 }
 
@@ -439,7 +447,7 @@ hipError_t launch_linear_gemm_2bit_shape(int fm, int fn, const int8_t* xq, const
     return hipErrorInvalidValue;
 }
 
-size_t gemm_splitk_workspace_bytes(int64_t M, int64_t N, int splits) { return (size_t)splits * (size_t)M * (size_t)N * 4; }
+size_t splitk_workspace_bytes(int64_t M, int64_t N, int splits) { return (size_t)splits * (size_t)M * (size_t)N * 4; }
 
 hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                    int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt,
@@ -467,7 +475,7 @@ hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void
     double best_cost = 0.0;
     for (int sp = 1; sp <= 8; sp *= 2) {
         if (force_splits > 0 && sp != force_splits) continue;
-        if (sp > 1 && (!workspace || workspace_bytes < gemm_splitk_workspace_bytes(M, N, sp) || sp > steps_total)) continue;
+        if (sp > 1 && (!workspace || workspace_bytes < splitk_workspace_bytes(M, N, sp) || sp > steps_total)) continue;
         const double steps = (double)ceil_div(steps_total, (int64_t)sp);
         const double second = sp > 1 ? 4.5 + (double)(sp + 1) * (double)M * (double)N * 4.0 / 3.0e6 : 0.0;   // launch + partials at 3 TB/s
         for (int c = 0; c < 6; ++c) {                   // largest tile first

@@ -34,7 +34,9 @@ template <int kMT, int kR, int kW, int kS, int kD, int kLx>
 __global__ __launch_bounds__(kS * kW * kWave) void linear_skinny_2bit(
         const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
         const float* __restrict__ gamma, int gstride, int M, int64_t N, int64_t K, int Kq, int RB, int spg,
-        void* __restrict__ y, OutType yt) {
+        int steps_per_split /* blockIdx.y selects a run of K steps (split-K: int32 partials, [M][N] each, one after the
+                               other at yv); one split: all steps */,
+        void* __restrict__ yv, OutType yt) {
 #if defined(__HIP_DEVICE_COMPILE__)      // the buffer-resource builtins exist in the device pass only
     extern __shared__ uint4 smem[];
     constexpr int kRing = kLx + 1;                     // LDS stages per group
@@ -55,8 +57,10 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_skinny_2bit(
     const int r = lane & 15, g = lane >> 4;
     const int steps = (Kq + 3) >> 2;
     const int tail_quads = 16 * (Kq - 4 * (steps - 1));
-    const int s_begin = ks * spg;                                      // this group's steps: s_begin + [0, n_here)
-    const int n_here = max(0, min(spg, steps - s_begin));
+    const int step0 = blockIdx.y * steps_per_split, step1 = min(steps, step0 + steps_per_split);
+    void* y = static_cast<char*>(yv) + (int64_t)blockIdx.y * M * N * 4;
+    const int s_begin = step0 + ks * spg;                              // this group's steps: s_begin + [0, n_here)
+    const int n_here = max(0, min(spg, step1 - s_begin));
     const int rbw = (blockIdx.x * kW + wv) * kR;
     const int64_t wstride = (int64_t)RB * 64;
     char* glds = lds + ks * kGroupBytes;
@@ -149,6 +153,7 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_skinny_2bit(
         constexpr int kLead = kD - kLx;
         const int xs = p >= kLead ? p - kLead : 0;
         copy_x(xs, xs % kRing);
+        issue_fence();                                                 // the counted wait relies on this issue order
         load_w(wst[p], p);
         issue_fence();
     }
@@ -169,6 +174,7 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_skinny_2bit(
             __builtin_amdgcn_s_barrier();                              // stage i is complete, stage i - 1 is free
             issue_fence();
             copy_x(i + kLx, (i + kLx) % kRing);
+            issue_fence();                                             // copies first: the wait above counts on it
             compute(wst[d], i, i % kRing);
             load_w(wst[d], i + kD);                                    // after the last use: reloaded in place
         }
@@ -228,7 +234,7 @@ template <int kMT, int kR, int kW, int kS, int kD, int kLx>
 __global__ __launch_bounds__((kS * kW + 1) * kWave) void linear_skinny_ws_2bit(
         const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
         const float* __restrict__ gamma, int gstride, int M, int64_t N, int64_t K, int Kq, int RB, int spg,
-        void* __restrict__ y, OutType yt) {
+        int steps_per_split /* as in linear_skinny_2bit */, void* __restrict__ yv, OutType yt) {
 #if defined(__HIP_DEVICE_COMPILE__)      // the buffer-resource builtins exist in the device pass only
     extern __shared__ uint4 smem[];
     constexpr int kRing = kLx + 1;                     // LDS stages per group
@@ -246,6 +252,8 @@ __global__ __launch_bounds__((kS * kW + 1) * kWave) void linear_skinny_ws_2bit(
     const int steps = (Kq + 3) >> 2;
     const int tail_quads = 16 * (Kq - 4 * (steps - 1));
     const int padded = (spg + kD - 1) / kD * kD;       // barriers per wave: the same for both roles
+    const int step0 = blockIdx.y * steps_per_split, step1 = min(steps, step0 + steps_per_split);
+    void* y = static_cast<char*>(yv) + (int64_t)blockIdx.y * M * N * 4;
 
     v4i acc[kR][kMT];
 #pragma unroll
@@ -269,7 +277,7 @@ __global__ __launch_bounds__((kS * kW + 1) * kWave) void linear_skinny_ws_2bit(
         auto copy_x = [&](int i, int stage) {                          // local step i of every group
 #pragma unroll
             for (int q = 0; q < kS; ++q) {
-                const uint32_t col = (uint32_t)(q * spg + i) * 256u;
+                const uint32_t col = (uint32_t)(step0 + q * spg + i) * 256u;
 #pragma unroll
                 for (int t = 0; t < kCopies; ++t)
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(
@@ -292,8 +300,8 @@ __global__ __launch_bounds__((kS * kW + 1) * kWave) void linear_skinny_ws_2bit(
         ks = wave / kW;
         wv = wave - ks * kW;
         rbw = (blockIdx.x * kW + wv) * kR;
-        const int s_begin = ks * spg;                                  // this group's steps: s_begin + [0, n_here)
-        const int n_here = max(0, min(spg, steps - s_begin));
+        const int s_begin = step0 + ks * spg;                          // this group's steps: s_begin + [0, n_here)
+        const int n_here = max(0, min(spg, step1 - s_begin));
         const int64_t wstride = (int64_t)RB * 64;
         const char* glds = lds + ks * kGroupBytes;
         int rbc[kR];
@@ -405,7 +413,8 @@ bool gemv_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
 
 template <int kMT, int kR, int kW, int kS, int kD, int kLx>
 static hipError_t launch_skinny(const int8_t* xq, const float* sx, const void* packed, const float* gamma, int gstride,
-                                int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
+                                int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream,
+                               int splits, void* workspace) {
     constexpr size_t lds = (size_t)kS * (kLx + 1) * kMT * 16 * 256;
     static_assert(lds <= 160 * 1024, "activation rings must fit the LDS of a CU");
     static_assert(kS * kW <= 16, "at most 1024 threads per workgroup");
@@ -417,16 +426,24 @@ static hipError_t launch_skinny(const int8_t* xq, const float* sx, const void* p
     }
     const int Kq = (int)ceil_div(K, kColsPerQuad);
     const int RB = (int)ceil_div(N, kRowsPerBlock);
-    const int spg = (int)ceil_div(ceil_div(K, 256), kS);
-    dim3 grid((unsigned)ceil_div(RB, kW * kR));
+    const int steps = (int)ceil_div(K, 256);
+    if (splits > steps) splits = steps;
+    const int sps = (int)ceil_div(steps, splits);
+    splits = (int)ceil_div(steps, sps);                 // no empty split
+    const int spg = (int)ceil_div(sps, kS);
+    const bool split = splits > 1;                      // then int32 partials go to the workspace and a second launch adds them
+    dim3 grid((unsigned)ceil_div(RB, kW * kR), (unsigned)splits);
     hipLaunchKernelGGL(kern, grid, dim3(kS * kW * kWave), lds, stream, xq, sx, static_cast<const uint4*>(packed), gamma,
-                       gstride, (int)M, N, K, Kq, RB, spg, y, yt);
+                       gstride, (int)M, N, K, Kq, RB, spg, sps, split ? workspace : y, split ? OutType::I32 : yt);
+    if (split)
+        return launch_splitk_reduce(static_cast<const int32_t*>(workspace), splits, sx, gamma, gstride, 0, M, N, y, yt, stream);
     return hipGetLastError();
 }
 
 template <int kMT, int kR, int kW, int kS, int kD, int kLx>
 static hipError_t launch_skinny_ws(const int8_t* xq, const float* sx, const void* packed, const float* gamma, int gstride,
-                                   int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
+                                   int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream,
+                                  int splits, void* workspace) {
     constexpr size_t lds = (size_t)kS * (kLx + 1) * kMT * 16 * 256;
     static_assert(lds <= 160 * 1024, "activation rings must fit the LDS of a CU");
     static_assert(kS * kW + 1 <= 16, "at most 1024 threads per workgroup");
@@ -438,15 +455,34 @@ static hipError_t launch_skinny_ws(const int8_t* xq, const float* sx, const void
     }
     const int Kq = (int)ceil_div(K, kColsPerQuad);
     const int RB = (int)ceil_div(N, kRowsPerBlock);
-    const int spg = (int)ceil_div(ceil_div(K, 256), kS);
-    dim3 grid((unsigned)ceil_div(RB, kW * kR));
+    const int steps = (int)ceil_div(K, 256);
+    if (splits > steps) splits = steps;
+    const int sps = (int)ceil_div(steps, splits);
+    splits = (int)ceil_div(steps, sps);                 // no empty split
+    const int spg = (int)ceil_div(sps, kS);
+    const bool split = splits > 1;                      // then int32 partials go to the workspace and a second launch adds them
+    dim3 grid((unsigned)ceil_div(RB, kW * kR), (unsigned)splits);
     hipLaunchKernelGGL(kern, grid, dim3((kS * kW + 1) * kWave), lds, stream, xq, sx, static_cast<const uint4*>(packed), gamma,
-                       gstride, (int)M, N, K, Kq, RB, spg, y, yt);
+                       gstride, (int)M, N, K, Kq, RB, spg, sps, split ? workspace : y, split ? OutType::I32 : yt);
+    if (split)
+        return launch_splitk_reduce(static_cast<const int32_t*>(workspace), splits, sx, gamma, gstride, 0, M, N, y, yt, stream);
     return hipGetLastError();
 }
+// Split-K of the batched-decode kernels, taken when the caller provides a workspace.  With few row blocks every
+// workgroup pulls all of x_q through its LDS with one K step of lookahead, and that latency chain, not HBM, sets the
+// time; splitting K over workgroups shortens the chain at the price of a second launch that adds the int32 partials.
+// Measured on MI355X it pays from 33 tokens on, for K >= 16384 and at most 512 row blocks (LLaMA-30B / 70B down
+// projections: 24.8 -> 22.6 us and 37.9 -> 33.8 us at 64 tokens; N = 4096, K = 22016: 29.1 -> 21.5 us).
+int skinny_splitk_splits(int64_t M, int64_t N, int64_t K) {
+    const int64_t RB = ceil_div(N, kRowsPerBlock);
+    if (M <= 32 || M > 64 || RB > 512 || K < 16384) return 1;
+    return RB <= 256 ? 4 : 2;
+}
+
 hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void* packed,
                                    const float* gamma, int gstride, int64_t M, int64_t N, int64_t K, void* y,
-                                   OutType yt, hipStream_t stream) {
+                                   OutType yt, hipStream_t stream, void* workspace, size_t workspace_bytes,
+                                   int force_splits) {
     if (M <= 4) return launch_linear_gemv16_2bit(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream);
     // More than four tokens: the activations of a step outweigh the weights a wave reads with them, so they
     // are staged once per group of waves (skinny kernel), 16 * kMT >= M tokens per step.  From sweeps on
@@ -454,24 +490,40 @@ hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void
     // per workgroup (kW * kR) follow N; with few row blocks the waves split K further instead.  Two steps
     // of prefetch were best throughout.
     const int64_t RB = ceil_div(N, kRowsPerBlock);
-#define SKINNY(...) return launch_skinny<__VA_ARGS__>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream)
-#define SKINNY_WS(...) return launch_skinny_ws<__VA_ARGS__>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream)
+    int splits = 1;
+    if (force_splits > 0) splits = force_splits;
+    else if (workspace && workspace_bytes >= splitk_workspace_bytes(M, N, skinny_splitk_splits(M, N, K)))
+        splits = skinny_splitk_splits(M, N, K);
+    // a split leaves each workgroup 1 / splits of K, so it can own that many more row blocks at the same running time:
+    // the kernel form is chosen as for a layer with splits times the rows (fewer, larger workgroups that each stage
+    // a fraction of x_q, instead of every workgroup staging all of it)
+    const int64_t RBc = RB * splits;
+#define SKINNY(...) \
+    return launch_skinny<__VA_ARGS__>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, splits, workspace)
+#define SKINNY_WS(...) \
+    return launch_skinny_ws<__VA_ARGS__>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, splits, workspace)
+    // The workgroups of a launch should fit the chip at once: 256 CUs times the workgroups whose activation rings
+    // fit the LDS of one (often a single one).  A few more than that and a second, nearly empty round doubles the
+    // time, so the row blocks per workgroup (kW * kR) step up with the row count.
     if (M <= 16) {
-        if (RB >= 2048)      SKINNY(1, 4, 4, 2, 2, 2);
-        else if (RB >= 1024) SKINNY(1, 3, 2, 4, 2, 2);
-        else if (RB >= 512)  SKINNY(1, 3, 1, 4, 2, 2);
-        else                 SKINNY(1, 1, 1, 8, 2, 2);
+        if (RBc >= 2048)      SKINNY(1, 4, 4, 2, 2, 2);
+        else if (RBc >= 1024) SKINNY(1, 3, 2, 4, 2, 2);
+        else if (RBc > 512)   SKINNY(1, 2, 2, 4, 2, 2);
+        else if (RBc > 256)   SKINNY(1, 1, 2, 8, 2, 2);
+        else                  SKINNY(1, 1, 1, 8, 2, 2);
     } else if (M <= 32) {
-        // from 1280 row blocks on, the form with a loader wave (weights 3 steps deep in flight per wave)
-        if (RB >= 2048)      SKINNY_WS(2, 4, 4, 1, 4, 3);
-        else if (RB >= 1280) SKINNY_WS(2, 2, 3, 2, 4, 3);
-        else if (RB >= 512)  SKINNY(2, 2, 2, 4, 2, 2);
-        else                 SKINNY(2, 1, 1, 4, 2, 2);
+        // from 1024 row blocks on, the form with a loader wave (weights 3 steps deep in flight per wave)
+        if (RBc >= 2048)      SKINNY_WS(2, 4, 4, 1, 4, 3);
+        else if (RBc >= 1024) SKINNY_WS(2, 2, 3, 2, 4, 3);
+        else if (RBc > 512)   SKINNY(2, 2, 2, 4, 2, 2);
+        else if (RBc > 256)   SKINNY(2, 1, 2, 4, 2, 2);
+        else                  SKINNY(2, 1, 1, 4, 2, 2);
     } else {
-        if (RB >= 2048)      SKINNY_WS(4, 4, 4, 1, 4, 2);
-        else if (RB >= 1280) SKINNY_WS(4, 2, 3, 1, 4, 2);
-        else if (RB >= 512)  SKINNY_WS(4, 2, 2, 2, 4, 2);
-        else                 SKINNY(4, 1, 1, 4, 2, 1);
+        if (RBc >= 2048)      SKINNY_WS(4, 4, 4, 1, 4, 2);
+        else if (RBc >= 1024) SKINNY_WS(4, 2, 3, 1, 4, 2);
+        else if (RBc >= 512)  SKINNY_WS(4, 2, 2, 2, 4, 2);
+        else if (RBc > 256)   SKINNY(4, 2, 1, 4, 2, 1);
+        else                  SKINNY(4, 1, 1, 4, 2, 1);
     }
 #undef SKINNY
 #undef SKINNY_WS

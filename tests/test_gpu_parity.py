@@ -504,11 +504,60 @@ def test_linear_splitk_matches_reference(gpu_lib, M, N, K):
     assert np.array_equal(acc.cpu().numpy(), ref["acc"])
 
 
+# split-K of the batched-decode kernels (5 ... 64 tokens): every split count, both kernel forms (with and without the
+# loader wave: N from 8192 / 20480 rows on), ragged K steps, per-block scales; bit-identical to the one-launch result
+@pytest.mark.parametrize("M,N,K", [(5, 300, 2064), (16, 1000, 1296), (17, 8200, 1040), (33, 520, 4112), (48, 20500, 784),
+                                   (64, 8208, 2320), (64, 40, 528), (40, 32784, 528)])
+def test_linear_splitk_batched_decode(gpu_lib, M, N, K):
+    say("split-K, batched decode M=%d N=%d K=%d" % (M, N, K))
+    W = synth.weights(N, K, config=0, layer=M % 5, tensor=17)
+    W[N // 32 * 16:] *= np.float32(0.25)
+    x = synth.activations(M, K, config=0, layer=M % 5, tensor=18)
+    packed, gamma = gpu_lib.quantize_weights(dev(W))
+    packed_rb, gamma_rb = gpu_lib.quantize_weights_segmented(dev(W), [N // 32 * 16, N - N // 32 * 16])
+    xq, sx = gpu_lib.quantize_acts(dev(x))
+    ws = torch.full((8 * M * N * 4 + 64,), 0xCD, dtype=torch.uint8, device="cuda")
+    for dt in (gpu_lib.I32, gpu_lib.F32, gpu_lib.BF16):
+        ref = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=dt)
+        ref_rb = gpu_lib.linear_segmented(xq, sx, packed_rb, gamma_rb, N, y_dtype=dt)
+        for splits, code in gpu_lib.KERNEL_GEMM_SPLITK.items():
+            if splits > (K + 255) // 256:
+                continue
+            assert torch.equal(gpu_lib.linear_ws(xq, sx, packed, gamma, N, ws[: 8 * M * N * 4], y_dtype=dt, kernel=code), ref)
+            assert torch.equal(gpu_lib.linear_ws(xq, sx, packed_rb, gamma_rb, N, ws[: 8 * M * N * 4], y_dtype=dt, kernel=code,
+                                                 gamma_per_block=True), ref_rb)
+    assert bool((ws[8 * M * N * 4:] == 0xCD).all())
+    acc = gpu_lib.linear_ws(xq, sx, packed, gamma, N, ws[: 8 * M * N * 4], y_dtype=gpu_lib.I32, kernel=gpu_lib.KERNEL_GEMM_SPLITK[2])
+    assert np.array_equal(acc.cpu().numpy(), oracle.bitlinear(x, W)["acc"])
+
+
+def test_linear_splitk_batched_decode_auto(gpu_lib):
+    say("split-K, batched decode: automatic choice and workspace query")
+    assert gpu_lib.linear_workspace(64, 4096, 22016) == 4 * 64 * 4096 * 4
+    assert gpu_lib.linear_workspace(48, 8192, 28672) == 2 * 48 * 8192 * 4
+    assert gpu_lib.linear_workspace(32, 4096, 22016) == 0 and gpu_lib.linear_workspace(64, 22016, 4096) == 0
+    assert gpu_lib.linear_workspace(64, 4096, 11008) == 0 and gpu_lib.linear_workspace(64, 8208, 28672) == 0
+    for (M, N, K, splits) in [(64, 2048, 16400, 4), (40, 4112, 16384, 2)]:
+        assert gpu_lib.linear_workspace(M, N, K) == splits * M * N * 4
+        W = synth.weights(N, K, config=2, layer=2, tensor=3)
+        x = synth.activations(M, K, config=2, layer=2, tensor=103)
+        packed, gamma = gpu_lib.quantize_weights(dev(W))
+        xq, sx = gpu_lib.quantize_acts(dev(x))
+        ws = torch.full((gpu_lib.linear_workspace(M, N, K),), 0, dtype=torch.uint8, device="cuda")
+        for dt in (gpu_lib.I32, gpu_lib.BF16):
+            ref = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=dt)
+            assert torch.equal(gpu_lib.linear_ws(xq, sx, packed, gamma, N, ws, y_dtype=dt), ref)
+            assert bool(ws.view(torch.int32)[-N:].any())                  # the last partial was written: the split ran
+            ws.zero_()
+            assert torch.equal(gpu_lib.linear_ws(xq, sx, packed, gamma, N, ws[:1024], y_dtype=dt), ref)   # too small: one launch
+            assert not bool(ws.any())
+
+
 def test_linear_splitk_auto_and_segment_scales(gpu_lib):
     say("split-K: automatic choice, per-block scales, workspace query")
     M, N, K = 128, 4096, 11008                           # 64 tiles of 64 x 128 and 43 K steps: the model splits
     assert gpu_lib.linear_workspace(M, N, K) == 8 * M * N * 4
-    assert gpu_lib.linear_workspace(64, N, K) == 0 and gpu_lib.linear_workspace(2048, 27648, 5120) == 0
+    assert gpu_lib.linear_workspace(32, N, K) == 0 and gpu_lib.linear_workspace(2048, 27648, 5120) == 0
     W = synth.weights(N, K, config=2, layer=1, tensor=3)
     W[2048:] *= np.float32(0.5)
     x, bits = synth.activations(M, K, config=2, layer=1, tensor=103, bf16=True)
