@@ -286,7 +286,10 @@ __global__ __launch_bounds__((kS * kW + 1) * kWave) void linear_skinny_ws_2bit(
             }
         };
 #pragma unroll
-        for (int p = 0; p < kLx; ++p) copy_x(p, p % kRing);
+        for (int p = 0; p < kLx; ++p) {
+            copy_x(p, p % kRing);
+            issue_fence();                                             // step by step: the counted wait relies on it
+        }
         for (int i = 0; i < padded; ++i) {
             issue_fence();
             __builtin_amdgcn_s_waitcnt((kYounger & 15) | 0x0F70 | ((kYounger >> 4) << 14));   // step i has landed
