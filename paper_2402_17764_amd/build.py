@@ -45,6 +45,41 @@ def _check_no_scratch(src, stderr):
         raise RuntimeError("%s: kernels that count loads in flight must not spill: %s" % (src, ", ".join(bad)))
 
 
+def _check_issue_order(src):
+    """linear_skinny_2bit waits for a step's LDS copies with a count of the younger loads (s_waitcnt vmcnt(n)), which
+    holds only if each step's copies are issued before the weight loads that follow them in the source.  Scheduling
+    fences in the kernel pin that; this reads the generated ISA and fails the build if a compiler ever ignores them:
+    between barriers a wave must issue kC = 4 kMT / kW copies ("buffer_load ... lds") and then kR weight loads, and
+    the prologue kD such groups."""
+    asm = os.path.join(BUILD, os.path.splitext(src)[0] + ".s")
+    cmd = [HIPCC, *FLAGS, "--cuda-device-only", "-S", os.path.join(CSRC, src), "-o", asm]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc -S failed on %s:\n%s" % (src, r.stderr))
+    cur, segs, checked = None, [""], 0
+    for line in open(asm):
+        m = re.match(r"^_ZN6bitnet18linear_skinny_2bitILi(\d+)ELi(\d+)ELi(\d+)ELi(\d+)ELi(\d+)ELi(\d+)E\S*:", line)
+        if m:
+            cur, segs = [int(v) for v in m.groups()], [""]
+            continue
+        if cur is None:
+            continue
+        if "buffer_load_dwordx4" in line:
+            segs[-1] += "L" if re.search(r"\blds\b", line) else "W"
+        elif "s_barrier" in line:
+            segs.append("")
+        elif "s_endpgm" in line:
+            kMT, kR, kW, kS, kD, kLx = cur
+            unit = "L" * (4 * kMT // kW) + "W" * kR
+            loops = [g for g in segs[1:] if g]
+            if segs[0] != unit * kD or not loops or any(g != unit for g in loops):
+                raise RuntimeError("%s: linear_skinny_2bit<%s>: loads are not issued in source order (%s), the counted "
+                                   "waits would be wrong" % (src, ", ".join(map(str, cur)), " | ".join(segs)))
+            cur, checked = None, checked + 1
+    if checked == 0:
+        raise RuntimeError("%s: no linear_skinny_2bit kernel found in the ISA: issue order unchecked" % src)
+
+
 def _compile(src):
     obj = os.path.join(BUILD, os.path.splitext(src)[0] + ".o")
     cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
@@ -67,8 +102,10 @@ def _compile(src):
 
 def build_library(verbose: bool = False) -> str:
     os.makedirs(BUILD, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES) + 1)) as ex:
+        order = ex.submit(_check_issue_order, "linear_skinny.hip")
         objs = list(ex.map(_compile, SOURCES))
+        order.result()
     tmp = LIB + ".tmp.%d" % os.getpid()
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", tmp])
     os.replace(tmp, LIB)
