@@ -523,8 +523,13 @@ constexpr size_t kGemvLdsBudget = 65536;
 
 static size_t gemv16_x_lds_bytes(int64_t M, int64_t K) { return (size_t)M * ceil_div(K, 256) * 256; }
 
-template <int kR, int kS, int kW, int kD>
-static void launch16(int xmode, const void* x, const float* sx, const void* packed, const float* gamma, int gstride,
+// kModes: which activation modes a launch shape is instantiated for (each is a kernel of its own)
+constexpr int kModesInt8 = 1;    // kXGlobal, kXLds
+constexpr int kModesFused = 2;   // kXFusedBf16, kXFusedF32
+constexpr int kModesPre = 4;     // RMSNorm and SwiGLU pre-operations
+
+template <int kR, int kS, int kW, int kD, int kModes>
+static hipError_t launch16(int xmode, const void* x, const float* sx, const void* packed, const float* gamma, int gstride,
                      int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream, const float* gain, float eps) {
     const int Kq = (int)ceil_div(K, kColsPerQuad);
     const int RB = (int)ceil_div(N, kRowsPerBlock);
@@ -539,61 +544,116 @@ static void launch16(int xmode, const void* x, const float* sx, const void* pack
     const uint4* p = static_cast<const uint4*>(packed);
 #define GO(X_) hipLaunchKernelGGL((linear_gemv16_2bit<kR, kS, kW, kD, X_>), grid, block, lds, stream, x, sx, p, gamma, gstride, (int)M, N, \
                                   K, Kq, RB, items, y, yt, gain, eps)
-    switch (xmode) {
-        case kXGlobal: GO(kXGlobal); break;
-        case kXLds: GO(kXLds); break;
-        case kXFusedBf16: GO(kXFusedBf16); break;
-        case kXFusedF32: GO(kXFusedF32); break;
-        case kXNormBf16: GO(kXNormBf16); break;
-        case kXNormF32: GO(kXNormF32); break;
-        case kXSwigluBf16: GO(kXSwigluBf16); break;
-        default: GO(kXSwigluF32); break;
+    if constexpr ((kModes & kModesInt8) != 0) {
+        if (xmode == kXGlobal) { GO(kXGlobal); return hipGetLastError(); }
+        if (xmode == kXLds) { GO(kXLds); return hipGetLastError(); }
+    }
+    if constexpr ((kModes & kModesFused) != 0) {
+        if (xmode == kXFusedBf16) { GO(kXFusedBf16); return hipGetLastError(); }
+        if (xmode == kXFusedF32) { GO(kXFusedF32); return hipGetLastError(); }
+    }
+    if constexpr ((kModes & kModesPre) != 0) {
+        if (xmode == kXNormBf16) { GO(kXNormBf16); return hipGetLastError(); }
+        if (xmode == kXNormF32) { GO(kXNormF32); return hipGetLastError(); }
+        if (xmode == kXSwigluBf16) { GO(kXSwigluBf16); return hipGetLastError(); }
+        if (xmode == kXSwigluF32) { GO(kXSwigluF32); return hipGetLastError(); }
     }
 #undef GO
+    return hipErrorInvalidDeviceFunction;      // a dispatch rule asked a launch shape for a mode it is not built for
 }
-// Shape heuristics from sweeps on MI355X (M = 1, HIP-graph replay over many distinct weight buffers):
-//   * many row blocks: few waves, each owning four row blocks for all of K with 2-3 steps of loads
-//     in flight -- the dense step-major front does the rest;
-//   * fewer row blocks: one row block per wave and K split over 4-8 waves, with depth chosen so that
-//     S * D covers all steps, i.e. the whole matrix is requested within the first memory round trip;
-//   * long K with few row blocks: two row blocks per wave, K split four ways, four steps in flight.
-// xmode < 0 (x_q given) lets the shape decide between global and LDS-staged x_q; the fused modes
-// pass their own and need the wide workgroups that can hold token 0 in registers.
-static void dispatch16(int xmode, const void* x, const float* sx, const void* packed, const float* gamma, int gstride,
-                       int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream,
-                       const float* gain = nullptr, float eps = 0.0f) {
-    const int64_t RB = ceil_div(N, kRowsPerBlock);
-    const int64_t steps = ceil_div(K, 256);
-    const bool fused = xmode >= 0;
-#define GEMV16(R_, S_, W_, D_, X_) launch16<R_, S_, W_, D_>(fused ? xmode : (X_), x, sx, packed, gamma, gstride, M, N, K, y, yt, stream, gain, eps)
+
+// Fraction of the K steps a shape walks that are real: each of kS waves takes ceil(steps / kS) steps, padded to a
+// multiple of the prefetch depth kD with masked steps that still cost their loads and MFMAs.
+static double walk_efficiency(int64_t steps, int kS, int kD) {
+    const int64_t items = ceil_div(ceil_div(steps, kS), kD) * kD;
+    return (double)steps / (double)(kS * items);
+}
+
+// Launch shapes from sweeps on MI355X (M = 1, 2 and 4; HIP-graph replay over many distinct weight buffers; twenty
+// configurations on the twenty projection shapes of the 3B ... 70B LLaMA family).  What decides:
+//   * many row blocks: few waves, each owning four row blocks for all of K with 2-3 steps of loads in flight --
+//     the dense step-major front does the rest;
+//   * fewer row blocks: K split over the 4-8 waves of a workgroup, one or two row blocks per wave, with a depth
+//     such that S * D covers all steps where possible, i.e. the whole matrix is requested within the first memory
+//     round trip; at most 256 row blocks: one row block per workgroup, or half the CUs get none;
+//   * padding: 20 steps over 4 waves at depth 4 walk 32 (13B-class K = 5120 ran 1.3-1.4x slower than its bytes
+//     warrant until the rules looked at it), so shapes are compared by walk_efficiency();
+//   * x_q staged in LDS pays only for one token, many row blocks and a short K.
+// The fused modes quantize the activations in every workgroup, so they lean towards fewer, wider workgroups; the
+// RMSNorm and SwiGLU modes repeat an fp64 reduction or an exponential and a division per element on top (a
+// microsecond or two of the CU's time) and go further that way.
+#define GEMV16(R_, S_, W_, D_, MODES_, X_) \
+    return launch16<R_, S_, W_, D_, MODES_>(X_, x, sx, packed, gamma, gstride, M, N, K, y, yt, stream, gain, eps)
+
+static hipError_t dispatch16_int8(const void* x, const float* sx, const void* packed, const float* gamma, int gstride, int64_t M,
+                            int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
+    const int64_t RB = ceil_div(N, kRowsPerBlock), steps = ceil_div(K, 256);
+    const float* gain = nullptr;
+    const float eps = 0.0f;
+    const bool pads44 = walk_efficiency(steps, 4, 4) < 0.8;        // four waves at depth 4 would walk 25 % or more in vain
     if (RB >= 2048) {
-        if (fused) GEMV16(4, 1, 4, 2, kXGlobal); else GEMV16(4, 1, 4, 3, kXGlobal);
-    } else if (steps >= 64) {
-        if (xmode >= kXNormBf16) GEMV16(1, 8, 1, 3, kXGlobal);      // RMSNorm / SwiGLU modes need more registers than 1024 threads leave
-        else if (fused) GEMV16(1, 8, 2, 2, kXGlobal);
-        else GEMV16(2, 4, 1, 4, kXGlobal);
+        if (steps >= 32) GEMV16(4, 1, 4, 2, kModesInt8 | kModesFused | kModesPre, kXGlobal);
+        else GEMV16(4, 1, 4, 3, kModesInt8, kXGlobal);
+    } else if (RB >= 1024) {
+        if (steps < 16 && M == 1) GEMV16(1, 4, 1, 4, kModesInt8 | kModesFused | kModesPre, kXLds);
+        else if (!pads44) GEMV16(2, 4, 1, 4, kModesInt8, kXGlobal);
+        else GEMV16(2, 1, 4, 4, kModesInt8 | kModesFused, kXGlobal);
+    } else if (RB <= 256) {
+        if (walk_efficiency(steps, 4, 5) > walk_efficiency(steps, 4, 4)) GEMV16(1, 4, 1, 5, kModesInt8 | kModesFused, kXGlobal);
+        else GEMV16(1, 4, 1, 4, kModesInt8 | kModesFused | kModesPre, kXGlobal);
     } else if (steps >= 24) {
-        if (steps <= 40) GEMV16(1, 8, 1, 5, kXLds); else GEMV16(1, 8, 1, 3, kXLds);
-    } else if (RB >= 1024 && steps >= 16 && !fused) {
-        GEMV16(2, 4, 1, 4, kXGlobal);
-    } else if (xmode >= kXNormBf16 && RB > 640) {
-        // RMSNorm and SwiGLU modes: every workgroup repeats the normalisation (an fp64 reduction and a square
-        // root) or the gating (an exponential and a division per element), which costs a microsecond or two of its
-        // CU's time -- so few, wide workgroups: four row blocks each, one wave per row block
-        GEMV16(1, 1, 4, 5, kXGlobal);
-    } else if (xmode >= kXNormBf16 && RB > 320) {
-        GEMV16(1, 2, 2, 4, kXGlobal);
+        GEMV16(2, 4, 1, 4, kModesInt8, kXGlobal);
+    } else if (!pads44) {
+        if (M > 1 && RB >= 512) GEMV16(2, 4, 1, 4, kModesInt8, kXGlobal);
+        else GEMV16(1, 4, 1, 4, kModesInt8 | kModesFused | kModesPre, (RB >= 400 && steps < 16) ? kXLds : kXGlobal);
+    } else if (RB < 512) {
+        GEMV16(1, 4, 1, 5, kModesInt8 | kModesFused, kXGlobal);
     } else {
-        GEMV16(1, 4, 1, 4, (RB >= 400 && steps < 16) ? kXLds : kXGlobal);
+        GEMV16(2, 2, 2, 4, kModesInt8, kXGlobal);
     }
-#undef GEMV16
 }
+
+// x is quantized in the kernel (xmode: plain, after RMSNorm, after SwiGLU); sx is unused
+static hipError_t dispatch16_fused(int xmode, const void* x, const void* packed, const float* gamma, int gstride, int64_t M,
+                             int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream, const float* gain, float eps) {
+    const int64_t RB = ceil_div(N, kRowsPerBlock), steps = ceil_div(K, 256);
+    const float* sx = nullptr;
+    if (xmode >= kXNormBf16) {
+        if (RB >= 2048) GEMV16(4, 1, 4, 2, kModesInt8 | kModesFused | kModesPre, xmode);
+        else if (steps >= 64) GEMV16(1, 8, 1, 3, kModesFused | kModesPre, xmode);   // 1024 threads leave these modes too few registers
+        else if (steps >= 24) { if (steps <= 40) GEMV16(1, 8, 1, 5, kModesFused | kModesPre, xmode); else GEMV16(1, 8, 1, 3, kModesFused | kModesPre, xmode); }
+        else if (RB > 640) GEMV16(1, 1, 4, 5, kModesPre, xmode);                    // four row blocks, one wave each
+        else if (RB > 320) GEMV16(1, 2, 2, 4, kModesFused | kModesPre, xmode);
+        else GEMV16(1, 4, 1, 4, kModesInt8 | kModesFused | kModesPre, xmode);
+    }
+    if (RB >= 2048) {
+        if (steps >= 32) GEMV16(4, 1, 4, 2, kModesInt8 | kModesFused | kModesPre, xmode);
+        else GEMV16(2, 1, 4, 4, kModesInt8 | kModesFused, xmode);
+    } else if (RB >= 1024) {
+        if (steps < 16) GEMV16(1, 4, 1, 4, kModesInt8 | kModesFused | kModesPre, xmode);
+        else if (RB >= 1536 && walk_efficiency(steps, 2, 4) < 0.9 && walk_efficiency(steps, 1, 4) > walk_efficiency(steps, 2, 4))
+            GEMV16(2, 1, 4, 4, kModesInt8 | kModesFused, xmode);
+        else GEMV16(1, 2, 2, 4, kModesFused | kModesPre, xmode);
+    } else if (steps >= 64) {
+        if (steps >= 96) GEMV16(1, 8, 2, 2, kModesFused, xmode); else GEMV16(1, 8, 2, 3, kModesFused, xmode);
+    } else if (steps >= 24) {
+        if (RB > 256) GEMV16(1, 4, 2, 4, kModesFused, xmode);
+        else if (steps <= 40) GEMV16(1, 8, 1, 5, kModesFused | kModesPre, xmode);
+        else GEMV16(1, 8, 1, 3, kModesFused | kModesPre, xmode);
+    } else if (walk_efficiency(steps, 4, 4) >= 0.8) {
+        GEMV16(1, 4, 1, 4, kModesInt8 | kModesFused | kModesPre, xmode);
+    } else if (RB < 512) {
+        GEMV16(1, 4, 1, 5, kModesInt8 | kModesFused, xmode);
+    } else {
+        GEMV16(1, 2, 2, 4, kModesFused | kModesPre, xmode);
+    }
+}
+#undef GEMV16
 
 // the product on pre-quantized activations, M <= 16 (the dispatcher of the M <= 64 kernels uses it up to M = 4)
 hipError_t launch_linear_gemv16_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma, int gstride,
                                      int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
-    dispatch16(-1, xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream);
-    return hipGetLastError();
+    return dispatch16_int8(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream);
 }
 
 bool gemv_fused_supports(int64_t M, int64_t N, int64_t K, const void* x) {
@@ -604,15 +664,13 @@ bool gemv_fused_supports(int64_t M, int64_t N, int64_t K, const void* x) {
 
 hipError_t launch_linear_fused_2bit(const void* x, bool bf16, const void* packed, const float* gamma, int gstride,
                                     int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
-    dispatch16(bf16 ? kXFusedBf16 : kXFusedF32, x, nullptr, packed, gamma, gstride, M, N, K, y, yt, stream);
-    return hipGetLastError();
+    return dispatch16_fused(bf16 ? kXFusedBf16 : kXFusedF32, x, packed, gamma, gstride, M, N, K, y, yt, stream, nullptr, 0.0f);
 }
 
 hipError_t launch_rmsnorm_linear_fused_2bit(const void* x, bool bf16, const float* gain, float eps, const void* packed,
                                             const float* gamma, int gstride, int64_t M, int64_t N, int64_t K, void* y,
                                             OutType yt, hipStream_t stream) {
-    dispatch16(bf16 ? kXNormBf16 : kXNormF32, x, nullptr, packed, gamma, gstride, M, N, K, y, yt, stream, gain, eps);
-    return hipGetLastError();
+    return dispatch16_fused(bf16 ? kXNormBf16 : kXNormF32, x, packed, gamma, gstride, M, N, K, y, yt, stream, gain, eps);
 }
 
 // merged gate | up projection with the SwiGLU gate in the epilogue; x goes through the fused quantization
@@ -656,8 +714,7 @@ hipError_t launch_linear_fused_swiglu_out_2bit(const void* x, bool bf16, bool no
 
 hipError_t launch_swiglu_linear_fused_2bit(const void* gu, bool bf16, const void* packed, const float* gamma, int gstride,
                                            int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
-    dispatch16(bf16 ? kXSwigluBf16 : kXSwigluF32, gu, nullptr, packed, gamma, gstride, M, N, K, y, yt, stream);
-    return hipGetLastError();
+    return dispatch16_fused(bf16 ? kXSwigluBf16 : kXSwigluF32, gu, packed, gamma, gstride, M, N, K, y, yt, stream, nullptr, 0.0f);
 }
 
 }  // namespace bitnet

@@ -663,6 +663,42 @@ def test_linear_decode_full_size_sampled(gpu_lib, config, name, K, N, Ms):
         assert torch.equal(a_ref, acc)
 
 
+# 13B- and 30B-class projections: between them and the benchmark's 3B / 7B / 70B shapes they reach every launch shape
+# the M <= 4 decode dispatch can pick (K = 5120 is the case whose 20 K steps pad badly over four waves)
+FAMILY_DECODE = [("13b_qkv", 5120, 15360), ("13b_o", 5120, 5120), ("13b_gate_up", 5120, 27648), ("13b_down", 13824, 5120),
+                 ("30b_qkv", 6656, 19968), ("30b_o", 6656, 6656), ("30b_gate_up", 6656, 35840), ("30b_down", 17920, 6656)]
+
+
+@pytest.mark.parametrize("name,K,N", FAMILY_DECODE)
+def test_linear_decode_family_shapes_sampled(gpu_lib, name, K, N):
+    say("linear decode %s K=%d N=%d" % (name, K, N))
+    W = synth.weights(N, K, config=3, layer=1, tensor=len(name))
+    gamma_ref, _ = oracle.absmean_gamma(W)
+    rng = np.random.default_rng([3, K, N])
+    cols = np.sort(rng.choice(N, 256, replace=False))
+    cols[0], cols[-1] = 0, N - 1
+    codes_ref = oracle.ternarize(W[cols], gamma_ref)
+    packed, gamma = gpu_lib.quantize_weights(dev(W))
+    del W
+    assert gamma.cpu().numpy()[0] == gamma_ref
+    ci = torch.from_numpy(cols).cuda()
+    for M in (1, 3):
+        x, bits = synth.activations(M, K, config=3, layer=M, tensor=100, bf16=True)
+        xq_ref, sx_ref = oracle.quantize_acts(x)
+        acc_ref = oracle.ternary_matmul(xq_ref, codes_ref)
+        y_ref = oracle.rescale(acc_ref, gamma_ref, sx_ref)
+        xd = bf16_tensor(bits).view(M, K)
+        xq, sx = gpu_lib.quantize_acts(xd)
+        acc = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.I32)
+        assert np.array_equal(acc[:, ci].cpu().numpy(), acc_ref)
+        y16 = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.BF16)
+        check_y(y16[:, ci].float().cpu().numpy(), y_ref, RTOL_BF16)
+        a_ref = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.I32, kernel=gpu_lib.KERNEL_REFERENCE)
+        assert torch.equal(a_ref, acc)
+        if 128 + M * ((K + 255) // 256) * 256 <= 60 * 1024:            # the fused entry point holds x_q in LDS
+            assert torch.equal(gpu_lib.linear_fused(xd, packed, gamma, N, y_dtype=gpu_lib.I32), a_ref)
+
+
 def test_linear_prefill_70b_full_size_sampled(gpu_lib):
     """70B-class FFN shapes at M = 4096 (the prefill sweep of the last benchmark configuration), sampled."""
     for (name, K, N) in (("gate_up", 8192, 57344), ("down", 28672, 8192)):
