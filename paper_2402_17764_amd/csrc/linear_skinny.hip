@@ -488,10 +488,7 @@ hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void
                                    int force_splits) {
     if (M <= 4) return launch_linear_gemv16_2bit(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream);
     // More than four tokens: the activations of a step outweigh the weights a wave reads with them, so they
-    // are staged once per group of waves (skinny kernel), 16 * kMT >= M tokens per step.  From sweeps on
-    // MI355X over 3B/7B/70B layer shapes: the workgroups should about cover the 256 CUs, so the row blocks
-    // per workgroup (kW * kR) follow N; with few row blocks the waves split K further instead.  Two steps
-    // of prefetch were best throughout.
+    // are staged once per group of waves (skinny kernel), 16 * kMT >= M tokens per step.
     const int64_t RB = ceil_div(N, kRowsPerBlock);
     int splits = 1;
     if (force_splits > 0) splits = force_splits;
@@ -505,28 +502,44 @@ hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void
     return launch_skinny<__VA_ARGS__>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, splits, workspace)
 #define SKINNY_WS(...) \
     return launch_skinny_ws<__VA_ARGS__>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, splits, workspace)
-    // The workgroups of a launch should fit the chip at once: 256 CUs times the workgroups whose activation rings
-    // fit the LDS of one (often a single one).  A few more than that and a second, nearly empty round doubles the
-    // time, so the row blocks per workgroup (kW * kR) step up with the row count.
+    // Row blocks per workgroup (kW * kR): the smallest count with which the launch is at most 256 workgroups, one per
+    // CU.  The activation rings take 48-128 KB of LDS, so a CU often holds a single workgroup and any more run as a
+    // second round (600 workgroups of one row block: 9.3 us where 150 of four take 5.5 us); and where several do fit,
+    // a CU streams at a fixed rate however many it holds, so 288 workgroups leave 32 CUs with twice the work of the
+    // others (13B gate / up at 8 tokens: 14.0 us with six row blocks per workgroup, 9.5 us with eight).  Beyond 4096
+    // row blocks sixteen per workgroup, the most a form has, measured best.  The kernel forms per size come from
+    // sweeps over the 3B ... 70B LLaMA family shapes (31 forms, 8 ... 64 tokens).
+    int rpw = 16;
+    for (const int c : {8, 6, 4, 2, 1})
+        if (ceil_div(RBc, c) <= 256) rpw = c;
     if (M <= 16) {
-        if (RBc >= 2048)      SKINNY(1, 4, 4, 2, 2, 2);
-        else if (RBc >= 1024) SKINNY(1, 3, 2, 4, 2, 2);
-        else if (RBc > 512)   SKINNY(1, 2, 2, 4, 2, 2);
-        else if (RBc > 256)   SKINNY(1, 1, 2, 8, 2, 2);
-        else                  SKINNY(1, 1, 1, 8, 2, 2);
+        if (rpw == 16)     SKINNY(1, 4, 4, 2, 2, 2);
+        else if (rpw == 8) SKINNY(1, 2, 4, 2, 2, 2);
+        else if (rpw == 6) SKINNY(1, 3, 2, 4, 2, 2);
+        else if (rpw == 4) SKINNY(1, 2, 2, 4, 2, 2);
+        else if (rpw == 2) {
+            // eight K groups, unless their shares pad much worse than four groups' would (20 steps: 8 x 4 against 4 x 6)
+            const int64_t steps = ceil_div(ceil_div(K, 256), splits);
+            const int64_t walk8 = 8 * (ceil_div(ceil_div(steps, 8), 2) * 2), walk4 = 4 * (ceil_div(ceil_div(steps, 4), 2) * 2);
+            if (walk8 * 20 >= walk4 * 25) SKINNY(1, 1, 2, 4, 2, 2);
+            else SKINNY(1, 1, 2, 8, 2, 2);
+        }
+        else               SKINNY(1, 1, 1, 8, 2, 2);
     } else if (M <= 32) {
-        // from 1024 row blocks on, the form with a loader wave (weights 3 steps deep in flight per wave)
-        if (RBc >= 2048)      SKINNY_WS(2, 4, 4, 1, 4, 3);
-        else if (RBc >= 1024) SKINNY_WS(2, 2, 3, 2, 4, 3);
-        else if (RBc > 512)   SKINNY(2, 2, 2, 4, 2, 2);
-        else if (RBc > 256)   SKINNY(2, 1, 2, 4, 2, 2);
-        else                  SKINNY(2, 1, 1, 4, 2, 2);
+        // from six row blocks on, the form with a loader wave (weights 3 steps deep in flight per wave)
+        if (rpw == 16)     SKINNY_WS(2, 4, 4, 1, 4, 3);
+        else if (rpw == 8) SKINNY_WS(2, 2, 4, 1, 4, 3);
+        else if (rpw == 6) SKINNY_WS(2, 2, 3, 2, 4, 3);
+        else if (rpw == 4) SKINNY(2, 2, 2, 4, 2, 2);
+        else if (rpw == 2) SKINNY(2, 1, 2, 4, 2, 2);
+        else               SKINNY(2, 1, 1, 4, 2, 2);
     } else {
-        if (RBc >= 2048)      SKINNY_WS(4, 4, 4, 1, 4, 2);
-        else if (RBc >= 1024) SKINNY_WS(4, 2, 3, 1, 4, 2);
-        else if (RBc >= 512)  SKINNY_WS(4, 2, 2, 2, 4, 2);
-        else if (RBc > 256)   SKINNY(4, 2, 1, 4, 2, 1);
-        else                  SKINNY(4, 1, 1, 4, 2, 1);
+        if (rpw == 16)     SKINNY_WS(4, 4, 4, 1, 4, 2);
+        else if (rpw == 8) SKINNY_WS(4, 2, 4, 1, 4, 2);
+        else if (rpw == 6) SKINNY_WS(4, 2, 3, 1, 4, 2);
+        else if (rpw == 4) SKINNY_WS(4, 2, 2, 2, 4, 2);
+        else if (rpw == 2) SKINNY(4, 2, 1, 4, 2, 1);
+        else               SKINNY(4, 1, 1, 4, 2, 1);
     }
 #undef SKINNY
 #undef SKINNY_WS

@@ -228,7 +228,12 @@ GEMV_SHAPES = [(1, 4096, 1536), (16, 4096, 1536), (1, 16, 64), (1, 17, 16), (3, 
                (9, 9000, 528), (10, 32800, 272), (5, 40, 16), (13, 16400, 1040),
                # ... and the form with a loader wave (many row blocks, more than 16 tokens): each of its five selections,
                # K from one partial step to 33 steps
-               (30, 32784, 272), (60, 32800, 144), (17, 20490, 80), (64, 20480, 8208), (40, 8200, 1040)]
+               (30, 32784, 272), (60, 32800, 144), (17, 20490, 80), (64, 20480, 8208), (40, 8200, 1040),
+               # ... two and eight row blocks per workgroup (257 ... 512 and 1537 ... 2047 row blocks) at every token tile
+               (9, 5000, 528), (12, 5008, 8208), (20, 6000, 272), (50, 8000, 1040), (9, 26000, 272), (30, 28000, 144), (64, 30000, 528),
+               # M <= 4: depth 5 where depth 4 would pad (34 K steps over four waves), two row blocks per wave from 512
+               # row blocks on with more than one token
+               (2, 100, 8640), (3, 9000, 3200)]
 
 
 @pytest.mark.parametrize("M,N,K", GEMV_SHAPES)
