@@ -609,7 +609,7 @@ static hipError_t dispatch16_int8(const void* x, const float* sx, const void* pa
     } else if (RB < 512) {
         GEMV16(1, 4, 1, 5, kModesInt8 | kModesFused, kXGlobal);
     } else {
-        GEMV16(2, 2, 2, 4, kModesInt8, kXGlobal);
+        GEMV16(2, 2, 2, 4, kModesInt8 | kModesPre, kXGlobal);
     }
 }
 
@@ -618,11 +618,23 @@ static hipError_t dispatch16_fused(int xmode, const void* x, const void* packed,
                              int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream, const float* gain, float eps) {
     const int64_t RB = ceil_div(N, kRowsPerBlock), steps = ceil_div(K, 256);
     const float* sx = nullptr;
-    if (xmode >= kXNormBf16) {
+    if (xmode == kXNormBf16 || xmode == kXNormF32) {
+        // every workgroup repeats the normalisation (an fp64 reduction and a square root, a microsecond or two of its
+        // CU's time), so few, wide workgroups: one wave per row block (or pair of them) and no K split from 769 row
+        // blocks on, at most 256 workgroups up to 4096 row blocks
+        if (RB >= 2048) GEMV16(2, 1, 8, 3, kModesPre, xmode);
+        else if (RB >= 1024) GEMV16(1, 1, 8, 5, kModesPre, xmode);
+        else if (RB > 768) GEMV16(1, 1, 4, 5, kModesPre, xmode);
+        else if (RB > 512) GEMV16(2, 2, 2, 4, kModesInt8 | kModesPre, xmode);
+        else if (RB > 256) GEMV16(1, 2, 2, 4, kModesFused | kModesPre, xmode);
+        else GEMV16(1, 4, 1, 4, kModesInt8 | kModesFused | kModesPre, xmode);
+    }
+    if (xmode >= kXSwigluBf16) {
+        // the gate (an exponential and a division per element) is repeated by every workgroup for the whole token
         if (RB >= 2048) GEMV16(4, 1, 4, 2, kModesInt8 | kModesFused | kModesPre, xmode);
-        else if (steps >= 64) GEMV16(1, 8, 1, 3, kModesFused | kModesPre, xmode);   // 1024 threads leave these modes too few registers
+        else if (steps >= 64) GEMV16(1, 8, 1, 3, kModesFused | kModesPre, xmode);   // 1024 threads leave this mode too few registers
         else if (steps >= 24) { if (steps <= 40) GEMV16(1, 8, 1, 5, kModesFused | kModesPre, xmode); else GEMV16(1, 8, 1, 3, kModesFused | kModesPre, xmode); }
-        else if (RB > 640) GEMV16(1, 1, 4, 5, kModesPre, xmode);                    // four row blocks, one wave each
+        else if (RB > 640) GEMV16(1, 1, 4, 5, kModesPre, xmode);
         else if (RB > 320) GEMV16(1, 2, 2, 4, kModesFused | kModesPre, xmode);
         else GEMV16(1, 4, 1, 4, kModesInt8 | kModesFused | kModesPre, xmode);
     }
@@ -705,10 +717,13 @@ hipError_t launch_linear_fused_swiglu_out_2bit(const void* x, bool bf16, bool no
                                                const void* packed, const float* gamma, int gstride, int64_t M, int64_t F,
                                                int64_t K, void* h, OutType yt, hipStream_t stream) {
     const int xmode = norm ? (bf16 ? kXNormBf16 : kXNormF32) : (bf16 ? kXFusedBf16 : kXFusedF32);
-    // few, wide workgroups as for the other pre-operations: two pairs per workgroup with K split in two, or four
-    // pairs with one wave each when there are many
-    if (F / kRowsPerBlock <= 700) launch16_pair<2, 2, 4>(xmode, x, packed, gamma, gstride, M, F, K, h, yt, stream, gain, eps);
-    else launch16_pair<1, 4, 5>(xmode, x, packed, gamma, gstride, M, F, K, h, yt, stream, gain, eps);
+    // From a sweep of fourteen launch shapes on the gate / up matrices of the 3B ... 70B family: without the
+    // normalisation, up to 700 pairs one pair per workgroup with K split over four waves; otherwise one wave per pair
+    // and no K split, four pairs per workgroup up to 1024 pairs (at most 256 workgroups), eight beyond.
+    const int64_t pairs = F / kRowsPerBlock;
+    if (!norm && pairs <= 700) launch16_pair<4, 1, 4>(xmode, x, packed, gamma, gstride, M, F, K, h, yt, stream, gain, eps);
+    else if (pairs <= 1024) launch16_pair<1, 4, 5>(xmode, x, packed, gamma, gstride, M, F, K, h, yt, stream, gain, eps);
+    else launch16_pair<1, 8, 3>(xmode, x, packed, gamma, gstride, M, F, K, h, yt, stream, gain, eps);
     return hipGetLastError();
 }
 
