@@ -257,7 +257,7 @@ bitnet_status bitnet_linear_fused(const void* x, bitnet_dtype x_dtype, const voi
  *   g    [K] float (device), 16-byte aligned, or NULL for no gain
  *   eps  added to the mean square; >= 0 (BITNET_ERR_SHAPE otherwise)
  *   Limits as for bitnet_linear_fused.  2-bit format only.
- * Measured at M = 1 on MI355X (3200 -> 9600 / 3200 -> 17280 / 8192 -> 57344): 7.5 / 8.7 / 25.4 us against 9.6 / 10.9 /
+ * Measured at M = 1 on MI355X (3200 -> 9600 / 3200 -> 17280 / 8192 -> 57344): 7.0 / 8.3 / 25.0 us against 9.6 / 10.9 /
  * 28.7 us for bitnet_rmsnorm_quantize + bitnet_linear.
  * bitnet_rmsnorm_linear_fused_segmented: with one gamma per 16-row block, as bitnet_linear_fused_segmented.
  */
