@@ -164,7 +164,7 @@ bitnet_status bitnet_quantize_acts(const void* x, bitnet_dtype x_dtype, int64_t 
  * computed in fp64, z = (x * r) * g in fp32 (g == NULL: no gain, z = x * r), then sx / xq from z as in
  * bitnet_quantize_acts.
  *   x    [M][K], dtype F32 or BF16, element-aligned (16- / 8-byte aligned rows with K % 4 == 0 and
- *        K <= 16384 stay in registers between the passes; other shapes re-read x)
+ *        K <= 65536 stay in registers between the passes; other shapes re-read x)
  *   g    [K] float (device) or NULL
  *   eps  added to the mean square; >= 0
  *   xq   out [M][K] int8;  sx  out [M] float

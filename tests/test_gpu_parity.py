@@ -122,7 +122,8 @@ def test_quantize_weights_edge_values(gpu_lib):
 # ------------------------------------------------------------------------------------------------
 # activations
 # ------------------------------------------------------------------------------------------------
-ACT_SHAPES = [(1, 1536), (16, 1536), (1, 1), (3, 515), (5, 28672), (70, 4096), (2, 40000)]
+ACT_SHAPES = [(1, 1536), (16, 1536), (1, 1), (3, 515), (5, 28672), (70, 4096), (2, 40000), (3, 8192), (2, 13824), (3, 70000),
+              (2, 131080)]
 
 
 @pytest.mark.parametrize("M,K", ACT_SHAPES)
@@ -770,9 +771,10 @@ def test_random_shapes_every_kernel_agrees(gpu_lib):
 # ------------------------------------------------------------------------------------------------
 # producers of int8 activations: RMSNorm -> int8, SwiGLU -> int8 (bit-exact codes and scales)
 # ------------------------------------------------------------------------------------------------
-# register-resident and re-reading paths (K % 4, K > 16384), one token and many, with and without gain
+# register-resident forms (4, 8, 16 chunks per thread at 256 and at 1024 threads) and the sweeping form (K % 4, K >
+# 65536), one token and many, with and without gain
 PRODUCER_SHAPES = [(1, 3200), (16, 1536), (5, 4), (3, 1), (7, 1003), (2, 16384), (2, 16388), (1, 28672), (33, 8640),
-                   (300, 520)]
+                   (300, 520), (70, 4096), (65, 6656), (64, 13824), (70, 20000), (3, 40000), (2, 70000)]
 
 
 @pytest.mark.parametrize("M,K", PRODUCER_SHAPES)
@@ -813,7 +815,8 @@ def test_rmsnorm_quantize_edge_cases(gpu_lib):
 
 
 @pytest.mark.parametrize("M,F", [(1, 8640), (16, 1536), (5, 4), (3, 1), (7, 1003), (2, 16384), (2, 16390), (1, 28672),
-                                 (40, 11008), (300, 260)])
+                                 (40, 11008), (300, 260), (70, 4096), (65, 8640), (64, 13824), (70, 28672), (3, 40000),
+                                 (2, 70000)])
 @pytest.mark.parametrize("bf16", [False, True])
 def test_swiglu_quantize_matches_oracle(gpu_lib, M, F, bf16):
     say("swiglu_quantize M=%d F=%d bf16=%s" % (M, F, bf16))
