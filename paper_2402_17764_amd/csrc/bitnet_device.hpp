@@ -73,6 +73,43 @@ __device__ inline void dd_add_dd(dd& s, const dd& o) {
     s.lo += err + o.lo;
 }
 
+// one double moved across lanes with a DPP control (both 32-bit halves)
+template <int kCtrl>
+__device__ inline double dpp_f64(double v) {
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = dpp_u32<kCtrl>((uint32_t)u), hi = dpp_u32<kCtrl>((uint32_t)(u >> 32));
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+__device__ inline double readlane_f64(double v, int lane) {
+    const uint64_t u = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)u, lane);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(u >> 32), lane);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+
+// Sum over the block of per-thread double-double partial sums; every thread gets the result.  The sums are
+// exact to ~2^-100, far below the rounding of the result to fp64, so the shape of the tree does not show:
+// four DPP steps inside each row of 16 lanes, the four rows of a wave through scalar reads, the waves in order.
+template <int kWaves>
+__device__ inline double block_sum_dd(dd v, double* sh_hi, double* sh_lo) {
+    dd_add_dd(v, dd{dpp_f64<0xB1>(v.hi), dpp_f64<0xB1>(v.lo)});       // lane ^ 1
+    dd_add_dd(v, dd{dpp_f64<0x4E>(v.hi), dpp_f64<0x4E>(v.lo)});       // lane ^ 2
+    dd_add_dd(v, dd{dpp_f64<0x141>(v.hi), dpp_f64<0x141>(v.lo)});     // other quad of the 8
+    dd_add_dd(v, dd{dpp_f64<0x140>(v.hi), dpp_f64<0x140>(v.lo)});     // other half of the 16
+    dd w{readlane_f64(v.hi, 0), readlane_f64(v.lo, 0)};
+    dd_add_dd(w, dd{readlane_f64(v.hi, 16), readlane_f64(v.lo, 16)});
+    dd_add_dd(w, dd{readlane_f64(v.hi, 32), readlane_f64(v.lo, 32)});
+    dd_add_dd(w, dd{readlane_f64(v.hi, 48), readlane_f64(v.lo, 48)});
+    if (kWaves == 1) return w.hi + w.lo;
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { sh_hi[wave] = w.hi; sh_lo[wave] = w.lo; }
+    __syncthreads();
+    dd t{sh_hi[0], sh_lo[0]};
+#pragma unroll
+    for (int q = 1; q < kWaves; ++q) dd_add_dd(t, dd{sh_hi[q], sh_lo[q]});
+    return t.hi + t.lo;
+}
+
 // ---- SwiGLU gating with fixed arithmetic (shared by the stand-alone producer and the fused decode kernel) ----
 // exp(t) in fp32 with every step fixed (no fused multiply-add: the library is compiled with
 // contraction off): clamp to [-87, 88], n = round(t log2 e), two-constant reduction by ln 2, degree-6 Horner, scale

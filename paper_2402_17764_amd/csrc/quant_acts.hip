@@ -143,24 +143,6 @@ __device__ inline float load_elem(const void* row, int64_t k) {
     return kBf16 ? bf16_to_f32(static_cast<const uint16_t*>(row)[k]) : static_cast<const float*>(row)[k];
 }
 
-// exact sum over the block of per-thread double-double partial sums (fixed-shape tree: butterfly inside each
-// wave, then the waves in order; every thread gets the result)
-template <int kWaves>
-__device__ inline double block_sum_dd(dd v, double* sh_hi, double* sh_lo) {
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        const dd o{__shfl_xor(v.hi, off, kWave), __shfl_xor(v.lo, off, kWave)};
-        dd_add_dd(v, o);
-    }
-    const int wave = threadIdx.x >> 6;
-    if ((threadIdx.x & 63) == 0) { sh_hi[wave] = v.hi; sh_lo[wave] = v.lo; }
-    __syncthreads();
-    dd t{sh_hi[0], sh_lo[0]};
-#pragma unroll
-    for (int w = 1; w < kWaves; ++w) dd_add_dd(t, dd{sh_hi[w], sh_lo[w]});
-    return t.hi + t.lo;
-}
-
 __device__ inline uint32_t pack4(const float (&v)[4], float inv) {
     uint32_t p = 0;
 #pragma unroll
