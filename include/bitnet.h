@@ -203,6 +203,23 @@ bitnet_status bitnet_linear_variant(const int8_t* xq, const float* sx, const voi
                                     bitnet_kernel which, void* stream);
 
 /*
+ * Which kernel and launch shape bitnet_linear (workspace_bytes == 0) or bitnet_linear_ws (with a workspace of that
+ * size) takes for a shape.  Host only: nothing is launched and no device is needed.  For operators who want to see
+ * why a shape runs the way it does, and for tests of the selection rules (Sections 1-2 fix what is computed; how the
+ * launch is shaped is this library's choice).  Pointers are assumed aligned as the fast kernels require.
+ *   text  out, host: "kernel=<family> params=<template parameters> grid=<x>x<y> block=<threads> lds=<bytes>
+ *         splits=<n>", zero-terminated; BITNET_ERR_WORKSPACE if text_bytes is too small (128 is enough)
+ *   families and their parameters:
+ *     decode                 M <= 4: row blocks per wave, K waves, row slots, prefetch depth, x_q source (0 global, 1 LDS)
+ *     batched_decode         5 ... 64 tokens: token tiles of 16, row blocks per wave, row slots, K groups, prefetch
+ *     batched_decode_loader  depth, LDS lookahead (the second form has a wave that only copies activations)
+ *     prefill                tile tokens, tile rows; grid y = split-K factor
+ *     reference, trit5_decode, trit5_reference: no parameters
+ */
+bitnet_status bitnet_linear_describe(int64_t M, int64_t N, int64_t K, bitnet_format f, size_t workspace_bytes,
+                                     char* text, size_t text_bytes);
+
+/*
  * bitnet_linear with a scratch buffer.  Between decode and large prefill -- a few hundred tokens on layers with few
  * output features -- even the smallest tiles of the prefill kernel give the 256 CUs too few workgroups, each walking
  * all of K.  With a workspace the K steps of a tile are split over 2, 4 or 8 workgroups that store int32 partial

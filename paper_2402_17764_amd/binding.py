@@ -28,7 +28,7 @@ SYMBOLS = [
     "bitnet_linear_fused", "bitnet_unpack_weights", "bitnet_rmsnorm_quantize", "bitnet_swiglu_quantize",
     "bitnet_quantize_weights_segmented", "bitnet_linear_segmented", "bitnet_linear_fused_segmented",
     "bitnet_rmsnorm_linear_fused", "bitnet_rmsnorm_linear_fused_segmented", "bitnet_swiglu_linear_fused",
-    "bitnet_ffn_gate_up_fused", "bitnet_linear_workspace", "bitnet_linear_ws",
+    "bitnet_ffn_gate_up_fused", "bitnet_linear_workspace", "bitnet_linear_ws", "bitnet_linear_describe",
 ]
 
 _lib = None
@@ -71,6 +71,7 @@ def load():
     lib.bitnet_rmsnorm_linear_fused_segmented.argtypes = [vp, ci, vp, ctypes.c_float, vp, vp, i64, i64, i64, ci, vp, ci, vp]
     lib.bitnet_swiglu_linear_fused.argtypes = [vp, ci, vp, vp, i64, i64, i64, ci, vp, ci, vp]
     lib.bitnet_linear_workspace.argtypes = [i64, i64, i64, ctypes.POINTER(sz)]
+    lib.bitnet_linear_describe.argtypes = [i64, i64, i64, ctypes.c_int, sz, ctypes.c_char_p, sz]
     lib.bitnet_linear_ws.argtypes = [vp, vp, vp, vp, ci, i64, i64, i64, ci, vp, ci, ci, vp, sz, vp]
     lib.bitnet_ffn_gate_up_fused.argtypes = [vp, ci, ci, vp, ctypes.c_float, vp, vp, ci, i64, i64, i64, ci, vp, ci, vp]
     for name in SYMBOLS[2:]:
@@ -208,6 +209,18 @@ def linear_workspace(M, N, K):
     out = ctypes.c_size_t(0)
     _check(lib.bitnet_linear_workspace(M, N, K, ctypes.byref(out)), "bitnet_linear_workspace")
     return int(out.value)
+
+
+def linear_describe(M, N, K, fmt=PACK_2BIT, workspace_bytes=0):
+    """The kernel family and launch shape linear (or linear_ws with a workspace of that size) takes for a shape; host
+    only, no device needed -> dict(kernel=str, params=[int], grid=(x, y), block=int, lds=int, splits=int)."""
+    lib = load()
+    buf = ctypes.create_string_buffer(256)
+    _check(lib.bitnet_linear_describe(M, N, K, fmt, workspace_bytes, buf, len(buf)), "bitnet_linear_describe")
+    f = dict(kv.split("=", 1) for kv in buf.value.decode().split())
+    gx, gy = f["grid"].split("x")
+    return {"kernel": f["kernel"], "params": [int(v) for v in f["params"].split(",") if v], "grid": (int(gx), int(gy)),
+            "block": int(f["block"]), "lds": int(f["lds"]), "splits": int(f["splits"])}
 
 
 def linear_ws(xq, sx, packed, gamma, N, workspace, fmt=PACK_2BIT, y_dtype=F32, y=None, kernel=KERNEL_AUTO,

@@ -5,6 +5,8 @@
 #include "bitnet_device.hpp"
 #include "bitnet_internal.hpp"
 
+#include <stdio.h>
+
 namespace {
 
 using bitnet::OutType;
@@ -247,6 +249,41 @@ bitnet_status bitnet_linear_ws(const int8_t* xq, const float* sx, const void* pa
                                                         workspace, workspace ? workspace_bytes : 0, force));
     return from_hip(bitnet::launch_linear_gemm_2bit(xq, sx, packed, gamma, gstride, M, N, K, y, yt, static_cast<hipStream_t>(stream),
                                                     workspace, workspace ? workspace_bytes : 0, force));
+}
+
+bitnet_status bitnet_linear_describe(int64_t M, int64_t N, int64_t K, bitnet_format f, size_t workspace_bytes,
+                                     char* text, size_t text_bytes) {
+    if (!text || text_bytes == 0) return BITNET_ERR_NULL;
+    text[0] = 0;
+    if (!shape_ok(M, N, K)) return BITNET_ERR_SHAPE;
+    if (!format_ok(f)) return BITNET_ERR_FORMAT;
+    // the launchers read nothing through their pointers when they are given a plan: stand-ins with the alignment
+    // the fast kernels ask for
+    const int8_t* xq = reinterpret_cast<const int8_t*>(uintptr_t{256});
+    const float* fp = reinterpret_cast<const float*>(uintptr_t{256});
+    void* vp = reinterpret_cast<void*>(uintptr_t{256});
+    void* ws = workspace_bytes ? vp : nullptr;
+    bitnet::LaunchPlan plan;
+    if (f == BITNET_PACK_TRIT5) {
+        plan.kernel = bitnet::gemv_trit5_supports(M < 16 ? M : 16, N, K, xq) ? "trit5_decode" : "trit5_reference";
+    } else if (bitnet::gemv_supports(M, N, K, xq)) {
+        const hipError_t e = bitnet::launch_linear_gemv_2bit(xq, fp, vp, fp, 0, M, N, K, vp, OutType::BF16, nullptr, ws, workspace_bytes,
+                                                            0, &plan);
+        if (e != hipSuccess) return BITNET_ERR_HIP;
+    } else if (bitnet::gemm_supports(M, N, K, xq)) {
+        const hipError_t e = bitnet::launch_linear_gemm_2bit(xq, fp, vp, fp, 0, M, N, K, vp, OutType::BF16, nullptr, ws, workspace_bytes,
+                                                            0, &plan);
+        if (e != hipSuccess) return BITNET_ERR_HIP;
+    } else {
+        plan.kernel = "reference";
+    }
+    char params[96] = "";
+    size_t at = 0;
+    for (int i = 0; i < plan.nparams && at < sizeof(params) - 16; ++i)
+        at += (size_t)snprintf(params + at, sizeof(params) - at, i ? ",%d" : "%d", plan.params[i]);
+    const int n = snprintf(text, text_bytes, "kernel=%s params=%s grid=%ux%u block=%u lds=%zu splits=%d", plan.kernel, params,
+                           plan.grid_x, plan.grid_y, plan.block, plan.lds_bytes, plan.splits);
+    return (n < 0 || (size_t)n >= text_bytes) ? BITNET_ERR_WORKSPACE : BITNET_OK;
 }
 
 bitnet_status bitnet_linear_segmented(const int8_t* xq, const float* sx, const void* packed, const float* gamma_rb,

@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <initializer_list>
 #include <stdint.h>
 
 namespace bitnet {
@@ -49,6 +50,22 @@ hipError_t launch_linear_reference_2bit(const int8_t* xq, const float* sx, const
                                         OutType yt, hipStream_t stream);
 hipError_t launch_unpack_2bit(const void* packed, int64_t N, int64_t K, int8_t* codes, hipStream_t stream);
 
+// What a launcher would do.  Every bitnet_linear launcher takes an optional LaunchPlan*: when it is given, the
+// launcher fills it in and returns without touching the device or its pointer arguments (bitnet_linear_describe).
+struct LaunchPlan {
+    const char* kernel = "";          // which kernel family
+    int params[6] = {0, 0, 0, 0, 0, 0};  // template parameters of the instantiation, in declaration order
+    int nparams = 0;
+    unsigned grid_x = 0, grid_y = 1, block = 0;
+    size_t lds_bytes = 0;
+    int splits = 1;                   // > 1: split-K, a second launch adds the partials
+    void set(const char* k, std::initializer_list<int> p, unsigned gx, unsigned gy, unsigned b, size_t lds, int sp) {
+        kernel = k; nparams = 0;
+        for (int v : p) params[nparams++] = v;
+        grid_x = gx; grid_y = gy; block = b; lds_bytes = lds; splits = sp;
+    }
+};
+
 // linear_gemv.hip
 bool gemv_supports(int64_t M, int64_t N, int64_t K, const void* xq);
 // workspace (may be null) and force_splits as for launch_linear_gemm_2bit: split-K of the batched-decode kernels
@@ -56,10 +73,11 @@ bool gemv_supports(int64_t M, int64_t N, int64_t K, const void* xq);
 int skinny_splitk_splits(int64_t M, int64_t N, int64_t K);
 hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                    int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream,
-                                   void* workspace = nullptr, size_t workspace_bytes = 0, int force_splits = 0);
+                                   void* workspace = nullptr, size_t workspace_bytes = 0, int force_splits = 0,
+                                   LaunchPlan* plan = nullptr);
 // the M <= 16 kernel alone (linear_gemv.hip); launch_linear_gemv_2bit (linear_skinny.hip) routes M <= 4 to it
 hipError_t launch_linear_gemv16_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma, int gstride,
-                                     int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);
+                                     int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream, LaunchPlan* plan = nullptr);
 bool gemv_fused_supports(int64_t M, int64_t N, int64_t K, const void* x);
 hipError_t launch_linear_fused_2bit(const void* x, bool bf16, const void* packed, const float* gamma, int gstride,
                                     int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);
@@ -82,12 +100,12 @@ bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq);
 hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                    int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt,
                                    hipStream_t stream, void* workspace = nullptr, size_t workspace_bytes = 0,
-                                   int force_splits = 0);
+                                   int force_splits = 0, LaunchPlan* plan = nullptr);
 // the same with the tile forced: 32 * fm tokens x 128 * fn weight rows, fm in 2 .. 4, fn in 1 .. 2 (hipErrorInvalidValue
 // otherwise); splits > 1 needs a workspace of splitk_workspace_bytes(M, N, splits)
 hipError_t launch_linear_gemm_2bit_shape(int fm, int fn, const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                          int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream,
-                                         int splits = 1, void* workspace = nullptr);
+                                         int splits = 1, void* workspace = nullptr, LaunchPlan* plan = nullptr);
 size_t splitk_workspace_bytes(int64_t M, int64_t N, int splits);
 // split-K, second launch: y = (sum of `splits` int32 partial accumulators, [M][N] each) * gamma * s_x / 127;
 // prefill_assoc: the association of the prefill kernel's per-block-gamma epilogue (gamma * (s_x / 127)) instead of

@@ -411,10 +411,12 @@ bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
 template <int kFM, int kFN>
 static hipError_t launch_gemm_tiles(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                     int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt,
-                                    hipStream_t stream, int splits = 1, void* workspace = nullptr) {
-    static bool raised[kMaxDevices] = {};
-    const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(linear_gemm_2bit<kFM, kFN>), gemm_lds_bytes(kFM), raised);
-    if (e != hipSuccess) return e;
+                                    hipStream_t stream, int splits = 1, void* workspace = nullptr, LaunchPlan* plan = nullptr) {
+    if (!plan) {
+        static bool raised[kMaxDevices] = {};
+        const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(linear_gemm_2bit<kFM, kFN>), gemm_lds_bytes(kFM), raised);
+        if (e != hipSuccess) return e;
+    }
     const int Kq = (int)ceil_div(K, kColsPerQuad);
     const int RB = (int)ceil_div(N, kRowsPerBlock);
     const int tiles_m = (int)ceil_div(M, 32 * kFM);
@@ -428,6 +430,10 @@ static hipError_t launch_gemm_tiles(const int8_t* xq, const float* sx, const voi
     const OutType ot = split ? OutType::I32 : yt;
     const size_t esz = ot == OutType::BF16 ? 2 : 4;
     const int vec_store = (reinterpret_cast<uintptr_t>(out) % 16 == 0) && ((N * esz) % 16 == 0);
+    if (plan) {
+        plan->set("prefill", {32 * kFM, 128 * kFN}, (unsigned)(tiles_m * tiles_n), (unsigned)splits, kGemmThreads, gemm_lds_bytes(kFM), splits);
+        return hipSuccess;
+    }
     hipLaunchKernelGGL((linear_gemm_2bit<kFM, kFN>), dim3((unsigned)(tiles_m * tiles_n), (unsigned)splits), dim3(kGemmThreads),
                        gemm_lds_bytes(kFM), stream, xq, sx, static_cast<const uint4*>(packed), gamma, gstride, (int)M, N, K, Kq, RB,
                        tiles_m, sps, out, ot, vec_store);
@@ -440,8 +446,8 @@ static hipError_t launch_gemm_tiles(const int8_t* xq, const float* sx, const voi
 // (splits * M * N int32)
 hipError_t launch_linear_gemm_2bit_shape(int fm, int fn, const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                          int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream,
-                                         int splits, void* workspace) {
-#define GEMM_SHAPE(FM_, FN_) if (fm == FM_ && fn == FN_) return launch_gemm_tiles<FM_, FN_>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, splits, workspace)
+                                         int splits, void* workspace, LaunchPlan* plan) {
+#define GEMM_SHAPE(FM_, FN_) if (fm == FM_ && fn == FN_) return launch_gemm_tiles<FM_, FN_>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, splits, workspace, plan)
     GEMM_SHAPE(2, 1); GEMM_SHAPE(3, 1); GEMM_SHAPE(4, 1); GEMM_SHAPE(2, 2); GEMM_SHAPE(3, 2); GEMM_SHAPE(4, 2);
 #undef GEMM_SHAPE
     return hipErrorInvalidValue;
@@ -451,7 +457,8 @@ size_t splitk_workspace_bytes(int64_t M, int64_t N, int splits) { return (size_t
 
 hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                    int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt,
-                                   hipStream_t stream, void* workspace, size_t workspace_bytes, int force_splits) {
+                                   hipStream_t stream, void* workspace, size_t workspace_bytes, int force_splits,
+                                   LaunchPlan* plan) {
     // Tile shape (32 * fm tokens x 128 * fn weight rows) from a cost model fitted to measurements on MI355X
     // (nine LLaMA-family shapes, M = 65 ... 2048, every tile shape).  In microseconds, per K step of 256 columns:
     //   * a workgroup that has its CU to itself is latency bound and takes kAlone per step, a little more as the
@@ -491,7 +498,7 @@ hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void
         }
     }
     return launch_linear_gemm_2bit_shape(kShapes[best].fm, kShapes[best].fn, xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream,
-                                         best_splits, workspace);
+                                         best_splits, workspace, plan);
 }
 
 }  // namespace bitnet

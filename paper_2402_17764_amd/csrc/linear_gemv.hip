@@ -493,7 +493,8 @@ constexpr int kModesPre = 4;     // RMSNorm and SwiGLU pre-operations
 
 template <int kR, int kS, int kW, int kD, int kModes>
 static hipError_t launch16(int xmode, const void* x, const float* sx, const void* packed, const float* gamma, int gstride,
-                     int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream, const float* gain, float eps) {
+                     int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream, const float* gain, float eps,
+                     LaunchPlan* plan = nullptr) {
     const int Kq = (int)ceil_div(K, kColsPerQuad);
     const int RB = (int)ceil_div(N, kRowsPerBlock);
     int items = (int)ceil_div(ceil_div(K, 256), kS);
@@ -504,6 +505,10 @@ static hipError_t launch16(int xmode, const void* x, const float* sx, const void
     if (xmode == kXLds && header + lds_x > kGemvLdsBudget) xmode = kXGlobal;
     const size_t lds = header + (xmode != kXGlobal && lds_x > lds_fold ? lds_x : lds_fold);
     dim3 grid((unsigned)ceil_div(RB, kW * kR)), block(kS * kW * kWave);
+    if (plan) {
+        plan->set("decode", {kR, kS, kW, kD, xmode}, grid.x, 1, block.x, lds, 1);
+        return hipSuccess;
+    }
     const uint4* p = static_cast<const uint4*>(packed);
 #define GO(X_) hipLaunchKernelGGL((linear_gemv16_2bit<kR, kS, kW, kD, X_>), grid, block, lds, stream, x, sx, p, gamma, gstride, (int)M, N, \
                                   K, Kq, RB, items, y, yt, gain, eps)
@@ -546,10 +551,10 @@ static double walk_efficiency(int64_t steps, int kS, int kD) {
 // RMSNorm and SwiGLU modes repeat an fp64 reduction or an exponential and a division per element on top (a
 // microsecond or two of the CU's time) and go further that way.
 #define GEMV16(R_, S_, W_, D_, MODES_, X_) \
-    return launch16<R_, S_, W_, D_, MODES_>(X_, x, sx, packed, gamma, gstride, M, N, K, y, yt, stream, gain, eps)
+    return launch16<R_, S_, W_, D_, MODES_>(X_, x, sx, packed, gamma, gstride, M, N, K, y, yt, stream, gain, eps, plan)
 
 static hipError_t dispatch16_int8(const void* x, const float* sx, const void* packed, const float* gamma, int gstride, int64_t M,
-                            int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
+                                  int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream, LaunchPlan* plan) {
     const int64_t RB = ceil_div(N, kRowsPerBlock), steps = ceil_div(K, 256);
     const float* gain = nullptr;
     const float eps = 0.0f;
@@ -581,6 +586,7 @@ static hipError_t dispatch16_fused(int xmode, const void* x, const void* packed,
                              int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream, const float* gain, float eps) {
     const int64_t RB = ceil_div(N, kRowsPerBlock), steps = ceil_div(K, 256);
     const float* sx = nullptr;
+    LaunchPlan* const plan = nullptr;
     if (xmode == kXNormBf16 || xmode == kXNormF32) {
         // every workgroup repeats the normalisation (an fp64 reduction and a square root, a microsecond or two of its
         // CU's time), so few, wide workgroups: one wave per row block (or pair of them) and no K split from 769 row
@@ -627,8 +633,9 @@ static hipError_t dispatch16_fused(int xmode, const void* x, const void* packed,
 
 // the product on pre-quantized activations, M <= 16 (the dispatcher of the M <= 64 kernels uses it up to M = 4)
 hipError_t launch_linear_gemv16_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma, int gstride,
-                                     int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
-    return dispatch16_int8(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream);
+                                     int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream,
+                                     LaunchPlan* plan) {
+    return dispatch16_int8(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, plan);
 }
 
 bool gemv_fused_supports(int64_t M, int64_t N, int64_t K, const void* x) {

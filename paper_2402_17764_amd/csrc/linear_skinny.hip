@@ -417,12 +417,12 @@ bool gemv_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
 template <int kMT, int kR, int kW, int kS, int kD, int kLx>
 static hipError_t launch_skinny(const int8_t* xq, const float* sx, const void* packed, const float* gamma, int gstride,
                                 int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream,
-                               int splits, void* workspace) {
+                               int splits, void* workspace, LaunchPlan* plan) {
     constexpr size_t lds = (size_t)kS * (kLx + 1) * kMT * 16 * 256;
     static_assert(lds <= 160 * 1024, "activation rings must fit the LDS of a CU");
     static_assert(kS * kW <= 16, "at most 1024 threads per workgroup");
     auto* kern = linear_skinny_2bit<kMT, kR, kW, kS, kD, kLx>;
-    if (lds > 65536) {
+    if (lds > 65536 && !plan) {
         static bool raised[kMaxDevices] = {};
         const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(kern), (int)lds, raised);
         if (e != hipSuccess) return e;
@@ -436,6 +436,10 @@ static hipError_t launch_skinny(const int8_t* xq, const float* sx, const void* p
     const int spg = (int)ceil_div(sps, kS);
     const bool split = splits > 1;                      // then int32 partials go to the workspace and a second launch adds them
     dim3 grid((unsigned)ceil_div(RB, kW * kR), (unsigned)splits);
+    if (plan) {
+        plan->set("batched_decode", {kMT, kR, kW, kS, kD, kLx}, grid.x, grid.y, kS * kW * kWave, lds, splits);
+        return hipSuccess;
+    }
     hipLaunchKernelGGL(kern, grid, dim3(kS * kW * kWave), lds, stream, xq, sx, static_cast<const uint4*>(packed), gamma,
                        gstride, (int)M, N, K, Kq, RB, spg, sps, split ? workspace : y, split ? OutType::I32 : yt);
     if (split)
@@ -446,12 +450,12 @@ static hipError_t launch_skinny(const int8_t* xq, const float* sx, const void* p
 template <int kMT, int kR, int kW, int kS, int kD, int kLx>
 static hipError_t launch_skinny_ws(const int8_t* xq, const float* sx, const void* packed, const float* gamma, int gstride,
                                    int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream,
-                                  int splits, void* workspace) {
+                                  int splits, void* workspace, LaunchPlan* plan) {
     constexpr size_t lds = (size_t)kS * (kLx + 1) * kMT * 16 * 256;
     static_assert(lds <= 160 * 1024, "activation rings must fit the LDS of a CU");
     static_assert(kS * kW + 1 <= 16, "at most 1024 threads per workgroup");
     auto* kern = linear_skinny_ws_2bit<kMT, kR, kW, kS, kD, kLx>;
-    if (lds > 65536) {
+    if (lds > 65536 && !plan) {
         static bool raised[kMaxDevices] = {};
         const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(kern), (int)lds, raised);
         if (e != hipSuccess) return e;
@@ -465,6 +469,10 @@ static hipError_t launch_skinny_ws(const int8_t* xq, const float* sx, const void
     const int spg = (int)ceil_div(sps, kS);
     const bool split = splits > 1;                      // then int32 partials go to the workspace and a second launch adds them
     dim3 grid((unsigned)ceil_div(RB, kW * kR), (unsigned)splits);
+    if (plan) {
+        plan->set("batched_decode_loader", {kMT, kR, kW, kS, kD, kLx}, grid.x, grid.y, (kS * kW + 1) * kWave, lds, splits);
+        return hipSuccess;
+    }
     hipLaunchKernelGGL(kern, grid, dim3((kS * kW + 1) * kWave), lds, stream, xq, sx, static_cast<const uint4*>(packed), gamma,
                        gstride, (int)M, N, K, Kq, RB, spg, sps, split ? workspace : y, split ? OutType::I32 : yt);
     if (split)
@@ -485,8 +493,8 @@ int skinny_splitk_splits(int64_t M, int64_t N, int64_t K) {
 hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void* packed,
                                    const float* gamma, int gstride, int64_t M, int64_t N, int64_t K, void* y,
                                    OutType yt, hipStream_t stream, void* workspace, size_t workspace_bytes,
-                                   int force_splits) {
-    if (M <= 4) return launch_linear_gemv16_2bit(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream);
+                                   int force_splits, LaunchPlan* plan) {
+    if (M <= 4) return launch_linear_gemv16_2bit(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, plan);
     // More than four tokens: the activations of a step outweigh the weights a wave reads with them, so they
     // are staged once per group of waves (skinny kernel), 16 * kMT >= M tokens per step.
     const int64_t RB = ceil_div(N, kRowsPerBlock);
@@ -499,9 +507,9 @@ hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void
     // a fraction of x_q, instead of every workgroup staging all of it)
     const int64_t RBc = RB * splits;
 #define SKINNY(...) \
-    return launch_skinny<__VA_ARGS__>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, splits, workspace)
+    return launch_skinny<__VA_ARGS__>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, splits, workspace, plan)
 #define SKINNY_WS(...) \
-    return launch_skinny_ws<__VA_ARGS__>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, splits, workspace)
+    return launch_skinny_ws<__VA_ARGS__>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, splits, workspace, plan)
     // Row blocks per workgroup (kW * kR): the smallest count with which the launch is at most 256 workgroups, one per
     // CU.  The activation rings take 48-128 KB of LDS, so a CU often holds a single workgroup and any more run as a
     // second round (600 workgroups of one row block: 9.3 us where 150 of four take 5.5 us); and where several do fit,

@@ -1,0 +1,112 @@
+"""Host-side launch selection of bitnet_linear / bitnet_linear_ws, read back through bitnet_linear_describe (nothing is
+launched, no GPU is touched).  The rules were fitted to measurements on MI355X; these tests pin the properties the
+measurements established, on the projection shapes of the 3B ... 70B LLaMA family, so that a later edit of a rule
+that breaks one of them fails here and not as a slow kernel on the GPU."""
+import ctypes
+
+import pytest
+
+from paper_2402_17764_amd import binding as B
+
+FAMILY = {"3b": (3200, 8640), "7b": (4096, 11008), "13b": (5120, 13824), "30b": (6656, 17920), "70b": (8192, 28672)}
+SHAPES = []
+for _fam, (_d, _f) in FAMILY.items():
+    SHAPES += [(_fam + "_qkv", 3 * _d, _d), (_fam + "_o", _d, _d), (_fam + "_gate_up", 2 * _f, _d), (_fam + "_down", _d, _f)]
+
+CUS = 256
+LDS_PER_CU = 160 * 1024
+
+
+def ceil_div(a, b):
+    return -(-a // b)
+
+
+@pytest.mark.parametrize("name,N,K", SHAPES)
+def test_decode_shapes_do_not_pad_the_k_walk(name, N, K):
+    """M <= 4: each of kS waves walks ceil(steps / kS) K steps padded to a multiple of the prefetch depth kD; the
+    padding is masked work, so at most a quarter of the walk may be padding (K = 5120 over 4 waves at depth 4 would
+    be 37 %)."""
+    steps, RB = ceil_div(K, 256), ceil_div(N, 16)
+    for M in (1, 2, 4):
+        d = B.linear_describe(M, N, K)
+        assert d["kernel"] == "decode" and d["splits"] == 1
+        kR, kS, kW, kD, xsrc = d["params"]
+        walked = kS * ceil_div(ceil_div(steps, kS), kD) * kD
+        assert steps / walked >= 0.75, (name, M, d)
+        assert d["block"] == 64 * kS * kW and d["grid"] == (ceil_div(RB, kR * kW), 1)
+        assert d["lds"] <= 64 * 1024
+        if RB <= CUS:                       # one row block per workgroup, or CUs get none
+            assert kR * kW == 1
+        assert xsrc in (0, 1) and (xsrc == 0 or 128 + M * steps * 256 <= 60 * 1024)
+
+
+@pytest.mark.parametrize("name,N,K", SHAPES)
+def test_batched_decode_is_one_round_of_workgroups(name, N, K):
+    """5 ... 64 tokens: the smallest token tile that holds M, activation rings within a CU's LDS, and up to 4096 row
+    blocks at most one workgroup per CU with the fewest row blocks per workgroup that achieves it."""
+    RB = ceil_div(N, 16)
+    for M in (5, 8, 16, 17, 32, 33, 48, 64):
+        d = B.linear_describe(M, N, K)
+        assert d["kernel"] in ("batched_decode", "batched_decode_loader") and d["splits"] == 1, (name, M, d)
+        kMT, kR, kW, kS, kD, kLx = d["params"]
+        assert kMT == (1 if M <= 16 else 2 if M <= 32 else 4)
+        assert d["lds"] == kS * (kLx + 1) * kMT * 4096 <= LDS_PER_CU
+        assert d["block"] == 64 * (kS * kW + (d["kernel"] == "batched_decode_loader")) <= 1024
+        rpw = kR * kW
+        assert d["grid"] == (ceil_div(RB, rpw), 1)
+        if RB <= 4096:
+            assert d["grid"][0] <= CUS, (name, M, d)
+            smaller = [c for c in (1, 2, 4, 6, 8, 16) if c < rpw]
+            assert all(ceil_div(RB, c) > CUS for c in smaller), (name, M, d)
+
+
+def test_batched_decode_split_k_only_for_long_k_and_few_rows():
+    ws4 = lambda M, N: 4 * M * N * 4
+    d = B.linear_describe(64, 4096, 22016, workspace_bytes=ws4(64, 4096))
+    assert d["splits"] == 4 and d["grid"][1] == 4 and d["grid"][0] * 4 <= CUS
+    d = B.linear_describe(48, 8192, 28672, workspace_bytes=2 * 48 * 8192 * 4)
+    assert d["splits"] == 2 and d["grid"][1] == 2
+    assert B.linear_describe(64, 4096, 22016, workspace_bytes=1024)["splits"] == 1          # workspace too small
+    assert B.linear_describe(64, 4096, 22016)["splits"] == 1                                # none
+    assert B.linear_describe(64, 4096, 11008, workspace_bytes=ws4(64, 4096))["splits"] == 1  # K too short to pay
+    assert B.linear_describe(32, 4096, 22016, workspace_bytes=ws4(32, 4096))["splits"] == 1  # too few tokens
+    assert B.linear_describe(64, 22016, 16384, workspace_bytes=ws4(64, 22016))["splits"] == 1  # enough row blocks
+
+
+def test_prefill_tiles_follow_the_measured_cases():
+    """The cases the cost model's comment quotes, and its limits: big grids stay on the widest tile, small ones take
+    narrow tiles so that CUs are not left idle, split-K only with a workspace, a long K and few tiles."""
+    assert B.linear_describe(2048, 27648, 5120)["params"] == [128, 256]
+    assert B.linear_describe(4096, 57344, 8192)["params"] == [128, 256]
+    assert B.linear_describe(512, 5120, 5120)["params"] == [96, 128]
+    assert B.linear_describe(128, 5120, 5120)["params"] == [64, 128]
+    assert B.linear_describe(128, 4096, 11008)["params"] == [64, 128]
+    for (M, N, K) in [(65, 3200, 3200), (300, 9600, 3200), (1024, 4096, 11008), (2048, 8192, 28672), (4096, 3200, 8640)]:
+        d = B.linear_describe(M, N, K)
+        tm, tn = d["params"]
+        assert d["kernel"] == "prefill" and d["splits"] == 1 and d["block"] == 256
+        assert d["grid"] == (ceil_div(M, tm) * ceil_div(N, tn), 1)
+        assert d["lds"] <= LDS_PER_CU // 2                      # two workgroups per CU
+    big = 8 * 128 * 8192 * 4
+    d = B.linear_describe(128, 4096, 11008, workspace_bytes=big)
+    assert d["splits"] in (2, 4, 8) and d["grid"][1] == d["splits"]
+    assert B.linear_describe(128, 8192, 28672, workspace_bytes=big)["splits"] > 1
+    assert B.linear_describe(128, 4096, 4096, workspace_bytes=big)["splits"] == 1       # K = 4096: nothing to gain
+    assert B.linear_describe(2048, 4096, 11008, workspace_bytes=8 * 2048 * 4096 * 4)["splits"] == 1
+    assert B.linear_describe(128, 4096, 11008, workspace_bytes=2 * 128 * 4096 * 4)["splits"] == 2   # what fits
+
+
+def test_fallbacks_and_errors():
+    assert B.linear_describe(3, 100, 70)["kernel"] == "reference"                   # K not a multiple of 16
+    assert B.linear_describe(100, 64, 72)["kernel"] == "reference"
+    assert B.linear_describe(1, 17280, 3200, fmt=B.PACK_TRIT5)["kernel"] == "trit5_decode"
+    assert B.linear_describe(100, 17280, 3200, fmt=B.PACK_TRIT5)["kernel"] == "trit5_decode"   # 16 tokens at a time
+    lib = B.load()
+    buf = ctypes.create_string_buffer(128)
+    assert lib.bitnet_linear_describe(1, 4096, 4096, 0, 0, None, 128) == 1
+    assert lib.bitnet_linear_describe(1, 4096, 4096, 0, 0, buf, 0) == 1
+    assert lib.bitnet_linear_describe(0, 4096, 4096, 0, 0, buf, 128) == 2
+    assert lib.bitnet_linear_describe(1, 4096, 4096, 7, 0, buf, 128) == 4
+    assert lib.bitnet_linear_describe(1, 4096, 4096, 0, 0, buf, 8) == 6                # text does not fit
+    assert lib.bitnet_linear_describe(1, 4096, 4096, 0, 0, buf, 128) == 0
+    assert buf.value.decode().startswith("kernel=decode params=1,4,1,4,0 grid=256x1 block=256")
