@@ -226,10 +226,9 @@ bitnet_status bitnet_linear_describe(int64_t M, int64_t N, int64_t K, bitnet_for
  * accumulators there; a second launch adds them (exact, independent of the split) and rescales.  Chosen by the same
  * cost model as the tile shape, only where it pays: long K, few tiles (measured on MI355X, M = 128: 11008 -> 4096 in
  * 18.1 instead of 25.4 us, 28672 -> 8192 in 40.7 instead of 70.9 us; nothing to gain at K = 4096 or from 512 tokens
- * on).  The batched-decode kernels split the same way at 33 ... 64 tokens where K >= 16384 and N <= 8192: there
- * every workgroup streams all of x_q through its LDS, a latency chain that a split shortens (64 tokens, 28672 -> 8192:
- * 33.8 instead of 37.9 us; 22016 -> 4096: 21.5 instead of 29.1 us).  Results are bit-identical to bitnet_linear /
- * bitnet_linear_segmented.
+ * on).  The batched-decode kernels (5 ... 64 tokens) can split the same way when forced, but never do by themselves:
+ * tiling the tokens over workgroups serves their small-layer cases better without a second launch.  Results are
+ * bit-identical to bitnet_linear / bitnet_linear_segmented.
  *   gamma_per_block  0: one gamma; otherwise one per 16-row block (as bitnet_linear_segmented)
  *   which            BITNET_KERNEL_AUTO, any selector of bitnet_linear_variant (the workspace is then unused), or
  *                    BITNET_KERNEL_GEMM_SPLITK_n to force n splits (BITNET_ERR_WORKSPACE if the buffer is too small
@@ -238,8 +237,7 @@ bitnet_status bitnet_linear_describe(int64_t M, int64_t N, int64_t K, bitnet_for
  *   workspace        device memory, 16-byte aligned, or NULL (then this is bitnet_linear); contents are scratch:
  *                    nothing is expected in it and nothing of value is left; calls that share it must not overlap
  *   workspace_bytes  its size; bitnet_linear_workspace reports the size with which every split the model may want fits
- *                    (0 where split-K is never considered: above 64 tokens with 512 or more tiles of 64 x 128; up
- *                    to 64 tokens outside the range named above)
+ *                    (0 where split-K is never considered: up to 64 tokens, or 512 or more tiles of 64 x 128)
  */
 bitnet_status bitnet_linear_workspace(int64_t M, int64_t N, int64_t K, size_t* bytes);
 bitnet_status bitnet_linear_ws(const int8_t* xq, const float* sx, const void* packed, const float* gamma,

@@ -206,7 +206,7 @@ bitnet_status bitnet_linear_workspace(int64_t M, int64_t N, int64_t K, size_t* b
     if (!bytes) return BITNET_ERR_NULL;
     if (!shape_ok(M, N, K)) return BITNET_ERR_SHAPE;
     // prefill kernel: split-K is considered only where even 64 x 128 tiles leave workgroup slots empty (fewer than
-    // 512 of them); batched-decode kernels: 2 or 4 splits at 33 ... 64 tokens on layers with few rows and a long K
+    // 512 of them); the batched-decode kernels split only when forced
     const int64_t tiles = ((M + 63) / 64) * ((N + 127) / 128);
     const int skinny_splits = bitnet::skinny_splitk_splits(M, N, K);
     if (M > 64) *bytes = tiles < 512 ? bitnet::splitk_workspace_bytes(M, N, 8) : 0;

@@ -69,7 +69,7 @@ struct LaunchPlan {
 // linear_gemv.hip
 bool gemv_supports(int64_t M, int64_t N, int64_t K, const void* xq);
 // workspace (may be null) and force_splits as for launch_linear_gemm_2bit: split-K of the batched-decode kernels
-// (4 < M <= 64), taken by itself where skinny_splitk_splits() > 1 and the workspace holds that many partials
+// (4 < M <= 64); never taken by itself at present (skinny_splitk_splits() is 1 for every shape)
 int skinny_splitk_splits(int64_t M, int64_t N, int64_t K);
 hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                    int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream,

@@ -32,8 +32,9 @@ namespace bitnet {
 // the build checks that every instantiation compiles without scratch memory.
 template <int kMT, int kR, int kW, int kS, int kD, int kLx>
 __global__ __launch_bounds__(kS * kW * kWave) void linear_skinny_2bit(
-        const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
-        const float* __restrict__ gamma, int gstride, int M, int64_t N, int64_t K, int Kq, int RB, int spg,
+        const int8_t* __restrict__ xq_all, const float* __restrict__ sx_all, const uint4* __restrict__ packed,
+        const float* __restrict__ gamma, int gstride, int M_all /* blockIdx.z selects a tile of 16 * kMT tokens */,
+        int64_t N, int64_t K, int Kq, int RB, int spg,
         int steps_per_split /* blockIdx.y selects a run of K steps (split-K: int32 partials, [M][N] each, one after the
                                other at yv); one split: all steps */,
         void* __restrict__ yv, OutType yt) {
@@ -58,7 +59,13 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_skinny_2bit(
     const int steps = (Kq + 3) >> 2;
     const int tail_quads = 16 * (Kq - 4 * (steps - 1));
     const int step0 = blockIdx.y * steps_per_split, step1 = min(steps, step0 + steps_per_split);
-    void* y = static_cast<char*>(yv) + (int64_t)blockIdx.y * M * N * 4;
+    // this workgroup's tokens: tile blockIdx.z of 16 * kMT (the launcher may tile M finer than it has to: with few row
+    // blocks several workgroups that each stage a quarter of x_q move less through the L2 than one that stages all)
+    const int m0 = blockIdx.z * (16 * kMT);
+    const int M = min(M_all - m0, 16 * kMT);
+    const int8_t* xq = xq_all + (int64_t)m0 * K;
+    const float* sx = sx_all + m0;
+    void* y = static_cast<char*>(yv) + (int64_t)blockIdx.y * M_all * N * 4 + (int64_t)m0 * N * (yt == OutType::BF16 ? 2 : 4);
     const int s_begin = step0 + ks * spg;                              // this group's steps: s_begin + [0, n_here)
     const int n_here = max(0, min(spg, step1 - s_begin));
     const int rbw = (blockIdx.x * kW + wv) * kR;
@@ -232,8 +239,8 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_skinny_2bit(
 // Everything else (K groups, kR row blocks per wave, swizzled LDS tiles, fold) is as above.
 template <int kMT, int kR, int kW, int kS, int kD, int kLx>
 __global__ __launch_bounds__((kS * kW + 1) * kWave) void linear_skinny_ws_2bit(
-        const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
-        const float* __restrict__ gamma, int gstride, int M, int64_t N, int64_t K, int Kq, int RB, int spg,
+        const int8_t* __restrict__ xq_all, const float* __restrict__ sx_all, const uint4* __restrict__ packed,
+        const float* __restrict__ gamma, int gstride, int M_all, int64_t N, int64_t K, int Kq, int RB, int spg,
         int steps_per_split /* as in linear_skinny_2bit */, void* __restrict__ yv, OutType yt) {
 #if defined(__HIP_DEVICE_COMPILE__)      // the buffer-resource builtins exist in the device pass only
     extern __shared__ uint4 smem[];
@@ -253,7 +260,13 @@ __global__ __launch_bounds__((kS * kW + 1) * kWave) void linear_skinny_ws_2bit(
     const int tail_quads = 16 * (Kq - 4 * (steps - 1));
     const int padded = (spg + kD - 1) / kD * kD;       // barriers per wave: the same for both roles
     const int step0 = blockIdx.y * steps_per_split, step1 = min(steps, step0 + steps_per_split);
-    void* y = static_cast<char*>(yv) + (int64_t)blockIdx.y * M * N * 4;
+    // this workgroup's tokens: tile blockIdx.z of 16 * kMT (the launcher may tile M finer than it has to: with few row
+    // blocks several workgroups that each stage a quarter of x_q move less through the L2 than one that stages all)
+    const int m0 = blockIdx.z * (16 * kMT);
+    const int M = min(M_all - m0, 16 * kMT);
+    const int8_t* xq = xq_all + (int64_t)m0 * K;
+    const float* sx = sx_all + m0;
+    void* y = static_cast<char*>(yv) + (int64_t)blockIdx.y * M_all * N * 4 + (int64_t)m0 * N * (yt == OutType::BF16 ? 2 : 4);
 
     v4i acc[kR][kMT];
 #pragma unroll
@@ -435,9 +448,9 @@ static hipError_t launch_skinny(const int8_t* xq, const float* sx, const void* p
     splits = (int)ceil_div(steps, sps);                 // no empty split
     const int spg = (int)ceil_div(sps, kS);
     const bool split = splits > 1;                      // then int32 partials go to the workspace and a second launch adds them
-    dim3 grid((unsigned)ceil_div(RB, kW * kR), (unsigned)splits);
+    dim3 grid((unsigned)ceil_div(RB, kW * kR), (unsigned)splits, (unsigned)ceil_div(M, 16 * kMT));
     if (plan) {
-        plan->set("batched_decode", {kMT, kR, kW, kS, kD, kLx}, grid.x, grid.y, kS * kW * kWave, lds, splits);
+        plan->set("batched_decode", {kMT, kR, kW, kS, kD, kLx}, grid.x * grid.z, grid.y, kS * kW * kWave, lds, splits);
         return hipSuccess;
     }
     hipLaunchKernelGGL(kern, grid, dim3(kS * kW * kWave), lds, stream, xq, sx, static_cast<const uint4*>(packed), gamma,
@@ -468,9 +481,9 @@ static hipError_t launch_skinny_ws(const int8_t* xq, const float* sx, const void
     splits = (int)ceil_div(steps, sps);                 // no empty split
     const int spg = (int)ceil_div(sps, kS);
     const bool split = splits > 1;                      // then int32 partials go to the workspace and a second launch adds them
-    dim3 grid((unsigned)ceil_div(RB, kW * kR), (unsigned)splits);
+    dim3 grid((unsigned)ceil_div(RB, kW * kR), (unsigned)splits, (unsigned)ceil_div(M, 16 * kMT));
     if (plan) {
-        plan->set("batched_decode_loader", {kMT, kR, kW, kS, kD, kLx}, grid.x, grid.y, (kS * kW + 1) * kWave, lds, splits);
+        plan->set("batched_decode_loader", {kMT, kR, kW, kS, kD, kLx}, grid.x * grid.z, grid.y, (kS * kW + 1) * kWave, lds, splits);
         return hipSuccess;
     }
     hipLaunchKernelGGL(kern, grid, dim3((kS * kW + 1) * kWave), lds, stream, xq, sx, static_cast<const uint4*>(packed), gamma,
@@ -479,15 +492,14 @@ static hipError_t launch_skinny_ws(const int8_t* xq, const float* sx, const void
         return launch_splitk_reduce(static_cast<const int32_t*>(workspace), splits, sx, gamma, gstride, 0, M, N, y, yt, stream);
     return hipGetLastError();
 }
-// Split-K of the batched-decode kernels, taken when the caller provides a workspace.  With few row blocks every
-// workgroup pulls all of x_q through its LDS with one K step of lookahead, and that latency chain, not HBM, sets the
-// time; splitting K over workgroups shortens the chain at the price of a second launch that adds the int32 partials.
-// Measured on MI355X it pays from 33 tokens on, for K >= 16384 and at most 512 row blocks (LLaMA-30B / 70B down
-// projections: 24.8 -> 22.6 us and 37.9 -> 33.8 us at 64 tokens; N = 4096, K = 22016: 29.1 -> 21.5 us).
+// Split-K of the batched-decode kernels: blockIdx.y takes a run of K steps, int32 partials go to the workspace and the
+// prefill kernel's second launch adds them.  It exists as a forced variant only: what it was built for -- few row
+// blocks and a long K, where every workgroup pulls all of x_q through its LDS -- is served better by tiling the tokens
+// over workgroups (launch_linear_gemv_2bit below), which cuts the same traffic without a second launch (64 tokens,
+// 22016 -> 4096: 29.1 us as one tile, 21.5 us with four splits, 15.9 us with four token tiles).
 int skinny_splitk_splits(int64_t M, int64_t N, int64_t K) {
-    const int64_t RB = ceil_div(N, kRowsPerBlock);
-    if (M <= 32 || M > 64 || RB > 512 || K < 16384) return 1;
-    return RB <= 256 ? 4 : 2;
+    (void)M; (void)N; (void)K;
+    return 1;
 }
 
 hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void* packed,
@@ -510,17 +522,41 @@ hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void
     return launch_skinny<__VA_ARGS__>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, splits, workspace, plan)
 #define SKINNY_WS(...) \
     return launch_skinny_ws<__VA_ARGS__>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, splits, workspace, plan)
-    // Row blocks per workgroup (kW * kR): the smallest count with which the launch is at most 256 workgroups, one per
-    // CU.  The activation rings take 48-128 KB of LDS, so a CU often holds a single workgroup and any more run as a
-    // second round (600 workgroups of one row block: 9.3 us where 150 of four take 5.5 us); and where several do fit,
-    // a CU streams at a fixed rate however many it holds, so 288 workgroups leave 32 CUs with twice the work of the
-    // others (13B gate / up at 8 tokens: 14.0 us with six row blocks per workgroup, 9.5 us with eight).  Beyond 4096
-    // row blocks sixteen per workgroup, the most a form has, measured best.  The kernel forms per size come from
-    // sweeps over the 3B ... 70B LLaMA family shapes (31 forms, 8 ... 64 tokens).
-    int rpw = 16;
+    // Token tile (16 * kMT tokens per workgroup, grid z walks the tiles) and row blocks per workgroup (kW * kR).
+    //   * One round of workgroups: the activation rings take 48-128 KB of LDS, so a CU often holds a single workgroup
+    //     and any beyond 256 run as a second round (600 workgroups of one row block: 9.3 us where 150 of four take
+    //     5.5 us); and where several do fit, a CU streams at a fixed rate however many it holds, so 288 workgroups
+    //     leave 32 CUs with twice the work of the others (13B gate / up at 8 tokens: 14.0 us with six row blocks per
+    //     workgroup, 9.5 us with eight).  So: the fewest row blocks per workgroup that give at most 256 workgroups;
+    //     beyond 4096 row blocks sixteen, the most a form has.
+    //   * With few row blocks the traffic that counts is x_q through the L2s: every workgroup stages all K columns of
+    //     its tokens, 16 kMT K bytes against 4 K per row block of weights.  One tile of 64 tokens per workgroup and
+    //     256 workgroups of one row block move 17408 K bytes; four tiles of 16 tokens and 64 x 4 workgroups of four row
+    //     blocks move 8192 K (7B down projection at 64 tokens: 15.4 -> 10.0 us; 13B down at 48: 19.9 -> 11.2 us).  Up to
+    //     1024 row blocks the tile is therefore the one with the least such traffic among the one-round launches.
+    // The kernel forms per size come from sweeps over the 3B ... 70B LLaMA family shapes (31 forms, 8 ... 64 tokens).
+    const int kmt_full = M <= 16 ? 1 : M <= 32 ? 2 : 4;            // the smallest tile that holds all tokens
+    int kmt = kmt_full, rpw = 16;
     for (const int c : {8, 6, 4, 2, 1})
         if (ceil_div(RBc, c) <= 256) rpw = c;
-    if (M <= 16) {
+    if (RBc <= 1024 && kmt_full > 1) {
+        int64_t best = 0, best_wgs = 0;
+        for (const int t : {1, 2, 4}) {
+            if (t > kmt_full) break;
+            const int64_t tiles = ceil_div(M, 16 * t);
+            for (const int c : {1, 2, 4, 6, 8}) {
+                const int64_t wgs = ceil_div(RBc, c) * tiles;
+                if (wgs > 256) continue;
+                const int64_t traffic = wgs * (16 * t + 4 * c);
+                // equal traffic: more workgroups, then the larger tile (its form splits K over more waves)
+                if (best == 0 || traffic < best || (traffic == best && wgs >= best_wgs)) {
+                    best = traffic; best_wgs = wgs; kmt = t; rpw = c;
+                }
+                break;                                          // the most workgroups that still make one round
+            }
+        }
+    }
+    if (kmt == 1) {
         if (rpw == 16)     SKINNY(1, 4, 4, 2, 2, 2);
         else if (rpw == 8) SKINNY(1, 2, 4, 2, 2, 2);
         else if (rpw == 6) SKINNY(1, 3, 2, 4, 2, 2);
@@ -533,7 +569,7 @@ hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void
             else SKINNY(1, 1, 2, 8, 2, 2);
         }
         else               SKINNY(1, 1, 1, 8, 2, 2);
-    } else if (M <= 32) {
+    } else if (kmt == 2) {
         // from six row blocks on, the form with a loader wave (weights 3 steps deep in flight per wave)
         if (rpw == 16)     SKINNY_WS(2, 4, 4, 1, 4, 3);
         else if (rpw == 8) SKINNY_WS(2, 2, 4, 1, 4, 3);

@@ -40,37 +40,56 @@ def test_decode_shapes_do_not_pad_the_k_walk(name, N, K):
         assert xsrc in (0, 1) and (xsrc == 0 or 128 + M * steps * 256 <= 60 * 1024)
 
 
+def _one_round_rpw(RB, tiles):
+    """the fewest row blocks per workgroup with which the launch is at most one workgroup per CU (None: no such form)"""
+    for c in (1, 2, 4, 6, 8, 16):
+        if ceil_div(RB, c) * tiles <= CUS:
+            return c
+    return None
+
+
 @pytest.mark.parametrize("name,N,K", SHAPES)
 def test_batched_decode_is_one_round_of_workgroups(name, N, K):
-    """5 ... 64 tokens: the smallest token tile that holds M, activation rings within a CU's LDS, and up to 4096 row
-    blocks at most one workgroup per CU with the fewest row blocks per workgroup that achieves it."""
+    """5 ... 64 tokens: activation rings within a CU's LDS; up to 4096 row blocks at most one workgroup per CU, with
+    the fewest row blocks per workgroup that achieve it for the token tile taken; the tile is the smallest that holds M
+    except on layers of up to 1024 row blocks, where a finer tile (several workgroups per row group, grid z) is
+    taken when that moves less x_q + weight traffic through the L2s."""
     RB = ceil_div(N, 16)
     for M in (5, 8, 16, 17, 32, 33, 48, 64):
         d = B.linear_describe(M, N, K)
         assert d["kernel"] in ("batched_decode", "batched_decode_loader") and d["splits"] == 1, (name, M, d)
         kMT, kR, kW, kS, kD, kLx = d["params"]
-        assert kMT == (1 if M <= 16 else 2 if M <= 32 else 4)
+        full = 1 if M <= 16 else 2 if M <= 32 else 4
+        assert kMT in (1, 2, 4) and kMT <= full
+        if RB > 1024 or M <= 16:
+            assert kMT == full
+        tiles = ceil_div(M, 16 * kMT)
         assert d["lds"] == kS * (kLx + 1) * kMT * 4096 <= LDS_PER_CU
         assert d["block"] == 64 * (kS * kW + (d["kernel"] == "batched_decode_loader")) <= 1024
         rpw = kR * kW
-        assert d["grid"] == (ceil_div(RB, rpw), 1)
+        assert d["grid"] == (ceil_div(RB, rpw) * tiles, 1)
         if RB <= 4096:
             assert d["grid"][0] <= CUS, (name, M, d)
-            smaller = [c for c in (1, 2, 4, 6, 8, 16) if c < rpw]
-            assert all(ceil_div(RB, c) > CUS for c in smaller), (name, M, d)
+            assert rpw == _one_round_rpw(RB, tiles), (name, M, d)
+        if RB <= 1024:
+            traffic = lambda t, c: ceil_div(RB, c) * ceil_div(M, 16 * t) * (16 * t + 4 * c)
+            assert traffic(kMT, rpw) <= traffic(full, _one_round_rpw(RB, 1)), (name, M, d)
 
 
-def test_batched_decode_split_k_only_for_long_k_and_few_rows():
-    ws4 = lambda M, N: 4 * M * N * 4
-    d = B.linear_describe(64, 4096, 22016, workspace_bytes=ws4(64, 4096))
-    assert d["splits"] == 4 and d["grid"][1] == 4 and d["grid"][0] * 4 <= CUS
-    d = B.linear_describe(48, 8192, 28672, workspace_bytes=2 * 48 * 8192 * 4)
-    assert d["splits"] == 2 and d["grid"][1] == 2
-    assert B.linear_describe(64, 4096, 22016, workspace_bytes=1024)["splits"] == 1          # workspace too small
-    assert B.linear_describe(64, 4096, 22016)["splits"] == 1                                # none
-    assert B.linear_describe(64, 4096, 11008, workspace_bytes=ws4(64, 4096))["splits"] == 1  # K too short to pay
-    assert B.linear_describe(32, 4096, 22016, workspace_bytes=ws4(32, 4096))["splits"] == 1  # too few tokens
-    assert B.linear_describe(64, 22016, 16384, workspace_bytes=ws4(64, 22016))["splits"] == 1  # enough row blocks
+def test_batched_decode_token_tiles_on_small_layers():
+    """the measured cases: 7B down at 64 and 32 tokens, 13B down at 48, 70B O at 64"""
+    assert B.linear_describe(64, 4096, 11008)["params"][:3] == [1, 2, 2] and B.linear_describe(64, 4096, 11008)["grid"] == (256, 1)
+    assert B.linear_describe(32, 4096, 11008)["params"][:3] == [1, 1, 2]
+    assert B.linear_describe(48, 5120, 13824)["params"][:3] == [1, 2, 2] and B.linear_describe(48, 5120, 13824)["grid"] == (240, 1)
+    assert B.linear_describe(64, 8192, 8192)["grid"] == (256, 1)
+    assert B.linear_describe(64, 22016, 4096)["params"][0] == 4          # many row blocks: one tile of 64 tokens
+
+
+def test_batched_decode_never_splits_by_itself():
+    """token tiles over workgroups do what split-K was for, without its second launch"""
+    for (M, N, K) in [(64, 4096, 22016), (48, 8192, 28672), (64, 4096, 11008), (33, 3200, 8640)]:
+        assert B.linear_describe(M, N, K, workspace_bytes=8 * M * N * 4)["splits"] == 1
+        assert B.linear_workspace(M, N, K) == 0
 
 
 def test_prefill_tiles_follow_the_measured_cases():
