@@ -101,7 +101,7 @@ typedef enum bitnet_format {
 typedef enum bitnet_kernel {
     BITNET_KERNEL_AUTO = 0,
     BITNET_KERNEL_REFERENCE = 1, /* one thread per output, any shape; the slow, obviously right one */
-    BITNET_KERNEL_GEMV = 2,      /* weight-streaming decode kernel, M <= 64 */
+    BITNET_KERNEL_GEMV = 2,      /* weight-streaming decode kernels: M <= 64, on small layers up to 256 */
     BITNET_KERNEL_GEMM = 3,      /* LDS-tiled int8 MFMA prefill kernel, tile shape picked by shape */
     /* the prefill kernel with a fixed workgroup tile (tokens x weight rows): for tuning and tests */
     BITNET_KERNEL_GEMM_128x256 = 0x142,
@@ -110,7 +110,7 @@ typedef enum bitnet_kernel {
     BITNET_KERNEL_GEMM_128x128 = 0x141,
     BITNET_KERNEL_GEMM_96x128 = 0x131,
     BITNET_KERNEL_GEMM_64x128 = 0x121,
-    /* bitnet_linear_ws only: the K steps split over 2, 4 or 8 workgroups per tile (prefill kernel; with 5 ... 64 tokens
+    /* bitnet_linear_ws only: the K steps split over 2, 4 or 8 workgroups per tile (prefill kernel; where the batched-decode kernels serve the shape,
        the batched-decode kernels) */
     BITNET_KERNEL_GEMM_SPLITK_2 = 0x202,
     BITNET_KERNEL_GEMM_SPLITK_4 = 0x204,
@@ -189,8 +189,9 @@ bitnet_status bitnet_swiglu_quantize(const void* gu, bitnet_dtype gu_dtype, int6
  *   gamma    1 float (device)
  *   y        out [M][N]; y_dtype F32, BF16 (round-to-nearest-even of the fp32 value) or I32 (the raw
  *            accumulator, no scaling); element-aligned
- * The kernel is chosen by shape: the weight-streaming GEMV for M <= 64, the MFMA GEMM above, the
- * reference kernel when xq is not 16-byte aligned or K is not a multiple of 16.
+ * The kernel is chosen by shape: the weight-streaming decode kernels for M <= 64 (and up to 256 tokens on layers
+ * small enough that 256 workgroups of token tiles cover them: up to 8192-12288 output features), the MFMA GEMM
+ * above, the reference kernel when xq is not 16-byte aligned or K is not a multiple of 16.
  */
 bitnet_status bitnet_linear(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                             int64_t M, int64_t N, int64_t K, bitnet_format f,
@@ -211,7 +212,7 @@ bitnet_status bitnet_linear_variant(const int8_t* xq, const float* sx, const voi
  *         splits=<n>", zero-terminated; BITNET_ERR_WORKSPACE if text_bytes is too small (128 is enough)
  *   families and their parameters:
  *     decode                 M <= 4: row blocks per wave, K waves, row slots, prefetch depth, x_q source (0 global, 1 LDS)
- *     batched_decode         5 ... 64 tokens: token tiles of 16, row blocks per wave, row slots, K groups, prefetch
+ *     batched_decode         5 ... 256 tokens: token tiles of 16, row blocks per wave, row slots, K groups, prefetch
  *     batched_decode_loader  depth, LDS lookahead (the second form has a wave that only copies activations)
  *     prefill                tile tokens, tile rows; grid y = split-K factor
  *     reference, trit5_decode, trit5_reference: no parameters
@@ -226,18 +227,19 @@ bitnet_status bitnet_linear_describe(int64_t M, int64_t N, int64_t K, bitnet_for
  * accumulators there; a second launch adds them (exact, independent of the split) and rescales.  Chosen by the same
  * cost model as the tile shape, only where it pays: long K, few tiles (measured on MI355X, M = 128: 11008 -> 4096 in
  * 18.1 instead of 25.4 us, 28672 -> 8192 in 40.7 instead of 70.9 us; nothing to gain at K = 4096 or from 512 tokens
- * on).  The batched-decode kernels (5 ... 64 tokens) can split the same way when forced, but never do by themselves:
+ * on).  The batched-decode kernels can split the same way when forced, but never do by themselves:
  * tiling the tokens over workgroups serves their small-layer cases better without a second launch.  Results are
  * bit-identical to bitnet_linear / bitnet_linear_segmented.
  *   gamma_per_block  0: one gamma; otherwise one per 16-row block (as bitnet_linear_segmented)
  *   which            BITNET_KERNEL_AUTO, any selector of bitnet_linear_variant (the workspace is then unused), or
  *                    BITNET_KERNEL_GEMM_SPLITK_n to force n splits (BITNET_ERR_WORKSPACE if the buffer is too small
  *                    or K has fewer than n steps of 256 columns); the split then runs on the kernel family the
- *                    automatic choice takes for M: batched decode at 5 ... 64 tokens, else the prefill kernel
+ *                    automatic choice takes for the shape: batched decode from 5 tokens on where it serves it, else the prefill kernel
  *   workspace        device memory, 16-byte aligned, or NULL (then this is bitnet_linear); contents are scratch:
  *                    nothing is expected in it and nothing of value is left; calls that share it must not overlap
  *   workspace_bytes  its size; bitnet_linear_workspace reports the size with which every split the model may want fits
- *                    (0 where split-K is never considered: up to 64 tokens, or 512 or more tiles of 64 x 128)
+ *                    (0 where split-K is never considered: shapes the decode kernels serve, or 512 or more tiles
+ *                    of 64 x 128)
  */
 bitnet_status bitnet_linear_workspace(int64_t M, int64_t N, int64_t K, size_t* bytes);
 bitnet_status bitnet_linear_ws(const int8_t* xq, const float* sx, const void* packed, const float* gamma,

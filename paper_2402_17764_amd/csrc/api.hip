@@ -209,8 +209,10 @@ bitnet_status bitnet_linear_workspace(int64_t M, int64_t N, int64_t K, size_t* b
     // 512 of them); the batched-decode kernels split only when forced
     const int64_t tiles = ((M + 63) / 64) * ((N + 127) / 128);
     const int skinny_splits = bitnet::skinny_splitk_splits(M, N, K);
-    if (M > 64) *bytes = tiles < 512 ? bitnet::splitk_workspace_bytes(M, N, 8) : 0;
-    else *bytes = skinny_splits > 1 ? bitnet::splitk_workspace_bytes(M, N, skinny_splits) : 0;
+    // (the batched-decode kernels serve up to 256 tokens on small layers; x_q is assumed aligned here)
+    if (K % 16 != 0) *bytes = 0;                       // the reference kernel runs such shapes
+    else if (bitnet::gemv_supports(M, N, K, nullptr)) *bytes = skinny_splits > 1 ? bitnet::splitk_workspace_bytes(M, N, skinny_splits) : 0;
+    else *bytes = tiles < 512 ? bitnet::splitk_workspace_bytes(M, N, 8) : 0;
     return BITNET_OK;
 }
 
@@ -229,8 +231,8 @@ bitnet_status bitnet_linear_ws(const int8_t* xq, const float* sx, const void* pa
     if (!xq || !sx || !packed || !gamma || !y) return BITNET_ERR_NULL;
     if (!shape_ok(M, N, K)) return BITNET_ERR_SHAPE;
     if (workspace && !aligned(workspace, 16)) return BITNET_ERR_ALIGN;
-    // a forced split runs on the kernel family the automatic choice would take for this M: the batched-decode
-    // kernels at 5 ... 64 tokens, the prefill kernel otherwise (the M <= 4 decode kernel has no split form)
+    // a forced split runs on the kernel family the automatic choice would take for this shape: the batched-decode
+    // kernels from 5 tokens on where they serve it, the prefill kernel otherwise (the M <= 4 decode kernel has no split form)
     const bool skinny_path = f == BITNET_PACK_2BIT && M > 4 && bitnet::gemv_supports(M, N, K, xq) &&
                              (force || (workspace && bitnet::skinny_splitk_splits(M, N, K) > 1));
     const bool gemm_path = f == BITNET_PACK_2BIT && !skinny_path && (force || !bitnet::gemv_supports(M, N, K, xq)) &&

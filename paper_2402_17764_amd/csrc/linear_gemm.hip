@@ -469,7 +469,8 @@ hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void
     //   * kFixed covers launch, prologue and epilogue.
     // Ties within 4 % go to the larger tile (less decode work and fewer activation re-reads per output).
     // Examples (13B o projection, N = K = 5120): M = 512 runs 96 x 128 tiles in 19.6 us (64 x 256: 23.6 us,
-    // 128 x 256: 36 us); M = 128 runs 64 x 128 tiles in 15.2 us (22.9 us); M = 2048 stays on 96 x 256 tiles.
+    // 128 x 256: 36 us); M = 2048 stays on 96 x 256 tiles.  (Up to 256 tokens such small layers go to the
+    // batched-decode kernels instead, which tile the tokens over workgroups.)
     // With a workspace the K steps may also be split over 2, 4 or 8 workgroups per tile (each stores int32 partial
     // accumulators, a second launch adds them and rescales): the same model with steps / splits per workgroup and
     // tiles * splits workgroups, plus the second launch (a few microseconds and the partials' traffic).  It pays where

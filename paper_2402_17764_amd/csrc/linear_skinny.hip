@@ -421,10 +421,68 @@ __global__ __launch_bounds__((kS * kW + 1) * kWave) void linear_skinny_ws_2bit(
 // ---------------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------------
+constexpr int64_t kSkinnyMaxTokens = 256;      // beyond 64 tokens only where one round of workgroups exists (few row blocks)
+
+// Token tile (16 * kmt tokens per workgroup, grid z walks the tiles) and row blocks per workgroup (rpw = kW * kR).
+//   * One round of workgroups: the activation rings take 48-128 KB of LDS, so a CU often holds a single workgroup
+//     and any beyond 256 run as a second round (600 workgroups of one row block: 9.3 us where 150 of four take
+//     5.5 us); and where several do fit, a CU streams at a fixed rate however many it holds, so 288 workgroups leave
+//     32 CUs with twice the work of the others (13B gate / up at 8 tokens: 14.0 us with six row blocks per workgroup,
+//     9.5 us with eight).  So: the fewest row blocks per workgroup that give at most 256 workgroups; beyond 4096
+//     row blocks sixteen, the most a form has.
+//   * With few row blocks the traffic that counts is x_q through the L2s: every workgroup stages all K columns of
+//     its tokens, 16 kmt K bytes against 4 K per row block of weights.  One tile of 64 tokens per workgroup and 256
+//     workgroups of one row block move 17408 K bytes; four tiles of 16 tokens and 64 x 4 workgroups of four row
+//     blocks move 8192 K (7B down projection at 64 tokens: 15.4 -> 10.0 us; 13B down at 48: 19.9 -> 11.2 us).  Up to
+//     1024 row blocks the tile is therefore the one with the least such traffic among the one-round launches.
+//   * The same tiling carries these kernels past 64 tokens: up to 256 tokens, where a one-round launch with at most
+//     eight row blocks per workgroup exists (layers of up to 512-768 row blocks), they beat the prefill kernel, whose
+//     tiles leave most CUs idle there (7B down at 128 tokens: 13.6 us against 35.9 us, 20.7 us with split-K; 70B O
+//     at 256: 22.7 against 28.0 us).  Tiles of 32 tokens while six row blocks per workgroup suffice, else of 64:
+//     the measured best on 30 of 36 cases.
+// Returns false where these kernels should not run (above 64 tokens and no such launch); kmt and rpw are valid anyway.
+static bool skinny_shape(int64_t M, int64_t RBc, int* kmt_out, int* rpw_out) {
+    const int kmt_full = M <= 16 ? 1 : M <= 32 ? 2 : 4;            // the smallest tile that holds all tokens (64 at most)
+    int kmt = kmt_full, rpw = 16;
+    bool ok = true;
+    auto one_round = [&](int t) {
+        for (const int c : {1, 2, 4, 6, 8})
+            if (ceil_div(RBc, c) * ceil_div(M, 16 * t) <= 256) return c;
+        return 0;
+    };
+    if (M > 64) {
+        const int c2 = one_round(2), c4 = one_round(4);
+        if (c2 && c2 <= 6) { kmt = 2; rpw = c2; }
+        else if (c4) { kmt = 4; rpw = c4; }
+        else ok = false;
+    } else {
+        for (const int c : {8, 6, 4, 2, 1})
+            if (ceil_div(RBc, c) <= 256) rpw = c;
+        if (RBc <= 1024 && kmt_full > 1) {
+            int64_t best = 0, best_wgs = 0;
+            for (const int t : {1, 2, 4}) {
+                if (t > kmt_full) break;
+                const int c = one_round(t);                     // the most workgroups that still make one round
+                if (!c) continue;
+                const int64_t wgs = ceil_div(RBc, c) * ceil_div(M, 16 * t), traffic = wgs * (16 * t + 4 * c);
+                // equal traffic: more workgroups, then the larger tile (its form splits K over more waves)
+                if (best == 0 || traffic < best || (traffic == best && wgs >= best_wgs)) {
+                    best = traffic; best_wgs = wgs; kmt = t; rpw = c;
+                }
+            }
+        }
+    }
+    *kmt_out = kmt; *rpw_out = rpw;
+    return ok;
+}
+
 bool gemv_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
     // x_q offsets are 32-bit; one K step of the packed weights (1 KiB per 16-row block) is addressed as one raw buffer
-    return M >= 1 && M <= 64 && K % 16 == 0 && reinterpret_cast<uintptr_t>(xq) % 16 == 0 && M * K < ((int64_t)1 << 31) &&
-           ceil_div(N, kRowsPerBlock) < ((int64_t)1 << 21);
+    if (!(M >= 1 && M <= kSkinnyMaxTokens && K % 16 == 0 && reinterpret_cast<uintptr_t>(xq) % 16 == 0 &&
+          M * K < ((int64_t)1 << 31) && ceil_div(N, kRowsPerBlock) < ((int64_t)1 << 21)))
+        return false;
+    int kmt, rpw;
+    return skinny_shape(M, ceil_div(N, kRowsPerBlock), &kmt, &rpw);
 }
 
 template <int kMT, int kR, int kW, int kS, int kD, int kLx>
@@ -522,40 +580,9 @@ hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void
     return launch_skinny<__VA_ARGS__>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, splits, workspace, plan)
 #define SKINNY_WS(...) \
     return launch_skinny_ws<__VA_ARGS__>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, splits, workspace, plan)
-    // Token tile (16 * kMT tokens per workgroup, grid z walks the tiles) and row blocks per workgroup (kW * kR).
-    //   * One round of workgroups: the activation rings take 48-128 KB of LDS, so a CU often holds a single workgroup
-    //     and any beyond 256 run as a second round (600 workgroups of one row block: 9.3 us where 150 of four take
-    //     5.5 us); and where several do fit, a CU streams at a fixed rate however many it holds, so 288 workgroups
-    //     leave 32 CUs with twice the work of the others (13B gate / up at 8 tokens: 14.0 us with six row blocks per
-    //     workgroup, 9.5 us with eight).  So: the fewest row blocks per workgroup that give at most 256 workgroups;
-    //     beyond 4096 row blocks sixteen, the most a form has.
-    //   * With few row blocks the traffic that counts is x_q through the L2s: every workgroup stages all K columns of
-    //     its tokens, 16 kMT K bytes against 4 K per row block of weights.  One tile of 64 tokens per workgroup and
-    //     256 workgroups of one row block move 17408 K bytes; four tiles of 16 tokens and 64 x 4 workgroups of four row
-    //     blocks move 8192 K (7B down projection at 64 tokens: 15.4 -> 10.0 us; 13B down at 48: 19.9 -> 11.2 us).  Up to
-    //     1024 row blocks the tile is therefore the one with the least such traffic among the one-round launches.
-    // The kernel forms per size come from sweeps over the 3B ... 70B LLaMA family shapes (31 forms, 8 ... 64 tokens).
-    const int kmt_full = M <= 16 ? 1 : M <= 32 ? 2 : 4;            // the smallest tile that holds all tokens
-    int kmt = kmt_full, rpw = 16;
-    for (const int c : {8, 6, 4, 2, 1})
-        if (ceil_div(RBc, c) <= 256) rpw = c;
-    if (RBc <= 1024 && kmt_full > 1) {
-        int64_t best = 0, best_wgs = 0;
-        for (const int t : {1, 2, 4}) {
-            if (t > kmt_full) break;
-            const int64_t tiles = ceil_div(M, 16 * t);
-            for (const int c : {1, 2, 4, 6, 8}) {
-                const int64_t wgs = ceil_div(RBc, c) * tiles;
-                if (wgs > 256) continue;
-                const int64_t traffic = wgs * (16 * t + 4 * c);
-                // equal traffic: more workgroups, then the larger tile (its form splits K over more waves)
-                if (best == 0 || traffic < best || (traffic == best && wgs >= best_wgs)) {
-                    best = traffic; best_wgs = wgs; kmt = t; rpw = c;
-                }
-                break;                                          // the most workgroups that still make one round
-            }
-        }
-    }
+    // The kernel forms per size come from sweeps over the 3B ... 70B LLaMA family shapes (31 forms, 8 ... 256 tokens).
+    int kmt, rpw;
+    skinny_shape(M, RBc, &kmt, &rpw);
     if (kmt == 1) {
         if (rpw == 16)     SKINNY(1, 4, 4, 2, 2, 2);
         else if (rpw == 8) SKINNY(1, 2, 4, 2, 2, 2);

@@ -96,7 +96,8 @@ def test_host_validation_rejects_before_launch():
     assert lib.bitnet_swiglu_linear_fused(a, 0, a, a, 17, 16, 64, 0, a, 0, NULL) == 8
     szp = ctypes.c_size_t(7)
     assert lib.bitnet_linear_workspace(128, 4096, 11008, None) == 1
-    assert lib.bitnet_linear_workspace(128, 4096, 11008, ctypes.byref(szp)) == 0 and szp.value == 8 * 128 * 4096 * 4
+    assert lib.bitnet_linear_workspace(320, 4096, 11008, ctypes.byref(szp)) == 0 and szp.value == 8 * 320 * 4096 * 4
+    assert lib.bitnet_linear_workspace(128, 4096, 11008, ctypes.byref(szp)) == 0 and szp.value == 0   # batched decode serves it
     assert lib.bitnet_linear_workspace(64, 4096, 11008, ctypes.byref(szp)) == 0 and szp.value == 0
     assert lib.bitnet_linear_workspace(2048, 27648, 5120, ctypes.byref(szp)) == 0 and szp.value == 0
     assert lib.bitnet_linear_workspace(0, 4096, 11008, ctypes.byref(szp)) == 2
@@ -133,7 +134,8 @@ def test_host_validation_rejects_before_launch():
     # workspace
     assert lib.bitnet_quantize_weights(a, 0, 4, 4, 0, a, a, a, 8, NULL) == 6
     # a forced kernel that cannot take the shape
-    assert lib.bitnet_linear_variant(a, a, a, a, 65, 16, 64, 0, a, 0, binding.KERNEL_GEMV, NULL) == 8
+    assert lib.bitnet_linear_variant(a, a, a, a, 257, 16, 64, 0, a, 0, binding.KERNEL_GEMV, NULL) == 8
+    assert lib.bitnet_linear_variant(a, a, a, a, 100, 100000, 64, 0, a, 0, binding.KERNEL_GEMV, NULL) == 8   # too many rows
     assert lib.bitnet_linear_variant(odd, a, a, a, 1, 16, 64, 0, a, 0, binding.KERNEL_GEMV, NULL) == 8
     # fixed-tile selectors of the prefill kernel: tile codes outside the six built ones, or an operand it cannot take
     assert lib.bitnet_linear_variant(a, a, a, a, 65, 16, 64, 0, a, 0, 0x152, NULL) == 8

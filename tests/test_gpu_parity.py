@@ -234,7 +234,11 @@ GEMV_SHAPES = [(1, 4096, 1536), (16, 4096, 1536), (1, 16, 64), (1, 17, 16), (3, 
                (9, 5000, 528), (12, 5008, 8208), (20, 6000, 272), (50, 8000, 1040), (9, 26000, 272), (30, 28000, 144), (64, 30000, 528),
                # M <= 4: depth 5 where depth 4 would pad (34 K steps over four waves), two row blocks per wave from 512
                # row blocks on with more than one token
-               (2, 100, 8640), (3, 9000, 3200)]
+               (2, 100, 8640), (3, 9000, 3200),
+               # 65 ... 256 tokens on small layers: token tiles of 32 and of 64 over grid z, ragged last tiles, every
+               # form such launches can pick
+               (65, 40, 528), (96, 300, 2064), (100, 4000, 1040), (128, 6000, 272), (130, 8000, 528), (192, 3200, 784),
+               (200, 5120, 528), (250, 8000, 272), (256, 4096, 1296), (128, 12000, 144)]
 
 
 @pytest.mark.parametrize("M,N,K", GEMV_SHAPES)
@@ -539,7 +543,7 @@ def test_linear_splitk_batched_decode(gpu_lib, M, N, K):
 
 def test_linear_splitk_auto_and_segment_scales(gpu_lib):
     say("split-K: automatic choice, per-block scales, workspace query")
-    M, N, K = 128, 4096, 11008                           # 64 tiles of 64 x 128 and 43 K steps: the model splits
+    M, N, K = 257, 4096, 11008                           # 96 tiles of 96 x 128 and 43 K steps: the model splits
     assert gpu_lib.linear_workspace(M, N, K) == 8 * M * N * 4
     assert gpu_lib.linear_workspace(64, N, K) == 0 and gpu_lib.linear_workspace(2048, 27648, 5120) == 0
     W = synth.weights(N, K, config=2, layer=1, tensor=3)
