@@ -101,7 +101,7 @@ typedef enum bitnet_format {
 typedef enum bitnet_kernel {
     BITNET_KERNEL_AUTO = 0,
     BITNET_KERNEL_REFERENCE = 1, /* one thread per output, any shape; the slow, obviously right one */
-    BITNET_KERNEL_GEMV = 2,      /* weight-streaming decode kernels: M <= 64, on small layers up to 256 */
+    BITNET_KERNEL_GEMV = 2,      /* weight-streaming decode kernels: M <= 64, on small layers up to 512 */
     BITNET_KERNEL_GEMM = 3,      /* LDS-tiled int8 MFMA prefill kernel, tile shape picked by shape */
     /* the prefill kernel with a fixed workgroup tile (tokens x weight rows): for tuning and tests */
     BITNET_KERNEL_GEMM_128x256 = 0x142,
@@ -189,9 +189,9 @@ bitnet_status bitnet_swiglu_quantize(const void* gu, bitnet_dtype gu_dtype, int6
  *   gamma    1 float (device)
  *   y        out [M][N]; y_dtype F32, BF16 (round-to-nearest-even of the fp32 value) or I32 (the raw
  *            accumulator, no scaling); element-aligned
- * The kernel is chosen by shape: the weight-streaming decode kernels for M <= 64 (and up to 256 tokens on layers
- * small enough that 256 workgroups of token tiles cover them: up to 8192-12288 output features), the MFMA GEMM
- * above, the reference kernel when xq is not 16-byte aligned or K is not a multiple of 16.
+ * The kernel is chosen by shape: the weight-streaming decode kernels for M <= 64 (and up to 256 tokens, with
+ * K >= 5120 up to 512, on layers small enough that 256 workgroups of token tiles cover them: up to 4096-12288 output
+ * features), the MFMA GEMM above, the reference kernel when xq is not 16-byte aligned or K is not a multiple of 16.
  */
 bitnet_status bitnet_linear(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                             int64_t M, int64_t N, int64_t K, bitnet_format f,
@@ -212,7 +212,7 @@ bitnet_status bitnet_linear_variant(const int8_t* xq, const float* sx, const voi
  *         splits=<n>", zero-terminated; BITNET_ERR_WORKSPACE if text_bytes is too small (128 is enough)
  *   families and their parameters:
  *     decode                 M <= 4: row blocks per wave, K waves, row slots, prefetch depth, x_q source (0 global, 1 LDS)
- *     batched_decode         5 ... 256 tokens: token tiles of 16, row blocks per wave, row slots, K groups, prefetch
+ *     batched_decode         5 ... 512 tokens: token tiles of 16, row blocks per wave, row slots, K groups, prefetch
  *     batched_decode_loader  depth, LDS lookahead (the second form has a wave that only copies activations)
  *     prefill                tile tokens, tile rows; grid y = split-K factor
  *     reference, trit5_decode, trit5_reference: no parameters

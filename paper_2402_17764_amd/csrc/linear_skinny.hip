@@ -421,7 +421,7 @@ __global__ __launch_bounds__((kS * kW + 1) * kWave) void linear_skinny_ws_2bit(
 // ---------------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------------
-constexpr int64_t kSkinnyMaxTokens = 256;      // beyond 64 tokens only where one round of workgroups exists (few row blocks)
+constexpr int64_t kSkinnyMaxTokens = 512;      // beyond 64 tokens only where one round of workgroups exists (few row blocks)
 
 // Token tile (16 * kmt tokens per workgroup, grid z walks the tiles) and row blocks per workgroup (rpw = kW * kR).
 //   * One round of workgroups: the activation rings take 48-128 KB of LDS, so a CU often holds a single workgroup
@@ -439,7 +439,8 @@ constexpr int64_t kSkinnyMaxTokens = 256;      // beyond 64 tokens only where on
 //     eight row blocks per workgroup exists (layers of up to 512-768 row blocks), they beat the prefill kernel, whose
 //     tiles leave most CUs idle there (7B down at 128 tokens: 13.6 us against 35.9 us, 20.7 us with split-K; 70B O
 //     at 256: 22.7 against 28.0 us).  Tiles of 32 tokens while six row blocks per workgroup suffice, else of 64:
-//     the measured best on 30 of 36 cases.
+//     the measured best on 30 of 36 cases.  From 257 to 512 tokens the advantage remains only where K is long
+//     (K >= 5120: 7B down at 512 tokens 28.3 against 36.0 us; with K = 3200 the prefill kernel is 1.4x faster there).
 // Returns false where these kernels should not run (above 64 tokens and no such launch); kmt and rpw are valid anyway.
 static bool skinny_shape(int64_t M, int64_t RBc, int* kmt_out, int* rpw_out) {
     const int kmt_full = M <= 16 ? 1 : M <= 32 ? 2 : 4;            // the smallest tile that holds all tokens (64 at most)
@@ -481,6 +482,7 @@ bool gemv_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
     if (!(M >= 1 && M <= kSkinnyMaxTokens && K % 16 == 0 && reinterpret_cast<uintptr_t>(xq) % 16 == 0 &&
           M * K < ((int64_t)1 << 31) && ceil_div(N, kRowsPerBlock) < ((int64_t)1 << 21)))
         return false;
+    if (M > 256 && K < 5120) return false;          // a short K: the prefill kernel's few workgroups are done quickly
     int kmt, rpw;
     return skinny_shape(M, ceil_div(N, kRowsPerBlock), &kmt, &rpw);
 }

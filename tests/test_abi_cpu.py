@@ -96,7 +96,7 @@ def test_host_validation_rejects_before_launch():
     assert lib.bitnet_swiglu_linear_fused(a, 0, a, a, 17, 16, 64, 0, a, 0, NULL) == 8
     szp = ctypes.c_size_t(7)
     assert lib.bitnet_linear_workspace(128, 4096, 11008, None) == 1
-    assert lib.bitnet_linear_workspace(320, 4096, 11008, ctypes.byref(szp)) == 0 and szp.value == 8 * 320 * 4096 * 4
+    assert lib.bitnet_linear_workspace(520, 2048, 11008, ctypes.byref(szp)) == 0 and szp.value == 8 * 520 * 2048 * 4
     assert lib.bitnet_linear_workspace(128, 4096, 11008, ctypes.byref(szp)) == 0 and szp.value == 0   # batched decode serves it
     assert lib.bitnet_linear_workspace(64, 4096, 11008, ctypes.byref(szp)) == 0 and szp.value == 0
     assert lib.bitnet_linear_workspace(2048, 27648, 5120, ctypes.byref(szp)) == 0 and szp.value == 0

@@ -98,33 +98,34 @@ def test_prefill_tiles_follow_the_measured_cases():
     assert B.linear_describe(2048, 27648, 5120)["params"] == [128, 256]
     assert B.linear_describe(4096, 57344, 8192)["params"] == [128, 256]
     assert B.linear_describe(512, 5120, 5120)["params"] == [96, 128]
-    assert B.linear_describe(320, 5120, 5120)["params"] == [64, 128]
-    assert B.linear_describe(300, 4096, 11008)["params"] == [64, 128]
+    assert B.linear_describe(520, 5120, 5120)["params"] == [96, 128]
     for (M, N, K) in [(257, 3200, 3200), (300, 9600, 3200), (1024, 4096, 11008), (2048, 8192, 28672), (4096, 3200, 8640)]:
         d = B.linear_describe(M, N, K)
         tm, tn = d["params"]
         assert d["kernel"] == "prefill" and d["splits"] == 1 and d["block"] == 256
         assert d["grid"] == (ceil_div(M, tm) * ceil_div(N, tn), 1)
         assert d["lds"] <= LDS_PER_CU // 2                      # two workgroups per CU
-    big = 8 * 300 * 8192 * 4
-    d = B.linear_describe(257, 4096, 11008, workspace_bytes=big)
+    big = 8 * 520 * 8192 * 4
+    d = B.linear_describe(520, 2048, 11008, workspace_bytes=big)
     assert d["splits"] in (2, 4, 8) and d["grid"][1] == d["splits"]
     assert B.linear_describe(300, 8192, 28672, workspace_bytes=big)["splits"] > 1
-    assert B.linear_describe(257, 4096, 4096, workspace_bytes=big)["splits"] == 1       # K = 4096: nothing to gain
+    assert B.linear_describe(280, 6656, 17920, workspace_bytes=big)["splits"] > 1
+    assert B.linear_describe(520, 2048, 4096, workspace_bytes=big)["splits"] == 1       # K = 4096: nothing to gain
     assert B.linear_describe(2048, 4096, 11008, workspace_bytes=8 * 2048 * 4096 * 4)["splits"] == 1
-    assert B.linear_describe(257, 4096, 11008, workspace_bytes=2 * 257 * 4096 * 4)["splits"] <= 2   # what fits
+    assert B.linear_describe(520, 2048, 11008, workspace_bytes=2 * 520 * 2048 * 4)["splits"] <= 2   # what fits
 
 
 def test_batched_decode_beyond_64_tokens_only_as_one_round():
-    """65 ... 256 tokens: the decode kernels run where a launch of at most 256 workgroups with at most eight row blocks
-    each exists (tiles of 32 tokens while six row blocks suffice, else of 64); everything else is prefill."""
+    """65 ... 512 tokens (from 257 on only with K >= 5120): the decode kernels run where a launch of at most 256
+    workgroups with at most eight row blocks each exists (tiles of 32 tokens while six row blocks suffice, else of
+    64); everything else is prefill."""
     for (name, N, K) in SHAPES:
         RB = ceil_div(N, 16)
-        for M in (65, 96, 128, 192, 256, 257, 512):
+        for M in (65, 96, 128, 192, 256, 257, 384, 512, 513, 1024):
             d = B.linear_describe(M, N, K)
             c2 = next((c for c in (1, 2, 4, 6) if ceil_div(RB, c) * ceil_div(M, 32) <= CUS), None)
             c4 = next((c for c in (1, 2, 4, 6, 8) if ceil_div(RB, c) * ceil_div(M, 64) <= CUS), None)
-            if M > 256 or (c2 is None and c4 is None):
+            if M > 512 or (M > 256 and K < 5120) or (c2 is None and c4 is None):
                 assert d["kernel"] == "prefill", (name, M, d)
                 continue
             assert d["kernel"] in ("batched_decode", "batched_decode_loader"), (name, M, d)
@@ -132,6 +133,9 @@ def test_batched_decode_beyond_64_tokens_only_as_one_round():
             assert (kMT, kR * kW) == ((2, c2) if c2 else (4, c4)), (name, M, d)
             assert d["grid"] == (ceil_div(RB, kR * kW) * ceil_div(M, 16 * kMT), 1) and d["grid"][0] <= CUS
     assert B.linear_describe(128, 4096, 11008)["params"] == [2, 2, 2, 4, 2, 2]           # 7B down: 13.6 us, prefill 35.9
+    assert B.linear_describe(512, 4096, 11008)["params"] == [4, 2, 4, 1, 4, 2]           # 28.3 us, prefill 36.0
+    assert B.linear_describe(512, 4096, 4096)["kernel"] == "prefill"                     # short K
+    assert B.linear_describe(512, 5120, 13824)["kernel"] == "prefill"                    # 320 x 8 workgroups: two rounds
     assert B.linear_describe(256, 8192, 8192)["kernel"] == "batched_decode_loader"
     assert B.linear_describe(192, 12288, 4096)["kernel"] == "prefill"
     assert B.linear_describe(96, 22016, 4096)["kernel"] == "prefill"

@@ -238,7 +238,9 @@ GEMV_SHAPES = [(1, 4096, 1536), (16, 4096, 1536), (1, 16, 64), (1, 17, 16), (3, 
                # 65 ... 256 tokens on small layers: token tiles of 32 and of 64 over grid z, ragged last tiles, every
                # form such launches can pick
                (65, 40, 528), (96, 300, 2064), (100, 4000, 1040), (128, 6000, 272), (130, 8000, 528), (192, 3200, 784),
-               (200, 5120, 528), (250, 8000, 272), (256, 4096, 1296), (128, 12000, 144)]
+               (200, 5120, 528), (250, 8000, 272), (256, 4096, 1296), (128, 12000, 144),
+               # ... and up to 512 tokens where K >= 5120
+               (300, 3200, 5136), (512, 4096, 5120), (400, 2000, 5392)]
 
 
 @pytest.mark.parametrize("M,N,K", GEMV_SHAPES)
@@ -543,13 +545,13 @@ def test_linear_splitk_batched_decode(gpu_lib, M, N, K):
 
 def test_linear_splitk_auto_and_segment_scales(gpu_lib):
     say("split-K: automatic choice, per-block scales, workspace query")
-    M, N, K = 257, 4096, 11008                           # 96 tiles of 96 x 128 and 43 K steps: the model splits
+    M, N, K = 520, 2048, 11008                           # 96 tiles of 96 x 128 and 43 K steps: the model splits
     assert gpu_lib.linear_workspace(M, N, K) == 8 * M * N * 4
     assert gpu_lib.linear_workspace(64, N, K) == 0 and gpu_lib.linear_workspace(2048, 27648, 5120) == 0
     W = synth.weights(N, K, config=2, layer=1, tensor=3)
-    W[2048:] *= np.float32(0.5)
+    W[N // 2:] *= np.float32(0.5)
     x, bits = synth.activations(M, K, config=2, layer=1, tensor=103, bf16=True)
-    packed, gamma_rb = gpu_lib.quantize_weights_segmented(dev(W), [2048, 2048])
+    packed, gamma_rb = gpu_lib.quantize_weights_segmented(dev(W), [N // 2, N // 2])
     xq, sx = gpu_lib.quantize_acts(bf16_tensor(bits).view(M, K))
     ws = torch.empty(gpu_lib.linear_workspace(M, N, K), dtype=torch.uint8, device="cuda")
     ref = gpu_lib.linear_segmented(xq, sx, packed, gamma_rb, N, y_dtype=gpu_lib.BF16)
