@@ -266,27 +266,28 @@ def batched_decode_leg(torch, B, synth, gen, stream, args):
                                  "GB/s": round(gemv_bytes(M, N, K) / (us * 1e-6) / 1e9, 1),
                                  "TOPS": round(2.0 * M * N * K / us * 1e-6, 1)}
             del graph
-        # the serving regime just above the decode kernels: 128 tokens through the prefill kernel, without and with
-        # a split-K workspace (bitnet_linear_ws)
-        M = 128
-        x = make_acts(torch, M, K, gen, 2)
-        xq, sx = B.quantize_acts(x)
-        y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
-        ws = torch.empty(max(16, B.linear_workspace(M, N, K)), dtype=torch.uint8, device="cuda")
+        # the serving regime just above 64 tokens: small layers still run the token-tiled decode kernels, the others
+        # the prefill kernel, timed without and with a split-K workspace (bitnet_linear_ws)
+        for M in (128, 256):
+            x = make_acts(torch, M, K, gen, 2)
+            xq, sx = B.quantize_acts(x)
+            y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+            ws = torch.empty(max(16, B.linear_workspace(M, N, K)), dtype=torch.uint8, device="cuda")
 
-        def run_plain():
-            for (p, g) in packs:
-                B.linear(xq, sx, p, g, N, y_dtype=B.BF16, y=y)
+            def run_plain():
+                for (p, g) in packs:
+                    B.linear(xq, sx, p, g, N, y_dtype=B.BF16, y=y)
 
-        def run_ws():
-            for (p, g) in packs:
-                B.linear_ws(xq, sx, p, g, N, ws, y_dtype=B.BF16, y=y)
+            def run_ws():
+                for (p, g) in packs:
+                    B.linear_ws(xq, sx, p, g, N, ws, y_dtype=B.BF16, y=y)
 
-        ms_p, _, g1 = time_graph(torch, run_plain, max(2, args.warmup // 5), max(5, args.steps // 5), stream)
-        ms_w, _, g2 = time_graph(torch, run_ws, max(2, args.warmup // 5), max(5, args.steps // 5), stream)
-        entry["M=128"] = {"us_per_launch": round(ms_p * 1e3 / layers, 2), "us_with_workspace": round(ms_w * 1e3 / layers, 2),
-                          "TOPS": round(2.0 * M * N * K / (min(ms_p, ms_w) * 1e3 / layers) * 1e-6, 1)}
-        del g1, g2
+            ms_p, _, g1 = time_graph(torch, run_plain, max(2, args.warmup // 5), max(5, args.steps // 5), stream)
+            ms_w, _, g2 = time_graph(torch, run_ws, max(2, args.warmup // 5), max(5, args.steps // 5), stream)
+            entry["M=%d" % M] = {"us_per_launch": round(ms_p * 1e3 / layers, 2), "us_with_workspace": round(ms_w * 1e3 / layers, 2),
+                                 "TOPS": round(2.0 * M * N * K / (min(ms_p, ms_w) * 1e3 / layers) * 1e-6, 1),
+                                 "kernel": B.linear_describe(M, N, K)["kernel"]}
+            del g1, g2
         res[name] = entry
         del packs
         torch.cuda.empty_cache()
