@@ -558,12 +558,13 @@ static hipError_t dispatch16_int8(const void* x, const float* sx, const void* pa
     const int64_t RB = ceil_div(N, kRowsPerBlock), steps = ceil_div(K, 256);
     const float* gain = nullptr;
     const float eps = 0.0f;
-    const bool pads44 = walk_efficiency(steps, 4, 4) < 0.8;        // four waves at depth 4 would walk 25 % or more in vain
+    const bool pads44 = walk_efficiency(steps, 4, 4) < 0.75;       // four waves at depth 4 would walk over a third more than K
     if (RB >= 2048) {
         if (steps >= 32) GEMV16(4, 1, 4, 2, kModesInt8 | kModesFused | kModesPre, kXGlobal);
         else GEMV16(4, 1, 4, 3, kModesInt8, kXGlobal);
     } else if (RB >= 1024) {
-        if (steps < 16 && M == 1) GEMV16(1, 4, 1, 4, kModesInt8 | kModesFused | kModesPre, kXLds);
+        if (steps < 16 && M == 1 && !pads44) GEMV16(1, 4, 1, 4, kModesInt8 | kModesFused | kModesPre, kXLds);
+        else if (steps < 16 && M == 1) GEMV16(2, 2, 2, 4, kModesInt8 | kModesPre, kXGlobal);      // e.g. 8 steps: 2 x 4, no padding
         else if (!pads44) GEMV16(2, 4, 1, 4, kModesInt8, kXGlobal);
         else GEMV16(2, 1, 4, 4, kModesInt8 | kModesFused, kXGlobal);
     } else if (RB <= 256) {
@@ -575,7 +576,8 @@ static hipError_t dispatch16_int8(const void* x, const float* sx, const void* pa
         if (M > 1 && RB >= 512) GEMV16(2, 4, 1, 4, kModesInt8, kXGlobal);
         else GEMV16(1, 4, 1, 4, kModesInt8 | kModesFused | kModesPre, (RB >= 400 && steps < 16) ? kXLds : kXGlobal);
     } else if (RB < 512) {
-        GEMV16(1, 4, 1, 5, kModesInt8 | kModesFused, kXGlobal);
+        if (walk_efficiency(steps, 4, 5) > walk_efficiency(steps, 4, 4)) GEMV16(1, 4, 1, 5, kModesInt8 | kModesFused, kXGlobal);
+        else GEMV16(1, 4, 1, 4, kModesInt8 | kModesFused | kModesPre, kXGlobal);
     } else {
         GEMV16(2, 2, 2, 4, kModesInt8 | kModesPre, kXGlobal);
     }
