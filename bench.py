@@ -201,7 +201,50 @@ def large_gemv_leg(torch, B, synth, gen, stream, args):
                                       "frac_int8_mfma_peak": round(tops / INT8_MFMA_PEAK_TOPS, 4)}
         del packs, xq, sx, yp
         torch.cuda.empty_cache()
+    res["ffn_chain_m1"] = large_ffn_chain(torch, B, synth, gen, stream, args)
     return res
+
+
+def large_ffn_chain(torch, B, synth, gen, stream, args, layers=80):
+    """One token through the feed-forward halves of all 80 layers of the 70B-class model, every layer's packed
+    weights resident (14.1 GB), as one HIP graph of two launches per layer: the merged gate/up projection with
+    RMSNorm + quantization in front and the SwiGLU gate in its epilogue, then the down projection with absmax
+    quantization in front.  The attention half (QKV, attention, O) is not in the workload's shape list and is
+    left out; residual additions likewise."""
+    shapes = {name: (K, N) for (name, K, N) in synth.CONFIGS[4]["shapes"]}
+    H, N_gu = shapes["gate_up"]
+    F = shapes["down"][0]
+    assert N_gu == 2 * F and shapes["down"][1] == H
+    packs = []
+    for l in range(layers):
+        d = {}
+        for name, (K, N) in shapes.items():
+            W = torch.randn((N, K), device="cuda", generator=gen, dtype=torch.float32) * synth.SIGMA_W
+            d[name] = B.quantize_weights(W)
+            del W
+        packs.append(d)
+    x0 = make_acts(torch, 1, H, gen, 4)
+    gain = torch.ones(H, dtype=torch.float32, device="cuda")
+    h_f = torch.empty((1, F), dtype=torch.bfloat16, device="cuda")
+    y_d = [torch.empty((1, H), dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+
+    def run():
+        x = x0
+        for l, d in enumerate(packs):
+            B.ffn_gate_up_fused(x, d["gate_up"][0], d["gate_up"][1], F, norm=True, g=gain, eps=1e-6, h_dtype=B.BF16, h=h_f)
+            B.linear_fused(h_f, d["down"][0], d["down"][1], H, y_dtype=B.BF16, y=y_d[l & 1])
+            x = y_d[l & 1]
+
+    ms, _, _ = time_graph(torch, run, args.warmup, args.steps, stream)
+    nbytes = layers * sum(gemv_bytes(1, N, K) for (K, N) in shapes.values())
+    out = {"layers": layers, "launches": 2 * layers, "resident_GB": round(layers * (N_gu * H + H * F) / 4 / 1e9, 2),
+           "ms_per_token": round(ms, 4), "us_per_layer": round(ms * 1e3 / layers, 2),
+           "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1), "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+           "note": "ffn_gate_up_fused (RMSNorm in, SwiGLU out) + linear_fused(down) per layer, each layer feeding "
+                   "the next; the attention half is not in this workload's shape list"}
+    del packs
+    torch.cuda.empty_cache()
+    return out
 
 
 def format_leg(torch, B, synth, gen, stream, args):
