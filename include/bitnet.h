@@ -41,6 +41,9 @@
 extern "C" {
 #endif
 
+/* Every enum below ends in an *_INT_RANGE_ member that is never a valid argument: it makes every non-negative int a
+ * representable value of the type, so that a caller's out-of-range code reaches the library's own check (and comes
+ * back as BITNET_ERR_DTYPE / _FORMAT / _KERNEL) instead of being undefined in a C++ translation unit. */
 typedef enum bitnet_status {
     BITNET_OK = 0,
     BITNET_ERR_NULL = 1,        /* a required pointer is NULL */
@@ -50,13 +53,15 @@ typedef enum bitnet_status {
     BITNET_ERR_ALIGN = 5,       /* a pointer is not aligned as documented */
     BITNET_ERR_WORKSPACE = 6,   /* workspace smaller than the call needs (see the call's workspace query) */
     BITNET_ERR_HIP = 7,         /* the HIP runtime refused the launch */
-    BITNET_ERR_KERNEL = 8       /* requested kernel variant cannot run this shape */
+    BITNET_ERR_KERNEL = 8,      /* requested kernel variant cannot run this shape */
+    BITNET_STATUS_INT_RANGE_ = 0x7fffffff
 } bitnet_status;
 
 typedef enum bitnet_dtype {
     BITNET_F32 = 0,
     BITNET_BF16 = 1,
-    BITNET_I32 = 2              /* only as y_dtype: raw int32 accumulators, for exactness checks */
+    BITNET_I32 = 2,             /* only as y_dtype: raw int32 accumulators, for exactness checks */
+    BITNET_DTYPE_INT_RANGE_ = 0x7fffffff
 } bitnet_dtype;
 
 /*
@@ -94,7 +99,8 @@ typedef enum bitnet_dtype {
  */
 typedef enum bitnet_format {
     BITNET_PACK_2BIT = 0,
-    BITNET_PACK_TRIT5 = 1
+    BITNET_PACK_TRIT5 = 1,
+    BITNET_FORMAT_INT_RANGE_ = 0x7fffffff
 } bitnet_format;
 
 /* Kernel choice for bitnet_linear_variant (bitnet_linear picks by shape). */
@@ -114,7 +120,8 @@ typedef enum bitnet_kernel {
        the batched-decode kernels) */
     BITNET_KERNEL_GEMM_SPLITK_2 = 0x202,
     BITNET_KERNEL_GEMM_SPLITK_4 = 0x204,
-    BITNET_KERNEL_GEMM_SPLITK_8 = 0x208
+    BITNET_KERNEL_GEMM_SPLITK_8 = 0x208,
+    BITNET_KERNEL_INT_RANGE_ = 0x7fffffff
 } bitnet_kernel;
 
 /* Library version, major*10000 + minor*100 + patch.  Also the version of the packed layouts. */

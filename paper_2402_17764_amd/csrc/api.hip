@@ -34,6 +34,7 @@ bool out_type(bitnet_dtype t, OutType* o) {
         case BITNET_F32: *o = OutType::F32; return true;
         case BITNET_BF16: *o = OutType::BF16; return true;
         case BITNET_I32: *o = OutType::I32; return true;
+        default: break;
     }
     return false;
 }
@@ -55,6 +56,7 @@ const char* bitnet_status_string(bitnet_status s) {
         case BITNET_ERR_WORKSPACE: return "workspace too small";
         case BITNET_ERR_HIP: return "HIP launch failed";
         case BITNET_ERR_KERNEL: return "kernel variant cannot run this shape";
+        default: break;
     }
     return "unknown status";
 }

@@ -155,3 +155,36 @@ def test_fallbacks_and_errors():
     assert lib.bitnet_linear_describe(1, 4096, 4096, 0, 0, buf, 8) == 6                # text does not fit
     assert lib.bitnet_linear_describe(1, 4096, 4096, 0, 0, buf, 128) == 0
     assert buf.value.decode().startswith("kernel=decode params=1,4,1,4,0 grid=256x1 block=256")
+
+
+def test_every_launch_shape_is_within_the_hardware_limits():
+    """Seeded random shapes, ragged ones included: whatever kernel a shape gets, its launch covers the output, a
+    workgroup is a whole number of wavefronts up to 1024 threads, and its LDS fits a CU."""
+    import random
+    rng = random.Random(1758)
+    kernels = set()
+    for _ in range(4000):
+        M = rng.choice([1, 2, 3, 4, 5, 15, 16, 17, 33, 64, 65, 100, 128, 200, 256, 257, 400, 512, 513, 1000, 2048, 5000])
+        N = rng.choice([1, 15, 16, 17, 100, 1000, 3200, 4096, 8192, 12288, 22016, 57344, 128256]) + rng.choice([0, 0, 0, 1, 16, 48])
+        K = rng.choice([16, 64, 256, 272, 1024, 3200, 4096, 5120, 8640, 11008, 28672, 65536]) + rng.choice([0, 0, 0, 16, 64, 7])
+        ws = rng.choice([0, 0, 8 * M * N * 4])
+        d = B.linear_describe(M, N, K, workspace_bytes=ws)
+        kernels.add(d["kernel"])
+        RB = ceil_div(N, 16)
+        if d["kernel"] == "reference":
+            assert K % 16 != 0, (M, N, K, d)
+            continue
+        assert d["block"] % 64 == 0 and 64 <= d["block"] <= 1024, (M, N, K, d)
+        assert d["lds"] <= LDS_PER_CU and 1 <= d["grid"][0] < 2 ** 31 and 1 <= d["grid"][1] < 65536, (M, N, K, d)
+        assert d["splits"] == d["grid"][1] and (ws or d["splits"] == 1), (M, N, K, d)
+        if d["kernel"] == "decode":
+            kR, kS, kW, kD, _ = d["params"]
+            assert M <= 4 and d["grid"][0] == ceil_div(RB, kR * kW) and d["block"] == 64 * kS * kW
+        elif d["kernel"].startswith("batched_decode"):
+            kMT, kR, kW, kS, kD, kLx = d["params"]
+            assert 4 < M <= 512 and d["grid"][0] == ceil_div(RB, kR * kW) * ceil_div(M, 16 * kMT)
+        else:
+            assert d["kernel"] == "prefill", (M, N, K, d)
+            tm, tn = d["params"]
+            assert d["grid"][0] == ceil_div(M, tm) * ceil_div(N, tn) and d["block"] == 256
+    assert kernels == {"reference", "decode", "batched_decode", "batched_decode_loader", "prefill"}
