@@ -334,7 +334,7 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
         const int cq = sl == steps - 1 ? tail_quads : 64;
         const int ln = min(lane, cq - 1);
 #pragma unroll
-        for (int a = 0; a < kR; ++a) s.w[a] = packed[(int64_t)sl * wstride + (int64_t)rbc[a] * cq + ln];
+        for (int a = 0; a < kR; ++a) s.w[a] = load_streaming_b128(packed + ((int64_t)sl * wstride + (int64_t)rbc[a] * cq + ln));
         if (!kFromLds) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {

@@ -3,11 +3,13 @@
 //   pass 1  abs_sum_partials : grid-stride |W| sum, double-double per thread, fixed-shape tree
 //                              inside the block, one (hi, lo) pair per block into the workspace
 //   pass 2  finish_gamma     : one block folds the partials in a fixed order, gamma = fp32(S / (N K))
-//   pass 3  ternarize_pack   : re-reads W, takes the decision of Eq. (1)-(2) in fp32 and writes the
-//                              packed buffer through LDS so that both the 4 B/weight read and the
-//                              0.25 B/weight write are contiguous
+//   pass 3  ternarize_pack   : re-reads W from its end (what pass 1 read last is still in the memory-side
+//                              cache), takes the decision of Eq. (1)-(2) in fp32 and writes the packed
+//                              layout one 1 KiB (row block, K step) chunk per workgroup pass
 //
-// The whole path is HBM-bound at 8.25 B per weight (two reads of W, one packed write).
+// The whole path is HBM-bound at 8.25 B per weight (two reads of W, one packed write).  Both reading passes
+// are shaped by what a plain read loop reaches on this chip: 8 waves per CU with four 16-byte loads each in
+// flight read 6.1-6.2 TB/s, 32 waves per CU 5.1-5.3 TB/s.
 #include "bitnet_device.hpp"
 #include "bitnet_internal.hpp"
 
@@ -16,58 +18,66 @@ namespace bitnet {
 // ---------------------------------------------------------------------------------------------------
 // pass 1
 // ---------------------------------------------------------------------------------------------------
-constexpr int kSumThreads = 256;
+constexpr int kSumThreads = 512;
+constexpr int kSumBlocks = 256;                           // one per CU: 8 waves per CU
+constexpr int kSumLoads = 4;                              // 16-byte loads in flight per thread
 
-template <typename T> struct Vec4;
-template <> struct Vec4<float> {
-    using type = float4;
-    __device__ static void widen(const float4& v, float (&o)[4]) { o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w; }
-};
-template <> struct Vec4<uint16_t> {
-    using type = ushort4;
-    __device__ static void widen(const ushort4& v, float (&o)[4]) {
-        o[0] = bf16_to_f32(v.x); o[1] = bf16_to_f32(v.y); o[2] = bf16_to_f32(v.z); o[3] = bf16_to_f32(v.w);
-    }
-};
 __device__ inline float widen1(float v) { return v; }
 __device__ inline float widen1(uint16_t v) { return bf16_to_f32(v); }
+
+// |.| of the 4 (fp32) or 8 (bf16) elements of one 16-byte vector, each added to one of four accumulators
+template <typename T>
+__device__ inline void add_abs(const uint4& q, dd (&part)[4]) {
+    const uint32_t u[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (sizeof(T) == 4) {
+            dd_add_double(part[e], (double)fabsf(__uint_as_float(u[e])));
+        } else {
+            dd_add_double(part[e], (double)fabsf(bf16_to_f32((uint16_t)(u[e] & 0xFFFFu))));
+            dd_add_double(part[e], (double)fabsf(bf16_to_f32((uint16_t)(u[e] >> 16))));
+        }
+    }
+}
 
 template <typename T>
 __global__ __launch_bounds__(kSumThreads) void abs_sum_partials(const T* __restrict__ W, int64_t count,
                                                                 int vec_ok, double* __restrict__ partials) {
-    using V = typename Vec4<T>::type;
+    constexpr int kPer = 16 / (int)sizeof(T);             // elements per 16-byte vector
     dd acc{0.0, 0.0};
     const int64_t tid = (int64_t)blockIdx.x * kSumThreads + threadIdx.x;
     const int64_t nthreads = (int64_t)gridDim.x * kSumThreads;
     int64_t done = 0;
     if (vec_ok) {
-        const int64_t nvec = count / 4;
-        const V* Wv = reinterpret_cast<const V*>(W);
-        // four loads in flight per thread and four independent accumulators: the sums are exact, so the
-        // split changes nothing but the bytes in flight and the length of the dependent chains
+        const int64_t nvec = count / kPer;
+        const uint4* Wv = reinterpret_cast<const uint4*>(W);
+        // the sums are exact, so the split into four accumulators changes nothing but the length of the dependent
+        // chains; the next round of loads is requested before this round's values are added
         dd part[4] = {{0.0, 0.0}, {0.0, 0.0}, {0.0, 0.0}, {0.0, 0.0}};
         int64_t i = tid;
-        for (; i + 3 * nthreads < nvec; i += 4 * nthreads) {
-            V v[4];
+        uint4 nxt[kSumLoads];
+        bool have = i + (kSumLoads - 1) * nthreads < nvec;
+        if (have) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) v[u] = Wv[i + u * nthreads];
+            for (int u = 0; u < kSumLoads; ++u) nxt[u] = Wv[i + u * nthreads];
+        }
+        while (have) {
+            uint4 cur[kSumLoads];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                float f[4];
-                Vec4<T>::widen(v[u], f);
+            for (int u = 0; u < kSumLoads; ++u) cur[u] = nxt[u];
+            i += kSumLoads * nthreads;
+            have = i + (kSumLoads - 1) * nthreads < nvec;
+            if (have) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) dd_add_double(part[e], (double)fabsf(f[e]));
+                for (int u = 0; u < kSumLoads; ++u) nxt[u] = Wv[i + u * nthreads];
             }
-        }
-        for (; i < nvec; i += nthreads) {
-            float f[4];
-            Vec4<T>::widen(Wv[i], f);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) dd_add_double(part[e], (double)fabsf(f[e]));
+            for (int u = 0; u < kSumLoads; ++u) add_abs<T>(cur[u], part);
         }
+        for (; i < nvec; i += nthreads) add_abs<T>(Wv[i], part);
 #pragma unroll
         for (int e = 0; e < 4; ++e) dd_add_dd(acc, part[e]);
-        done = nvec * 4;
+        done = nvec * kPer;
     }
     for (int64_t i = done + tid; i < count; i += nthreads) dd_add_double(acc, (double)fabsf(widen1(W[i])));
 
@@ -96,20 +106,21 @@ __global__ __launch_bounds__(kSumThreads) void abs_sum_partials(const T* __restr
 // ---------------------------------------------------------------------------------------------------
 // pass 2
 // ---------------------------------------------------------------------------------------------------
+constexpr int kFinishThreads = 256;
 // gamma[0 .. nout-1] all receive the value (nout > 1: one copy per 16-row block of a segment)
-__global__ __launch_bounds__(kSumThreads) void finish_gamma(const double* __restrict__ partials, int nparts,
+__global__ __launch_bounds__(kFinishThreads) void finish_gamma(const double* __restrict__ partials, int nparts,
                                                             int64_t count, float* __restrict__ gamma, int64_t nout) {
     dd acc{0.0, 0.0};
-    for (int i = threadIdx.x; i < nparts; i += kSumThreads) {
+    for (int i = threadIdx.x; i < nparts; i += kFinishThreads) {
         dd p{partials[2 * i], partials[2 * i + 1]};
         dd_add_dd(acc, p);
     }
-    __shared__ double sh_hi[kSumThreads];
-    __shared__ double sh_lo[kSumThreads];
+    __shared__ double sh_hi[kFinishThreads];
+    __shared__ double sh_lo[kFinishThreads];
     sh_hi[threadIdx.x] = acc.hi;
     sh_lo[threadIdx.x] = acc.lo;
     __syncthreads();
-    for (int s = kSumThreads / 2; s > 0; s >>= 1) {
+    for (int s = kFinishThreads / 2; s > 0; s >>= 1) {
         if ((int)threadIdx.x < s) {
             dd a{sh_hi[threadIdx.x], sh_lo[threadIdx.x]};
             dd b{sh_hi[threadIdx.x + s], sh_lo[threadIdx.x + s]};
@@ -121,21 +132,38 @@ __global__ __launch_bounds__(kSumThreads) void finish_gamma(const double* __rest
     }
     const double S = sh_hi[0] + sh_lo[0];
     const float g = (float)(S / (double)count);     // Eq. (3); fp64 IEEE division, one rounding to fp32
-    for (int64_t i = threadIdx.x; i < nout; i += kSumThreads) gamma[i] = g;
+    for (int64_t i = threadIdx.x; i < nout; i += kFinishThreads) gamma[i] = g;
 }
 
 // ---------------------------------------------------------------------------------------------------
 // pass 3, 2-bit format
 // ---------------------------------------------------------------------------------------------------
-// One workgroup of 16 waves owns one 16-row block; wave r streams row 16*rb + r.  Per step the wave
-// reads 1024 consecutive columns (lane l, sub-step t: columns 256 t + 4 l .. +3, a 16-byte load for
-// fp32), so reads are 1 KiB runs.  The four codes of a lane land in one word at bits 8 b + 2 i with
-// i = l & 3; OR-ing the four lanes of a quad completes the word.  Words are staged in LDS in output
-// order ([16 quads of K][16 rows][4 words] = 4 KiB) and written out as 256-byte runs, one per quad
-// column, which land inside the 1 KiB (step, row block) chunks of the packed layout.
-constexpr int kPackWaves = 16;
-constexpr int kPackThreads = kPackWaves * kWave;          // 1024
-constexpr int kPackColsPerStep = 1024;                    // 16 quads along K per workgroup step
+// One work item is one 1 KiB chunk of the packed layout: a 16-row block x one K step of 256 columns.  A workgroup
+// has four waves; wave w reads rows 4w .. 4w+3 of the item (lane l: columns 4l .. 4l+3 of the step, one 16-byte
+// load per row for fp32, marked streaming: this is the last use of W).  The four codes of a lane land in one word at
+// bits 8 b + 2 i with i = l & 3; OR-ing the four lanes of a quad completes the word, which every lane of the quad
+// then holds.  One ds_bpermute transposes the wave's 4 rows x 16 words so that lane 16 g + 4 t + j holds word j of
+// quad column g for row 4w + t: the wave stores four 64-byte runs, no LDS memory and no barrier.  Items are walked
+// from the end of W backwards, workgroup b taking items b, b + gridDim.x, ...: neighbouring workgroups read
+// neighbouring 1 KiB runs of the same 16 rows, and the next item's rows are requested before this one's are coded.
+constexpr int kPackThreads = 256;
+constexpr int kPackBlocks = 1024;                          // four per CU
+
+template <typename T> struct PackVec;
+template <> struct PackVec<float> {
+    __device__ static void load(const float* p, float (&f)[4]) {
+        const uint4 q = load_streaming_b128(p);
+        f[0] = __uint_as_float(q.x); f[1] = __uint_as_float(q.y); f[2] = __uint_as_float(q.z); f[3] = __uint_as_float(q.w);
+    }
+};
+template <> struct PackVec<uint16_t> {
+    __device__ static void load(const uint16_t* p, float (&f)[4]) {
+        typedef unsigned v2u __attribute__((ext_vector_type(2)));
+        const v2u q = __builtin_nontemporal_load(reinterpret_cast<const v2u*>(p));
+        f[0] = __uint_as_float(q.x << 16); f[1] = __uint_as_float(q.x & 0xFFFF0000u);
+        f[2] = __uint_as_float(q.y << 16); f[3] = __uint_as_float(q.y & 0xFFFF0000u);
+    }
+};
 
 // W, N: the rows being packed (a whole matrix, or one segment of it); they become row blocks rb_off ... of a
 // packed matrix of RB row blocks in all.
@@ -144,50 +172,64 @@ __global__ __launch_bounds__(kPackThreads) void ternarize_pack_2bit(const T* __r
                                                                     int64_t Kq /* quads per row */, int64_t RB,
                                                                     int64_t rb_off, const float* __restrict__ gamma,
                                                                     uint32_t* __restrict__ packed) {
-    using V = typename Vec4<T>::type;
-    __shared__ uint32_t stage[16 * 16 * 4];
     const int lane = threadIdx.x & (kWave - 1);
-    const int r = threadIdx.x >> 6;                        // wave index = row inside the block
-    const int64_t rb = blockIdx.x;
-    const int64_t n = rb * kRowsPerBlock + r;
+    const int w = threadIdx.x >> 6;
     const float d = gamma[0] + kEps;                       // gamma + eps, one fp32 add (Eq. (1))
     const float thr = ternary_threshold(d);                // |w| >= thr  <=>  RoundClip(w / d) = +-1
-    const T* row = W + n * K;
     const int i = lane & 3;
+    const int64_t steps = ceil_div(Kq, 4);
+    const int64_t items = ceil_div(N, kRowsPerBlock) * steps;
+    // lane 16 g + 4 t + j takes its word from lane 16 g + 4 j + t (which selected row t's word below)
+    const int src = ((lane & 48) | ((lane & 3) << 2) | ((lane >> 2) & 3)) << 2;
 
-    for (int64_t k0 = (int64_t)blockIdx.y * kPackColsPerStep; k0 < Kq * kColsPerQuad;
-         k0 += (int64_t)gridDim.y * kPackColsPerStep) {
+    auto load = [&](int64_t item, float (&f)[4][4]) {
+        item = items - 1 - item;
+        const int64_t rb = item / steps, s = item - rb * steps;
+        const int64_t k = 256 * s + 4 * lane;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const int64_t k = k0 + 256 * t + 4 * lane;
-            float f[4] = {0.f, 0.f, 0.f, 0.f};             // padding rows / columns quantize to code 0
+            const int64_t n = rb * kRowsPerBlock + 4 * w + t;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) f[t][b] = 0.f;     // padding rows / columns quantize to code 0
             if (n < N) {
+                const T* row = W + n * K;
                 if (kVec) {
-                    if (k < K) Vec4<T>::widen(*reinterpret_cast<const V*>(row + k), f);
+                    if (k < K) PackVec<T>::load(row + k, f[t]);
                 } else {
 #pragma unroll
                     for (int b = 0; b < 4; ++b)
-                        if (k + b < K) f[b] = widen1(row[k + b]);
+                        if (k + b < K) f[t][b] = widen1(row[k + b]);
                 }
             }
-            uint32_t w = 0;
+        }
+    };
+
+    float nxt[4][4];
+    int64_t item = blockIdx.x;
+    if (item < items) load(item, nxt);
+    for (; item < items; item += gridDim.x) {
+        float cur[4][4];
 #pragma unroll
-            for (int b = 0; b < 4; ++b) w |= ternary_code2_threshold(f[b], thr) << (8 * b + 2 * i);
-            w = quad_or(w);
-            if (i == 0) {
-                const int quad = 4 * t + (lane >> 4);      // which of the 16 quads of this step
-                const int j = (lane >> 2) & 3;             // word inside the quad
-                stage[(quad * 16 + r) * 4 + j] = w;
-            }
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) cur[t][b] = nxt[t][b];
+        if (item + gridDim.x < items) load(item + gridDim.x, nxt);
+        uint32_t c[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            uint32_t v = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) v |= ternary_code2_threshold(cur[t][b], thr) << (8 * b + 2 * i);
+            c[t] = quad_or(v);
         }
-        __syncthreads();
-        // 16 quads x 16 rows x 4 words = 1024 words: one per thread, contiguous in the output
-        {
-            const int quad = threadIdx.x >> 6;
-            const int64_t kq = k0 / kColsPerQuad + quad;
-            if (kq < Kq) packed[quad_index_2bit(kq, rb + rb_off, 0, Kq, RB) * 4 + (threadIdx.x & 63)] = stage[threadIdx.x];
-        }
-        __syncthreads();
+        const uint32_t sel = i == 0 ? c[0] : i == 1 ? c[1] : i == 2 ? c[2] : c[3];
+        const uint32_t out = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)sel);
+        const int64_t it = items - 1 - item;
+        const int64_t rb = it / steps, s = it - rb * steps;
+        const int64_t nq = (Kq - 4 * s) < 4 ? (Kq - 4 * s) : 4;     // quads of this step (the last may hold fewer)
+        const int g = lane >> 4;
+        // word index inside the chunk: ((g * 16 + row) * 4 + j) with row = 4 w + t, and lane & 15 = 4 t + j
+        if (g < nq) packed[quad_index_2bit(4 * s, rb + rb_off, 0, Kq, RB) * 4 + g * 64 + 16 * w + (lane & 15)] = out;
     }
 }
 
@@ -202,16 +244,15 @@ hipError_t launch_absmean_gamma(const void* W, bool bf16, int64_t N, int64_t K, 
     const int64_t count = N * K;
     double* partials = static_cast<double*>(workspace);
     int64_t want = ceil_div(count, (int64_t)kSumThreads * 16);
-    int blocks = (int)(want < 1 ? 1 : (want > quant_weights_num_partials() ? quant_weights_num_partials() : want));
-    const size_t esz = bf16 ? 2 : 4;
-    const int vec_ok = (reinterpret_cast<uintptr_t>(W) % (4 * esz)) == 0;
+    int blocks = (int)(want < 1 ? 1 : (want > kSumBlocks ? kSumBlocks : want));
+    const int vec_ok = (reinterpret_cast<uintptr_t>(W) % 16) == 0;
     if (bf16)
         hipLaunchKernelGGL(abs_sum_partials<uint16_t>, dim3(blocks), dim3(kSumThreads), 0, stream,
                            static_cast<const uint16_t*>(W), count, vec_ok, partials);
     else
         hipLaunchKernelGGL(abs_sum_partials<float>, dim3(blocks), dim3(kSumThreads), 0, stream,
                            static_cast<const float*>(W), count, vec_ok, partials);
-    hipLaunchKernelGGL(finish_gamma, dim3(1), dim3(kSumThreads), 0, stream, partials, blocks, count, gamma, nout);
+    hipLaunchKernelGGL(finish_gamma, dim3(1), dim3(kFinishThreads), 0, stream, partials, blocks, count, gamma, nout);
     return hipGetLastError();
 }
 
@@ -226,12 +267,9 @@ hipError_t launch_quantize_weights_2bit(const void* W, bool bf16, int64_t N, int
     const int64_t Kq = ceil_div(K, kColsPerQuad);
     const int64_t RB = ceil_div(N, kRowsPerBlock);                       // row blocks packed by this call
     const int64_t RBT = rb_total > 0 ? rb_total : RB;                      // ... of the whole packed matrix
-    const int64_t steps = ceil_div(Kq * kColsPerQuad, kPackColsPerStep);
-    // enough workgroups to fill the chip even for few row blocks: split K across blockIdx.y
-    int64_t ysplit = 1;
-    while (RB * ysplit < 1024 && ysplit * 2 <= steps) ysplit *= 2;
+    const int64_t items = RB * ceil_div(Kq, 4);
     const bool vec = vec_ok && (K % 4 == 0);
-    dim3 grid((unsigned)RB, (unsigned)ysplit);
+    dim3 grid((unsigned)(items < kPackBlocks ? items : kPackBlocks));
     uint32_t* out = static_cast<uint32_t*>(packed);
     if (bf16) {
         const uint16_t* w = static_cast<const uint16_t*>(W);

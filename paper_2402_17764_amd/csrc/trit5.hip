@@ -152,7 +152,7 @@ __global__ __launch_bounds__(kS * kWave) void linear_gemv16_trit5(
     auto load = [&](Stage& s, int item) {
         const int sl = min(wave + item * kS, steps - 1);
 #pragma unroll
-        for (int a = 0; a < kR; ++a) s.w[a] = wp[a][(int64_t)sl * wstride];
+        for (int a = 0; a < kR; ++a) s.w[a] = load_streaming_b128(wp[a] + (int64_t)sl * wstride);
 #pragma unroll
         for (int j = 0; j < 5; ++j) {
             const int64_t col = min((int64_t)sl * kTritStep + kTritCols * g + 16 * j, K - 16);   // past K: zero codes
