@@ -560,11 +560,15 @@ static hipError_t dispatch16_int8(const void* x, const float* sx, const void* pa
     const float eps = 0.0f;
     const bool pads44 = walk_efficiency(steps, 4, 4) < 0.75;       // four waves at depth 4 would walk over a third more than K
     if (RB >= 2048) {
-        if (steps >= 32) GEMV16(4, 1, 4, 2, kModesInt8 | kModesFused | kModesPre, kXGlobal);
+        // one or two tokens: x_q from LDS, two waves splitting K per row block (30B gate/up 16.1 -> 14.6 us, 70B
+        // gate/up 23.0 -> 21.3 us at M = 1 once the weight loads were marked streaming); more tokens: wide waves
+        if (M <= 2) GEMV16(1, 2, 2, 4, kModesInt8, kXLds);
+        else if (steps >= 32) GEMV16(4, 1, 4, 2, kModesInt8 | kModesFused | kModesPre, kXGlobal);
         else GEMV16(4, 1, 4, 3, kModesInt8, kXGlobal);
     } else if (RB >= 1024) {
         if (steps < 16 && M == 1 && !pads44) GEMV16(1, 4, 1, 4, kModesInt8 | kModesFused | kModesPre, kXLds);
         else if (steps < 16 && M == 1) GEMV16(2, 2, 2, 4, kModesInt8 | kModesPre, kXGlobal);      // e.g. 8 steps: 2 x 4, no padding
+        else if (!pads44 && M == 1) GEMV16(1, 2, 2, 4, kModesInt8, kXLds);      // 7B gate/up 6.9 -> 6.6 us, 30B QKV 10.5 -> 9.6 us
         else if (!pads44) GEMV16(2, 4, 1, 4, kModesInt8, kXGlobal);
         else GEMV16(2, 1, 4, 4, kModesInt8 | kModesFused, kXGlobal);
     } else if (RB <= 256) {
@@ -611,6 +615,7 @@ static hipError_t dispatch16_fused(int xmode, const void* x, const void* packed,
     }
     if (RB >= 2048) {
         if (steps >= 32) GEMV16(4, 1, 4, 2, kModesInt8 | kModesFused | kModesPre, xmode);
+        else if (walk_efficiency(steps, 4, 4) >= 0.8) GEMV16(2, 4, 1, 4, kModesFused, xmode);      // 30B gate/up 15.8 -> 14.9 us
         else GEMV16(2, 1, 4, 4, kModesInt8 | kModesFused, xmode);
     } else if (RB >= 1024) {
         if (steps < 16) GEMV16(1, 4, 1, 4, kModesInt8 | kModesFused | kModesPre, xmode);
