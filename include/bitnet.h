@@ -143,9 +143,10 @@ bitnet_status bitnet_quantize_weights_workspace(int64_t N, int64_t K, size_t* by
  *   gamma      out, 1 float (device)
  *   workspace  scratch of at least bitnet_quantize_weights_workspace() bytes, 16-byte aligned;
  *              contents on entry are ignored, contents on exit are unspecified
- * Three launches on `stream`: |W| partial sums (double-double), the final reduction to gamma, and
- * the ternarize-and-pack pass.  One gamma per call: a fused QKV or gate/up matrix passed as one
- * tensor gets one scale.
+ * Two launches on `stream` for the 2-bit format: |W| partial sums (double-double), then the
+ * ternarize-and-pack pass, whose workgroups first fold the partial sums to gamma (the 5-trit format keeps
+ * that reduction as a launch of its own).  A 16-byte aligned W takes the vector path of the |W| sum.
+ * One gamma per call: a fused QKV or gate/up matrix passed as one tensor gets one scale.
  */
 bitnet_status bitnet_quantize_weights(const void* W, bitnet_dtype w_dtype, int64_t N, int64_t K,
                                       bitnet_format f, void* packed, float* gamma,
@@ -262,9 +263,9 @@ bitnet_status bitnet_linear_ws(const int8_t* xq, const float* sx, const void* pa
  *   x   [M][K], dtype F32 or BF16, 16-byte aligned
  *   Limits: M <= 16, K a multiple of 16 and M * 256 * ceil(K / 256) + 512 <= 65536 bytes of LDS
  *   (M = 1 up to K = 65024, M = 4 up to K = 16128); otherwise BITNET_ERR_KERNEL and nothing is launched.
- * Meant for M = 1, where it saves a launch (3B-class layers on MI355X: 3.7-7.2 us against 5.6-8.9 us for the
+ * Meant for M = 1, where it saves a launch (3B-class layers on MI355X: 3.6-6.8 us against 5.1-7.5 us for the
  * two calls).  Because every workgroup repeats the quantization of all M tokens, bitnet_quantize_acts followed
- * by bitnet_linear is the faster route from about M = 4 on (measured: 10.7 us against 12.9 us on a 3200 ->
+ * by bitnet_linear is the faster route from about M = 3 on (measured: 8.7 us against 12.4 us on a 3200 ->
  * 17280 layer at M = 4); a producer that already emits int8 (bitnet_rmsnorm_quantize, bitnet_swiglu_quantize)
  * avoids the question.
  */
@@ -281,8 +282,8 @@ bitnet_status bitnet_linear_fused(const void* x, bitnet_dtype x_dtype, const voi
  *   g    [K] float (device), 16-byte aligned, or NULL for no gain
  *   eps  added to the mean square; >= 0 (BITNET_ERR_SHAPE otherwise)
  *   Limits as for bitnet_linear_fused.  2-bit format only.
- * Measured at M = 1 on MI355X (3200 -> 9600 / 3200 -> 17280 / 8192 -> 57344): 7.0 / 8.3 / 25.0 us against 9.6 / 10.9 /
- * 28.7 us for bitnet_rmsnorm_quantize + bitnet_linear.
+ * Measured at M = 1 on MI355X (3200 -> 9600 / 3200 -> 17280 / 8192 -> 57344): 6.5 / 8.2 / 24.7 us against 9.2 / 10.6 /
+ * 27.0 us for bitnet_rmsnorm_quantize + bitnet_linear.
  * bitnet_rmsnorm_linear_fused_segmented: with one gamma per 16-row block, as bitnet_linear_fused_segmented.
  */
 bitnet_status bitnet_rmsnorm_linear_fused(const void* x, bitnet_dtype x_dtype, const float* g, float eps,
@@ -302,8 +303,8 @@ bitnet_status bitnet_rmsnorm_linear_fused_segmented(const void* x, bitnet_dtype 
  *   F    columns of the product (the K of bitnet_linear); packed holds an [N][F] matrix
  *   Limits as for bitnet_linear_fused with K = F.  2-bit format only.
  * Every workgroup repeats the gating of all F elements (an exponential and a division each), so this pays only
- * while F is small against the weight stream: measured at M = 1 on MI355X, 8.7 us against 9.3 us for the two calls
- * at F = 8640 (N = 3200), 9.4 against 10.1 us at F = 11008 (N = 4096), but 53 against 33 us at F = 28672 (N = 8192)
+ * while F is small against the weight stream: measured at M = 1 on MI355X, 8.1 us against 8.7 us for the two calls
+ * at F = 8640 (N = 3200), 9.2 against 9.5 us at F = 11008 (N = 4096), but 53 against 22 us at F = 28672 (N = 8192)
  * -- there bitnet_swiglu_quantize followed by bitnet_linear is the route.
  */
 bitnet_status bitnet_swiglu_linear_fused(const void* gu, bitnet_dtype gu_dtype, const void* packed,
