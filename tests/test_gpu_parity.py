@@ -86,6 +86,38 @@ def test_quantize_weights_bf16_input_and_unaligned_rows(gpu_lib):
     assert np.array_equal(gpu_lib.unpack_weights(packed, N, K).cpu().numpy(), codes_ref)
 
 
+def test_quantize_weights_vector_paths_and_partly_aligned_bases(gpu_lib):
+    """The |W| sum reads 16-byte vectors (8 bf16 or 4 fp32 elements) in rounds of four per thread, the packing pass 16- or
+    8-byte vectors per row and several items per workgroup: sizes that go round those loops more than once, and base
+    pointers aligned for one pass but not for the other."""
+    say("quantize_weights bf16 2048 x 3072 (vector paths, several rounds)")
+    N, K = 2048, 3072
+    Wf, bits = synth.to_bf16(synth.weights(N, K, config=0, layer=3))
+    codes_ref, gamma_ref = oracle.quantize_weights(Wf)
+    packed, gamma = gpu_lib.quantize_weights(bf16_tensor(bits).view(N, K))
+    assert gamma.cpu().numpy()[0].tobytes() == np.float32(gamma_ref).tobytes()
+    assert np.array_equal(gpu_lib.unpack_weights(packed, N, K).cpu().numpy(), codes_ref)
+    say("quantize_weights bf16, base 8-byte but not 16-byte aligned")
+    N, K = 40, 264
+    Wf, bits = synth.to_bf16(synth.weights(N, K, config=0, layer=4))
+    buf = torch.empty(N * K + 4, dtype=torch.bfloat16, device="cuda")
+    buf[4:] = bf16_tensor(bits).reshape(-1)
+    assert buf[4:].data_ptr() % 16 == 8
+    codes_ref, gamma_ref = oracle.quantize_weights(Wf)
+    packed, gamma = gpu_lib.quantize_weights(buf[4:].view(N, K))
+    assert gamma.cpu().numpy()[0].tobytes() == np.float32(gamma_ref).tobytes()
+    assert np.array_equal(gpu_lib.unpack_weights(packed, N, K).cpu().numpy(), codes_ref)
+    say("quantize_weights fp32, base 8-byte aligned, K a multiple of 4")
+    N, K = 35, 520
+    W = synth.weights(N, K, config=0, layer=2)
+    buf = torch.empty(N * K + 2, dtype=torch.float32, device="cuda")
+    buf[2:] = dev(W).reshape(-1)
+    codes_ref, gamma_ref = oracle.quantize_weights(W)
+    packed, gamma = gpu_lib.quantize_weights(buf[2:].view(N, K))
+    assert gamma.cpu().numpy()[0].tobytes() == np.float32(gamma_ref).tobytes()
+    assert np.array_equal(gpu_lib.unpack_weights(packed, N, K).cpu().numpy(), codes_ref)
+
+
 def test_quantize_weights_edge_values(gpu_lib):
     say("quantize_weights edge values")
     # all-zero matrix
