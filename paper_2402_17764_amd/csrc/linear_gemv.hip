@@ -570,7 +570,12 @@ static hipError_t dispatch16_int8(const void* x, const float* sx, const void* pa
         else if (steps < 16 && M == 1) GEMV16(2, 2, 2, 4, kModesInt8 | kModesPre, kXGlobal);      // e.g. 8 steps: 2 x 4, no padding
         else if (!pads44 && M == 1) GEMV16(1, 2, 2, 4, kModesInt8, kXLds);      // 7B gate/up 6.9 -> 6.6 us, 30B QKV 10.5 -> 9.6 us
         else if (!pads44) GEMV16(2, 4, 1, 4, kModesInt8, kXGlobal);
-        else GEMV16(2, 1, 4, 4, kModesInt8 | kModesFused, kXGlobal);
+        else if (M == 1) {
+            // a K walk that four waves cannot split evenly: no split, eight single-row-block waves, x_q in LDS
+            // (13B gate/up, 20 steps: 9.0 -> 8.2 us)
+            if (walk_efficiency(steps, 1, 5) >= walk_efficiency(steps, 1, 4)) GEMV16(1, 1, 8, 5, kModesInt8, kXLds);
+            else GEMV16(1, 1, 8, 4, kModesInt8, kXLds);
+        } else GEMV16(2, 1, 4, 4, kModesInt8 | kModesFused, kXGlobal);
     } else if (RB <= 256) {
         if (walk_efficiency(steps, 4, 5) > walk_efficiency(steps, 4, 4)) GEMV16(1, 4, 1, 5, kModesInt8 | kModesFused, kXGlobal);
         else GEMV16(1, 4, 1, 4, kModesInt8 | kModesFused | kModesPre, kXGlobal);
@@ -597,8 +602,8 @@ static hipError_t dispatch16_fused(int xmode, const void* x, const void* packed,
         // every workgroup repeats the normalisation (an fp64 reduction and a square root, a microsecond or two of its
         // CU's time), so few, wide workgroups: one wave per row block (or pair of them) and no K split from 769 row
         // blocks on, at most 256 workgroups up to 4096 row blocks
-        if (RB >= 2048) GEMV16(2, 1, 8, 3, kModesPre, xmode);
-        else if (RB >= 1024) GEMV16(1, 1, 8, 5, kModesPre, xmode);
+        if (RB >= 2048) GEMV16(2, 1, 8, 3, kModesFused | kModesPre, xmode);
+        else if (RB >= 1024) GEMV16(1, 1, 8, 5, kModesFused | kModesPre, xmode);
         else if (RB > 768) GEMV16(1, 1, 4, 5, kModesPre, xmode);
         else if (RB > 512) GEMV16(2, 2, 2, 4, kModesInt8 | kModesPre, xmode);
         else if (RB > 256) GEMV16(1, 2, 2, 4, kModesFused | kModesPre, xmode);
@@ -613,13 +618,18 @@ static hipError_t dispatch16_fused(int xmode, const void* x, const void* packed,
         else if (RB > 320) GEMV16(1, 2, 2, 4, kModesFused | kModesPre, xmode);
         else GEMV16(1, 4, 1, 4, kModesInt8 | kModesFused | kModesPre, xmode);
     }
+    // Many row blocks: eight waves per workgroup, each walking all of K for one or two row blocks of its own -- few
+    // workgroups repeat the quantization, no partial sums to fold, and about eight waves per CU with several loads
+    // each in flight is the shape in which a plain read loop is fastest on this chip (70B gate/up 22.9 -> 20.8 us,
+    // 30B gate/up 15.3 -> 14.4 us, 13B gate/up 8.9 -> 8.0 us, 7B gate/up 7.0 -> 6.8 us, 3B gate/up 6.7 -> 6.45 us).
     if (RB >= 2048) {
-        if (steps >= 32) GEMV16(4, 1, 4, 2, kModesInt8 | kModesFused | kModesPre, xmode);
-        else if (walk_efficiency(steps, 4, 4) >= 0.8) GEMV16(2, 4, 1, 4, kModesFused, xmode);      // 30B gate/up 15.8 -> 14.9 us
-        else GEMV16(2, 1, 4, 4, kModesInt8 | kModesFused, xmode);
+        if (steps >= 32) GEMV16(2, 1, 8, 2, kModesFused, xmode);
+        else GEMV16(2, 1, 8, 3, kModesFused | kModesPre, xmode);
     } else if (RB >= 1024) {
-        if (steps < 16) GEMV16(1, 4, 1, 4, kModesInt8 | kModesFused | kModesPre, xmode);
-        else if (RB >= 1536 && walk_efficiency(steps, 2, 4) < 0.9 && walk_efficiency(steps, 1, 4) > walk_efficiency(steps, 2, 4))
+        if (steps <= 24) {
+            if (walk_efficiency(steps, 1, 5) >= walk_efficiency(steps, 1, 4)) GEMV16(1, 1, 8, 5, kModesFused | kModesPre, xmode);
+            else GEMV16(1, 1, 8, 4, kModesFused, xmode);
+        } else if (RB >= 1536 && walk_efficiency(steps, 2, 4) < 0.9 && walk_efficiency(steps, 1, 4) > walk_efficiency(steps, 2, 4))
             GEMV16(2, 1, 4, 4, kModesInt8 | kModesFused, xmode);
         else GEMV16(1, 2, 2, 4, kModesFused | kModesPre, xmode);
     } else if (steps >= 64) {
