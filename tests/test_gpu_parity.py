@@ -118,6 +118,18 @@ def test_quantize_weights_vector_paths_and_partly_aligned_bases(gpu_lib):
     assert np.array_equal(gpu_lib.unpack_weights(packed, N, K).cpu().numpy(), codes_ref)
 
 
+def test_quantize_weights_larger_than_the_cached_tail(gpu_lib):
+    """Above 192 MB the |W| sum reads the head of W with the streaming cache policy and only the tail normally: a
+    235 MB matrix takes both branches; gamma and every code against the oracle."""
+    say("quantize_weights fp32 7168 x 8192 (235 MB)")
+    N, K = 7168, 8192
+    W = synth.weights(N, K, config=4, layer=1, tensor=0)
+    codes_ref, gamma_ref = oracle.quantize_weights(W)
+    packed, gamma = gpu_lib.quantize_weights(dev(W))
+    assert gamma.cpu().numpy()[0].tobytes() == np.float32(gamma_ref).tobytes(), "gamma bits differ"
+    assert np.array_equal(gpu_lib.unpack_weights(packed, N, K).cpu().numpy(), codes_ref)
+
+
 def test_quantize_weights_edge_values(gpu_lib):
     say("quantize_weights edge values")
     # all-zero matrix
