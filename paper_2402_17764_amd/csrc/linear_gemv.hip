@@ -709,8 +709,14 @@ hipError_t launch_linear_fused_swiglu_out_2bit(const void* x, bool bf16, bool no
     // and no K split, four pairs per workgroup up to 1024 pairs (at most 256 workgroups), eight beyond.
     const int64_t pairs = F / kRowsPerBlock;
     if (!norm && pairs <= 700) launch16_pair<4, 1, 4>(xmode, x, packed, gamma, gstride, M, F, K, h, yt, stream, gain, eps);
-    else if (pairs <= 1024) launch16_pair<1, 4, 5>(xmode, x, packed, gamma, gstride, M, F, K, h, yt, stream, gain, eps);
-    else launch16_pair<1, 8, 3>(xmode, x, packed, gamma, gstride, M, F, K, h, yt, stream, gain, eps);
+    else if (pairs <= 1024) {
+        // depth 5 or 4, whichever pads the K walk less (16 steps at depth 5 walk 20: 7B gate/up with the norm 10.5 -> 9.5 us)
+        const int64_t steps = ceil_div(K, 256);
+        if (walk_efficiency(steps, 1, 5) >= walk_efficiency(steps, 1, 4))
+            launch16_pair<1, 4, 5>(xmode, x, packed, gamma, gstride, M, F, K, h, yt, stream, gain, eps);
+        else
+            launch16_pair<1, 4, 4>(xmode, x, packed, gamma, gstride, M, F, K, h, yt, stream, gain, eps);
+    } else launch16_pair<1, 8, 3>(xmode, x, packed, gamma, gstride, M, F, K, h, yt, stream, gain, eps);
     return hipGetLastError();
 }
 
