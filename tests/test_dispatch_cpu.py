@@ -188,3 +188,18 @@ def test_every_launch_shape_is_within_the_hardware_limits():
             tm, tn = d["params"]
             assert d["grid"][0] == ceil_div(M, tm) * ceil_div(N, tn) and d["block"] == 256
     assert kernels == {"reference", "decode", "batched_decode", "batched_decode_loader", "prefill"}
+
+
+def test_decode_shapes_on_large_layers_follow_the_measured_cases():
+    """One or two tokens on layers of 1024 row blocks and more take x_q from LDS (last parameter 1): two K-split waves
+    per row block where four waves split K evenly, eight single-row-block waves without a split where they cannot
+    (K = 5120); from three tokens on the wide-wave forms on x_q from global memory."""
+    assert B.linear_describe(1, 35840, 6656)["params"] == [1, 2, 2, 4, 1]            # 30B gate/up: 16.1 -> 14.6 us
+    assert B.linear_describe(2, 57344, 8192)["params"] == [1, 2, 2, 4, 1]            # 70B gate/up: 23.0 -> 21.3 us at M = 1
+    assert B.linear_describe(4, 35840, 6656)["params"] == [4, 1, 4, 3, 0]
+    assert B.linear_describe(1, 22016, 4096)["params"] == [1, 2, 2, 4, 1]            # 7B gate/up
+    assert B.linear_describe(1, 19968, 6656)["params"] == [1, 2, 2, 4, 1]            # 30B QKV
+    assert B.linear_describe(1, 27648, 5120)["params"] == [1, 1, 8, 5, 1]            # 13B gate/up: 9.0 -> 8.2 us
+    assert B.linear_describe(1, 27648, 5120)["grid"] == (216, 1)
+    assert B.linear_describe(2, 27648, 5120)["params"] == [2, 1, 4, 4, 0]
+    assert B.linear_describe(1, 17280, 3200)["params"] == [1, 4, 1, 4, 1]            # 3B gate/up keeps four K-split waves
