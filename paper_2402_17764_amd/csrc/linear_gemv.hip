@@ -582,7 +582,7 @@ static hipError_t dispatch16_int8(const void* x, const float* sx, const void* pa
     } else if (steps >= 24) {
         GEMV16(2, 4, 1, 4, kModesInt8, kXGlobal);
     } else if (!pads44) {
-        if (M > 1 && RB >= 512) GEMV16(2, 4, 1, 4, kModesInt8, kXGlobal);
+        if (M > 1 && RB >= 512) GEMV16(2, 2, 2, 4, kModesInt8 | kModesPre, kXGlobal);     // 7B QKV at 2 / 4 / 8 tokens: 5.1 / 5.2 / 5.5 us (four K-split waves: 5.25 / 5.3 / 6.05)
         else GEMV16(1, 4, 1, 4, kModesInt8 | kModesFused | kModesPre, (RB >= 400 && steps < 16) ? kXLds : kXGlobal);
     } else if (RB < 512) {
         if (walk_efficiency(steps, 4, 5) > walk_efficiency(steps, 4, 4)) GEMV16(1, 4, 1, 5, kModesInt8 | kModesFused, kXGlobal);

@@ -566,10 +566,14 @@ hipError_t launch_linear_gemv_2bit(const int8_t* xq, const float* sx, const void
                                    const float* gamma, int gstride, int64_t M, int64_t N, int64_t K, void* y,
                                    OutType yt, hipStream_t stream, void* workspace, size_t workspace_bytes,
                                    int force_splits, LaunchPlan* plan) {
-    if (M <= 4) return launch_linear_gemv16_2bit(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, plan);
-    // More than four tokens: the activations of a step outweigh the weights a wave reads with them, so they
-    // are staged once per group of waves (skinny kernel), 16 * kMT >= M tokens per step.
     const int64_t RB = ceil_div(N, kRowsPerBlock);
+    // Up to four tokens, and up to eight on layers of fewer than 1024 row blocks, the M <= 16 kernel (each wave reads
+    // its own x_q) is the faster one: at eight tokens 3B down 6.1 -> 5.1 us, 7B QKV 6.0 -> 5.5 us, 70B O 6.8 -> 6.1 us;
+    // at sixteen the kernels below win on every layer measured.  A forced split-K stays on the kernels that have one.
+    if (M <= 4 || (M <= 8 && RB < 1024 && force_splits == 0))
+        return launch_linear_gemv16_2bit(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, plan);
+    // More tokens: the activations of a step outweigh the weights a wave reads with them, so they
+    // are staged once per group of waves (skinny kernel), 16 * kMT >= M tokens per step.
     int splits = 1;
     if (force_splits > 0) splits = force_splits;
     else if (workspace && workspace_bytes >= splitk_workspace_bytes(M, N, skinny_splitk_splits(M, N, K)))
