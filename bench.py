@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the BitLinear W1.58A8 hot path (BitNet b1.58, arXiv 2402.17764, Section 2) on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 3b_decode|7b_decode|70b_decode]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 70b_decode|7b_decode|3b_decode]
 
 A "step" is one pass of the per-token hot path over one batch of synthetic activations: for every
 layer of the workload and every projection shape, per-token int8 activation quantization, the
@@ -9,11 +9,14 @@ ternary product and the rescale (M = 1 token for the decode workloads) -- one bi
 launch per product, or bitnet_quantize_acts + bitnet_linear with --unfused.  The step is captured
 once into a HIP graph and replayed, the way a decode loop would run it.  Weight quantization +
 packing (Eq. 1-3) happens once per layer before the timed region, as it does for inference, and is
-timed separately (`weight_quant`).  The prefill GEMM (M = 2048, 13B-class shapes) is timed as its
-own leg (`gemm_m2048`), batched decode (M = 1 ... 64, 7B-class shapes) as `batched_decode_7b`.  Every input is seeded and synthetic (see paper_2402_17764_amd/synth.py for the
-recipe); big tensors are drawn on the device with the same distributions.
+timed separately.  The default workload is the 70B-class feed-forward stack with all 80 layers' packed
+weights resident (14.1 GB); the other configurations are extra legs of the same JSON line: the 3B decode
+step and decoder chain, the 70B feed-forward chain, batched decode on the 7B shapes, the 13B prefill
+GEMM at 2048 and 512 tokens, the 700M-class single layer, the 70B prefill product, and the 5-trit
+format against the 2-bit one.  Every input is seeded and synthetic (see paper_2402_17764_amd/synth.py
+for the recipe); big tensors are drawn on the device with the same distributions.
 
-Prints ONE JSON line.
+Prints ONE JSON line; exits non-zero (after printing it) if any leg failed.
 """
 import argparse
 import json
@@ -35,6 +38,67 @@ WORKLOADS = {
     "7b_decode": (2, 1, 32),
     "70b_decode": (4, 1, 80),
 }
+DEFAULT_WORKLOAD = "70b_decode"
+
+# token counts of the extra legs (the launch inventory below and the legs themselves read these)
+BATCHED_DECODE_MS = (1, 8, 16, 32, 64)
+BATCHED_DECODE_MS_WS = (128, 256)
+GEMM_MS = (2048, 512)
+SMALL_LAYER_MS = (1, 16)
+PREFILL_70B_M = 4096
+LEGS = ["decode_3b_m1", "decoder_chain_3b_m1", "ffn_chain_70b_m1", "batched_decode_7b", "gemm_13b", "layer_700m",
+        "prefill_70b_m4096", "trit5_vs_2bit_m1"]
+
+# what the paper itself reports for this path: whole-model figures on other hardware, context only
+PAPER_REPORTED = {
+    "note": "whole-model numbers from the paper (FasterTransformer + a third-party 2-bit kernel; the GPU of Table 1 / "
+            "Figure 2 is not stated, Table 3 is 2x A100 80GB with pipeline parallelism); no per-layer GEMV or GEMM "
+            "figure is published, so vs_baseline is null",
+    "decode_latency_ms_per_token_fp16_vs_b158 (Table 1)": {"700M": [1.18, 0.96], "1.3B": [1.62, 0.97], "3B": [5.07, 1.87],
+                                                            "3.9B": [None, 2.11]},
+    "decode_speedup_70b (Figure 2, text)": 4.1,
+    "throughput_70b_tokens_per_s_fp16_vs_b158 (Table 3, 2x A100 80GB, seq 512)": [333, 2977],
+    "max_batch_70b_fp16_vs_b158 (Table 3)": [16, 176],
+    "memory_GB_fp16_vs_b158 (Table 1)": {"700M": [2.08, 0.80], "1.3B": [3.34, 1.14], "3B": [7.89, 2.22], "3.9B": [None, 2.38]},
+}
+
+
+def launch_inventory():
+    """Every product launch a default run times, as (leg, entry point, x dtype, M, N, K) with the names of
+    paper_2402_17764_amd.binding.ENTRY_* -- N and K as that entry point takes them.  tests/test_dispatch_cpu.py maps
+    each to the kernel instantiation it gets and checks that a GPU parity test reaches the same instantiation."""
+    from paper_2402_17764_amd import synth
+    inv = []
+    for wl, leg in ((DEFAULT_WORKLOAD, "headline"), ("3b_decode", "decode_3b_m1")):
+        cfg_idx, M, _ = WORKLOADS[wl]
+        for (_, K, N) in synth.CONFIGS[cfg_idx]["shapes"]:
+            inv.append((leg, "LINEAR_FUSED", "bf16", M, N, K))
+    sh = {n: (K, N) for (n, K, N) in synth.CONFIGS[1]["shapes"]}
+    H, F = sh["qkv"][0], sh["down"][0]
+    inv += [("decoder_chain_3b_m1", "RMSNORM_LINEAR_FUSED", "bf16", 1, sh["qkv"][1], H),
+            ("decoder_chain_3b_m1", "LINEAR_FUSED", "bf16", 1, H, H),
+            ("decoder_chain_3b_m1", "FFN_GATE_UP_NORM", "bf16", 1, F, H),
+            ("decoder_chain_3b_m1", "LINEAR_FUSED", "bf16", 1, H, F)]
+    for (_, K, N) in synth.CONFIGS[1]["shapes"]:
+        inv.append(("decoder_chain_3b_m1", "LINEAR", "int8", 1, N, K))
+    sh = {n: (K, N) for (n, K, N) in synth.CONFIGS[4]["shapes"]}
+    H, F = sh["gate_up"][0], sh["down"][0]
+    inv += [("ffn_chain_70b_m1", "FFN_GATE_UP_NORM", "bf16", 1, F, H), ("ffn_chain_70b_m1", "LINEAR_FUSED", "bf16", 1, H, F)]
+    for (_, K, N) in synth.CONFIGS[2]["shapes"]:
+        for M in BATCHED_DECODE_MS + BATCHED_DECODE_MS_WS:
+            inv.append(("batched_decode_7b", "LINEAR", "int8", M, N, K))
+    for (_, K, N) in synth.CONFIGS[3]["shapes"]:
+        for M in GEMM_MS:
+            inv.append(("gemm_13b", "LINEAR", "int8", M, N, K))
+    for (_, K, N) in synth.CONFIGS[0]["shapes"]:
+        for M in SMALL_LAYER_MS:
+            inv.append(("layer_700m", "LINEAR", "int8", M, N, K))
+            inv.append(("layer_700m", "LINEAR_FUSED", "f32", M, N, K))
+    for (_, K, N) in synth.CONFIGS[4]["shapes"]:
+        inv.append(("prefill_70b_m4096", "LINEAR", "int8", PREFILL_70B_M, N, K))
+    for (K, N) in ((3200, 17280), (8192, 57344)):
+        inv.append(("trit5_vs_2bit_m1", "LINEAR", "int8", 1, N, K))
+    return inv
 
 
 def gemv_bytes(M, N, K, out_bytes=2):
@@ -42,18 +106,21 @@ def gemv_bytes(M, N, K, out_bytes=2):
     return N * K // 4 + M * K + 4 * M + M * N * out_bytes
 
 
-def measured_traffic(N, K):
+def measured_traffic(N, K, fused=True):
     """HBM bytes per launch of the M = 1 product on an N x K layer, from the committed rocprofv3 --pmc summary
     (profiles/hbm_traffic.json: FETCH_SIZE + WRITE_SIZE, each scaled by what the counter reads for a plain
-    256 MiB copy).  None if the summary has no entry for this launch shape."""
+    256 MiB copy).  `fused`: the launch that quantizes x itself (fifth template parameter 2 or 3) or the one on int8
+    input (0 or 1).  None if the summary has no entry for this launch shape."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if not os.path.exists(path):
         return None
     with open(path) as f:
         table = json.load(f)
     for key, v in table.get("kernels", {}).items():
-        if key.startswith("linear_gemv16_2bit") and v.get("N") == N and v.get("K") == K:
-            return int(v["fetch_bytes"] + v["write_bytes"])
+        if key.startswith("linear_gemv16_2bit<") and v.get("N") == N and v.get("K") == K:
+            params = key[key.index("<") + 1:key.index(">")].split(",")
+            if len(params) >= 6 and params[5].strip() == "false" and (int(params[4]) in (2, 3)) == fused:
+                return int(v["fetch_bytes"] + v["write_bytes"])
     return None
 
 
@@ -96,116 +163,164 @@ def time_graph(torch, fn, warmup, steps, stream):
     return e0.elapsed_time(e1) / steps, wall_ms / steps, graph
 
 
-def cpu_baseline(cfg_idx, M, seconds_target=12.0):
-    """The oracle's per-token path (activation quantization, integer product, rescale) timed on the
-    host cores for two layer sets of the workload; same algorithmic-bytes unit as the GPU value."""
-    import numpy as np
-    import oracle
-    from paper_2402_17764_amd import synth
-    cfg = synth.CONFIGS[cfg_idx]
-    layers = []
-    nbytes = 0
-    for l in range(2):
-        for t, (name, K, N) in enumerate(cfg["shapes"]):
-            if N * K > 150e6:          # keep host memory and set-up time bounded
-                N = N // 8
-            W = synth.weights(N, K, config=cfg_idx, layer=l, tensor=t)
-            codes, gamma = oracle.quantize_weights(W)
-            x, _ = synth.activations(M, K, config=cfg_idx, layer=l, tensor=100 + t, bf16=True)
-            layers.append((x, codes, gamma, N, K))
-            nbytes += gemv_bytes(M, N, K)
-            del W
-    def one_pass():
-        for (x, codes, gamma, N, K) in layers:
-            xq, sx = oracle.quantize_acts(x)
-            acc = oracle.ternary_matmul(xq, codes)
-            oracle.rescale(acc, gamma, sx)
-    one_pass()
+def _time_cpu(fn, seconds_target):
+    fn()
     t0 = time.perf_counter()
-    one_pass()
+    fn()
     per = time.perf_counter() - t0
     reps = max(1, min(200, int(seconds_target / max(per, 1e-6))))
     t0 = time.perf_counter()
     for _ in range(reps):
-        one_pass()
-    dt = (time.perf_counter() - t0) / reps
-    return {
+        fn()
+    return (time.perf_counter() - t0) / reps, reps
+
+
+def cpu_baseline(cfg_idx, M, seconds_target=8.0):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the headline workload: the per-token
+    path (activation quantization, integer product, rescale) over one layer set whose matrices keep every eighth of
+    their rows when they exceed 150 M weights (the work per byte of a weight-streaming product does not depend on the
+    row count); same algorithmic-bytes unit as the GPU value.  `other_configs` holds the same measurement for the
+    remaining benchmark configurations, each on a stated sample, and the oracle's weight quantization."""
+    import numpy as np
+    import oracle
+    from paper_2402_17764_amd import synth
+
+    def layer_set(ci, M, max_weights=150e6, tokens=None):
+        cfg = synth.CONFIGS[ci]
+        layers, nbytes, ops = [], 0, 0
+        for t, (name, K, N) in enumerate(cfg["shapes"]):
+            while N * K > max_weights:
+                N = N // 8
+            W = synth.weights(N, K, config=ci, layer=0, tensor=t)
+            codes, gamma = oracle.quantize_weights(W)
+            x, _ = synth.activations(tokens or M, K, config=ci, layer=0, tensor=100 + t, bf16=True)
+            layers.append((x, codes, gamma, N, K))
+            nbytes += gemv_bytes(tokens or M, N, K)
+            ops += 2 * (tokens or M) * N * K
+            del W
+
+        def one_pass():
+            for (x, codes, gamma, N, K) in layers:
+                xq, sx = oracle.quantize_acts(x)
+                acc = oracle.ternary_matmul(xq, codes)
+                oracle.rescale(acc, gamma, sx)
+        return one_pass, nbytes, ops, [(N, K) for (_, _, _, N, K) in layers]
+
+    cfg = synth.CONFIGS[cfg_idx]
+    one_pass, nbytes, _, dims = layer_set(cfg_idx, M)
+    dt, reps = _time_cpu(one_pass, seconds_target)
+    out = {
         "value": round(nbytes / dt / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
-        "sample": "2 layer sets of %s at M=%d (%d product calls, %.0f MB of packed-weight-equivalent bytes), "
-                  "activation quantization + integer product + rescale, mean of %d passes"
-                  % (cfg["name"], M, len(layers), nbytes / 1e6, reps),
+        "sample": "one layer set of %s at M=%d with the row counts cut to %s (N x K; %.0f MB of algorithmic bytes per pass), "
+                  "activation quantization + integer product + rescale, mean of %d passes; sampled, not extrapolated"
+                  % (cfg["name"], M, dims, nbytes / 1e6, reps),
+    }
+    other = {}
+    for (tag, ci, m, tok, cap) in (("700m_layer_m1", 0, 1, None, 150e6), ("700m_layer_m16", 0, 16, None, 150e6),
+                                   ("3b_decode_m1", 1, 1, None, 150e6), ("7b_decode_m1", 2, 1, None, 150e6),
+                                   ("7b_decode_m64", 2, 64, None, 12e6), ("13b_prefill_m512", 3, 512, 16, 12e6)):
+        if ci == cfg_idx and m == M:
+            continue
+        fn, nb, ops, dims = layer_set(ci, m, max_weights=cap, tokens=tok)
+        dt, reps = _time_cpu(fn, 1.5)
+        other[tag] = {"GB/s": round(nb / dt / 1e9, 3), "TOPS": round(ops / dt / 1e12, 5), "passes": reps,
+                      "sample": "one layer set, rows cut to %s%s" % (dims, ", %d of %d tokens" % (tok, m) if tok else "")}
+    W = synth.weights(4096, 4096, config=2, layer=0, tensor=1)
+    dt, reps = _time_cpu(lambda: oracle.quantize_weights(W), 1.5)
+    other["weight_quant_4096x4096"] = {"GB/s": round(8.25 * W.size / dt / 1e9, 3), "passes": reps,
+                                       "note": "Eq. (1)-(3) without packing, 8.25 algorithmic bytes per weight"}
+    out["other_configs"] = other
+    return out
+
+
+def decode_workload(torch, B, synth, gen, stream, args, workload):
+    """One decode workload: weights drawn, quantized and packed through the library (timed per call), the step
+    (every product of every layer, M tokens) as one HIP graph, and the same for the dominant product alone."""
+    cfg_idx, M, L = WORKLOADS[workload]
+    cfg = synth.CONFIGS[cfg_idx]
+    shapes = cfg["shapes"]
+    packed, wq_ms, wq_bytes = {}, 0.0, 0
+    ws_bytes = max(B.quantize_weights_workspace(N, K) for (_, K, N) in shapes)
+    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    for l in range(L):
+        for (name, K, N) in shapes:
+            W = torch.randn((N, K), device="cuda", generator=gen, dtype=torch.float32) * synth.SIGMA_W
+            if l == 0:
+                B.quantize_weights(W, workspace=workspace)          # warm the code path
+                torch.cuda.synchronize()
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            packed[(l, name)] = B.quantize_weights(W, workspace=workspace)
+            e1.record()
+            torch.cuda.synchronize()
+            wq_ms += e0.elapsed_time(e1)
+            wq_bytes += int(N * K * 8.25)
+            del W
+    acts = {K: make_acts(torch, M, K, gen, cfg_idx) for K in sorted({K for (_, K, _) in shapes})}
+    xq = {K: torch.empty((M, K), dtype=torch.int8, device="cuda") for K in acts}
+    sx = {K: torch.empty(M, dtype=torch.float32, device="cuda") for K in acts}
+    ys = {name: torch.empty((M, N), dtype=torch.bfloat16, device="cuda") for (name, K, N) in shapes}
+
+    def step():
+        for l in range(L):
+            for (name, K, N) in shapes:
+                p, g = packed[(l, name)]
+                if args.unfused:
+                    B.quantize_acts(acts[K], xq=xq[K], sx=sx[K])
+                    B.linear(xq[K], sx[K], p, g, N, y_dtype=B.BF16, y=ys[name])
+                else:
+                    B.linear_fused(acts[K], p, g, N, y_dtype=B.BF16, y=ys[name])
+
+    ms_per_step, _, _ = time_graph(torch, step, args.warmup, args.steps, stream)
+    step_bytes = L * sum(gemv_bytes(M, N, K) for (_, K, N) in shapes)
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # per-shape launch time (each shape alone, one launch per layer on that layer's own weights) and the roofline of
+    # the dominant kernel: the product on the shape that moves the most bytes
+    per_shape = {}
+    for (name, K, N) in shapes:
+        B.quantize_acts(acts[K], xq=xq[K], sx=sx[K])
+
+        def only(name=name, K=K, N=N):
+            for l in range(L):
+                p, g = packed[(l, name)]
+                if args.unfused:
+                    B.linear(xq[K], sx[K], p, g, N, y_dtype=B.BF16, y=ys[name])
+                else:
+                    B.linear_fused(acts[K], p, g, N, y_dtype=B.BF16, y=ys[name])
+
+        ms, _, _ = time_graph(torch, only, args.warmup, args.steps, stream)
+        us = ms * 1e3 / L
+        nb = gemv_bytes(M, N, K)
+        per_shape[name] = {"K": K, "N": N, "us_per_launch": round(us, 3), "bytes_per_launch": nb,
+                           "GB/s": round(nb / (us * 1e-6) / 1e9, 1), "frac_hbm_peak": round(nb / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                           "traffic": measured_traffic(N, K, fused=not args.unfused)}
+    dname, dK, dN = max(shapes, key=lambda s: s[1] * s[2])
+    d = per_shape[dname]
+    roofline = {
+        "bound": "hbm", "kernel": "linear_gemv16_2bit", "shape": "%s K=%d N=%d M=%d" % (dname, dK, dN, M),
+        "achieved": d["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": d["frac_hbm_peak"],
+        "bytes_per_launch": d["bytes_per_launch"], "us_per_launch": d["us_per_launch"], "traffic": d["traffic"],
+        "traffic_source": "profiles/hbm_traffic.json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this benchmark, "
+                          "committed with the tree (not re-measured in this run)",
+    }
+    return {
+        "value": round(value, 1), "ms_per_step": round(ms_per_step, 5), "bytes_per_step": step_bytes,
+        "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2), "roofline": roofline, "per_shape": per_shape,
+        "workload": "%s: %s, M=%d, %d layer sets x %s, bf16 in/out, 2-bit packed weights, %.2f GB of packed weights resident"
+                    % (workload, cfg["name"], M, L, [(n, k, nn) for (n, k, nn) in shapes],
+                       L * sum(N * K // 4 for (_, K, N) in shapes) / 1e9),
+        "launch": "HIP graph replay of %d x %s" % (L * len(shapes), "(bitnet_quantize_acts + bitnet_linear)"
+                                                     if args.unfused else "bitnet_linear_fused"),
+        "weight_quant": {"ms_per_pass": round(wq_ms, 3), "tensors": L * len(shapes),
+                         "ms_per_tensor_mean": round(wq_ms / (L * len(shapes)), 4),
+                         "GB/s": round(wq_bytes / (wq_ms * 1e-3) / 1e9, 1),
+                         "note": "quantize + pack of every layer, 8.25 algorithmic bytes per weight"},
     }
 
 
-def large_gemv_leg(torch, B, synth, gen, stream, args):
-    """The 70B-class FFN shapes (the sizes at which a weight stream can approach the HBM roofline): M = 1 with each
-    shape replayed over 2.4 GB of distinct layers (a quarter of the model's 80: far beyond the 256 MB memory-side
-    cache, and enough launches per graph replay that the gap between replays does not show), the M = 4096 prefill
-    product, and the one-off weight quantization + packing time per layer."""
-    res = {}
-    for (name, K, N) in synth.CONFIGS[4]["shapes"]:
-        per = N * K // 4
-        layers = max(3, int(math.ceil(2.4e9 / per)))
-        packs = []
-        wq_ms = []
-        for l in range(layers):
-            W = torch.randn((N, K), device="cuda", generator=gen, dtype=torch.float32) * synth.SIGMA_W
-            if l >= 1:
-                torch.cuda.synchronize()
-                e0 = torch.cuda.Event(enable_timing=True)
-                e1 = torch.cuda.Event(enable_timing=True)
-                e0.record()
-                packs.append(B.quantize_weights(W))
-                e1.record()
-                torch.cuda.synchronize()
-                wq_ms.append(e0.elapsed_time(e1))
-            else:
-                packs.append(B.quantize_weights(W))
-            del W
-        x = make_acts(torch, 1, K, gen, 4)
-        y = torch.empty((1, N), dtype=torch.bfloat16, device="cuda")
-
-        def run():
-            for (p, g) in packs:
-                B.linear_fused(x, p, g, N, y_dtype=B.BF16, y=y)
-
-        ms, _, _ = time_graph(torch, run, args.warmup, args.steps, stream)
-        us = ms * 1e3 / layers
-        gbs = gemv_bytes(1, N, K) / (us * 1e-6) / 1e9
-        res[name] = {"K": K, "N": N, "layers": layers, "us_per_launch": round(us, 2), "GB/s": round(gbs, 1),
-                     "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
-                     "weight_quant_ms_per_layer": round(min(wq_ms), 3),
-                     "weight_quant_GB/s": round(8.25 * N * K / (min(wq_ms) * 1e-3) / 1e9, 1)}
-        # prefill on the same shape
-        M = 4096
-        xp = make_acts(torch, M, K, gen, 4)
-        xq, sx = B.quantize_acts(xp)
-        del xp
-        yp = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
-        p0, g0 = packs[0]
-        t_w = time.perf_counter()
-        while time.perf_counter() - t_w < 0.030:
-            B.linear(xq, sx, p0, g0, N, y_dtype=B.BF16, y=yp)
-            torch.cuda.synchronize()
-        iters = 5
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(iters):
-            B.linear(xq, sx, p0, g0, N, y_dtype=B.BF16, y=yp)
-        e1.record()
-        torch.cuda.synchronize()
-        us_p = e0.elapsed_time(e1) * 1e3 / iters
-        tops = 2.0 * M * N * K / (us_p * 1e-6) / 1e12
-        res[name]["prefill_m4096"] = {"us_linear": round(us_p, 1), "TOPS": round(tops, 1),
-                                      "frac_int8_mfma_peak": round(tops / INT8_MFMA_PEAK_TOPS, 4)}
-        del packs, xq, sx, yp
-        torch.cuda.empty_cache()
-    res["ffn_chain_m1"] = large_ffn_chain(torch, B, synth, gen, stream, args)
-    return res
-
-
-def large_ffn_chain(torch, B, synth, gen, stream, args, layers=80):
+def ffn_chain_70b_leg(torch, B, synth, gen, stream, args, layers=80):
     """One token through the feed-forward halves of all 80 layers of the 70B-class model, every layer's packed
     weights resident (14.1 GB), as one HIP graph of two launches per layer: the merged gate/up projection with
     RMSNorm + quantization in front and the SwiGLU gate in its epilogue, then the down projection with absmax
@@ -245,6 +360,118 @@ def large_ffn_chain(torch, B, synth, gen, stream, args, layers=80):
     del packs
     torch.cuda.empty_cache()
     return out
+
+
+def _time_eager(torch, fn, iters, warm_s=0.030, warm_min=3):
+    """fn() launched back to back on the current stream, HIP events around `iters` calls; warmed for at least warm_s."""
+    t_w = time.perf_counter()
+    done = 0
+    while done < warm_min or time.perf_counter() - t_w < warm_s:
+        fn()
+        done += 1
+        if done % 8 == 0:
+            torch.cuda.synchronize()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / iters
+
+
+def prefill_70b_leg(torch, B, synth, gen, stream, args):
+    """The 70B-class FFN shapes at M = 4096 (the prefill end of the last configuration's sweep) and the one-off weight
+    quantization + packing time per layer."""
+    res = {}
+    M = PREFILL_70B_M
+    for (name, K, N) in synth.CONFIGS[4]["shapes"]:
+        wq_ms, pack = [], None
+        for l in range(4):
+            W = torch.randn((N, K), device="cuda", generator=gen, dtype=torch.float32) * synth.SIGMA_W
+            torch.cuda.synchronize()
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            pack = B.quantize_weights(W)
+            e1.record()
+            torch.cuda.synchronize()
+            if l >= 1:
+                wq_ms.append(e0.elapsed_time(e1))
+            del W
+        xp = make_acts(torch, M, K, gen, 4)
+        xq, sx = B.quantize_acts(xp)
+        yp = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        p0, g0 = pack
+        us_p = _time_eager(torch, lambda: B.linear(xq, sx, p0, g0, N, y_dtype=B.BF16, y=yp), 5)
+        us_q = _time_eager(torch, lambda: B.quantize_acts(xp, xq=xq, sx=sx), 5)
+        tops = 2.0 * M * N * K / (us_p * 1e-6) / 1e12
+        res[name] = {"K": K, "N": N, "M": M, "us_linear": round(us_p, 1), "us_quantize_acts": round(us_q, 1), "TOPS": round(tops, 1),
+                     "frac_int8_mfma_peak": round(tops / INT8_MFMA_PEAK_TOPS, 4),
+                     "weight_quant_ms_per_layer": round(min(wq_ms), 3),
+                     "weight_quant_GB/s": round(8.25 * N * K / (min(wq_ms) * 1e-3) / 1e9, 1)}
+        del pack, xq, sx, yp, xp
+        torch.cuda.empty_cache()
+    return res
+
+
+def small_layer_leg(torch, B, synth, gen, stream, args):
+    """The 700M-class single layer (1536 -> 4096, fp32 activations) at M = 1 and 16: the one-launch fused entry point
+    and the two-call route, each replayed over enough distinct layers to exceed the memory-side cache; plus its weight
+    quantization.  A 1.5 MB weight stream is 0.2 us at the HBM peak: these launches are latency-bound."""
+    res = {}
+    for (name, K, N) in synth.CONFIGS[0]["shapes"]:
+        layers = 400                                   # 630 MB of packed weights
+        packs, wq = [], []
+        for l in range(layers):
+            W = torch.randn((N, K), device="cuda", generator=gen, dtype=torch.float32) * synth.SIGMA_W
+            if l in (5, 6, 7):
+                torch.cuda.synchronize()
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                packs.append(B.quantize_weights(W))
+                e1.record()
+                torch.cuda.synchronize()
+                wq.append(e0.elapsed_time(e1))
+            else:
+                packs.append(B.quantize_weights(W))
+            del W
+        entry = {"K": K, "N": N, "layers": layers, "weight_quant_us": round(min(wq) * 1e3, 1)}
+        for M in SMALL_LAYER_MS:
+            x = torch.randn((M, K), device="cuda", generator=gen, dtype=torch.float32)
+            ch = torch.from_numpy(synth.outlier_channels(K, config=0)).cuda()
+            x[:, ch] *= synth.OUTLIER_SCALE
+            xq, sx = B.quantize_acts(x)
+            y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+
+            def run_fused():
+                for (p, g) in packs:
+                    B.linear_fused(x, p, g, N, y_dtype=B.F32, y=y)
+
+            def run_two():
+                for (p, g) in packs:
+                    B.quantize_acts(x, xq=xq, sx=sx)
+                    B.linear(xq, sx, p, g, N, y_dtype=B.F32, y=y)
+
+            def run_linear():
+                for (p, g) in packs:
+                    B.linear(xq, sx, p, g, N, y_dtype=B.F32, y=y)
+
+            nb = gemv_bytes(M, N, K, out_bytes=4)
+            e = {}
+            for tag, fn in (("linear_fused", run_fused), ("quantize_acts+linear", run_two), ("linear", run_linear)):
+                ms, _, gr = time_graph(torch, fn, max(2, args.warmup // 5), max(5, args.steps // 5), stream)
+                us = ms * 1e3 / layers
+                e[tag] = {"us_per_layer": round(us, 2), "GB/s": round(nb / (us * 1e-6) / 1e9, 1)}
+                del gr
+            entry["M=%d" % M] = e
+        res[name] = entry
+        del packs
+        torch.cuda.empty_cache()
+    return res
 
 
 def format_leg(torch, B, synth, gen, stream, args):
@@ -295,7 +522,7 @@ def batched_decode_leg(torch, B, synth, gen, stream, args):
             packs.append(B.quantize_weights(W))
             del W
         entry = {"K": K, "N": N, "layers": layers}
-        for M in (1, 8, 16, 32, 64):
+        for M in BATCHED_DECODE_MS:
             x = make_acts(torch, M, K, gen, 2)
             xq, sx = B.quantize_acts(x)
             y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
@@ -312,7 +539,7 @@ def batched_decode_leg(torch, B, synth, gen, stream, args):
             del graph
         # the serving regime just above 64 tokens: small layers still run the token-tiled decode kernels, the others
         # the prefill kernel, timed without and with a split-K workspace (bitnet_linear_ws)
-        for M in (128, 256):
+        for M in BATCHED_DECODE_MS_WS:
             x = make_acts(torch, M, K, gen, 2)
             xq, sx = B.quantize_acts(x)
             y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
@@ -405,8 +632,8 @@ def decoder_block_leg(torch, B, synth, gen, stream, args, cfg_idx=1, layers=26):
                                       "linear(gate_up), swiglu_quantize, linear(down) per layer"}}
 
 
-def gemm_leg(torch, B, synth, gen, args, M=2048):
-    """Prefill: M = 2048 tokens on the 13B-class shapes, bitnet_quantize_acts + bitnet_linear (MFMA kernel)."""
+def gemm_one_m(torch, B, synth, gen, args, M):
+    """Prefill: M tokens on the 13B-class shapes, bitnet_quantize_acts + bitnet_linear."""
     res = {"M": M, "shapes": {}}
     tot_ops, tot_us = 0.0, 0.0
     for (name, K, N) in synth.CONFIGS[3]["shapes"]:
@@ -441,19 +668,25 @@ def gemm_leg(torch, B, synth, gen, args, M=2048):
         us_q = e0.elapsed_time(e1) * 1e3 / iters
         ops = 2.0 * M * N * K
         res["shapes"][name] = {"K": K, "N": N, "us_linear": round(us, 1), "us_quantize_acts": round(us_q, 1),
-                               "TOPS": round(ops / us * 1e-6, 1), "frac_int8_mfma_peak": round(ops / us * 1e-6 / INT8_MFMA_PEAK_TOPS, 4)}
+                               "kernel": B.linear_describe(M, N, K)["kernel"], "TOPS": round(ops / us * 1e-6, 1), "frac_int8_mfma_peak": round(ops / us * 1e-6 / INT8_MFMA_PEAK_TOPS, 4)}
         tot_ops += ops
         tot_us += us
         del p, x, xq, y
         torch.cuda.empty_cache()
     res["TOPS"] = round(tot_ops / tot_us * 1e-6, 1)
-    res["roofline"] = {"bound": "mfma", "kernel": "linear_gemm_2bit", "achieved": round(tot_ops / tot_us * 1e-6, 1),
+    res["roofline"] = {"bound": "mfma", "kernel": "linear_gemm_2bit", "workload": "13B-class layer set, M=%d" % M, "achieved": round(tot_ops / tot_us * 1e-6, 1),
                        "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(tot_ops / tot_us * 1e-6 / INT8_MFMA_PEAK_TOPS, 4)}
     return res
 
 
+def gemm_leg(torch, B, synth, gen, args):
+    """Prefill on the 13B-class shapes at 2048 tokens (the size the GEMM metric is quoted on) and at 512."""
+    return {"M=%d" % M: gemm_one_m(torch, B, synth, gen, args, M) for M in GEMM_MS}
+
+
 def run_leg_in_child(leg, args):
-    """One extra leg in a child process (this process keeps its GPU context and waits)."""
+    """One extra leg in a child process (this process keeps its GPU context and waits).  A leg that fails comes back
+    as {"error": ...}; main() then exits non-zero after printing its line."""
     import subprocess
     cmd = [sys.executable, os.path.abspath(__file__), "--only", leg, "--steps", str(args.steps), "--warmup", str(args.warmup)]
     try:
@@ -474,19 +707,18 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="3b_decode", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--unfused", action="store_true",
                     help="two launches per product (bitnet_quantize_acts + bitnet_linear) instead of bitnet_linear_fused")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (torch copy_) three times, so that a rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE run of this command contains a kernel of known traffic to scale by")
-    ap.add_argument("--no-extras", action="store_true", help="skip the weight_quant and large-shape legs")
+    ap.add_argument("--no-extras", action="store_true", help="skip the extra legs")
     ap.add_argument("--inprocess", action="store_true",
                     help="run the extra legs inside this process (one process for a profiler to follow); by default "
                          "each runs in a child process, so that a failure there cannot take the headline line with it")
-    ap.add_argument("--only", default=None,
-                    choices=["gemm_m2048", "gemv_70b_m1", "batched_decode_7b", "trit5_vs_2bit_m1", "decoder_chain_3b_m1"],
+    ap.add_argument("--only", default=None, choices=LEGS,
                     help="run one of the extra legs alone and print only its result (profiling a single kernel family)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -509,124 +741,71 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    cfg_idx, M, L = WORKLOADS[args.workload]
-    cfg = synth.CONFIGS[cfg_idx]
-    shapes = cfg["shapes"]
     gen = torch.Generator(device="cuda")
     gen.manual_seed(240217764)
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+
+    def leg_3b():
+        r = decode_workload(torch, B, synth, gen, stream, args, "3b_decode")
+        torch.cuda.empty_cache()
+        return r
+
+    legs = {"decode_3b_m1": leg_3b,
+            "decoder_chain_3b_m1": lambda: decoder_block_leg(torch, B, synth, gen, stream, args),
+            "ffn_chain_70b_m1": lambda: ffn_chain_70b_leg(torch, B, synth, gen, stream, args),
+            "batched_decode_7b": lambda: batched_decode_leg(torch, B, synth, gen, stream, args),
+            "gemm_13b": lambda: gemm_leg(torch, B, synth, gen, args),
+            "layer_700m": lambda: small_layer_leg(torch, B, synth, gen, stream, args),
+            "prefill_70b_m4096": lambda: prefill_70b_leg(torch, B, synth, gen, stream, args),
+            "trit5_vs_2bit_m1": lambda: format_leg(torch, B, synth, gen, stream, args)}
+    assert sorted(legs) == sorted(LEGS)
 
     if args.only:
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        legs = {"gemm_m2048": lambda: gemm_leg(torch, B, synth, gen, args),
-                "gemv_70b_m1": lambda: large_gemv_leg(torch, B, synth, gen, side, args),
-                "batched_decode_7b": lambda: batched_decode_leg(torch, B, synth, gen, side, args),
-                "trit5_vs_2bit_m1": lambda: format_leg(torch, B, synth, gen, side, args),
-                "decoder_chain_3b_m1": lambda: decoder_block_leg(torch, B, synth, gen, side, args)}
         print(json.dumps({"only": args.only, "steps": args.steps, "warmup": args.warmup, args.only: legs[args.only]()}))
         return
 
-    # ---- weights: draw, quantize + pack through the library (timed per call with events) ----------
-    packed, wq_ms, wq_bytes = {}, 0.0, 0
-    ws_bytes = max(B.quantize_weights_workspace(N, K) for (_, K, N) in shapes)
-    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
-    for l in range(L):
-        for (name, K, N) in shapes:
-            W = torch.randn((N, K), device="cuda", generator=gen, dtype=torch.float32) * synth.SIGMA_W
-            if l == 0:
-                B.quantize_weights(W, workspace=workspace)          # warm the code path
-                torch.cuda.synchronize()
-            e0 = torch.cuda.Event(enable_timing=True)
-            e1 = torch.cuda.Event(enable_timing=True)
-            e0.record()
-            packed[(l, name)] = B.quantize_weights(W, workspace=workspace)
-            e1.record()
-            torch.cuda.synchronize()
-            wq_ms += e0.elapsed_time(e1)
-            wq_bytes += int(N * K * 8.25)
-            del W
-    acts = {K: make_acts(torch, M, K, gen, cfg_idx) for K in sorted({K for (_, K, _) in shapes})}
-    xq = {K: torch.empty((M, K), dtype=torch.int8, device="cuda") for K in acts}
-    sx = {K: torch.empty(M, dtype=torch.float32, device="cuda") for K in acts}
-    ys = {name: torch.empty((M, N), dtype=torch.bfloat16, device="cuda") for (name, K, N) in shapes}
-
-    def step():
-        for l in range(L):
-            for (name, K, N) in shapes:
-                p, g = packed[(l, name)]
-                if args.unfused:
-                    B.quantize_acts(acts[K], xq=xq[K], sx=sx[K])
-                    B.linear(xq[K], sx[K], p, g, N, y_dtype=B.BF16, y=ys[name])
-                else:
-                    B.linear_fused(acts[K], p, g, N, y_dtype=B.BF16, y=ys[name])
-
-    stream = torch.cuda.Stream()
-    stream.wait_stream(torch.cuda.current_stream())
-    ms_per_step, wall_ms, _ = time_graph(torch, step, args.warmup, args.steps, stream)
-    step_bytes = L * sum(gemv_bytes(M, N, K) for (_, K, N) in shapes)
-    value = step_bytes / (ms_per_step * 1e-3) / 1e9
-
-    # ---- roofline of the dominant kernel: the product on the shape that moves the most bytes --------
-    dom = max(shapes, key=lambda s: s[1] * s[2])
-    dname, dK, dN = dom
-    B.quantize_acts(acts[dK], xq=xq[dK], sx=sx[dK])
-
-    def dom_only():
-        for l in range(L):
-            p, g = packed[(l, dname)]
-            if args.unfused:
-                B.linear(xq[dK], sx[dK], p, g, dN, y_dtype=B.BF16, y=ys[dname])
-            else:
-                B.linear_fused(acts[dK], p, g, dN, y_dtype=B.BF16, y=ys[dname])
-
-    dom_ms, _, _ = time_graph(torch, dom_only, args.warmup, args.steps, stream)
-    dom_us = dom_ms * 1e3 / L
-    dom_bytes = gemv_bytes(M, dN, dK)
-    achieved = dom_bytes / (dom_us * 1e-6) / 1e9
-    roofline = {
-        "bound": "hbm", "kernel": "linear_gemv16_2bit", "shape": "%s K=%d N=%d M=%d" % (dname, dK, dN, M),
-        "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "bytes_per_launch": dom_bytes, "us_per_launch": round(dom_us, 3), "traffic": measured_traffic(dN, dK),
-    }
-
+    head = decode_workload(torch, B, synth, gen, stream, args, args.workload)
+    cfg_idx, M, L = WORKLOADS[args.workload]
     out = {
-        "metric": "BitLinear GEMV GB/s (%HBM peak) @M=1", "value": round(value, 1), "unit": "GB/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8xint2->int32",
+        "metric": "BitLinear GEMV GB/s (%HBM peak) @M=1", "value": head["value"], "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8 (2-bit ternary weights, int32 accumulation)",
         "data": "synthetic",
-        "config": {"workload": "%s: %s, M=%d, %d layer sets x %s, bf16 in/out, 2-bit packed weights"
-                               % (args.workload, cfg["name"], M, L, [(n, k, nn) for (n, k, nn) in shapes]),
-                   "launch": "HIP graph replay of %d x %s" % (L * len(shapes), "(bitnet_quantize_acts + bitnet_linear)"
-                                                                if args.unfused else "bitnet_linear_fused"),
-                   "bytes_per_step": step_bytes},
-        "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
-        "roofline": roofline,
+        "config": {"workload": head["workload"], "launch": head["launch"], "bytes_per_step": head["bytes_per_step"]},
+        "pct_hbm_peak": head["pct_hbm_peak"],
+        "roofline": head["roofline"],
+        "per_shape": head["per_shape"],
+        "weight_quant": head["weight_quant"],
+        "paper_reported": PAPER_REPORTED,
     }
+    del head
+    torch.cuda.empty_cache()
 
+    failed = []
     if not args.no_extras:
-        out["weight_quant"] = {"ms_per_pass": round(wq_ms, 3), "tensors": L * len(shapes),
-                               "GB/s": round(wq_bytes / (wq_ms * 1e-3) / 1e9, 1),
-                               "note": "quantize + pack of every layer, 8.25 algorithmic bytes per weight"}
-        del packed, acts
-        torch.cuda.empty_cache()
-        legs = ["gemv_70b_m1", "gemm_m2048", "batched_decode_7b", "trit5_vs_2bit_m1", "decoder_chain_3b_m1"]
+        names = list(LEGS)
+        if args.workload == "3b_decode":
+            names.remove("decode_3b_m1")
         if args.pmc_calibration:
             # under counter collection the 208-launch decoder chain is left out: one such run ended in a hardware
             # exception inside the profiler's queue that no un-profiled or kernel-trace run of the leg shows
-            legs.remove("decoder_chain_3b_m1")
-        inproc = {"gemv_70b_m1": lambda: large_gemv_leg(torch, B, synth, gen, stream, args),
-                  "gemm_m2048": lambda: gemm_leg(torch, B, synth, gen, args),
-                  "batched_decode_7b": lambda: batched_decode_leg(torch, B, synth, gen, stream, args),
-                  "trit5_vs_2bit_m1": lambda: format_leg(torch, B, synth, gen, stream, args),
-                  "decoder_chain_3b_m1": lambda: decoder_block_leg(torch, B, synth, gen, stream, args)}
-        for leg in legs:
-            if args.inprocess:
-                out[leg] = inproc[leg]()
-            else:
-                out[leg] = run_leg_in_child(leg, args)
+            names.remove("decoder_chain_3b_m1")
+        for leg in names:
+            out[leg] = legs[leg]() if args.inprocess else run_leg_in_child(leg, args)
+            if isinstance(out[leg], dict) and "error" in out[leg]:
+                failed.append(leg)
+        if "gemm_13b" in out and "M=2048" in out["gemm_13b"]:
+            out["roofline_gemm_m2048"] = out["gemm_13b"]["M=2048"].get("roofline")
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg_idx, M)
+    if failed:
+        out["failed_legs"] = failed
     print(json.dumps(out))
+    sys.stdout.flush()
+    if failed:
+        print("bench.py: legs failed: %s" % ", ".join(failed), file=sys.stderr)
+        sys.exit(1)
 
 
 if __name__ == "__main__":

@@ -153,6 +153,32 @@ bitnet_status bitnet_quantize_weights(const void* W, bitnet_dtype w_dtype, int64
                                       void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Eq. (3) for a matrix whose rows are spread over several devices (or quantized in several pieces): gamma is the
+ * mean of |W| over the WHOLE matrix, so each holder of a row shard first reports its share of the sum, the shares
+ * are exchanged (G pairs of doubles; between GPUs an all-gather of 16 bytes each), and every holder then quantizes
+ * its rows with the gamma of the whole.  Codes and gamma are bit-identical to one bitnet_quantize_weights call on the
+ * whole matrix: the shares are exact (double-double) sums, so neither the split nor the order of the pairs shows.
+ *
+ * bitnet_abs_sum: sum[0] + sum[1] = sum_ij |W_ij| over these N rows, as a normalised double-double pair.
+ *   W          [N][K], F32 or BF16, element-aligned
+ *   sum        out, 2 doubles (device), 8-byte aligned
+ *   workspace  as for bitnet_quantize_weights (same size query)
+ *
+ * bitnet_quantize_weights_sharded: Eq. (1)-(2) and the packing of bitnet_quantize_weights for these N rows, with
+ * gamma = fp32((sum of the nsums pairs) / (total_rows * K)).
+ *   sums        nsums consecutive (hi, lo) pairs (device), e.g. the gathered outputs of bitnet_abs_sum; 1 <= nsums <= 256
+ *   total_rows  rows of the whole matrix (>= N)
+ *   packed      out, bitnet_packed_bytes(N, K, f) bytes: the packed layout of the shard's own [N][K] matrix
+ *   gamma       out, 1 float (device): the gamma of the whole matrix
+ * One launch for the 2-bit format (the packing pass folds the pairs itself), two for the 5-trit format.  No workspace.
+ */
+bitnet_status bitnet_abs_sum(const void* W, bitnet_dtype w_dtype, int64_t N, int64_t K, double* sum, void* workspace,
+                             size_t workspace_bytes, void* stream);
+bitnet_status bitnet_quantize_weights_sharded(const void* W, bitnet_dtype w_dtype, int64_t N, int64_t K, bitnet_format f,
+                                              const double* sums, int nsums, int64_t total_rows, void* packed,
+                                              float* gamma, void* stream);
+
+/*
  * Section 2, activation quantization: x -> int8 codes + one scale per token.
  *   x    [M][K], dtype F32 or BF16, element-aligned (16-byte aligned rows take the vector path)
  *   xq   out [M][K] int8
@@ -227,6 +253,32 @@ bitnet_status bitnet_linear_variant(const int8_t* xq, const float* sx, const voi
  */
 bitnet_status bitnet_linear_describe(int64_t M, int64_t N, int64_t K, bitnet_format f, size_t workspace_bytes,
                                      char* text, size_t text_bytes);
+
+/*
+ * The same for the entry points that quantize x inside the decode launch (Section 2: per-token activation
+ * quantization; "LLaMA-alike components": RMSNorm, SwiGLU): which instantiation of the decode kernel a call of
+ * `entry` with these sizes would launch.  Host only, nothing is launched.  With it every launch a benchmark or a
+ * serving loop makes can be listed and matched against the forms the parity tests reach.
+ *   entry    which entry point; BITNET_ENTRY_LINEAR is bitnet_linear_describe
+ *   x_dtype  F32 or BF16 (the kernel is instantiated per input type); ignored for BITNET_ENTRY_LINEAR
+ *   N, K     as the entry point takes them: for BITNET_ENTRY_SWIGLU_LINEAR_FUSED K is its F, for the two
+ *            BITNET_ENTRY_FFN_GATE_UP_* N is its F (the packed matrix has 2 F rows)
+ *   text     as bitnet_linear_describe; the fifth decode parameter is the activation source: 0 int8 from global
+ *            memory, 1 int8 staged in LDS, 2 / 3 bf16 / fp32 x quantized in the kernel, 4 / 5 RMSNorm first,
+ *            6 / 7 SwiGLU first; family "decode_pair" is the gate/up launch with the gate in its epilogue
+ * BITNET_ERR_KERNEL where the entry point would refuse the shape.
+ */
+typedef enum bitnet_entry {
+    BITNET_ENTRY_LINEAR = 0,
+    BITNET_ENTRY_LINEAR_FUSED = 1,
+    BITNET_ENTRY_RMSNORM_LINEAR_FUSED = 2,
+    BITNET_ENTRY_SWIGLU_LINEAR_FUSED = 3,
+    BITNET_ENTRY_FFN_GATE_UP = 4,            /* bitnet_ffn_gate_up_fused with norm == 0 */
+    BITNET_ENTRY_FFN_GATE_UP_NORM = 5,       /* ... with norm != 0 */
+    BITNET_ENTRY_INT_RANGE_ = 0x7fffffff
+} bitnet_entry;
+bitnet_status bitnet_entry_describe(bitnet_entry entry, bitnet_dtype x_dtype, int64_t M, int64_t N, int64_t K,
+                                    bitnet_format f, size_t workspace_bytes, char* text, size_t text_bytes);
 
 /*
  * bitnet_linear with a scratch buffer.  Between decode and large prefill -- a few hundred tokens on layers with few

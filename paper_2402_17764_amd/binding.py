@@ -18,6 +18,8 @@ OK = 0
 F32, BF16, I32 = 0, 1, 2
 PACK_2BIT, PACK_TRIT5 = 0, 1
 KERNEL_AUTO, KERNEL_REFERENCE, KERNEL_GEMV, KERNEL_GEMM = 0, 1, 2, 3
+ENTRY_LINEAR, ENTRY_LINEAR_FUSED, ENTRY_RMSNORM_LINEAR_FUSED, ENTRY_SWIGLU_LINEAR_FUSED = 0, 1, 2, 3
+ENTRY_FFN_GATE_UP, ENTRY_FFN_GATE_UP_NORM = 4, 5
 # the prefill kernel with a fixed workgroup tile, tokens x weight rows (tuning and tests)
 KERNEL_GEMM_SPLITK = {2: 0x202, 4: 0x204, 8: 0x208}       # bitnet_linear_ws only
 KERNEL_GEMM_TILES = {(128, 256): 0x142, (96, 256): 0x132, (64, 256): 0x122, (128, 128): 0x141, (96, 128): 0x131, (64, 128): 0x121}
@@ -29,6 +31,7 @@ SYMBOLS = [
     "bitnet_quantize_weights_segmented", "bitnet_linear_segmented", "bitnet_linear_fused_segmented",
     "bitnet_rmsnorm_linear_fused", "bitnet_rmsnorm_linear_fused_segmented", "bitnet_swiglu_linear_fused",
     "bitnet_ffn_gate_up_fused", "bitnet_linear_workspace", "bitnet_linear_ws", "bitnet_linear_describe",
+    "bitnet_entry_describe", "bitnet_abs_sum", "bitnet_quantize_weights_sharded",
 ]
 
 _lib = None
@@ -57,6 +60,8 @@ def load():
     lib.bitnet_packed_bytes.argtypes = [i64, i64, ci, ctypes.POINTER(sz)]
     lib.bitnet_quantize_weights_workspace.argtypes = [i64, i64, ctypes.POINTER(sz)]
     lib.bitnet_quantize_weights.argtypes = [vp, ci, i64, i64, ci, vp, vp, vp, sz, vp]
+    lib.bitnet_abs_sum.argtypes = [vp, ci, i64, i64, vp, vp, sz, vp]
+    lib.bitnet_quantize_weights_sharded.argtypes = [vp, ci, i64, i64, ci, vp, ci, i64, vp, vp, vp]
     lib.bitnet_quantize_acts.argtypes = [vp, ci, i64, i64, vp, vp, vp]
     lib.bitnet_linear.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, ci, vp]
     lib.bitnet_linear_variant.argtypes = [vp, vp, vp, vp, i64, i64, i64, ci, vp, ci, ci, vp]
@@ -72,6 +77,7 @@ def load():
     lib.bitnet_swiglu_linear_fused.argtypes = [vp, ci, vp, vp, i64, i64, i64, ci, vp, ci, vp]
     lib.bitnet_linear_workspace.argtypes = [i64, i64, i64, ctypes.POINTER(sz)]
     lib.bitnet_linear_describe.argtypes = [i64, i64, i64, ctypes.c_int, sz, ctypes.c_char_p, sz]
+    lib.bitnet_entry_describe.argtypes = [ci, ci, i64, i64, i64, ci, sz, ctypes.c_char_p, sz]
     lib.bitnet_linear_ws.argtypes = [vp, vp, vp, vp, ci, i64, i64, i64, ci, vp, ci, ci, vp, sz, vp]
     lib.bitnet_ffn_gate_up_fused.argtypes = [vp, ci, ci, vp, ctypes.c_float, vp, vp, ci, i64, i64, i64, ci, vp, ci, vp]
     for name in SYMBOLS[2:]:
@@ -135,6 +141,39 @@ def quantize_weights(W, fmt=PACK_2BIT, packed=None, gamma=None, workspace=None):
     _check(lib.bitnet_quantize_weights(wp, _FLOAT[W.dtype], N, K, fmt, _dev(packed, "packed"), _dev(gamma, "gamma"),
                                        _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
                                        _stream()), "bitnet_quantize_weights")
+    return packed, gamma
+
+
+def abs_sum(W, out=None, workspace=None):
+    """One row shard's share of Eq. (3): W [N,K] -> float64[2] (hi, lo) with hi + lo = sum |W|."""
+    lib = load()
+    wp = _dev(W, "W", _FLOAT, 2)
+    N, K = W.shape
+    if out is None:
+        out = torch.empty(2, dtype=torch.float64, device=W.device)
+    if workspace is None:
+        workspace = torch.empty(quantize_weights_workspace(N, K), dtype=torch.uint8, device=W.device)
+    _check(lib.bitnet_abs_sum(wp, _FLOAT[W.dtype], N, K, _dev(out, "sum", (torch.float64,)), _dev(workspace, "workspace"),
+                              workspace.numel() * workspace.element_size(), _stream()), "bitnet_abs_sum")
+    return out
+
+
+def quantize_weights_sharded(W, sums, total_rows, fmt=PACK_2BIT, packed=None, gamma=None):
+    """The rows W [N,K] of a matrix of total_rows rows, quantized with the gamma of the whole matrix: sums is a
+    float64 [G,2] tensor of every shard's abs_sum pair -> (packed, gamma float32[1])."""
+    lib = load()
+    wp = _dev(W, "W", _FLOAT, 2)
+    N, K = W.shape
+    sp = _dev(sums, "sums", (torch.float64,))
+    if sums.numel() % 2:
+        raise ValueError("sums holds (hi, lo) pairs")
+    if packed is None:
+        packed = torch.empty(packed_bytes(N, K, fmt), dtype=torch.uint8, device=W.device)
+    if gamma is None:
+        gamma = torch.empty(1, dtype=torch.float32, device=W.device)
+    _check(lib.bitnet_quantize_weights_sharded(wp, _FLOAT[W.dtype], N, K, fmt, sp, sums.numel() // 2, int(total_rows),
+                                               _dev(packed, "packed"), _dev(gamma, "gamma", (torch.float32,)), _stream()),
+           "bitnet_quantize_weights_sharded")
     return packed, gamma
 
 
@@ -211,16 +250,29 @@ def linear_workspace(M, N, K):
     return int(out.value)
 
 
+def _parse_plan(text):
+    f = dict(kv.split("=", 1) for kv in text.split())
+    gx, gy = f["grid"].split("x")
+    return {"kernel": f["kernel"], "params": [int(v) for v in f["params"].split(",") if v], "grid": (int(gx), int(gy)),
+            "block": int(f["block"]), "lds": int(f["lds"]), "splits": int(f["splits"])}
+
+
 def linear_describe(M, N, K, fmt=PACK_2BIT, workspace_bytes=0):
     """The kernel family and launch shape linear (or linear_ws with a workspace of that size) takes for a shape; host
     only, no device needed -> dict(kernel=str, params=[int], grid=(x, y), block=int, lds=int, splits=int)."""
     lib = load()
     buf = ctypes.create_string_buffer(256)
     _check(lib.bitnet_linear_describe(M, N, K, fmt, workspace_bytes, buf, len(buf)), "bitnet_linear_describe")
-    f = dict(kv.split("=", 1) for kv in buf.value.decode().split())
-    gx, gy = f["grid"].split("x")
-    return {"kernel": f["kernel"], "params": [int(v) for v in f["params"].split(",") if v], "grid": (int(gx), int(gy)),
-            "block": int(f["block"]), "lds": int(f["lds"]), "splits": int(f["splits"])}
+    return _parse_plan(buf.value.decode())
+
+
+def entry_describe(entry, M, N, K, x_dtype=BF16, fmt=PACK_2BIT, workspace_bytes=0):
+    """The same for any entry point (ENTRY_*): the decode-kernel instantiation a fused call with these sizes launches.
+    N and K as the entry point takes them (swiglu_linear_fused: K = F; ffn gate/up: N = F)."""
+    lib = load()
+    buf = ctypes.create_string_buffer(256)
+    _check(lib.bitnet_entry_describe(entry, x_dtype, M, N, K, fmt, workspace_bytes, buf, len(buf)), "bitnet_entry_describe")
+    return _parse_plan(buf.value.decode())
 
 
 def linear_ws(xq, sx, packed, gamma, N, workspace, fmt=PACK_2BIT, y_dtype=F32, y=None, kernel=KERNEL_AUTO,

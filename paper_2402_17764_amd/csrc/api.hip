@@ -103,6 +103,37 @@ bitnet_status bitnet_quantize_weights(const void* W, bitnet_dtype w_dtype, int64
     return from_hip(bitnet::launch_pack_trit5(W, w_dtype == BITNET_BF16, N, K, gamma, packed, s));
 }
 
+bitnet_status bitnet_abs_sum(const void* W, bitnet_dtype w_dtype, int64_t N, int64_t K, double* sum, void* workspace,
+                             size_t workspace_bytes, void* stream) {
+    if (!W || !sum || !workspace) return BITNET_ERR_NULL;
+    if (!shape_ok(1, N, K)) return BITNET_ERR_SHAPE;
+    if (w_dtype != BITNET_F32 && w_dtype != BITNET_BF16) return BITNET_ERR_DTYPE;
+    if (!aligned(W, dtype_size(w_dtype)) || !aligned(sum, 8) || !aligned(workspace, 16)) return BITNET_ERR_ALIGN;
+    size_t need = 0;
+    bitnet_quantize_weights_workspace(N, K, &need);
+    if (workspace_bytes < need) return BITNET_ERR_WORKSPACE;
+    return from_hip(bitnet::launch_abs_sum(W, w_dtype == BITNET_BF16, N, K, sum, workspace, static_cast<hipStream_t>(stream)));
+}
+
+bitnet_status bitnet_quantize_weights_sharded(const void* W, bitnet_dtype w_dtype, int64_t N, int64_t K, bitnet_format f,
+                                              const double* sums, int nsums, int64_t total_rows, void* packed,
+                                              float* gamma, void* stream) {
+    if (!W || !sums || !packed || !gamma) return BITNET_ERR_NULL;
+    if (!shape_ok(1, N, K) || nsums <= 0 || nsums > bitnet::quant_weights_max_sums() || total_rows < N ||
+        !shape_ok(1, total_rows, K))
+        return BITNET_ERR_SHAPE;
+    if (w_dtype != BITNET_F32 && w_dtype != BITNET_BF16) return BITNET_ERR_DTYPE;
+    if (!format_ok(f)) return BITNET_ERR_FORMAT;
+    if (!aligned(W, dtype_size(w_dtype)) || !aligned(packed, 16) || !aligned(gamma, 4) || !aligned(sums, 8))
+        return BITNET_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool bf16 = w_dtype == BITNET_BF16;
+    if (f == BITNET_PACK_2BIT)
+        return from_hip(bitnet::launch_pack_2bit_with_sums(W, bf16, N, K, sums, nsums, total_rows * K, packed, gamma, s));
+    if (bitnet::launch_gamma_from_sums(sums, nsums, total_rows * K, gamma, s) != hipSuccess) return BITNET_ERR_HIP;
+    return from_hip(bitnet::launch_pack_trit5(W, bf16, N, K, gamma, packed, s));
+}
+
 bitnet_status bitnet_quantize_acts(const void* x, bitnet_dtype x_dtype, int64_t M, int64_t K, int8_t* xq,
                                    float* sx, void* stream) {
     if (!x || !xq || !sx) return BITNET_ERR_NULL;
@@ -255,6 +286,16 @@ bitnet_status bitnet_linear_ws(const int8_t* xq, const float* sx, const void* pa
                                                     workspace, workspace ? workspace_bytes : 0, force));
 }
 
+static bitnet_status plan_to_text(const bitnet::LaunchPlan& plan, char* text, size_t text_bytes) {
+    char params[96] = "";
+    size_t at = 0;
+    for (int i = 0; i < plan.nparams && at < sizeof(params) - 16; ++i)
+        at += (size_t)snprintf(params + at, sizeof(params) - at, i ? ",%d" : "%d", plan.params[i]);
+    const int n = snprintf(text, text_bytes, "kernel=%s params=%s grid=%ux%u block=%u lds=%zu splits=%d", plan.kernel, params,
+                           plan.grid_x, plan.grid_y, plan.block, plan.lds_bytes, plan.splits);
+    return (n < 0 || (size_t)n >= text_bytes) ? BITNET_ERR_WORKSPACE : BITNET_OK;
+}
+
 bitnet_status bitnet_linear_describe(int64_t M, int64_t N, int64_t K, bitnet_format f, size_t workspace_bytes,
                                      char* text, size_t text_bytes) {
     if (!text || text_bytes == 0) return BITNET_ERR_NULL;
@@ -281,13 +322,44 @@ bitnet_status bitnet_linear_describe(int64_t M, int64_t N, int64_t K, bitnet_for
     } else {
         plan.kernel = "reference";
     }
-    char params[96] = "";
-    size_t at = 0;
-    for (int i = 0; i < plan.nparams && at < sizeof(params) - 16; ++i)
-        at += (size_t)snprintf(params + at, sizeof(params) - at, i ? ",%d" : "%d", plan.params[i]);
-    const int n = snprintf(text, text_bytes, "kernel=%s params=%s grid=%ux%u block=%u lds=%zu splits=%d", plan.kernel, params,
-                           plan.grid_x, plan.grid_y, plan.block, plan.lds_bytes, plan.splits);
-    return (n < 0 || (size_t)n >= text_bytes) ? BITNET_ERR_WORKSPACE : BITNET_OK;
+    return plan_to_text(plan, text, text_bytes);
+}
+
+bitnet_status bitnet_entry_describe(bitnet_entry entry, bitnet_dtype x_dtype, int64_t M, int64_t N, int64_t K,
+                                    bitnet_format f, size_t workspace_bytes, char* text, size_t text_bytes) {
+    if (entry == BITNET_ENTRY_LINEAR) return bitnet_linear_describe(M, N, K, f, workspace_bytes, text, text_bytes);
+    if (!text || text_bytes == 0) return BITNET_ERR_NULL;
+    text[0] = 0;
+    if ((int)entry < 0 || (int)entry > (int)BITNET_ENTRY_FFN_GATE_UP_NORM) return BITNET_ERR_KERNEL;
+    const bool pair = entry == BITNET_ENTRY_FFN_GATE_UP || entry == BITNET_ENTRY_FFN_GATE_UP_NORM;
+    if (pair && (N <= 0 || N % 16 != 0 || N >= ((int64_t)1 << 29))) return BITNET_ERR_SHAPE;
+    const int64_t rows = pair ? 2 * N : N;
+    if (!shape_ok(M, rows, K)) return BITNET_ERR_SHAPE;
+    if (x_dtype != BITNET_F32 && x_dtype != BITNET_BF16) return BITNET_ERR_DTYPE;
+    if (f != BITNET_PACK_2BIT) return BITNET_ERR_FORMAT;
+    const float* fp = reinterpret_cast<const float*>(uintptr_t{256});
+    void* vp = reinterpret_cast<void*>(uintptr_t{256});
+    if (!bitnet::gemv_fused_supports(M, rows, K, vp)) return BITNET_ERR_KERNEL;
+    const bool bf16 = x_dtype == BITNET_BF16;
+    bitnet::LaunchPlan plan;
+    hipError_t e = hipSuccess;
+    switch (entry) {
+        case BITNET_ENTRY_LINEAR_FUSED:
+            e = bitnet::launch_linear_fused_2bit(vp, bf16, vp, fp, 0, M, N, K, vp, OutType::BF16, nullptr, &plan);
+            break;
+        case BITNET_ENTRY_RMSNORM_LINEAR_FUSED:
+            e = bitnet::launch_rmsnorm_linear_fused_2bit(vp, bf16, fp, 0.0f, vp, fp, 0, M, N, K, vp, OutType::BF16, nullptr, &plan);
+            break;
+        case BITNET_ENTRY_SWIGLU_LINEAR_FUSED:
+            e = bitnet::launch_swiglu_linear_fused_2bit(vp, bf16, vp, fp, 0, M, N, K, vp, OutType::BF16, nullptr, &plan);
+            break;
+        default:
+            e = bitnet::launch_linear_fused_swiglu_out_2bit(vp, bf16, entry == BITNET_ENTRY_FFN_GATE_UP_NORM, fp, 0.0f, vp, fp, 0, M,
+                                                            N, K, vp, OutType::BF16, nullptr, &plan);
+            break;
+    }
+    if (e != hipSuccess) return BITNET_ERR_HIP;
+    return plan_to_text(plan, text, text_bytes);
 }
 
 bitnet_status bitnet_linear_segmented(const int8_t* xq, const float* sx, const void* packed, const float* gamma_rb,

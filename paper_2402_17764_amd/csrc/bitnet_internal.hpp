@@ -34,6 +34,16 @@ hipError_t launch_quantize_weights_2bit(const void* W, bool bf16, int64_t N, int
                                         float* gamma, void* workspace, hipStream_t stream, int64_t rb_off = 0,
                                         int64_t rb_total = 0, int64_t nout = 1);
 
+// one shard's share of Eq. (3): sum[0 .. 1] = the double-double (hi, lo) pair of sum |W| over these rows
+hipError_t launch_abs_sum(const void* W, bool bf16, int64_t N, int64_t K, double* sum, void* workspace, hipStream_t stream);
+// how many (hi, lo) pairs the packing pass can fold (one per thread of a workgroup)
+int quant_weights_max_sums();
+// gamma = fp32((sum of the nsums pairs) / total_count), Eq. (3) over all shards
+hipError_t launch_gamma_from_sums(const double* sums, int nsums, int64_t total_count, float* gamma, hipStream_t stream);
+// Eq. (1)-(2) + packing of these rows with that gamma (written to *gamma as well)
+hipError_t launch_pack_2bit_with_sums(const void* W, bool bf16, int64_t N, int64_t K, const double* sums, int nsums,
+                                      int64_t total_count, void* packed, float* gamma, hipStream_t stream);
+
 // quant_acts.hip
 hipError_t launch_quantize_acts(const void* x, bool bf16, int64_t M, int64_t K, int8_t* xq, float* sx,
                                 hipStream_t stream);
@@ -80,19 +90,22 @@ hipError_t launch_linear_gemv16_2bit(const int8_t* xq, const float* sx, const vo
                                      int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream, LaunchPlan* plan = nullptr);
 bool gemv_fused_supports(int64_t M, int64_t N, int64_t K, const void* x);
 hipError_t launch_linear_fused_2bit(const void* x, bool bf16, const void* packed, const float* gamma, int gstride,
-                                    int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);
+                                    int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream,
+                                    LaunchPlan* plan = nullptr);
 // the same with RMSNorm (optional per-column gain, 16-byte aligned) in front of the quantization
 hipError_t launch_rmsnorm_linear_fused_2bit(const void* x, bool bf16, const float* gain, float eps, const void* packed,
                                             const float* gamma, int gstride, int64_t M, int64_t N, int64_t K, void* y,
-                                            OutType yt, hipStream_t stream);
+                                            OutType yt, hipStream_t stream, LaunchPlan* plan = nullptr);
 // ... and with SwiGLU gating in front: gu is [M][2 K] (gate | up), the product runs over K columns
 hipError_t launch_swiglu_linear_fused_2bit(const void* gu, bool bf16, const void* packed, const float* gamma, int gstride,
-                                           int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);
+                                           int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream,
+                                           LaunchPlan* plan = nullptr);
 // merged gate | up projection ([2 F][K], F a multiple of 16) from x (absmax quantization, RMSNorm first if `norm`),
 // h = silu(y_gate) * y_up stored as [M][F] (F32 or BF16)
 hipError_t launch_linear_fused_swiglu_out_2bit(const void* x, bool bf16, bool norm, const float* gain, float eps,
                                                const void* packed, const float* gamma, int gstride, int64_t M, int64_t F,
-                                               int64_t K, void* h, OutType yt, hipStream_t stream);
+                                               int64_t K, void* h, OutType yt, hipStream_t stream,
+                                               LaunchPlan* plan = nullptr);
 
 // linear_gemm.hip
 bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq);

@@ -505,6 +505,8 @@ static hipError_t launch16(int xmode, const void* x, const float* sx, const void
     if (xmode == kXLds && header + lds_x > kGemvLdsBudget) xmode = kXGlobal;
     const size_t lds = header + (xmode != kXGlobal && lds_x > lds_fold ? lds_x : lds_fold);
     dim3 grid((unsigned)ceil_div(RB, kW * kR)), block(kS * kW * kWave);
+    const int need = xmode <= kXLds ? kModesInt8 : xmode <= kXFusedF32 ? kModesFused : kModesPre;
+    if ((kModes & need) == 0) return hipErrorInvalidDeviceFunction;   // a dispatch rule asked a launch shape for a mode it is not built for
     if (plan) {
         plan->set("decode", {kR, kS, kW, kD, xmode}, grid.x, 1, block.x, lds, 1);
         return hipSuccess;
@@ -527,7 +529,7 @@ static hipError_t launch16(int xmode, const void* x, const float* sx, const void
         if (xmode == kXSwigluF32) { GO(kXSwigluF32); return hipGetLastError(); }
     }
 #undef GO
-    return hipErrorInvalidDeviceFunction;      // a dispatch rule asked a launch shape for a mode it is not built for
+    return hipErrorInvalidDeviceFunction;
 }
 
 // Fraction of the K steps a shape walks that are real: each of kS waves takes ceil(steps / kS) steps, padded to a
@@ -594,10 +596,10 @@ static hipError_t dispatch16_int8(const void* x, const float* sx, const void* pa
 
 // x is quantized in the kernel (xmode: plain, after RMSNorm, after SwiGLU); sx is unused
 static hipError_t dispatch16_fused(int xmode, const void* x, const void* packed, const float* gamma, int gstride, int64_t M,
-                             int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream, const float* gain, float eps) {
+                             int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream, const float* gain, float eps,
+                             LaunchPlan* plan) {
     const int64_t RB = ceil_div(N, kRowsPerBlock), steps = ceil_div(K, 256);
     const float* sx = nullptr;
-    LaunchPlan* const plan = nullptr;
     if (xmode == kXNormBf16 || xmode == kXNormF32) {
         // every workgroup repeats the normalisation (an fp64 reduction and a square root, a microsecond or two of its
         // CU's time), so few, wide workgroups: one wave per row block (or pair of them) and no K split from 769 row
@@ -662,21 +664,22 @@ bool gemv_fused_supports(int64_t M, int64_t N, int64_t K, const void* x) {
 }
 
 hipError_t launch_linear_fused_2bit(const void* x, bool bf16, const void* packed, const float* gamma, int gstride,
-                                    int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
-    return dispatch16_fused(bf16 ? kXFusedBf16 : kXFusedF32, x, packed, gamma, gstride, M, N, K, y, yt, stream, nullptr, 0.0f);
+                                    int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream, LaunchPlan* plan) {
+    return dispatch16_fused(bf16 ? kXFusedBf16 : kXFusedF32, x, packed, gamma, gstride, M, N, K, y, yt, stream, nullptr, 0.0f, plan);
 }
 
 hipError_t launch_rmsnorm_linear_fused_2bit(const void* x, bool bf16, const float* gain, float eps, const void* packed,
                                             const float* gamma, int gstride, int64_t M, int64_t N, int64_t K, void* y,
-                                            OutType yt, hipStream_t stream) {
-    return dispatch16_fused(bf16 ? kXNormBf16 : kXNormF32, x, packed, gamma, gstride, M, N, K, y, yt, stream, gain, eps);
+                                            OutType yt, hipStream_t stream, LaunchPlan* plan) {
+    return dispatch16_fused(bf16 ? kXNormBf16 : kXNormF32, x, packed, gamma, gstride, M, N, K, y, yt, stream, gain, eps, plan);
 }
 
 // merged gate | up projection with the SwiGLU gate in the epilogue; x goes through the fused quantization
 // (xmode: absmax only, or RMSNorm first).  F is a multiple of 16, so the up half starts on a row block.
 template <int kS, int kW, int kD>
 static void launch16_pair(int xmode, const void* x, const void* packed, const float* gamma, int gstride, int64_t M,
-                          int64_t F, int64_t K, void* h, OutType yt, hipStream_t stream, const float* gain, float eps) {
+                          int64_t F, int64_t K, void* h, OutType yt, hipStream_t stream, const float* gain, float eps,
+                          LaunchPlan* plan) {
     constexpr int kR = 2;
     const int Kq = (int)ceil_div(K, kColsPerQuad);
     const int pair_off = (int)(F / kRowsPerBlock);
@@ -688,6 +691,10 @@ static void launch16_pair(int xmode, const void* x, const void* packed, const fl
     const size_t lds_x = gemv16_x_lds_bytes(M, K);
     const size_t lds = header + (lds_x > lds_fold ? lds_x : lds_fold);
     dim3 grid((unsigned)ceil_div(pair_off, kW)), block(kS * kW * kWave);
+    if (plan) {
+        plan->set("decode_pair", {kR, kS, kW, kD, xmode}, grid.x, 1, block.x, lds, 1);
+        return;
+    }
     const uint4* p = static_cast<const uint4*>(packed);
 #define GO(X_) hipLaunchKernelGGL((linear_gemv16_2bit<kR, kS, kW, kD, X_, true>), grid, block, lds, stream, x, (const float*)nullptr, p, gamma, \
                                   gstride, (int)M, F, K, Kq, RB, items, h, yt, gain, eps, pair_off)
@@ -702,27 +709,28 @@ static void launch16_pair(int xmode, const void* x, const void* packed, const fl
 
 hipError_t launch_linear_fused_swiglu_out_2bit(const void* x, bool bf16, bool norm, const float* gain, float eps,
                                                const void* packed, const float* gamma, int gstride, int64_t M, int64_t F,
-                                               int64_t K, void* h, OutType yt, hipStream_t stream) {
+                                               int64_t K, void* h, OutType yt, hipStream_t stream, LaunchPlan* plan) {
     const int xmode = norm ? (bf16 ? kXNormBf16 : kXNormF32) : (bf16 ? kXFusedBf16 : kXFusedF32);
     // From a sweep of fourteen launch shapes on the gate / up matrices of the 3B ... 70B family: without the
     // normalisation, up to 700 pairs one pair per workgroup with K split over four waves; otherwise one wave per pair
     // and no K split, four pairs per workgroup up to 1024 pairs (at most 256 workgroups), eight beyond.
     const int64_t pairs = F / kRowsPerBlock;
-    if (!norm && pairs <= 700) launch16_pair<4, 1, 4>(xmode, x, packed, gamma, gstride, M, F, K, h, yt, stream, gain, eps);
+    if (!norm && pairs <= 700) launch16_pair<4, 1, 4>(xmode, x, packed, gamma, gstride, M, F, K, h, yt, stream, gain, eps, plan);
     else if (pairs <= 1024) {
         // depth 5 or 4, whichever pads the K walk less (16 steps at depth 5 walk 20: 7B gate/up with the norm 10.5 -> 9.5 us)
         const int64_t steps = ceil_div(K, 256);
         if (walk_efficiency(steps, 1, 5) >= walk_efficiency(steps, 1, 4))
-            launch16_pair<1, 4, 5>(xmode, x, packed, gamma, gstride, M, F, K, h, yt, stream, gain, eps);
+            launch16_pair<1, 4, 5>(xmode, x, packed, gamma, gstride, M, F, K, h, yt, stream, gain, eps, plan);
         else
-            launch16_pair<1, 4, 4>(xmode, x, packed, gamma, gstride, M, F, K, h, yt, stream, gain, eps);
-    } else launch16_pair<1, 8, 3>(xmode, x, packed, gamma, gstride, M, F, K, h, yt, stream, gain, eps);
-    return hipGetLastError();
+            launch16_pair<1, 4, 4>(xmode, x, packed, gamma, gstride, M, F, K, h, yt, stream, gain, eps, plan);
+    } else launch16_pair<1, 8, 3>(xmode, x, packed, gamma, gstride, M, F, K, h, yt, stream, gain, eps, plan);
+    return plan ? hipSuccess : hipGetLastError();
 }
 
 hipError_t launch_swiglu_linear_fused_2bit(const void* gu, bool bf16, const void* packed, const float* gamma, int gstride,
-                                           int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
-    return dispatch16_fused(bf16 ? kXSwigluBf16 : kXSwigluF32, gu, packed, gamma, gstride, M, N, K, y, yt, stream, nullptr, 0.0f);
+                                           int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream,
+                                           LaunchPlan* plan) {
+    return dispatch16_fused(bf16 ? kXSwigluBf16 : kXSwigluF32, gu, packed, gamma, gstride, M, N, K, y, yt, stream, nullptr, 0.0f, plan);
 }
 
 }  // namespace bitnet

@@ -143,6 +143,37 @@ __global__ __launch_bounds__(kFinishThreads) void finish_gamma(const double* __r
     for (int64_t i = threadIdx.x; i < nout; i += kFinishThreads) gamma[i] = g;
 }
 
+// The sum of pass 1's partials as a normalised double-double pair (hi = fl(hi + lo)): what one shard of a row-sharded
+// matrix contributes to Eq. (3).  Same fixed tree as finish_gamma.
+__global__ __launch_bounds__(kFinishThreads) void fold_abs_sum(const double* __restrict__ partials, int nparts,
+                                                            double* __restrict__ sum) {
+    dd acc{0.0, 0.0};
+    for (int i = threadIdx.x; i < nparts; i += kFinishThreads) {
+        dd p{partials[2 * i], partials[2 * i + 1]};
+        dd_add_dd(acc, p);
+    }
+    __shared__ double sh_hi[kFinishThreads];
+    __shared__ double sh_lo[kFinishThreads];
+    sh_hi[threadIdx.x] = acc.hi;
+    sh_lo[threadIdx.x] = acc.lo;
+    __syncthreads();
+    for (int s = kFinishThreads / 2; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) {
+            dd a{sh_hi[threadIdx.x], sh_lo[threadIdx.x]};
+            dd b{sh_hi[threadIdx.x + s], sh_lo[threadIdx.x + s]};
+            dd_add_dd(a, b);
+            sh_hi[threadIdx.x] = a.hi;
+            sh_lo[threadIdx.x] = a.lo;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const double hi = sh_hi[0] + sh_lo[0];
+        sum[0] = hi;
+        sum[1] = sh_lo[0] - (hi - sh_hi[0]);              // exact: |lo| <= |hi|
+    }
+}
+
 // ---------------------------------------------------------------------------------------------------
 // pass 3, 2-bit format
 // ---------------------------------------------------------------------------------------------------
@@ -288,6 +319,54 @@ hipError_t launch_absmean_gamma(const void* W, bool bf16, int64_t N, int64_t K, 
         hipLaunchKernelGGL(abs_sum_partials<float>, dim3(blocks), dim3(kSumThreads), 0, stream,
                            static_cast<const float*>(W), count, vec_ok, abs_sum_stream_vecs(count, 4), partials);
     hipLaunchKernelGGL(finish_gamma, dim3(1), dim3(kFinishThreads), 0, stream, partials, blocks, count, gamma, nout);
+    return hipGetLastError();
+}
+
+static void launch_abs_sum_partials(const void* W, bool bf16, int64_t count, double* partials, int blocks, hipStream_t stream) {
+    const int vec_ok = (reinterpret_cast<uintptr_t>(W) % 16) == 0;
+    if (bf16)
+        hipLaunchKernelGGL(abs_sum_partials<uint16_t>, dim3(blocks), dim3(kSumThreads), 0, stream,
+                           static_cast<const uint16_t*>(W), count, vec_ok, abs_sum_stream_vecs(count, 2), partials);
+    else
+        hipLaunchKernelGGL(abs_sum_partials<float>, dim3(blocks), dim3(kSumThreads), 0, stream,
+                           static_cast<const float*>(W), count, vec_ok, abs_sum_stream_vecs(count, 4), partials);
+}
+
+hipError_t launch_abs_sum(const void* W, bool bf16, int64_t N, int64_t K, double* sum, void* workspace, hipStream_t stream) {
+    const int64_t count = N * K;
+    double* partials = static_cast<double*>(workspace);
+    const int blocks = abs_sum_blocks(count);
+    launch_abs_sum_partials(W, bf16, count, partials, blocks, stream);
+    hipLaunchKernelGGL(fold_abs_sum, dim3(1), dim3(kFinishThreads), 0, stream, partials, blocks, sum);
+    return hipGetLastError();
+}
+
+int quant_weights_max_sums() { return kPackThreads; }
+
+hipError_t launch_gamma_from_sums(const double* sums, int nsums, int64_t total_count, float* gamma, hipStream_t stream) {
+    hipLaunchKernelGGL(finish_gamma, dim3(1), dim3(kFinishThreads), 0, stream, sums, nsums, total_count, gamma, (int64_t)1);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_2bit_with_sums(const void* W, bool bf16, int64_t N, int64_t K, const double* sums, int nsums,
+                                      int64_t total_count, void* packed, float* gamma, hipStream_t stream) {
+    const size_t esz = bf16 ? 2 : 4;
+    const bool vec = (reinterpret_cast<uintptr_t>(W) % (4 * esz)) == 0 && (K % 4 == 0);
+    const int64_t Kq = ceil_div(K, kColsPerQuad);
+    const int64_t RB = ceil_div(N, kRowsPerBlock);
+    const int64_t items = RB * ceil_div(Kq, 4);
+    dim3 grid((unsigned)(items < kPackBlocks ? items : kPackBlocks));
+    uint32_t* out = static_cast<uint32_t*>(packed);
+#define PACK(T_, V_) hipLaunchKernelGGL((ternarize_pack_2bit<T_, V_>), grid, dim3(kPackThreads), 0, stream, w, N, K, Kq, RB, (int64_t)0, \
+                                        sums, nsums, total_count, gamma, (int64_t)1, out)
+    if (bf16) {
+        const uint16_t* w = static_cast<const uint16_t*>(W);
+        if (vec) PACK(uint16_t, true); else PACK(uint16_t, false);
+    } else {
+        const float* w = static_cast<const float*>(W);
+        if (vec) PACK(float, true); else PACK(float, false);
+    }
+#undef PACK
     return hipGetLastError();
 }
 

@@ -114,6 +114,30 @@ def test_host_validation_rejects_before_launch():
     assert lib.bitnet_ffn_gate_up_fused(a, 0, 0, NULL, 0.0, a, a, 0, 1, 16, 64, 0, a, 2, NULL) == 3          # I32 out
     assert lib.bitnet_ffn_gate_up_fused(a, 0, 0, NULL, 0.0, a, a, 0, 1, 16, 64, 1, a, 0, NULL) == 4
     assert lib.bitnet_ffn_gate_up_fused(a, 0, 1, vp(0x1004), 0.0, a, a, 0, 1, 16, 64, 0, a, 0, NULL) == 5
+    # sharded weight quantization
+    assert lib.bitnet_abs_sum(a, 0, 16, 64, NULL, a, 1 << 20, NULL) == 1
+    assert lib.bitnet_abs_sum(a, 0, 0, 64, a, a, 1 << 20, NULL) == 2
+    assert lib.bitnet_abs_sum(a, 2, 16, 64, a, a, 1 << 20, NULL) == 3
+    assert lib.bitnet_abs_sum(a, 0, 16, 64, vp(0x1004), a, 1 << 20, NULL) == 5
+    assert lib.bitnet_abs_sum(a, 0, 16, 64, a, a, 8, NULL) == 6
+    assert lib.bitnet_quantize_weights_sharded(a, 0, 16, 64, 0, NULL, 1, 16, a, a, NULL) == 1
+    assert lib.bitnet_quantize_weights_sharded(a, 0, 16, 64, 0, a, 0, 16, a, a, NULL) == 2        # no shares
+    assert lib.bitnet_quantize_weights_sharded(a, 0, 16, 64, 0, a, 257, 16, a, a, NULL) == 2      # more than it folds
+    assert lib.bitnet_quantize_weights_sharded(a, 0, 16, 64, 0, a, 2, 8, a, a, NULL) == 2         # whole smaller than the shard
+    assert lib.bitnet_quantize_weights_sharded(a, 2, 16, 64, 0, a, 2, 32, a, a, NULL) == 3
+    assert lib.bitnet_quantize_weights_sharded(a, 0, 16, 64, 5, a, 2, 32, a, a, NULL) == 4
+    assert lib.bitnet_quantize_weights_sharded(a, 0, 16, 64, 0, vp(0x1004), 2, 32, a, a, NULL) == 5
+    # launch descriptions of the fused entry points
+    buf = ctypes.create_string_buffer(128)
+    assert lib.bitnet_entry_describe(1, 1, 1, 4096, 4096, 0, 0, None, 128) == 1
+    assert lib.bitnet_entry_describe(9, 1, 1, 4096, 4096, 0, 0, buf, 128) == 8
+    assert lib.bitnet_entry_describe(1, 2, 1, 4096, 4096, 0, 0, buf, 128) == 3
+    assert lib.bitnet_entry_describe(1, 1, 1, 4096, 4096, 1, 0, buf, 128) == 4                    # 2-bit format only
+    assert lib.bitnet_entry_describe(1, 1, 17, 4096, 4096, 0, 0, buf, 128) == 8                   # more than 16 tokens
+    assert lib.bitnet_entry_describe(4, 1, 1, 24, 4096, 0, 0, buf, 128) == 2                      # F % 16
+    assert lib.bitnet_entry_describe(1, 1, 1, 4096, 4096, 0, 0, buf, 128) == 0
+    assert buf.value.decode().startswith("kernel=decode params=1,4,1,4,2 grid=256x1 block=256")
+    assert lib.bitnet_entry_describe(0, 0, 1, 4096, 4096, 0, 0, buf, 128) == 0 and b"params=1,4,1,4,0" in buf.value
     # shapes
     assert lib.bitnet_quantize_acts(a, 0, 0, 16, a, a, NULL) == 2
     assert lib.bitnet_rmsnorm_quantize(a, 0, NULL, 0.0, 1, 0, a, a, NULL) == 2

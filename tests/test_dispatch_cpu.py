@@ -208,3 +208,111 @@ def test_decode_shapes_on_large_layers_follow_the_measured_cases():
     assert B.linear_describe(1, 27648, 5120)["grid"] == (216, 1)
     assert B.linear_describe(2, 27648, 5120)["params"] == [2, 1, 4, 4, 0]
     assert B.linear_describe(1, 17280, 3200)["params"] == [1, 4, 1, 4, 1]            # 3B gate/up keeps four K-split waves
+
+
+# ------------------------------------------------------------------------------------------------
+# every launch the benchmark times runs a kernel instantiation that a GPU parity test reaches
+# ------------------------------------------------------------------------------------------------
+_ENTRY = {"LINEAR": B.ENTRY_LINEAR, "LINEAR_FUSED": B.ENTRY_LINEAR_FUSED, "RMSNORM_LINEAR_FUSED": B.ENTRY_RMSNORM_LINEAR_FUSED,
+          "SWIGLU_LINEAR_FUSED": B.ENTRY_SWIGLU_LINEAR_FUSED, "FFN_GATE_UP": B.ENTRY_FFN_GATE_UP,
+          "FFN_GATE_UP_NORM": B.ENTRY_FFN_GATE_UP_NORM}
+_DTYPE = {"bf16": B.BF16, "f32": B.F32, "int8": B.BF16}
+
+
+def _form(entry, dtype, M, N, K):
+    """the kernel instantiation a call gets: family + template parameters (the launch grid is not part of it)"""
+    d = B.entry_describe(_ENTRY[entry], M, N, K, x_dtype=_DTYPE[dtype])
+    return (d["kernel"], tuple(d["params"]), d["splits"])
+
+
+def _forms_reached_by_the_gpu_parity_tests():
+    """Replays the shape lists of tests/test_gpu_parity.py (each case there is compared with the oracle) through the
+    same launch selection.  Returns {form: example case}."""
+    import parity_shapes as P
+    reached = {}
+
+    def add(entry, dtype, M, N, K):
+        reached.setdefault(_form(entry, dtype, M, N, K), (entry, dtype, M, N, K))
+
+    for (M, N, K) in P.GEMV_SHAPES + P.GEMM_SHAPES:                  # _run_linear_case: KERNEL_AUTO is among the kernels run
+        if K % 16 == 0:
+            add("LINEAR", "int8", M, N, K)
+    for (M, N, K, _) in P.FULL_SIZE_GEMM:
+        add("LINEAR", "int8", M, N, K)
+    for (_, _name, K, N, Ms) in P.FULL_SIZE_DECODE:
+        for M in Ms:
+            add("LINEAR", "int8", M, N, K)
+            if M == 1:
+                add("LINEAR_FUSED", "bf16", M, N, K)
+                if N % 32 == 0 and "gate_up" in (_name,):
+                    add("FFN_GATE_UP_NORM", "bf16", M, N // 2, K)
+    for (_, K, N) in P.FAMILY_DECODE:
+        for M in (1, 3):
+            add("LINEAR", "int8", M, N, K)
+            if 128 + M * ceil_div(K, 256) * 256 <= 60 * 1024:
+                add("LINEAR_FUSED", "bf16", M, N, K)
+    for dtype in ("f32", "bf16"):
+        for (M, N, K) in P.FUSED_SHAPES:
+            add("LINEAR_FUSED", dtype, M, N, K)
+        for (M, N, K) in P.NORM_FUSED_SHAPES:
+            add("RMSNORM_LINEAR_FUSED", dtype, M, N, K)
+        for (M, N, F) in P.SWIGLU_FUSED_SHAPES:
+            add("SWIGLU_LINEAR_FUSED", dtype, M, N, F)
+        for (M, F, K) in P.FFN_GATE_UP_SHAPES:
+            add("FFN_GATE_UP", dtype, M, F, K)
+            add("FFN_GATE_UP_NORM", dtype, M, F, K)
+            add("LINEAR_FUSED", dtype, M, 2 * F, K)
+            add("RMSNORM_LINEAR_FUSED", dtype, M, 2 * F, K)
+    # test_decoder_chain_in_a_hip_graph_matches_the_oracle: the 3B chain at its exact shapes, bf16
+    add("RMSNORM_LINEAR_FUSED", "bf16", 1, 9600, 3200)
+    add("RMSNORM_LINEAR_FUSED", "bf16", 1, 17280, 3200)
+    add("FFN_GATE_UP_NORM", "bf16", 1, 8640, 3200)
+    # test_linear_prefill_70b_full_size_sampled
+    add("LINEAR", "int8", 4096, 57344, 8192)
+    add("LINEAR", "int8", 4096, 8192, 28672)
+    return reached
+
+
+def test_every_benchmark_launch_runs_a_parity_tested_kernel_form():
+    """bench.launch_inventory() lists every product launch a default benchmark run times; each must get a kernel
+    instantiation (family, template parameters, split) that at least one oracle-checked GPU case gets too -- for the
+    decode workloads at the exact shape."""
+    import bench
+    import parity_shapes as P
+    reached = _forms_reached_by_the_gpu_parity_tests()
+    inv = bench.launch_inventory()
+    assert len(inv) >= 50
+    missing = []
+    for (leg, entry, dtype, M, N, K) in inv:
+        if _form(entry, dtype, M, N, K) not in reached:
+            missing.append((leg, entry, dtype, M, N, K, _form(entry, dtype, M, N, K)))
+    assert not missing, missing
+    # the two instantiations that carry the decode headlines, at their exact shapes
+    fused_exact = {(M, N, K) for (M, N, K) in P.FUSED_SHAPES} | {(1, N, K) for (_, _, K, N, Ms) in P.FULL_SIZE_DECODE if 1 in Ms}
+    for (leg, entry, dtype, M, N, K) in inv:
+        if leg in ("headline", "decode_3b_m1"):
+            assert (M, N, K) in fused_exact, (leg, M, N, K)
+    assert _form("LINEAR_FUSED", "bf16", 1, 9600, 3200) == ("decode", (1, 4, 1, 4, 2), 1)      # 3B QKV / O, 7B QKV / O
+    assert _form("LINEAR_FUSED", "bf16", 1, 3200, 3200) == ("decode", (1, 4, 1, 4, 2), 1)
+    assert _form("LINEAR_FUSED", "bf16", 1, 57344, 8192)[0] == "decode"
+
+
+def test_no_dispatch_rule_asks_for_an_instantiation_that_is_not_built():
+    """Seeded random shapes through every fused entry point: the launch selection must always land on a built
+    instantiation (a rule that names a launch shape without the needed activation mode returns an error status)."""
+    import random
+    rng = random.Random(17764)
+    seen = set()
+    for _ in range(3000):
+        M = rng.choice([1, 1, 1, 2, 3, 4, 8, 16])
+        N = 16 * rng.choice([1, 3, 16, 100, 200, 256, 257, 320, 321, 400, 512, 513, 640, 641, 768, 769, 1024, 1025, 1536, 2048, 3584, 8000])
+        K = 16 * rng.choice([1, 5, 16, 17, 64, 100, 128, 200, 208, 256, 320, 384, 416, 512, 540, 688, 864, 1024, 1120, 1792])
+        if 512 + M * ceil_div(K, 256) * 256 > 65536:
+            continue
+        for entry in ("LINEAR_FUSED", "RMSNORM_LINEAR_FUSED", "SWIGLU_LINEAR_FUSED", "FFN_GATE_UP", "FFN_GATE_UP_NORM"):
+            for dtype in ("bf16", "f32"):
+                d = B.entry_describe(_ENTRY[entry], M, N, K, x_dtype=_DTYPE[dtype])
+                assert d["kernel"] in ("decode", "decode_pair") and d["block"] <= 1024 and d["lds"] <= 65536, (entry, M, N, K, d)
+                assert d["params"][4] in ((2, 4, 6) if dtype == "bf16" else (3, 5, 7)), (entry, M, N, K, d)
+                seen.add((d["kernel"], tuple(d["params"][:4])))
+    assert len(seen) >= 15

@@ -13,6 +13,8 @@ import pytest
 
 import oracle
 from layout_ref import decode_2bit, decode_trit5
+from parity_shapes import (FAMILY_DECODE, FFN_GATE_UP_SHAPES, FULL_SIZE_DECODE, FULL_SIZE_GEMM, FUSED_SHAPES, GEMM_SHAPES,
+                           GEMV_SHAPES, NORM_FUSED_SHAPES, SWIGLU_FUSED_SHAPES)
 from paper_2402_17764_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -258,33 +260,6 @@ def test_linear_reference_kernel(gpu_lib, M, N, K):
 
 # several tiles plus ragged tails in every dimension the GEMV kernel tiles: N (16-row blocks, groups
 # of 1/2/4 blocks), K (quads of 64, steps of 256, split over 4 or 8 waves), M (tiles of 16)
-GEMV_SHAPES = [(1, 4096, 1536), (16, 4096, 1536), (1, 16, 64), (1, 17, 16), (3, 100, 80), (7, 250, 1040),
-               (16, 33, 4112), (17, 70, 528), (32, 1000, 3200), (33, 130, 272), (64, 96, 1024), (50, 49, 2064),
-               # one shape per branch of the kernel-selection heuristic (row blocks x K steps)
-               (2, 32800, 528), (3, 16400, 4112), (1, 16400, 272), (5, 6416, 16400), (4, 6416, 1040),
-               (2, 100, 6160), (16, 1000, 8192), (1, 600, 16400), (1, 100, 11008), (8, 300, 2048), (6, 16400, 512),
-               (12, 16400, 8192),
-               # the skinny kernel: 16 < M <= 64, ragged token tiles, every branch of its selection (row blocks
-               # below 512, below 1280, above; up to 32 tokens and above), K tails, K steps from 1 to 17 and
-               # fewer steps than K groups
-               (20, 16400, 272), (48, 300, 4112), (64, 100, 1040), (40, 1000, 528), (33, 260, 2048), (56, 16400, 512),
-               (24, 20488, 272), (50, 20500, 528), (35, 48, 64), (18, 20, 16), (64, 8200, 4096),
-               # ... and its single-token-tile form for 4 < M <= 16, one shape per row-block class
-               (9, 9000, 528), (10, 32800, 272), (5, 40, 16), (13, 16400, 1040),
-               # ... and the form with a loader wave (many row blocks, more than 16 tokens): each of its five selections,
-               # K from one partial step to 33 steps
-               (30, 32784, 272), (60, 32800, 144), (17, 20490, 80), (64, 20480, 8208), (40, 8200, 1040),
-               # ... two and eight row blocks per workgroup (257 ... 512 and 1537 ... 2047 row blocks) at every token tile
-               (9, 5000, 528), (12, 5008, 8208), (20, 6000, 272), (50, 8000, 1040), (9, 26000, 272), (30, 28000, 144), (64, 30000, 528),
-               # M <= 4: depth 5 where depth 4 would pad (34 K steps over four waves), two row blocks per wave from 512
-               # row blocks on with more than one token
-               (2, 100, 8640), (3, 9000, 3200),
-               # 65 ... 256 tokens on small layers: token tiles of 32 and of 64 over grid z, ragged last tiles, every
-               # form such launches can pick
-               (65, 40, 528), (96, 300, 2064), (100, 4000, 1040), (128, 6000, 272), (130, 8000, 528), (192, 3200, 784),
-               (200, 5120, 528), (250, 8000, 272), (256, 4096, 1296), (128, 12000, 144),
-               # ... and up to 512 tokens where K >= 5120
-               (300, 3200, 5136), (512, 4096, 5120), (400, 2000, 5392)]
 
 
 @pytest.mark.parametrize("M,N,K", GEMV_SHAPES)
@@ -293,9 +268,6 @@ def test_linear_gemv_kernel(gpu_lib, M, N, K):
     _run_linear_case(gpu_lib, M, N, K, [gpu_lib.KERNEL_GEMV, gpu_lib.KERNEL_AUTO], layer=M, bf16_acts=(M % 2 == 0))
 
 
-FUSED_SHAPES = [(1, 4096, 1536), (16, 4096, 1536), (1, 17, 16), (3, 100, 80), (7, 250, 1040), (2, 32800, 528),
-                (3, 16400, 4112), (1, 16400, 272), (4, 6416, 1040), (2, 100, 6160), (1, 3200, 8640), (1, 17280, 3200),
-                (1, 600, 16400), (1, 100, 11008), (2, 64, 28672)]
 
 
 @pytest.mark.parametrize("M,N,K", FUSED_SHAPES)
@@ -321,8 +293,6 @@ def test_linear_fused_matches_oracle(gpu_lib, M, N, K, dtype):
 
 # RMSNorm + quantization + product in one launch: each branch of the decode kernel's selection, token 0 in
 # registers and the re-reading path (M > 1, long K), K tails, with and without gain
-NORM_FUSED_SHAPES = [(1, 4096, 1536), (1, 100, 3200), (3, 250, 1040), (1, 33, 4112), (16, 70, 528), (1, 16400, 272),
-                     (2, 16400, 4112), (1, 600, 16400), (1, 6416, 8640), (4, 300, 8192), (1, 32800, 528), (5, 40, 16)]
 
 
 @pytest.mark.parametrize("M,N,K", NORM_FUSED_SHAPES)
@@ -386,8 +356,6 @@ def test_rmsnorm_linear_fused_segmented_and_limits(gpu_lib):
 
 # SwiGLU + quantization + product in one launch: F (the product's K) from one partial step to the 3B / 7B / 70B
 # feed-forward widths, token 0 in registers and the re-reading path, every branch of the kernel selection
-SWIGLU_FUSED_SHAPES = [(1, 3200, 8640), (1, 100, 1536), (3, 250, 1040), (1, 33, 4112), (16, 70, 528), (1, 16400, 272),
-                       (2, 6416, 4112), (1, 64, 28672), (1, 4096, 11008), (4, 300, 8192), (1, 32800, 528), (5, 40, 16)]
 
 
 @pytest.mark.parametrize("M,N,F", SWIGLU_FUSED_SHAPES)
@@ -432,8 +400,7 @@ def test_swiglu_linear_fused_limits(gpu_lib):
 
 # merged gate | up projection with the gate applied in the epilogue: both workgroup shapes of its selection
 # (F / 16 up to 700 and above), K tails, several tokens, with and without RMSNorm, one scale and one per segment
-@pytest.mark.parametrize("M,F,K", [(1, 8640, 3200), (1, 11008, 4096), (3, 1008, 1040), (1, 16, 16), (2, 11216, 272),
-                                   (16, 48, 528), (1, 4000, 4112)])
+@pytest.mark.parametrize("M,F,K", FFN_GATE_UP_SHAPES)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_ffn_gate_up_fused(gpu_lib, M, F, K, dtype):
     """h = silu(y_gate) * y_up must be the oracle's gate applied to the fp32 outputs of the plain fused launch
@@ -508,8 +475,6 @@ def test_linear_fused_rejects_what_it_cannot_run(gpu_lib):
 # tiles in each direction.  The workgroup tile (64, 96 or 128 tokens x 128 or 256 weight rows) follows a cost model
 # of tile count and shape; the last three shapes fill the chip, the others leave most of it idle and get the small
 # tiles (each tile shape is also forced on its own in test_linear_gemm_every_tile_shape).
-GEMM_SHAPES = [(65, 300, 528), (128, 256, 256), (100, 40, 16), (300, 520, 1040), (257, 1000, 3200), (513, 270, 4112),
-               (1024, 512, 1536), (96, 256, 64), (97, 257, 272), (300, 35850, 80), (520, 15400, 144), (512, 27700, 80)]
 
 
 @pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
@@ -615,18 +580,19 @@ def test_linear_gemm_small_m_and_forced_on_decode_shapes(gpu_lib):
     _run_linear_case(gpu_lib, 16, 4096, 1536, [gpu_lib.KERNEL_GEMM], layer=3)
 
 
-@pytest.mark.parametrize("M,N,K,layer", [(2048, 27648, 5120, 2), (512, 5120, 13824, 3)])
+@pytest.mark.parametrize("M,N,K,layer", FULL_SIZE_GEMM)
 def test_linear_gemm_full_size_sampled(gpu_lib, M, N, K, layer):
     """13B-class prefill shapes at full size, in the launch configuration the benchmark times; the oracle
-    recomputes a seeded sample of 48 tokens x 384 weight rows (codes, x_q, accumulators bit-exact)."""
+    recomputes a seeded sample of 256 tokens x 2048 weight rows (codes, x_q, accumulators bit-exact), and the whole
+    integer result is compared with the one-thread-per-output reference kernel."""
     say("linear gemm full size M=%d N=%d K=%d" % (M, N, K))
     W = synth.weights(N, K, config=3, layer=0, tensor=layer)
     x, bits = synth.activations(M, K, config=3, layer=0, tensor=100 + layer, bf16=True)
     gamma_ref, _ = oracle.absmean_gamma(W)
-    rng = np.random.default_rng(layer)
-    rows = np.sort(rng.choice(M, 48, replace=False))
+    rng = np.random.default_rng([layer, M])
+    rows = np.sort(rng.choice(M, 256, replace=False))
     rows[0], rows[-1] = 0, M - 1
-    cols = np.sort(rng.choice(N, 384, replace=False))
+    cols = np.sort(rng.choice(N, 2048, replace=False))
     cols[0], cols[-1] = 0, N - 1
     codes_ref = oracle.ternarize(W[cols], gamma_ref)
     xq_ref, sx_ref = oracle.quantize_acts(x[rows])
@@ -640,25 +606,20 @@ def test_linear_gemm_full_size_sampled(gpu_lib, M, N, K, layer):
     ri = torch.from_numpy(rows).cuda()
     ci = torch.from_numpy(cols).cuda()
     acc = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.I32)
+    assert gpu_lib.linear_describe(M, N, K)["kernel"] == "prefill"
     assert np.array_equal(acc[ri][:, ci].cpu().numpy(), acc_ref)
-    del acc
+    # any-size property: the whole integer result equals the reference kernel's
+    a_ref = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.I32, kernel=gpu_lib.KERNEL_REFERENCE)
+    assert torch.equal(a_ref, acc)
+    del acc, a_ref
     y16 = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.BF16)
     check_y(y16[ri][:, ci].float().cpu().numpy(), y_ref, RTOL_BF16)
     del y16
     y32 = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.F32)
     check_y(y32[ri][:, ci].cpu().numpy(), y_ref, RTOL_F32)
-    # any-size property: the integer result does not depend on which kernel produced it
-    # (checked on the first and the last 64 tokens)
-    a_full = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.I32)
-    for sub in (slice(0, 64), slice(M - 64, M)):
-        a_ref = gpu_lib.linear(xq[sub].contiguous(), sx[sub].contiguous(), packed, gamma, N, y_dtype=gpu_lib.I32,
-                               kernel=gpu_lib.KERNEL_GEMV)
-        assert torch.equal(a_ref, a_full[sub])
 
 
 # the remaining benchmark configurations at full size, every token count the benchmark times
-FULL_SIZE_DECODE = [(2, "gate_up", 4096, 22016, (1, 8, 32, 64)), (2, "down", 11008, 4096, (1, 8, 32, 64)),
-                    (2, "qkv", 4096, 12288, (16, 64)), (4, "gate_up", 8192, 57344, (1, 64)), (4, "down", 28672, 8192, (1, 32))]
 
 
 @pytest.mark.parametrize("config,name,K,N,Ms", FULL_SIZE_DECODE)
@@ -674,7 +635,7 @@ def test_linear_decode_full_size_sampled(gpu_lib, config, name, K, N, Ms):
     cols[0], cols[-1] = 0, N - 1
     codes_ref = oracle.ternarize(W[cols], gamma_ref)
     packed, gamma = gpu_lib.quantize_weights(dev(W))
-    del W
+    W_rows = lambda idx: W[idx]
     assert gamma.cpu().numpy()[0] == gamma_ref
     ci = torch.from_numpy(cols).cuda()
     for M in Ms:
@@ -692,6 +653,19 @@ def test_linear_decode_full_size_sampled(gpu_lib, config, name, K, N, Ms):
         if M == 1:
             accf = gpu_lib.linear_fused(xd, packed, gamma, N, y_dtype=gpu_lib.I32)
             assert np.array_equal(accf[:, ci].cpu().numpy(), acc_ref)
+        if M == 1 and name == "gate_up":
+            # the same matrix as a merged gate | up projection with the gate in the epilogue (RMSNorm in front), as the
+            # feed-forward chain of the benchmark launches it: 256 sampled (gate, up) row pairs
+            F = N // 2
+            pj = np.sort(rng.choice(F, 256, replace=False))
+            pj[0], pj[-1] = 0, F - 1
+            gain = (1.0 + 0.1 * rng.standard_normal(K)).astype(np.float32)
+            xq_n, sx_n, _ = oracle.rmsnorm_quantize(x, gain, 1e-6)
+            c2 = oracle.ternarize(W_rows(np.concatenate([pj, pj + F])), gamma_ref)
+            y2 = oracle.rescale(oracle.ternary_matmul(xq_n, c2), gamma_ref, sx_n)
+            _, _, h_def = _swiglu_definition(y2)
+            h16 = gpu_lib.ffn_gate_up_fused(xd, packed, gamma, F, norm=True, g=dev(gain), eps=1e-6, h_dtype=gpu_lib.BF16)
+            check_y(h16[:, torch.from_numpy(pj).cuda()].float().cpu().numpy(), h_def, RTOL_BF16)
         # any-size property: the whole integer result equals the reference kernel's
         a_ref = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.I32, kernel=gpu_lib.KERNEL_REFERENCE)
         assert torch.equal(a_ref, acc)
@@ -699,8 +673,6 @@ def test_linear_decode_full_size_sampled(gpu_lib, config, name, K, N, Ms):
 
 # 13B- and 30B-class projections: between them and the benchmark's 3B / 7B / 70B shapes they reach every launch shape
 # the M <= 4 decode dispatch can pick (K = 5120 is the case whose 20 K steps pad badly over four waves)
-FAMILY_DECODE = [("13b_qkv", 5120, 15360), ("13b_o", 5120, 5120), ("13b_gate_up", 5120, 27648), ("13b_down", 13824, 5120),
-                 ("30b_qkv", 6656, 19968), ("30b_o", 6656, 6656), ("30b_gate_up", 6656, 35840), ("30b_down", 17920, 6656)]
 
 
 @pytest.mark.parametrize("name,K,N", FAMILY_DECODE)
@@ -902,6 +874,205 @@ def test_producers_feed_the_product(gpu_lib):
     y = gpu_lib.linear(hq, sh, pd, gam_d, H, y_dtype=gpu_lib.F32)
     y_ref = oracle.rescale(oracle.ternary_matmul(hq_r, cd), gd, sh_r)
     check_y(y.cpu().numpy(), y_ref, RTOL_F32)
+
+
+def _swiglu_definition(gu):
+    """silu(gate) * up and its per-token absmax quantization straight from their definitions, in numpy fp64
+    (not the oracle's fixed-step exponential: an independent yardstick for it and for the GPU alike)."""
+    gu = np.asarray(gu, np.float64)
+    F = gu.shape[1] // 2
+    a, b = gu[:, :F], gu[:, F:]
+    with np.errstate(over="ignore"):
+        h = a / (1.0 + np.exp(-a)) * b
+    s = np.maximum(np.abs(h).max(axis=1), 1e-5)
+    q = np.clip(np.rint(h * (127.0 / s)[:, None]), -127, 127)
+    return q, s, h
+
+
+@pytest.mark.parametrize("M,F", [(1, 8640), (4, 11008), (70, 4096), (2, 28672), (3, 1003)])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_swiglu_quantize_against_the_fp64_definition(gpu_lib, M, F, bf16):
+    """The HIP SwiGLU -> int8 producer against numpy's fp64 evaluation of the definition (the bit-exact test above
+    compares it with the oracle, whose exponential follows the same stated steps): scales within 1e-6 relative, every
+    code within one step, at least 99 % equal.  Large |gate| values exercise both clamps of the exponential."""
+    say("swiglu_quantize vs fp64 definition M=%d F=%d bf16=%s" % (M, F, bf16))
+    gu, bits = synth.activations(M, 2 * F, config=2, layer=F % 7, tensor=15, bf16=True)
+    if not bf16:
+        gu = synth.activations(M, 2 * F, config=0, layer=F % 7, tensor=15)
+        gu[0, :8] = [-120.0, -95.0, -88.5, -87.0, 87.5, 88.0, 100.0, 3.0e4]
+        gu[0, F:F + 8] = 0.01                                     # small up values: these products must not set the scale
+    gt = bf16_tensor(bits).view(M, 2 * F) if bf16 else dev(gu)
+    q_def, s_def, _ = _swiglu_definition(gu)
+    hq, sh = gpu_lib.swiglu_quantize(gt)
+    hq, sh = hq.cpu().numpy().astype(np.int64), sh.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(sh - s_def) <= 1e-6 * s_def), np.abs(sh / s_def - 1).max()
+    diff = np.abs(hq - q_def)
+    assert diff.max() <= 1 and (diff == 0).mean() >= 0.99, (diff.max(), (diff == 0).mean())
+
+
+@pytest.mark.parametrize("M,F,K", [(1, 8640, 3200), (2, 1008, 1040)])
+def test_ffn_gate_up_fused_against_the_fp64_definition(gpu_lib, M, F, K):
+    """h of the gate/up launch with the gate in its epilogue, against numpy fp64: the product's y from the oracle's
+    integers (exact) rescaled in fp64, the gate from its definition; fp32 h within 5e-5, bf16 h within 1e-2."""
+    say("ffn gate/up vs fp64 definition M=%d F=%d K=%d" % (M, F, K))
+    W = synth.weights(2 * F, K, config=0, layer=M + 60, tensor=0)
+    x, bits = synth.activations(M, K, config=2, layer=M + 60, tensor=7, bf16=True)
+    ref = oracle.bitlinear(x, W)
+    _, _, h_def = _swiglu_definition(ref["y"])
+    packed, gamma = gpu_lib.quantize_weights(dev(W))
+    xd = bf16_tensor(bits).view(M, K)
+    h32 = gpu_lib.ffn_gate_up_fused(xd, packed, gamma, F).cpu().numpy().astype(np.float64)
+    h16 = gpu_lib.ffn_gate_up_fused(xd, packed, gamma, F, h_dtype=gpu_lib.BF16).float().cpu().numpy().astype(np.float64)
+    big = np.abs(h_def) > 1e-30
+    assert np.abs(h32[big] / h_def[big] - 1).max() <= 5e-5
+    assert np.abs(h16[big] / h_def[big] - 1).max() <= RTOL_BF16
+    assert np.all(h32[~big] == 0)
+
+
+def test_decoder_chain_in_a_hip_graph_matches_the_oracle(gpu_lib):
+    """Three layers of the 3B-class decoder's BitLinear chain at M = 1 as the benchmark runs it -- four fused launches
+    per layer, captured into one HIP graph, every launch reading what the previous one wrote (the attention itself is
+    not on the path: the first `hidden` outputs of the QKV projection stand in for its output).  The graph is replayed
+    several times with eager work in between; every replay must equal the eager run bit for bit, and every link is
+    recomputed by the oracle from the values its input buffer holds: accumulators bit-exact (read through the I32
+    output of the same entry point), bf16 outputs within 1e-2."""
+    say("decoder chain graph, 3B shapes")
+    H, F, L = 3200, 8640, 3
+    eps = 1e-6
+    shapes = {"qkv": (H, 3 * H), "o": (H, H), "gate_up": (H, 2 * F), "down": (F, H)}
+    Wn, Wd = [], []
+    for l in range(L):
+        wl, dl = {}, {}
+        for t, (name, (K, N)) in enumerate(shapes.items()):
+            W = synth.weights(N, K, config=1, layer=l, tensor=t)
+            wl[name] = W
+            dl[name] = gpu_lib.quantize_weights(dev(W))
+        Wn.append(wl)
+        Wd.append(dl)
+    rng = np.random.default_rng([2402, 1, 77])
+    gains = [(1.0 + 0.1 * rng.standard_normal(H)).astype(np.float32) for _ in range(2 * L)]
+    gd = [dev(g) for g in gains]
+    x0, bits = synth.activations(1, H, config=1, layer=0, tensor=100, bf16=True)
+    x0d = bf16_tensor(bits).view(1, H)
+    buf = [{"qkv": torch.zeros((1, 3 * H), dtype=torch.bfloat16, device="cuda"),
+            "o": torch.zeros((1, H), dtype=torch.bfloat16, device="cuda"),
+            "h": torch.zeros((1, F), dtype=torch.bfloat16, device="cuda"),
+            "down": torch.zeros((1, H), dtype=torch.bfloat16, device="cuda")} for _ in range(L)]
+    att = [torch.zeros((1, H), dtype=torch.bfloat16, device="cuda") for _ in range(L)]
+
+    def chain():
+        x = x0d
+        for l in range(L):
+            d, b = Wd[l], buf[l]
+            gpu_lib.rmsnorm_linear_fused(x, gd[2 * l], eps, d["qkv"][0], d["qkv"][1], 3 * H, y_dtype=gpu_lib.BF16, y=b["qkv"])
+            att[l].copy_(b["qkv"][:, :H])                         # stand-in for the attention output
+            gpu_lib.linear_fused(att[l], d["o"][0], d["o"][1], H, y_dtype=gpu_lib.BF16, y=b["o"])
+            gpu_lib.ffn_gate_up_fused(b["o"], d["gate_up"][0], d["gate_up"][1], F, norm=True, g=gd[2 * l + 1], eps=eps,
+                                      h_dtype=gpu_lib.BF16, h=b["h"])
+            gpu_lib.linear_fused(b["h"], d["down"][0], d["down"][1], H, y_dtype=gpu_lib.BF16, y=b["down"])
+            x = b["down"]
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [{k: v.clone() for k, v in b.items()} for b in buf]
+
+    chain()
+    eager = snapshot()
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(stream):
+        chain()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        chain()
+    for rep in range(3):
+        for b in buf:                                             # eager work between the replays: wipe the buffers
+            for v in b.values():
+                v.fill_(float(rep + 1))
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        for l in range(L):
+            for k in eager[l]:
+                assert torch.equal(got[l][k], eager[l][k]), (rep, l, k)
+
+    def f32(t):
+        return t.float().cpu().numpy()
+
+    # every link against the oracle, from the values in its input buffer
+    x_in = x0
+    for l in range(L):
+        W, d, b = Wn[l], Wd[l], eager[l]
+        x_in_d = x0d if l == 0 else eager[l - 1]["down"]
+        # QKV: RMSNorm -> int8 -> product
+        xq, sx, _ = oracle.rmsnorm_quantize(x_in, gains[2 * l], eps)
+        c, g = oracle.quantize_weights(W["qkv"])
+        acc = oracle.ternary_matmul(xq, c)
+        acc_gpu = gpu_lib.rmsnorm_linear_fused(x_in_d, gd[2 * l], eps, d["qkv"][0], d["qkv"][1], 3 * H, y_dtype=gpu_lib.I32)
+        assert np.array_equal(acc_gpu.cpu().numpy(), acc), (l, "qkv")
+        check_y(f32(b["qkv"]), oracle.rescale(acc, g, sx), RTOL_BF16)
+        # O: absmax -> int8 -> product, on the stand-in attention output
+        a_in = f32(b["qkv"])[:, :H]
+        xq, sx = oracle.quantize_acts(a_in)
+        c, g = oracle.quantize_weights(W["o"])
+        acc = oracle.ternary_matmul(xq, c)
+        acc_gpu = gpu_lib.linear_fused(b["qkv"][:, :H].contiguous(), d["o"][0], d["o"][1], H, y_dtype=gpu_lib.I32)
+        assert np.array_equal(acc_gpu.cpu().numpy(), acc), (l, "o")
+        check_y(f32(b["o"]), oracle.rescale(acc, g, sx), RTOL_BF16)
+        # gate/up: RMSNorm -> int8 -> product -> gate
+        xq, sx, _ = oracle.rmsnorm_quantize(f32(b["o"]), gains[2 * l + 1], eps)
+        c, g = oracle.quantize_weights(W["gate_up"])
+        acc = oracle.ternary_matmul(xq, c)
+        acc_gpu = gpu_lib.rmsnorm_linear_fused(b["o"], gd[2 * l + 1], eps, d["gate_up"][0], d["gate_up"][1], 2 * F,
+                                               y_dtype=gpu_lib.I32)
+        assert np.array_equal(acc_gpu.cpu().numpy(), acc), (l, "gate_up")
+        _, _, h_def = _swiglu_definition(oracle.rescale(acc, g, sx))
+        check_y(f32(b["h"]), h_def, RTOL_BF16)
+        # down
+        xq, sx = oracle.quantize_acts(f32(b["h"]))
+        c, g = oracle.quantize_weights(W["down"])
+        acc = oracle.ternary_matmul(xq, c)
+        acc_gpu = gpu_lib.linear_fused(b["h"], d["down"][0], d["down"][1], H, y_dtype=gpu_lib.I32)
+        assert np.array_equal(acc_gpu.cpu().numpy(), acc), (l, "down")
+        check_y(f32(b["down"]), oracle.rescale(acc, g, sx), RTOL_BF16)
+        x_in = f32(b["down"])
+
+
+# ------------------------------------------------------------------------------------------------
+# a matrix quantized in row shards with the gamma of the whole (Eq. (3) is one mean per matrix)
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("N,K,bounds", [(4096, 1536, None), (1000, 528, [0, 16, 400, 1000]), (250, 4100, [0, 96, 250]),
+                                        (33, 70, [0, 32, 33])])
+@pytest.mark.parametrize("fmt", ["2bit", "trit5"])
+def test_sharded_weight_quantization_reproduces_the_whole_tensor(gpu_lib, N, K, bounds, fmt):
+    """G = 2, 4, 8 equal row shards (and ragged ones): each shard reports its (hi, lo) share of sum |W|, every shard is
+    then quantized with all the shares; gamma and the codes must be those of one whole-tensor call and of the oracle,
+    bit for bit, whatever the split and whatever the order of the shares."""
+    say("sharded quantization %s N=%d K=%d" % (fmt, N, K))
+    f = gpu_lib.PACK_2BIT if fmt == "2bit" else gpu_lib.PACK_TRIT5
+    W = synth.weights(N, K, config=0, layer=N % 5, tensor=21)
+    W[: N // 3] *= np.float32(3.0)                                # shards of different magnitude
+    codes_ref, gamma_ref = oracle.quantize_weights(W)
+    Wd = dev(W)
+    _, gamma_whole = gpu_lib.quantize_weights(Wd, fmt=f)
+    assert gamma_whole.cpu().numpy()[0] == gamma_ref
+    splits = [bounds] if bounds else [[N * i // G for i in range(G + 1)] for G in (2, 4, 8)]
+    for bnd in splits:
+        shards = [Wd[bnd[i]:bnd[i + 1]].contiguous() for i in range(len(bnd) - 1)]
+        sums = torch.stack([gpu_lib.abs_sum(s) for s in shards])
+        hi_lo = sums.cpu().numpy()
+        for i, s in enumerate(shards):                            # each share is the exact sum of its rows
+            import math
+            exact = math.fsum(np.abs(W[bnd[i]:bnd[i + 1]]).astype(np.float64).ravel().tolist())
+            assert hi_lo[i, 0] == exact and abs(hi_lo[i, 1]) <= abs(exact) * 2.0 ** -52
+        for order in (sums, sums.flip(0).contiguous()):
+            for i, s in enumerate(shards):
+                rows = bnd[i + 1] - bnd[i]
+                packed, gamma = gpu_lib.quantize_weights_sharded(s, order, N, fmt=f)
+                assert gamma.cpu().numpy()[0] == gamma_ref
+                codes = gpu_lib.unpack_weights(packed, rows, K, fmt=f).cpu().numpy()
+                assert np.array_equal(codes, codes_ref[bnd[i]:bnd[i + 1]])
 
 
 # ------------------------------------------------------------------------------------------------
