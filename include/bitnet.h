@@ -153,6 +153,22 @@ bitnet_status bitnet_quantize_weights(const void* W, bitnet_dtype w_dtype, int64
                                       void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * bitnet_quantize_weights without a workspace argument and without any allocation, for callers that cannot
+ * allocate device memory: code running under HIP-graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The block partial sums of the |W| reduction go to a static 32 KiB array in device memory that belongs to
+ * the library (one copy per GPU, held until the process ends) instead of a caller's buffer; kernels, launch shapes and
+ * results are those of bitnet_quantize_weights, bit for bit.
+ *   W, packed, gamma, stream   as for bitnet_quantize_weights
+ *   Limit: the partial sums of the shape must fit the static array (BITNET_ERR_WORKSPACE otherwise; true of every
+ *   shape the library accepts today, whose need is a fixed 32 KiB).
+ * Every call on a GPU uses that GPU's one array: calls that may overlap on one GPU (different streams, no ordering
+ * between them) race on it and must use bitnet_quantize_weights with workspaces of their own.  Nothing in the array
+ * has to be cleared between calls: the first kernel overwrites every entry the second one reads.
+ */
+bitnet_status bitnet_quantize_weights_static(const void* W, bitnet_dtype w_dtype, int64_t N, int64_t K,
+                                             bitnet_format f, void* packed, float* gamma, void* stream);
+
+/*
  * Eq. (3) for a matrix whose rows are spread over several devices (or quantized in several pieces): gamma is the
  * mean of |W| over the WHOLE matrix, so each holder of a row shard first reports its share of the sum, the shares
  * are exchanged (G pairs of doubles; between GPUs an all-gather of 16 bytes each), and every holder then quantizes

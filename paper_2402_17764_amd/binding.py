@@ -31,7 +31,7 @@ SYMBOLS = [
     "bitnet_quantize_weights_segmented", "bitnet_linear_segmented", "bitnet_linear_fused_segmented",
     "bitnet_rmsnorm_linear_fused", "bitnet_rmsnorm_linear_fused_segmented", "bitnet_swiglu_linear_fused",
     "bitnet_ffn_gate_up_fused", "bitnet_linear_workspace", "bitnet_linear_ws", "bitnet_linear_describe",
-    "bitnet_entry_describe", "bitnet_abs_sum", "bitnet_quantize_weights_sharded",
+    "bitnet_entry_describe", "bitnet_abs_sum", "bitnet_quantize_weights_sharded", "bitnet_quantize_weights_static",
 ]
 
 _lib = None
@@ -60,6 +60,7 @@ def load():
     lib.bitnet_packed_bytes.argtypes = [i64, i64, ci, ctypes.POINTER(sz)]
     lib.bitnet_quantize_weights_workspace.argtypes = [i64, i64, ctypes.POINTER(sz)]
     lib.bitnet_quantize_weights.argtypes = [vp, ci, i64, i64, ci, vp, vp, vp, sz, vp]
+    lib.bitnet_quantize_weights_static.argtypes = [vp, ci, i64, i64, ci, vp, vp, vp]
     lib.bitnet_abs_sum.argtypes = [vp, ci, i64, i64, vp, vp, sz, vp]
     lib.bitnet_quantize_weights_sharded.argtypes = [vp, ci, i64, i64, ci, vp, ci, i64, vp, vp, vp]
     lib.bitnet_quantize_acts.argtypes = [vp, ci, i64, i64, vp, vp, vp]
@@ -141,6 +142,18 @@ def quantize_weights(W, fmt=PACK_2BIT, packed=None, gamma=None, workspace=None):
     _check(lib.bitnet_quantize_weights(wp, _FLOAT[W.dtype], N, K, fmt, _dev(packed, "packed"), _dev(gamma, "gamma"),
                                        _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
                                        _stream()), "bitnet_quantize_weights")
+    return packed, gamma
+
+
+def quantize_weights_static(W, packed, gamma, fmt=PACK_2BIT):
+    """quantize_weights through the entry point that allocates nothing: the caller passes every buffer, the scratch is
+    the library's static device array."""
+    lib = load()
+    wp = _dev(W, "W", _FLOAT, 2)
+    N, K = W.shape
+    _check(lib.bitnet_quantize_weights_static(wp, _FLOAT[W.dtype], N, K, fmt, _dev(packed, "packed"),
+                                              _dev(gamma, "gamma", (torch.float32,)), _stream()),
+           "bitnet_quantize_weights_static")
     return packed, gamma
 
 

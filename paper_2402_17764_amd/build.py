@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libbitnet_hip.so")
 
-SOURCES = ["api.hip", "quant_weights.hip", "quant_acts.hip", "linear_ref.hip", "linear_gemv.hip", "linear_skinny.hip", "linear_gemm.hip", "trit5.hip"]
+SOURCES = ["api.hip", "quant_weights.hip", "quant_acts.hip", "linear_ref.hip", "linear_gemv.hip", "linear_skinny.hip", "linear_gemm.hip", "trit5.hip", "static_scratch.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

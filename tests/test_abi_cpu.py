@@ -127,6 +127,12 @@ def test_host_validation_rejects_before_launch():
     assert lib.bitnet_quantize_weights_sharded(a, 2, 16, 64, 0, a, 2, 32, a, a, NULL) == 3
     assert lib.bitnet_quantize_weights_sharded(a, 0, 16, 64, 5, a, 2, 32, a, a, NULL) == 4
     assert lib.bitnet_quantize_weights_sharded(a, 0, 16, 64, 0, vp(0x1004), 2, 32, a, a, NULL) == 5
+    # the entry point that allocates nothing validates like bitnet_quantize_weights, before it touches a device
+    assert lib.bitnet_quantize_weights_static(NULL, 0, 16, 64, 0, a, a, NULL) == 1
+    assert lib.bitnet_quantize_weights_static(a, 0, 0, 64, 0, a, a, NULL) == 2
+    assert lib.bitnet_quantize_weights_static(a, 2, 16, 64, 0, a, a, NULL) == 3
+    assert lib.bitnet_quantize_weights_static(a, 0, 16, 64, 7, a, a, NULL) == 4
+    assert lib.bitnet_quantize_weights_static(a, 0, 16, 64, 0, odd, a, NULL) == 5
     # launch descriptions of the fused entry points
     buf = ctypes.create_string_buffer(128)
     assert lib.bitnet_entry_describe(1, 1, 1, 4096, 4096, 0, 0, None, 128) == 1
