@@ -101,6 +101,11 @@ def launch_inventory():
     return inv
 
 
+def progress(msg):
+    """a line on stderr per finished stage, so that a long run (under a profiler, say) is seen to move"""
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
 def gemv_bytes(M, N, K, out_bytes=2):
     """Algorithmic bytes of one product call: packed 2-bit weights + int8 x + scales + y."""
     return N * K // 4 + M * K + 4 * M + M * N * out_bytes
@@ -257,6 +262,7 @@ def decode_workload(torch, B, synth, gen, stream, args, workload):
             wq_ms += e0.elapsed_time(e1)
             wq_bytes += int(N * K * 8.25)
             del W
+    progress("%s: %d tensors quantized and packed" % (workload, L * len(shapes)))
     acts = {K: make_acts(torch, M, K, gen, cfg_idx) for K in sorted({K for (_, K, _) in shapes})}
     xq = {K: torch.empty((M, K), dtype=torch.int8, device="cuda") for K in acts}
     sx = {K: torch.empty(M, dtype=torch.float32, device="cuda") for K in acts}
@@ -275,6 +281,7 @@ def decode_workload(torch, B, synth, gen, stream, args, workload):
     ms_per_step, _, _ = time_graph(torch, step, args.warmup, args.steps, stream)
     step_bytes = L * sum(gemv_bytes(M, N, K) for (_, K, N) in shapes)
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
+    progress("%s: step timed, %.4f ms" % (workload, ms_per_step))
 
     # per-shape launch time (each shape alone, one launch per layer on that layer's own weights) and the roofline of
     # the dominant kernel: the product on the shape that moves the most bytes
@@ -762,6 +769,7 @@ def main():
     assert sorted(legs) == sorted(LEGS)
 
     if args.only:
+        progress("leg %s alone" % args.only)
         print(json.dumps({"only": args.only, "steps": args.steps, "warmup": args.warmup, args.only: legs[args.only]()}))
         return
 
@@ -793,6 +801,7 @@ def main():
             names.remove("decoder_chain_3b_m1")
         for leg in names:
             out[leg] = legs[leg]() if args.inprocess else run_leg_in_child(leg, args)
+            progress("leg %s done" % leg)
             if isinstance(out[leg], dict) and "error" in out[leg]:
                 failed.append(leg)
         if "gemm_13b" in out and "M=2048" in out["gemm_13b"]:
