@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <initializer_list>
 #include <stdint.h>
 
@@ -11,16 +12,18 @@ namespace bitnet {
 enum class OutType { F32 = 0, BF16 = 1, I32 = 2 };
 
 // Raises a kernel's dynamic-LDS limit above the 64 KiB default, once per device and kernel (the attribute
-// belongs to the function on the current device).  `done` is the caller's per-kernel flag array.
+// belongs to the function on the current device).  `done` is the caller's per-kernel flag array; the flags are
+// atomic, so host threads that meet on a kernel's first use at worst both set the same attribute to the same value.
 constexpr int kMaxDevices = 64;
-inline hipError_t raise_dynamic_lds(const void* kernel, int bytes, bool (&done)[kMaxDevices]) {
+using RaisedFlags = std::atomic<bool>[kMaxDevices];
+inline hipError_t raise_dynamic_lds(const void* kernel, int bytes, RaisedFlags& done) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
-    if (done[dev]) return hipSuccess;
+    if (done[dev].load(std::memory_order_acquire)) return hipSuccess;
     e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    if (e == hipSuccess) done[dev] = true;
+    if (e == hipSuccess) done[dev].store(true, std::memory_order_release);
     return e;
 }
 

@@ -413,7 +413,7 @@ static hipError_t launch_gemm_tiles(const int8_t* xq, const float* sx, const voi
                                     int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt,
                                     hipStream_t stream, int splits = 1, void* workspace = nullptr, LaunchPlan* plan = nullptr) {
     if (!plan) {
-        static bool raised[kMaxDevices] = {};
+        static RaisedFlags raised = {};
         const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(linear_gemm_2bit<kFM, kFN>), gemm_lds_bytes(kFM), raised);
         if (e != hipSuccess) return e;
     }

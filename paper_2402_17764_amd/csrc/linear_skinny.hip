@@ -496,7 +496,7 @@ static hipError_t launch_skinny(const int8_t* xq, const float* sx, const void* p
     static_assert(kS * kW <= 16, "at most 1024 threads per workgroup");
     auto* kern = linear_skinny_2bit<kMT, kR, kW, kS, kD, kLx>;
     if (lds > 65536 && !plan) {
-        static bool raised[kMaxDevices] = {};
+        static RaisedFlags raised = {};
         const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(kern), (int)lds, raised);
         if (e != hipSuccess) return e;
     }
@@ -529,7 +529,7 @@ static hipError_t launch_skinny_ws(const int8_t* xq, const float* sx, const void
     static_assert(kS * kW + 1 <= 16, "at most 1024 threads per workgroup");
     auto* kern = linear_skinny_ws_2bit<kMT, kR, kW, kS, kD, kLx>;
     if (lds > 65536 && !plan) {
-        static bool raised[kMaxDevices] = {};
+        static RaisedFlags raised = {};
         const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(kern), (int)lds, raised);
         if (e != hipSuccess) return e;
     }
