@@ -482,8 +482,10 @@ def small_layer_leg(torch, B, synth, gen, stream, args):
 
 
 def format_leg(torch, B, synth, gen, stream, args):
-    """The 5-trits-per-byte format measured against the 2-bit one on the M = 1 product (bitnet_linear on
-    pre-quantized activations), same weights, on the dominant 3B shape and the 70B gate/up shape."""
+    """The 5-trits-per-byte format measured against the 2-bit one, same weights: the M = 1 product (bitnet_linear on
+    pre-quantized activations) on the dominant 3B shape and the 70B gate/up shape, and the prefill product at 2048
+    tokens on the 13B gate/up shape, where 5-trit weights go through bitnet_linear_ws (repacked to 2 bits in the
+    workspace, then the MFMA prefill kernel)."""
     res = {}
     for (tag, K, N) in (("3b_gate_up", 3200, 17280), ("70b_gate_up", 8192, 57344)):
         entry = {"K": K, "N": N}
@@ -512,6 +514,24 @@ def format_leg(torch, B, synth, gen, stream, args):
             torch.cuda.empty_cache()
         entry["time_ratio_trit5_over_2bit"] = round(entry["trit5"]["us_per_launch"] / entry["2bit"]["us_per_launch"], 3)
         res[tag] = entry
+    # prefill
+    M, K, N = 2048, 5120, 27648
+    W = torch.randn((N, K), device="cuda", generator=gen, dtype=torch.float32) * synth.SIGMA_W
+    p2, g2 = B.quantize_weights(W, fmt=B.PACK_2BIT)
+    p5, g5 = B.quantize_weights(W, fmt=B.PACK_TRIT5)
+    del W
+    xq, sx = B.quantize_acts(make_acts(torch, M, K, gen, 3))
+    y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(B.linear_workspace(M, N, K, fmt=B.PACK_TRIT5), dtype=torch.uint8, device="cuda")
+    scratch2 = torch.empty_like(p2)
+    us2 = _time_eager(torch, lambda: B.linear(xq, sx, p2, g2, N, y_dtype=B.BF16, y=y), 10)
+    us5 = _time_eager(torch, lambda: B.linear_ws(xq, sx, p5, g5, N, ws, fmt=B.PACK_TRIT5, y_dtype=B.BF16, y=y), 10)
+    usr = _time_eager(torch, lambda: B.repack_weights(p5, N, K, B.PACK_TRIT5, B.PACK_2BIT, out=scratch2), 10)
+    ops = 2.0 * M * N * K
+    res["13b_gate_up_m2048"] = {"K": K, "N": N, "M": M, "2bit": {"packed_bytes": p2.numel(), "us_linear": round(us2, 1), "TOPS": round(ops / us2 * 1e-6, 1)},
+                                "trit5": {"packed_bytes": p5.numel(), "us_linear_ws": round(us5, 1), "TOPS": round(ops / us5 * 1e-6, 1),
+                                          "us_repack_alone": round(usr, 1), "workspace_bytes": ws.numel()},
+                                "time_ratio_trit5_over_2bit": round(us5 / us2, 3)}
     return res
 
 

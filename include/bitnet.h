@@ -324,6 +324,29 @@ bitnet_status bitnet_linear_ws(const int8_t* xq, const float* sx, const void* pa
                                size_t workspace_bytes, void* stream);
 
 /*
+ * The 5-trit format at prefill sizes (Section 3: storage below 2 bits per weight).  The MFMA prefill kernel and the
+ * batched-decode kernels read the 2-bit layout, whose fields are MFMA operand bytes after one shift and one AND; base-3
+ * digits need a table look-up per byte, which costs more issue slots than the product leaves free.  So weights kept in
+ * HBM in the 5-trit format are repacked to the 2-bit layout once per call -- 0.45 bytes of traffic per weight -- rather
+ * than decoded once per tile:
+ *
+ * bitnet_repack_weights: the same code matrix in the other format, on the device (either direction; the result is
+ * byte-identical to what bitnet_quantize_weights writes in that format).
+ *   packed_in / packed_out  bitnet_packed_bytes() bytes of their formats, 16-byte aligned, not overlapping
+ *   f_in != f_out           (BITNET_ERR_FORMAT otherwise)
+ *
+ * bitnet_linear_ws with f == BITNET_PACK_TRIT5, which == BITNET_KERNEL_AUTO, one gamma, more than 16 tokens, K a multiple
+ * of 16 and a workspace of at least bitnet_linear_workspace_format() bytes does this by itself: it repacks into the
+ * head of the workspace and runs the 2-bit path on the copy with the rest of the workspace.  With a smaller workspace,
+ * and through bitnet_linear, 5-trit weights are walked 16 tokens at a time by the decode kernel as before.
+ *
+ * bitnet_linear_workspace_format: bitnet_linear_workspace for a given weight format.
+ */
+bitnet_status bitnet_repack_weights(const void* packed_in, bitnet_format f_in, int64_t N, int64_t K, void* packed_out,
+                                    bitnet_format f_out, void* stream);
+bitnet_status bitnet_linear_workspace_format(int64_t M, int64_t N, int64_t K, bitnet_format f, size_t* bytes);
+
+/*
  * Decode path in one launch: activation quantization fused into the weight-streaming kernel, x -> y.
  * Same arithmetic as bitnet_quantize_acts followed by bitnet_linear, with bit-identical x_q and s_x:
  * every workgroup re-derives them for all M tokens into LDS (x is small and cache-resident at decode

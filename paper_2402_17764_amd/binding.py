@@ -32,6 +32,7 @@ SYMBOLS = [
     "bitnet_rmsnorm_linear_fused", "bitnet_rmsnorm_linear_fused_segmented", "bitnet_swiglu_linear_fused",
     "bitnet_ffn_gate_up_fused", "bitnet_linear_workspace", "bitnet_linear_ws", "bitnet_linear_describe",
     "bitnet_entry_describe", "bitnet_abs_sum", "bitnet_quantize_weights_sharded", "bitnet_quantize_weights_static",
+    "bitnet_repack_weights", "bitnet_linear_workspace_format",
 ]
 
 _lib = None
@@ -61,6 +62,8 @@ def load():
     lib.bitnet_quantize_weights_workspace.argtypes = [i64, i64, ctypes.POINTER(sz)]
     lib.bitnet_quantize_weights.argtypes = [vp, ci, i64, i64, ci, vp, vp, vp, sz, vp]
     lib.bitnet_quantize_weights_static.argtypes = [vp, ci, i64, i64, ci, vp, vp, vp]
+    lib.bitnet_repack_weights.argtypes = [vp, ci, i64, i64, vp, ci, vp]
+    lib.bitnet_linear_workspace_format.argtypes = [i64, i64, i64, ci, ctypes.POINTER(sz)]
     lib.bitnet_abs_sum.argtypes = [vp, ci, i64, i64, vp, vp, sz, vp]
     lib.bitnet_quantize_weights_sharded.argtypes = [vp, ci, i64, i64, ci, vp, ci, i64, vp, vp, vp]
     lib.bitnet_quantize_acts.argtypes = [vp, ci, i64, i64, vp, vp, vp]
@@ -255,12 +258,23 @@ def linear(xq, sx, packed, gamma, N, fmt=PACK_2BIT, y_dtype=F32, y=None, kernel=
     return y
 
 
-def linear_workspace(M, N, K):
-    """Bytes of scratch with which linear_ws can use every split-K variant it may choose for this shape (0: none)."""
+def linear_workspace(M, N, K, fmt=PACK_2BIT):
+    """Bytes of scratch with which linear_ws can use every variant it may choose for this shape and weight format:
+    split-K partials, and for 5-trit weights at more than 16 tokens the 2-bit copy of the matrix (0: none)."""
     lib = load()
     out = ctypes.c_size_t(0)
-    _check(lib.bitnet_linear_workspace(M, N, K, ctypes.byref(out)), "bitnet_linear_workspace")
+    _check(lib.bitnet_linear_workspace_format(M, N, K, fmt, ctypes.byref(out)), "bitnet_linear_workspace_format")
     return int(out.value)
+
+
+def repack_weights(packed, N, K, f_in, f_out, out=None):
+    """The packed matrix in the other format (device to device)."""
+    lib = load()
+    if out is None:
+        out = torch.empty(packed_bytes(N, K, f_out), dtype=torch.uint8, device=packed.device)
+    _check(lib.bitnet_repack_weights(_dev(packed, "packed"), f_in, N, K, _dev(out, "out"), f_out, _stream()),
+           "bitnet_repack_weights")
+    return out
 
 
 def _parse_plan(text):

@@ -249,11 +249,43 @@ bitnet_status bitnet_linear_workspace(int64_t M, int64_t N, int64_t K, size_t* b
     return BITNET_OK;
 }
 
+// bytes of a 2-bit copy of the matrix, rounded up so that what follows it in a workspace stays 256-byte aligned
+static size_t repacked_bytes(int64_t N, int64_t K) {
+    size_t b = 0;
+    bitnet_packed_bytes(N, K, BITNET_PACK_2BIT, &b);
+    return (b + 255) / 256 * 256;
+}
+
+bitnet_status bitnet_linear_workspace_format(int64_t M, int64_t N, int64_t K, bitnet_format f, size_t* bytes) {
+    if (!format_ok(f)) return BITNET_ERR_FORMAT;
+    const bitnet_status st = bitnet_linear_workspace(M, N, K, bytes);
+    if (st != BITNET_OK || f == BITNET_PACK_2BIT) return st;
+    // 5-trit weights and more than 16 tokens: room for the matrix repacked to 2 bits, plus what the 2-bit path may use
+    if (M > 16 && K % 16 == 0) *bytes += repacked_bytes(N, K);
+    else *bytes = 0;
+    return BITNET_OK;
+}
+
 bitnet_status bitnet_linear_ws(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                int gamma_per_block, int64_t M, int64_t N, int64_t K, bitnet_format f, void* y,
                                bitnet_dtype y_dtype, bitnet_kernel which, void* workspace, size_t workspace_bytes,
                                void* stream) {
     const int gstride = gamma_per_block ? 1 : 0;
+    if (f == BITNET_PACK_TRIT5 && which == BITNET_KERNEL_AUTO && !gamma_per_block && workspace && shape_ok(M, N, K) && M > 16 &&
+        K % 16 == 0 && workspace_bytes >= repacked_bytes(N, K)) {
+        // 5-trit weights at prefill sizes: one pass repacks the matrix to the 2-bit layout at the head of the workspace
+        // (0.45 bytes per weight of traffic, against 2 M operations per weight of product), then the 2-bit kernels run
+        // on it with the rest of the workspace.  Everything is validated before that first launch.
+        if (!xq || !sx || !packed || !gamma || !y) return BITNET_ERR_NULL;
+        OutType yt0;
+        if (!out_type(y_dtype, &yt0)) return BITNET_ERR_DTYPE;
+        if (!aligned(packed, 16) || !aligned(workspace, 16) || !aligned(sx, 4) || !aligned(gamma, 4) || !aligned(y, dtype_size(y_dtype)))
+            return BITNET_ERR_ALIGN;
+        const size_t head = repacked_bytes(N, K);
+        if (bitnet::launch_repack(packed, true, N, K, workspace, static_cast<hipStream_t>(stream)) != hipSuccess) return BITNET_ERR_HIP;
+        return bitnet_linear_ws(xq, sx, workspace, gamma, 0, M, N, K, BITNET_PACK_2BIT, y, y_dtype, BITNET_KERNEL_AUTO,
+                                workspace_bytes > head ? static_cast<char*>(workspace) + head : nullptr, workspace_bytes - head, stream);
+    }
     int force = 0;
     if (((int)which & ~0xFF) == 0x200) {               // split-K forced: 0x200 | splits
         force = (int)which & 0xFF;
@@ -495,6 +527,15 @@ bitnet_status bitnet_ffn_gate_up_fused(const void* x, bitnet_dtype x_dtype, int 
     return from_hip(bitnet::launch_linear_fused_swiglu_out_2bit(
         x, x_dtype == BITNET_BF16, norm != 0, norm ? g : nullptr, eps, packed, gamma, gamma_per_block ? 1 : 0, M, F, K, h,
         h_dtype == BITNET_BF16 ? OutType::BF16 : OutType::F32, static_cast<hipStream_t>(stream)));
+}
+
+bitnet_status bitnet_repack_weights(const void* packed_in, bitnet_format f_in, int64_t N, int64_t K, void* packed_out,
+                                    bitnet_format f_out, void* stream) {
+    if (!packed_in || !packed_out) return BITNET_ERR_NULL;
+    if (!shape_ok(1, N, K)) return BITNET_ERR_SHAPE;
+    if (!format_ok(f_in) || !format_ok(f_out) || f_in == f_out) return BITNET_ERR_FORMAT;
+    if (!aligned(packed_in, 16) || !aligned(packed_out, 16)) return BITNET_ERR_ALIGN;
+    return from_hip(bitnet::launch_repack(packed_in, f_in == BITNET_PACK_TRIT5, N, K, packed_out, static_cast<hipStream_t>(stream)));
 }
 
 bitnet_status bitnet_unpack_weights(const void* packed, int64_t N, int64_t K, bitnet_format f, int8_t* codes,

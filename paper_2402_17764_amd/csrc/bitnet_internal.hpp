@@ -135,6 +135,8 @@ hipError_t launch_pack_trit5(const void* W, bool bf16, int64_t N, int64_t K, con
 hipError_t launch_unpack_trit5(const void* packed, int64_t N, int64_t K, int8_t* codes, hipStream_t stream);
 hipError_t launch_linear_reference_trit5(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                          int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);
+// the same matrix in the other packing format (in_trit5: 5-trit -> 2-bit, else 2-bit -> 5-trit)
+hipError_t launch_repack(const void* in, bool in_trit5, int64_t N, int64_t K, void* out, hipStream_t stream);
 bool gemv_trit5_supports(int64_t M, int64_t N, int64_t K, const void* xq);
 hipError_t launch_linear_gemv_trit5(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                     int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream);

@@ -265,6 +265,107 @@ hipError_t launch_linear_reference_trit5(const int8_t* xq, const float* sx, cons
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------------
+// repacking between the two formats on the device (no weights in full precision needed)
+// ---------------------------------------------------------------------------------------------------
+// 320 columns are one step of the 5-trit layout (4 quads of 80) and five quads of the 2-bit layout (64 each): one
+// thread moves the 320 codes of one row.  Consecutive threads take consecutive rows of a 16-row block, so their
+// 16-byte loads and stores form 256-byte runs in both layouts.
+//
+// 5-trit -> 2-bit.  A 5-trit byte p of quad g holds quad columns 4p .. 4p+3, i.e. step columns 80 g + 4 p + (0 .. 3):
+// four columns that the 2-bit layout keeps in one 32-bit word (word (80 g + 4 p) / 16 of the step), in field i = p & 3
+// of its four bytes; the table gives those four 2-bit codes already spread to bits 0, 8, 16, 24.  The sixteen fifth
+// digits of a quad are step columns 80 g + 64 .. 80 g + 79: exactly one word.
+__global__ __launch_bounds__(256) void repack_trit5_to_2bit(const uint4* __restrict__ in, int64_t RB, int64_t steps5,
+                                                            int64_t Kq2, uint4* __restrict__ out) {
+    __shared__ uint2 lut[256];                       // byte -> {codes 0..3 as 2-bit fields at bits 0, 8, 16, 24; code 4}
+    {
+        const int b = threadIdx.x;
+        uint32_t sp = 0, c4 = 0;
+        if (b < 243) {
+#pragma unroll
+            for (int d = 0; d < 4; ++d) sp |= ((uint32_t)trit5_digit(b, d) & 3u) << (8 * d);
+            c4 = (uint32_t)trit5_digit(b, 4) & 3u;
+        }
+        lut[b] = make_uint2(sp, c4);
+    }
+    __syncthreads();
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= 16 * RB * steps5) return;
+    const int r = (int)(idx & 15);
+    const int64_t rb = (idx >> 4) % RB, s5 = (idx >> 4) / RB;
+    uint32_t words[20];                              // the row's 320 codes as twenty 2-bit words of 16 columns
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const uint4 q = in[64 * (RB * s5 + rb) + 16 * g + r];
+        const uint32_t wd[4] = {q.x, q.y, q.z, q.w};
+        uint32_t fifth = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t w = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint2 e = lut[(wd[j] >> (8 * i)) & 0xFFu];               // byte p = 4 j + i
+                w |= e.x << (2 * i);
+                fifth |= e.y << (8 * i + 2 * j);                                // column 64 + p = 64 + 4 j + i: byte i, field j
+            }
+            words[5 * g + j] = w;
+        }
+        words[5 * g + 4] = fifth;
+    }
+#pragma unroll
+    for (int q5 = 0; q5 < 5; ++q5) {
+        const int64_t kq = 5 * s5 + q5;
+        if (kq < Kq2)
+            out[quad_index_2bit(kq, rb, r, Kq2, RB)] = make_uint4(words[4 * q5], words[4 * q5 + 1], words[4 * q5 + 2], words[4 * q5 + 3]);
+    }
+}
+
+// 2-bit -> 5-trit: the same move backwards; 2-bit quads past the matrix's last one read as zero codes.
+__global__ __launch_bounds__(256) void repack_2bit_to_trit5(const uint4* __restrict__ in, int64_t RB, int64_t steps5,
+                                                            int64_t Kq2, uint4* __restrict__ out) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= 16 * RB * steps5) return;
+    const int r = (int)(idx & 15);
+    const int64_t rb = (idx >> 4) % RB, s5 = (idx >> 4) / RB;
+    uint32_t words[20];
+#pragma unroll
+    for (int q5 = 0; q5 < 5; ++q5) {
+        const int64_t kq = 5 * s5 + q5;
+        uint4 q = make_uint4(0, 0, 0, 0);
+        if (kq < Kq2) q = in[quad_index_2bit(kq, rb, r, Kq2, RB)];
+        words[4 * q5] = q.x; words[4 * q5 + 1] = q.y; words[4 * q5 + 2] = q.z; words[4 * q5 + 3] = q.w;
+    }
+    // code + 1 of step column c: word c / 16, bits 8 (c & 3) + 2 ((c & 15) >> 2)
+    auto digit = [&](int c) -> uint32_t {
+        const uint32_t f = (words[c >> 4] >> (8 * (c & 3) + 2 * ((c & 15) >> 2))) & 3u;   // 0, 1, 3 for codes 0, +1, -1
+        return f == 3u ? 0u : f + 1u;
+    };
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        uint32_t o[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int p = 0; p < 16; ++p) {
+            const int c = 80 * g + 4 * p;
+            const uint32_t b = digit(c) + 3 * digit(c + 1) + 9 * digit(c + 2) + 27 * digit(c + 3) + 81 * digit(80 * g + 64 + p);
+            o[p >> 2] |= b << (8 * (p & 3));
+        }
+        out[64 * (RB * s5 + rb) + 16 * g + r] = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+}
+
+hipError_t launch_repack(const void* in, bool in_trit5, int64_t N, int64_t K, void* out, hipStream_t stream) {
+    const int64_t RB = ceil_div(N, kRowsPerBlock), steps5 = ceil_div(K, kTritStep), Kq2 = ceil_div(K, kColsPerQuad);
+    dim3 grid((unsigned)ceil_div(16 * RB * steps5, 256));
+    if (in_trit5)
+        hipLaunchKernelGGL(repack_trit5_to_2bit, grid, dim3(256), 0, stream, static_cast<const uint4*>(in), RB, steps5, Kq2,
+                           static_cast<uint4*>(out));
+    else
+        hipLaunchKernelGGL(repack_2bit_to_trit5, grid, dim3(256), 0, stream, static_cast<const uint4*>(in), RB, steps5, Kq2,
+                           static_cast<uint4*>(out));
+    return hipGetLastError();
+}
+
 bool gemv_trit5_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
     (void)N;
     return M >= 1 && M <= 16 && K % 16 == 0 && reinterpret_cast<uintptr_t>(xq) % 16 == 0;

@@ -1200,6 +1200,56 @@ def test_trit5_linear_matches_oracle(gpu_lib, M, N, K):
         assert e.value.status == 8
 
 
+@pytest.mark.parametrize("N,K", [(4096, 1536), (16, 320), (1, 1), (37, 129), (100, 70), (17, 1000), (250, 4100), (33, 641), (3200, 3200)])
+def test_repack_between_the_formats_is_byte_exact(gpu_lib, N, K):
+    """The device repacking in both directions: the result must be the very bytes bitnet_quantize_weights writes in
+    the target format (codes from the oracle's quantizer, padding zero), for K not a multiple of 64, 80 or 320 too."""
+    say("repack N=%d K=%d" % (N, K))
+    W = synth.weights(N, K, config=0, layer=N % 7, tensor=41)
+    codes_ref, _ = oracle.quantize_weights(W)
+    p2, _ = gpu_lib.quantize_weights(dev(W), fmt=gpu_lib.PACK_2BIT)
+    p5, _ = gpu_lib.quantize_weights(dev(W), fmt=gpu_lib.PACK_TRIT5)
+    to2 = torch.full_like(p2, 0x5A)
+    to5 = torch.full_like(p5, 0x5A)
+    gpu_lib.repack_weights(p5, N, K, gpu_lib.PACK_TRIT5, gpu_lib.PACK_2BIT, out=to2)
+    gpu_lib.repack_weights(p2, N, K, gpu_lib.PACK_2BIT, gpu_lib.PACK_TRIT5, out=to5)
+    assert torch.equal(to2, p2) and torch.equal(to5, p5)
+    dec2, pad2 = decode_2bit(to2.cpu().numpy(), N, K)
+    dec5, pad5 = decode_trit5(to5.cpu().numpy(), N, K)
+    assert pad2 and pad5 and np.array_equal(dec2, codes_ref) and np.array_equal(dec5, codes_ref)
+    lib = gpu_lib.load()
+    assert lib.bitnet_repack_weights(p2.data_ptr(), 0, N, K, to5.data_ptr(), 0, None) == 4      # same format both sides
+    assert lib.bitnet_repack_weights(None, 0, N, K, to5.data_ptr(), 1, None) == 1
+    assert lib.bitnet_repack_weights(p2.data_ptr() + 1, 0, N, K, to5.data_ptr(), 1, None) == 5
+
+
+@pytest.mark.parametrize("M,N,K", [(17, 300, 528), (65, 300, 528), (100, 520, 1040), (300, 1000, 3200), (130, 8000, 272),
+                                   (513, 270, 4112), (256, 4096, 1296), (2048, 5120, 640)])
+def test_trit5_prefill_through_the_workspace_matches_oracle(gpu_lib, M, N, K):
+    """5-trit weights at more than 16 tokens through bitnet_linear_ws: repacked to 2 bits in the workspace, then the
+    batched-decode or MFMA prefill kernel -- accumulators bit-exact, outputs within the bars; with a workspace that
+    cannot hold the copy the 16-tokens-at-a-time route gives the same integers."""
+    say("trit5 prefill M=%d N=%d K=%d" % (M, N, K))
+    W = synth.weights(N, K, config=0, layer=M % 9, tensor=42)
+    x = synth.activations(M, K, config=0, layer=M % 9, tensor=43)
+    ref = oracle.bitlinear(x, W)
+    p5, gamma = gpu_lib.quantize_weights(dev(W), fmt=gpu_lib.PACK_TRIT5)
+    xq, sx = gpu_lib.quantize_acts(dev(x))
+    need = gpu_lib.linear_workspace(M, N, K, fmt=gpu_lib.PACK_TRIT5)
+    assert need >= gpu_lib.packed_bytes(N, K, gpu_lib.PACK_2BIT)
+    ws = torch.full((need + 64,), 0x77, dtype=torch.uint8, device="cuda")
+    acc = gpu_lib.linear_ws(xq, sx, p5, gamma, N, ws[:need], fmt=gpu_lib.PACK_TRIT5, y_dtype=gpu_lib.I32)
+    assert np.array_equal(acc.cpu().numpy(), ref["acc"])
+    assert bool((ws[need:] == 0x77).all())                                  # nothing written past the stated size
+    check_y(gpu_lib.linear_ws(xq, sx, p5, gamma, N, ws[:need], fmt=gpu_lib.PACK_TRIT5, y_dtype=gpu_lib.F32).cpu().numpy(), ref["y"], RTOL_F32)
+    check_y(gpu_lib.linear_ws(xq, sx, p5, gamma, N, ws[:need], fmt=gpu_lib.PACK_TRIT5, y_dtype=gpu_lib.BF16).float().cpu().numpy(),
+            ref["y"], RTOL_BF16)
+    small = ws[:1024]
+    acc2 = gpu_lib.linear_ws(xq, sx, p5, gamma, N, small, fmt=gpu_lib.PACK_TRIT5, y_dtype=gpu_lib.I32)
+    assert torch.equal(acc2, acc)
+    assert gpu_lib.linear_workspace(16, N, K, fmt=gpu_lib.PACK_TRIT5) == 0  # the decode kernel reads 5-trit weights directly
+
+
 def test_trit5_is_rejected_where_unsupported(gpu_lib):
     say("trit5 limits")
     W = dev(synth.weights(32, 320, config=0, layer=1))
