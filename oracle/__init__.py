@@ -12,8 +12,13 @@ Functions follow the paper's order:
     ternary_matmul     the integer product
     rescale            undoing gamma and s_x / 127
     bitlinear          all of it, x and W in, y out
+
+Setting BITNET_ORACLE_LIBRARY to the path of another build of bitnet_oracle.c (the sanitized one of
+oracle.build.build_oracle_sanitized) makes this module load that instead.
 """
 import ctypes
+import os
+
 import numpy as np
 
 from .build import build_oracle
@@ -24,7 +29,7 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build_oracle())
+        lib = ctypes.CDLL(os.environ.get("BITNET_ORACLE_LIBRARY") or build_oracle())
         i64, vp = ctypes.c_int64, ctypes.c_void_p
         lib.oracle_absmean_gamma.argtypes = [vp, i64, i64, vp, vp]
         lib.oracle_ternarize.argtypes = [vp, i64, i64, ctypes.c_float, vp]

@@ -3,7 +3,8 @@
 Marshalling only: every function takes torch tensors that already live on the GPU (torch is used
 for device memory and streams, nothing else), checks dtype / shape / contiguity, passes raw device
 pointers and the current HIP stream through the C ABI, and raises BitnetError on a non-zero status.
-There is no fallback: if the shared library has not been built, load() raises.
+There is no fallback: if the shared library has not been built, load() raises.  BITNET_HIP_LIBRARY names another build
+of the same library to load instead (the host-sanitized one of paper_2402_17764_amd.build.build_library(sanitize=True)).
 """
 import ctypes
 import os
@@ -11,7 +12,7 @@ import os
 import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libbitnet_hip.so")
+LIB_PATH = os.environ.get("BITNET_HIP_LIBRARY") or os.path.join(HERE, "libbitnet_hip.so")
 
 # enums of bitnet.h
 OK = 0

@@ -45,22 +45,26 @@ def _check_no_scratch(src, stderr):
         raise RuntimeError("%s: kernels that count loads in flight must not spill: %s" % (src, ", ".join(bad)))
 
 
-def _check_issue_order(src):
+def skinny_instantiations(source_text):
+    """The linear_skinny_2bit<kMT, kR, kW, kS, kD, kLx> instantiations that the launcher dispatches: every
+    `SKINNY(a, b, c, d, e, f)` use in the source."""
+    return sorted({tuple(int(v) for v in m.groups())
+                   for m in re.finditer(r"\bSKINNY\((\d+), (\d+), (\d+), (\d+), (\d+), (\d+)\)", source_text)})
+
+
+def check_issue_order(asm_text, expected):
     """linear_skinny_2bit waits for a step's LDS copies with a count of the younger loads (s_waitcnt vmcnt(n)), which
     holds only if each step's copies are issued before the weight loads that follow them in the source.  Scheduling
-    fences in the kernel pin that; this reads the generated ISA and fails the build if a compiler ever ignores them:
-    between barriers a wave must issue kC = 4 kMT / kW copies ("buffer_load ... lds") and then kR weight loads, and
-    the prologue kD such groups."""
-    asm = os.path.join(BUILD, os.path.splitext(src)[0] + ".s")
-    cmd = [HIPCC, *FLAGS, "--cuda-device-only", "-S", os.path.join(CSRC, src), "-o", asm]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("hipcc -S failed on %s:\n%s" % (src, r.stderr))
-    cur, segs, checked = None, [""], 0
-    for line in open(asm):
+    fences in the kernel pin that; this reads the device assembly the object is assembled from and raises if a
+    compiler ever ignores them: between barriers a wave must issue kC = 4 kMT / kW copies ("buffer_load ... lds") and
+    then kR weight loads, and the prologue kD such groups.  Every instantiation in `expected` must be present and pass;
+    an instantiation in the assembly that is not expected is an error too (it would ship unchecked by the dispatch
+    tests).  Returns the instantiations checked."""
+    cur, segs, checked = None, [""], []
+    for line in asm_text.splitlines():
         m = re.match(r"^_ZN6bitnet18linear_skinny_2bitILi(\d+)ELi(\d+)ELi(\d+)ELi(\d+)ELi(\d+)ELi(\d+)E\S*:", line)
         if m:
-            cur, segs = [int(v) for v in m.groups()], [""]
+            cur, segs = tuple(int(v) for v in m.groups()), [""]
             continue
         if cur is None:
             continue
@@ -73,18 +77,61 @@ def _check_issue_order(src):
             unit = "L" * (4 * kMT // kW) + "W" * kR
             loops = [g for g in segs[1:] if g]
             if segs[0] != unit * kD or not loops or any(g != unit for g in loops):
-                raise RuntimeError("%s: linear_skinny_2bit<%s>: loads are not issued in source order (%s), the counted "
-                                   "waits would be wrong" % (src, ", ".join(map(str, cur)), " | ".join(segs)))
-            cur, checked = None, checked + 1
-    if checked == 0:
-        raise RuntimeError("%s: no linear_skinny_2bit kernel found in the ISA: issue order unchecked" % src)
+                raise RuntimeError("linear_skinny_2bit<%s>: loads are not issued in source order (%s), the counted "
+                                   "waits would be wrong" % (", ".join(map(str, cur)), " | ".join(segs)))
+            checked.append(cur)
+            cur = None
+    if cur is not None:
+        raise RuntimeError("linear_skinny_2bit<%s>: the kernel's end was not found in the assembly" % ", ".join(map(str, cur)))
+    missing = sorted(set(expected) - set(checked))
+    extra = sorted(set(checked) - set(expected))
+    if missing or extra or len(checked) != len(set(checked)):
+        raise RuntimeError("linear_skinny_2bit: issue order unchecked for %s; not dispatched but built: %s" % (missing, extra))
+    return checked
+
+
+def _check_issue_order(src):
+    """Runs check_issue_order on the assembly that -save-temps left next to the object: the very text the device
+    code of the shipped object was assembled from."""
+    asm = os.path.join(BUILD, os.path.splitext(src)[0] + "-hip-amdgcn-amd-amdhsa-gfx950.s")
+    expected = skinny_instantiations(open(os.path.join(CSRC, src)).read())
+    if not expected:
+        raise RuntimeError("%s: no SKINNY(...) dispatch found: the issue-order check has nothing to go by" % src)
+    check_issue_order(open(asm).read(), expected)
+
+
+# Host code with the undefined-behaviour sanitizer compiled in as traps (no runtime library to load): signed overflow,
+# bad shifts, out-of-range enum and integer conversions, misaligned and null accesses in the validation and dispatch
+# code end the process.  The device code is built as usual; only host-side calls are meant to run against this build.
+SANITIZE_HOST = ["-Xarch_host", "-fsanitize=undefined,integer", "-Xarch_host", "-fsanitize-trap=all", "-Xarch_host",
+                 "-fno-sanitize=unsigned-integer-overflow,unsigned-shift-base,implicit-conversion"]
+
+
+def _compile_sanitized(src, out_dir):
+    obj = os.path.join(out_dir, os.path.splitext(src)[0] + ".o")
+    flags = [f for f in FLAGS if f != "-O3"] + ["-O1", *SANITIZE_HOST]
+    r = subprocess.run([HIPCC, *flags, "-c", os.path.join(CSRC, src), "-o", obj], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc (host-sanitized) failed on %s:\n%s" % (src, r.stderr))
+    return obj
+
+
+def build_library_sanitized() -> str:
+    """libbitnet_hip_ubsan.so under _build/ubsan: for the CPU test that runs the host-side tests against it."""
+    out_dir = os.path.join(BUILD, "ubsan")
+    os.makedirs(out_dir, exist_ok=True)
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+        objs = list(ex.map(lambda s: _compile_sanitized(s, out_dir), SOURCES))
+    lib = os.path.join(out_dir, "libbitnet_hip_ubsan.so")
+    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", lib])
+    return lib
 
 
 def _compile(src):
     obj = os.path.join(BUILD, os.path.splitext(src)[0] + ".o")
     cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
     if src in NO_SCRATCH:
-        cmd.append("-Rpass-analysis=kernel-resource-usage")
+        cmd += ["-Rpass-analysis=kernel-resource-usage", "-save-temps=obj"]      # the device assembly stays next to the object
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     lines = [l for l in r.stderr.splitlines() if noise not in l]
@@ -95,6 +142,7 @@ def _compile(src):
         raise RuntimeError("hipcc failed on %s:\n%s" % (src, err))
     if src in NO_SCRATCH:
         _check_no_scratch(src, r.stderr)
+        _check_issue_order(src)
     if err.strip():
         sys.stderr.write(err + "\n")
     return obj
@@ -102,10 +150,8 @@ def _compile(src):
 
 def build_library(verbose: bool = False) -> str:
     os.makedirs(BUILD, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES) + 1)) as ex:
-        order = ex.submit(_check_issue_order, "linear_skinny.hip")
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
-        order.result()
     tmp = LIB + ".tmp.%d" % os.getpid()
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", tmp])
     os.replace(tmp, LIB)
