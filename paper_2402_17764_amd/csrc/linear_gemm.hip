@@ -307,30 +307,34 @@ __device__ __forceinline__ void gemm_tile(
     };
 
     // One loop body for every step: operands of step s + 1 are requested right before step s is
-    // consumed (activations into the other LDS stage, weights into wnext), and the barrier at the top of
-    // the next iteration both publishes them and retires the stage that was just read.
-    uint4 wq[kFN][2], wnext[kFN][2];
+    // consumed (activations into the other LDS stage, weights into the other of two register sets), and the
+    // barrier at the top of the next step both publishes them and retires the stage that was just read.  The
+    // loop is unrolled by two so that the two register sets swap roles by name: copying the landed quads into
+    // a working set cost 32 moves per step.
+    uint4 wa[kFN][2], wb[kFN][2];
     const uint32_t keep_t0 = (kg * 16 + brow) < tail_quads ? 0xC0C0C0C0u : 0u;
     const uint32_t keep_t1 = ((kg + 2) * 16 + brow) < tail_quads ? 0xC0C0C0C0u : 0u;
-    auto issue = [&](int step) {
+    auto issue = [&](uint4 (&into)[kFN][2], int step) {
         copy_x(step, step & 1);
-        if (step < full_steps) load_w(wnext, step); else load_w_tail(wnext, step);
+        if (step < full_steps) load_w(into, step); else load_w_tail(into, step);
     };
-    issue(step0);
-#pragma unroll 1
-    for (int s = step0; s < step1; ++s) {
+    auto one_step = [&](uint4 (&wcur)[kFN][2], uint4 (&wnxt)[kFN][2], int s) {
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        // move the step's quads out of the landing registers; lanes past a partial last step get a zero decode constant
+        // lanes past a partial last step get a zero decode constant
         const uint32_t all = s >= full_steps ? 0u : 0xC0C0C0C0u;   // uniform
         const uint32_t km[2] = {keep_t0 | all, keep_t1 | all};
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int fn = 0; fn < kFN; ++fn) wq[fn][h] = wnext[fn][h];
-        if (s + 1 < step1) issue(s + 1);
-        compute(wq, km, s & 1);
+        if (s + 1 < step1) issue(wnxt, s + 1);
+        compute(wcur, km, s & 1);
+    };
+    issue(wa, step0);
+    int s = step0;
+#pragma unroll 1
+    for (; s + 1 < step1; s += 2) {
+        one_step(wa, wb, s);
+        one_step(wb, wa, s + 1);
     }
+    if (s < step1) one_step(wa, wb, s);
     __syncthreads();                                    // every wave is done with the activation stages
 
     // ---- epilogue: one instantiation per output type, chosen once ---------------------------------------
