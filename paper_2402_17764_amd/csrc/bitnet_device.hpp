@@ -36,6 +36,25 @@ __device__ inline uint16_t f32_to_bf16(float f) {
     return (uint16_t)(u >> 16);
 }
 
+// ---- Section 2, the int8 code of one activation ------------------------------------------------------
+// x_q = clip(round(x * inv), -127, 127) with inv = fl(127 / s) and round = ties to even.  p = fl(x * inv) is one fp32
+// multiply; adding 1.5 * 2^23 to it rounds p to the nearest integer, ties to even, in the addition itself (the sum lies
+// in [2^23, 2^24), where floats are the integers; the constant is even, so the tie rule is p's), and leaves that integer,
+// two's complement, in the low bits of the result -- one add where rint, a conversion and a clamp were three
+// instructions.  The clamp of the definition never binds for finite input: |x| <= s and inv <= (127 / s)(1 + 2^-24) give
+// |p| < 127.5.  (Contraction is off for the whole library, so the multiply and the add are never fused.)
+constexpr float kRoundMagic = 12582912.0f;       // 1.5 * 2^23
+__device__ inline uint32_t quantize_bits(float v, float inv) {
+    const float p = v * inv;
+    return __float_as_uint(p + kRoundMagic);      // low byte = x_q
+}
+// four values -> their four codes in one word, lowest address first (two byte permutes and an OR)
+__device__ inline uint32_t pack4_quantized(float a, float b, float c, float d, float inv) {
+    const uint32_t ab = __builtin_amdgcn_perm(quantize_bits(b, inv), quantize_bits(a, inv), 0x0c0c0400u);   // bytes a, b, 0, 0
+    const uint32_t cd = __builtin_amdgcn_perm(quantize_bits(d, inv), quantize_bits(c, inv), 0x04000c0cu);   // bytes 0, 0, c, d
+    return ab | cd;
+}
+
 // ---- wave64 all-lanes reductions with DPP for the four in-row steps ------------------------------
 // quad_perm [1,0,3,2] = 0xB1, quad_perm [2,3,0,1] = 0x4E, row_half_mirror = 0x141, row_mirror = 0x140.
 template <int kCtrl>

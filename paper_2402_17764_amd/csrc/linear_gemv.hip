@@ -73,17 +73,8 @@ __device__ inline float vec_absmax(const uint4& q, float amax) {
     return amax;
 }
 
-// Four values -> four int8 codes in one word.  rint(v * inv) is one fp32 multiply and a round to nearest even;
-// the clamp to [-127, 127] never binds for finite input (|v| <= s and inv = fl(127 / s) give |v * inv| < 127.5)
-// and costs one median instruction; the bytes are gathered with two byte permutes and an OR.
-__device__ inline uint32_t quant_int(float v, float inv) {
-    return (uint32_t)(int)__builtin_amdgcn_fmed3f(rintf(v * inv), -kQb, kQb);
-}
-__device__ inline uint32_t pack4_codes(float a, float b, float c, float d, float inv) {
-    const uint32_t ab = __builtin_amdgcn_perm(quant_int(b, inv), quant_int(a, inv), 0x0c0c0400u);   // bytes a, b, 0, 0
-    const uint32_t cd = __builtin_amdgcn_perm(quant_int(d, inv), quant_int(c, inv), 0x04000c0cu);   // bytes 0, 0, c, d
-    return ab | cd;
-}
+// Four values -> four int8 codes in one word (pack4_quantized: the stand-alone quantizers' own arithmetic).
+__device__ inline uint32_t pack4_codes(float a, float b, float c, float d, float inv) { return pack4_quantized(a, b, c, d, inv); }
 
 // one 16-byte vector of x -> its int8 codes, written to the token's LDS row (32-bit words)
 template <bool kBf16>

@@ -14,11 +14,7 @@ constexpr int kActThreads = 256;
 constexpr int kActWaves = kActThreads / kWave;
 constexpr int kActMaxVec = 16;         // register-resident path: up to 16 x 16 bytes per thread (256 or 1024 threads)
 
-__device__ inline int quantize_one(float v, float inv) {
-    float r = rintf(v * inv);                              // one fp32 multiply, ties to even
-    r = fminf(kQb, fmaxf(-kQb, r));
-    return (int)r;
-}
+__device__ inline int quantize_one(float v, float inv) { return (int)(int8_t)(quantize_bits(v, inv) & 0xFFu); }
 
 template <int kWaves = kActWaves>
 __device__ inline float block_max_nonneg(float v, float* sh) {
@@ -79,20 +75,14 @@ __global__ __launch_bounds__(kThreads) void quantize_acts_vec(const void* __rest
         if (idx >= nvec) continue;
         const uint32_t u[4] = {raw[v].x, raw[v].y, raw[v].z, raw[v].w};
         if (kBf16) {
-            uint32_t lo = 0, hi = 0;
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                lo |= ((uint32_t)quantize_one(__uint_as_float(u[e] << 16), inv) & 0xFFu) << (16 * e);
-                lo |= ((uint32_t)quantize_one(__uint_as_float(u[e] & 0xFFFF0000u), inv) & 0xFFu) << (16 * e + 8);
-                hi |= ((uint32_t)quantize_one(__uint_as_float(u[e + 2] << 16), inv) & 0xFFu) << (16 * e);
-                hi |= ((uint32_t)quantize_one(__uint_as_float(u[e + 2] & 0xFFFF0000u), inv) & 0xFFu) << (16 * e + 8);
-            }
+            const uint32_t lo = pack4_quantized(__uint_as_float(u[0] << 16), __uint_as_float(u[0] & 0xFFFF0000u),
+                                                __uint_as_float(u[1] << 16), __uint_as_float(u[1] & 0xFFFF0000u), inv);
+            const uint32_t hi = pack4_quantized(__uint_as_float(u[2] << 16), __uint_as_float(u[2] & 0xFFFF0000u),
+                                                __uint_as_float(u[3] << 16), __uint_as_float(u[3] & 0xFFFF0000u), inv);
             reinterpret_cast<uint2*>(out)[idx] = make_uint2(lo, hi);
         } else {
-            uint32_t p = 0;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) p |= ((uint32_t)quantize_one(__uint_as_float(u[e]), inv) & 0xFFu) << (8 * e);
-            reinterpret_cast<uint32_t*>(out)[idx] = p;
+            reinterpret_cast<uint32_t*>(out)[idx] = pack4_quantized(__uint_as_float(u[0]), __uint_as_float(u[1]), __uint_as_float(u[2]),
+                                                                    __uint_as_float(u[3]), inv);
         }
     }
 }
@@ -143,12 +133,7 @@ __device__ inline float load_elem(const void* row, int64_t k) {
     return kBf16 ? bf16_to_f32(static_cast<const uint16_t*>(row)[k]) : static_cast<const float*>(row)[k];
 }
 
-__device__ inline uint32_t pack4(const float (&v)[4], float inv) {
-    uint32_t p = 0;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) p |= ((uint32_t)quantize_one(v[e], inv) & 0xFFu) << (8 * e);
-    return p;
-}
+__device__ inline uint32_t pack4(const float (&v)[4], float inv) { return pack4_quantized(v[0], v[1], v[2], v[3], inv); }
 
 // RMSNorm -> absmax int8.  Per token: ms = mean of squares (exact: squares of fp32 values are exact in
 // fp64 and the sum is carried in double-double), r = (float)(1 / sqrt(ms + eps)) in fp64, z = (x * r) * g
