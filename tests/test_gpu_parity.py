@@ -706,16 +706,18 @@ def test_linear_decode_family_shapes_sampled(gpu_lib, name, K, N):
 
 
 def test_linear_prefill_70b_full_size_sampled(gpu_lib):
-    """70B-class FFN shapes at M = 4096 (the prefill sweep of the last benchmark configuration), sampled."""
+    """70B-class FFN shapes at M = 4096 (the prefill sweep of the last benchmark configuration): the oracle recomputes
+    a seeded sample of 128 tokens x 1024 weight rows, and the integer result of 256 more tokens (four runs of 64, from
+    both ends and the middle) is compared in full with the batched-decode kernels' result for the same tokens."""
     for (name, K, N) in (("gate_up", 8192, 57344), ("down", 28672, 8192)):
         say("linear prefill full size 70B %s" % name)
         M = 4096
         W = synth.weights(N, K, config=4, layer=1, tensor=len(name))
         gamma_ref, _ = oracle.absmean_gamma(W)
         rng = np.random.default_rng([4, K, N])
-        rows = np.sort(rng.choice(M, 40, replace=False))
+        rows = np.sort(rng.choice(M, 128, replace=False))
         rows[0], rows[-1] = 0, M - 1
-        cols = np.sort(rng.choice(N, 320, replace=False))
+        cols = np.sort(rng.choice(N, 1024, replace=False))
         cols[0], cols[-1] = 0, N - 1
         codes_ref = oracle.ternarize(W[cols], gamma_ref)
         packed, gamma = gpu_lib.quantize_weights(dev(W))
@@ -731,7 +733,13 @@ def test_linear_prefill_70b_full_size_sampled(gpu_lib):
         ci = torch.from_numpy(cols).cuda()
         assert np.array_equal(xq[ri].cpu().numpy(), xq_ref)
         acc = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.I32)
+        assert gpu_lib.linear_describe(M, N, K)["kernel"] == "prefill"
         assert np.array_equal(acc[ri][:, ci].cpu().numpy(), acc_ref)
+        for m0 in (0, 1000, 2048, M - 64):
+            sub = slice(m0, m0 + 64)
+            a_dec = gpu_lib.linear(xq[sub].contiguous(), sx[sub].contiguous(), packed, gamma, N, y_dtype=gpu_lib.I32,
+                                   kernel=gpu_lib.KERNEL_GEMV)
+            assert torch.equal(a_dec, acc[sub]), (name, m0)
         del acc
         y16 = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.BF16)
         check_y(y16[ri][:, ci].float().cpu().numpy(), y_ref, RTOL_BF16)
