@@ -233,7 +233,9 @@ bitnet_status bitnet_swiglu_quantize(const void* gu, bitnet_dtype gu_dtype, int6
                                      int8_t* hq, float* sh, void* stream);
 
 /*
- * The BitLinear product and rescale: y = (x_q . Wt^T) * gamma * s_x / 127.
+ * The BitLinear product and rescale (Section 2: BitLinear replaces nn.Linear; Section 1: the product of ternary weights
+ * and 8-bit activations needs integer addition only): y = (x_q . Wt^T) * gamma * s_x / 127, the integer sum exact in
+ * int32, gamma of Eq. (3) and the per-token s_x undone in floating point.
  *   xq, sx   as written by bitnet_quantize_acts
  *   packed   as written by bitnet_quantize_weights for the same (N, K, f); 16-byte aligned
  *   gamma    1 float (device)

@@ -264,6 +264,40 @@ __device__ inline void fused_quantize_to_lds(const void* __restrict__ xv, const 
     }
 }
 
+// The same quantization with one wave per token, for several tokens of short rows (at most kWaveTokenVecs 16-byte vectors
+// per lane: 4096 bf16 or 2048 fp32 elements): wave w takes tokens w, w + waves, ...; a token's absmax is a reduction
+// inside the wave, so the tokens of different waves proceed side by side and the workgroup meets once at the end --
+// where the block-wide form above pays two barriers and a trip to the L2 per token, one token after the other (1536
+// columns, 16 tokens: 15.7 -> 6.9 us per launch).  Same arithmetic, same bits; the absmax is order-free.
+constexpr int kWaveTokenVecs = 8;
+template <bool kBf16, int kThreads>
+__device__ inline void fused_quantize_wave_per_token(const void* __restrict__ xv, int M, int64_t K, int Kpad, float* sxl, uint4* xlds) {
+    constexpr int kE = kBf16 ? 8 : 4;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int nvec = (int)(K / kE), nvec_pad = Kpad / kE;
+    for (int m = wave; m < M; m += kThreads / kWave) {
+        const uint4* row = reinterpret_cast<const uint4*>(static_cast<const char*>(xv) + (int64_t)m * K * (kBf16 ? 2 : 4));
+        uint32_t* out = reinterpret_cast<uint32_t*>(xlds) + (size_t)m * (Kpad >> 2);
+        uint4 q[kWaveTokenVecs];
+        float amax = 0.0f;
+#pragma unroll
+        for (int v = 0; v < kWaveTokenVecs; ++v) {
+            q[v] = row[min(v * kWave + lane, nvec - 1)];            // clamped duplicates do not change a maximum
+            amax = vec_absmax<kBf16>(q[v], amax);
+        }
+        const float sc = fmaxf(wave_max_nonneg(amax), kEps);
+        const float inv = kQb / sc;                                 // one IEEE division per token
+        if (lane == 0) sxl[m] = sc;
+#pragma unroll
+        for (int v = 0; v < kWaveTokenVecs; ++v) {
+            const int idx = v * kWave + lane;
+            if (idx < nvec) vec_quantize_store<kBf16>(q[v], inv, out, idx);
+        }
+        for (int v = nvec + lane; v < nvec_pad; v += kWave) vec_quantize_store<kBf16>(make_uint4(0, 0, 0, 0), inv, out, v);
+    }
+    __syncthreads();
+}
+
 // kR    row blocks (16 rows each) per wave
 // kS    waves that split K: wave ws takes steps ws, ws + kS, ...
 // kW    row slots per workgroup (waves with different row blocks), workgroup = kS * kW waves
@@ -404,7 +438,10 @@ __global__ __launch_bounds__(kS * kW * kWave) void linear_gemv16_2bit(
         }
         __syncthreads();
     } else if (kFused) {
-        fused_quantize_to_lds<kInBf16, kPre, kThreads>(xin, row0, up0, row0_in_regs, gain0, M, K, Kpad, gain, eps, red, sxl, xlds);
+        if (kPre == kPreNone && M >= 3 && K <= (int64_t)kWaveTokenVecs * kWave * (kInBf16 ? 8 : 4))
+            fused_quantize_wave_per_token<kInBf16, kThreads>(xin, M, K, Kpad, sxl, xlds);
+        else
+            fused_quantize_to_lds<kInBf16, kPre, kThreads>(xin, row0, up0, row0_in_regs, gain0, M, K, Kpad, gain, eps, red, sxl, xlds);
     }
 
     int i = 0;

@@ -37,7 +37,10 @@ FUSED_SHAPES = [(1, 4096, 1536), (16, 4096, 1536), (1, 17, 16), (3, 100, 80), (7
                 (1, 600, 16400), (1, 100, 11008), (2, 64, 28672),
                 # the attention projections of the 3B and 7B decode workloads at their exact sizes (13 and 16 K steps on
                 # 200 ... 768 row blocks: four K-split waves on one row block), and two and four tokens on them
-                (1, 9600, 3200), (1, 3200, 3200), (1, 12288, 4096), (1, 4096, 4096), (2, 9600, 3200), (4, 3200, 3200)]
+                (1, 9600, 3200), (1, 3200, 3200), (1, 12288, 4096), (1, 4096, 4096), (2, 9600, 3200), (4, 3200, 3200),
+                # 2048 row blocks and more with 32 K steps and more: depth 3 with two extra steps requested up front
+                # (ragged rows, a partial 33rd step)
+                (2, 32816, 8208)]
 
 NORM_FUSED_SHAPES = [(1, 4096, 1536), (1, 100, 3200), (3, 250, 1040), (1, 33, 4112), (16, 70, 528), (1, 16400, 272),
                      (2, 16400, 4112), (1, 600, 16400), (1, 6416, 8640), (4, 300, 8192), (1, 32800, 528), (5, 40, 16)]
@@ -57,7 +60,8 @@ FAMILY_DECODE = [("13b_qkv", 5120, 15360), ("13b_o", 5120, 5120), ("13b_gate_up"
 # merged gate | up projection with the gate in the epilogue, (M, F, K): both workgroup shapes of its selection (F / 16 up
 # to 700 and above), K tails, several tokens
 FFN_GATE_UP_SHAPES = [(1, 8640, 3200), (1, 11008, 4096), (3, 1008, 1040), (1, 16, 16), (2, 11216, 272), (16, 48, 528),
-                      (1, 4000, 4112), (1, 16400, 272), (2, 16640, 528)]   # the last two: more than 1024 pairs (eight per workgroup)
+                      (1, 4000, 4112), (1, 16400, 272), (2, 16640, 528),   # the last two: more than 1024 pairs (eight per workgroup)
+                      (1, 16400, 8208)]                                     # ... and 32 K steps and more (extra steps up front)
 
 # prefill at full size, (M, N, K, tensor index of the seed): the four 13B-class projections at 2048 and at 512 tokens
 FULL_SIZE_GEMM = [(2048, 15360, 5120, 0), (2048, 5120, 5120, 1), (2048, 27648, 5120, 2), (2048, 5120, 13824, 3),
