@@ -268,6 +268,8 @@ bitnet_status bitnet_linear_variant(const int8_t* xq, const float* sx, const voi
  *     batched_decode_loader  depth, LDS lookahead (the second form has a wave that only copies activations)
  *     prefill                tile tokens, tile rows; grid y = split-K factor
  *     reference, trit5_decode, trit5_reference: no parameters
+ *   5-trit weights, more than 16 tokens and a workspace that holds the 2-bit copy (bitnet_linear_workspace_format):
+ *   the plan of the 2-bit launch that follows the repacking pass, with " repack=trit5_to_2bit" appended
  */
 bitnet_status bitnet_linear_describe(int64_t M, int64_t N, int64_t K, bitnet_format f, size_t workspace_bytes,
                                      char* text, size_t text_bytes);

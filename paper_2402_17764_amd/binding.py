@@ -282,12 +282,13 @@ def _parse_plan(text):
     f = dict(kv.split("=", 1) for kv in text.split())
     gx, gy = f["grid"].split("x")
     return {"kernel": f["kernel"], "params": [int(v) for v in f["params"].split(",") if v], "grid": (int(gx), int(gy)),
-            "block": int(f["block"]), "lds": int(f["lds"]), "splits": int(f["splits"])}
+            "block": int(f["block"]), "lds": int(f["lds"]), "splits": int(f["splits"]), "repack": f.get("repack")}
 
 
 def linear_describe(M, N, K, fmt=PACK_2BIT, workspace_bytes=0):
     """The kernel family and launch shape linear (or linear_ws with a workspace of that size) takes for a shape; host
-    only, no device needed -> dict(kernel=str, params=[int], grid=(x, y), block=int, lds=int, splits=int)."""
+    only, no device needed -> dict(kernel=str, params=[int], grid=(x, y), block=int, lds=int, splits=int, repack=str or
+    None: "trit5_to_2bit" where linear_ws first repacks 5-trit weights into the workspace)."""
     lib = load()
     buf = ctypes.create_string_buffer(256)
     _check(lib.bitnet_linear_describe(M, N, K, fmt, workspace_bytes, buf, len(buf)), "bitnet_linear_describe")

@@ -6,6 +6,7 @@
 #include "bitnet_internal.hpp"
 
 #include <stdio.h>
+#include <string.h>
 
 namespace {
 
@@ -341,6 +342,14 @@ bitnet_status bitnet_linear_describe(int64_t M, int64_t N, int64_t K, bitnet_for
     void* vp = reinterpret_cast<void*>(uintptr_t{256});
     void* ws = workspace_bytes ? vp : nullptr;
     bitnet::LaunchPlan plan;
+    if (f == BITNET_PACK_TRIT5 && M > 16 && K % 16 == 0 && workspace_bytes >= repacked_bytes(N, K)) {
+        // bitnet_linear_ws repacks to 2 bits at the head of the workspace and runs the 2-bit path on the rest
+        const bitnet_status st = bitnet_linear_describe(M, N, K, BITNET_PACK_2BIT, workspace_bytes - repacked_bytes(N, K), text, text_bytes);
+        if (st != BITNET_OK) return st;
+        const size_t at = strlen(text);
+        const int n = snprintf(text + at, text_bytes - at, " repack=trit5_to_2bit");
+        return (n < 0 || (size_t)n >= text_bytes - at) ? BITNET_ERR_WORKSPACE : BITNET_OK;
+    }
     if (f == BITNET_PACK_TRIT5) {
         plan.kernel = bitnet::gemv_trit5_supports(M < 16 ? M : 16, N, K, xq) ? "trit5_decode" : "trit5_reference";
     } else if (bitnet::gemv_supports(M, N, K, xq)) {

@@ -115,16 +115,14 @@ __global__ __launch_bounds__(kSumThreads) void abs_sum_partials(const T* __restr
 // pass 2
 // ---------------------------------------------------------------------------------------------------
 constexpr int kFinishThreads = 256;
-// gamma[0 .. nout-1] all receive the value (nout > 1: one copy per 16-row block of a segment)
-__global__ __launch_bounds__(kFinishThreads) void finish_gamma(const double* __restrict__ partials, int nparts,
-                                                            int64_t count, float* __restrict__ gamma, int64_t nout) {
+// The partial sums of pass 1 added up over one workgroup in a fixed tree: thread t folds partials t, t + 256, ...,
+// then the 256 running pairs are halved eight times.  Returned unnormalised to every thread.
+__device__ inline dd fold_partials(const double* __restrict__ partials, int nparts, double* sh_hi, double* sh_lo) {
     dd acc{0.0, 0.0};
     for (int i = threadIdx.x; i < nparts; i += kFinishThreads) {
         dd p{partials[2 * i], partials[2 * i + 1]};
         dd_add_dd(acc, p);
     }
-    __shared__ double sh_hi[kFinishThreads];
-    __shared__ double sh_lo[kFinishThreads];
     sh_hi[threadIdx.x] = acc.hi;
     sh_lo[threadIdx.x] = acc.lo;
     __syncthreads();
@@ -138,7 +136,16 @@ __global__ __launch_bounds__(kFinishThreads) void finish_gamma(const double* __r
         }
         __syncthreads();
     }
-    const double S = sh_hi[0] + sh_lo[0];
+    return dd{sh_hi[0], sh_lo[0]};
+}
+
+// gamma[0 .. nout-1] all receive the value (nout > 1: one copy per 16-row block of a segment)
+__global__ __launch_bounds__(kFinishThreads) void finish_gamma(const double* __restrict__ partials, int nparts,
+                                                            int64_t count, float* __restrict__ gamma, int64_t nout) {
+    __shared__ double sh_hi[kFinishThreads];
+    __shared__ double sh_lo[kFinishThreads];
+    const dd t = fold_partials(partials, nparts, sh_hi, sh_lo);
+    const double S = t.hi + t.lo;
     const float g = (float)(S / (double)count);     // Eq. (3); fp64 IEEE division, one rounding to fp32
     for (int64_t i = threadIdx.x; i < nout; i += kFinishThreads) gamma[i] = g;
 }
@@ -147,30 +154,13 @@ __global__ __launch_bounds__(kFinishThreads) void finish_gamma(const double* __r
 // matrix contributes to Eq. (3).  Same fixed tree as finish_gamma.
 __global__ __launch_bounds__(kFinishThreads) void fold_abs_sum(const double* __restrict__ partials, int nparts,
                                                             double* __restrict__ sum) {
-    dd acc{0.0, 0.0};
-    for (int i = threadIdx.x; i < nparts; i += kFinishThreads) {
-        dd p{partials[2 * i], partials[2 * i + 1]};
-        dd_add_dd(acc, p);
-    }
     __shared__ double sh_hi[kFinishThreads];
     __shared__ double sh_lo[kFinishThreads];
-    sh_hi[threadIdx.x] = acc.hi;
-    sh_lo[threadIdx.x] = acc.lo;
-    __syncthreads();
-    for (int s = kFinishThreads / 2; s > 0; s >>= 1) {
-        if ((int)threadIdx.x < s) {
-            dd a{sh_hi[threadIdx.x], sh_lo[threadIdx.x]};
-            dd b{sh_hi[threadIdx.x + s], sh_lo[threadIdx.x + s]};
-            dd_add_dd(a, b);
-            sh_hi[threadIdx.x] = a.hi;
-            sh_lo[threadIdx.x] = a.lo;
-        }
-        __syncthreads();
-    }
+    const dd t = fold_partials(partials, nparts, sh_hi, sh_lo);
     if (threadIdx.x == 0) {
-        const double hi = sh_hi[0] + sh_lo[0];
+        const double hi = t.hi + t.lo;
         sum[0] = hi;
-        sum[1] = sh_lo[0] - (hi - sh_hi[0]);              // exact: |lo| <= |hi|
+        sum[1] = t.lo - (hi - t.hi);                      // exact: |lo| <= |hi|
     }
 }
 
@@ -305,23 +295,6 @@ static int abs_sum_blocks(int64_t count) {
     return (int)(want < 1 ? 1 : (want > kSumBlocks ? kSumBlocks : want));
 }
 
-// Eq. (3) as passes 1 and 2 (the 5-trit packing reads gamma from memory; the 2-bit packing folds pass 2 into pass 3)
-hipError_t launch_absmean_gamma(const void* W, bool bf16, int64_t N, int64_t K, float* gamma, void* workspace,
-                                hipStream_t stream, int64_t nout) {
-    const int64_t count = N * K;
-    double* partials = static_cast<double*>(workspace);
-    const int blocks = abs_sum_blocks(count);
-    const int vec_ok = (reinterpret_cast<uintptr_t>(W) % 16) == 0;
-    if (bf16)
-        hipLaunchKernelGGL(abs_sum_partials<uint16_t>, dim3(blocks), dim3(kSumThreads), 0, stream,
-                           static_cast<const uint16_t*>(W), count, vec_ok, abs_sum_stream_vecs(count, 2), partials);
-    else
-        hipLaunchKernelGGL(abs_sum_partials<float>, dim3(blocks), dim3(kSumThreads), 0, stream,
-                           static_cast<const float*>(W), count, vec_ok, abs_sum_stream_vecs(count, 4), partials);
-    hipLaunchKernelGGL(finish_gamma, dim3(1), dim3(kFinishThreads), 0, stream, partials, blocks, count, gamma, nout);
-    return hipGetLastError();
-}
-
 static void launch_abs_sum_partials(const void* W, bool bf16, int64_t count, double* partials, int blocks, hipStream_t stream) {
     const int vec_ok = (reinterpret_cast<uintptr_t>(W) % 16) == 0;
     if (bf16)
@@ -330,6 +303,17 @@ static void launch_abs_sum_partials(const void* W, bool bf16, int64_t count, dou
     else
         hipLaunchKernelGGL(abs_sum_partials<float>, dim3(blocks), dim3(kSumThreads), 0, stream,
                            static_cast<const float*>(W), count, vec_ok, abs_sum_stream_vecs(count, 4), partials);
+}
+
+// Eq. (3) as passes 1 and 2 (the 5-trit packing reads gamma from memory; the 2-bit packing folds pass 2 into pass 3)
+hipError_t launch_absmean_gamma(const void* W, bool bf16, int64_t N, int64_t K, float* gamma, void* workspace,
+                                hipStream_t stream, int64_t nout) {
+    const int64_t count = N * K;
+    double* partials = static_cast<double*>(workspace);
+    const int blocks = abs_sum_blocks(count);
+    launch_abs_sum_partials(W, bf16, count, partials, blocks, stream);
+    hipLaunchKernelGGL(finish_gamma, dim3(1), dim3(kFinishThreads), 0, stream, partials, blocks, count, gamma, nout);
+    return hipGetLastError();
 }
 
 hipError_t launch_abs_sum(const void* W, bool bf16, int64_t N, int64_t K, double* sum, void* workspace, hipStream_t stream) {
@@ -377,8 +361,8 @@ hipError_t launch_quantize_weights_2bit(const void* W, bool bf16, int64_t N, int
     double* partials = static_cast<double*>(workspace);
     const int blocks = abs_sum_blocks(count);
     const size_t esz = bf16 ? 2 : 4;
-    const int sum_vec_ok = (reinterpret_cast<uintptr_t>(W) % 16) == 0;
     const bool vec = (reinterpret_cast<uintptr_t>(W) % (4 * esz)) == 0 && (K % 4 == 0);
+    launch_abs_sum_partials(W, bf16, count, partials, blocks, stream);
 
     const int64_t Kq = ceil_div(K, kColsPerQuad);
     const int64_t RB = ceil_div(N, kRowsPerBlock);                       // row blocks packed by this call
@@ -390,11 +374,9 @@ hipError_t launch_quantize_weights_2bit(const void* W, bool bf16, int64_t N, int
                                         partials, blocks, count, gamma, nout, out)
     if (bf16) {
         const uint16_t* w = static_cast<const uint16_t*>(W);
-        hipLaunchKernelGGL(abs_sum_partials<uint16_t>, dim3(blocks), dim3(kSumThreads), 0, stream, w, count, sum_vec_ok, abs_sum_stream_vecs(count, 2), partials);
         if (vec) PACK(uint16_t, true); else PACK(uint16_t, false);
     } else {
         const float* w = static_cast<const float*>(W);
-        hipLaunchKernelGGL(abs_sum_partials<float>, dim3(blocks), dim3(kSumThreads), 0, stream, w, count, sum_vec_ok, abs_sum_stream_vecs(count, 4), partials);
         if (vec) PACK(float, true); else PACK(float, false);
     }
 #undef PACK

@@ -151,6 +151,14 @@ def test_fallbacks_and_errors():
     assert B.linear_describe(100, 64, 72)["kernel"] == "reference"
     assert B.linear_describe(1, 17280, 3200, fmt=B.PACK_TRIT5)["kernel"] == "trit5_decode"
     assert B.linear_describe(100, 17280, 3200, fmt=B.PACK_TRIT5)["kernel"] == "trit5_decode"   # 16 tokens at a time
+    # 5-trit weights with a workspace that holds the 2-bit copy: the repacking pass, then the 2-bit plan for the rest
+    need = B.linear_workspace(2048, 27648, 5120, B.PACK_TRIT5)
+    assert need >= 27648 * 5120 // 4
+    d = B.linear_describe(2048, 27648, 5120, fmt=B.PACK_TRIT5, workspace_bytes=need)
+    assert d["repack"] == "trit5_to_2bit" and d["kernel"] == "prefill" and d["params"] == [128, 256]
+    assert B.linear_describe(2048, 27648, 5120, fmt=B.PACK_TRIT5, workspace_bytes=need - 257)["repack"] is None
+    assert B.linear_describe(16, 27648, 5120, fmt=B.PACK_TRIT5, workspace_bytes=need)["kernel"] == "trit5_decode"
+    assert B.linear_describe(2048, 27648, 5120)["repack"] is None
     lib = B.load()
     buf = ctypes.create_string_buffer(128)
     assert lib.bitnet_linear_describe(1, 4096, 4096, 0, 0, None, 128) == 1
