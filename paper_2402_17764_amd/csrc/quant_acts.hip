@@ -19,6 +19,7 @@ __device__ inline int quantize_one(float v, float inv) { return (int)(int8_t)(qu
 template <int kWaves = kActWaves>
 __device__ inline float block_max_nonneg(float v, float* sh) {
     v = wave_max_nonneg(v);
+    if (kWaves == 1) return v;
     const int wave = threadIdx.x >> 6;
     if ((threadIdx.x & 63) == 0) sh[wave] = v;
     __syncthreads();
@@ -135,91 +136,101 @@ __device__ inline float load_elem(const void* row, int64_t k) {
 
 __device__ inline uint32_t pack4(const float (&v)[4], float inv) { return pack4_quantized(v[0], v[1], v[2], v[3], inv); }
 
+// one 16-byte piece of a row widened to fp32: eight bf16 or four fp32 elements
+template <bool kBf16>
+__device__ inline void expand_vec(const uint4& q, float (&f)[kBf16 ? 8 : 4]) {
+    const uint32_t u[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (kBf16) {
+            f[2 * e] = __uint_as_float(u[e] << 16);
+            f[2 * e + 1] = __uint_as_float(u[e] & 0xFFFF0000u);
+        } else {
+            f[e] = __uint_as_float(u[e]);
+        }
+    }
+}
+
 // RMSNorm -> absmax int8.  Per token: ms = mean of squares (exact: squares of fp32 values are exact in
 // fp64 and the sum is carried in double-double), r = (float)(1 / sqrt(ms + eps)) in fp64, z = (x * r) * g
-// in fp32, then the per-token quantization of z.  kChunks > 0: the token stays in registers between the passes,
-// kChunks chunks of four elements per thread (the launcher picks the smallest count that covers K); 0: three sweeps
-// over memory, any K.  The gain is requested together with the token where it costs few registers (up to eight
-// chunks: its latency would otherwise sit in the token's dependent chain) and loaded where
-// it is used otherwise.
-template <bool kBf16, int kChunks, int kThreads>
-__global__ __launch_bounds__(kThreads) void rmsnorm_quantize_kernel(
+// in fp32, then the per-token quantization of z.
+//
+// Register-resident form: the token is read once, kVecs 16-byte loads per thread (the launcher picks the smallest
+// count that covers K), and stays in registers *as loaded* -- bf16 pairs are widened where they are used -- so that a
+// workgroup needs few registers and a CU holds many tokens at different stages: the kernel does more arithmetic than
+// memory traffic (nine fp64 operations per element for the exact sum), and only tokens in other phases can hide one
+// token's loads and reductions.  z is kept in registers between the absmax and the rounding where that takes at most
+// 32 of them and recomputed with the same two multiplications otherwise.
+template <bool kBf16, int kVecs, int kThreads>
+__global__ __launch_bounds__(kThreads) void rmsnorm_quantize_vec(
         const void* __restrict__ xv, const float* __restrict__ g, float eps, int64_t K, int8_t* __restrict__ xq,
         float* __restrict__ sx) {
+    constexpr int kElems = kBf16 ? 8 : 4;
     constexpr int kWaves = kThreads / kWave;
-    constexpr bool kVec = kChunks > 0, kHoldGain = kChunks > 0 && kChunks <= 8;
+    constexpr bool kKeepZ = kVecs * kElems <= 32;
     __shared__ double sh_hi[kWaves], sh_lo[kWaves];
     __shared__ float sh[kWaves];
     const int64_t m = blockIdx.x;
-    const void* row = static_cast<const char*>(xv) + m * K * (kBf16 ? 2 : 4);
-    int8_t* out = xq + m * K;
-    const int nchunks = (int)(K / 4);
-    float v[kVec ? kChunks : 1][4], gv[kHoldGain ? kChunks : 1][4];
+    const int nvec = (int)(K / kElems);
+    const uint4* row = reinterpret_cast<const uint4*>(static_cast<const char*>(xv) + m * K * (kBf16 ? 2 : 4));
+    const float4* g4 = reinterpret_cast<const float4*>(g);
+    uint4 raw[kVecs];
+#pragma unroll
+    for (int v = 0; v < kVecs; ++v) {
+        const int idx = v * kThreads + threadIdx.x;
+        raw[v] = make_uint4(0, 0, 0, 0);
+        if (idx < nvec) raw[v] = row[idx];
+    }
 
     // four interleaved double-double accumulators: the sums are exact, so splitting them changes nothing
-    // but the length of the dependent chain
-    dd acc{0.0, 0.0}, acc2{0.0, 0.0}, acc3{0.0, 0.0}, acc4{0.0, 0.0};
-    if (kVec) {
+    // but the length of the dependent chain (vectors past the row hold zeros and are skipped whole)
+    dd acc[4] = {{0.0, 0.0}, {0.0, 0.0}, {0.0, 0.0}, {0.0, 0.0}};
 #pragma unroll
-        for (int i = 0; i < kChunks; ++i) {
-            if (i * kThreads >= nchunks) continue;              // uniform: whole iterations past the row
-            const int c = i * kThreads + threadIdx.x;
+    for (int v = 0; v < kVecs; ++v) {
+        if (v * kThreads >= nvec) continue;                     // uniform
+        float f[kElems];
+        expand_vec<kBf16>(raw[v], f);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[i][e] = 0.0f;
-            if (c < nchunks) {
-                load_chunk<kBf16>(row, 4 * (int64_t)c, v[i]);
-                if (kHoldGain && g) {                              // requested now, needed after the reduction
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) gv[i][e] = g[4 * c + e];
-                }
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < kChunks; ++i) {
-            if (i * kThreads >= nchunks) continue;
-            dd_add_double(acc, (double)v[i][0] * (double)v[i][0]);
-            dd_add_double(acc2, (double)v[i][1] * (double)v[i][1]);
-            dd_add_double(acc3, (double)v[i][2] * (double)v[i][2]);
-            dd_add_double(acc4, (double)v[i][3] * (double)v[i][3]);
-        }
-        dd_add_dd(acc, acc2);
-        dd_add_dd(acc3, acc4);
-        dd_add_dd(acc, acc3);
-    } else {
-        for (int64_t k = threadIdx.x; k < K; k += kThreads) {
-            const double a = (double)load_elem<kBf16>(row, k);
-            dd_add_double(acc, a * a);
-        }
+        for (int e = 0; e < kElems; ++e) dd_add_double(acc[e & 3], (double)f[e] * (double)f[e]);
     }
-    const double ms = block_sum_dd<kWaves>(acc, sh_hi, sh_lo) / (double)K;
+    dd_add_dd(acc[0], acc[1]);
+    dd_add_dd(acc[2], acc[3]);
+    dd_add_dd(acc[0], acc[2]);
+    const double ms = block_sum_dd<kWaves>(acc[0], sh_hi, sh_lo) / (double)K;
     const float r = (float)(1.0 / sqrt(ms + (double)eps));
 
-    float amax = 0.0f;
-    if (kVec) {
+    // z = (x * r) * g of one vector; the gain comes from the caches (every token reads the same K floats)
+    auto scaled = [&](int v, int idx, float (&z)[kElems]) {
+        expand_vec<kBf16>(raw[v], z);
+        float gl[kElems];
+        if (g) {
 #pragma unroll
-        for (int i = 0; i < kChunks; ++i) {
-            if (i * kThreads >= nchunks) continue;              // uniform: whole iterations past the row
-            const int c = i * kThreads + threadIdx.x;
-            if (c < nchunks) {
-                float gl[4] = {1.0f, 1.0f, 1.0f, 1.0f};
-                if (g) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) gl[e] = kHoldGain ? gv[i][e] : g[4 * c + e];
-                }
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    float z = v[i][e] * r;
-                    if (g) z = z * gl[e];
-                    v[i][e] = z;
-                    amax = fmaxf(amax, fabsf(z));
-                }
+            for (int q = 0; q < kElems / 4; ++q) {
+                const float4 t = g4[idx * (kElems / 4) + q];
+                gl[4 * q] = t.x; gl[4 * q + 1] = t.y; gl[4 * q + 2] = t.z; gl[4 * q + 3] = t.w;
             }
         }
-    } else {
-        for (int64_t k = threadIdx.x; k < K; k += kThreads) {
-            float z = load_elem<kBf16>(row, k) * r;
-            if (g) z = z * g[k];
-            amax = fmaxf(amax, fabsf(z));
+#pragma unroll
+        for (int e = 0; e < kElems; ++e) {
+            z[e] = z[e] * r;
+            if (g) z[e] = z[e] * gl[e];
+        }
+    };
+
+    float zk[kKeepZ ? kVecs : 1][kElems];
+    float amax = 0.0f;
+#pragma unroll
+    for (int v = 0; v < kVecs; ++v) {
+        const int idx = v * kThreads + threadIdx.x;
+        if (v * kThreads >= nvec) continue;                     // uniform
+        if (idx < nvec) {
+            float z[kElems];
+            scaled(v, idx, z);
+#pragma unroll
+            for (int e = 0; e < kElems; ++e) {
+                amax = fmaxf(amax, fabsf(z[e]));
+                if (kKeepZ) zk[v][e] = z[e];
+            }
         }
     }
     amax = block_max_nonneg<kWaves>(amax, sh);
@@ -227,19 +238,60 @@ __global__ __launch_bounds__(kThreads) void rmsnorm_quantize_kernel(
     const float inv = kQb / s;
     if (threadIdx.x == 0) sx[m] = s;
 
-    if (kVec) {
+    int8_t* out = xq + m * K;
 #pragma unroll
-        for (int i = 0; i < kChunks; ++i) {
-            if (i * kThreads >= nchunks) continue;              // uniform: whole iterations past the row
-            const int c = i * kThreads + threadIdx.x;
-            if (c < nchunks) reinterpret_cast<uint32_t*>(out)[c] = pack4(v[i], inv);
+    for (int v = 0; v < kVecs; ++v) {
+        const int idx = v * kThreads + threadIdx.x;
+        if (v * kThreads >= nvec) continue;                     // uniform
+        if (idx >= nvec) continue;
+        float z[kElems];
+        if (kKeepZ) {
+#pragma unroll
+            for (int e = 0; e < kElems; ++e) z[e] = zk[v][e];
+        } else {
+            scaled(v, idx, z);                                  // the same two multiplications: the same z
         }
-    } else {
-        for (int64_t k = threadIdx.x; k < K; k += kThreads) {
-            float z = load_elem<kBf16>(row, k) * r;                // the same two multiplies: the same z
-            if (g) z = z * g[k];
-            out[k] = (int8_t)quantize_one(z, inv);
+        if (kBf16) {
+            reinterpret_cast<uint2*>(out)[idx] = make_uint2(pack4_quantized(z[0], z[1], z[2], z[3], inv),
+                                                            pack4_quantized(z[4], z[5], z[6], z[7], inv));
+        } else {
+            reinterpret_cast<uint32_t*>(out)[idx] = pack4_quantized(z[0], z[1], z[2], z[3], inv);
         }
+    }
+}
+
+// Any K and any alignment: three sweeps over the token in memory, element loads.
+template <bool kBf16, int kThreads>
+__global__ __launch_bounds__(kThreads) void rmsnorm_quantize_any(
+        const void* __restrict__ xv, const float* __restrict__ g, float eps, int64_t K, int8_t* __restrict__ xq,
+        float* __restrict__ sx) {
+    constexpr int kWaves = kThreads / kWave;
+    __shared__ double sh_hi[kWaves], sh_lo[kWaves];
+    __shared__ float sh[kWaves];
+    const int64_t m = blockIdx.x;
+    const void* row = static_cast<const char*>(xv) + m * K * (kBf16 ? 2 : 4);
+    int8_t* out = xq + m * K;
+    dd acc{0.0, 0.0};
+    for (int64_t k = threadIdx.x; k < K; k += kThreads) {
+        const double a = (double)load_elem<kBf16>(row, k);
+        dd_add_double(acc, a * a);
+    }
+    const double ms = block_sum_dd<kWaves>(acc, sh_hi, sh_lo) / (double)K;
+    const float r = (float)(1.0 / sqrt(ms + (double)eps));
+    float amax = 0.0f;
+    for (int64_t k = threadIdx.x; k < K; k += kThreads) {
+        float z = load_elem<kBf16>(row, k) * r;
+        if (g) z = z * g[k];
+        amax = fmaxf(amax, fabsf(z));
+    }
+    amax = block_max_nonneg<kWaves>(amax, sh);
+    const float s = fmaxf(amax, kEps);
+    const float inv = kQb / s;
+    if (threadIdx.x == 0) sx[m] = s;
+    for (int64_t k = threadIdx.x; k < K; k += kThreads) {
+        float z = load_elem<kBf16>(row, k) * r;                    // the same two multiplies: the same z
+        if (g) z = z * g[k];
+        out[k] = (int8_t)quantize_one(z, inv);
     }
 }
 
@@ -330,12 +382,38 @@ static void producer_shape(bool vec, int64_t M, int64_t cols, int* threads, int*
 
 hipError_t launch_rmsnorm_quantize(const void* x, bool bf16, const float* g, float eps, int64_t M, int64_t K,
                                    int8_t* xq, float* sx, hipStream_t stream) {
-    int threads, chunks;
-    producer_shape(producer_vec_ok(x, bf16 ? 2 : 4, K, xq), M, K, &threads, &chunks);
+    const int elems = bf16 ? 8 : 4;
+    const int max_vecs = bf16 ? 8 : 16;                            // 64 token elements per thread at most
+    const bool aligned = K % elems == 0 && reinterpret_cast<uintptr_t>(x) % 16 == 0 &&
+                         reinterpret_cast<uintptr_t>(xq) % (bf16 ? 8 : 4) == 0 && reinterpret_cast<uintptr_t>(g) % 16 == 0;
+    const int64_t nvec = K / elems;
+    // few tokens: 1024 threads each, so that the dependent chains of the exact sum interleave over four waves per
+    // SIMD; many tokens: 256, and the tokens fill the CUs (one or two waves per token were measured too: slower at
+    // every size from 64 to 4096 tokens); rows that would need more than eight loads per thread at 256 threads
+    // take 1024 at any count (sixteen loads cost occupancy: fp32 rows of 13824 run 5-15 % faster on 1024 threads)
+    const int threads = (M < kProdFewTokens || nvec > (int64_t)8 * 256) ? 1024 : 256;
+    const int64_t need = ceil_div(nvec, threads);
     dim3 grid((unsigned)M), block(threads);
-#define GO(B_, C_, T_) hipLaunchKernelGGL((rmsnorm_quantize_kernel<B_, C_, T_>), grid, block, 0, stream, x, g, eps, K, xq, sx)
-    if (bf16) PRODUCER_PICK(true); else PRODUCER_PICK(false);
+#define GO(B_, V_, T_) hipLaunchKernelGGL((rmsnorm_quantize_vec<B_, V_, T_>), grid, block, 0, stream, x, g, eps, K, xq, sx)
+#define PICK(B_, T_)                                                                                             \
+    do {                                                                                                         \
+        if (need <= 1) GO(B_, 1, T_); else if (need <= 2) GO(B_, 2, T_); else if (need <= 4) GO(B_, 4, T_);      \
+        else if (need <= 8) GO(B_, 8, T_); else if (!B_ && T_ == 1024) GO(false, 16, 1024);                      \
+    } while (0)
+    if (aligned && need <= max_vecs) {
+        if (bf16) { if (threads == 1024) PICK(true, 1024); else PICK(true, 256); }
+        else      { if (threads == 1024) PICK(false, 1024); else PICK(false, 256); }
+    } else {
+        if (bf16) {
+            if (threads >= 1024) hipLaunchKernelGGL((rmsnorm_quantize_any<true, 1024>), grid, block, 0, stream, x, g, eps, K, xq, sx);
+            else                 hipLaunchKernelGGL((rmsnorm_quantize_any<true, 256>), grid, block, 0, stream, x, g, eps, K, xq, sx);
+        } else {
+            if (threads >= 1024) hipLaunchKernelGGL((rmsnorm_quantize_any<false, 1024>), grid, block, 0, stream, x, g, eps, K, xq, sx);
+            else                 hipLaunchKernelGGL((rmsnorm_quantize_any<false, 256>), grid, block, 0, stream, x, g, eps, K, xq, sx);
+        }
+    }
 #undef GO
+#undef PICK
     return hipGetLastError();
 }
 

@@ -779,10 +779,12 @@ def test_random_shapes_every_kernel_agrees(gpu_lib):
 # ------------------------------------------------------------------------------------------------
 # producers of int8 activations: RMSNorm -> int8, SwiGLU -> int8 (bit-exact codes and scales)
 # ------------------------------------------------------------------------------------------------
-# register-resident forms (4, 8, 16 chunks per thread at 256 and at 1024 threads) and the sweeping form (K % 4, K >
+# register-resident forms (1, 2, 4, 8 loads of 16 bytes per thread at 256 and at 1024 threads, 16 for fp32 at 1024:
+# every instantiation of either input type is reached) and the sweeping form (K not a multiple of the load, K >
 # 65536), one token and many, with and without gain
 PRODUCER_SHAPES = [(1, 3200), (16, 1536), (5, 4), (3, 1), (7, 1003), (2, 16384), (2, 16388), (1, 28672), (33, 8640),
-                   (300, 520), (70, 4096), (65, 6656), (64, 13824), (70, 20000), (3, 40000), (2, 70000)]
+                   (300, 520), (70, 4096), (65, 6656), (64, 13824), (70, 20000), (3, 40000), (2, 70000), (80, 2048),
+                   (4, 8192)]
 
 
 @pytest.mark.parametrize("M,K", PRODUCER_SHAPES)
