@@ -116,6 +116,10 @@ typedef enum bitnet_kernel {
     BITNET_KERNEL_GEMM_128x128 = 0x141,
     BITNET_KERNEL_GEMM_96x128 = 0x131,
     BITNET_KERNEL_GEMM_64x128 = 0x121,
+    /* the same tiles contracted by eight waves in two K groups (each group half of the K steps, integer accumulators
+       added through LDS: same result): the form for grids that leave a CU with one workgroup */
+    BITNET_KERNEL_GEMM_96x128_K2 = 0x1B1,
+    BITNET_KERNEL_GEMM_64x256_K2 = 0x1A2,
     /* bitnet_linear_ws only: the K steps split over 2, 4 or 8 workgroups per tile (prefill kernel; where the batched-decode kernels serve the shape,
        the batched-decode kernels) */
     BITNET_KERNEL_GEMM_SPLITK_2 = 0x202,
@@ -266,7 +270,8 @@ bitnet_status bitnet_linear_variant(const int8_t* xq, const float* sx, const voi
  *     decode                 M <= 4: row blocks per wave, K waves, row slots, prefetch depth, x_q source (0 global, 1 LDS)
  *     batched_decode         5 ... 512 tokens: token tiles of 16, row blocks per wave, row slots, K groups, prefetch
  *     batched_decode_loader  depth, LDS lookahead (the second form has a wave that only copies activations)
- *     prefill                tile tokens, tile rows; grid y = split-K factor
+ *     prefill                tile tokens, tile rows, and 2 as a third parameter for the eight-wave form with two
+ *                            K groups; grid y = split-K factor
  *     reference, trit5_decode, trit5_reference: no parameters
  *   5-trit weights, more than 16 tokens and a workspace that holds the 2-bit copy (bitnet_linear_workspace_format):
  *   the plan of the 2-bit launch that follows the repacking pass, with " repack=trit5_to_2bit" appended

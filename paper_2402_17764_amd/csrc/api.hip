@@ -205,10 +205,11 @@ static bitnet_status linear_any(const int8_t* xq, const float* sx, const void* p
         else if (bitnet::gemm_supports(M, N, K, xq)) which = BITNET_KERNEL_GEMM;
         else which = BITNET_KERNEL_REFERENCE;
     }
-    if (((int)which & ~0xFF) == 0x100) {               // prefill kernel, tile forced: 0x100 | fm << 4 | fn
-        const int fm = ((int)which >> 4) & 0xF, fn = (int)which & 0xF;
+    if (((int)which & ~0xFF) == 0x100) {               // prefill kernel, tile forced: 0x100 | two K groups << 7 | fm << 4 | fn
+        const int fm = ((int)which >> 4) & 0x7, fn = (int)which & 0xF, kg = 1 + (((int)which >> 7) & 1);
         if (fm < 2 || fm > 4 || fn < 1 || fn > 2 || !bitnet::gemm_supports(M, N, K, xq)) return BITNET_ERR_KERNEL;
-        return from_hip(bitnet::launch_linear_gemm_2bit_shape(fm, fn, xq, sx, packed, gamma, gstride, M, N, K, y, yt, s));
+        if (kg == 2 && !((fm == 3 && fn == 1) || (fm == 2 && fn == 2))) return BITNET_ERR_KERNEL;
+        return from_hip(bitnet::launch_linear_gemm_2bit_shape(fm, fn, kg, xq, sx, packed, gamma, gstride, M, N, K, y, yt, s));
     }
     switch (which) {
         case BITNET_KERNEL_REFERENCE:

@@ -20,6 +20,10 @@
 //   * inside a K step the eight 32-column slices are software pipelined: the LDS reads and the decode
 //     of slice t + 1 are issued among the 16 MFMAs of slice t;
 //   * one barrier per K step of 256 columns (64 MFMAs per wave between barriers);
+//   * for grids that leave a CU with a single workgroup (a few hundred tokens on a layer with few rows), a form with
+//     eight waves: two groups of four, each contracting half of the K steps through activation stages of its own, the
+//     second group's accumulators added through LDS at the end -- the two waves per SIMD that two workgroups per CU
+//     provide elsewhere, without a second launch;
 //   * the epilogue rescales in registers, transposes each 32 x 64 fragment row through LDS and writes
 //     whole 16-byte pieces of output rows;
 //   * tile order: consecutive workgroups take consecutive token tiles of the same weight tile, so the
@@ -49,10 +53,13 @@ constexpr int kGemmPitch16 = 64 * 2 + 32;      // same for bf16 outputs
 constexpr int gemm_stage_bytes(int fm) { return fm * 32 * 256; }            // one K step of activations
 // float scale[32 * fm] sits behind the two stages and behind the epilogue's staging area (four waves x 32 rows),
 // which reuses the stages while the scales are still read
-constexpr int gemm_scale_offset(int fm) {
-    return 2 * gemm_stage_bytes(fm) > 4 * 32 * kGemmPitch32 ? 2 * gemm_stage_bytes(fm) : 4 * 32 * kGemmPitch32;
+// ... and behind the area through which a second K group (kg == 2) hands over its accumulators: fm * fn * 16 registers
+// of 256 threads
+constexpr int gemm_max3(int a, int b, int c) { return a > b ? (a > c ? a : c) : (b > c ? b : c); }
+constexpr int gemm_scale_offset(int fm, int fn, int kg) {
+    return gemm_max3(kg * 2 * gemm_stage_bytes(fm), 4 * 32 * kGemmPitch32, (kg - 1) * fm * fn * 16 * 4 * kGemmThreads);
 }
-constexpr int gemm_lds_bytes(int fm) { return gemm_scale_offset(fm) + fm * 32 * 4; }
+constexpr int gemm_lds_bytes(int fm, int fn, int kg) { return gemm_scale_offset(fm, fn, kg) + fm * 32 * 4; }
 
 __device__ inline uint32_t gemm_quad_word(const uint4& q, int j) { return j == 0 ? q.x : j == 1 ? q.y : j == 2 ? q.z : q.w; }
 
@@ -162,8 +169,8 @@ __device__ inline void gemm_epilogue(v16i (&acc)[kFM][kFN], const GemmOutCtx& c)
     }
 }
 
-// One output tile of 32 * kFM tokens (first token row0) x 128 * kFN weight rows (tile bn).
-template <int kFM, int kFN>
+// One output tile of 32 * kFM tokens (first token row0) x 128 * kFN weight rows (tile bn), by kKG groups of four waves.
+template <int kFM, int kFN, int kKG>
 __device__ __forceinline__ void gemm_tile(
         const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
         const float* __restrict__ gamma, int gstride, int M, int64_t N, int64_t K, int Kq, int RB, int row0, int bn,
@@ -175,11 +182,14 @@ __device__ __forceinline__ void gemm_tile(
     constexpr int kGemmStageBytes = gemm_stage_bytes(kFM);
     constexpr int kCopies = 2 * kFM;                // 1 KiB wave-loads (4 token rows) per wave and stage
     char* lds = reinterpret_cast<char*>(smem);
-    float* scale_lds = reinterpret_cast<float*>(lds + gemm_scale_offset(kFM));
+    float* scale_lds = reinterpret_cast<float*>(lds + gemm_scale_offset(kFM, kFN, kKG));
 
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);    // scalar: LDS-DMA targets need no per-step broadcast
+    const int wave_all = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: LDS-DMA targets need no per-step broadcast
+    const int grp = kKG > 1 ? wave_all >> 2 : 0;        // K group: four waves that contract their own run of K steps
+    const int wave = wave_all & 3;                      // the wave's place in its group
     const int wn = wave;
+    char* glds = lds + grp * 2 * kGemmStageBytes;       // the group's two activation stages
     const int steps = (Kq + 3) >> 2;
     const int full_steps = (int)(K >> 8);           // steps whose 256 columns all exist
     const int tail_quads = 16 * (Kq - 4 * (steps - 1));
@@ -233,7 +243,7 @@ __device__ __forceinline__ void gemm_tile(
         const int64_t left = xbytes - (int64_t)step * 256;
         const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<int8_t*>(xtile + (int64_t)step * 256), 0, (int)min(left, (int64_t)0x7FFFFFFF), 0x00020000);
-        char* dst_stage = lds + stage * kGemmStageBytes;
+        char* dst_stage = glds + stage * kGemmStageBytes;
 #pragma unroll
         for (int t = 0; t < kCopies; ++t)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (__attribute__((address_space(3))) void*)(dst_stage + (wave * (4 * kCopies) + t * 4) * 256),
@@ -268,7 +278,7 @@ __device__ __forceinline__ void gemm_tile(
     // One K step: 8 slices of 32 columns, slice (h, j) uses word j of quad h; the LDS reads and the
     // decode for slice t + 1 are placed among the MFMAs of slice t.
     auto compute = [&](const uint4 (&wq)[kFN][2], const uint32_t (&km)[2], int stage) {
-        const char* src = lds + stage * kGemmStageBytes + a_row_base;
+        const char* src = glds + stage * kGemmStageBytes + a_row_base;
         const int sw = am & 15;
         v4i a[2][kFM], b[2][kFN];
         auto read_a = [&](v4i (&dst)[kFM], int t) {
@@ -314,28 +324,61 @@ __device__ __forceinline__ void gemm_tile(
     uint4 wa[kFN][2], wb[kFN][2];
     const uint32_t keep_t0 = (kg * 16 + brow) < tail_quads ? 0xC0C0C0C0u : 0u;
     const uint32_t keep_t1 = ((kg + 2) * 16 + brow) < tail_quads ? 0xC0C0C0C0u : 0u;
+    // This group's run of K steps.  Every group walks the same number of loop iterations, `per_group`, so that all
+    // waves of the workgroup meet at the same barriers; a group whose run is shorter (or empty) idles through the rest.
+    const int per_group = (step1 - step0 + kKG - 1) / kKG;
+    const int my0 = step0 + grp * per_group, my1 = min(step1, my0 + per_group);
     auto issue = [&](uint4 (&into)[kFN][2], int step) {
-        copy_x(step, step & 1);
+        copy_x(step, (step - my0) & 1);
         if (step < full_steps) load_w(into, step); else load_w_tail(into, step);
     };
     auto one_step = [&](uint4 (&wcur)[kFN][2], uint4 (&wnxt)[kFN][2], int s) {
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-        // lanes past a partial last step get a zero decode constant
-        const uint32_t all = s >= full_steps ? 0u : 0xC0C0C0C0u;   // uniform
-        const uint32_t km[2] = {keep_t0 | all, keep_t1 | all};
-        if (s + 1 < step1) issue(wnxt, s + 1);
-        compute(wcur, km, s & 1);
+        if (s < my1) {
+            // lanes past a partial last step get a zero decode constant
+            const uint32_t all = s >= full_steps ? 0u : 0xC0C0C0C0u;   // uniform
+            const uint32_t km[2] = {keep_t0 | all, keep_t1 | all};
+            if (s + 1 < my1) issue(wnxt, s + 1);
+            compute(wcur, km, (s - my0) & 1);
+        }
     };
-    issue(wa, step0);
-    int s = step0;
+    if (my0 < my1) issue(wa, my0);
+    int it = 0;
 #pragma unroll 1
-    for (; s + 1 < step1; s += 2) {
-        one_step(wa, wb, s);
-        one_step(wb, wa, s + 1);
+    for (; it + 1 < per_group; it += 2) {
+        one_step(wa, wb, my0 + it);
+        one_step(wb, wa, my0 + it + 1);
     }
-    if (s < step1) one_step(wa, wb, s);
+    if (it < per_group) one_step(wa, wb, my0 + it);
     __syncthreads();                                    // every wave is done with the activation stages
+
+    if (kKG > 1) {
+        // Fold the K groups: group 1 parks its accumulators in LDS (over the stages), group 0 adds them -- integer
+        // sums, the same result as one group walking all of K.  Group 1 leaves after the last barrier; what follows
+        // synchronises inside single waves only.
+        int* fold = reinterpret_cast<int*>(lds);
+        const int t = threadIdx.x & (kGemmThreads - 1);
+        if (grp == 1) {
+#pragma unroll
+            for (int fm = 0; fm < kFM; ++fm)
+#pragma unroll
+                for (int fn = 0; fn < kFN; ++fn)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) fold[((fm * kFN + fn) * 16 + v) * kGemmThreads + t] = acc[fm][fn][v];
+        }
+        __syncthreads();
+        if (grp == 0) {
+#pragma unroll
+            for (int fm = 0; fm < kFM; ++fm)
+#pragma unroll
+                for (int fn = 0; fn < kFN; ++fn)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[fm][fn][v] += fold[((fm * kFN + fn) * 16 + v) * kGemmThreads + t];
+        }
+        __syncthreads();                                // the fold area is free: the epilogue stages through it
+        if (grp != 0) return;
+    }
 
     // ---- epilogue: one instantiation per output type, chosen once ---------------------------------------
     const GemmOutCtx ctx{lds, scale_lds, y, gamma, gstride, RB, M, N, row0, bn, wave, lane, vec_store};
@@ -346,13 +389,14 @@ __device__ __forceinline__ void gemm_tile(
 }
 
 // Consecutive workgroups take consecutive token tiles of the same weight tile (see the header).  Workgroups per
-// CU: what the registers and the LDS stages allow (two with the tall wide tiles, up to four with 64-token tiles).
+// CU: what the registers and the LDS stages allow (two with the tall wide tiles, up to four with 64-token tiles);
+// one for the eight-wave form, which exists for grids that give a CU one workgroup anyway.
 constexpr int gemm_blocks_per_cu(int fm, int fn) { return fn == 1 ? (fm == 2 ? 4 : fm == 3 ? 3 : 2) : (fm == 2 ? 3 : 2); }
 
 // blockIdx.y selects a split of the K steps (split-K: every split stores its int32 partial accumulators, [M][N] each,
 // one after the other at y; a second kernel adds them up and rescales).  One split: the whole product, stored as yt.
-template <int kFM, int kFN>
-__global__ __launch_bounds__(kGemmThreads, gemm_blocks_per_cu(kFM, kFN)) void linear_gemm_2bit(
+template <int kFM, int kFN, int kKG = 1>
+__global__ __launch_bounds__(kGemmThreads * kKG, kKG > 1 ? 1 : gemm_blocks_per_cu(kFM, kFN)) void linear_gemm_2bit(
         const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
         const float* __restrict__ gamma, int gstride, int M, int64_t N, int64_t K, int Kq, int RB, int tiles_m,
         int steps_per_split, void* __restrict__ y, OutType yt, int vec_store) {
@@ -361,7 +405,7 @@ __global__ __launch_bounds__(kGemmThreads, gemm_blocks_per_cu(kFM, kFN)) void li
     const int step0 = blockIdx.y * steps_per_split;
     const int step1 = min(steps, step0 + steps_per_split);
     void* yp = static_cast<char*>(y) + (int64_t)blockIdx.y * M * N * 4;        // blockIdx.y > 0 only with int32 partials
-    gemm_tile<kFM, kFN>(xq, sx, packed, gamma, gstride, M, N, K, Kq, RB, (b % tiles_m) * (32 * kFM), b / tiles_m, step0, step1,
+    gemm_tile<kFM, kFN, kKG>(xq, sx, packed, gamma, gstride, M, N, K, Kq, RB, (b % tiles_m) * (32 * kFM), b / tiles_m, step0, step1,
                         yp, yt, vec_store);
 }
 
@@ -412,13 +456,13 @@ bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
     return M >= 1 && K % 16 == 0 && reinterpret_cast<uintptr_t>(xq) % 16 == 0 && ceil_div(N, kRowsPerBlock) < ((int64_t)1 << 21);
 }
 
-template <int kFM, int kFN>
+template <int kFM, int kFN, int kKG = 1>
 static hipError_t launch_gemm_tiles(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                     int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt,
                                     hipStream_t stream, int splits = 1, void* workspace = nullptr, LaunchPlan* plan = nullptr) {
     if (!plan) {
         static RaisedFlags raised = {};
-        const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(linear_gemm_2bit<kFM, kFN>), gemm_lds_bytes(kFM), raised);
+        const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(linear_gemm_2bit<kFM, kFN, kKG>), gemm_lds_bytes(kFM, kFN, kKG), raised);
         if (e != hipSuccess) return e;
     }
     const int Kq = (int)ceil_div(K, kColsPerQuad);
@@ -435,24 +479,27 @@ static hipError_t launch_gemm_tiles(const int8_t* xq, const float* sx, const voi
     const size_t esz = ot == OutType::BF16 ? 2 : 4;
     const int vec_store = (reinterpret_cast<uintptr_t>(out) % 16 == 0) && ((N * esz) % 16 == 0);
     if (plan) {
-        plan->set("prefill", {32 * kFM, 128 * kFN}, (unsigned)(tiles_m * tiles_n), (unsigned)splits, kGemmThreads, gemm_lds_bytes(kFM), splits);
+        if (kKG > 1) plan->set("prefill", {32 * kFM, 128 * kFN, kKG}, (unsigned)(tiles_m * tiles_n), (unsigned)splits, kGemmThreads * kKG, gemm_lds_bytes(kFM, kFN, kKG), splits);
+        else plan->set("prefill", {32 * kFM, 128 * kFN}, (unsigned)(tiles_m * tiles_n), (unsigned)splits, kGemmThreads, gemm_lds_bytes(kFM, kFN, 1), splits);
         return hipSuccess;
     }
-    hipLaunchKernelGGL((linear_gemm_2bit<kFM, kFN>), dim3((unsigned)(tiles_m * tiles_n), (unsigned)splits), dim3(kGemmThreads),
-                       gemm_lds_bytes(kFM), stream, xq, sx, static_cast<const uint4*>(packed), gamma, gstride, (int)M, N, K, Kq, RB,
+    hipLaunchKernelGGL((linear_gemm_2bit<kFM, kFN, kKG>), dim3((unsigned)(tiles_m * tiles_n), (unsigned)splits), dim3(kGemmThreads * kKG),
+                       gemm_lds_bytes(kFM, kFN, kKG), stream, xq, sx, static_cast<const uint4*>(packed), gamma, gstride, (int)M, N, K, Kq, RB,
                        tiles_m, sps, out, ot, vec_store);
     if (split)
         return launch_splitk_reduce(static_cast<const int32_t*>(workspace), splits, sx, gamma, gstride, 1, M, N, y, yt, stream);
     return hipGetLastError();
 }
 
-// tile shape forced by the caller (tuning and tests); fm in 2 .. 4, fn in 1 .. 2; splits > 1: split-K through `workspace`
-// (splits * M * N int32)
-hipError_t launch_linear_gemm_2bit_shape(int fm, int fn, const int8_t* xq, const float* sx, const void* packed, const float* gamma,
+// tile shape forced by the caller (tuning and tests); fm in 2 .. 4, fn in 1 .. 2; kg 1, or 2 (two K groups per workgroup:
+// 96 x 128 and 64 x 256 tiles only, one launch only); splits > 1: split-K through `workspace` (splits * M * N int32)
+hipError_t launch_linear_gemm_2bit_shape(int fm, int fn, int kg, const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                          int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream,
                                          int splits, void* workspace, LaunchPlan* plan) {
-#define GEMM_SHAPE(FM_, FN_) if (fm == FM_ && fn == FN_) return launch_gemm_tiles<FM_, FN_>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, splits, workspace, plan)
-    GEMM_SHAPE(2, 1); GEMM_SHAPE(3, 1); GEMM_SHAPE(4, 1); GEMM_SHAPE(2, 2); GEMM_SHAPE(3, 2); GEMM_SHAPE(4, 2);
+#define GEMM_SHAPE(FM_, FN_, KG_) if (fm == FM_ && fn == FN_ && kg == KG_) return launch_gemm_tiles<FM_, FN_, KG_>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, splits, workspace, plan)
+    if (kg == 2 && splits > 1) return hipErrorInvalidValue;
+    GEMM_SHAPE(2, 1, 1); GEMM_SHAPE(3, 1, 1); GEMM_SHAPE(4, 1, 1); GEMM_SHAPE(2, 2, 1); GEMM_SHAPE(3, 2, 1); GEMM_SHAPE(4, 2, 1);
+    GEMM_SHAPE(3, 1, 2); GEMM_SHAPE(2, 2, 2);
 #undef GEMM_SHAPE
     return hipErrorInvalidValue;
 }
@@ -475,6 +522,10 @@ hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void
     // Examples (13B o projection, N = K = 5120): M = 512 runs 96 x 128 tiles in 19.6 us (64 x 256: 23.6 us,
     // 128 x 256: 36 us); M = 2048 stays on 96 x 256 tiles.  (Up to 256 tokens such small layers go to the
     // batched-decode kernels instead, which tile the tokens over workgroups.)
+    // Where one launch of four-wave workgroups gives no CU more than one of them, the 96 x 128 and 64 x 256 tiles also
+    // exist with eight waves in two K groups (13B O / down at 512 tokens: 19.1 -> 17.9 us, 40.2 -> 36.6 us; 8192 rows,
+    // K = 28672, 300 tokens: 99 -> 75 us): ceil(steps / 2) iterations of kPair[] us each and a fold, in kPairFixed; a CU
+    // holds one such workgroup, so they are candidates only while the tiles fit the chip in one round.
     // With a workspace the K steps may also be split over 2, 4 or 8 workgroups per tile (each stores int32 partial
     // accumulators, a second launch adds them and rescales): the same model with steps / splits per workgroup and
     // tiles * splits workgroups, plus the second launch (a few microseconds and the partials' traffic).  It pays where
@@ -482,8 +533,10 @@ hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void
     struct Shape { int fm, fn; double alone, saturated, fixed; };
     static const Shape kShapes[6] = {{4, 2, 1.48, 1.45, 5.4}, {3, 2, 1.15, 1.10, 4.7}, {2, 2, 0.94, 0.74, 4.4},
                                      {4, 1, 0.94, 0.86, 3.5}, {3, 1, 0.715, 0.613, 3.4}, {2, 1, 0.594, 0.43, 3.2}};
+    struct PairShape { int fm, fn; double per_iteration, fixed; };
+    static const PairShape kPair[2] = {{3, 1, 0.95, 7.0}, {2, 2, 1.10, 7.0}};
     const int64_t steps_total = ceil_div(K, 256);
-    int best = 0, best_splits = 1;
+    int best = 0, best_splits = 1, best_kg = 1;
     double best_cost = 0.0;
     for (int sp = 1; sp <= 8; sp *= 2) {
         if (force_splits > 0 && sp != force_splits) continue;
@@ -498,12 +551,22 @@ hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void
             const double shared = (double)ceil_div(tiles, (int64_t)256) * sh.saturated;
             const double cost = sh.fixed + steps * (alone > shared ? alone : shared) + second;
             if ((sp == 1 && c == 0) || (force_splits > 0 && sp == force_splits && c == 0) || cost < 0.96 * best_cost) {
-                best = c; best_splits = sp; best_cost = cost;
+                best = c; best_splits = sp; best_kg = 1; best_cost = cost;
             }
         }
     }
-    return launch_linear_gemm_2bit_shape(kShapes[best].fm, kShapes[best].fn, xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream,
-                                         best_splits, workspace, plan);
+    int fm = kShapes[best].fm, fn = kShapes[best].fn;
+    if (force_splits <= 0) {
+        for (int c = 0; c < 2; ++c) {
+            const PairShape& sh = kPair[c];
+            const int64_t tiles = ceil_div(M, 32 * sh.fm) * ceil_div(N, 128 * sh.fn);
+            if (tiles > 256 || steps_total < 2) continue;
+            const double fill = (double)tiles / 256.0;
+            const double cost = sh.fixed + (double)ceil_div(steps_total, (int64_t)2) * sh.per_iteration * (1.0 + 0.2 * fill * fill);
+            if (cost < 0.96 * best_cost) { fm = sh.fm; fn = sh.fn; best_splits = 1; best_kg = 2; best_cost = cost; }
+        }
+    }
+    return launch_linear_gemm_2bit_shape(fm, fn, best_kg, xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, best_splits, workspace, plan);
 }
 
 }  // namespace bitnet
