@@ -116,11 +116,10 @@ __device__ inline double readlane_f64(double v, int lane) {
     return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
 }
 
-// Sum over the block of per-thread double-double partial sums; every thread gets the result.  The sums are
-// exact to ~2^-100, far below the rounding of the result to fp64, so the shape of the tree does not show:
-// four DPP steps inside each row of 16 lanes, the four rows of a wave through scalar reads, the waves in order.
-template <int kWaves>
-__device__ inline double block_sum_dd(dd v, double* sh_hi, double* sh_lo) {
+// Sum over a wave of per-lane double-double partial sums; every lane gets the result.  The sums are exact to
+// ~2^-100, far below the rounding of the result to fp64, so the shape of the tree does not show: four DPP steps
+// inside each row of 16 lanes, the four rows through scalar reads.
+__device__ inline dd wave_sum_dd(dd v) {
     dd_add_dd(v, dd{dpp_f64<0xB1>(v.hi), dpp_f64<0xB1>(v.lo)});       // lane ^ 1
     dd_add_dd(v, dd{dpp_f64<0x4E>(v.hi), dpp_f64<0x4E>(v.lo)});       // lane ^ 2
     dd_add_dd(v, dd{dpp_f64<0x141>(v.hi), dpp_f64<0x141>(v.lo)});     // other quad of the 8
@@ -129,6 +128,13 @@ __device__ inline double block_sum_dd(dd v, double* sh_hi, double* sh_lo) {
     dd_add_dd(w, dd{readlane_f64(v.hi, 16), readlane_f64(v.lo, 16)});
     dd_add_dd(w, dd{readlane_f64(v.hi, 32), readlane_f64(v.lo, 32)});
     dd_add_dd(w, dd{readlane_f64(v.hi, 48), readlane_f64(v.lo, 48)});
+    return w;
+}
+
+// ... and over the block (the waves in order); every thread gets the result.
+template <int kWaves>
+__device__ inline double block_sum_dd(dd v, double* sh_hi, double* sh_lo) {
+    const dd w = wave_sum_dd(v);
     if (kWaves == 1) return w.hi + w.lo;
     const int wave = threadIdx.x >> 6;
     if ((threadIdx.x & 63) == 0) { sh_hi[wave] = w.hi; sh_lo[wave] = w.lo; }

@@ -151,6 +151,28 @@ __device__ inline void expand_vec(const uint4& q, float (&f)[kBf16 ? 8 : 4]) {
     }
 }
 
+// r = (float)(1 / sqrt(mean(x^2) + eps)) from the threads' double-double partial sums of squares.  Every wave adds
+// up its lanes; wave 0 alone then adds the waves, divides and takes the root in fp64 -- a hundred dependent
+// instructions that the other waves' SIMDs can give to other tokens meanwhile -- and hands r over through LDS.
+template <int kWaves>
+__device__ inline float rms_scale(dd v, int64_t K, float eps, double* sh_hi, double* sh_lo, float* shr) {
+    const dd w = wave_sum_dd(v);
+    if (kWaves == 1) return (float)(1.0 / sqrt((w.hi + w.lo) / (double)K + (double)eps));
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { sh_hi[wave] = w.hi; sh_lo[wave] = w.lo; }
+    __syncthreads();
+    if (wave == 0) {
+        dd t{sh_hi[0], sh_lo[0]};
+#pragma unroll
+        for (int q = 1; q < kWaves; ++q) dd_add_dd(t, dd{sh_hi[q], sh_lo[q]});
+        const double ms = (t.hi + t.lo) / (double)K;
+        const float r = (float)(1.0 / sqrt(ms + (double)eps));
+        if (threadIdx.x == 0) shr[0] = r;
+    }
+    __syncthreads();
+    return shr[0];
+}
+
 // RMSNorm -> absmax int8.  Per token: ms = mean of squares (exact: squares of fp32 values are exact in
 // fp64 and the sum is carried in double-double), r = (float)(1 / sqrt(ms + eps)) in fp64, z = (x * r) * g
 // in fp32, then the per-token quantization of z.
@@ -169,7 +191,7 @@ __global__ __launch_bounds__(kThreads) void rmsnorm_quantize_vec(
     constexpr int kWaves = kThreads / kWave;
     constexpr bool kKeepZ = kVecs * kElems <= 32;
     __shared__ double sh_hi[kWaves], sh_lo[kWaves];
-    __shared__ float sh[kWaves];
+    __shared__ float sh[kWaves + 1];                               // the waves' maxima; r of the token behind them
     const int64_t m = blockIdx.x;
     const int nvec = (int)(K / kElems);
     const uint4* row = reinterpret_cast<const uint4*>(static_cast<const char*>(xv) + m * K * (kBf16 ? 2 : 4));
@@ -196,8 +218,7 @@ __global__ __launch_bounds__(kThreads) void rmsnorm_quantize_vec(
     dd_add_dd(acc[0], acc[1]);
     dd_add_dd(acc[2], acc[3]);
     dd_add_dd(acc[0], acc[2]);
-    const double ms = block_sum_dd<kWaves>(acc[0], sh_hi, sh_lo) / (double)K;
-    const float r = (float)(1.0 / sqrt(ms + (double)eps));
+    const float r = rms_scale<kWaves>(acc[0], K, eps, sh_hi, sh_lo, sh + kWaves);
 
     // z = (x * r) * g of one vector; the gain comes from the caches (every token reads the same K floats)
     auto scaled = [&](int v, int idx, float (&z)[kElems]) {
@@ -267,7 +288,7 @@ __global__ __launch_bounds__(kThreads) void rmsnorm_quantize_any(
         float* __restrict__ sx) {
     constexpr int kWaves = kThreads / kWave;
     __shared__ double sh_hi[kWaves], sh_lo[kWaves];
-    __shared__ float sh[kWaves];
+    __shared__ float sh[kWaves + 1];                               // the waves' maxima; r of the token behind them
     const int64_t m = blockIdx.x;
     const void* row = static_cast<const char*>(xv) + m * K * (kBf16 ? 2 : 4);
     int8_t* out = xq + m * K;
@@ -276,8 +297,7 @@ __global__ __launch_bounds__(kThreads) void rmsnorm_quantize_any(
         const double a = (double)load_elem<kBf16>(row, k);
         dd_add_double(acc, a * a);
     }
-    const double ms = block_sum_dd<kWaves>(acc, sh_hi, sh_lo) / (double)K;
-    const float r = (float)(1.0 / sqrt(ms + (double)eps));
+    const float r = rms_scale<kWaves>(acc, K, eps, sh_hi, sh_lo, sh + kWaves);
     float amax = 0.0f;
     for (int64_t k = threadIdx.x; k < K; k += kThreads) {
         float z = load_elem<kBf16>(row, k) * r;
