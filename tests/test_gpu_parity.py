@@ -1327,3 +1327,104 @@ def test_outputs_do_not_spill_past_their_buffers(gpu_lib):
                  tuple(gpu_lib.KERNEL_GEMM_TILES_K2.values())):
         gpu_lib.linear(xq, sx, packed, gamma, N, y=y_big[: M * N].view(M, N), kernel=kern)
         assert bool((y_big[M * N:] == 7.0).all())
+
+
+# ------------------------------------------------------------------------------------------------
+# maximum sizes: operands beyond 2^31 elements (an output-embedding-sized matrix, a prefill's worth of logits)
+# ------------------------------------------------------------------------------------------------
+def test_matrix_and_output_beyond_2_to_31_elements(gpu_lib):
+    """135168 x 16384 weights (2.2e9 > 2^31 elements, 8.9 GB in fp32) and 16384 x 135168 outputs: every index that is a
+    product of two dimensions must be 64 bits wide.  The matrix is a 4224-element pattern repeated 2^19 times (the pattern
+    is not aligned with rows or row blocks), so its gamma and codes are those the oracle gives for the pattern -- the
+    exact sum scales by a power of two and the fp64 division sees the same quotient -- and the expected tensors are laid
+    out by torch, not by this library.  Accumulators are compared with torch's fp32 matrix product of the expected codes
+    and the oracle-checked x_q, which is exact here (|acc| <= 127 * 16384 < 2^24)."""
+    N, K, period = 135168, 16384, 4224
+    if torch.cuda.mem_get_info()[0] < 60e9:
+        pytest.skip("needs 60 GB of free device memory")
+    say("beyond 2^31 elements: N=%d K=%d" % (N, K))
+    assert N * K > 2 ** 31 and (N * K) % period == 0 and K % period != 0
+    reps = N * K // period
+    assert reps == 2 ** 19
+    P = synth.weights(33, 128, config=0, layer=3, tensor=41).reshape(1, period)
+    codes_p, gamma_p = oracle.quantize_weights(P)
+    W = dev(P.reshape(-1)).repeat(reps).view(N, K)
+    packed, gamma = gpu_lib.quantize_weights(W)
+    del W
+    assert gamma.cpu().numpy()[0] == gamma_p
+    expected = dev(codes_p.reshape(-1)).repeat(reps).view(N, K)
+    codes = gpu_lib.unpack_weights(packed, N, K)
+    assert torch.equal(codes, expected)
+    del codes
+    ef = expected.to(torch.float32)
+    del expected
+
+    # decode: 1 and 4 tokens (and the launch that quantizes x itself), accumulators over all 135168 rows
+    x, bits = synth.activations(4, K, config=2, layer=1, tensor=42, bf16=True)
+    xq_ref, sx_ref = oracle.quantize_acts(x)
+    xd = bf16_tensor(bits).view(4, K)
+    xq, sx = gpu_lib.quantize_acts(xd)
+    assert np.array_equal(xq.cpu().numpy(), xq_ref) and sx.cpu().numpy().tobytes() == sx_ref.tobytes()
+    acc_ref = (ef @ xq.to(torch.float32).T).T.contiguous().to(torch.int32)
+    assert int(acc_ref.abs().max()) < 2 ** 24
+    say("beyond 2^31 elements: decode")
+    for M in (1, 4):
+        acc = gpu_lib.linear(xq[:M], sx[:M], packed, gamma, N, y_dtype=gpu_lib.I32)
+        assert torch.equal(acc, acc_ref[:M])
+    assert torch.equal(gpu_lib.linear_fused(xd[:1], packed, gamma, N, y_dtype=gpu_lib.I32), acc_ref[:1])
+    y = gpu_lib.linear(xq, sx, packed, gamma, N, y_dtype=gpu_lib.F32).cpu().numpy()
+    check_y(y, oracle.rescale(acc_ref.cpu().numpy(), gamma_p, sx_ref), RTOL_F32)
+
+    # prefill: 16384 tokens, 2.2e9 outputs; sampled tokens on both sides of element 2^31 of y, the first and the last
+    M = 16384
+    say("beyond 2^31 elements: prefill, M=%d" % M)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(4242)
+    X = torch.randn((M, K), device="cuda", generator=gen, dtype=torch.float32).to(torch.bfloat16)
+    xq2, sx2 = gpu_lib.quantize_acts(X)
+    edge = 2 ** 31 // N
+    rows = [0, 1, 127, 128, edge - 1, edge, edge + 1, M - 129, M - 2, M - 1]
+    xs = X[rows].to(torch.float32).cpu().numpy()
+    xq_s, sx_s = oracle.quantize_acts(xs)
+    assert np.array_equal(xq2[rows].cpu().numpy(), xq_s) and sx2[rows].cpu().numpy().tobytes() == sx_s.tobytes()
+    acc_s = (ef @ xq2[rows].to(torch.float32).T).T.contiguous().to(torch.int32)
+    del ef
+    acc2 = gpu_lib.linear(xq2, sx2, packed, gamma, N, y_dtype=gpu_lib.I32)
+    assert tuple(acc2.shape) == (M, N) and acc2.numel() > 2 ** 31
+    assert torch.equal(acc2[rows], acc_s)
+    del acc2
+    y2 = gpu_lib.linear(xq2, sx2, packed, gamma, N, y_dtype=gpu_lib.BF16)
+    check_y(y2[rows].to(torch.float32).cpu().numpy(), oracle.rescale(acc_s.cpu().numpy(), gamma_p, sx_s), RTOL_BF16)
+
+
+def test_activations_beyond_2_to_31_elements(gpu_lib):
+    """75198 tokens of 28672 elements (2.16e9 > 2^31): the three producers of int8 activations on sampled tokens on both
+    sides of element 2^31, the first and the last, against the oracle."""
+    K = 28672
+    M = 2 ** 31 // K + 300
+    if torch.cuda.mem_get_info()[0] < 20e9:
+        pytest.skip("needs 20 GB of free device memory")
+    say("activations beyond 2^31 elements: M=%d K=%d" % (M, K))
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(777)
+    X = torch.empty((M, K), device="cuda", dtype=torch.bfloat16)
+    for m0 in range(0, M, 8192):                                     # drawn in slabs: no fp32 copy of the whole tensor
+        m1 = min(M, m0 + 8192)
+        X[m0:m1] = torch.randn((m1 - m0, K), device="cuda", generator=gen, dtype=torch.float32).to(torch.bfloat16)
+    assert X.numel() > 2 ** 31
+    edge = 2 ** 31 // K
+    rows = [0, 1, edge - 1, edge, edge + 1, M - 2, M - 1]
+    xs = X[rows].to(torch.float32).cpu().numpy()
+    g = (1.0 + 0.25 * np.random.default_rng(5).standard_normal(K)).astype(np.float32)
+
+    xq, sx = gpu_lib.quantize_acts(X)
+    xq_ref, sx_ref = oracle.quantize_acts(xs)
+    assert np.array_equal(xq[rows].cpu().numpy(), xq_ref) and sx[rows].cpu().numpy().tobytes() == sx_ref.tobytes()
+    del xq
+    zq, sz = gpu_lib.rmsnorm_quantize(X, dev(g), 1e-5)
+    zq_ref, sz_ref, _ = oracle.rmsnorm_quantize(xs, g, 1e-5)
+    assert np.array_equal(zq[rows].cpu().numpy(), zq_ref) and sz[rows].cpu().numpy().tobytes() == sz_ref.tobytes()
+    del zq
+    hq, sh = gpu_lib.swiglu_quantize(X)                              # rows as [gate | up] of F = K / 2
+    hq_ref, sh_ref, _ = oracle.swiglu_quantize(xs)
+    assert np.array_equal(hq[rows].cpu().numpy(), hq_ref) and sh[rows].cpu().numpy().tobytes() == sh_ref.tobytes()
