@@ -648,6 +648,16 @@ static hipError_t dispatch16_fused(int xmode, const void* x, const void* packed,
         else if (RB > 320) GEMV16(1, 2, 2, 4, kModesFused | kModesPre, xmode);
         else GEMV16(1, 4, 1, 4, kModesInt8 | kModesFused | kModesPre, xmode);
     }
+    // Eight tokens and more: every workgroup quantizes all of them before its first product, so the forms that give a
+    // workgroup more row blocks (fewer workgroups repeating that work, eight waves sharing it) win by 10-25 %:
+    // 16 tokens on 3200 -> 17280 13.3 -> 10.4 us, on 3200 -> 9600 11.5 -> 8.6 us, on 3200 -> 3200 7.6 -> 6.8 us; 8 tokens
+    // on 4096 -> 22016 10.8 -> 9.5 us, on 4096 -> 12288 9.0 -> 7.5 us; 12 tokens on 5120 -> 15360 22.3 -> 18.8 us, on
+    // 5120 -> 5120 19.1 -> 15.7 us (at four tokens the forms below are within 3 % of the best).
+    if (M >= 8) {
+        if (RB >= 1024) GEMV16(4, 4, 2, 2, kModesFused, xmode);
+        else if (RB > 384) GEMV16(2, 4, 2, 4, kModesFused, xmode);
+        else GEMV16(1, 8, 1, 3, kModesFused | kModesPre, xmode);
+    }
     // Many row blocks: eight waves per workgroup, each walking all of K for one or two row blocks of its own -- few
     // workgroups repeat the quantization, no partial sums to fold, and about eight waves per CU with several loads
     // each in flight is the shape in which a plain read loop is fastest on this chip (70B gate/up 22.9 -> 20.8 us,

@@ -40,7 +40,11 @@ FUSED_SHAPES = [(1, 4096, 1536), (16, 4096, 1536), (1, 17, 16), (3, 100, 80), (7
                 (1, 9600, 3200), (1, 3200, 3200), (1, 12288, 4096), (1, 4096, 4096), (2, 9600, 3200), (4, 3200, 3200),
                 # 2048 row blocks and more with 32 K steps and more: depth 3 with two extra steps requested up front
                 # (ragged rows, a partial 33rd step)
-                (2, 32816, 8208)]
+                (2, 32816, 8208),
+                # eight tokens and more: the forms with more row blocks per workgroup (1024 row blocks and more; 385 ... 1023;
+                # fewer), ragged and at the 3B / 7B / 13B sizes, K beyond the wave-per-token quantizer's 4096 included
+                (8, 16400, 528), (16, 17280, 3200), (9, 6160, 272), (16, 9600, 3200), (8, 12288, 4096), (16, 3200, 3200),
+                (12, 5120, 5120)]
 
 NORM_FUSED_SHAPES = [(1, 4096, 1536), (1, 100, 3200), (3, 250, 1040), (1, 33, 4112), (16, 70, 528), (1, 16400, 272),
                      (2, 16400, 4112), (1, 600, 16400), (1, 6416, 8640), (4, 300, 8192), (1, 32800, 528), (5, 40, 16)]
