@@ -386,9 +386,17 @@ hipError_t launch_linear_gemv_trit5(const int8_t* xq, const float* sx, const voi
                                     int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream) {
     const int64_t RB = ceil_div(N, kRowsPerBlock);
     const int64_t steps = ceil_div(K, kTritStep);
-    if (RB >= 2048)        launch_trit5<2, 2, 2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
-    else if (steps >= 24)  launch_trit5<1, 8, 2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
-    else                   launch_trit5<1, 4, 2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
+    // the share of a wave's padded K walk (a multiple of the prefetch depth) that is real steps
+    auto walk = [&](int ks, int kd) { return (double)steps / (double)(ceil_div(ceil_div(steps, (int64_t)ks), (int64_t)kd) * kd * ks); };
+    // Measured on MI355X, M = 1, fifteen forms per shape: 3200 -> 3200 4.0 -> 3.5 us and 3200 -> 17280 8.0 -> 6.6 us with
+    // depth 3 (ten steps fill three rounds of four waves exactly; thirteen steps would walk 24), 4096 -> 22016 9.4 -> 8.7 us
+    // and 28672 -> 8192 17.9 -> 15.5 us with two row blocks per wave.
+    if (RB >= 2048)                                   launch_trit5<2, 2, 2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
+    else if (steps >= 64 && RB >= 512)                launch_trit5<2, 8, 2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
+    else if (steps >= 24)                             launch_trit5<1, 8, 2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
+    else if (walk(4, 3) > walk(4, 2))                 launch_trit5<1, 4, 3>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
+    else if (RB >= 1024)                              launch_trit5<2, 4, 2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
+    else                                              launch_trit5<1, 4, 2>(xq, sx, packed, gamma, M, N, K, y, yt, stream);
     return hipGetLastError();
 }
 

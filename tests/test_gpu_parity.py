@@ -1188,7 +1188,9 @@ def test_trit5_quantize_weights_matches_oracle(gpu_lib, N, K):
 
 TRIT_LINEAR_SHAPES = [(1, 4096, 1536), (16, 4096, 1536), (1, 17, 16), (3, 100, 80), (7, 250, 1040), (1, 3200, 3200),
                       (2, 32800, 528), (2, 64, 8640), (16, 300, 4112), (20, 70, 336), (70, 40, 640),
-                      (33, 1000, 656), (100, 2000, 320)]      # more than 16 tokens: walked 16 at a time
+                      (33, 1000, 656), (100, 2000, 320),      # more than 16 tokens: walked 16 at a time
+                      # the two-row-block forms: 65 steps (the last partial) on 513 row blocks; 13 steps on 1025
+                      (2, 8200, 20496), (3, 16400, 4112)]
 
 
 @pytest.mark.parametrize("M,N,K", TRIT_LINEAR_SHAPES)
