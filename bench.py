@@ -43,6 +43,7 @@ DEFAULT_WORKLOAD = "70b_decode"
 # token counts of the extra legs (the launch inventory below and the legs themselves read these)
 BATCHED_DECODE_MS = (1, 8, 16, 32, 64)
 BATCHED_DECODE_MS_WS = (128, 256)
+BATCHED_DECODE_FUSED_MS = (8,)
 GEMM_MS = (2048, 512)
 SMALL_LAYER_MS = (1, 16)
 PREFILL_70B_M = 4096
@@ -87,6 +88,9 @@ def launch_inventory():
     for (_, K, N) in synth.CONFIGS[2]["shapes"]:
         for M in BATCHED_DECODE_MS + BATCHED_DECODE_MS_WS:
             inv.append(("batched_decode_7b", "LINEAR", "int8", M, N, K))
+        for M in BATCHED_DECODE_FUSED_MS:
+            if 32 * 16 + M * ((K + 255) // 256) * 256 <= 65536:       # header + int8 rows within the fused kernel's LDS budget
+                inv.append(("batched_decode_7b", "LINEAR_FUSED", "bf16", M, N, K))
     for (_, K, N) in synth.CONFIGS[3]["shapes"]:
         for M in GEMM_MS:
             inv.append(("gemm_13b", "LINEAR", "int8", M, N, K))
@@ -104,6 +108,15 @@ def launch_inventory():
 def progress(msg):
     """a line on stderr per finished stage, so that a long run (under a profiler, say) is seen to move"""
     print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def fused_supported(B, M, N, K):
+    """whether bitnet_linear_fused takes this shape (host-side query, nothing is launched)"""
+    try:
+        B.entry_describe(B.ENTRY_LINEAR_FUSED, M, N, K, x_dtype=B.BF16)
+        return True
+    except B.BitnetError:
+        return False
 
 
 def gemv_bytes(M, N, K, out_bytes=2):
@@ -564,6 +577,16 @@ def batched_decode_leg(torch, B, synth, gen, stream, args):
                                  "GB/s": round(gemv_bytes(M, N, K) / (us * 1e-6) / 1e9, 1),
                                  "TOPS": round(2.0 * M * N * K / us * 1e-6, 1)}
             del graph
+            if M in BATCHED_DECODE_FUSED_MS and fused_supported(B, M, N, K):
+                # the same product with the activation quantization inside the launch (bf16 x; up to 16 tokens whose int8
+                # rows fit the workgroup's LDS budget)
+                def run_fused():
+                    for (p, g) in packs:
+                        B.linear_fused(x, p, g, N, y_dtype=B.BF16, y=y)
+
+                ms, _, graph = time_graph(torch, run_fused, max(2, args.warmup // 5), max(5, args.steps // 5), stream)
+                entry["M=%d" % M]["us_fused"] = round(ms * 1e3 / layers, 2)
+                del graph
         # the serving regime just above 64 tokens: small layers still run the token-tiled decode kernels, the others
         # the prefill kernel, timed without and with a split-K workspace (bitnet_linear_ws)
         for M in BATCHED_DECODE_MS_WS:
