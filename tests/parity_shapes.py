@@ -44,7 +44,9 @@ FUSED_SHAPES = [(1, 4096, 1536), (16, 4096, 1536), (1, 17, 16), (3, 100, 80), (7
                 # eight tokens and more: the forms with more row blocks per workgroup (1024 row blocks and more; 385 ... 1023;
                 # fewer), ragged and at the 3B / 7B / 13B sizes, K beyond the wave-per-token quantizer's 4096 included
                 (8, 16400, 528), (16, 17280, 3200), (9, 6160, 272), (16, 9600, 3200), (8, 12288, 4096), (16, 3200, 3200),
-                (12, 5120, 5120)]
+                (12, 5120, 5120),
+                # three and four tokens of rows too long for one wave per token: quantized one after the other
+                (4, 300, 8640), (3, 4096, 11008)]
 
 NORM_FUSED_SHAPES = [(1, 4096, 1536), (1, 100, 3200), (3, 250, 1040), (1, 33, 4112), (16, 70, 528), (1, 16400, 272),
                      (2, 16400, 4112), (1, 600, 16400), (1, 6416, 8640), (4, 300, 8192), (1, 32800, 528), (5, 40, 16)]
