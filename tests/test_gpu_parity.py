@@ -778,6 +778,68 @@ def test_random_shapes_every_kernel_agrees(gpu_lib):
             check_y(y32.cpu().numpy(), o["y"], RTOL_F32)
 
 
+def test_random_shapes_block_entry_points_match_oracle(gpu_lib):
+    """40 seeded shapes (1 ... 16 tokens, 16 ... 4000 rows, K a multiple of 16 within the fused launches' LDS budget, both
+    input types) through the entry points that do a block's work in one launch -- RMSNorm in front, SwiGLU in front,
+    merged gate / up with the gate behind -- each against the oracle's own chain: accumulators bit for bit, the gate's
+    output bit for bit on the oracle's gate of the library's fp32 y and within the bf16 bar end to end."""
+    rng = np.random.default_rng(1764)
+    for case in range(40):
+        M = int(rng.choice([1, 1, 2, 3, 4, 7, 8, 12, 16]))
+        F = 16 * int(rng.integers(1, 126))                               # gate / up width; the product has 2 F rows
+        N = int(rng.integers(1, 4001))
+        K = 16 * int(rng.integers(1, min(257, 60000 // (16 * M))))
+        bf16 = case % 2 == 1
+        say("random block case %d: M=%d N=%d F=%d K=%d %s" % (case, M, N, F, K, "bf16" if bf16 else "f32"))
+        g = (1.0 + 0.25 * rng.standard_normal(K)).astype(np.float32)
+        eps = float(rng.choice([0.0, 1e-6, 1e-5]))
+        if bf16:
+            x, bits = synth.activations(M, K, config=2, layer=case, tensor=51, bf16=True)
+            xd = bf16_tensor(bits).view(M, K)
+        else:
+            x = synth.activations(M, K, config=0, layer=case, tensor=51)
+            xd = dev(x)
+        # RMSNorm -> int8 -> product
+        W = synth.weights(N, K, config=0, layer=case, tensor=52)
+        codes, gamma_ref = oracle.quantize_weights(W)
+        packed, gamma = gpu_lib.quantize_weights(dev(W))
+        xq_ref, sx_ref, _ = oracle.rmsnorm_quantize(x, g, eps)
+        acc_ref = oracle.ternary_matmul(xq_ref, codes)
+        acc = gpu_lib.rmsnorm_linear_fused(xd, dev(g), eps, packed, gamma, N, y_dtype=gpu_lib.I32)
+        assert np.array_equal(acc.cpu().numpy(), acc_ref), ("rmsnorm_linear_fused", M, N, K)
+        y16 = gpu_lib.rmsnorm_linear_fused(xd, dev(g), eps, packed, gamma, N, y_dtype=gpu_lib.BF16)
+        check_y(y16.float().cpu().numpy(), oracle.rescale(acc_ref, gamma_ref, sx_ref), RTOL_BF16)
+        # merged gate / up with RMSNorm in front and the gate behind
+        Wgu = synth.weights(2 * F, K, config=0, layer=case, tensor=53)
+        codes_gu, gamma_gu = oracle.quantize_weights(Wgu)
+        packed_gu, gamma_gu_d = gpu_lib.quantize_weights(dev(Wgu))
+        y_gu = oracle.rescale(oracle.ternary_matmul(xq_ref, codes_gu), gamma_gu, sx_ref)
+        h_chain = oracle.swiglu_quantize(y_gu.astype(np.float32))[2]
+        y32 = gpu_lib.rmsnorm_linear_fused(xd, dev(g), eps, packed_gu, gamma_gu_d, 2 * F).cpu().numpy()
+        check_y(y32, y_gu, RTOL_F32)
+        h32 = gpu_lib.ffn_gate_up_fused(xd, packed_gu, gamma_gu_d, F, norm=True, g=dev(g), eps=eps)
+        assert h32.cpu().numpy().tobytes() == oracle.swiglu_quantize(y32)[2].tobytes(), ("ffn_gate_up_fused", M, F, K)
+        nz = np.abs(h_chain) > 1e-6                                      # tiny gated values carry y's 1e-5 into a ratio of near-zeros
+        check_y(h32.cpu().numpy()[nz], h_chain.astype(np.float64)[nz], 1e-3)
+        # SwiGLU -> int8 -> product (the gated row has F columns: a down projection of N rows)
+        if 2 * F * M * (2 if bf16 else 4) <= 10 ** 9 and F <= 60000 // M:
+            Wd = synth.weights(N, F, config=0, layer=case, tensor=54)
+            codes_d, gamma_d = oracle.quantize_weights(Wd)
+            packed_d, gamma_dd = gpu_lib.quantize_weights(dev(Wd))
+            if bf16:
+                gu, gbits = synth.activations(M, 2 * F, config=2, layer=case, tensor=55, bf16=True)
+                gud = bf16_tensor(gbits).view(M, 2 * F)
+            else:
+                gu = synth.activations(M, 2 * F, config=0, layer=case, tensor=55)
+                gud = dev(gu)
+            hq_ref, sh_ref, _ = oracle.swiglu_quantize(gu)
+            acc_d = oracle.ternary_matmul(hq_ref, codes_d)
+            got = gpu_lib.swiglu_linear_fused(gud, packed_d, gamma_dd, N, y_dtype=gpu_lib.I32)
+            assert np.array_equal(got.cpu().numpy(), acc_d), ("swiglu_linear_fused", M, N, F)
+            y16 = gpu_lib.swiglu_linear_fused(gud, packed_d, gamma_dd, N, y_dtype=gpu_lib.BF16)
+            check_y(y16.float().cpu().numpy(), oracle.rescale(acc_d, gamma_d, sh_ref), RTOL_BF16)
+
+
 # ------------------------------------------------------------------------------------------------
 # producers of int8 activations: RMSNorm -> int8, SwiGLU -> int8 (bit-exact codes and scales)
 # ------------------------------------------------------------------------------------------------
