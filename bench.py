@@ -834,7 +834,8 @@ def main():
     out = {
         "metric": "BitLinear GEMV GB/s (%HBM peak) @M=1", "value": head["value"], "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8 (2-bit ternary weights, int32 accumulation)",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
+        "dtype_note": "int8 activations x 2-bit ternary weights on int8 MFMA, int32 accumulation, fp32 rescale, bf16 in / out",
         "data": "synthetic",
         "config": {"workload": head["workload"], "launch": head["launch"], "bytes_per_step": head["bytes_per_step"]},
         "pct_hbm_peak": head["pct_hbm_peak"],
