@@ -33,39 +33,76 @@ __device__ inline int trit5_digit(uint32_t byte, int d) {
 }
 
 // ---------------------------------------------------------------------------------------------------
-// packer: one thread per (row, quad): 80 consecutive weights in, 16 bytes out
+// packer: one wave per chunk of the packed layout (a 16-row block x one step of 320 columns: 20 KB of fp32 in, 1 KiB out)
 // ---------------------------------------------------------------------------------------------------
+// The wave reads the chunk's 16 x 320 weights as 20 rounds of 64 four-element loads that run along the rows (a thread
+// that walked its own 80 columns would touch 64 cache lines per load instruction: 1.3 TB/s), ternarizes them where they
+// land and parks the digits (code + 1, one per byte) in a wave-private LDS tile; lane 16 g + r then collects the 80
+// digits of row r, quad g and forms its 16 bytes, so that the wave stores the chunk as one 1 KiB run.  The tile's rows
+// are 81 words apart: both the row-wise writes and the quad-wise reads spread over the banks.
 __device__ inline float trit_w(const float* p) { return *p; }
 __device__ inline float trit_w(const uint16_t* p) { return bf16_to_f32(*p); }
+__device__ inline void trit_w4(const float* p, float (&w)[4]) {
+    const float4 v = *reinterpret_cast<const float4*>(p);
+    w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+}
+__device__ inline void trit_w4(const uint16_t* p, float (&w)[4]) {
+    const uint2 u = *reinterpret_cast<const uint2*>(p);
+    w[0] = __uint_as_float(u.x << 16); w[1] = __uint_as_float(u.x & 0xFFFF0000u);
+    w[2] = __uint_as_float(u.y << 16); w[3] = __uint_as_float(u.y & 0xFFFF0000u);
+}
 
+constexpr int kTritTilePitch = 81;                   // words per tile row: 80 + 1
 template <typename T>
 __global__ __launch_bounds__(256) void ternarize_pack_trit5(const T* __restrict__ W, int64_t N, int64_t K, int64_t RB,
-                                                            int64_t steps, const float* __restrict__ gamma,
-                                                            uint4* __restrict__ packed) {
-    const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;      // = (n_padded * steps * 4 + quad-in-row)
-    const int64_t quads_per_row = steps * 4;
-    const int64_t n = tid / quads_per_row;
-    const int64_t qr = tid % quads_per_row;
-    if (n >= RB * 16) return;
-    const int64_t s = qr >> 2;
-    const int g = (int)(qr & 3);
-    const int64_t k0 = s * kTritStep + g * kTritCols;
+                                                            int64_t steps, int vec_ok /* rows start on 4-element boundaries */,
+                                                            const float* __restrict__ gamma, uint4* __restrict__ packed) {
+    __shared__ uint32_t tiles[4][kRowsPerBlock * kTritTilePitch];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int64_t chunk = (int64_t)blockIdx.x * 4 + wave;             // = RB * step + row block: the chunk's place in the packed matrix
+    if (chunk >= RB * steps) return;                                   // whole waves leave; no workgroup barrier below
+    const int64_t s = chunk / RB, rb = chunk - s * RB;
     const float d = gamma[0] + kEps;                                   // Eq. (1): gamma + eps
-    uint32_t t[80];                                                    // code + 1 per column
+    uint32_t* tile = tiles[wave];
+#pragma unroll 4
+    for (int i = 0; i < 20; ++i) {
+        const int f = i * kWave + lane;                                // four-element piece f of the chunk, row-major
+        const int row = f / 80, c4 = f - row * 80;
+        const int64_t n = rb * kRowsPerBlock + row, k = s * kTritStep + 4 * c4;
+        float w[4] = {0.0f, 0.0f, 0.0f, 0.0f};                         // padding quantizes to code 0
+        if (n < N) {
+            const T* src = W + n * K + k;
+            if (vec_ok && k < K) {
+                trit_w4(src, w);                                       // K is a multiple of 4 here: k < K covers k + 3
+            } else {
 #pragma unroll
-    for (int c = 0; c < 80; ++c) {
-        float w = 0.0f;                                                // padding quantizes to code 0
-        if (n < N && k0 + c < K) w = trit_w(W + n * K + k0 + c);
-        const float r = fminf(1.0f, fmaxf(-1.0f, rintf(w / d)));       // Eq. (1)-(2)
-        t[c] = (uint32_t)((int)r + 1);
+                for (int e = 0; e < 4; ++e)
+                    if (k + e < K) w[e] = trit_w(src + e);
+            }
+        }
+        uint32_t t = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float r = fminf(1.0f, fmaxf(-1.0f, rintf(w[e] / d)));   // Eq. (1)-(2)
+            t |= (uint32_t)((int)r + 1) << (8 * e);
+        }
+        tile[row * kTritTilePitch + c4] = t;
     }
+    __builtin_amdgcn_wave_barrier();                                   // the tile is the wave's own: its LDS accesses complete in order
+    const int g = lane >> 4, r = lane & 15;
+    const uint32_t* src = tile + r * kTritTilePitch + 20 * g;
+    uint32_t dg[20];
+#pragma unroll
+    for (int w = 0; w < 20; ++w) dg[w] = src[w];
     uint32_t words[4] = {0, 0, 0, 0};
 #pragma unroll
     for (int p = 0; p < 16; ++p) {
-        const uint32_t b = t[4 * p] + 3 * t[4 * p + 1] + 9 * t[4 * p + 2] + 27 * t[4 * p + 3] + 81 * t[64 + p];
+        const uint32_t q = dg[p];                                      // digits of columns 4 p .. 4 p + 3
+        const uint32_t fifth = (dg[16 + (p >> 2)] >> (8 * (p & 3))) & 0xFFu;   // ... and of column 64 + p
+        const uint32_t b = (q & 0xFFu) + 3u * ((q >> 8) & 0xFFu) + 9u * ((q >> 16) & 0xFFu) + 27u * (q >> 24) + 81u * fifth;
         words[p >> 2] |= b << (8 * (p & 3));
     }
-    packed[64 * (RB * s + (n >> 4)) + 16 * g + (n & 15)] = make_uint4(words[0], words[1], words[2], words[3]);
+    packed[64 * chunk + lane] = make_uint4(words[0], words[1], words[2], words[3]);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -235,14 +272,14 @@ hipError_t launch_pack_trit5(const void* W, bool bf16, int64_t N, int64_t K, con
                              hipStream_t stream) {
     const int64_t RB = ceil_div(N, kRowsPerBlock);
     const int64_t steps = ceil_div(K, kTritStep);
-    const int64_t threads = RB * 16 * steps * 4;
-    dim3 grid((unsigned)ceil_div(threads, 256));
+    dim3 grid((unsigned)ceil_div(RB * steps, 4));
+    const int vec_ok = K % 4 == 0 && reinterpret_cast<uintptr_t>(W) % (bf16 ? 8 : 16) == 0;
     if (bf16)
         hipLaunchKernelGGL(ternarize_pack_trit5<uint16_t>, grid, dim3(256), 0, stream, static_cast<const uint16_t*>(W), N, K, RB,
-                           steps, gamma, static_cast<uint4*>(packed));
+                           steps, vec_ok, gamma, static_cast<uint4*>(packed));
     else
         hipLaunchKernelGGL(ternarize_pack_trit5<float>, grid, dim3(256), 0, stream, static_cast<const float*>(W), N, K, RB,
-                           steps, gamma, static_cast<uint4*>(packed));
+                           steps, vec_ok, gamma, static_cast<uint4*>(packed));
     return hipGetLastError();
 }
 
