@@ -142,6 +142,33 @@ def measured_traffic(N, K, fused=True):
     return None
 
 
+def plain_read_floor(torch, buffers, nbytes, stream, args):
+    """A kernel that only reads `nbytes` of each buffer (paper_2402_17764_amd/csrc/read_floor.hip, a library of its own),
+    timed like the product: one HIP graph of back-to-back launches over the distinct buffers, best of five launch shapes.
+    What the memory system gives a launch of this size when nothing else is done; None if that library is not built."""
+    try:
+        from paper_2402_17764_amd import read_floor
+        lib = read_floor.load()
+    except Exception:                                     # measurement aid only: the benchmark line does not depend on it
+        return None
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    best = None
+    for (blocks, loads) in ((256, 4), (256, 8), (512, 2), (512, 4), (1024, 2)):
+        def run():
+            s = torch.cuda.current_stream().cuda_stream
+            for b in buffers:
+                lib.read_only_launch(b.data_ptr(), nbytes, sink.data_ptr(), blocks, loads, s)
+
+        ms, _, graph = time_graph(torch, run, max(2, args.warmup // 3), max(5, args.steps // 3), stream)
+        del graph
+        us = ms * 1e3 / len(buffers)
+        if best is None or us < best["us_per_launch"]:
+            best = {"us_per_launch": round(us, 3), "GB/s": round(nbytes / (us * 1e-6) / 1e9, 1),
+                    "frac_hbm_peak": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                    "launch": "%d workgroups x 512 threads, %d loads of 16 bytes in flight per thread" % (blocks, loads)}
+    return best
+
+
 def make_acts(torch, M, K, gen, seed_channels):
     import numpy as np
     from paper_2402_17764_amd import synth
@@ -318,10 +345,17 @@ def decode_workload(torch, B, synth, gen, stream, args, workload):
                            "traffic": measured_traffic(N, K, fused=not args.unfused)}
     dname, dK, dN = max(shapes, key=lambda s: s[1] * s[2])
     d = per_shape[dname]
+    for (name, K, N) in shapes:
+        floor = plain_read_floor(torch, [packed[(l, name)][0] for l in range(L)], N * K // 4, stream, args)
+        per_shape[name]["plain_read"] = floor
+        if floor:
+            per_shape[name]["frac_of_plain_read_rate"] = round(floor["us_per_launch"] / per_shape[name]["us_per_launch"], 4)
+    progress("%s: per-shape launches and the plain-read floor timed" % workload)
     roofline = {
         "bound": "hbm", "kernel": "linear_gemv16_2bit", "shape": "%s K=%d N=%d M=%d" % (dname, dK, dN, M),
         "achieved": d["GB/s"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": d["frac_hbm_peak"],
         "bytes_per_launch": d["bytes_per_launch"], "us_per_launch": d["us_per_launch"], "traffic": d["traffic"],
+        "plain_read_of_the_same_weights": d.get("plain_read"), "frac_of_plain_read_rate": d.get("frac_of_plain_read_rate"),
         "traffic_source": "profiles/hbm_traffic.json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this benchmark, "
                           "committed with the tree (not re-measured in this run)",
     }

@@ -2,8 +2,8 @@
 
     python -m paper_2402_17764_amd.read_floor
 
-Builds a plain streaming-read kernel (128-bit loads with the streaming cache policy, nothing else) into a library of its
-own under _build/, and for each decode layer of the benchmark's configurations replays a HIP graph of back-to-back
+Uses a plain streaming-read kernel (csrc/read_floor.hip: 128-bit loads with the streaming cache policy, nothing else; a
+library of its own next to the BitLinear one), and for each decode layer of the benchmark's configurations replays a HIP graph of back-to-back
 launches over distinct buffers of the layer's packed size -- the same way bench.py times the product -- for nine launch
 shapes (256 / 512 / 1024 workgroups of 512 threads x 2 / 4 / 8 loads in flight per thread), printing the fastest next to
 the product launches (bitnet_linear_fused on bf16 x, bitnet_linear on int8 x) timed in the same run.  The HBM peak is a
@@ -12,54 +12,27 @@ For the figures quoted in the design notes; nothing in the product path uses it.
 """
 import ctypes
 import os
-import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
-BUILD = os.path.join(HERE, "_build", "read_floor")
 
-SOURCE = r'''
-#include <hip/hip_runtime.h>
-#include <stdint.h>
-// every thread walks the buffer with a grid stride, kUnroll 16-byte loads in flight; the XOR keeps the loads alive
-template <int kUnroll>
-__global__ __launch_bounds__(512) void read_only(const uint4* __restrict__ p, int64_t nvec, uint32_t* __restrict__ out) {
-    typedef unsigned v4u __attribute__((ext_vector_type(4)));
-    const int64_t tid = (int64_t)blockIdx.x * 512 + threadIdx.x, nt = (int64_t)gridDim.x * 512;
-    uint32_t acc = 0;
-    int64_t i = tid;
-    for (; i + (kUnroll - 1) * nt < nvec; i += kUnroll * nt) {
-        v4u q[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) q[u] = __builtin_nontemporal_load(reinterpret_cast<const v4u*>(p + i + u * nt));
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) acc += q[u].x ^ q[u].y ^ q[u].z ^ q[u].w;
-    }
-    for (; i < nvec; i += nt) { const uint4 q = p[i]; acc += q.x ^ q.y ^ q.z ^ q.w; }
-    if (acc == 0x12345678u) out[0] = acc;
-}
-extern "C" int read_only_launch(const void* p, long long bytes, void* out, int blocks, int unroll, void* stream) {
-    const int64_t nvec = bytes / 16;
-    hipStream_t s = (hipStream_t)stream;
-    if (unroll == 2) hipLaunchKernelGGL(read_only<2>, dim3(blocks), dim3(512), 0, s, (const uint4*)p, nvec, (uint32_t*)out);
-    else if (unroll == 4) hipLaunchKernelGGL(read_only<4>, dim3(blocks), dim3(512), 0, s, (const uint4*)p, nvec, (uint32_t*)out);
-    else hipLaunchKernelGGL(read_only<8>, dim3(blocks), dim3(512), 0, s, (const uint4*)p, nvec, (uint32_t*)out);
-    return (int)hipGetLastError();
-}
-'''
+LIB = os.path.join(HERE, "libbitnet_read_floor.so")
 
 
-def build():
-    os.makedirs(BUILD, exist_ok=True)
-    src = os.path.join(BUILD, "read_floor.hip")
-    lib = os.path.join(BUILD, "libread_floor.so")
-    open(src, "w").write(SOURCE)
-    subprocess.check_call([os.environ.get("HIPCC", "/opt/rocm/bin/hipcc"), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
-                           "-shared", src, "-o", lib])
+def load():
+    """the read-only kernel's library (csrc/read_floor.hip), built by paper_2402_17764_amd.build; built here if it is missing"""
+    if not os.path.exists(LIB):
+        from paper_2402_17764_amd.build import build_read_floor
+        build_read_floor()
+    lib = ctypes.CDLL(LIB)
+    lib.read_only_launch.argtypes = [ctypes.c_void_p, ctypes.c_longlong, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
     return lib
+
+
+SHAPES = [(b, u) for b in (256, 512, 1024) for u in (2, 4, 8)]       # workgroups of 512 threads x loads in flight per thread
 
 
 def time_graph(torch, run, layers, replays=5):
@@ -91,8 +64,7 @@ def main():
     import torch
     from paper_2402_17764_amd import binding as B
     from paper_2402_17764_amd import synth
-    lib = ctypes.CDLL(build())
-    lib.read_only_launch.argtypes = [ctypes.c_void_p, ctypes.c_longlong, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    lib = load()
     sink = torch.zeros(4, dtype=torch.int32, device="cuda")
     gen = torch.Generator(device="cuda")
     gen.manual_seed(1)
@@ -109,12 +81,11 @@ def main():
                 packs.append(B.quantize_weights(W))
                 del W
             res = []
-            for blocks in (256, 512, 1024):
-                for unroll in (2, 4, 8):
-                    def run(s):
-                        for (p, _) in packs:
-                            lib.read_only_launch(p.data_ptr(), nbytes, sink.data_ptr(), blocks, unroll, s)
-                    res.append((time_graph(torch, run, layers), blocks, unroll))
+            for (blocks, unroll) in SHAPES:
+                def run(s):
+                    for (p, _) in packs:
+                        lib.read_only_launch(p.data_ptr(), nbytes, sink.data_ptr(), blocks, unroll, s)
+                res.append((time_graph(torch, run, layers), blocks, unroll))
             res.sort()
             x = torch.randn((1, K), device="cuda", generator=gen, dtype=torch.float32).to(torch.bfloat16)
             xq, sx = B.quantize_acts(x)
