@@ -143,12 +143,12 @@ def measured_traffic(N, K, fused=True):
 
 
 def plain_read_floor(torch, buffers, nbytes, stream, args):
-    """A kernel that only reads `nbytes` of each buffer (paper_2402_17764_amd/csrc/read_floor.hip, a library of its own),
+    """A kernel that only reads `nbytes` of each buffer (paper_2402_17764_amd/csrc/floors.hip, a library of its own),
     timed like the product: one HIP graph of back-to-back launches over the distinct buffers, best of five launch shapes.
     What the memory system gives a launch of this size when nothing else is done; None if that library is not built."""
     try:
-        from paper_2402_17764_amd import read_floor
-        lib = read_floor.load()
+        from paper_2402_17764_amd import floors
+        lib = floors.load()
     except Exception:                                     # measurement aid only: the benchmark line does not depend on it
         return None
     sink = torch.zeros(4, dtype=torch.int32, device="cuda")
@@ -167,6 +167,40 @@ def plain_read_floor(torch, buffers, nbytes, stream, args):
                     "frac_hbm_peak": round(nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
                     "launch": "%d workgroups x 512 threads, %d loads of 16 bytes in flight per thread" % (blocks, loads)}
     return best
+
+
+def mfma_only_floor(torch, xq, codes):
+    """A loop of v_mfma_i32_32x32x32_i8 from registers and nothing else (csrc/floors.hip: eight accumulator fragments per
+    wave, two workgroups of four waves per CU, as the prefill kernel's 128 x 256 tile), on operand registers filled from the
+    leg's own x_q and decoded weights (64 x code), and on all-zero operands: what the matrix pipe sustains on data like the
+    workload's -- the clock under MFMA load follows the operands' switching activity.  None if the library is not built."""
+    try:
+        from paper_2402_17764_amd import floors
+        lib = floors.load()
+    except Exception:
+        return None
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    w64 = (codes.reshape(-1)[: 1 << 24] * 64).contiguous()
+    xa = xq.reshape(-1)[: 1 << 24].contiguous()
+    zeros = torch.zeros(1 << 20, dtype=torch.int8, device="cuda")
+    blocks, iters = 512, 20000
+    ops = blocks * 4.0 * iters * 8 * 65536
+    out = {}
+    for tag, a, b in (("workload_operands", xa, w64), ("zero_operands", zeros, zeros)):
+        nbytes = min(a.numel(), b.numel())
+        s = torch.cuda.current_stream().cuda_stream
+        best = None
+        for rep in range(3):
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            lib.mfma_only_launch(a.data_ptr(), b.data_ptr(), nbytes, blocks, iters, sink.data_ptr(), s)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None or ms < best else best
+        out[tag + "_TOPS"] = round(ops / (best * 1e-3) / 1e12, 1)
+    return out
 
 
 def make_acts(torch, M, K, gen, seed_channels):
@@ -768,11 +802,16 @@ def gemm_one_m(torch, B, synth, gen, args, M, stream):
                                "kernel": B.linear_describe(M, N, K)["kernel"], "TOPS": round(ops / us * 1e-6, 1), "frac_int8_mfma_peak": round(ops / us * 1e-6 / INT8_MFMA_PEAK_TOPS, 4)}
         tot_ops += ops
         tot_us += us
+        if name == "gate_up":
+            res["mfma_only_loop"] = mfma_only_floor(torch, xq, B.unpack_weights(p, N, K))
         del p, x, xq, y
         torch.cuda.empty_cache()
     res["TOPS"] = round(tot_ops / tot_us * 1e-6, 1)
+    if res.get("mfma_only_loop"):
+        res["frac_of_mfma_only_loop"] = round(res["TOPS"] / res["mfma_only_loop"]["workload_operands_TOPS"], 4)
     res["roofline"] = {"bound": "mfma", "kernel": "linear_gemm_2bit", "workload": "13B-class layer set, M=%d" % M, "achieved": round(tot_ops / tot_us * 1e-6, 1),
-                       "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(tot_ops / tot_us * 1e-6 / INT8_MFMA_PEAK_TOPS, 4)}
+                       "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": round(tot_ops / tot_us * 1e-6 / INT8_MFMA_PEAK_TOPS, 4),
+                       "mfma_only_loop": res.get("mfma_only_loop"), "frac_of_mfma_only_loop": res.get("frac_of_mfma_only_loop")}
     return res
 
 

@@ -160,14 +160,14 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
-def build_read_floor(verbose: bool = False) -> str:
-    """libbitnet_read_floor.so: the read-only kernel that bench.py and read_floor.py time next to the product (no part of
-    the BitLinear library)."""
-    lib = os.path.join(HERE, "libbitnet_read_floor.so")
+def build_floors(verbose: bool = False) -> str:
+    """libbitnet_floors.so: the read-only and the MFMA-only kernel that bench.py and read_floor.py time next to the product
+    (no part of the BitLinear library)."""
+    lib = os.path.join(HERE, "libbitnet_floors.so")
     tmp = lib + ".tmp.%d" % os.getpid()
-    r = subprocess.run([HIPCC, *FLAGS, "-shared", os.path.join(CSRC, "read_floor.hip"), "-o", tmp], capture_output=True, text=True)
+    r = subprocess.run([HIPCC, *FLAGS, "-shared", os.path.join(CSRC, "floors.hip"), "-o", tmp], capture_output=True, text=True)
     if r.returncode != 0:
-        raise RuntimeError("hipcc failed on read_floor.hip:\n" + r.stderr)
+        raise RuntimeError("hipcc failed on floors.hip:\n" + r.stderr)
     os.replace(tmp, lib)
     if verbose:
         print("built", lib)
@@ -176,4 +176,4 @@ def build_read_floor(verbose: bool = False) -> str:
 
 if __name__ == "__main__":
     build_library(verbose=True)
-    build_read_floor(verbose=True)
+    build_floors(verbose=True)

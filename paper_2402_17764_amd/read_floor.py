@@ -2,7 +2,7 @@
 
     python -m paper_2402_17764_amd.read_floor
 
-Uses a plain streaming-read kernel (csrc/read_floor.hip: 128-bit loads with the streaming cache policy, nothing else; a
+Uses a plain streaming-read kernel (csrc/floors.hip: 128-bit loads with the streaming cache policy, nothing else; a
 library of its own next to the BitLinear one), and for each decode layer of the benchmark's configurations replays a HIP graph of back-to-back
 launches over distinct buffers of the layer's packed size -- the same way bench.py times the product -- for nine launch
 shapes (256 / 512 / 1024 workgroups of 512 threads x 2 / 4 / 8 loads in flight per thread), printing the fastest next to
@@ -10,7 +10,6 @@ the product launches (bitnet_linear_fused on bf16 x, bitnet_linear on int8 x) ti
 rate; a launch of a few megabytes also pays for starting and ending, and this is how much of that no kernel avoids.
 For the figures quoted in the design notes; nothing in the product path uses it.
 """
-import ctypes
 import os
 import sys
 
@@ -18,22 +17,6 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
-
-LIB = os.path.join(HERE, "libbitnet_read_floor.so")
-
-
-def load():
-    """the read-only kernel's library (csrc/read_floor.hip), built by paper_2402_17764_amd.build; built here if it is missing"""
-    if not os.path.exists(LIB):
-        from paper_2402_17764_amd.build import build_read_floor
-        build_read_floor()
-    lib = ctypes.CDLL(LIB)
-    lib.read_only_launch.argtypes = [ctypes.c_void_p, ctypes.c_longlong, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
-    return lib
-
-
-SHAPES = [(b, u) for b in (256, 512, 1024) for u in (2, 4, 8)]       # workgroups of 512 threads x loads in flight per thread
-
 
 def time_graph(torch, run, layers, replays=5):
     st = torch.cuda.Stream()
@@ -63,8 +46,8 @@ def time_graph(torch, run, layers, replays=5):
 def main():
     import torch
     from paper_2402_17764_amd import binding as B
-    from paper_2402_17764_amd import synth
-    lib = load()
+    from paper_2402_17764_amd import floors, synth
+    lib = floors.load()
     sink = torch.zeros(4, dtype=torch.int32, device="cuda")
     gen = torch.Generator(device="cuda")
     gen.manual_seed(1)
@@ -81,7 +64,7 @@ def main():
                 packs.append(B.quantize_weights(W))
                 del W
             res = []
-            for (blocks, unroll) in SHAPES:
+            for (blocks, unroll) in floors.READ_SHAPES:
                 def run(s):
                     for (p, _) in packs:
                         lib.read_only_launch(p.data_ptr(), nbytes, sink.data_ptr(), blocks, unroll, s)
