@@ -165,9 +165,10 @@ def build_floors(verbose: bool = False) -> str:
     (no part of the BitLinear library)."""
     lib = os.path.join(HERE, "libbitnet_floors.so")
     tmp = lib + ".tmp.%d" % os.getpid()
-    r = subprocess.run([HIPCC, *FLAGS, "-shared", os.path.join(CSRC, "floors.hip"), "-o", tmp], capture_output=True, text=True)
+    r = subprocess.run([HIPCC, *FLAGS, "-shared", os.path.join(CSRC, "floors.hip"), os.path.join(CSRC, "prefill_ladder.hip"), "-o", tmp],
+                       capture_output=True, text=True)
     if r.returncode != 0:
-        raise RuntimeError("hipcc failed on floors.hip:\n" + r.stderr)
+        raise RuntimeError("hipcc failed on floors.hip / prefill_ladder.hip:\n" + r.stderr)
     os.replace(tmp, lib)
     if verbose:
         print("built", lib)

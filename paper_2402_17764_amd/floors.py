@@ -1,5 +1,6 @@
-"""Loader of libbitnet_floors.so (csrc/floors.hip): a read-only kernel and an MFMA-only kernel, the yardsticks that bench.py
-and read_floor.py time next to the product kernels.  Measurement aids; no part of the BitLinear library."""
+"""Loader of libbitnet_floors.so (csrc/floors.hip, csrc/prefill_ladder.hip): a read-only kernel, an MFMA-only kernel and the
+prefill K loop built up ingredient by ingredient -- the yardsticks that bench.py, read_floor.py and prefill_ladder.py time
+next to the product kernels.  Measurement aids; no part of the BitLinear library."""
 import ctypes
 import os
 
@@ -18,4 +19,6 @@ def load():
     lib.read_only_launch.argtypes = [ctypes.c_void_p, ctypes.c_longlong, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
     lib.mfma_only_launch.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_longlong, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
                                      ctypes.c_void_p]
+    lib.prefill_ladder_launch.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_longlong, ctypes.c_int, ctypes.c_int,
+                                          ctypes.c_void_p, ctypes.c_longlong, ctypes.c_void_p, ctypes.c_void_p]
     return lib
