@@ -120,6 +120,9 @@ typedef enum bitnet_kernel {
        added through LDS: same result): the form for grids that leave a CU with one workgroup */
     BITNET_KERNEL_GEMM_96x128_K2 = 0x1B1,
     BITNET_KERNEL_GEMM_64x256_K2 = 0x1A2,
+    /* eight waves in two row groups on one token tile: tiles of 512 weight rows whose activation stages both groups
+       read (less traffic into the CU per multiply); one workgroup per CU */
+    BITNET_KERNEL_GEMM_128x512 = 0x14A,
     /* bitnet_linear_ws only: the K steps split over 2, 4 or 8 workgroups per tile (prefill kernel; where the batched-decode kernels serve the shape,
        the batched-decode kernels) */
     BITNET_KERNEL_GEMM_SPLITK_2 = 0x202,
@@ -271,7 +274,7 @@ bitnet_status bitnet_linear_variant(const int8_t* xq, const float* sx, const voi
  *     batched_decode         5 ... 512 tokens: token tiles of 16, row blocks per wave, row slots, K groups, prefetch
  *     batched_decode_loader  depth, LDS lookahead (the second form has a wave that only copies activations)
  *     prefill                tile tokens, tile rows, and 2 as a third parameter for the eight-wave form with two
- *                            K groups; grid y = split-K factor
+ *                            K groups (512 tile rows: the eight-wave form with two row groups); grid y = split-K factor
  *     reference, trit5_decode, trit5_reference: no parameters
  *   5-trit weights, more than 16 tokens and a workspace that holds the 2-bit copy (bitnet_linear_workspace_format):
  *   the plan of the 2-bit launch that follows the repacking pass, with " repack=trit5_to_2bit" appended

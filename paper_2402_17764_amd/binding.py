@@ -25,6 +25,7 @@ ENTRY_FFN_GATE_UP, ENTRY_FFN_GATE_UP_NORM = 4, 5
 KERNEL_GEMM_SPLITK = {2: 0x202, 4: 0x204, 8: 0x208}       # bitnet_linear_ws only
 KERNEL_GEMM_TILES = {(128, 256): 0x142, (96, 256): 0x132, (64, 256): 0x122, (128, 128): 0x141, (96, 128): 0x131, (64, 128): 0x121}
 KERNEL_GEMM_TILES_K2 = {(96, 128): 0x1B1, (64, 256): 0x1A2}      # eight waves in two K groups
+KERNEL_GEMM_TILES_WIDE = {(128, 512): 0x14A}      # eight waves in two row groups
 
 SYMBOLS = [
     "bitnet_version", "bitnet_status_string", "bitnet_packed_bytes", "bitnet_quantize_weights_workspace",

@@ -206,9 +206,11 @@ static bitnet_status linear_any(const int8_t* xq, const float* sx, const void* p
         else which = BITNET_KERNEL_REFERENCE;
     }
     if (((int)which & ~0xFF) == 0x100) {               // prefill kernel, tile forced: 0x100 | two K groups << 7 | fm << 4 | fn
-        const int fm = ((int)which >> 4) & 0x7, fn = (int)which & 0xF, kg = 1 + (((int)which >> 7) & 1);
+        const int fm = ((int)which >> 4) & 0x7, fn = (int)which & 0x7, wide = ((int)which >> 3) & 1;
+        const int kg = wide ? 3 : 1 + (((int)which >> 7) & 1);          // 2: two K groups, 3: two row groups
         if (fm < 2 || fm > 4 || fn < 1 || fn > 2 || !bitnet::gemm_supports(M, N, K, xq)) return BITNET_ERR_KERNEL;
         if (kg == 2 && !((fm == 3 && fn == 1) || (fm == 2 && fn == 2))) return BITNET_ERR_KERNEL;
+        if (wide && (fn != 2 || fm != 4 || (((int)which >> 7) & 1))) return BITNET_ERR_KERNEL;
         return from_hip(bitnet::launch_linear_gemm_2bit_shape(fm, fn, kg, xq, sx, packed, gamma, gstride, M, N, K, y, yt, s));
     }
     switch (which) {

@@ -118,8 +118,8 @@ hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void
                                    hipStream_t stream, void* workspace = nullptr, size_t workspace_bytes = 0,
                                    int force_splits = 0, LaunchPlan* plan = nullptr);
 // the same with the tile forced: 32 * fm tokens x 128 * fn weight rows, fm in 2 .. 4, fn in 1 .. 2, kg = 1, or kg = 2 (eight waves in
-// two K groups) with (fm, fn) = (3, 1) or (2, 2) and one split (hipErrorInvalidValue otherwise); splits > 1 needs a
-// workspace of splitk_workspace_bytes(M, N, splits)
+// two K groups) with (fm, fn) = (3, 1) or (2, 2) and one split, or kg = 3 (eight waves in two row groups: tiles of 128 x 512)
+// with (fm, fn) = (4, 2) (hipErrorInvalidValue otherwise); splits > 1 needs a workspace of splitk_workspace_bytes(M, N, splits)
 hipError_t launch_linear_gemm_2bit_shape(int fm, int fn, int kg, const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                          int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream,
                                          int splits = 1, void* workspace = nullptr, LaunchPlan* plan = nullptr);

@@ -24,6 +24,10 @@
 //     eight waves: two groups of four, each contracting half of the K steps through activation stages of its own, the
 //     second group's accumulators added through LDS at the end -- the two waves per SIMD that two workgroups per CU
 //     provide elsewhere, without a second launch;
+//   * for grids of many 128 x 256 tiles whose count suits the chip, a form with eight waves in two row groups on one token
+//     tile (128 x 512): both groups read the same activation stages, so the CU fetches a third less per MFMA than two
+//     separate workgroups do -- the K loop's losses are waves held at the issue of their loads while the vector-memory
+//     queues are full, and they shrink with the bytes a CU pulls in;
 //   * the epilogue rescales in registers, transposes each 32 x 64 fragment row through LDS and writes
 //     whole 16-byte pieces of output rows;
 //   * tile order: consecutive workgroups take consecutive token tiles of the same weight tile, so the
@@ -56,10 +60,11 @@ constexpr int gemm_stage_bytes(int fm) { return fm * 32 * 256; }            // o
 // ... and behind the area through which a second K group (kg == 2) hands over its accumulators: fm * fn * 16 registers
 // of 256 threads
 constexpr int gemm_max3(int a, int b, int c) { return a > b ? (a > c ? a : c) : (b > c ? b : c); }
-constexpr int gemm_scale_offset(int fm, int fn, int kg) {
-    return gemm_max3(kg * 2 * gemm_stage_bytes(fm), 4 * 32 * kGemmPitch32, (kg - 1) * fm * fn * 16 * 4 * kGemmThreads);
+// ... and, with two row groups (ng == 2: eight waves on one token tile), behind eight waves' staging areas
+constexpr int gemm_scale_offset(int fm, int fn, int kg, int ng = 1) {
+    return gemm_max3(kg * 2 * gemm_stage_bytes(fm), 4 * ng * 32 * kGemmPitch32, (kg - 1) * fm * fn * 16 * 4 * kGemmThreads);
 }
-constexpr int gemm_lds_bytes(int fm, int fn, int kg) { return gemm_scale_offset(fm, fn, kg) + fm * 32 * 4; }
+constexpr int gemm_lds_bytes(int fm, int fn, int kg, int ng = 1) { return gemm_scale_offset(fm, fn, kg, ng) + fm * 32 * 4; }
 
 __device__ inline uint32_t gemm_quad_word(const uint4& q, int j) { return j == 0 ? q.x : j == 1 ? q.y : j == 2 ? q.z : q.w; }
 
@@ -76,6 +81,7 @@ struct GemmOutCtx {
     int M;
     int64_t N;
     int row0, bn, wave, lane, vec_store;
+    int slot;               // which staging area: the wave's number in the workgroup
 };
 
 // A lane holds, per 32 x 32 fragment, 16 tokens (8 (v >> 2) + 4 (lane >> 5) + (v & 3)) of weight row
@@ -98,7 +104,7 @@ __device__ inline void gemm_epilogue(v16i (&acc)[kFM][kFN], const GemmOutCtx& c)
     constexpr int rows_per_pass = 64 / lanes_per_row;
     const int am = c.lane & 31, kg = c.lane >> 5;
     const int wn = c.wave;
-    char* stage_out = c.lds + c.wave * (32 * kGemmPitch32);
+    char* stage_out = c.lds + c.slot * (32 * kGemmPitch32);
     const int64_t n_wave = (int64_t)c.bn * (128 * kFN) + wn * (32 * kFN);
     // with one gamma per row block the lane's weight row (am of fragment fn) picks its own; otherwise the
     // factor is 1 and the staged scale already carries gamma
@@ -169,8 +175,9 @@ __device__ inline void gemm_epilogue(v16i (&acc)[kFM][kFN], const GemmOutCtx& c)
     }
 }
 
-// One output tile of 32 * kFM tokens (first token row0) x 128 * kFN weight rows (tile bn), by kKG groups of four waves.
-template <int kFM, int kFN, int kKG>
+// One output tile of 32 * kFM tokens (first token row0) x 128 * kFN * kNG weight rows (tile bn), by kKG * kNG groups of
+// four waves: kKG > 1 splits the K steps over the groups, kNG > 1 the weight rows (one of the two is 1).
+template <int kFM, int kFN, int kKG, int kNG>
 __device__ __forceinline__ void gemm_tile(
         const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
         const float* __restrict__ gamma, int gstride, int M, int64_t N, int64_t K, int Kq, int RB, int row0, int bn,
@@ -180,9 +187,10 @@ __device__ __forceinline__ void gemm_tile(
     extern __shared__ uint4 smem[];
     constexpr int kGemmBM = 32 * kFM;
     constexpr int kGemmStageBytes = gemm_stage_bytes(kFM);
-    constexpr int kCopies = 2 * kFM;                // 1 KiB wave-loads (4 token rows) per wave and stage
+    constexpr int kCopies = 2 * kFM / kNG;          // 1 KiB wave-loads (4 token rows) per wave and stage
+    static_assert(kKG == 1 || kNG == 1, "groups split either the K steps or the weight rows");
     char* lds = reinterpret_cast<char*>(smem);
-    float* scale_lds = reinterpret_cast<float*>(lds + gemm_scale_offset(kFM, kFN, kKG));
+    float* scale_lds = reinterpret_cast<float*>(lds + gemm_scale_offset(kFM, kFN, kKG, kNG));
 
     const int lane = threadIdx.x & 63;
     const int wave_all = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: LDS-DMA targets need no per-step broadcast
@@ -190,6 +198,11 @@ __device__ __forceinline__ void gemm_tile(
     const int wave = wave_all & 3;                      // the wave's place in its group
     const int wn = wave;
     char* glds = lds + grp * 2 * kGemmStageBytes;       // the group's two activation stages
+    // Row groups: both contract every K step from the same activation stages (each of the eight waves copies an
+    // eighth of a stage), the second on the next 128 * kFN weight rows -- half the activation traffic into the CU
+    // per MFMA of two separate workgroups.
+    const int copier = kNG > 1 ? wave_all : wave;
+    bn = bn * kNG + (kNG > 1 ? wave_all >> 2 : 0);
     const int steps = (Kq + 3) >> 2;
     const int full_steps = (int)(K >> 8);           // steps whose 256 columns all exist
     const int tail_quads = 16 * (Kq - 4 * (steps - 1));
@@ -210,7 +223,7 @@ __device__ __forceinline__ void gemm_tile(
     uint32_t xoff[kCopies];
 #pragma unroll
     for (int t = 0; t < kCopies; ++t) {
-        const int row = wave * (4 * kCopies) + t * 4 + cp_row;
+        const int row = copier * (4 * kCopies) + t * 4 + cp_row;
         xoff[t] = (uint32_t)min(row, rows_here - 1) * (uint32_t)K + (uint32_t)((cp_slot ^ (row & 15)) << 4);
     }
     // ---- A operand, LDS -> registers
@@ -246,7 +259,7 @@ __device__ __forceinline__ void gemm_tile(
         char* dst_stage = glds + stage * kGemmStageBytes;
 #pragma unroll
         for (int t = 0; t < kCopies; ++t)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (__attribute__((address_space(3))) void*)(dst_stage + (wave * (4 * kCopies) + t * 4) * 256),
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (__attribute__((address_space(3))) void*)(dst_stage + (copier * (4 * kCopies) + t * 4) * 256),
                                                      16, xoff[t], 0, 0, 0);
     };
     // For the weights a raw buffer per step as well: one whole step of the packed layout (RB KiB), the lane's
@@ -381,7 +394,7 @@ __device__ __forceinline__ void gemm_tile(
     }
 
     // ---- epilogue: one instantiation per output type, chosen once ---------------------------------------
-    const GemmOutCtx ctx{lds, scale_lds, y, gamma, gstride, RB, M, N, row0, bn, wave, lane, vec_store};
+    const GemmOutCtx ctx{lds, scale_lds, y, gamma, gstride, RB, M, N, row0, bn, wave, lane, vec_store, kNG > 1 ? wave_all : wave};
     if (yt == OutType::BF16) gemm_epilogue<OutType::BF16, kFM, kFN>(acc, ctx);
     else if (yt == OutType::F32) gemm_epilogue<OutType::F32, kFM, kFN>(acc, ctx);
     else gemm_epilogue<OutType::I32, kFM, kFN>(acc, ctx);
@@ -395,8 +408,8 @@ constexpr int gemm_blocks_per_cu(int fm, int fn) { return fn == 1 ? (fm == 2 ? 4
 
 // blockIdx.y selects a split of the K steps (split-K: every split stores its int32 partial accumulators, [M][N] each,
 // one after the other at y; a second kernel adds them up and rescales).  One split: the whole product, stored as yt.
-template <int kFM, int kFN, int kKG = 1>
-__global__ __launch_bounds__(kGemmThreads * kKG, kKG > 1 ? 1 : gemm_blocks_per_cu(kFM, kFN)) void linear_gemm_2bit(
+template <int kFM, int kFN, int kKG = 1, int kNG = 1>
+__global__ __launch_bounds__(kGemmThreads * kKG * kNG, kKG * kNG > 1 ? 1 : gemm_blocks_per_cu(kFM, kFN)) void linear_gemm_2bit(
         const int8_t* __restrict__ xq, const float* __restrict__ sx, const uint4* __restrict__ packed,
         const float* __restrict__ gamma, int gstride, int M, int64_t N, int64_t K, int Kq, int RB, int tiles_m,
         int steps_per_split, void* __restrict__ y, OutType yt, int vec_store) {
@@ -405,7 +418,7 @@ __global__ __launch_bounds__(kGemmThreads * kKG, kKG > 1 ? 1 : gemm_blocks_per_c
     const int step0 = blockIdx.y * steps_per_split;
     const int step1 = min(steps, step0 + steps_per_split);
     void* yp = static_cast<char*>(y) + (int64_t)blockIdx.y * M * N * 4;        // blockIdx.y > 0 only with int32 partials
-    gemm_tile<kFM, kFN, kKG>(xq, sx, packed, gamma, gstride, M, N, K, Kq, RB, (b % tiles_m) * (32 * kFM), b / tiles_m, step0, step1,
+    gemm_tile<kFM, kFN, kKG, kNG>(xq, sx, packed, gamma, gstride, M, N, K, Kq, RB, (b % tiles_m) * (32 * kFM), b / tiles_m, step0, step1,
                         yp, yt, vec_store);
 }
 
@@ -456,19 +469,19 @@ bool gemm_supports(int64_t M, int64_t N, int64_t K, const void* xq) {
     return M >= 1 && K % 16 == 0 && reinterpret_cast<uintptr_t>(xq) % 16 == 0 && ceil_div(N, kRowsPerBlock) < ((int64_t)1 << 21);
 }
 
-template <int kFM, int kFN, int kKG = 1>
+template <int kFM, int kFN, int kKG = 1, int kNG = 1>
 static hipError_t launch_gemm_tiles(const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                     int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt,
                                     hipStream_t stream, int splits = 1, void* workspace = nullptr, LaunchPlan* plan = nullptr) {
     if (!plan) {
         static RaisedFlags raised = {};
-        const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(linear_gemm_2bit<kFM, kFN, kKG>), gemm_lds_bytes(kFM, kFN, kKG), raised);
+        const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(linear_gemm_2bit<kFM, kFN, kKG, kNG>), gemm_lds_bytes(kFM, kFN, kKG, kNG), raised);
         if (e != hipSuccess) return e;
     }
     const int Kq = (int)ceil_div(K, kColsPerQuad);
     const int RB = (int)ceil_div(N, kRowsPerBlock);
     const int tiles_m = (int)ceil_div(M, 32 * kFM);
-    const int64_t tiles_n = ceil_div(N, 128 * kFN);
+    const int64_t tiles_n = ceil_div(N, 128 * kFN * kNG);
     const int steps = (int)ceil_div(K, 256);
     if (splits > steps) splits = steps;
     const int sps = (int)ceil_div(steps, splits);
@@ -479,12 +492,13 @@ static hipError_t launch_gemm_tiles(const int8_t* xq, const float* sx, const voi
     const size_t esz = ot == OutType::BF16 ? 2 : 4;
     const int vec_store = (reinterpret_cast<uintptr_t>(out) % 16 == 0) && ((N * esz) % 16 == 0);
     if (plan) {
-        if (kKG > 1) plan->set("prefill", {32 * kFM, 128 * kFN, kKG}, (unsigned)(tiles_m * tiles_n), (unsigned)splits, kGemmThreads * kKG, gemm_lds_bytes(kFM, kFN, kKG), splits);
+        if (kNG > 1) plan->set("prefill", {32 * kFM, 128 * kFN * kNG}, (unsigned)(tiles_m * tiles_n), (unsigned)splits, kGemmThreads * kNG, gemm_lds_bytes(kFM, kFN, 1, kNG), splits);
+        else if (kKG > 1) plan->set("prefill", {32 * kFM, 128 * kFN, kKG}, (unsigned)(tiles_m * tiles_n), (unsigned)splits, kGemmThreads * kKG, gemm_lds_bytes(kFM, kFN, kKG), splits);
         else plan->set("prefill", {32 * kFM, 128 * kFN}, (unsigned)(tiles_m * tiles_n), (unsigned)splits, kGemmThreads, gemm_lds_bytes(kFM, kFN, 1), splits);
         return hipSuccess;
     }
-    hipLaunchKernelGGL((linear_gemm_2bit<kFM, kFN, kKG>), dim3((unsigned)(tiles_m * tiles_n), (unsigned)splits), dim3(kGemmThreads * kKG),
-                       gemm_lds_bytes(kFM, kFN, kKG), stream, xq, sx, static_cast<const uint4*>(packed), gamma, gstride, (int)M, N, K, Kq, RB,
+    hipLaunchKernelGGL((linear_gemm_2bit<kFM, kFN, kKG, kNG>), dim3((unsigned)(tiles_m * tiles_n), (unsigned)splits), dim3(kGemmThreads * kKG * kNG),
+                       gemm_lds_bytes(kFM, kFN, kKG, kNG), stream, xq, sx, static_cast<const uint4*>(packed), gamma, gstride, (int)M, N, K, Kq, RB,
                        tiles_m, sps, out, ot, vec_store);
     if (split)
         return launch_splitk_reduce(static_cast<const int32_t*>(workspace), splits, sx, gamma, gstride, 1, M, N, y, yt, stream);
@@ -492,14 +506,16 @@ static hipError_t launch_gemm_tiles(const int8_t* xq, const float* sx, const voi
 }
 
 // tile shape forced by the caller (tuning and tests); fm in 2 .. 4, fn in 1 .. 2; kg 1, or 2 (two K groups per workgroup:
-// 96 x 128 and 64 x 256 tiles only, one launch only); splits > 1: split-K through `workspace` (splits * M * N int32)
+// 96 x 128 and 64 x 256 tiles only, one launch only), or 3 (two row groups per workgroup, 32 fm x 512 tiles: fn == 2
+// and fm == 4 only); splits > 1: split-K through `workspace` (splits * M * N int32)
 hipError_t launch_linear_gemm_2bit_shape(int fm, int fn, int kg, const int8_t* xq, const float* sx, const void* packed, const float* gamma,
                                          int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream,
                                          int splits, void* workspace, LaunchPlan* plan) {
-#define GEMM_SHAPE(FM_, FN_, KG_) if (fm == FM_ && fn == FN_ && kg == KG_) return launch_gemm_tiles<FM_, FN_, KG_>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, splits, workspace, plan)
+#define GEMM_SHAPE(FM_, FN_, KG_) if (fm == FM_ && fn == FN_ && kg == KG_) return launch_gemm_tiles<FM_, FN_, KG_ == 2 ? 2 : 1, KG_ == 3 ? 2 : 1>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, splits, workspace, plan)
     if (kg == 2 && splits > 1) return hipErrorInvalidValue;
     GEMM_SHAPE(2, 1, 1); GEMM_SHAPE(3, 1, 1); GEMM_SHAPE(4, 1, 1); GEMM_SHAPE(2, 2, 1); GEMM_SHAPE(3, 2, 1); GEMM_SHAPE(4, 2, 1);
     GEMM_SHAPE(3, 1, 2); GEMM_SHAPE(2, 2, 2);
+    GEMM_SHAPE(4, 2, 3);
 #undef GEMM_SHAPE
     return hipErrorInvalidValue;
 }
@@ -565,6 +581,16 @@ hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void
             const double cost = sh.fixed + (double)ceil_div(steps_total, (int64_t)2) * sh.per_iteration * (1.0 + 0.2 * fill * fill);
             if (cost < 0.96 * best_cost) { fm = sh.fm; fn = sh.fn; best_splits = 1; best_kg = 2; best_cost = cost; }
         }
+    }
+    // Two row groups on one token tile (128 x 512, eight waves, one workgroup per CU): 2.70 us per K step, against 2.9 for
+    // two 128 x 256 workgroups on a CU, because the CU fetches the activations once for both.  Rounds are whole here --
+    // a CU cannot take half a tile while the last round drains -- so it wins where the count of tiles suits 256 CUs
+    // (13B-class QKV at 2048 tokens, 480 tiles: 127 -> 116 us) and loses where it does not (gate/up there, 864 tiles:
+    // 200 -> 220 us); not considered below a full round, where four-wave workgroups spread over more CUs.
+    if (force_splits <= 0) {
+        const int64_t tiles = ceil_div(M, 128) * ceil_div(N, 512);
+        const double cost = 6.0 + (double)steps_total * (double)ceil_div(tiles, (int64_t)256) * 2.70;
+        if (tiles >= 256 && cost < 0.96 * best_cost) { fm = 4; fn = 2; best_splits = 1; best_kg = 3; best_cost = cost; }
     }
     return launch_linear_gemm_2bit_shape(fm, fn, best_kg, xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, best_splits, workspace, plan);
 }

@@ -101,7 +101,11 @@ def test_prefill_tiles_follow_the_measured_cases():
     """The cases the cost model's comment quotes, and its limits: big grids stay on the widest tile, small ones take
     narrow tiles so that CUs are not left idle, split-K only with a workspace, a long K and few tiles."""
     assert B.linear_describe(2048, 27648, 5120)["params"] == [128, 256]
-    assert B.linear_describe(4096, 57344, 8192)["params"] == [128, 256]
+    # many tiles whose count suits 256 CUs: eight waves in two row groups on one token tile (measured: 127 -> 116 us,
+    # 1231 -> 1207 us); where whole rounds of such tiles fit badly (864 tiles: 200 -> 220 us) the four-wave tiles stay
+    assert B.linear_describe(2048, 15360, 5120)["params"] == [128, 512]
+    assert B.linear_describe(4096, 57344, 8192)["params"] == [128, 512]
+    assert B.linear_describe(512, 27648, 5120)["params"] == [128, 256]            # 216 such tiles: less than a round
     # one workgroup per CU at most: eight waves in two K groups (measured: 19.2 -> 18.1 us, 39.7 -> 37.5 us)
     assert B.linear_describe(512, 5120, 5120)["params"] == [96, 128, 2]
     assert B.linear_describe(520, 5120, 5120)["params"] == [96, 128, 2]
@@ -110,13 +114,15 @@ def test_prefill_tiles_follow_the_measured_cases():
     assert B.linear_describe(768, 5120, 5120)["params"] == [64, 128]              # 480 tiles: more than one round
     assert B.linear_describe(512, 5120, 5120, workspace_bytes=8 * 512 * 5120 * 4)["params"] == [96, 128, 2]
     for (M, N, K) in [(257, 3200, 3200), (300, 9600, 3200), (1024, 4096, 11008), (2048, 8192, 28672), (4096, 3200, 8640),
-                      (512, 5120, 13824), (300, 8192, 28672)]:
+                      (512, 5120, 13824), (300, 8192, 28672), (2048, 15360, 5120), (4096, 8192, 28672)]:
         d = B.linear_describe(M, N, K)
         tm, tn = d["params"][:2]
-        groups = d["params"][2] if len(d["params"]) == 3 else 1
+        groups = d["params"][2] if len(d["params"]) == 3 else 2 if tn == 512 else 1
         assert d["kernel"] == "prefill" and d["splits"] == 1 and d["block"] == 256 * groups
         assert d["grid"] == (ceil_div(M, tm) * ceil_div(N, tn), 1)
-        if groups == 2:
+        if tn == 512:
+            assert d["grid"][0] >= 256 and d["lds"] <= LDS_PER_CU                 # whole rounds of one workgroup per CU
+        elif groups == 2:
             assert d["grid"][0] <= 256 and d["lds"] <= LDS_PER_CU                 # one round of one workgroup per CU
         else:
             assert d["lds"] <= LDS_PER_CU // 2                  # two workgroups per CU
@@ -212,9 +218,11 @@ def test_every_launch_shape_is_within_the_hardware_limits():
         else:
             assert d["kernel"] == "prefill", (M, N, K, d)
             tm, tn = d["params"][:2]
-            groups = d["params"][2] if len(d["params"]) == 3 else 1
+            groups = d["params"][2] if len(d["params"]) == 3 else 2 if tn == 512 else 1
             assert d["grid"][0] == ceil_div(M, tm) * ceil_div(N, tn) and d["block"] == 256 * groups and groups in (1, 2)
-            if groups == 2:                  # one workgroup per CU, one round, never together with a split through memory
+            if tn == 512:                    # two row groups: one workgroup per CU, at least a whole round of them
+                assert d["grid"][0] >= 256 and d["splits"] == 1 and tm == 128, (M, N, K, d)
+            elif groups == 2:                # one workgroup per CU, one round, never together with a split through memory
                 assert d["grid"][0] <= 256 and d["splits"] == 1 and (tm, tn) in ((96, 128), (64, 256)), (M, N, K, d)
     assert kernels == {"reference", "decode", "batched_decode", "batched_decode_loader", "prefill"}
 

@@ -486,10 +486,12 @@ def test_linear_gemm_kernel(gpu_lib, M, N, K):
 # every workgroup tile of the prefill kernel (tokens x weight rows), each on shapes with several tiles and ragged
 # tails in M, N and K, one of them smaller than a single tile
 # (a third entry 2: the eight-wave form with two K groups -- the shapes give its groups 3 + 2, 2 + 1, 1 + 0 and 1 + 1
-# K steps, the last one partial)
-@pytest.mark.parametrize("tile", [(128, 256), (96, 256), (64, 256), (128, 128), (96, 128), (64, 128), (96, 128, 2), (64, 256, 2)])
+# K steps, the last one partial; 512 rows: the eight-wave form with two row groups -- the shapes give its second group
+# whole, ragged and empty row ranges)
+@pytest.mark.parametrize("tile", [(128, 256), (96, 256), (64, 256), (128, 128), (96, 128), (64, 128), (96, 128, 2), (64, 256, 2), (128, 512)])
 def test_linear_gemm_every_tile_shape(gpu_lib, tile):
-    kern = gpu_lib.KERNEL_GEMM_TILES[tile] if len(tile) == 2 else gpu_lib.KERNEL_GEMM_TILES_K2[tile[:2]]
+    kern = (gpu_lib.KERNEL_GEMM_TILES_K2[tile[:2]] if len(tile) == 3 else gpu_lib.KERNEL_GEMM_TILES_WIDE[tile] if tile[1] == 512
+            else gpu_lib.KERNEL_GEMM_TILES[tile])
     for (M, N, K) in [(300, 520, 1040), (257, 1000, 528), (100, 40, 16), (129, 130, 272), (65, 2100, 80)]:
         say("linear gemm tile %s M=%d N=%d K=%d" % ("x".join(map(str, tile)), M, N, K))
         _run_linear_case(gpu_lib, M, N, K, [kern], layer=(M + tile[0] + tile[1]) % 11, bf16_acts=(M % 2 == 1))
@@ -1196,7 +1198,7 @@ def test_segmented_gamma_matches_oracle(gpu_lib, M, K, seg_rows):
     xq, sx = gpu_lib.quantize_acts(dev(x))
     kernels = [gpu_lib.KERNEL_AUTO, gpu_lib.KERNEL_REFERENCE, gpu_lib.KERNEL_GEMM,
                gpu_lib.KERNEL_GEMM_TILES[(96, 128)], gpu_lib.KERNEL_GEMM_TILES[(64, 128)], gpu_lib.KERNEL_GEMM_TILES[(128, 256)],
-               gpu_lib.KERNEL_GEMM_TILES_K2[(96, 128)], gpu_lib.KERNEL_GEMM_TILES_K2[(64, 256)]]
+               gpu_lib.KERNEL_GEMM_TILES_K2[(96, 128)], gpu_lib.KERNEL_GEMM_TILES_K2[(64, 256)], gpu_lib.KERNEL_GEMM_TILES_WIDE[(128, 512)]]
     if M <= 64:
         kernels.append(gpu_lib.KERNEL_GEMV)
     for kern in kernels:
@@ -1388,7 +1390,7 @@ def test_outputs_do_not_spill_past_their_buffers(gpu_lib):
     assert bool((xq_big[M * K:] == 0x55).all())
     y_big = torch.full((M * N + 16,), 7.0, dtype=torch.float32, device="cuda")
     for kern in ((gpu_lib.KERNEL_REFERENCE, gpu_lib.KERNEL_GEMV, gpu_lib.KERNEL_GEMM) + tuple(gpu_lib.KERNEL_GEMM_TILES.values()) +
-                 tuple(gpu_lib.KERNEL_GEMM_TILES_K2.values())):
+                 tuple(gpu_lib.KERNEL_GEMM_TILES_K2.values()) + tuple(gpu_lib.KERNEL_GEMM_TILES_WIDE.values())):
         gpu_lib.linear(xq, sx, packed, gamma, N, y=y_big[: M * N].view(M, N), kernel=kern)
         assert bool((y_big[M * N:] == 7.0).all())
 
