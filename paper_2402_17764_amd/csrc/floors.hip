@@ -22,7 +22,9 @@ __global__ __launch_bounds__(512) void read_only(const uint4* __restrict__ p, in
     for (; i < nvec; i += nt) { const uint4 q = p[i]; acc += q.x ^ q.y ^ q.z ^ q.w; }
     if (acc == 0x12345678u) out[0] = acc;
 }
+// -3: a null pointer, no whole 16-byte vector, no workgroup (checked before anything is launched)
 extern "C" int read_only_launch(const void* p, long long bytes, void* out, int blocks, int unroll, void* stream) {
+    if (!p || !out || bytes < 16 || blocks < 1) return -3;
     const int64_t nvec = bytes / 16;
     hipStream_t s = (hipStream_t)stream;
     if (unroll == 2) hipLaunchKernelGGL(read_only<2>, dim3(blocks), dim3(512), 0, s, (const uint4*)p, nvec, (uint32_t*)out);
@@ -73,6 +75,7 @@ __global__ __launch_bounds__(256, 2) void mfma_only(const v4i* __restrict__ a_sr
 }
 // iters (even) rounds of eight MFMAs per wave: 2 * 32 * 32 * 32 * 8 * iters operations per wave, four waves per workgroup
 extern "C" int mfma_only_launch(const void* a_src, const void* b_src, long long bytes, int blocks, int iters, void* out, void* stream) {
+    if (!a_src || !b_src || !out || bytes < 16 || blocks < 1 || iters < 1) return -3;
     hipLaunchKernelGGL(mfma_only, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (const v4i*)a_src, (const v4i*)b_src, (int)(bytes / 16),
                        iters, (int*)out);
     return (int)hipGetLastError();

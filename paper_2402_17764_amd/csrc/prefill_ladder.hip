@@ -125,11 +125,12 @@ int ladder_go(const void* a, const void* b, long long bytes, int blocks, int ste
 
 // rung: 0 MFMAs only; 1 + barrier per step; 2 + decode arithmetic; 3 + LDS operand reads; 4 + weight loads (streaming); 5 + LDS-DMA
 // copies (streaming) = every ingredient of the product's K loop; 6 as 4 and 7 as 5 with the same addresses every step; 8 barrier +
-// weight loads only; 9 barrier + LDS-DMA copies only.  a, b: at least `bytes` of int8 operand data; g: at least gbytes (>= 64 MiB)
-// of anything.  out: four ints; out[1] / out[2] is the shader clock in units of 100 MHz.
+// weight loads only; 9 barrier + LDS-DMA copies only.  a, b: at least `bytes` of int8 operand data; g: at least gbytes (>= 64 MiB
+// and below 2 GiB, one raw buffer) of anything.  out: four ints; out[1] / out[2] is the shader clock in units of 100 MHz.
+// Returns -3 for arguments outside that and -1 for an unknown rung, both before anything is launched.
 extern "C" int prefill_ladder_launch(int rung, const void* a, const void* b, long long bytes, int blocks, int steps, const void* g,
                                      long long gbytes, void* out, void* stream) {
-    if (bytes < 16 || gbytes < (64ll << 20) || steps < 1 || blocks < 1) return -3;
+    if (!a || !b || !g || !out || bytes < 16 || gbytes < (64ll << 20) || gbytes >= (2ll << 30) || steps < 1 || blocks < 1) return -3;
     switch (rung) {
         case 0: return ladder_go<0, 0, 0, 0, 0, 0>(a, b, bytes, blocks, steps, g, gbytes, out, stream);
         case 1: return ladder_go<0, 0, 1, 0, 0, 0>(a, b, bytes, blocks, steps, g, gbytes, out, stream);

@@ -219,3 +219,23 @@ def test_trit5_layout_decoder_on_a_hand_packed_matrix():
         got, pad_zero = decode_trit5(buf.astype(np.uint8).tobytes(), N, K)
         assert pad_zero and np.array_equal(got, codes)
         assert buf.size == binding.packed_bytes(N, K, binding.PACK_TRIT5)
+
+
+def test_yardstick_library_loads_and_checks_its_arguments():
+    """libbitnet_floors.so (the read-only, MFMA-only and K-loop-ladder kernels that bench.py and the measurement tools time
+    next to the product): it loads, exports its three entry points, and turns bad arguments into an error code before
+    anything is launched -- no GPU is touched here."""
+    from paper_2402_17764_amd import floors
+    lib = floors.load()
+    for name in ("read_only_launch", "mfma_only_launch", "prefill_ladder_launch"):
+        assert hasattr(lib, name)
+    assert lib.read_only_launch(None, 1 << 20, None, 256, 4, None) == -3
+    assert lib.read_only_launch(0x1000, 8, 0x1000, 256, 4, None) == -3
+    assert lib.mfma_only_launch(None, None, 1 << 20, 512, 10, None, None) == -3
+    assert lib.mfma_only_launch(0x1000, 0x1000, 1 << 20, 512, 0, 0x1000, None) == -3
+    ok = (0x1000, 0x1000, 1 << 24, 512, 10, 0x1000, 256 << 20, 0x1000, None)
+    assert lib.prefill_ladder_launch(5, None, *ok[1:]) == -3
+    assert lib.prefill_ladder_launch(5, *ok[:6], 1 << 20, 0x1000, None) == -3          # streaming source below 64 MiB
+    assert lib.prefill_ladder_launch(5, *ok[:6], 2 << 30, 0x1000, None) == -3          # ... or beyond one raw buffer
+    assert lib.prefill_ladder_launch(5, *ok[:4], 0, *ok[5:]) == -3                     # no steps
+    assert lib.prefill_ladder_launch(10, *ok) == -1                                    # no such rung
