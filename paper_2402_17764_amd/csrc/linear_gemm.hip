@@ -586,11 +586,12 @@ hipError_t launch_linear_gemm_2bit(const int8_t* xq, const float* sx, const void
     // two 128 x 256 workgroups on a CU, because the CU fetches the activations once for both.  Rounds are whole here --
     // a CU cannot take half a tile while the last round drains -- so it wins where the count of tiles suits 256 CUs
     // (13B-class QKV at 2048 tokens, 480 tiles: 127 -> 116 us) and loses where it does not (gate/up there, 864 tiles:
-    // 200 -> 220 us); not considered below a full round, where four-wave workgroups spread over more CUs.
+    // 200 -> 220 us); not considered while its tiles fill less than 7/8 of the CUs, where four-wave workgroups spread over more
+    // of them (240 tiles: 65 -> 62.5 us; 216 tiles: 58 -> 59 us; 192 tiles: 42 -> 46 us).
     if (force_splits <= 0) {
         const int64_t tiles = ceil_div(M, 128) * ceil_div(N, 512);
         const double cost = 6.0 + (double)steps_total * (double)ceil_div(tiles, (int64_t)256) * 2.70;
-        if (tiles >= 256 && cost < 0.96 * best_cost) { fm = 4; fn = 2; best_splits = 1; best_kg = 3; best_cost = cost; }
+        if (tiles >= 224 && cost < 0.96 * best_cost) { fm = 4; fn = 2; best_splits = 1; best_kg = 3; best_cost = cost; }
     }
     return launch_linear_gemm_2bit_shape(fm, fn, best_kg, xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, best_splits, workspace, plan);
 }

@@ -105,7 +105,8 @@ def test_prefill_tiles_follow_the_measured_cases():
     # 1231 -> 1207 us); where whole rounds of such tiles fit badly (864 tiles: 200 -> 220 us) the four-wave tiles stay
     assert B.linear_describe(2048, 15360, 5120)["params"] == [128, 512]
     assert B.linear_describe(4096, 57344, 8192)["params"] == [128, 512]
-    assert B.linear_describe(512, 27648, 5120)["params"] == [128, 256]            # 216 such tiles: less than a round
+    assert B.linear_describe(1024, 15360, 5120)["params"] == [128, 512]           # 240 tiles: 65 -> 62.5 us
+    assert B.linear_describe(512, 27648, 5120)["params"] == [128, 256]            # 216 such tiles: too few of the CUs
     # one workgroup per CU at most: eight waves in two K groups (measured: 19.2 -> 18.1 us, 39.7 -> 37.5 us)
     assert B.linear_describe(512, 5120, 5120)["params"] == [96, 128, 2]
     assert B.linear_describe(520, 5120, 5120)["params"] == [96, 128, 2]
@@ -121,7 +122,7 @@ def test_prefill_tiles_follow_the_measured_cases():
         assert d["kernel"] == "prefill" and d["splits"] == 1 and d["block"] == 256 * groups
         assert d["grid"] == (ceil_div(M, tm) * ceil_div(N, tn), 1)
         if tn == 512:
-            assert d["grid"][0] >= 256 and d["lds"] <= LDS_PER_CU                 # whole rounds of one workgroup per CU
+            assert d["grid"][0] >= 224 and d["lds"] <= LDS_PER_CU                 # (nearly) whole rounds of one workgroup per CU
         elif groups == 2:
             assert d["grid"][0] <= 256 and d["lds"] <= LDS_PER_CU                 # one round of one workgroup per CU
         else:
@@ -220,8 +221,8 @@ def test_every_launch_shape_is_within_the_hardware_limits():
             tm, tn = d["params"][:2]
             groups = d["params"][2] if len(d["params"]) == 3 else 2 if tn == 512 else 1
             assert d["grid"][0] == ceil_div(M, tm) * ceil_div(N, tn) and d["block"] == 256 * groups and groups in (1, 2)
-            if tn == 512:                    # two row groups: one workgroup per CU, at least a whole round of them
-                assert d["grid"][0] >= 256 and d["splits"] == 1 and tm == 128, (M, N, K, d)
+            if tn == 512:                    # two row groups: one workgroup per CU, at least 7/8 of a round of them
+                assert d["grid"][0] >= 224 and d["splits"] == 1 and tm == 128, (M, N, K, d)
             elif groups == 2:                # one workgroup per CU, one round, never together with a split through memory
                 assert d["grid"][0] <= 256 and d["splits"] == 1 and (tm, tn) in ((96, 128), (64, 256)), (M, N, K, d)
     assert kernels == {"reference", "decode", "batched_decode", "batched_decode_loader", "prefill"}
