@@ -512,7 +512,7 @@ hipError_t launch_linear_gemm_2bit_shape(int fm, int fn, int kg, const int8_t* x
                                          int gstride, int64_t M, int64_t N, int64_t K, void* y, OutType yt, hipStream_t stream,
                                          int splits, void* workspace, LaunchPlan* plan) {
 #define GEMM_SHAPE(FM_, FN_, KG_) if (fm == FM_ && fn == FN_ && kg == KG_) return launch_gemm_tiles<FM_, FN_, KG_ == 2 ? 2 : 1, KG_ == 3 ? 2 : 1>(xq, sx, packed, gamma, gstride, M, N, K, y, yt, stream, splits, workspace, plan)
-    if (kg == 2 && splits > 1) return hipErrorInvalidValue;
+    if (kg != 1 && splits > 1) return hipErrorInvalidValue;           // the eight-wave forms: one launch only
     GEMM_SHAPE(2, 1, 1); GEMM_SHAPE(3, 1, 1); GEMM_SHAPE(4, 1, 1); GEMM_SHAPE(2, 2, 1); GEMM_SHAPE(3, 2, 1); GEMM_SHAPE(4, 2, 1);
     GEMM_SHAPE(3, 1, 2); GEMM_SHAPE(2, 2, 2);
     GEMM_SHAPE(4, 2, 3);
