@@ -123,6 +123,50 @@ int ladder_go(const void* a, const void* b, long long bytes, int blocks, int ste
 
 }  // namespace
 
+// What the L2s deliver into the CUs when nothing else is done: every workgroup (256 threads) reads the whole buffer -- small
+// enough to stay in each XCD's L2, a power of two in size -- `reps` times from a place of its own, eight 16-byte loads per
+// lane in flight, into registers or, as LDS-DMA copies, into 32 KB of LDS.  The prefill kernel takes 48 KB per 8.4 M
+// multiply-adds this way; this is the rate that traffic can reach at most.
+template <bool kToLds>
+__global__ __launch_bounds__(256, 2) void l2_read_kernel(const uint4* __restrict__ p, int nvec, int reps, uint32_t* __restrict__ out) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    extern __shared__ uint4 smem[];
+    char* lds = reinterpret_cast<char*>(smem);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t mask = (uint32_t)nvec - 1u, rot = (blockIdx.x * 4099u + 17u) & mask;
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4*>(p), 0, nvec * 16, 0x00020000);
+    uint32_t acc = 0;
+    for (int r = 0; r < reps; ++r) {
+        for (uint32_t base = 0; base < (uint32_t)nvec; base += 256u * 8u) {
+            if (kToLds) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(lds + (wave * 8 + u) * 1024), 16,
+                                                             ((base + u * 256u + threadIdx.x + rot) & mask) * 16u, 0, 0, 0);
+            } else {
+                uint4 q[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) q[u] = p[(base + u * 256u + threadIdx.x + rot) & mask];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) acc += q[u].x ^ q[u].y ^ q[u].z ^ q[u].w;
+            }
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    if (kToLds) { __syncthreads(); acc = smem[threadIdx.x].x; }
+    if (acc == 0x12345678u) out[0] = acc;
+#endif
+}
+
+// bytes: a power of two from 64 KiB to 64 MiB; to_lds: 0 loads into registers, 1 LDS-DMA copies.  -3: arguments outside that.
+extern "C" int l2_read_launch(const void* p, long long bytes, int reps, int blocks, int to_lds, void* out, void* stream) {
+    if (!p || !out || bytes < (64ll << 10) || bytes > (64ll << 20) || (bytes & (bytes - 1)) || reps < 1 || blocks < 1) return -3;
+    const int nvec = (int)(bytes / 16);
+    if (to_lds) hipLaunchKernelGGL(l2_read_kernel<true>, dim3(blocks), dim3(256), 32768, (hipStream_t)stream, (const uint4*)p, nvec, reps, (uint32_t*)out);
+    else hipLaunchKernelGGL(l2_read_kernel<false>, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (const uint4*)p, nvec, reps, (uint32_t*)out);
+    return (int)hipGetLastError();
+}
+
 // rung: 0 MFMAs only; 1 + barrier per step; 2 + decode arithmetic; 3 + LDS operand reads; 4 + weight loads (streaming); 5 + LDS-DMA
 // copies (streaming) = every ingredient of the product's K loop; 6 as 4 and 7 as 5 with the same addresses every step; 8 barrier +
 // weight loads only; 9 barrier + LDS-DMA copies only.  a, b: at least `bytes` of int8 operand data; g: at least gbytes (>= 64 MiB

@@ -62,6 +62,26 @@ def main():
                 best, clock = ms, o[1] / max(1, o[2]) * 0.1
         tops = ops / (best * 1e-3) / 1e12
         print("%-78s %9.0f %9.2f %9.0f %%" % (name, tops, clock, 100.0 * tops / (5000.0 * clock / 2.4)), flush=True)
+    # the rate at which the L2s feed the CUs when nothing else happens: 512 workgroups of 256 threads read a 2 MiB buffer
+    # (resident in every XCD's L2) over and over, each from a place of its own
+    print()
+    buf = torch.randint(0, 2 ** 31 - 1, (2 << 18,), dtype=torch.int32, device="cuda")        # 2 MiB
+    reps = 400
+    for to_lds, name in ((0, "plain 16-byte loads into registers"), (1, "LDS-DMA copies (16 bytes per lane) into LDS")):
+        best = None
+        for _ in range(3):
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            rc = lib.l2_read_launch(buf.data_ptr(), buf.numel() * 4, reps, blocks, to_lds, out.data_ptr(), s)
+            e1.record()
+            torch.cuda.synchronize()
+            assert rc == 0, rc
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None or ms < best else best
+        tbs = blocks * reps * buf.numel() * 4.0 / (best * 1e-3) / 1e12
+        print("L2 -> CU, %-46s %6.1f TB/s over 256 CUs = %5.1f bytes per clock and CU at 2.1 GHz" % (name + ":", tbs, tbs * 1e12 / 256 / 2.1e9), flush=True)
+    print("the prefill kernel's 128 x 256 tile takes 48 KB through this path per 8.39 M multiply-adds: 175 multiply-adds per byte")
 
 
 if __name__ == "__main__":

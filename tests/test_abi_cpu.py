@@ -223,11 +223,11 @@ def test_trit5_layout_decoder_on_a_hand_packed_matrix():
 
 def test_yardstick_library_loads_and_checks_its_arguments():
     """libbitnet_floors.so (the read-only, MFMA-only and K-loop-ladder kernels that bench.py and the measurement tools time
-    next to the product): it loads, exports its three entry points, and turns bad arguments into an error code before
+    next to the product): it loads, exports its entry points, and turns bad arguments into an error code before
     anything is launched -- no GPU is touched here."""
     from paper_2402_17764_amd import floors
     lib = floors.load()
-    for name in ("read_only_launch", "mfma_only_launch", "prefill_ladder_launch"):
+    for name in ("read_only_launch", "mfma_only_launch", "prefill_ladder_launch", "l2_read_launch"):
         assert hasattr(lib, name)
     assert lib.read_only_launch(None, 1 << 20, None, 256, 4, None) == -3
     assert lib.read_only_launch(0x1000, 8, 0x1000, 256, 4, None) == -3
@@ -239,3 +239,6 @@ def test_yardstick_library_loads_and_checks_its_arguments():
     assert lib.prefill_ladder_launch(5, *ok[:6], 2 << 30, 0x1000, None) == -3          # ... or beyond one raw buffer
     assert lib.prefill_ladder_launch(5, *ok[:4], 0, *ok[5:]) == -3                     # no steps
     assert lib.prefill_ladder_launch(10, *ok) == -1                                    # no such rung
+    assert lib.l2_read_launch(None, 2 << 20, 10, 512, 0, 0x1000, None) == -3
+    assert lib.l2_read_launch(0x1000, (2 << 20) + 16, 10, 512, 1, 0x1000, None) == -3   # not a power of two
+    assert lib.l2_read_launch(0x1000, 1 << 30, 10, 512, 1, 0x1000, None) == -3          # larger than the kernel's raw buffer allows
