@@ -1494,3 +1494,33 @@ def test_activations_beyond_2_to_31_elements(gpu_lib):
     hq, sh = gpu_lib.swiglu_quantize(X)                              # rows as [gate | up] of F = K / 2
     hq_ref, sh_ref, _ = oracle.swiglu_quantize(xs)
     assert np.array_equal(hq[rows].cpu().numpy(), hq_ref) and sh[rows].cpu().numpy().tobytes() == sh_ref.tobytes()
+
+
+# ------------------------------------------------------------------------------------------------
+# the yardstick kernels that bench.py and the measurement tools time next to the product: they run and return
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.gpu
+def test_yardstick_kernels_run(gpu_lib):
+    """The read-only, MFMA-only, K-loop-ladder and L2-read kernels of libbitnet_floors.so on small inputs: every launch
+    is accepted and the device is healthy afterwards (their results are rates, not values -- nothing to compare)."""
+    from paper_2402_17764_amd import floors
+    lib = floors.load()
+    s = torch.cuda.current_stream().cuda_stream
+    a = torch.randint(-127, 128, (1 << 22,), dtype=torch.int8, device="cuda")
+    b = (torch.randint(-1, 2, (1 << 22,), dtype=torch.int8, device="cuda") * 64).to(torch.int8)
+    big = torch.zeros(64 << 20, dtype=torch.uint8, device="cuda")
+    out = torch.zeros(8, dtype=torch.int32, device="cuda")
+    say("yardsticks: read_only")
+    for (blocks, unroll) in floors.READ_SHAPES:
+        assert lib.read_only_launch(big.data_ptr(), big.numel(), out.data_ptr(), blocks, unroll, s) == 0
+    say("yardsticks: mfma_only")
+    assert lib.mfma_only_launch(a.data_ptr(), b.data_ptr(), a.numel(), 512, 4, out.data_ptr(), s) == 0
+    for rung in range(10):
+        say("yardsticks: ladder rung %d" % rung)
+        assert lib.prefill_ladder_launch(rung, a.data_ptr(), b.data_ptr(), a.numel(), 512, 3, big.data_ptr(), big.numel(),
+                                         out.data_ptr(), s) == 0
+    say("yardsticks: l2_read")
+    for to_lds in (0, 1):
+        assert lib.l2_read_launch(big.data_ptr(), 2 << 20, 2, 512, to_lds, out.data_ptr(), s) == 0
+    torch.cuda.synchronize()
+    assert int(out[2]) > 0                      # the ladder's last rung stamped its clocks
